@@ -1,0 +1,124 @@
+"""ctypes front end of the CPU oracle (oracle/dyn_oracle.cpp).
+
+TEST INFRASTRUCTURE: only tests, the smoke check and the benchmark's CPU-baseline leg
+may import this.  Argument marshalling only; all arithmetic is in the C++ file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Dict, Optional
+
+import numpy as np
+
+from .build_oracle import build
+
+_lib = None
+
+_P = C.c_void_p
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.dynoracle_ingest.restype = C.c_int
+        _lib.dynoracle_eval.restype = C.c_int
+        _lib.dynoracle_window_totals.restype = C.c_int
+        _lib.dynoracle_select_row.restype = C.c_int
+    return _lib
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(_P)
+
+
+def _c(a, dt):
+    return np.ascontiguousarray(a, dtype=dt)
+
+
+def ingest(trace: Dict[str, np.ndarray], edges: Dict[str, np.ndarray], n_window: int,
+           window_s: float) -> Dict[str, np.ndarray]:
+    """Raw trace -> cell-sorted in/out arrays and cell offsets."""
+    lib = _load()
+    t = _c(trace["t_s"], np.float64); i = _c(trace["in_tok"], np.int32)
+    o = _c(trace["out_tok"], np.int32); mdl = _c(trace["model"], np.int32)
+    ie = _c(edges["in_edge"], np.int32); oe = _c(edges["out_edge"], np.int32)
+    n_model, bi, bo = ie.shape[0], ie.shape[1] + 1, oe.shape[1] + 1
+    n = t.size
+    cells = n_window * n_model * bi * bo
+    ins = np.empty(n, np.int32); outs = np.empty(n, np.int32)
+    off = np.empty(cells + 1, np.int64)
+    rc = lib.dynoracle_ingest(_ptr(t), _ptr(i), _ptr(o), _ptr(mdl), C.c_int64(n), C.c_int32(n_model),
+                              C.c_int32(bi), C.c_int32(bo), _ptr(ie), _ptr(oe), C.c_int32(n_window),
+                              C.c_double(window_s), _ptr(ins), _ptr(outs), _ptr(off))
+    if rc != 0:
+        raise ValueError(f"dynoracle_ingest failed: {rc}")
+    return {"in_tok": ins, "out_tok": outs, "cell_off": off}
+
+
+def evaluate(profile: Dict[str, np.ndarray], sorted_trace: Dict[str, np.ndarray], n_window: int,
+             window_s: float, configs: Dict[str, np.ndarray], slos: Dict[str, np.ndarray],
+             pct=(99, 100), gpu_budget: Optional[np.ndarray] = None, idle_cost_weight: float = 0.0,
+             cell_ids: Optional[np.ndarray] = None, full_sort: bool = False,
+             want_space: bool = True) -> Dict[str, np.ndarray]:
+    """Evaluates the listed cells (all when cell_ids is None) under every configuration."""
+    lib = _load()
+    tp = _c(profile["tp"], np.int32); fg = _c(profile["f_mhz"], np.float64)
+    rg = _c(profile["rho"], np.float64)
+    PF = _c(profile["prefill_ms_per_tok"], np.float64); TB = _c(profile["tbt_ms"], np.float64)
+    PW = _c(profile["power_w"], np.float64); ML = _c(profile["max_load_tps"], np.float64)
+    G = PF.shape[0]
+    assert PF.shape == (G, tp.size, fg.size, rg.size) == TB.shape == PW.shape
+    assert ML.shape == (G, tp.size, fg.size)
+    ins = _c(sorted_trace["in_tok"], np.int32); outs = _c(sorted_trace["out_tok"], np.int32)
+    off = _c(sorted_trace["cell_off"], np.int64)
+    cells = n_window * G
+    assert off.size == cells + 1
+    cn = _c(configs["n_inst"], np.int32); ct = _c(configs["tp_index"], np.int32)
+    cf = _c(configs["f_mhz"], np.float64)
+    K = cn.size
+    st = _c(slos["slo_ttft_ms"], np.float64); sb = _c(slos["slo_tbt_ms"], np.float64)
+    assert st.size == G and sb.size == G
+    bud = None if gpu_budget is None else _c(gpu_budget, np.int32)
+    ids = None if cell_ids is None else _c(cell_ids, np.int64)
+    ns = cells if ids is None else ids.size
+    r: Dict[str, np.ndarray] = {}
+    if want_space:
+        r["energy_j"] = np.empty((ns, K)); r["p99_ttft_ms"] = np.empty((ns, K))
+        r["p99_tbt_ms"] = np.empty((ns, K)); r["flags"] = np.empty((ns, K), np.uint8)
+        r["cost"] = np.empty((ns, K))
+    r["m"] = np.empty(ns, np.int64); r["tin"] = np.empty(ns, np.int64); r["tout"] = np.empty(ns, np.int64)
+    r["in_p99"] = np.empty(ns, np.int32); r["sel"] = np.empty(ns, np.int32)
+    r["sel_energy_j"] = np.empty(ns); r["sel_cost"] = np.empty(ns)
+    rc = lib.dynoracle_eval(
+        C.c_int32(G), C.c_int32(tp.size), _ptr(tp), C.c_int32(fg.size), _ptr(fg), C.c_int32(rg.size),
+        _ptr(rg), _ptr(PF), _ptr(TB), _ptr(PW), _ptr(ML),
+        C.c_int64(ins.size), C.c_int32(n_window), C.c_double(window_s), _ptr(ins), _ptr(outs), _ptr(off),
+        C.c_int32(K), _ptr(cn), _ptr(ct), _ptr(cf),
+        _ptr(st), _ptr(sb), C.c_int32(pct[0]), C.c_int32(pct[1]), _ptr(bud), C.c_double(idle_cost_weight),
+        C.c_int64(ns), _ptr(ids), C.c_int32(1 if full_sort else 0),
+        _ptr(r.get("energy_j")), _ptr(r.get("p99_ttft_ms")), _ptr(r.get("p99_tbt_ms")), _ptr(r.get("flags")),
+        _ptr(r.get("cost")), _ptr(r["m"]), _ptr(r["tin"]), _ptr(r["tout"]), _ptr(r["in_p99"]),
+        _ptr(r["sel"]), _ptr(r["sel_energy_j"]), _ptr(r["sel_cost"]))
+    if rc != 0:
+        raise ValueError(f"dynoracle_eval failed: {rc}")
+    return r
+
+
+def window_totals(sel: np.ndarray, sel_energy_j: np.ndarray, n_window: int, n_class: int):
+    lib = _load()
+    s = _c(sel, np.int32); e = _c(sel_energy_j, np.float64)
+    assert s.size == n_window * n_class == e.size
+    we = np.empty(n_window); wi = np.empty(n_window, np.int32)
+    rc = lib.dynoracle_window_totals(C.c_int32(n_window), C.c_int32(n_class), _ptr(s), _ptr(e), _ptr(we),
+                                     _ptr(wi))
+    if rc != 0:
+        raise ValueError(f"dynoracle_window_totals failed: {rc}")
+    return we, wi
+
+
+def select_row(cost: np.ndarray, feasible: np.ndarray) -> int:
+    lib = _load()
+    c = _c(cost, np.float64); f = _c(feasible, np.uint8)
+    assert c.size == f.size
+    return int(lib.dynoracle_select_row(C.c_int32(c.size), _ptr(c), _ptr(f)))

@@ -1,0 +1,312 @@
+// CPU oracle for the batched evaluation of DynamoLLM's reconfiguration search space.
+//
+// TEST INFRASTRUCTURE.  Plain, slow, single-threaded, fp64.  It exists to define the
+// expected result; only the test-suite, the smoke check and the CPU-baseline leg of the
+// benchmark may build, load or call it.  It shares no code with the HIP library and
+// neither includes the other.
+//
+// What it computes, for every (time window, request class) cell and every candidate
+// configuration (instances n, tensor-parallel degree TP, GPU frequency f):
+//   * the class's load in the window, in tokens per second (Section III-A, "Request
+//     loads": system load is measured in tokens per second);
+//   * the per-instance share of that load, every instance of a pool receiving the same
+//     amount of work (Section IV-A, the fair-share assumption stated before Eq. 1);
+//   * TTFT, TBT and power read from the profile, a function of (load, request class,
+//     TP, frequency) that is known at a few load levels up to the maximum throughput
+//     and taken piecewise-linearly in between (Section IV-A "Generating LLM profiles";
+//     Section IV-E names one-dimensional linear interpolation);
+//   * for every request of the cell its predicted TTFT (prefill time grows with the
+//     number of input tokens, Section II), its TBT and its share of the energy, then
+//     the P99 of TTFT and of TBT over the cell (Section III-A "Service SLO");
+//   * feasibility: Performance <= SLO and instances x TP <= GPU budget (Eq. 1,
+//     constraints 3 and 1), plus "the load does not exceed the profiled range";
+//   * the objective N x Energy(load per instance) (Eq. 1) and, per cell, the feasible
+//     configuration of least cost (Section IV-B "Scale-up/down": first drop what
+//     violates the SLO, then take the least energy).
+//
+// Every request is evaluated under every configuration and the percentile is taken from
+// the per-request values themselves; nothing is blocked, fused or reordered.
+//
+// Readings where the paper is silent (each also listed in the design notes):
+//   load = (input + output tokens of the cell) / window length;
+//   load axis of the tables = per-instance load / max_load_tps(class, TP, f);
+//   a load beyond the last profiled point makes the configuration infeasible, values
+//     are reported at the last point;
+//   bracket of x on a grid = largest i with grid[i] <= x, clamped to len-2;
+//   bilinear order: along load on the two bracketing frequency rows, then along f;
+//   percentile = nearest rank, rank = ceil(num*m/den) in integer arithmetic;
+//   empty cell: load 0, percentiles 0, SLOs hold, energy = idle energy;
+//   energy in joules = n * power * window length;
+//   cost = energy + idle_cost_weight * n * power(load 0) * window length;
+//   ties in the argmin go to the lowest configuration index; no feasible one -> -1.
+//
+// Build: g++ -O2 -std=c++17 -ffp-contract=off -shared -fPIC (see build_oracle.py).
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <limits>
+#include <numeric>
+#include <vector>
+
+namespace {
+
+enum : int {
+  ORC_OK = 0, ORC_E_NULL = -1, ORC_E_SHAPE = -2, ORC_E_RANGE = -3, ORC_E_NOTFINITE = -4,
+  ORC_E_ORDER = -5, ORC_E_SELFCHECK = -8
+};
+
+// largest i with grid[i] <= x, clamped to [0, len-2]  (len >= 2)
+int bracket(const double* grid, int len, double x) {
+  int i = 0;
+  for (int q = 0; q < len; ++q)
+    if (grid[q] <= x) i = q;
+  if (i > len - 2) i = len - 2;
+  return i;
+}
+
+bool increasing(const double* g, int n) {
+  for (int i = 0; i < n; ++i)
+    if (!std::isfinite(g[i])) return false;
+  for (int i = 1; i < n; ++i)
+    if (!(g[i] > g[i - 1])) return false;
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+// Section III-A, Table IV: requests are classified by input and output length; a value
+// equal to a threshold belongs to the upper bin ("< 256" is Short, 256 is Medium).
+// Windows are the controllers' epochs (Section IV-B): w = floor(t / window_s).
+// Output: requests reordered by cell = w*G + class (order of arrival kept inside a
+// cell) and the start offset of every cell.
+int dynoracle_ingest(const double* t_s, const int32_t* in_tok, const int32_t* out_tok,
+                     const int32_t* model, int64_t n_req, int32_t n_model, int32_t n_in_bin,
+                     int32_t n_out_bin, const int32_t* in_edge, const int32_t* out_edge,
+                     int32_t n_window, double window_s, int32_t* in_sorted,
+                     int32_t* out_sorted, int64_t* cell_off) {
+  if (!t_s || !in_tok || !out_tok || !in_sorted || !out_sorted || !cell_off) return ORC_E_NULL;
+  if (n_req < 0 || n_model < 1 || n_in_bin < 1 || n_out_bin < 1 || n_window < 1) return ORC_E_SHAPE;
+  if (!(window_s > 0.0)) return ORC_E_RANGE;
+  const int64_t G = (int64_t)n_model * n_in_bin * n_out_bin;
+  const int64_t cells = (int64_t)n_window * G;
+  std::vector<int64_t> cell(n_req);
+  for (int64_t r = 0; r < n_req; ++r) {
+    const double wq = std::floor(t_s[r] / window_s);
+    if (!(wq >= 0.0) || !(wq < (double)n_window)) return ORC_E_RANGE;
+    const int64_t w = (int64_t)wq;
+    const int32_t mdl = model ? model[r] : 0;
+    if (mdl < 0 || mdl >= n_model) return ORC_E_RANGE;
+    int bi = 0, bo = 0;
+    for (int e = 0; e < n_in_bin - 1; ++e)
+      if (in_tok[r] >= in_edge[(int64_t)mdl * (n_in_bin - 1) + e]) ++bi;
+    for (int e = 0; e < n_out_bin - 1; ++e)
+      if (out_tok[r] >= out_edge[(int64_t)mdl * (n_out_bin - 1) + e]) ++bo;
+    const int64_t g = ((int64_t)mdl * n_in_bin + bi) * n_out_bin + bo;
+    cell[r] = w * G + g;
+  }
+  std::vector<int64_t> order(n_req);
+  std::iota(order.begin(), order.end(), (int64_t)0);
+  std::stable_sort(order.begin(), order.end(),
+                   [&](int64_t a, int64_t b) { return cell[a] < cell[b]; });
+  for (int64_t c = 0; c <= cells; ++c) cell_off[c] = 0;
+  for (int64_t r = 0; r < n_req; ++r) cell_off[cell[r] + 1] += 1;
+  for (int64_t c = 0; c < cells; ++c) cell_off[c + 1] += cell_off[c];
+  for (int64_t i = 0; i < n_req; ++i) {
+    in_sorted[i] = in_tok[order[i]];
+    out_sorted[i] = out_tok[order[i]];
+  }
+  return ORC_OK;
+}
+
+// Evaluates the cells listed in cell_ids (all cells 0..n_sel-1 when cell_ids is null)
+// under all K configurations.  Outputs are indexed by position in that list:
+// energy_j, p99_ttft_ms, p99_tbt_ms, cost [n_sel][K] (k fastest), flags [n_sel][K],
+// m, tin, tout, in_p99, sel, sel_energy_j, sel_cost [n_sel].  Any output may be null.
+// flags: bit0 feasible, bit1 load beyond the profiled range, bit2 TTFT > SLO,
+// bit3 TBT > SLO, bit4 GPU budget exceeded, bit5 empty cell.
+// full_sort != 0 sorts the per-request latencies completely; otherwise the element of
+// the same rank is found with std::nth_element (same value by definition).
+int dynoracle_eval(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f, const double* fg,
+                   int32_t n_rho, const double* rg, const double* PF, const double* TB,
+                   const double* PW, const double* ML,
+                   int64_t n_req, int32_t n_window, double window_s, const int32_t* in_tok,
+                   const int32_t* out_tok, const int64_t* cell_off,
+                   int32_t K, const int32_t* cfg_n, const int32_t* cfg_tp_index,
+                   const double* cfg_f,
+                   const double* slo_ttft, const double* slo_tbt, int32_t pct_num,
+                   int32_t pct_den, const int32_t* gpu_budget, double idle_cost_weight,
+                   int64_t n_sel, const int64_t* cell_ids, int32_t full_sort,
+                   double* energy_j, double* p99_ttft_ms, double* p99_tbt_ms, uint8_t* flags,
+                   double* cost_out, int64_t* m_out, int64_t* tin_out, int64_t* tout_out,
+                   int32_t* in_p99_out, int32_t* sel_out, double* sel_energy_j,
+                   double* sel_cost) {
+  if (!tp || !fg || !rg || !PF || !TB || !PW || !ML || !cell_off || !cfg_n || !cfg_tp_index ||
+      !cfg_f || !slo_ttft || !slo_tbt)
+    return ORC_E_NULL;
+  if (n_req > 0 && (!in_tok || !out_tok)) return ORC_E_NULL;
+  if (G < 1 || n_tp < 1 || n_f < 1 || n_rho < 2 || K < 1 || n_window < 1 || n_sel < 0)
+    return ORC_E_SHAPE;
+  if (!(window_s > 0.0) || pct_num < 1 || pct_den < 1 || pct_num > pct_den) return ORC_E_RANGE;
+  if (!increasing(fg, n_f) || !increasing(rg, n_rho)) return ORC_E_ORDER;
+  if (rg[0] != 0.0) return ORC_E_RANGE;
+  const int64_t n_tab = (int64_t)G * n_tp * n_f * n_rho;
+  for (int64_t i = 0; i < n_tab; ++i)
+    if (!std::isfinite(PF[i]) || !std::isfinite(TB[i]) || !std::isfinite(PW[i]) || PF[i] < 0.0 ||
+        TB[i] < 0.0 || PW[i] < 0.0)
+      return ORC_E_NOTFINITE;
+  for (int64_t i = 0; i < (int64_t)G * n_tp * n_f; ++i)
+    if (!std::isfinite(ML[i]) || !(ML[i] > 0.0)) return ORC_E_NOTFINITE;
+  for (int k = 0; k < K; ++k) {
+    if (cfg_n[k] < 1 || cfg_tp_index[k] < 0 || cfg_tp_index[k] >= n_tp) return ORC_E_RANGE;
+    if (!(cfg_f[k] >= fg[0]) || !(cfg_f[k] <= fg[n_f - 1])) return ORC_E_RANGE;
+  }
+  const int64_t cells = (int64_t)n_window * G;
+  const double INF = std::numeric_limits<double>::infinity();
+
+  // frequency bracket and weight of every configuration (independent of the cell)
+  std::vector<int> fi(K);
+  std::vector<double> u(K);
+  for (int k = 0; k < K; ++k) {
+    if (n_f == 1) { fi[k] = 0; u[k] = 0.0; continue; }
+    fi[k] = bracket(fg, n_f, cfg_f[k]);
+    u[k] = (cfg_f[k] - fg[fi[k]]) / (fg[fi[k] + 1] - fg[fi[k]]);
+  }
+  auto tab = [&](const double* X, int g, int ti, int f, int j) -> double {
+    return X[(((int64_t)g * n_tp + ti) * n_f + f) * n_rho + j];
+  };
+
+  std::vector<double> lat, e_cost(K), e_energy(K);
+  std::vector<uint8_t> e_flags(K);
+  for (int64_t s = 0; s < n_sel; ++s) {
+    const int64_t c = cell_ids ? cell_ids[s] : s;
+    if (c < 0 || c >= cells) return ORC_E_RANGE;
+    const int g = (int)(c % G);
+    const int64_t beg = cell_off[c], end = cell_off[c + 1];
+    if (beg < 0 || end < beg || end > n_req) return ORC_E_ORDER;
+    const int64_t m = end - beg;
+
+    // load of the class in this window: tokens per second
+    int64_t tin = 0, tout = 0;
+    for (int64_t r = beg; r < end; ++r) { tin += in_tok[r]; tout += out_tok[r]; }
+    const double L = (double)(tin + tout) / window_s;
+    const int64_t rank = (m > 0) ? ((int64_t)pct_num * m + pct_den - 1) / pct_den : 0;
+
+    // the cell's P99 input length (an intermediate the tests compare bit for bit)
+    int32_t in_p99 = 0;
+    if (m > 0) {
+      std::vector<int32_t> tmp(in_tok + beg, in_tok + end);
+      std::sort(tmp.begin(), tmp.end());
+      in_p99 = tmp[rank - 1];
+    }
+    if (m_out) m_out[s] = m;
+    if (tin_out) tin_out[s] = tin;
+    if (tout_out) tout_out[s] = tout;
+    if (in_p99_out) in_p99_out[s] = in_p99;
+
+    for (int k = 0; k < K; ++k) {
+      const int ti = cfg_tp_index[k], f0 = fi[k];
+      const double uk = u[k], nk = (double)cfg_n[k];
+      // capacity of one instance at (TP, f), then the per-instance load on the table axis
+      const double* mlrow = ML + ((int64_t)g * n_tp + ti) * n_f;
+      const double ml = (n_f == 1) ? mlrow[0] : (1.0 - uk) * mlrow[f0] + uk * mlrow[f0 + 1];
+      const double rho = L / (nk * ml);
+      const bool ov = rho > rg[n_rho - 1];
+      const double rc = ov ? rg[n_rho - 1] : rho;
+      const int j = bracket(rg, n_rho, rc);
+      const double t = (rc - rg[j]) / (rg[j + 1] - rg[j]);
+      double val[3];
+      const double* X[3] = {PF, TB, PW};
+      for (int q = 0; q < 3; ++q) {
+        const double a = (1.0 - t) * tab(X[q], g, ti, f0, j) + t * tab(X[q], g, ti, f0, j + 1);
+        if (n_f == 1) { val[q] = a; continue; }
+        const double b =
+            (1.0 - t) * tab(X[q], g, ti, f0 + 1, j) + t * tab(X[q], g, ti, f0 + 1, j + 1);
+        val[q] = (1.0 - uk) * a + uk * b;
+      }
+      const double pf = val[0], tb = val[1], pw = val[2];
+      const double pw0 = (n_f == 1) ? tab(PW, g, ti, 0, 0)
+                                    : (1.0 - uk) * tab(PW, g, ti, f0, 0) + uk * tab(PW, g, ti, f0 + 1, 0);
+      const double E = (nk * pw) * window_s;
+
+      double p_ttft = 0.0, p_tbt = 0.0;
+      if (m > 0) {
+        // every request under this configuration: TTFT grows with its input length,
+        // TBT is the profile's per-token latency, energy is shared by token count
+        lat.resize((size_t)m);
+        double esum = 0.0;
+        const double tok = (double)(tin + tout);
+        for (int64_t r = 0; r < m; ++r) {
+          lat[(size_t)r] = (double)in_tok[beg + r] * pf;
+          esum += E * ((double)((int64_t)in_tok[beg + r] + out_tok[beg + r]) / tok);
+        }
+        if (std::fabs(esum - E) > 1e-9 * std::fabs(E)) return ORC_E_SELFCHECK;
+        if (full_sort) {
+          std::sort(lat.begin(), lat.end());
+        } else {
+          std::nth_element(lat.begin(), lat.begin() + (rank - 1), lat.end());
+        }
+        p_ttft = lat[(size_t)(rank - 1)];
+        p_tbt = tb;  // all m per-request TBTs equal tb, so does their percentile
+      }
+      const double cost = E + idle_cost_weight * ((nk * pw0) * window_s);
+
+      uint8_t fl = 0;
+      if (ov) fl |= 2;
+      if (p_ttft > slo_ttft[g]) fl |= 4;
+      if (p_tbt > slo_tbt[g]) fl |= 8;
+      if (gpu_budget && gpu_budget[g] > 0 && (int64_t)cfg_n[k] * tp[ti] > gpu_budget[g]) fl |= 16;
+      if (m == 0) fl |= 32;
+      if (!(fl & (2 | 4 | 8 | 16))) fl |= 1;
+
+      e_energy[k] = E; e_cost[k] = cost; e_flags[k] = fl;
+      const int64_t o = s * K + k;
+      if (energy_j) energy_j[o] = E;
+      if (p99_ttft_ms) p99_ttft_ms[o] = p_ttft;
+      if (p99_tbt_ms) p99_tbt_ms[o] = p_tbt;
+      if (flags) flags[o] = fl;
+      if (cost_out) cost_out[o] = cost;
+    }
+
+    int best = -1;
+    for (int k = 0; k < K; ++k)
+      if ((e_flags[k] & 1) && (best < 0 || e_cost[k] < e_cost[best])) best = k;
+    if (sel_out) sel_out[s] = best;
+    if (sel_energy_j) sel_energy_j[s] = best < 0 ? INF : e_energy[best];
+    if (sel_cost) sel_cost[s] = best < 0 ? INF : e_cost[best];
+  }
+  return ORC_OK;
+}
+
+// Objective summed over the pools of a window (Eq. 1 sums over instance types; here one
+// pool per class), classes added in index order; cells without a feasible configuration
+// are counted, not added.
+int dynoracle_window_totals(int32_t n_window, int32_t G, const int32_t* sel,
+                            const double* sel_energy_j, double* window_energy_j,
+                            int32_t* window_infeasible) {
+  if (!sel || !sel_energy_j || !window_energy_j || !window_infeasible) return ORC_E_NULL;
+  for (int w = 0; w < n_window; ++w) {
+    double e = 0.0;
+    int32_t ninf = 0;
+    for (int g = 0; g < G; ++g) {
+      const int64_t c = (int64_t)w * G + g;
+      if (sel[c] >= 0) e += sel_energy_j[c]; else ++ninf;
+    }
+    window_energy_j[w] = e;
+    window_infeasible[w] = ninf;
+  }
+  return ORC_OK;
+}
+
+// Least-cost feasible column of one row (used to check the selector against the energy
+// tables the paper prints): lowest index on exact ties, -1 when nothing is feasible.
+int dynoracle_select_row(int32_t K, const double* cost, const uint8_t* feasible) {
+  int best = -1;
+  for (int k = 0; k < K; ++k)
+    if (feasible[k] && (best < 0 || cost[k] < cost[best])) best = k;
+  return best;
+}
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+"""A second, independent statement of the evaluator in NumPy/SciPy, for tiny inputs.
+
+Used only to pin the C++ oracle: it is written against library routines (np.interp,
+scipy's RegularGridInterpolator, np.sort, np.searchsorted, stable argsort) and Python
+integers/Fractions, not against the oracle's formulas, and shares nothing with it.
+"""
+from fractions import Fraction
+import math
+
+import numpy as np
+from scipy.interpolate import RegularGridInterpolator
+
+
+def np_ingest(trace, edges, n_window, window_s):
+    t = np.asarray(trace["t_s"]); x = np.asarray(trace["in_tok"]); y = np.asarray(trace["out_tok"])
+    mdl = np.asarray(trace["model"])
+    ie, oe = np.asarray(edges["in_edge"]), np.asarray(edges["out_edge"])
+    n_model, bi, bo = ie.shape[0], ie.shape[1] + 1, oe.shape[1] + 1
+    G = n_model * bi * bo
+    cell = np.empty(t.size, np.int64)
+    for r in range(t.size):
+        w = int(math.floor(Fraction(float(t[r])) / Fraction(float(window_s))))  # exact quotient
+        a = int(np.searchsorted(ie[mdl[r]], x[r], side="right"))
+        b = int(np.searchsorted(oe[mdl[r]], y[r], side="right"))
+        cell[r] = w * G + (mdl[r] * bi + a) * bo + b
+    order = np.argsort(cell, kind="stable")
+    off = np.zeros(n_window * G + 1, np.int64)
+    np.add.at(off, cell + 1, 1)
+    return {"in_tok": x[order].astype(np.int32), "out_tok": y[order].astype(np.int32),
+            "cell_off": np.cumsum(off)}
+
+
+def np_eval(profile, st, n_window, window_s, configs, slos, pct=(99, 100), gpu_budget=None,
+            idle_cost_weight=0.0):
+    tp = profile["tp"]; fg = profile["f_mhz"]; rg = profile["rho"]
+    PF, TB, PW, ML = (profile[k] for k in ("prefill_ms_per_tok", "tbt_ms", "power_w", "max_load_tps"))
+    G = PF.shape[0]
+    K = configs["n_inst"].size
+    cells = n_window * G
+    off = st["cell_off"]
+    out = {k: np.zeros((cells, K)) for k in ("energy_j", "p99_ttft_ms", "p99_tbt_ms", "cost", "rho")}
+    out["flags"] = np.zeros((cells, K), np.uint8)
+    out["sel"] = np.full(cells, -1, np.int32)
+    out["in_p99"] = np.zeros(cells, np.int32)
+    out["m"] = np.diff(off)
+
+    def look(X, g, ti, f, r):
+        if fg.size == 1:
+            return float(np.interp(r, rg, X[g, ti, 0]))
+        hit = np.nonzero(fg == f)[0]
+        if hit.size:                                    # profiled frequency: the paper's 1-D case
+            return float(np.interp(r, rg, X[g, ti, hit[0]]))
+        return float(RegularGridInterpolator((fg, rg), X[g, ti])((f, r)))
+
+    for c in range(cells):
+        g = c % G
+        x = st["in_tok"][off[c]:off[c + 1]].astype(np.int64)
+        y = st["out_tok"][off[c]:off[c + 1]].astype(np.int64)
+        m = x.size
+        load = float(Fraction(int(x.sum() + y.sum())) / Fraction(float(window_s)))
+        rank = int(math.ceil(Fraction(pct[0] * m, pct[1])))
+        if m:
+            out["in_p99"][c] = np.sort(x)[rank - 1]
+        best, best_cost = -1, math.inf
+        for k in range(K):
+            n = int(configs["n_inst"][k]); ti = int(configs["tp_index"][k]); f = float(configs["f_mhz"][k])
+            cap = float(np.interp(f, fg, ML[g, ti])) if fg.size > 1 else float(ML[g, ti, 0])
+            rho = load / (n * cap)
+            over = rho > rg[-1]
+            r = min(rho, rg[-1])
+            pf, tb, pw = look(PF, g, ti, f, r), look(TB, g, ti, f, r), look(PW, g, ti, f, r)
+            pw0 = look(PW, g, ti, f, 0.0)
+            ttft = float(np.sort(x * pf)[rank - 1]) if m else 0.0
+            tbt = tb if m else 0.0
+            e = n * pw * window_s
+            cost = e + idle_cost_weight * n * pw0 * window_s
+            fl = 0
+            if over: fl |= 2
+            if ttft > slos["slo_ttft_ms"][g]: fl |= 4
+            if tbt > slos["slo_tbt_ms"][g]: fl |= 8
+            if gpu_budget is not None and gpu_budget[g] > 0 and n * int(tp[ti]) > gpu_budget[g]: fl |= 16
+            if m == 0: fl |= 32
+            if not fl & 30: fl |= 1
+            out["energy_j"][c, k] = e; out["p99_ttft_ms"][c, k] = ttft; out["p99_tbt_ms"][c, k] = tbt
+            out["cost"][c, k] = cost; out["flags"][c, k] = fl; out["rho"][c, k] = rho
+            if fl & 1 and cost < best_cost:
+                best, best_cost = k, cost
+        out["sel"][c] = best
+    return out
