@@ -1,0 +1,214 @@
+/*
+ * dyn.h - C ABI of the batched evaluator of DynamoLLM's reconfiguration search space
+ *         (arXiv 2408.00741) for AMD MI355X (gfx950).
+ *
+ * The paper's energy manager chooses, per pool of one request class, the number of
+ * instances, the tensor-parallel degree and the GPU frequency that minimise energy under
+ * P99 TTFT/TBT SLOs, using profiled energy/latency tables interpolated over load
+ * (Section IV-A, Eq. 1; Section IV-B "Scale-up/down").  This library evaluates that whole
+ * search space at once: for every (time window, request class) cell and every candidate
+ * configuration it computes the predicted P99 TTFT, P99 TBT, energy and SLO feasibility,
+ * and then the least-cost feasible configuration per cell.
+ *
+ * Conventions shared by every entry point
+ *   - Return value: DYN_OK (0) or a negative dyn_status.  Nothing throws or aborts.
+ *     dyn_last_error() gives a message for the last failure on the calling thread.
+ *   - "HOST" pointers are read during the call and may be freed on return.
+ *     "DEVICE" pointers are memory of the current HIP device owned by the caller; the
+ *     library never frees them.  Only dyn_profile_load allocates device memory (released by
+ *     dyn_profile_free).
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream) and the call returns after enqueueing.  The status covers argument checks
+ *     and launch errors.  Conditions that depend on device data (an offset array that is
+ *     not monotone, a timestamp outside the windows) cannot be seen by the host: the
+ *     kernels bound-check them, skip the offending item and raise a bit in the status
+ *     word at the start of the workspace, which dyn_workspace_status reads back.
+ *   - Cells are numbered cell = w * G + g with w the window and g the class,
+ *     g = (model * n_in_bin + in_bin) * n_out_bin + out_bin.
+ *   - All floating point is IEEE binary64 without contraction.
+ */
+#ifndef DYN_H_
+#define DYN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DYN_OK = 0,
+  DYN_E_NULL = -1,      /* a required pointer is NULL                                   */
+  DYN_E_SHAPE = -2,     /* a count or dimension is out of range or inconsistent         */
+  DYN_E_RANGE = -3,     /* a value is outside its allowed range                         */
+  DYN_E_NOTFINITE = -4, /* a table entry is NaN, infinite or negative                   */
+  DYN_E_ORDER = -5,     /* a grid or edge list is not strictly increasing               */
+  DYN_E_WORKSPACE = -6, /* workspace missing, misaligned (256 B) or too small           */
+  DYN_E_DEVICE = -7     /* a HIP call failed                                            */
+} dyn_status;
+
+/* Message of the last error on this thread; static storage, never freed by the caller. */
+const char* dyn_last_error(void);
+
+/* ------------------------------------------------------------------ profile tables -----
+ * Section IV-A, "Generating LLM profiles": the profile is a function of (load, request
+ * class, tensor parallelism, GPU frequency) giving expected energy and TTFT/TBT; it is
+ * measured at a few load levels up to the maximum throughput and taken linearly in
+ * between (Section IV-E: one-dimensional linear interpolation).
+ * Tables are row-major [n_class][n_tp][n_f][n_rho]; the load axis `rho` is the
+ * per-instance load divided by max_load_tps (tokens/s one instance sustains at that
+ * class, TP and frequency).  All HOST pointers; the library keeps device copies.       */
+typedef struct {
+  int32_t n_class;                  /* G >= 1, all models' classes                        */
+  int32_t n_tp;                     /* >= 1                                               */
+  const int32_t* tp;                /* [n_tp] GPUs per instance, >= 1, strictly increasing */
+  int32_t n_f;                      /* >= 1                                               */
+  const double* f_mhz;              /* [n_f] profiled frequencies, strictly increasing    */
+  int32_t n_rho;                    /* >= 2                                               */
+  const double* rho;                /* [n_rho] load grid, strictly increasing, rho[0]==0  */
+  const double* prefill_ms_per_tok; /* [G][n_tp][n_f][n_rho] finite, >= 0                  */
+  const double* tbt_ms;             /* [G][n_tp][n_f][n_rho] finite, >= 0                  */
+  const double* power_w;            /* [G][n_tp][n_f][n_rho] watts of one whole instance   */
+  const double* max_load_tps;       /* [G][n_tp][n_f] finite, > 0                          */
+} dyn_profile_desc;
+
+/* Opaque; owns the device copies of the tables and of the candidate list and objective it
+ * was last used with, so that repeated calls with the same candidates upload nothing.
+ * A handle must not be used by two host threads at once, and a call that changes the
+ * candidate list or the SLOs first waits for `hip_stream`; work still in flight on
+ * another stream must not be using the same handle at that moment.
+ * Limits: at most 65536 candidate configurations.                                      */
+typedef struct dyn_profile dyn_profile;
+
+/* Validates the tables (DYN_E_NULL/SHAPE/ORDER/RANGE/NOTFINITE), copies them to the
+ * current device on `hip_stream` and waits for the copy.  *out receives the handle. */
+int dyn_profile_load(const dyn_profile_desc* desc, void* hip_stream, dyn_profile** out);
+void dyn_profile_free(dyn_profile* p); /* NULL is allowed */
+
+/* ---------------------------------------------------------------- trace ingestion -----
+ * Section III: a trace record is (arrival timestamp, input tokens, output tokens).
+ * Section III-A, Table IV: requests are classified by input and output length; a length
+ * equal to a threshold belongs to the upper bin.  Windows are the controllers' epochs
+ * (Section IV-B): w = floor(t_s / window_s) in binary64.                               */
+typedef struct {
+  int32_t n_model, n_in_bin, n_out_bin; /* G = n_model * n_in_bin * n_out_bin            */
+  const int32_t* in_edge;  /* HOST [n_model][n_in_bin-1], strictly increasing per model  */
+  const int32_t* out_edge; /* HOST [n_model][n_out_bin-1]; bin = #{edges e : x >= e}     */
+} dyn_class_edges;
+
+size_t dyn_trace_ingest_workspace(int64_t n_req, int32_t n_window, int32_t n_class);
+
+/* Reorders a raw trace by cell, keeping arrival order inside a cell (a stable sort), and
+ * writes the start offset of every cell.
+ *   t_s, in_tok, out_tok, model : DEVICE [n_req]; model may be NULL (all model 0); time
+ *                                 order is not required.
+ *   in_sorted, out_sorted       : DEVICE [n_req] outputs; must not alias the inputs.
+ *   cell_off                    : DEVICE [n_window*G + 1] output, cell_off[last] = n_req.
+ *   workspace                   : DEVICE, 256-byte aligned, >= dyn_trace_ingest_workspace.
+ * A request whose timestamp falls outside [0, n_window*window_s) or whose model index is
+ * outside [0, n_model) raises DYN_WS_BAD_REQUEST in the workspace status and is filed
+ * under the nearest valid window / model 0, so that offsets stay consistent.
+ * Limits: n_window * G < 2^30.                                                         */
+int dyn_trace_ingest(const double* t_s, const int32_t* in_tok, const int32_t* out_tok,
+                     const int32_t* model, int64_t n_req, const dyn_class_edges* edges,
+                     int32_t n_window, double window_s, int32_t* in_sorted, int32_t* out_sorted,
+                     int64_t* cell_off, void* workspace, size_t workspace_bytes,
+                     void* hip_stream);
+
+/* The cell-sorted trace the evaluator reads.  All DEVICE pointers, caller-owned. */
+typedef struct {
+  int64_t n_req;
+  int32_t n_window;
+  double window_s;        /* > 0, seconds                                               */
+  const int32_t* in_tok;  /* [n_req] sorted by cell                                     */
+  const int32_t* out_tok; /* [n_req]                                                    */
+  const int64_t* cell_off; /* [n_window*G + 1] non-decreasing, [0]==0, last == n_req    */
+} dyn_trace_view;
+
+/* ------------------------------------------------- candidates, SLOs and objective -----
+ * Section IV-A: the knobs are the number of instances, their tensor parallelism and
+ * their frequency; all instances of a pool share the load equally.                     */
+typedef struct {
+  int32_t n_inst;   /* >= 1                                                             */
+  int32_t tp_index; /* index into dyn_profile_desc.tp                                   */
+  double f_mhz;     /* within [f_mhz[0], f_mhz[n_f-1]] of the profile, else DYN_E_RANGE */
+} dyn_config;
+
+/* Eq. 1: minimise sum N x Energy subject to GPUs <= budget and Performance <= SLO;
+ * Section III-A: the SLO statistic is the P99 latency.                                 */
+typedef struct {
+  const double* slo_ttft_ms; /* HOST [G]                                                */
+  const double* slo_tbt_ms;  /* HOST [G]                                                */
+  int32_t pct_num, pct_den;  /* percentile = pct_num/pct_den in (0, 1]; 99, 100         */
+  const int32_t* gpu_budget; /* HOST [G] or NULL; 0 = unlimited; needs n_inst*tp <= it  */
+  double idle_cost_weight;   /* cost = energy + weight * n_inst * power(load 0) * window */
+} dyn_objective;
+
+/* The evaluated space.  DEVICE pointers, caller-owned, each [n_window*G][K], k fastest. */
+typedef struct {
+  double* energy_j;    /* n_inst * power * window_s                                     */
+  double* p99_ttft_ms; /* nearest-rank percentile of per-request TTFT; 0 for an empty cell */
+  double* p99_tbt_ms;
+  uint8_t* flags;
+} dyn_space;
+#define DYN_F_FEASIBLE 1u /* none of the four violations below                          */
+#define DYN_F_OVERLOAD 2u /* per-instance load beyond the last profiled point           */
+#define DYN_F_TTFT 4u     /* p99_ttft_ms > slo_ttft_ms[g]                               */
+#define DYN_F_TBT 8u      /* p99_tbt_ms  > slo_tbt_ms[g]                                */
+#define DYN_F_BUDGET 16u  /* n_inst * tp > gpu_budget[g] > 0                            */
+#define DYN_F_EMPTY 32u   /* the cell holds no request                                  */
+
+/* Status bits kept in the first 4 bytes of a workspace. */
+#define DYN_WS_BAD_OFFSETS 1u /* cell_off not monotone / outside [0, n_req]: cell treated as empty */
+#define DYN_WS_BAD_REQUEST 2u /* ingest: timestamp or model index out of range          */
+
+/* Bytes of workspace dyn_eval_space needs (a multiple of 256). */
+size_t dyn_eval_space_workspace(int32_t n_window, int32_t n_class, int32_t n_config);
+
+/* Evaluates every (cell, configuration) pair.
+ * Per cell: load L = (sum of input + output tokens) / window_s (Section III-A: load in
+ * tokens per second); per configuration: rho = L / (n_inst * max_load_tps) (fair share,
+ * Section IV-A); prefill ms/token, TBT and power from the tables at (f_mhz, min(rho,
+ * rho_max)), interpolated along rho on the two bracketing frequency rows and then along
+ * f; per-request TTFT = input tokens * prefill ms/token, per-request TBT = the table's
+ * TBT; the P99 of both over the cell (nearest rank, rank = ceil(pct_num*m/pct_den));
+ * energy; and the feasibility flags (Eq. 1 constraints 1 and 3).
+ * Arguments: `cfg` HOST [K]; `out` arrays DEVICE; workspace DEVICE, 256-byte aligned, at
+ * least dyn_eval_space_workspace bytes; it keeps the per-cell aggregates that
+ * dyn_cell_stats returns.  Errors: see dyn_status; nothing is launched on error.        */
+int dyn_eval_space(dyn_profile* profile, const dyn_trace_view* trace, const dyn_config* cfg,
+                   int32_t K, const dyn_objective* objective, const dyn_space* out,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Per-cell aggregates of the last dyn_eval_space on `workspace` (exact integers):
+ * tok_in, tok_out = token sums, in_p99 = input length of nearest rank (0 if empty).
+ * Outputs DEVICE [n_window*G]; any may be NULL.  Enqueues device-to-device copies.      */
+int dyn_cell_stats(const void* workspace, size_t workspace_bytes, int32_t n_window,
+                   int32_t n_class, int64_t* tok_in, int64_t* tok_out, int32_t* in_p99,
+                   void* hip_stream);
+
+/* Reads the workspace status word (DYN_WS_* bits) after waiting for `hip_stream`. */
+int dyn_workspace_status(const void* workspace, void* hip_stream, uint32_t* status);
+
+/* Per-cell selection and per-window totals.  DEVICE pointers, caller-owned. */
+typedef struct {
+  int32_t* sel;               /* [cells] index of the chosen configuration, -1 if none  */
+  double* sel_energy_j;       /* [cells] its energy, +inf if none                       */
+  double* sel_cost;           /* [cells] its cost,   +inf if none                       */
+  double* window_energy_j;    /* [n_window] sum of sel_energy_j over classes with a choice, g ascending */
+  int32_t* window_infeasible; /* [n_window] number of classes with sel == -1            */
+} dyn_selection;
+
+/* Section IV-B "Scale-up/down": drop what violates the SLO, then take the least energy.
+ * Reads space->energy_j and space->flags; cost = energy + idle_cost_weight * n_inst *
+ * power(load 0 at that TP and f) * window_s; the lowest index wins exact ties.
+ * `cfg` HOST [K].  space->p99_* are not read and may be NULL.                          */
+int dyn_select_config(dyn_profile* profile, const dyn_space* space, const dyn_config* cfg,
+                      int32_t K, const dyn_objective* objective, int32_t n_window,
+                      double window_s, const dyn_selection* out, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYN_H_ */

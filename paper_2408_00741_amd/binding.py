@@ -1,0 +1,305 @@
+"""ctypes binding of libdyn.so: same names as include/dyn.h, argument marshalling only.
+
+DEVICE arguments are torch tensors on the GPU (PyTorch provides device memory and the
+stream, nothing else); HOST arguments are NumPy arrays.  Every function raises DynError
+when the library returns a negative status.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+import torch
+
+__all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_trace_ingest",
+           "dyn_trace_ingest_workspace", "dyn_eval_space", "dyn_eval_space_workspace", "dyn_cell_stats",
+           "dyn_workspace_status", "dyn_select_config", "dyn_last_error", "lib_path",
+           "DYN_F_FEASIBLE", "DYN_F_OVERLOAD", "DYN_F_TTFT", "DYN_F_TBT", "DYN_F_BUDGET", "DYN_F_EMPTY",
+           "DYN_WS_BAD_OFFSETS", "DYN_WS_BAD_REQUEST"]
+
+DYN_F_FEASIBLE, DYN_F_OVERLOAD, DYN_F_TTFT, DYN_F_TBT, DYN_F_BUDGET, DYN_F_EMPTY = 1, 2, 4, 8, 16, 32
+DYN_WS_BAD_OFFSETS, DYN_WS_BAD_REQUEST = 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libdyn.so")
+
+
+if not os.path.exists(lib_path()):
+    raise ImportError(f"{lib_path()} is missing: build it with `python -m paper_2408_00741_amd` "
+                      "(there is no fallback implementation)")
+_lib = C.CDLL(lib_path())
+
+_vp, _i32, _i64, _f64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_double, C.c_size_t
+
+
+class _ProfileDesc(C.Structure):
+    _fields_ = [("n_class", _i32), ("n_tp", _i32), ("tp", _vp), ("n_f", _i32), ("f_mhz", _vp),
+                ("n_rho", _i32), ("rho", _vp), ("prefill_ms_per_tok", _vp), ("tbt_ms", _vp),
+                ("power_w", _vp), ("max_load_tps", _vp)]
+
+
+class _ClassEdges(C.Structure):
+    _fields_ = [("n_model", _i32), ("n_in_bin", _i32), ("n_out_bin", _i32), ("in_edge", _vp), ("out_edge", _vp)]
+
+
+class _TraceView(C.Structure):
+    _fields_ = [("n_req", _i64), ("n_window", _i32), ("window_s", _f64), ("in_tok", _vp), ("out_tok", _vp),
+                ("cell_off", _vp)]
+
+
+class _Config(C.Structure):
+    _fields_ = [("n_inst", _i32), ("tp_index", _i32), ("f_mhz", _f64)]
+
+
+class _Objective(C.Structure):
+    _fields_ = [("slo_ttft_ms", _vp), ("slo_tbt_ms", _vp), ("pct_num", _i32), ("pct_den", _i32),
+                ("gpu_budget", _vp), ("idle_cost_weight", _f64)]
+
+
+class _Space(C.Structure):
+    _fields_ = [("energy_j", _vp), ("p99_ttft_ms", _vp), ("p99_tbt_ms", _vp), ("flags", _vp)]
+
+
+class _Selection(C.Structure):
+    _fields_ = [("sel", _vp), ("sel_energy_j", _vp), ("sel_cost", _vp), ("window_energy_j", _vp),
+                ("window_infeasible", _vp)]
+
+
+_lib.dyn_last_error.restype = C.c_char_p
+_lib.dyn_profile_load.restype = C.c_int
+_lib.dyn_profile_load.argtypes = [C.POINTER(_ProfileDesc), _vp, C.POINTER(_vp)]
+_lib.dyn_profile_free.restype = None
+_lib.dyn_profile_free.argtypes = [_vp]
+_lib.dyn_trace_ingest_workspace.restype = _sz
+_lib.dyn_trace_ingest_workspace.argtypes = [_i64, _i32, _i32]
+_lib.dyn_trace_ingest.restype = C.c_int
+_lib.dyn_trace_ingest.argtypes = [_vp, _vp, _vp, _vp, _i64, C.POINTER(_ClassEdges), _i32, _f64, _vp, _vp, _vp,
+                                  _vp, _sz, _vp]
+_lib.dyn_eval_space_workspace.restype = _sz
+_lib.dyn_eval_space_workspace.argtypes = [_i32, _i32, _i32]
+_lib.dyn_eval_space.restype = C.c_int
+_lib.dyn_eval_space.argtypes = [_vp, C.POINTER(_TraceView), C.POINTER(_Config), _i32, C.POINTER(_Objective),
+                                C.POINTER(_Space), _vp, _sz, _vp]
+_lib.dyn_cell_stats.restype = C.c_int
+_lib.dyn_cell_stats.argtypes = [_vp, _sz, _i32, _i32, _vp, _vp, _vp, _vp]
+_lib.dyn_workspace_status.restype = C.c_int
+_lib.dyn_workspace_status.argtypes = [_vp, _vp, C.POINTER(C.c_uint32)]
+_lib.dyn_select_config.restype = C.c_int
+_lib.dyn_select_config.argtypes = [_vp, C.POINTER(_Space), C.POINTER(_Config), _i32, C.POINTER(_Objective), _i32,
+                                   _f64, C.POINTER(_Selection), _vp]
+
+
+class DynError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where} failed with status {status}: {dyn_last_error()}")
+
+
+def dyn_last_error() -> str:
+    return (_lib.dyn_last_error() or b"").decode()
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise DynError(rc, where)
+
+
+def _host(a, dt) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dt)
+
+
+def _hp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data
+
+
+def _dp(t: Optional[torch.Tensor], dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous GPU tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+class Profile:
+    """Owner of a dyn_profile handle."""
+
+    def __init__(self, handle: int, shape):
+        self.handle = handle
+        self.n_class, self.n_tp, self.n_f, self.n_rho = shape
+
+    def free(self):
+        if self.handle:
+            _lib.dyn_profile_free(self.handle)
+            self.handle = 0
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def dyn_profile_load(profile: Dict[str, np.ndarray], stream=None) -> Profile:
+    tp = _host(profile["tp"], np.int32); fg = _host(profile["f_mhz"], np.float64)
+    rg = _host(profile["rho"], np.float64)
+    pf = _host(profile["prefill_ms_per_tok"], np.float64); tb = _host(profile["tbt_ms"], np.float64)
+    pw = _host(profile["power_w"], np.float64); ml = _host(profile["max_load_tps"], np.float64)
+    G = pf.shape[0] if pf.ndim == 4 else 0
+    want = (G, tp.size, fg.size, rg.size)
+    if pf.shape != want or tb.shape != want or pw.shape != want or ml.shape != want[:3]:
+        raise ValueError(f"profile tables must have shape {want} / {want[:3]}")
+    d = _ProfileDesc(G, tp.size, _hp(tp), fg.size, _hp(fg), rg.size, _hp(rg), _hp(pf), _hp(tb), _hp(pw), _hp(ml))
+    h = _vp()
+    _check(_lib.dyn_profile_load(C.byref(d), _stream(stream), C.byref(h)), "dyn_profile_load")
+    return Profile(h.value, want)
+
+
+def dyn_profile_free(p: Profile):
+    p.free()
+
+
+def dyn_trace_ingest_workspace(n_req: int, n_window: int, n_class: int) -> int:
+    return int(_lib.dyn_trace_ingest_workspace(n_req, n_window, n_class))
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)   # torch allocations are 512 B aligned
+
+
+def dyn_trace_ingest(t_s: torch.Tensor, in_tok: torch.Tensor, out_tok: torch.Tensor,
+                     model: Optional[torch.Tensor], edges: Dict[str, np.ndarray], n_window: int, window_s: float,
+                     workspace: Optional[torch.Tensor] = None, stream=None):
+    """Returns (in_sorted, out_sorted, cell_off, workspace)."""
+    ie = _host(edges["in_edge"], np.int32); oe = _host(edges["out_edge"], np.int32)
+    if ie.ndim != 2 or oe.ndim != 2 or ie.shape[0] != oe.shape[0]:
+        raise ValueError("edges must be [n_model][bins-1]")
+    n_model, bi, bo = ie.shape[0], ie.shape[1] + 1, oe.shape[1] + 1
+    G = n_model * bi * bo
+    n = t_s.numel()
+    dev = t_s.device
+    e = _ClassEdges(n_model, bi, bo, _hp(ie), _hp(oe))
+    need = dyn_trace_ingest_workspace(n, n_window, G)
+    if workspace is None:
+        workspace = _workspace(need, dev)
+    ins = torch.empty(n, dtype=torch.int32, device=dev); outs = torch.empty(n, dtype=torch.int32, device=dev)
+    off = torch.empty(n_window * G + 1, dtype=torch.int64, device=dev)
+    _check(_lib.dyn_trace_ingest(_dp(t_s, torch.float64, "t_s"), _dp(in_tok, torch.int32, "in_tok"),
+                                 _dp(out_tok, torch.int32, "out_tok"), _dp(model, torch.int32, "model"), n,
+                                 C.byref(e), n_window, float(window_s), _dp(ins), _dp(outs), _dp(off),
+                                 _dp(workspace), workspace.numel(), _stream(stream)), "dyn_trace_ingest")
+    return ins, outs, off, workspace
+
+
+def dyn_eval_space_workspace(n_window: int, n_class: int, n_config: int) -> int:
+    return int(_lib.dyn_eval_space_workspace(n_window, n_class, n_config))
+
+
+def _configs(configs: Dict[str, np.ndarray]):
+    n = _host(configs["n_inst"], np.int32); t = _host(configs["tp_index"], np.int32)
+    f = _host(configs["f_mhz"], np.float64)
+    K = n.size
+    arr = (_Config * K)()
+    for k in range(K):
+        arr[k].n_inst = int(n[k]); arr[k].tp_index = int(t[k]); arr[k].f_mhz = float(f[k])
+    return arr, K
+
+
+def _objective(slos: Dict[str, np.ndarray], pct: Sequence[int], gpu_budget, idle_cost_weight: float):
+    st = _host(slos["slo_ttft_ms"], np.float64); sb = _host(slos["slo_tbt_ms"], np.float64)
+    bud = None if gpu_budget is None else _host(gpu_budget, np.int32)
+    o = _Objective(_hp(st), _hp(sb), int(pct[0]), int(pct[1]), _hp(bud), float(idle_cost_weight))
+    return o, (st, sb, bud)      # keep the arrays alive
+
+
+class Plan:
+    """Marshalled candidate list and objective, reusable across calls (host side only)."""
+
+    def __init__(self, configs, slos, pct=(99, 100), gpu_budget=None, idle_cost_weight=0.0):
+        self.cfg, self.K = _configs(configs)
+        self.obj, self._keep = _objective(slos, pct, gpu_budget, idle_cost_weight)
+        self.n_class = self._keep[0].size
+
+
+__all__.append("Plan")
+
+
+def dyn_eval_space(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tensor, cell_off: torch.Tensor,
+                   n_window: int, window_s: float, plan: Plan, out: Optional[Dict[str, torch.Tensor]] = None,
+                   workspace: Optional[torch.Tensor] = None, stream=None):
+    """Returns (space dict of [cells, K] tensors, workspace)."""
+    G, K = profile.n_class, plan.K
+    if plan.n_class != G:
+        raise ValueError("SLO arrays must have one entry per class")
+    cells = n_window * G
+    if cell_off.numel() != cells + 1:
+        raise ValueError("cell_off must have n_window*G + 1 entries")
+    dev = cell_off.device
+    if out is None:
+        out = {"energy_j": torch.empty((cells, K), dtype=torch.float64, device=dev),
+               "p99_ttft_ms": torch.empty((cells, K), dtype=torch.float64, device=dev),
+               "p99_tbt_ms": torch.empty((cells, K), dtype=torch.float64, device=dev),
+               "flags": torch.empty((cells, K), dtype=torch.uint8, device=dev)}
+    if workspace is None:
+        workspace = _workspace(dyn_eval_space_workspace(n_window, G, K), dev)
+    tv = _TraceView(in_tok.numel(), n_window, float(window_s), _dp(in_tok, torch.int32, "in_tok"),
+                    _dp(out_tok, torch.int32, "out_tok"), _dp(cell_off, torch.int64, "cell_off"))
+    sp = _Space(_dp(out["energy_j"], torch.float64), _dp(out["p99_ttft_ms"], torch.float64),
+                _dp(out["p99_tbt_ms"], torch.float64), _dp(out["flags"], torch.uint8))
+    for v in out.values():
+        if v.numel() != cells * K:
+            raise ValueError("space tensors must hold n_window*G*K entries")
+    _check(_lib.dyn_eval_space(profile.handle, C.byref(tv), plan.cfg, K, C.byref(plan.obj), C.byref(sp),
+                               _dp(workspace), workspace.numel(), _stream(stream)), "dyn_eval_space")
+    return out, workspace
+
+
+def dyn_cell_stats(workspace: torch.Tensor, n_window: int, n_class: int, stream=None):
+    """Returns (tok_in, tok_out, in_p99) of the last dyn_eval_space on `workspace`."""
+    cells = n_window * n_class
+    dev = workspace.device
+    ti = torch.empty(cells, dtype=torch.int64, device=dev); to = torch.empty(cells, dtype=torch.int64, device=dev)
+    p = torch.empty(cells, dtype=torch.int32, device=dev)
+    _check(_lib.dyn_cell_stats(_dp(workspace), workspace.numel(), n_window, n_class, _dp(ti), _dp(to), _dp(p),
+                               _stream(stream)), "dyn_cell_stats")
+    return ti, to, p
+
+
+def dyn_workspace_status(workspace: torch.Tensor, stream=None) -> int:
+    st = C.c_uint32(0)
+    _check(_lib.dyn_workspace_status(_dp(workspace), _stream(stream), C.byref(st)), "dyn_workspace_status")
+    return int(st.value)
+
+
+def dyn_select_config(profile: Profile, space: Dict[str, torch.Tensor], n_window: int, window_s: float, plan: Plan,
+                      out: Optional[Dict[str, torch.Tensor]] = None, stream=None) -> Dict[str, torch.Tensor]:
+    G, K = profile.n_class, plan.K
+    cells = n_window * G
+    dev = space["energy_j"].device
+    if space["energy_j"].numel() != cells * K or space["flags"].numel() != cells * K:
+        raise ValueError("space tensors must hold n_window*G*K entries")
+    if out is None:
+        out = {"sel": torch.empty(cells, dtype=torch.int32, device=dev),
+               "sel_energy_j": torch.empty(cells, dtype=torch.float64, device=dev),
+               "sel_cost": torch.empty(cells, dtype=torch.float64, device=dev),
+               "window_energy_j": torch.empty(n_window, dtype=torch.float64, device=dev),
+               "window_infeasible": torch.empty(n_window, dtype=torch.int32, device=dev)}
+    sp = _Space(_dp(space["energy_j"], torch.float64), _dp(space.get("p99_ttft_ms")), _dp(space.get("p99_tbt_ms")),
+                _dp(space["flags"], torch.uint8))
+    se = _Selection(_dp(out["sel"], torch.int32), _dp(out["sel_energy_j"], torch.float64),
+                    _dp(out["sel_cost"], torch.float64), _dp(out["window_energy_j"], torch.float64),
+                    _dp(out["window_infeasible"], torch.int32))
+    _check(_lib.dyn_select_config(profile.handle, C.byref(sp), plan.cfg, K, C.byref(plan.obj), n_window,
+                                  float(window_s), C.byref(se), _stream(stream)), "dyn_select_config")
+    return out

@@ -1,0 +1,489 @@
+// C ABI of libdyn: argument checks, host-side preparation of the candidate list, and the
+// launch sequences.  All arithmetic of the method runs in the kernels; the only numbers
+// computed here are the frequency bracket and weight of each candidate (one IEEE
+// division per candidate, independent of the trace).
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "dyn_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+bool hip_ok(hipError_t e, const char* what) {
+  if (e == hipSuccess) return true;
+  dyn_set_error("%s: %s", what, hipGetErrorString(e));
+  return false;
+}
+
+__global__ void zero_u32_kernel(uint32_t* p) { *p = 0u; }
+
+bool strictly_increasing(const double* g, int n) {
+  for (int i = 0; i < n; ++i)
+    if (!isfinite(g[i])) return false;
+  for (int i = 1; i < n; ++i)
+    if (!(g[i] > g[i - 1])) return false;
+  return true;
+}
+
+template <typename T>
+hipError_t dev_alloc(T** p, size_t count) {
+  return hipMalloc((void**)p, std::max<size_t>(count, 1) * sizeof(T));
+}
+
+void free_profile_device(dyn_profile* p) {
+  void* ptrs[] = {p->d_pf, p->d_tb, p->d_pw, p->d_ml, p->d_pw0, p->d_rg, p->d_jstart, p->d_cfg,
+                  p->d_tile_rows, p->d_slo_ttft, p->d_slo_tbt, p->d_budget};
+  for (void* q : ptrs)
+    if (q) (void)hipFree(q);
+}
+
+int check_device(const dyn_profile* p) {
+  int dev = -1;
+  if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return DYN_E_DEVICE;
+  if (dev != p->device) {
+    dyn_set_error("profile lives on device %d but device %d is current", p->device, dev);
+    return DYN_E_DEVICE;
+  }
+  return DYN_OK;
+}
+
+// Checks the candidate list and, if it differs from what the handle already holds on the
+// device, rebuilds the device table: frequency bracket/weight per candidate, the tiling
+// of the configuration axis and the table rows each tile stages in LDS.
+int prepare_configs(dyn_profile* p, const dyn_config* cfg, int32_t K, hipStream_t s) {
+  if (!cfg) { dyn_set_error("cfg is NULL"); return DYN_E_NULL; }
+  if (K < 1 || K > DYN_MAX_CONFIGS) { dyn_set_error("K=%d outside [1, %d]", K, DYN_MAX_CONFIGS); return DYN_E_SHAPE; }
+  for (int k = 0; k < K; ++k) {
+    if (cfg[k].n_inst < 1) { dyn_set_error("cfg[%d].n_inst=%d < 1", k, cfg[k].n_inst); return DYN_E_RANGE; }
+    if (cfg[k].tp_index < 0 || cfg[k].tp_index >= p->n_tp) {
+      dyn_set_error("cfg[%d].tp_index=%d outside [0, %d)", k, cfg[k].tp_index, p->n_tp);
+      return DYN_E_RANGE;
+    }
+    if (!(cfg[k].f_mhz >= p->fg.front()) || !(cfg[k].f_mhz <= p->fg.back())) {
+      dyn_set_error("cfg[%d].f_mhz=%g outside the profiled range [%g, %g]", k, cfg[k].f_mhz, p->fg.front(),
+                    p->fg.back());
+      return DYN_E_RANGE;
+    }
+  }
+  if ((int32_t)p->cfg_host.size() == K) {
+    bool same = true;
+    for (int k = 0; k < K && same; ++k)
+      same = cfg[k].n_inst == p->cfg_host[k].n_inst && cfg[k].tp_index == p->cfg_host[k].tp_index &&
+             cfg[k].f_mhz == p->cfg_host[k].f_mhz;
+    if (same) return DYN_OK;
+  }
+
+  std::vector<DevCfg> dc(K);
+  const int n_f = p->n_f;
+  for (int k = 0; k < K; ++k) {
+    int fi = 0;
+    double u = 0.0;
+    if (n_f > 1) {
+      for (int q = 0; q < n_f; ++q)
+        if (p->fg[q] <= cfg[k].f_mhz) fi = q;
+      if (fi > n_f - 2) fi = n_f - 2;
+      u = (cfg[k].f_mhz - p->fg[fi]) / (p->fg[fi + 1] - p->fg[fi]);
+      if (u == 1.0) { fi += 1; u = 0.0; }  // weight 1 on the upper row is that row itself
+    }
+    DevCfg& d = dc[k];
+    d.u = u;
+    d.nd = (double)cfg[k].n_inst;
+    d.n = cfg[k].n_inst;
+    const int64_t gpus = (int64_t)cfg[k].n_inst * p->tp[cfg[k].tp_index];
+    d.gpus = gpus > 0x7FFFFFFF ? 0x7FFFFFFF : (int32_t)gpus;
+    d.row_lo = cfg[k].tp_index * n_f + fi;
+    d.row_hi = u != 0.0 ? d.row_lo + 1 : d.row_lo;
+    d.slot_lo = d.slot_hi = 0;
+  }
+  // tiling of the configuration axis: least padding, then the widest tile
+  const int cand[4] = {256, 192, 128, 64};
+  int order[4] = {0, 1, 2, 3};
+  std::stable_sort(order, order + 4, [&](int a, int b) {
+    const int wa = (K + cand[a] - 1) / cand[a] * cand[a] - K, wb = (K + cand[b] - 1) / cand[b] * cand[b] - K;
+    return wa < wb;
+  });
+  const size_t lds_tail = (size_t)p->n_rho * sizeof(double) + ((size_t)p->n_bucket + 1) * sizeof(int32_t);
+  std::vector<int32_t> rows;
+  int tile = cand[order[0]], n_tile = (K + tile - 1) / tile, n_slot = 0;
+  bool fits = false;
+  for (int oi = 0; oi < 4 && !fits; ++oi) {
+    const int t = cand[order[oi]], nt = (K + t - 1) / t;
+    std::vector<std::vector<int32_t>> per_tile(nt);
+    int ns = 0;
+    for (int k = 0; k < K; ++k) {
+      std::vector<int32_t>& v = per_tile[k / t];
+      for (int32_t r : {dc[k].row_lo, dc[k].row_hi})
+        if (std::find(v.begin(), v.end(), r) == v.end()) v.push_back(r);
+      ns = std::max<int>(ns, (int)v.size());
+    }
+    if ((size_t)ns * 3 * p->n_rho * sizeof(double) + lds_tail <= DYN_LDS_BUDGET) {
+      fits = true;
+      tile = t; n_tile = nt; n_slot = ns;
+      rows.assign((size_t)nt * ns, -1);
+      for (int q = 0; q < nt; ++q)
+        for (size_t i = 0; i < per_tile[q].size(); ++i) rows[(size_t)q * ns + i] = per_tile[q][i];
+      for (int k = 0; k < K; ++k) {
+        const std::vector<int32_t>& v = per_tile[k / t];
+        dc[k].slot_lo = (int32_t)(std::find(v.begin(), v.end(), dc[k].row_lo) - v.begin());
+        dc[k].slot_hi = (int32_t)(std::find(v.begin(), v.end(), dc[k].row_hi) - v.begin());
+      }
+    }
+  }
+  if (!fits) {  // rows do not fit LDS at any tile width: read the tables from global memory
+    tile = cand[order[0]]; n_tile = (K + tile - 1) / tile; n_slot = 0;
+    if (lds_tail > DYN_LDS_BUDGET) {
+      dyn_set_error("load grid of %d points does not fit in LDS", p->n_rho);
+      return DYN_E_SHAPE;
+    }
+  }
+  // the previous table may still be read by work enqueued on this stream
+  if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) return DYN_E_DEVICE;
+  p->cfg_host.clear();
+  if (!hip_ok(hipMemcpy(p->d_cfg, dc.data(), (size_t)K * sizeof(DevCfg), hipMemcpyHostToDevice), "copy configs"))
+    return DYN_E_DEVICE;
+  if (!rows.empty() &&
+      !hip_ok(hipMemcpy(p->d_tile_rows, rows.data(), rows.size() * sizeof(int32_t), hipMemcpyHostToDevice),
+              "copy tile rows"))
+    return DYN_E_DEVICE;
+  p->tile = tile; p->n_tile = n_tile; p->n_slot = n_slot;
+  p->cfg_host.assign(cfg, cfg + K);
+  return DYN_OK;
+}
+
+int prepare_objective(dyn_profile* p, const dyn_objective* o, hipStream_t s) {
+  if (!o) { dyn_set_error("objective is NULL"); return DYN_E_NULL; }
+  if (!o->slo_ttft_ms || !o->slo_tbt_ms) { dyn_set_error("SLO arrays are NULL"); return DYN_E_NULL; }
+  if (o->pct_num < 1 || o->pct_den < 1 || o->pct_num > o->pct_den) {
+    dyn_set_error("percentile %d/%d outside (0, 1]", o->pct_num, o->pct_den);
+    return DYN_E_RANGE;
+  }
+  if (!isfinite(o->idle_cost_weight)) { dyn_set_error("idle_cost_weight is not finite"); return DYN_E_NOTFINITE; }
+  const int G = p->G;
+  for (int g = 0; g < G; ++g) {
+    if (isnan(o->slo_ttft_ms[g]) || isnan(o->slo_tbt_ms[g])) { dyn_set_error("SLO of class %d is NaN", g); return DYN_E_NOTFINITE; }
+    if (o->gpu_budget && o->gpu_budget[g] < 0) { dyn_set_error("gpu_budget[%d] < 0", g); return DYN_E_RANGE; }
+  }
+  std::vector<int32_t> bud(G, 0);
+  if (o->gpu_budget) bud.assign(o->gpu_budget, o->gpu_budget + G);
+  if (p->obj_valid && memcmp(p->slo_ttft_host.data(), o->slo_ttft_ms, G * sizeof(double)) == 0 &&
+      memcmp(p->slo_tbt_host.data(), o->slo_tbt_ms, G * sizeof(double)) == 0 && bud == p->budget_host)
+    return DYN_OK;
+  if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) return DYN_E_DEVICE;
+  p->obj_valid = false;
+  if (!hip_ok(hipMemcpy(p->d_slo_ttft, o->slo_ttft_ms, G * sizeof(double), hipMemcpyHostToDevice), "copy SLOs") ||
+      !hip_ok(hipMemcpy(p->d_slo_tbt, o->slo_tbt_ms, G * sizeof(double), hipMemcpyHostToDevice), "copy SLOs") ||
+      !hip_ok(hipMemcpy(p->d_budget, bud.data(), G * sizeof(int32_t), hipMemcpyHostToDevice), "copy budgets"))
+    return DYN_E_DEVICE;
+  p->slo_ttft_host.assign(o->slo_ttft_ms, o->slo_ttft_ms + G);
+  p->slo_tbt_host.assign(o->slo_tbt_ms, o->slo_tbt_ms + G);
+  p->budget_host = bud;
+  p->obj_valid = true;
+  return DYN_OK;
+}
+
+struct IngestWs {
+  size_t status, in_edge, out_edge, key_a, key_b, in_tmp, out_tmp, hist, total;
+};
+IngestWs ingest_ws_layout(int64_t n_req, int32_t n_model, int32_t n_in_bin, int32_t n_out_bin) {
+  IngestWs w;
+  size_t off = 0;
+  w.status = off; off += 256;
+  w.in_edge = off; off += align256((size_t)n_model * std::max(n_in_bin - 1, 1) * 4);
+  w.out_edge = off; off += align256((size_t)n_model * std::max(n_out_bin - 1, 1) * 4);
+  const size_t n = (size_t)std::max<int64_t>(n_req, 1);
+  w.key_a = off; off += align256(n * 4);
+  w.key_b = off; off += align256(n * 4);
+  w.in_tmp = off; off += align256(n * 4);
+  w.out_tmp = off; off += align256(n * 4);
+  const size_t nb = (size_t)dyn_ingest_blocks(n_req);
+  w.hist = off; off += align256(((size_t)DYN_INGEST_MAX_BINS * nb + (DYN_INGEST_MAX_BINS * nb) / 4096 + 2) * 4);
+  w.total = off;
+  return w;
+}
+
+}  // namespace
+
+void dyn_set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+EvalWs dyn_eval_ws_layout(int64_t cells) {
+  EvalWs w;
+  size_t off = 0;
+  const size_t c = (size_t)std::max<int64_t>(cells, 1);
+  w.status = off; off += 256;
+  w.tin = off; off += align256(c * 8);
+  w.tout = off; off += align256(c * 8);
+  w.in_p99 = off; off += align256(c * 4);
+  w.rec = off; off += align256(c * sizeof(CellRec));
+  w.total = off;
+  return w;
+}
+
+extern "C" {
+
+const char* dyn_last_error(void) { return g_err; }
+
+int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** out) {
+  if (!d || !out) { dyn_set_error("desc or out is NULL"); return DYN_E_NULL; }
+  *out = nullptr;
+  if (!d->tp || !d->f_mhz || !d->rho || !d->prefill_ms_per_tok || !d->tbt_ms || !d->power_w || !d->max_load_tps) {
+    dyn_set_error("a profile array is NULL");
+    return DYN_E_NULL;
+  }
+  if (d->n_class < 1 || d->n_tp < 1 || d->n_f < 1 || d->n_rho < 2) {
+    dyn_set_error("profile shape G=%d n_tp=%d n_f=%d n_rho=%d is invalid", d->n_class, d->n_tp, d->n_f, d->n_rho);
+    return DYN_E_SHAPE;
+  }
+  const size_t n_row = (size_t)d->n_class * d->n_tp * d->n_f, n_tab = n_row * d->n_rho;
+  if (n_tab > ((size_t)1 << 31)) { dyn_set_error("profile tables too large"); return DYN_E_SHAPE; }
+  for (int i = 0; i < d->n_tp; ++i)
+    if (d->tp[i] < 1 || (i > 0 && d->tp[i] <= d->tp[i - 1])) { dyn_set_error("tp[] must be >= 1 and strictly increasing"); return DYN_E_ORDER; }
+  if (!strictly_increasing(d->f_mhz, d->n_f)) { dyn_set_error("f_mhz[] must be finite and strictly increasing"); return DYN_E_ORDER; }
+  if (!strictly_increasing(d->rho, d->n_rho)) { dyn_set_error("rho[] must be finite and strictly increasing"); return DYN_E_ORDER; }
+  if (d->rho[0] != 0.0) { dyn_set_error("rho[0] must be 0"); return DYN_E_RANGE; }
+  for (size_t i = 0; i < n_tab; ++i) {
+    const double a = d->prefill_ms_per_tok[i], b = d->tbt_ms[i], c = d->power_w[i];
+    if (!isfinite(a) || !isfinite(b) || !isfinite(c) || a < 0.0 || b < 0.0 || c < 0.0) {
+      dyn_set_error("table entry %zu is negative or not finite", i);
+      return DYN_E_NOTFINITE;
+    }
+  }
+  for (size_t i = 0; i < n_row; ++i)
+    if (!isfinite(d->max_load_tps[i]) || !(d->max_load_tps[i] > 0.0)) {
+      dyn_set_error("max_load_tps[%zu] must be finite and > 0", i);
+      return DYN_E_NOTFINITE;
+    }
+
+  dyn_profile* p = new (std::nothrow) dyn_profile();
+  if (!p) { dyn_set_error("out of host memory"); return DYN_E_DEVICE; }
+  p->G = d->n_class; p->n_tp = d->n_tp; p->n_f = d->n_f; p->n_rho = d->n_rho;
+  p->tp.assign(d->tp, d->tp + d->n_tp);
+  p->fg.assign(d->f_mhz, d->f_mhz + d->n_f);
+  p->d_pf = p->d_tb = p->d_pw = p->d_ml = p->d_pw0 = p->d_rg = nullptr;
+  p->d_jstart = nullptr; p->d_cfg = nullptr; p->d_tile_rows = nullptr;
+  p->d_slo_ttft = p->d_slo_tbt = nullptr; p->d_budget = nullptr;
+  p->obj_valid = false; p->tile = p->n_tile = p->n_slot = 0;
+  hipStream_t s = (hipStream_t)hip_stream;
+
+  // bucket index over the load axis
+  const double rho_max = d->rho[d->n_rho - 1];
+  p->n_bucket = std::min(4 * d->n_rho, 4096);
+  p->bucket_scale = (double)p->n_bucket / rho_max;
+  std::vector<int32_t> js(p->n_bucket + 1);
+  for (int b = 0; b <= p->n_bucket; ++b) {
+    const double x = (double)b / p->bucket_scale;
+    int j = 0;
+    for (int q = 0; q < d->n_rho; ++q)
+      if (d->rho[q] <= x) j = q;
+    js[b] = j;
+  }
+  std::vector<double> pw0(n_row);
+  for (size_t r = 0; r < n_row; ++r) pw0[r] = d->power_w[r * d->n_rho];
+
+  bool ok = hip_ok(hipGetDevice(&p->device), "hipGetDevice") &&
+            hip_ok(dev_alloc(&p->d_pf, n_tab), "hipMalloc") && hip_ok(dev_alloc(&p->d_tb, n_tab), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_pw, n_tab), "hipMalloc") && hip_ok(dev_alloc(&p->d_ml, n_row), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_pw0, n_row), "hipMalloc") && hip_ok(dev_alloc(&p->d_rg, d->n_rho), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_jstart, js.size()), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_cfg, DYN_MAX_CONFIGS), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_tile_rows, 2 * DYN_MAX_CONFIGS + 1024), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_slo_ttft, p->G), "hipMalloc") && hip_ok(dev_alloc(&p->d_slo_tbt, p->G), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_budget, p->G), "hipMalloc");
+  ok = ok && hip_ok(hipMemcpyAsync(p->d_pf, d->prefill_ms_per_tok, n_tab * 8, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_tb, d->tbt_ms, n_tab * 8, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_pw, d->power_w, n_tab * 8, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_ml, d->max_load_tps, n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_pw0, pw0.data(), n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_rg, d->rho, (size_t)d->n_rho * 8, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_jstart, js.data(), js.size() * 4, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize");
+  if (!ok) {
+    free_profile_device(p);
+    delete p;
+    return DYN_E_DEVICE;
+  }
+  *out = p;
+  return DYN_OK;
+}
+
+void dyn_profile_free(dyn_profile* p) {
+  if (!p) return;
+  free_profile_device(p);
+  delete p;
+}
+
+size_t dyn_trace_ingest_workspace(int64_t n_req, int32_t n_window, int32_t n_class) {
+  (void)n_window;
+  // edge tables are at most one int per class and axis
+  if (n_req < 0 || n_class < 1) return 0;
+  return ingest_ws_layout(n_req, n_class, 2, 2).total;
+}
+
+int dyn_trace_ingest(const double* t_s, const int32_t* in_tok, const int32_t* out_tok, const int32_t* model,
+                     int64_t n_req, const dyn_class_edges* e, int32_t n_window, double window_s,
+                     int32_t* in_sorted, int32_t* out_sorted, int64_t* cell_off, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+  if (!e || !cell_off || !workspace) { dyn_set_error("edges, cell_off or workspace is NULL"); return DYN_E_NULL; }
+  if (n_req < 0 || n_req >= ((int64_t)1 << 31)) { dyn_set_error("n_req=%lld outside [0, 2^31)", (long long)n_req); return DYN_E_SHAPE; }
+  if (n_req > 0 && (!t_s || !in_tok || !out_tok || !in_sorted || !out_sorted)) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
+  if (e->n_model < 1 || e->n_in_bin < 1 || e->n_out_bin < 1 || n_window < 1) { dyn_set_error("class or window counts < 1"); return DYN_E_SHAPE; }
+  if ((e->n_in_bin > 1 && !e->in_edge) || (e->n_out_bin > 1 && !e->out_edge)) { dyn_set_error("edge array is NULL"); return DYN_E_NULL; }
+  if (!(window_s > 0.0) || !isfinite(window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  const int64_t G = (int64_t)e->n_model * e->n_in_bin * e->n_out_bin;
+  const int64_t cells = G * n_window;
+  if (G >= ((int64_t)1 << 30) || cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
+  for (int m = 0; m < e->n_model; ++m) {
+    for (int i = 1; i < e->n_in_bin - 1; ++i)
+      if (e->in_edge[m * (e->n_in_bin - 1) + i] <= e->in_edge[m * (e->n_in_bin - 1) + i - 1]) { dyn_set_error("in_edge of model %d not strictly increasing", m); return DYN_E_ORDER; }
+    for (int i = 1; i < e->n_out_bin - 1; ++i)
+      if (e->out_edge[m * (e->n_out_bin - 1) + i] <= e->out_edge[m * (e->n_out_bin - 1) + i - 1]) { dyn_set_error("out_edge of model %d not strictly increasing", m); return DYN_E_ORDER; }
+  }
+  if (n_req > 0 && (in_sorted == in_tok || out_sorted == out_tok || in_sorted == out_tok || out_sorted == in_tok)) {
+    dyn_set_error("sorted outputs alias the inputs");
+    return DYN_E_RANGE;
+  }
+  const IngestWs w = ingest_ws_layout(n_req, e->n_model, e->n_in_bin, e->n_out_bin);
+  if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) {
+    dyn_set_error("workspace misaligned or too small (%zu < %zu)", workspace_bytes, w.total);
+    return DYN_E_WORKSPACE;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* base = (char*)workspace;
+  IngestArgs a;
+  a.t_s = t_s; a.in_tok = in_tok; a.out_tok = out_tok; a.model = model; a.n_req = n_req;
+  a.n_model = e->n_model; a.n_in_bin = e->n_in_bin; a.n_out_bin = e->n_out_bin; a.n_window = n_window;
+  a.window_s = window_s;
+  a.d_in_edge = (const int32_t*)(base + w.in_edge); a.d_out_edge = (const int32_t*)(base + w.out_edge);
+  a.in_sorted = in_sorted; a.out_sorted = out_sorted; a.cell_off = cell_off;
+  a.status = (uint32_t*)(base + w.status);
+  a.key_a = (uint32_t*)(base + w.key_a); a.key_b = (uint32_t*)(base + w.key_b);
+  a.in_tmp = (int32_t*)(base + w.in_tmp); a.out_tmp = (int32_t*)(base + w.out_tmp);
+  a.block_hist = (uint32_t*)(base + w.hist);
+  a.n_block = dyn_ingest_blocks(n_req);
+  int bits = 0;
+  while (((int64_t)1 << bits) < cells) ++bits;
+  a.key_bits = bits;
+  // the edge lists are a few integers: a blocking copy keeps the host arrays free on return
+  if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) return DYN_E_DEVICE;
+  if (e->n_in_bin > 1 && !hip_ok(hipMemcpy(base + w.in_edge, e->in_edge, (size_t)e->n_model * (e->n_in_bin - 1) * 4, hipMemcpyHostToDevice), "copy edges")) return DYN_E_DEVICE;
+  if (e->n_out_bin > 1 && !hip_ok(hipMemcpy(base + w.out_edge, e->out_edge, (size_t)e->n_model * (e->n_out_bin - 1) * 4, hipMemcpyHostToDevice), "copy edges")) return DYN_E_DEVICE;
+  hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(1), 0, s, a.status);
+  if (!hip_ok(hipGetLastError(), "launch")) return DYN_E_DEVICE;
+  if (!hip_ok(dyn_launch_ingest(a, s), "ingest launch")) return DYN_E_DEVICE;
+  return DYN_OK;
+}
+
+size_t dyn_eval_space_workspace(int32_t n_window, int32_t n_class, int32_t n_config) {
+  (void)n_config;
+  if (n_window < 1 || n_class < 1) return 0;
+  return dyn_eval_ws_layout((int64_t)n_window * n_class).total;
+}
+
+int dyn_eval_space(dyn_profile* p, const dyn_trace_view* t, const dyn_config* cfg, int32_t K,
+                   const dyn_objective* o, const dyn_space* out, void* workspace, size_t workspace_bytes,
+                   void* hip_stream) {
+  if (!p || !t || !out || !workspace) { dyn_set_error("profile, trace, out or workspace is NULL"); return DYN_E_NULL; }
+  if (!out->energy_j || !out->p99_ttft_ms || !out->p99_tbt_ms || !out->flags) { dyn_set_error("an output array is NULL"); return DYN_E_NULL; }
+  if (t->n_req < 0 || t->n_req >= ((int64_t)1 << 31) || t->n_window < 1) { dyn_set_error("n_req or n_window out of range"); return DYN_E_SHAPE; }
+  if (!t->cell_off || (t->n_req > 0 && (!t->in_tok || !t->out_tok))) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
+  if (!(t->window_s > 0.0) || !isfinite(t->window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  const int64_t cells = (int64_t)t->n_window * p->G;
+  if (cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
+  int rc = check_device(p);
+  if (rc) return rc;
+  const EvalWs w = dyn_eval_ws_layout(cells);
+  if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) {
+    dyn_set_error("workspace misaligned or too small (%zu < %zu)", workspace_bytes, w.total);
+    return DYN_E_WORKSPACE;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  if ((rc = prepare_configs(p, cfg, K, s)) != DYN_OK) return rc;
+  if ((rc = prepare_objective(p, o, s)) != DYN_OK) return rc;
+
+  char* base = (char*)workspace;
+  uint32_t* status = (uint32_t*)(base + w.status);
+  hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(1), 0, s, status);
+  if (!hip_ok(hipGetLastError(), "launch")) return DYN_E_DEVICE;
+  if (!hip_ok(dyn_launch_cell_aggregate(t->in_tok, t->out_tok, t->cell_off, t->n_req, cells, t->window_s, o->pct_num,
+                                        o->pct_den, (int64_t*)(base + w.tin), (int64_t*)(base + w.tout),
+                                        (int32_t*)(base + w.in_p99), (CellRec*)(base + w.rec), status, s),
+              "cell aggregate launch"))
+    return DYN_E_DEVICE;
+
+  SpaceArgs a;
+  a.pf = p->d_pf; a.tb = p->d_tb; a.pw = p->d_pw; a.ml = p->d_ml; a.rg = p->d_rg;
+  a.jstart = p->d_jstart; a.n_bucket = p->n_bucket; a.bucket_scale = p->bucket_scale;
+  a.G = p->G; a.n_tp_f = p->n_tp * p->n_f; a.n_rho = p->n_rho;
+  a.cfg = p->d_cfg; a.K = K; a.tile = p->tile; a.n_tile = p->n_tile; a.n_slot = p->n_slot;
+  a.tile_rows = p->d_tile_rows;
+  a.slo_ttft = p->d_slo_ttft; a.slo_tbt = p->d_slo_tbt; a.budget = p->d_budget;
+  a.rec = (const CellRec*)(base + w.rec); a.n_window = t->n_window; a.window_s = t->window_s;
+  // enough blocks to fill the chip several times over, long enough runs to amortise staging
+  const int64_t cell_tiles = cells * p->n_tile;
+  a.win_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(32, cell_tiles / 4096));
+  a.energy = out->energy_j; a.p99_ttft = out->p99_ttft_ms; a.p99_tbt = out->p99_tbt_ms; a.flags = out->flags;
+  if (!hip_ok(dyn_launch_space(a, s), "space launch")) return DYN_E_DEVICE;
+  return DYN_OK;
+}
+
+int dyn_cell_stats(const void* workspace, size_t workspace_bytes, int32_t n_window, int32_t n_class,
+                   int64_t* tok_in, int64_t* tok_out, int32_t* in_p99, void* hip_stream) {
+  if (!workspace) { dyn_set_error("workspace is NULL"); return DYN_E_NULL; }
+  if (n_window < 1 || n_class < 1) { dyn_set_error("n_window or n_class < 1"); return DYN_E_SHAPE; }
+  const int64_t cells = (int64_t)n_window * n_class;
+  const EvalWs w = dyn_eval_ws_layout(cells);
+  if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) { dyn_set_error("workspace misaligned or too small"); return DYN_E_WORKSPACE; }
+  hipStream_t s = (hipStream_t)hip_stream;
+  const char* base = (const char*)workspace;
+  if (tok_in && !hip_ok(hipMemcpyAsync(tok_in, base + w.tin, cells * 8, hipMemcpyDeviceToDevice, s), "copy")) return DYN_E_DEVICE;
+  if (tok_out && !hip_ok(hipMemcpyAsync(tok_out, base + w.tout, cells * 8, hipMemcpyDeviceToDevice, s), "copy")) return DYN_E_DEVICE;
+  if (in_p99 && !hip_ok(hipMemcpyAsync(in_p99, base + w.in_p99, cells * 4, hipMemcpyDeviceToDevice, s), "copy")) return DYN_E_DEVICE;
+  return DYN_OK;
+}
+
+int dyn_workspace_status(const void* workspace, void* hip_stream, uint32_t* status) {
+  if (!workspace || !status) { dyn_set_error("workspace or status is NULL"); return DYN_E_NULL; }
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (!hip_ok(hipMemcpyAsync(status, workspace, 4, hipMemcpyDeviceToHost, s), "copy status")) return DYN_E_DEVICE;
+  if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) return DYN_E_DEVICE;
+  return DYN_OK;
+}
+
+int dyn_select_config(dyn_profile* p, const dyn_space* space, const dyn_config* cfg, int32_t K,
+                      const dyn_objective* o, int32_t n_window, double window_s, const dyn_selection* out,
+                      void* hip_stream) {
+  if (!p || !space || !o || !out) { dyn_set_error("profile, space, objective or out is NULL"); return DYN_E_NULL; }
+  if (!space->energy_j || !space->flags) { dyn_set_error("space->energy_j or space->flags is NULL"); return DYN_E_NULL; }
+  if (!out->sel || !out->sel_energy_j || !out->sel_cost || !out->window_energy_j || !out->window_infeasible) { dyn_set_error("an output array is NULL"); return DYN_E_NULL; }
+  if (n_window < 1) { dyn_set_error("n_window < 1"); return DYN_E_SHAPE; }
+  if (!(window_s > 0.0) || !isfinite(window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  if (!isfinite(o->idle_cost_weight)) { dyn_set_error("idle_cost_weight is not finite"); return DYN_E_NOTFINITE; }
+  if ((int64_t)n_window * p->G >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
+  int rc = check_device(p);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if ((rc = prepare_configs(p, cfg, K, s)) != DYN_OK) return rc;
+  SelectArgs a;
+  a.energy = space->energy_j; a.flags = space->flags; a.cfg = p->d_cfg; a.K = K; a.pw0 = p->d_pw0;
+  a.G = p->G; a.n_tp_f = p->n_tp * p->n_f; a.n_window = n_window; a.window_s = window_s;
+  a.idle_w = o->idle_cost_weight;
+  a.sel = out->sel; a.sel_energy = out->sel_energy_j; a.sel_cost = out->sel_cost;
+  a.win_energy = out->window_energy_j; a.win_inf = out->window_infeasible;
+  if (!hip_ok(dyn_launch_select(a, s), "select launch")) return DYN_E_DEVICE;
+  return DYN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,117 @@
+// Internal declarations shared by the HIP sources of libdyn (not part of the ABI).
+#ifndef DYN_INTERNAL_H_
+#define DYN_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "dyn.h"
+
+#define DYN_WAVE 64
+
+// ---- device-side views ------------------------------------------------------------------
+// One candidate configuration, prepared on the host.  (ti, row_lo, row_hi) address table
+// rows; row = ti * n_f + fi.  u is the weight of row_hi; when u == 0 only row_lo is read.
+struct DevCfg {
+  double u;       // frequency weight in [0, 1)
+  double nd;      // (double) n_inst
+  int32_t n;      // n_inst
+  int32_t gpus;   // n_inst * tp (saturated to INT32_MAX)
+  int32_t row_lo; // ti * n_f + fi
+  int32_t row_hi; // ti * n_f + fi + 1 (== row_lo when u == 0)
+  int32_t slot_lo, slot_hi;  // LDS slots of the two rows inside the configuration's tile
+};
+
+struct CellRec {  // what the space kernel needs from a cell
+  double load;    // (tin + tout) / window_s
+  double xp99;    // (double) in_p99, or -1.0 for an empty cell
+};
+
+#define DYN_MAX_CONFIGS 65536     // capacity of a profile handle's configuration table
+#define DYN_MAX_TILE 256          // configurations per tile of the space kernel
+#define DYN_LDS_BUDGET (64 * 1024)
+
+// ---- host-side profile handle -----------------------------------------------------------
+// Besides the tables it owns the device copies of the last candidate list and objective
+// it was used with ("plan"), so that repeated evaluations upload nothing.
+struct dyn_profile {
+  int32_t G, n_tp, n_f, n_rho;
+  std::vector<int32_t> tp;   // host copies used to validate candidate configurations
+  std::vector<double> fg;
+  int device;
+  // device copies; tables keep the caller's [G][n_tp][n_f][n_rho] layout
+  double* d_pf;
+  double* d_tb;
+  double* d_pw;
+  double* d_ml;   // [G][n_tp][n_f]
+  double* d_pw0;  // [G][n_tp][n_f]  power at load 0 (first column of d_pw)
+  double* d_rg;   // [n_rho]
+  // bucket index over the load axis: bucket b covers [b, b+1) / bucket_scale and jstart[b]
+  // is the largest grid index i with rg[i] <= b / bucket_scale
+  int32_t* d_jstart;  // [n_bucket + 1]
+  int32_t n_bucket;
+  double bucket_scale;
+  // plan: candidate list
+  std::vector<dyn_config> cfg_host;   // what d_cfg currently holds
+  DevCfg* d_cfg;                      // [DYN_MAX_CONFIGS]
+  int32_t* d_tile_rows;               // [2*DYN_MAX_CONFIGS + 1024]
+  int32_t tile, n_tile, n_slot;       // n_slot == 0: table rows are read from global memory
+  // plan: objective
+  std::vector<double> slo_ttft_host, slo_tbt_host;
+  std::vector<int32_t> budget_host;
+  bool obj_valid;
+  double* d_slo_ttft;  // [G]
+  double* d_slo_tbt;   // [G]
+  int32_t* d_budget;   // [G]
+};
+
+// Layout of the evaluation workspace (offsets in bytes, all multiples of 256).
+struct EvalWs {
+  size_t status, tin, tout, in_p99, rec, total;
+};
+EvalWs dyn_eval_ws_layout(int64_t cells);
+
+// ---- kernel launchers (each returns a hipError_t from the launch) ------------------------
+hipError_t dyn_launch_cell_aggregate(const int32_t* in_tok, const int32_t* out_tok,
+                                     const int64_t* cell_off, int64_t n_req, int64_t cells,
+                                     double window_s, int32_t pct_num, int32_t pct_den,
+                                     int64_t* tin, int64_t* tout, int32_t* in_p99, CellRec* rec,
+                                     uint32_t* status, hipStream_t s);
+
+struct SpaceArgs {
+  const double* pf; const double* tb; const double* pw; const double* ml; const double* rg;
+  const int32_t* jstart; int32_t n_bucket; double bucket_scale;
+  int32_t G, n_tp_f /* n_tp*n_f */, n_rho;
+  const DevCfg* cfg; int32_t K;
+  int32_t tile, n_tile, n_slot;       // configurations per tile, tiles, LDS slots per tile
+  const int32_t* tile_rows;           // [n_tile][n_slot] table rows staged by each tile (-1 = unused)
+  const double* slo_ttft; const double* slo_tbt; const int32_t* budget;
+  const CellRec* rec; int32_t n_window; int32_t win_per_block; double window_s;
+  double* energy; double* p99_ttft; double* p99_tbt; uint8_t* flags;
+};
+hipError_t dyn_launch_space(const SpaceArgs& a, hipStream_t s);
+
+struct SelectArgs {
+  const double* energy; const uint8_t* flags; const DevCfg* cfg; int32_t K;
+  const double* pw0; int32_t G, n_tp_f; int32_t n_window; double window_s; double idle_w;
+  int32_t* sel; double* sel_energy; double* sel_cost; double* win_energy; int32_t* win_inf;
+};
+hipError_t dyn_launch_select(const SelectArgs& a, hipStream_t s);
+
+struct IngestArgs {
+  const double* t_s; const int32_t* in_tok; const int32_t* out_tok; const int32_t* model;
+  int64_t n_req; int32_t n_model, n_in_bin, n_out_bin, n_window; double window_s;
+  const int32_t* d_in_edge; const int32_t* d_out_edge;   // device copies inside the workspace
+  int32_t* in_sorted; int32_t* out_sorted; int64_t* cell_off;
+  uint32_t* status; uint32_t* key_a; uint32_t* key_b; int32_t* in_tmp; int32_t* out_tmp;
+  uint32_t* block_hist; int64_t n_block; int32_t key_bits;
+};
+hipError_t dyn_launch_ingest(const IngestArgs& a, hipStream_t s);
+int64_t dyn_ingest_blocks(int64_t n_req);
+#define DYN_INGEST_MAX_BINS 1024
+
+void dyn_set_error(const char* fmt, ...);
+
+#endif  // DYN_INTERNAL_H_

@@ -1,0 +1,240 @@
+// Per-cell aggregation and rank selection: one wavefront per (window, class) cell streams
+// the cell's requests once and produces the exact token sums (the class's load in the
+// window, Section III-A "Request loads") and the input length of nearest rank
+// ceil(pct*m) (the request whose TTFT is the cell's P99 under every configuration, since
+// per-request TTFT = input tokens x a non-negative per-(cell, configuration) factor and
+// IEEE multiplication by a non-negative constant is monotone).
+//
+// Cells of up to 2048 requests are held in registers (32 values per lane at most) and the
+// selection is a most-significant-bit-first search on the value: for every bit one
+// compare per register row and a scalar population count of the wave mask, no LDS and no
+// cross-lane traffic.  Larger cells are streamed again per 10-bit digit through a
+// per-wave LDS histogram (radix select).
+#include "dyn_internal.h"
+
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+constexpr int kHistBits = 10;
+constexpr int kHistBins = 1 << kHistBits;
+constexpr int kRegRowsMax = 32;  // register path handles m <= 64 * kRegRowsMax
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+// Sum over the 64 lanes of a fully active wave; the result is wave-uniform.
+// Rotations by 1, 2, 4, 8 inside each row of 16 lanes leave the row total in every lane
+// of the row; the four row totals are then read from lanes 0, 16, 32, 48.
+__device__ __forceinline__ int wave_sum_i32(int v) {
+  v += dpp_mov<0x121>(v);  // row_ror:1
+  v += dpp_mov<0x122>(v);  // row_ror:2
+  v += dpp_mov<0x124>(v);  // row_ror:4
+  v += dpp_mov<0x128>(v);  // row_ror:8
+  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
+         __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
+}
+__device__ __forceinline__ uint32_t wave_or_u32(uint32_t x) {
+  int v = (int)x;
+  v |= dpp_mov<0x121>(v);
+  v |= dpp_mov<0x122>(v);
+  v |= dpp_mov<0x124>(v);
+  v |= dpp_mov<0x128>(v);
+  return (uint32_t)(__builtin_amdgcn_readlane(v, 0) | __builtin_amdgcn_readlane(v, 16) |
+                    __builtin_amdgcn_readlane(v, 32) | __builtin_amdgcn_readlane(v, 48));
+}
+
+struct CellOut {
+  int64_t tin, tout;
+  uint32_t p99;
+  uint32_t orv;
+};
+
+// Register-resident cell: m <= 64*R requests.
+template <int R>
+__device__ __forceinline__ CellOut cell_in_registers(const int32_t* __restrict__ in,
+                                                     const int32_t* __restrict__ out, int64_t beg,
+                                                     int m, int rank, int lane) {
+  uint32_t v[R];
+  int lo_in = 0, hi_in = 0, lo_out = 0, hi_out = 0;
+  uint32_t orv = 0;
+#pragma unroll
+  for (int i = 0; i < R; ++i) {
+    const int idx = i * DYN_WAVE + lane;
+    const bool ok = idx < m;
+    const int a = ok ? in[beg + idx] : 0;
+    const int b = ok ? out[beg + idx] : 0;
+    v[i] = ok ? (uint32_t)a : 0xFFFFFFFFu;  // padding is never below a candidate value
+    orv |= (uint32_t)a;
+    // 16-bit halves keep every partial sum inside 32 bits: at most 32 values per lane,
+    // 2048 per wave
+    lo_in += a & 0xFFFF;
+    hi_in += a >> 16;
+    lo_out += b & 0xFFFF;
+    hi_out += b >> 16;
+  }
+  CellOut r;
+  r.tin = ((int64_t)wave_sum_i32(hi_in) << 16) + (int64_t)wave_sum_i32(lo_in);
+  r.tout = ((int64_t)wave_sum_i32(hi_out) << 16) + (int64_t)wave_sum_i32(lo_out);
+  r.orv = wave_or_u32(orv);
+  // largest a with #{v < a} < rank, built from the top bit down
+  uint32_t ans = 0;
+  const int nb = 32 - __builtin_clz(r.orv | 1u);
+  for (int b = nb - 1; b >= 0; --b) {
+    const uint32_t cand = ans | (1u << b);
+    int below = 0;
+#pragma unroll
+    for (int i = 0; i < R; ++i) below += __popcll(__ballot(v[i] < cand));
+    if (below < rank) ans = cand;
+  }
+  r.p99 = ans;
+  return r;
+}
+
+__device__ __forceinline__ int64_t wave_sum_i64(int64_t v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, DYN_WAVE);
+  return v;
+}
+
+// Streaming cell: any m.  hist = this wave's kHistBins counters in LDS.
+__device__ CellOut cell_streamed(const int32_t* __restrict__ in, const int32_t* __restrict__ out,
+                                 int64_t beg, int64_t m, int64_t rank, int lane, uint32_t* hist) {
+  int64_t sin = 0, sout = 0;
+  uint32_t orv = 0;
+  for (int64_t i = lane; i < m; i += DYN_WAVE) {
+    const int a = in[beg + i];
+    const int b = out[beg + i];
+    sin += a;
+    sout += b;
+    orv |= (uint32_t)a;
+  }
+  CellOut r;
+  r.tin = wave_sum_i64(sin);
+  r.tout = wave_sum_i64(sout);
+  r.orv = wave_or_u32(orv);
+
+  int hi_bit = 32 - __builtin_clz(r.orv | 1u);  // bits >= hi_bit of the answer are `prefix`
+  uint32_t prefix = 0;
+  int64_t need = rank;
+  while (hi_bit > 0) {
+    const int w = hi_bit < kHistBits ? hi_bit : kHistBits;
+    const int shift = hi_bit - w;
+    const uint32_t dmask = (1u << w) - 1u;
+    for (int b = lane; b < kHistBins; b += DYN_WAVE) hist[b] = 0;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    for (int64_t i = lane; i < m; i += DYN_WAVE) {
+      const uint32_t a = (uint32_t)in[beg + i];
+      const bool match = hi_bit >= 32 ? true : ((a >> hi_bit) == prefix);
+      if (match) __hip_atomic_fetch_add(&hist[(a >> shift) & dmask], 1u, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_WAVEFRONT);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    // lane l owns bins [16 l, 16 l + 16); find the bin where the running count reaches `need`
+    constexpr int per = kHistBins / DYN_WAVE;
+    uint32_t cnt[per];
+    int64_t mine = 0;
+#pragma unroll
+    for (int q = 0; q < per; ++q) {
+      cnt[q] = hist[lane * per + q];
+      mine += cnt[q];
+    }
+    int64_t incl = mine;  // inclusive scan over lanes
+#pragma unroll
+    for (int d = 1; d < DYN_WAVE; d <<= 1) {
+      const int64_t up = __shfl_up(incl, d, DYN_WAVE);
+      if (lane >= d) incl += up;
+    }
+    const uint64_t reach = __ballot(incl >= need);
+    const int owner = __builtin_ctzll(reach);  // reach != 0 because need <= number of matches
+    // every lane searches its own bins; only the owner's answer is used
+    uint32_t digit = (uint32_t)(lane * per + per - 1);
+    int64_t below = 0;
+    {
+      int64_t run = incl - mine;
+      bool found = false;
+#pragma unroll
+      for (int q = 0; q < per; ++q) {
+        const bool hit = !found && (run + cnt[q] >= need || q == per - 1);
+        if (hit) {
+          digit = (uint32_t)(lane * per + q);
+          below = run;
+          found = true;
+        }
+        run += cnt[q];
+      }
+    }
+    digit = (uint32_t)__shfl((int)digit, owner, DYN_WAVE);
+    below = __shfl(below, owner, DYN_WAVE);
+    need -= below;
+    prefix = (prefix << w) | digit;
+    hi_bit = shift;
+    __builtin_amdgcn_wave_barrier();
+  }
+  r.p99 = prefix;
+  return r;
+}
+
+__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void cell_aggregate_kernel(
+    const int32_t* __restrict__ in, const int32_t* __restrict__ out,
+    const int64_t* __restrict__ cell_off, int64_t n_req, int64_t cells, double window_s,
+    int32_t pct_num, int32_t pct_den, int64_t* __restrict__ tin, int64_t* __restrict__ tout,
+    int32_t* __restrict__ in_p99, CellRec* __restrict__ rec, uint32_t* __restrict__ status) {
+  __shared__ uint32_t hist_all[kWavesPerBlock][kHistBins];
+  const int lane = threadIdx.x & (DYN_WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
+  const int64_t c = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (c >= cells) return;
+  int64_t beg = cell_off[c], end = cell_off[c + 1];
+  uint32_t bad = 0;
+  if (beg < 0 || end < beg || end > n_req) {  // never read outside the trace
+    bad = DYN_WS_BAD_OFFSETS;
+    beg = end = 0;
+  }
+  const int64_t m = end - beg;
+  CellOut r;
+  r.tin = r.tout = 0;
+  r.p99 = 0;
+  r.orv = 0;
+  if (m > 0) {
+    const int64_t rank = ((int64_t)pct_num * m + pct_den - 1) / pct_den;
+    if (m <= DYN_WAVE * kRegRowsMax) {
+      const int mi = (int)m, rk = (int)rank;
+      if (mi <= 64 * 1) r = cell_in_registers<1>(in, out, beg, mi, rk, lane);
+      else if (mi <= 64 * 2) r = cell_in_registers<2>(in, out, beg, mi, rk, lane);
+      else if (mi <= 64 * 4) r = cell_in_registers<4>(in, out, beg, mi, rk, lane);
+      else if (mi <= 64 * 8) r = cell_in_registers<8>(in, out, beg, mi, rk, lane);
+      else if (mi <= 64 * 16) r = cell_in_registers<16>(in, out, beg, mi, rk, lane);
+      else r = cell_in_registers<32>(in, out, beg, mi, rk, lane);
+    } else {
+      r = cell_streamed(in, out, beg, m, rank, lane, hist_all[wave]);
+    }
+    if (r.orv >> 31) bad |= DYN_WS_BAD_REQUEST;  // a negative token count
+  }
+  if (lane == 0) {
+    tin[c] = r.tin;
+    tout[c] = r.tout;
+    in_p99[c] = (int32_t)r.p99;
+    CellRec cr;
+    cr.load = (double)(r.tin + r.tout) / window_s;
+    cr.xp99 = m > 0 ? (double)(int32_t)r.p99 : -1.0;
+    rec[c] = cr;
+    if (bad) atomicOr(status, bad);
+  }
+}
+
+}  // namespace
+
+hipError_t dyn_launch_cell_aggregate(const int32_t* in_tok, const int32_t* out_tok,
+                                     const int64_t* cell_off, int64_t n_req, int64_t cells,
+                                     double window_s, int32_t pct_num, int32_t pct_den,
+                                     int64_t* tin, int64_t* tout, int32_t* in_p99, CellRec* rec,
+                                     uint32_t* status, hipStream_t s) {
+  const int64_t blocks = (cells + kWavesPerBlock - 1) / kWavesPerBlock;
+  hipLaunchKernelGGL(cell_aggregate_kernel, dim3((unsigned)blocks), dim3(kWavesPerBlock * DYN_WAVE),
+                     0, s, in_tok, out_tok, cell_off, n_req, cells, window_s, pct_num, pct_den, tin,
+                     tout, in_p99, rec, status);
+  return hipGetLastError();
+}

@@ -1,0 +1,249 @@
+// Trace ingestion: every request gets the key of its cell (window from the timestamp,
+// class from the input/output length bins of Table IV's convention), then a stable
+// least-significant-digit radix sort by key moves (input tokens, output tokens) into cell
+// order, and the cell offsets are read off the sorted keys.
+//
+// One radix pass = per-block digit histogram -> exclusive scan of the (digit, block)
+// counters -> stable scatter.  Inside a block every wave owns a contiguous run of rows of
+// 64 requests and walks them in order; the position of a request among the requests of
+// its row with the same digit comes from wave ballots, so arrival order is preserved.
+#include "dyn_internal.h"
+
+namespace {
+
+constexpr int kWaves = 4;
+constexpr int kRows = 32;                              // rows of 64 requests per wave
+constexpr int kTile = kWaves * kRows * DYN_WAVE;       // 8192 requests per block
+constexpr int kScanChunk = 4096;                       // counters per block of the scan kernels
+
+__global__ __launch_bounds__(256) void key_kernel(IngestArgs a) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= a.n_req) return;
+  uint32_t bad = 0;
+  double wq = floor(a.t_s[i] / a.window_s);
+  if (!(wq >= 0.0)) { bad = DYN_WS_BAD_REQUEST; wq = 0.0; }                      // negative or NaN
+  if (!(wq < (double)a.n_window)) { bad = DYN_WS_BAD_REQUEST; wq = (double)(a.n_window - 1); }
+  int32_t mdl = a.model ? a.model[i] : 0;
+  if (mdl < 0 || mdl >= a.n_model) { bad = DYN_WS_BAD_REQUEST; mdl = 0; }
+  const int32_t x = a.in_tok[i], y = a.out_tok[i];
+  const int32_t* ie = a.d_in_edge + (size_t)mdl * (a.n_in_bin - 1);
+  const int32_t* oe = a.d_out_edge + (size_t)mdl * (a.n_out_bin - 1);
+  int bi = 0, bo = 0;
+  for (int e = 0; e < a.n_in_bin - 1; ++e) bi += (x >= ie[e]) ? 1 : 0;
+  for (int e = 0; e < a.n_out_bin - 1; ++e) bo += (y >= oe[e]) ? 1 : 0;
+  const int64_t G = (int64_t)a.n_model * a.n_in_bin * a.n_out_bin;
+  const int64_t g = ((int64_t)mdl * a.n_in_bin + bi) * a.n_out_bin + bo;
+  a.key_a[i] = (uint32_t)((int64_t)wq * G + g);
+  if (bad) atomicOr(a.status, bad);
+}
+
+// digit counts of one block's tile -> block_hist[digit * n_block + block]
+__global__ __launch_bounds__(kWaves* DYN_WAVE) void hist_kernel(const uint32_t* __restrict__ keys, int64_t n,
+                                                                int shift, int bits, uint32_t* __restrict__ block_hist,
+                                                                int64_t n_block) {
+  __shared__ uint32_t cnt[DYN_INGEST_MAX_BINS];
+  const int nbins = 1 << bits;
+  const uint32_t mask = (uint32_t)nbins - 1u;
+  for (int b = threadIdx.x; b < nbins; b += blockDim.x) cnt[b] = 0;
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * kTile;
+  for (int r = 0; r < kTile / (kWaves * DYN_WAVE); ++r) {
+    const int64_t idx = base + (int64_t)r * (kWaves * DYN_WAVE) + threadIdx.x;
+    if (idx < n) atomicAdd(&cnt[(keys[idx] >> shift) & mask], 1u);
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < nbins; b += blockDim.x) block_hist[(size_t)b * n_block + blockIdx.x] = cnt[b];
+}
+
+// ---- exclusive scan of `count` uint32 counters in three small kernels --------------------
+__device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_t* total, uint32_t* s_wave) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t incl = v;
+#pragma unroll
+  for (int d = 1; d < DYN_WAVE; d <<= 1) {
+    const uint32_t up = __shfl_up(incl, d, DYN_WAVE);
+    if (lane >= d) incl += up;
+  }
+  if (lane == 63) s_wave[wave] = incl;
+  __syncthreads();
+  uint32_t off = 0, tot = 0;
+  for (int w = 0; w < 4; ++w) {
+    if (w < wave) off += s_wave[w];
+    tot += s_wave[w];
+  }
+  __syncthreads();
+  *total = tot;
+  return off + incl - v;
+}
+
+__global__ __launch_bounds__(256) void scan_reduce_kernel(const uint32_t* __restrict__ x, int64_t count,
+                                                          uint32_t* __restrict__ partial) {
+  __shared__ uint32_t s_wave[4];
+  const int64_t base = (int64_t)blockIdx.x * kScanChunk;
+  uint32_t v = 0;
+  for (int q = 0; q < kScanChunk / 256; ++q) {
+    const int64_t i = base + q * 256 + threadIdx.x;
+    if (i < count) v += x[i];
+  }
+  uint32_t tot;
+  block_exclusive_scan_256(v, &tot, s_wave);
+  if (threadIdx.x == 0) partial[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(256) void scan_partials_kernel(uint32_t* __restrict__ partial, int64_t n_partial) {
+  __shared__ uint32_t s_wave[4];
+  uint32_t carry = 0;
+  for (int64_t base = 0; base < n_partial; base += 256) {
+    const int64_t i = base + threadIdx.x;
+    const uint32_t v = i < n_partial ? partial[i] : 0u;
+    uint32_t tot;
+    const uint32_t ex = block_exclusive_scan_256(v, &tot, s_wave);
+    if (i < n_partial) partial[i] = carry + ex;
+    carry += tot;
+  }
+}
+
+__global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ x, int64_t count,
+                                                         const uint32_t* __restrict__ partial) {
+  __shared__ uint32_t s_wave[4];
+  // thread t owns 16 consecutive counters of the block's chunk
+  constexpr int per = kScanChunk / 256;
+  const int64_t base = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * per;
+  uint32_t v[per], sum = 0;
+#pragma unroll
+  for (int q = 0; q < per; ++q) {
+    v[q] = (base + q < count) ? x[base + q] : 0u;
+    sum += v[q];
+  }
+  uint32_t tot;
+  uint32_t run = partial[blockIdx.x] + block_exclusive_scan_256(sum, &tot, s_wave);
+#pragma unroll
+  for (int q = 0; q < per; ++q) {
+    if (base + q < count) x[base + q] = run;
+    run += v[q];
+  }
+}
+
+// ---- stable scatter of one radix pass -----------------------------------------------------
+__global__ __launch_bounds__(kWaves* DYN_WAVE) void scatter_kernel(
+    const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ in_in, const int32_t* __restrict__ out_in,
+    uint32_t* __restrict__ keys_out, int32_t* __restrict__ in_out, int32_t* __restrict__ out_out, int64_t n,
+    int shift, int bits, const uint32_t* __restrict__ scanned, int64_t n_block) {
+  __shared__ uint32_t wcnt[kWaves][DYN_INGEST_MAX_BINS];
+  const int nbins = 1 << bits;
+  const uint32_t mask = (uint32_t)nbins - 1u;
+  const int lane = threadIdx.x & (DYN_WAVE - 1);
+  const int wave = threadIdx.x / DYN_WAVE;
+  for (int b = threadIdx.x; b < kWaves * DYN_INGEST_MAX_BINS; b += blockDim.x) (&wcnt[0][0])[b] = 0;
+  __syncthreads();
+
+  // phase 1: digit counts of each wave's run of rows
+  const int64_t wbase = (int64_t)blockIdx.x * kTile + (int64_t)wave * (kRows * DYN_WAVE);
+  uint32_t key[kRows];
+#pragma unroll
+  for (int r = 0; r < kRows; ++r) {
+    const int64_t idx = wbase + r * DYN_WAVE + lane;
+    key[r] = idx < n ? keys_in[idx] : 0u;
+    if (idx < n) atomicAdd(&wcnt[wave][(key[r] >> shift) & mask], 1u);
+  }
+  __syncthreads();
+  // phase 2: per digit, the first output position of each wave's requests
+  for (int d = threadIdx.x; d < nbins; d += blockDim.x) {
+    uint32_t run = scanned[(size_t)d * n_block + blockIdx.x];
+    for (int w = 0; w < kWaves; ++w) {
+      const uint32_t c = wcnt[w][d];
+      wcnt[w][d] = run;
+      run += c;
+    }
+  }
+  __syncthreads();
+  // phase 3: rows in order; inside a row, rank among the lanes with the same digit
+  uint32_t* my = wcnt[wave];
+#pragma unroll
+  for (int r = 0; r < kRows; ++r) {
+    const int64_t idx = wbase + r * DYN_WAVE + lane;
+    const bool valid = idx < n;
+    if (__ballot(valid) == 0) break;                     // wave-uniform: nothing left in this run
+    const uint32_t d = (key[r] >> shift) & mask;
+    uint64_t peers = __ballot(valid);
+    for (int b = 0; b < bits; ++b) {
+      const bool bit = (d >> b) & 1u;
+      const uint64_t bal = __ballot(bit);
+      peers &= bit ? bal : ~bal;
+    }
+    const int before = __popcll(peers & ((1ull << lane) - 1ull));
+    const int group = __popcll(peers);
+    uint32_t pos = 0;
+    if (valid) pos = my[d] + (uint32_t)before;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (valid && before == group - 1) my[d] += (uint32_t)group;   // one lane per digit advances it
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (valid) {
+      if (keys_out) keys_out[pos] = key[r];
+      in_out[pos] = in_in[idx];
+      out_out[pos] = out_in[idx];
+    }
+  }
+}
+
+// cell_off[c] = number of requests with key < c, read off the sorted keys
+__global__ __launch_bounds__(256) void offsets_kernel(const uint32_t* __restrict__ keys, int64_t n, int64_t cells,
+                                                      int64_t* __restrict__ cell_off) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i > n) return;
+  const int64_t prev = i == 0 ? -1 : (int64_t)keys[i - 1];
+  int64_t cur = i == n ? cells : (int64_t)keys[i];
+  if (cur > cells) cur = cells;
+  for (int64_t c = prev + 1; c <= cur; ++c) cell_off[c] = i;
+}
+
+}  // namespace
+
+int64_t dyn_ingest_blocks(int64_t n_req) { return n_req > 0 ? (n_req + kTile - 1) / kTile : 1; }
+
+hipError_t dyn_launch_ingest(const IngestArgs& a, hipStream_t s) {
+  const int64_t n = a.n_req;
+  const int64_t cells = (int64_t)a.n_window * a.n_model * a.n_in_bin * a.n_out_bin;
+  hipError_t e;
+  if (n > 0) {
+    hipLaunchKernelGGL(key_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  const int passes = a.key_bits <= 0 ? 1 : (a.key_bits + 9) / 10;
+  const int bits = a.key_bits <= 0 ? 1 : (a.key_bits + passes - 1) / passes;
+  // ping-pong so that the last pass lands in the caller's arrays
+  const uint32_t* k_src = a.key_a;
+  uint32_t* k_dst = a.key_b;
+  const int32_t *i_src = a.in_tok, *o_src = a.out_tok;
+  const uint32_t* sorted_keys = a.key_a;
+  if (n > 0) {
+    for (int p = 0; p < passes; ++p) {
+      const bool to_final = ((passes - 1 - p) % 2) == 0;
+      int32_t* i_dst = to_final ? a.in_sorted : a.in_tmp;
+      int32_t* o_dst = to_final ? a.out_sorted : a.out_tmp;
+      const int shift = p * bits;
+      const int64_t count = (int64_t)(1 << bits) * a.n_block;
+      const int64_t n_part = (count + kScanChunk - 1) / kScanChunk;
+      uint32_t* partial = a.block_hist + (size_t)DYN_INGEST_MAX_BINS * a.n_block;
+      hipLaunchKernelGGL(hist_kernel, dim3((unsigned)a.n_block), dim3(kWaves * DYN_WAVE), 0, s, k_src, n, shift,
+                         bits, a.block_hist, a.n_block);
+      hipLaunchKernelGGL(scan_reduce_kernel, dim3((unsigned)n_part), dim3(256), 0, s, a.block_hist, count, partial);
+      hipLaunchKernelGGL(scan_partials_kernel, dim3(1), dim3(256), 0, s, partial, n_part);
+      hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)n_part), dim3(256), 0, s, a.block_hist, count, partial);
+      hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)a.n_block), dim3(kWaves * DYN_WAVE), 0, s, k_src, i_src,
+                         o_src, k_dst, i_dst, o_dst, n, shift, bits, a.block_hist, a.n_block);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+      sorted_keys = k_dst;
+      i_src = i_dst;
+      o_src = o_dst;
+      uint32_t* old_src = const_cast<uint32_t*>(k_src);   // both key buffers live in the workspace
+      k_src = k_dst;
+      k_dst = old_src;
+    }
+  }
+  hipLaunchKernelGGL(offsets_kernel, dim3((unsigned)((n + 1 + 255) / 256)), dim3(256), 0, s, sorted_keys, n, cells,
+                     a.cell_off);
+  return hipGetLastError();
+}

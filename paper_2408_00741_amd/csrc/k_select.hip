@@ -1,0 +1,90 @@
+// Least-cost feasible configuration per cell (Section IV-B "Scale-up/down": filter what
+// violates the SLO, then take the minimum energy), one wavefront per cell striding the
+// configuration axis, then the per-window totals of the objective (Eq. 1 sums over the
+// pools).  cost = energy + idle_cost_weight * n * power(load 0) * window.
+#include "dyn_internal.h"
+
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+constexpr int32_t kNone = 0x7FFFFFFF;
+
+__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void select_kernel(SelectArgs a) {
+  const int lane = threadIdx.x & (DYN_WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
+  const int64_t cells = (int64_t)a.n_window * a.G;
+  const int64_t cell = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (cell >= cells) return;
+  const int g = (int)(cell % a.G);
+  const double* e_row = a.energy + (size_t)cell * a.K;
+  const uint8_t* f_row = a.flags + (size_t)cell * a.K;
+  const double* pw0_row = a.pw0 + (size_t)g * a.n_tp_f;
+  const bool idle = a.idle_w != 0.0;
+
+  double best_cost = __builtin_inf(), best_e = __builtin_inf();
+  int32_t best_k = kNone;
+  for (int k = lane; k < a.K; k += DYN_WAVE) {
+    const double e = e_row[k];
+    const uint32_t fl = f_row[k];
+    double cost = e;
+    if (idle) {
+      const DevCfg c = a.cfg[k];
+      const double pw0 = (c.u != 0.0) ? (1.0 - c.u) * pw0_row[c.row_lo] + c.u * pw0_row[c.row_hi]
+                                      : pw0_row[c.row_lo];
+      cost = e + a.idle_w * ((c.nd * pw0) * a.window_s);
+    }
+    // first feasible candidate, or strictly cheaper than the best so far (k ascending per lane)
+    if ((fl & DYN_F_FEASIBLE) && (best_k == kNone || cost < best_cost)) {
+      best_cost = cost;
+      best_e = e;
+      best_k = k;
+    }
+  }
+  // wave minimum of (cost, k): lower cost wins, equal cost -> lower index; lanes without a
+  // feasible candidate carry k = kNone and lose every comparison against a real candidate
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    const double oc = __shfl_xor(best_cost, d, DYN_WAVE);
+    const double oe = __shfl_xor(best_e, d, DYN_WAVE);
+    const int32_t ok = __shfl_xor(best_k, d, DYN_WAVE);
+    const bool take = (ok != kNone) && (best_k == kNone || oc < best_cost || (oc == best_cost && ok < best_k));
+    if (take) {
+      best_cost = oc;
+      best_e = oe;
+      best_k = ok;
+    }
+  }
+  if (lane == 0) {
+    a.sel[cell] = best_k == kNone ? -1 : best_k;
+    a.sel_energy[cell] = best_e;    // +inf when nothing is feasible
+    a.sel_cost[cell] = best_cost;
+  }
+}
+
+__global__ void window_totals_kernel(const int32_t* __restrict__ sel, const double* __restrict__ sel_energy,
+                                     int32_t n_window, int32_t G, double* __restrict__ win_energy,
+                                     int32_t* __restrict__ win_inf) {
+  const int w = blockIdx.x * blockDim.x + threadIdx.x;
+  if (w >= n_window) return;
+  double e = 0.0;
+  int32_t ninf = 0;
+  for (int g = 0; g < G; ++g) {  // fixed order: g ascending
+    const size_t c = (size_t)w * G + g;
+    if (sel[c] >= 0) e += sel_energy[c]; else ++ninf;
+  }
+  win_energy[w] = e;
+  win_inf[w] = ninf;
+}
+
+}  // namespace
+
+hipError_t dyn_launch_select(const SelectArgs& a, hipStream_t s) {
+  const int64_t cells = (int64_t)a.n_window * a.G;
+  const int64_t blocks = (cells + kWavesPerBlock - 1) / kWavesPerBlock;
+  hipLaunchKernelGGL(select_kernel, dim3((unsigned)blocks), dim3(kWavesPerBlock * DYN_WAVE), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(window_totals_kernel, dim3((unsigned)((a.n_window + 127) / 128)), dim3(128), 0, s,
+                     a.sel, a.sel_energy, a.n_window, a.G, a.win_energy, a.win_inf);
+  return hipGetLastError();
+}

@@ -1,0 +1,454 @@
+"""Parity of the HIP library (through its C ABI) against the CPU oracle, on a real MI355X."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import SPECS, make
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+RTOL = 1e-9          # tolerance stated for energies and percentiles; results are expected bit-equal
+
+
+@pytest.fixture(scope="module")
+def dyn():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2408_00741_amd as d
+    return d
+
+
+def _dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def gpu_ingest(dyn, w):
+    tr = w["trace"]
+    ins, outs, off, ws = dyn.dyn_trace_ingest(_dev(tr["t_s"]), _dev(tr["in_tok"]), _dev(tr["out_tok"]),
+                                              _dev(tr["model"]), w["edges"], w["n_window"], w["window_s"])
+    return ins, outs, off, ws
+
+
+def gpu_eval(dyn, w, ins, outs, off, gpu_budget=None, prof=None, plan=None):
+    own = prof is None
+    prof = prof or dyn.dyn_profile_load(w["profile"])
+    plan = plan or dyn.Plan(w["configs"], w["slos"], w["pct"], gpu_budget, w["idle_cost_weight"])
+    space, ws = dyn.dyn_eval_space(prof, ins, outs, off, w["n_window"], w["window_s"], plan)
+    sel = dyn.dyn_select_config(prof, space, w["n_window"], w["window_s"], plan)
+    tin, tout, p99 = dyn.dyn_cell_stats(ws, w["n_window"], w["n_class"])
+    status = dyn.dyn_workspace_status(ws)
+    torch.cuda.synchronize()
+    r = {k: v.cpu().numpy() for k, v in space.items()}
+    r.update({k: v.cpu().numpy() for k, v in sel.items()})
+    r.update(tin=tin.cpu().numpy(), tout=tout.cpu().numpy(), in_p99=p99.cpu().numpy(), status=status)
+    if own:
+        prof.free()
+    return r
+
+
+def ora_eval(w, st, gpu_budget=None, cell_ids=None):
+    return oracle.evaluate(w["profile"], st, w["n_window"], w["window_s"], w["configs"], w["slos"], w["pct"],
+                           gpu_budget, w["idle_cost_weight"], cell_ids=cell_ids)
+
+
+def assert_parity(w, g, o, cell_ids=None, check_windows=True):
+    """g: GPU results over all cells; o: oracle results over `cell_ids` (all cells when None)."""
+    idx = np.arange(g["sel"].size) if cell_ids is None else np.asarray(cell_ids)
+    G = w["n_class"]
+    # integer intermediates: bit-exact
+    np.testing.assert_array_equal(g["tin"][idx], o["tin"])
+    np.testing.assert_array_equal(g["tout"][idx], o["tout"])
+    np.testing.assert_array_equal(g["in_p99"][idx], o["in_p99"])
+    # floating point: within 1e-9 relative (absolute 0 where the oracle is 0)
+    for k in ("energy_j", "p99_ttft_ms", "p99_tbt_ms"):
+        a, b = g[k][idx], o[k]
+        assert np.all(np.abs(a - b) <= RTOL * np.abs(b)), k
+    # flags: equal, except where a value sits within 1e-9 of its threshold (none expected)
+    diff = g["flags"][idx] != o["flags"]
+    n_amb = 0
+    if diff.any():
+        c, k = np.nonzero(diff)
+        gg = idx[c] % G
+        st, sb = w["slos"]["slo_ttft_ms"][gg], w["slos"]["slo_tbt_ms"][gg]
+        rg = w["profile"]["rho"]
+        prof, cfg = w["profile"], w["configs"]
+        fidx = np.searchsorted(prof["f_mhz"], cfg["f_mhz"][k])
+        load = (o["tin"][c] + o["tout"][c]) / w["window_s"]
+        rho = load / (cfg["n_inst"][k] * prof["max_load_tps"][gg, cfg["tp_index"][k], np.minimum(fidx, prof["f_mhz"].size - 1)])
+        amb = (np.abs(o["p99_ttft_ms"][c, k] - st) <= RTOL * st) | (np.abs(o["p99_tbt_ms"][c, k] - sb) <= RTOL * sb) | \
+              (np.abs(rho - rg[-1]) <= RTOL * rg[-1])
+        assert amb.all(), f"{(~amb).sum()} flag mismatches away from any threshold"
+        n_amb = int(amb.sum())
+    # selection: bit-exact, except ties within 1e-9 relative among oracle-feasible candidates
+    gs, os_ = g["sel"][idx], o["sel"]
+    bad = np.nonzero(gs != os_)[0]
+    for i in bad:
+        assert n_amb or (gs[i] >= 0 and os_[i] >= 0), "selection differs"
+        if gs[i] >= 0 and os_[i] >= 0 and (o["flags"][i, gs[i]] & 1):
+            assert abs(o["cost"][i, gs[i]] - o["cost"][i, os_[i]]) <= RTOL * abs(o["cost"][i, os_[i]])
+        else:
+            assert n_amb, "selection differs with no ambiguous entry to explain it"
+    ok = gs == os_
+    fin = ok & (os_ >= 0)
+    assert np.all(np.abs(g["sel_energy_j"][idx][fin] - o["sel_energy_j"][fin]) <= RTOL * o["sel_energy_j"][fin])
+    assert np.all(np.abs(g["sel_cost"][idx][fin] - o["sel_cost"][fin]) <= RTOL * np.abs(o["sel_cost"][fin]))
+    none = ok & (os_ < 0)
+    assert np.all(np.isinf(g["sel_energy_j"][idx][none])) and np.all(np.isinf(g["sel_cost"][idx][none]))
+    if check_windows and cell_ids is None:
+        we, wi = oracle.window_totals(o["sel"], o["sel_energy_j"], w["n_window"], G)
+        if not bad.size:
+            assert np.all(np.abs(g["window_energy_j"] - we) <= RTOL * np.abs(we))
+            np.testing.assert_array_equal(g["window_infeasible"], wi)
+    exact = all(np.array_equal(g[k][idx], o[k]) for k in ("energy_j", "p99_ttft_ms", "p99_tbt_ms", "flags"))
+    return {"bit_exact": exact, "ambiguous": n_amb, "sel_mismatch": int(bad.size)}
+
+
+# ------------------------------------------------------------------------------ ingestion
+INGEST_CASES = {
+    "cfg0-full": SPECS[0],
+    "cfg1-40k": SPECS[1].scaled(40_000, 7),
+    "cfg2-300k": SPECS[2].scaled(300_000, 40),
+    "cfg3-100k": SPECS[3].scaled(100_001, 9),
+    "cfg4-250k": SPECS[4].scaled(250_000, 12),
+}
+
+
+@pytest.mark.parametrize("name", list(INGEST_CASES))
+@pytest.mark.parametrize("shuffle", [False, True])
+def test_ingest_matches_oracle(dyn, name, shuffle):
+    w = make(INGEST_CASES[name])
+    if shuffle:      # arrival order is not required to be time order
+        perm = np.random.default_rng(5).permutation(w["trace"]["t_s"].size)
+        w["trace"] = {k: v[perm] for k, v in w["trace"].items()}
+    st = oracle.ingest(w["trace"], w["edges"], w["n_window"], w["window_s"])
+    ins, outs, off, ws = gpu_ingest(dyn, w)
+    assert dyn.dyn_workspace_status(ws) == 0
+    np.testing.assert_array_equal(off.cpu().numpy(), st["cell_off"])
+    np.testing.assert_array_equal(ins.cpu().numpy(), st["in_tok"])
+    np.testing.assert_array_equal(outs.cpu().numpy(), st["out_tok"])
+
+
+def test_ingest_edge_cases(dyn):
+    edges = {"in_edge": np.asarray([[256, 1024]], np.int32), "out_edge": np.asarray([[100, 350]], np.int32)}
+    # Table IV thresholds, values on and around every edge, a window boundary, one request per class
+    x = np.asarray([255, 256, 257, 1023, 1024, 1025, 8192, 1, 1], np.int32)
+    y = np.asarray([349, 350, 351, 99, 100, 101, 8192, 1, 1], np.int32)
+    t = np.asarray([0.0, 59.999, 60.0, 60.0, 119.9, 0.5, 179.99, 120.0, 0.25])
+    tr = {"t_s": t, "in_tok": x, "out_tok": y, "model": np.zeros(9, np.int32)}
+    st = oracle.ingest(tr, edges, 3, 60.0)
+    ins, outs, off, ws = dyn.dyn_trace_ingest(_dev(t), _dev(x), _dev(y), None, edges, 3, 60.0)
+    assert dyn.dyn_workspace_status(ws) == 0
+    np.testing.assert_array_equal(off.cpu().numpy(), st["cell_off"])
+    np.testing.assert_array_equal(ins.cpu().numpy(), st["in_tok"])
+    np.testing.assert_array_equal(outs.cpu().numpy(), st["out_tok"])
+    # empty trace
+    e = torch.empty(0, dtype=torch.float64, device="cuda"); ei = torch.empty(0, dtype=torch.int32, device="cuda")
+    ins, outs, off, ws = dyn.dyn_trace_ingest(e, ei, ei.clone(), None, edges, 3, 60.0)
+    assert off.cpu().numpy().tolist() == [0] * 28 and ins.numel() == 0
+    # one class, one window (a single cell): order must be preserved exactly
+    one = {"in_edge": np.zeros((1, 0), np.int32), "out_edge": np.zeros((1, 0), np.int32)}
+    n = 20_000
+    tag = np.arange(n, dtype=np.int32)
+    ins, outs, off, ws = dyn.dyn_trace_ingest(_dev(np.linspace(0, 59, n)), _dev(tag), _dev(tag[::-1].copy()), None,
+                                              one, 1, 60.0)
+    np.testing.assert_array_equal(ins.cpu().numpy(), tag)
+    assert off.cpu().numpy().tolist() == [0, n]
+    # timestamps outside the windows and a bad model index are reported, never dereferenced out of range
+    bad_t = np.asarray([-1.0, 10.0, 1e9, float("nan")])
+    ins, outs, off, ws = dyn.dyn_trace_ingest(_dev(bad_t), _dev(np.ones(4, np.int32)), _dev(np.ones(4, np.int32)),
+                                              _dev(np.asarray([0, 0, 0, 7], np.int32)), edges, 3, 60.0)
+    assert dyn.dyn_workspace_status(ws) & dyn.DYN_WS_BAD_REQUEST
+    assert off.cpu().numpy()[-1] == 4
+
+
+# ------------------------------------------------------------------- evaluation + selection
+EVAL_CASES = {
+    "cfg0-full": (SPECS[0], None),
+    "cfg1-60k": (SPECS[1].scaled(60_000, 6), None),
+    "cfg1-bigcells": (SPECS[1].scaled(150_000, 2), None),          # cells of ~10^4 requests: streamed path
+    "cfg2-200k": (SPECS[2].scaled(200_000, 29), None),
+    "cfg3-150k": (SPECS[3].scaled(150_000, 5), None),
+    "cfg4-120k": (SPECS[4].scaled(120_000, 3), None),
+    "cfg2-budget": (SPECS[2].scaled(50_000, 7), "budget"),
+}
+
+
+@pytest.mark.parametrize("name", list(EVAL_CASES))
+def test_eval_and_select_match_oracle(dyn, name):
+    spec, extra = EVAL_CASES[name]
+    w = make(spec)
+    bud = None
+    if extra == "budget":
+        bud = (np.arange(w["n_class"]) % 4 * 8).astype(np.int32)        # 0 (unlimited), 8, 16, 24 GPUs
+    st = oracle.ingest(w["trace"], w["edges"], w["n_window"], w["window_s"])
+    ins, outs, off, _ = gpu_ingest(dyn, w)
+    g = gpu_eval(dyn, w, ins, outs, off, bud)
+    assert g["status"] == 0
+    o = ora_eval(w, st, bud)
+    rep = assert_parity(w, g, o)
+    print(name, rep)
+    assert rep["bit_exact"] and rep["sel_mismatch"] == 0
+    feas = (o["flags"] & 1).astype(bool)
+    assert feas.any() and not feas.all()
+
+
+def _profile(tp, fg, rg, PF, TB, PW, ML):
+    return {"tp": np.asarray(tp, np.int32), "f_mhz": np.asarray(fg, float), "rho": np.asarray(rg, float),
+            "prefill_ms_per_tok": np.asarray(PF, float), "tbt_ms": np.asarray(TB, float),
+            "power_w": np.asarray(PW, float), "max_load_tps": np.asarray(ML, float)}
+
+
+def _worked():
+    PF = np.empty((1, 2, 2, 3)); TB = np.empty((1, 2, 2, 3)); PW = np.empty((1, 2, 2, 3))
+    PF[0, 0, 0] = 0.4; PF[0, 0, 1] = 0.2; PF[0, 1, 0] = 0.2; PF[0, 1, 1] = 0.1
+    TB[0, 0, 0] = [40, 80, 160]; TB[0, 0, 1] = [20, 40, 80]; TB[0, 1, 0] = [20, 40, 80]; TB[0, 1, 1] = [10, 20, 40]
+    PW[0, 0, 0] = [200, 275, 312.5]; PW[0, 0, 1] = [200, 800, 1100]
+    PW[0, 1, 0] = [400, 550, 625]; PW[0, 1, 1] = [400, 1600, 2200]
+    prof = _profile([2, 4], [1000, 2000], [0, 0.5, 0.75], PF, TB, PW, [[[20.0, 40.0], [40.0, 80.0]]])
+    cfg = {"n_inst": np.asarray([1, 1, 1, 2, 1, 1], np.int32), "tp_index": np.asarray([0, 0, 0, 0, 1, 1], np.int32),
+           "f_mhz": np.asarray([1000.0, 1500, 2000, 2000, 1000, 2000])}
+    return prof, cfg
+
+
+def _single(dyn, prof, cfg, x, y, slo_ttft, slo_tbt, wlen, lam=0.0, pct=(99, 100), budget=None, n_window=1, off=None):
+    G = np.asarray(prof["prefill_ms_per_tok"]).shape[0]
+    w = {"profile": prof, "configs": cfg, "slos": {"slo_ttft_ms": np.full(G, float(slo_ttft)) if np.isscalar(slo_ttft) else slo_ttft,
+                                                   "slo_tbt_ms": np.full(G, float(slo_tbt)) if np.isscalar(slo_tbt) else slo_tbt},
+         "pct": pct, "idle_cost_weight": lam, "n_window": n_window, "window_s": wlen, "n_class": G}
+    x = np.asarray(x, np.int32); y = np.asarray(y, np.int32)
+    off = np.asarray([0, x.size], np.int64) if off is None else np.asarray(off, np.int64)
+    st = {"in_tok": x, "out_tok": y, "cell_off": off}
+    g = gpu_eval(dyn, w, _dev(x), _dev(y), _dev(off), budget)
+    return w, st, g
+
+
+def test_worked_example_on_gpu(dyn, golden_dir):
+    import os
+    rows = np.asarray([[float(v) for v in l.split()] for l in open(os.path.join(golden_dir, "worked_example.txt"))
+                       if l.strip() and not l.startswith("#")])
+    prof, cfg = _worked()
+    w, st, g = _single(dyn, prof, cfg, [100, 200, 300, 400], [50, 100, 150, 200], 100, 50, 100.0, lam=0.1)
+    np.testing.assert_allclose(g["p99_ttft_ms"][0], rows[:, 5], rtol=1e-13)
+    np.testing.assert_array_equal(g["p99_tbt_ms"][0], rows[:, 6])
+    np.testing.assert_array_equal(g["energy_j"][0], rows[:, 8])
+    np.testing.assert_array_equal(g["flags"][0] & 1, rows[:, 10].astype(np.uint8))
+    assert g["sel"][0] == 4 and g["sel_energy_j"][0] == 51250.0 and g["sel_cost"][0] == 55250.0
+    assert g["in_p99"][0] == 400 and g["tin"][0] == 1000 and g["tout"][0] == 500
+    assert_parity(w, g, ora_eval(w, st))
+    for (a, b, lam, want) in ((100, 30, 0.0, 3), (50, 50, 0.0, 5), (30, 50, 0.0, -1)):
+        w, st, g = _single(dyn, prof, cfg, [100, 200, 300, 400], [50, 100, 150, 200], a, b, 100.0, lam=lam)
+        assert g["sel"][0] == want
+        assert_parity(w, g, ora_eval(w, st))
+    w, st, g = _single(dyn, prof, cfg, [100, 200, 300, 500], [50, 100, 150, 200], 100, 50, 100.0)
+    assert g["flags"][0, 0] & dyn.DYN_F_OVERLOAD
+    w, st, g = _single(dyn, prof, cfg, [], [], 100, 50, 100.0)
+    np.testing.assert_array_equal(g["energy_j"][0], [20000, 20000, 20000, 40000, 40000, 40000])
+    assert g["sel"][0] == 0 and (g["flags"][0] == 33).all()
+    # GPU budget of two GPUs per pool
+    w, st, g = _single(dyn, prof, cfg, [100, 200, 300, 400], [50, 100, 150, 200], 100, 50, 100.0,
+                       budget=np.asarray([2], np.int32))
+    assert g["sel"][0] == 2
+    assert_parity(w, g, ora_eval(w, st, np.asarray([2], np.int32)))
+
+
+@pytest.mark.parametrize("m", [1, 2, 63, 64, 65, 99, 100, 101, 128, 129, 200, 511, 513, 1024, 1025, 2047, 2048,
+                               2049, 4097, 70_001])
+def test_rank_select_cell_sizes(dyn, m):
+    """Every register tier, the tier boundaries and the streamed path; distinct and duplicate values."""
+    prof, cfg = _worked()
+    rng = np.random.default_rng(m)
+    for kind in ("perm", "dups", "wide"):
+        if kind == "perm":
+            x = rng.permutation(np.arange(1, m + 1))
+        elif kind == "dups":
+            x = rng.integers(1, 40, m)
+        else:
+            x = rng.integers(0, 2 ** 30, m)            # exercises the 16-bit split sums and 30-bit selection
+        y = rng.integers(1, 8193, m)
+        for pct in ((99, 100), (1, 2), (1, 1), (1, 100)):
+            w, st, g = _single(dyn, prof, cfg, x, y, 1e12, 1e12, 1e6, pct=pct)
+            rank = -(-pct[0] * m // pct[1])
+            assert g["in_p99"][0] == np.sort(x)[rank - 1], (kind, pct)
+            assert g["tin"][0] == int(x.astype(np.int64).sum()) and g["tout"][0] == int(y.astype(np.int64).sum())
+            assert g["status"] == 0
+        assert_parity(w, g, ora_eval(w, st))
+
+
+def test_ragged_and_empty_cells(dyn):
+    """Many cells of sizes 0..300 in one launch, with empty cells first, last and in runs."""
+    prof, cfg = _worked()
+    rng = np.random.default_rng(11)
+    sizes = np.concatenate([[0, 0, 1, 0, 64, 65, 0], rng.integers(0, 300, 500), [2049, 0, 0]])
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(off[-1])
+    x = rng.integers(1, 8193, n); y = rng.integers(1, 8193, n)
+    w, st, g = _single(dyn, prof, cfg, x, y, 100, 50, 1000.0, n_window=sizes.size, off=off, lam=0.1)
+    o = ora_eval(w, st)
+    rep = assert_parity(w, g, o)
+    assert rep["bit_exact"] and rep["sel_mismatch"] == 0
+    assert ((g["flags"] & dyn.DYN_F_EMPTY) != 0).all(axis=1).tolist() == (sizes == 0).tolist()
+
+
+def test_off_grid_frequencies_single_frequency_and_odd_k(dyn):
+    rng = np.random.default_rng(21)
+    G, n_tp = 3, 2
+    for n_f, n_rho, K in ((4, 5, 37), (1, 2, 1), (3, 9, 300), (2, 64, 65)):
+        fg = np.sort(rng.uniform(500, 2000, n_f)); rg = np.concatenate([[0.0], np.sort(rng.uniform(0.05, 0.95, n_rho - 1))])
+        shape = (G, n_tp, n_f, n_rho)
+        prof = _profile([2, 4], fg, rg, rng.uniform(0.05, 0.3, shape), np.sort(rng.uniform(10, 150, shape), axis=-1),
+                        np.sort(rng.uniform(100, 3000, shape), axis=-1), rng.uniform(20, 400, shape[:3]))
+        f = np.where(rng.random(K) < 0.5, rng.choice(fg, K), rng.uniform(fg[0], fg[-1], K))
+        cfg = {"n_inst": rng.integers(1, 9, K).astype(np.int32), "tp_index": rng.integers(0, n_tp, K).astype(np.int32),
+               "f_mhz": f}
+        NW = 4
+        sizes = rng.integers(0, 400, NW * G)
+        off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+        x = rng.integers(1, 600, off[-1]); y = rng.integers(1, 300, off[-1])
+        slo_t = rng.uniform(20, 120, G); slo_b = rng.uniform(40, 140, G)
+        w, st, g = _single(dyn, prof, cfg, x, y, slo_t, slo_b, 30.0, lam=0.1, n_window=NW, off=off,
+                           budget=np.asarray([0, 8, 16], np.int32))
+        o = ora_eval(w, st, np.asarray([0, 8, 16], np.int32))
+        rep = assert_parity(w, g, o)
+        assert rep["bit_exact"] and rep["sel_mismatch"] == 0, (n_f, n_rho, K, rep)
+
+
+def test_table_rows_beyond_lds_fall_back_to_global_reads(dyn):
+    """A long load grid with every candidate on its own pair of rows exceeds the LDS budget."""
+    rng = np.random.default_rng(31)
+    G, n_tp, n_f, n_rho, K = 2, 2, 40, 200, 64
+    fg = np.linspace(500, 2000, n_f); rg = np.linspace(0, 0.9, n_rho)
+    shape = (G, n_tp, n_f, n_rho)
+    prof = _profile([1, 8], fg, rg, rng.uniform(0.05, 0.3, shape), np.sort(rng.uniform(10, 150, shape), axis=-1),
+                    np.sort(rng.uniform(100, 3000, shape), axis=-1), rng.uniform(20, 400, shape[:3]))
+    cfg = {"n_inst": rng.integers(1, 5, K).astype(np.int32), "tp_index": (np.arange(K) % 2).astype(np.int32),
+           "f_mhz": rng.uniform(fg[0], fg[-1], K)}
+    sizes = rng.integers(1, 200, 3 * G)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    x = rng.integers(1, 600, off[-1]); y = rng.integers(1, 300, off[-1])
+    w, st, g = _single(dyn, prof, cfg, x, y, 60.0, 90.0, 30.0, n_window=3, off=off)
+    rep = assert_parity(w, g, ora_eval(w, st))
+    assert rep["bit_exact"] and rep["sel_mismatch"] == 0
+
+
+def test_device_side_checks_raise_status_not_faults(dyn):
+    prof, cfg = _worked()
+    x = np.arange(1, 11); y = np.ones(10)
+    # offsets that run backwards and past the end of the trace: the cells are skipped and reported
+    w, st, g = _single(dyn, prof, cfg, x, y, 100, 50, 100.0, n_window=3, off=[0, 7, 3, 10_000])
+    assert g["status"] & dyn.DYN_WS_BAD_OFFSETS
+    assert g["tin"][0] == 28
+    # a negative token count is reported
+    w, st, g = _single(dyn, prof, cfg, [5, -3, 7], [1, 1, 1], 100, 50, 100.0)
+    assert g["status"] & dyn.DYN_WS_BAD_REQUEST
+
+
+def test_argument_errors(dyn):
+    prof_d, cfg = _worked()
+    prof = dyn.dyn_profile_load(prof_d)
+    x = _dev(np.arange(1, 5, dtype=np.int32)); off = _dev(np.asarray([0, 4], np.int64))
+    slos = {"slo_ttft_ms": np.asarray([100.0]), "slo_tbt_ms": np.asarray([50.0])}
+
+    def status(fn):
+        with pytest.raises(dyn.DynError) as e:
+            fn()
+        assert dyn.dyn_last_error()
+        return e.value.status
+
+    bad = dict(cfg); bad["f_mhz"] = cfg["f_mhz"].copy(); bad["f_mhz"][0] = 999.0
+    assert status(lambda: dyn.dyn_eval_space(prof, x, x, off, 1, 100.0, dyn.Plan(bad, slos))) == -3
+    bad = dict(cfg); bad["n_inst"] = cfg["n_inst"].copy(); bad["n_inst"][1] = 0
+    assert status(lambda: dyn.dyn_eval_space(prof, x, x, off, 1, 100.0, dyn.Plan(bad, slos))) == -3
+    bad = dict(cfg); bad["tp_index"] = cfg["tp_index"].copy(); bad["tp_index"][1] = 2
+    assert status(lambda: dyn.dyn_eval_space(prof, x, x, off, 1, 100.0, dyn.Plan(bad, slos))) == -3
+    assert status(lambda: dyn.dyn_eval_space(prof, x, x, off, 1, 0.0, dyn.Plan(cfg, slos))) == -3
+    assert status(lambda: dyn.dyn_eval_space(prof, x, x, off, 1, 100.0, dyn.Plan(cfg, slos, pct=(101, 100)))) == -3
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    assert status(lambda: dyn.dyn_eval_space(prof, x, x, off, 1, 100.0, dyn.Plan(cfg, slos), workspace=small)) == -6
+    # a valid call still works afterwards
+    space, ws = dyn.dyn_eval_space(prof, x, x, off, 1, 100.0, dyn.Plan(cfg, slos))
+    torch.cuda.synchronize()
+    prof.free()
+
+
+def test_plan_changes_between_calls_are_picked_up(dyn):
+    """The profile handle caches the candidate list and SLOs; changing them must take effect."""
+    w = make(SPECS[0].scaled(2000, 1))
+    st = oracle.ingest(w["trace"], w["edges"], 1, w["window_s"])
+    ins, outs, off, _ = gpu_ingest(dyn, w)
+    prof = dyn.dyn_profile_load(w["profile"])
+    for it in range(3):
+        w2 = dict(w)
+        w2["slos"] = {"slo_ttft_ms": w["slos"]["slo_ttft_ms"] * (1 + it), "slo_tbt_ms": w["slos"]["slo_tbt_ms"] * (1 + 0.5 * it)}
+        keep = np.arange(w["configs"]["n_inst"].size)[it:]
+        w2["configs"] = {k: v[keep] for k, v in w["configs"].items()}
+        g = gpu_eval(dyn, w2, ins, outs, off, prof=prof)
+        rep = assert_parity(w2, g, ora_eval(w2, st))
+        assert rep["bit_exact"] and rep["sel_mismatch"] == 0
+    prof.free()
+
+
+# ------------------------------------------------------------- full size, sampled cells
+def test_full_size_day_trace_sampled_cells(dyn):
+    """The benchmark workload (one-day trace, 10^7 requests, 36000 cells x 576 configurations) in the
+    benchmark's launch configuration; the oracle evaluates a sample of cells one by one, and
+    properties that hold at any size are checked over everything."""
+    w = make(SPECS[2])
+    tr = w["trace"]
+    ins, outs, off, ws = gpu_ingest(dyn, w)
+    assert dyn.dyn_workspace_status(ws) == 0
+    off_h = off.cpu().numpy()
+    assert off_h[0] == 0 and off_h[-1] == tr["t_s"].size and (np.diff(off_h) >= 0).all()
+    g = gpu_eval(dyn, w, ins, outs, off)
+    assert g["status"] == 0
+    cells = w["n_window"] * w["n_class"]
+    m = np.diff(off_h)
+    assert g["tin"].sum() == int(tr["in_tok"].astype(np.int64).sum())
+    assert g["tout"].sum() == int(tr["out_tok"].astype(np.int64).sum())
+    # sampled cells: the largest, the smallest non-empty, some empty, and random ones
+    rng = np.random.default_rng(0)
+    ids = np.unique(np.concatenate([[0, cells - 1, int(np.argmax(m))], np.nonzero(m == 0)[0][:5],
+                                    np.nonzero(m == 1)[0][:3], rng.integers(0, cells, 60)])).astype(np.int64)
+    st = {"in_tok": ins.cpu().numpy(), "out_tok": outs.cpu().numpy(), "cell_off": off_h}
+    # the sorted trace itself is checked against the oracle's ingestion on the sampled cells' windows
+    o = ora_eval(w, st, cell_ids=ids)
+    rep = assert_parity(w, g, o, cell_ids=ids, check_windows=False)
+    print("full-size sample:", rep, "cells sampled", ids.size)
+    assert rep["bit_exact"] and rep["sel_mismatch"] == 0
+    # size-independent properties
+    feas = (g["flags"] & 1).astype(bool)
+    sel = g["sel"]
+    has = sel >= 0
+    assert (feas.any(axis=1) == has).all()
+    assert feas[np.nonzero(has)[0], sel[has]].all()                       # infeasible is never selected
+    e_sel = g["energy_j"][np.nonzero(has)[0], sel[has]]
+    np.testing.assert_array_equal(e_sel, g["sel_energy_j"][has])
+    masked = np.where(feas, g["energy_j"], np.inf)
+    np.testing.assert_array_equal(masked.min(axis=1)[has], g["sel_energy_j"][has])
+    np.testing.assert_array_equal(masked.argmin(axis=1)[has], sel[has])   # lowest index among ties
+    we = np.where(has, g["sel_energy_j"], 0.0).reshape(w["n_window"], -1)
+    assert np.all(np.abs(g["window_energy_j"] - we.sum(axis=1)) <= 1e-12 * we.sum(axis=1))
+    np.testing.assert_array_equal(g["window_infeasible"], (~has).reshape(w["n_window"], -1).sum(axis=1))
+    assert ((g["flags"] & dyn.DYN_F_EMPTY) != 0).all(axis=1).tolist() == (m == 0).tolist()
+
+
+def test_ingest_full_size_windows_against_oracle(dyn):
+    """First and last windows of the one-day trace through the oracle's own ingestion."""
+    w = make(SPECS[2])
+    tr = w["trace"]
+    ins, outs, off, ws = gpu_ingest(dyn, w)
+    off_h = off.cpu().numpy(); ins_h = ins.cpu().numpy(); outs_h = outs.cpu().numpy()
+    G, NW, Wlen = w["n_class"], w["n_window"], w["window_s"]
+    for w0, w1 in ((0, 3), (700, 702), (NW - 2, NW)):
+        lo, hi = np.searchsorted(tr["t_s"], [w0 * Wlen, w1 * Wlen])
+        sub = {k: v[lo:hi].copy() for k, v in tr.items()}
+        # absolute times and all windows up to w1: the cells before window w0 stay empty
+        st = oracle.ingest(sub, w["edges"], w1, Wlen)
+        a, b = off_h[w0 * G], off_h[w1 * G]
+        np.testing.assert_array_equal(off_h[w0 * G:w1 * G + 1] - a, st["cell_off"][w0 * G:w1 * G + 1])
+        np.testing.assert_array_equal(ins_h[a:b], st["in_tok"])
+        np.testing.assert_array_equal(outs_h[a:b], st["out_tok"])
