@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the search-space evaluator on one MI355X.
+
+A step is one pass of the whole hot path over the resident, cell-sorted trace: per-cell
+aggregation + rank selection, evaluation of every (cell, configuration) pair, per-cell
+least-cost feasible configuration and per-window totals.  By default this is one call of
+dyn_eval_select (selection reduced inside the evaluation kernel); --unfused times
+dyn_eval_space followed by dyn_select_config instead.  Ingestion and profile upload are
+timed separately.
+
+Prints one JSON line.  `value` = requests x configurations / step time.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
+
+
+def cpu_baseline(w, n_sample_windows):
+    """The CPU oracle, as it stands, on the first windows of the same workload (one thread)."""
+    import numpy as np
+    import oracle
+    tr = w["trace"]
+    hi = int(np.searchsorted(tr["t_s"], n_sample_windows * w["window_s"]))
+    sub = {k: v[:hi] for k, v in tr.items()}
+    st = oracle.ingest(sub, w["edges"], n_sample_windows, w["window_s"])
+    t0 = time.perf_counter()
+    oracle.evaluate(w["profile"], st, n_sample_windows, w["window_s"], w["configs"], w["slos"], w["pct"], None,
+                    w["idle_cost_weight"], want_space=False)
+    dt = time.perf_counter() - t0
+    k = w["configs"]["n_inst"].size
+    return {"value": hi * k / dt, "unit": "evals/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {n_sample_windows} of {w['n_window']} windows ({hi} requests x {k} configurations, "
+                      f"{dt:.1f} s, single thread)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="workload index (0..4); the headline is 2")
+    ap.add_argument("--unfused", action="store_true", help="dyn_eval_space + dyn_select_config as two calls")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-windows", type=int, default=0, help="windows in the CPU-baseline sample (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (windows would shard "
+              "independently across GPUs; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2408_00741_amd as dyn
+    from workloads import SPECS, make
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    spec = SPECS[args.config]
+    t0 = time.perf_counter()
+    w = make(spec)
+    gen_s = time.perf_counter() - t0
+    tr = w["trace"]
+    R, K, NW, G = spec.n_req, spec.n_config, spec.n_window, spec.n_class
+    cells = NW * G
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    # ---- one-time set-up, timed separately: upload, ingestion, profile load
+    t_s, x, y, mdl = dev(tr["t_s"]), dev(tr["in_tok"]), dev(tr["out_tok"]), dev(tr["model"])
+    ws_ing = torch.empty(dyn.dyn_trace_ingest_workspace(R, NW, G), dtype=torch.uint8, device="cuda")
+    dyn.dyn_trace_ingest(t_s, x, y, mdl, w["edges"], NW, w["window_s"], workspace=ws_ing)   # warm-up
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    ins, outs, off, _ = dyn.dyn_trace_ingest(t_s, x, y, mdl, w["edges"], NW, w["window_s"], workspace=ws_ing)
+    e1.record()
+    torch.cuda.synchronize()
+    ingest_ms = e0.elapsed_time(e1)
+    assert dyn.dyn_workspace_status(ws_ing) == 0
+    del t_s, x, y, mdl, ws_ing
+    t0 = time.perf_counter()
+    prof = dyn.dyn_profile_load(w["profile"])
+    profile_load_ms = (time.perf_counter() - t0) * 1e3
+    plan = dyn.Plan(w["configs"], w["slos"], w["pct"], None, w["idle_cost_weight"])
+
+    space = {"energy_j": torch.empty((cells, K), dtype=torch.float64, device="cuda"),
+             "p99_ttft_ms": torch.empty((cells, K), dtype=torch.float64, device="cuda"),
+             "p99_tbt_ms": torch.empty((cells, K), dtype=torch.float64, device="cuda"),
+             "flags": torch.empty((cells, K), dtype=torch.uint8, device="cuda")}
+    sel = {"sel": torch.empty(cells, dtype=torch.int32, device="cuda"),
+           "sel_energy_j": torch.empty(cells, dtype=torch.float64, device="cuda"),
+           "sel_cost": torch.empty(cells, dtype=torch.float64, device="cuda"),
+           "window_energy_j": torch.empty(NW, dtype=torch.float64, device="cuda"),
+           "window_infeasible": torch.empty(NW, dtype=torch.int32, device="cuda")}
+    ws = torch.empty(dyn.dyn_eval_space_workspace(NW, G, K), dtype=torch.uint8, device="cuda")
+
+    if args.unfused:
+        def step():
+            dyn.dyn_eval_space(prof, ins, outs, off, NW, w["window_s"], plan, out=space, workspace=ws)
+            dyn.dyn_select_config(prof, space, NW, w["window_s"], plan, out=sel)
+    else:
+        def step():
+            dyn.dyn_eval_select(prof, ins, outs, off, NW, w["window_s"], plan, out=space, sel=sel, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` steps, per-kernel HIP events recorded by the library
+    dyn.dyn_timing_enable(True, args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ktime = {}
+    for name, kid in (("cell", dyn.DYN_K_CELL), ("space", dyn.DYN_K_SPACE), ("select", dyn.DYN_K_SELECT),
+                      ("totals", dyn.DYN_K_TOTALS)):
+        ms, n = dyn.dyn_timing_read(kid)
+        ktime[name] = ms / max(n, 1)
+    dyn.dyn_timing_enable(False)
+    assert dyn.dyn_workspace_status(ws) == 0
+    ms_per_step = wall / args.steps * 1e3
+
+    # ---- roofline of the dominant kernel (space evaluation): 25 B written per (cell, configuration)
+    space_bytes = 25.0 * cells * K
+    space_gbps = space_bytes / (ktime["space"] * 1e-3) / 1e9
+    # whole path, algorithmic bytes: read the request stream and offsets once, write the space,
+    # re-read energy + flags for the selection, write the selection and the window totals
+    path_bytes = (8.0 * R + 8.0 * (cells + 1) + 25.0 * cells * K + (9.0 * cells * K if args.unfused else 0.0)
+                  + 20.0 * cells + 12.0 * NW)
+    path_gbps = path_bytes / (ms_per_step * 1e-3) / 1e9
+
+    sel_h = sel["sel"].cpu().numpy()
+    we = sel["window_energy_j"].cpu().numpy()
+    out = {
+        "metric": "(request x config) evals/sec at 1 MI355X; achieved HBM GB/s vs peak",
+        "value": R * K / (ms_per_step * 1e-3),
+        "unit": "evals/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {spec.name}: {R} requests, {NW} windows x {G} classes = "
+                               f"{cells} cells, {K} configurations", "requests": R, "cells": cells, "configs": K,
+                   "entry_points": "dyn_eval_space+dyn_select_config" if args.unfused else "dyn_eval_select"},
+        "roofline": {"bound": "hbm", "kernel": "space_kernel", "achieved": space_gbps, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": space_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes_per_launch": space_bytes, "avg_launch_ms": ktime["space"]},
+        "kernel_ms": ktime,
+        "path": {"algorithmic_bytes": path_bytes, "gbps": path_gbps, "frac_of_hbm_peak": path_gbps / HBM_PEAK_GBPS},
+        "setup": {"ingest_ms": ingest_ms, "profile_load_ms": profile_load_ms, "generate_s": gen_s,
+                  "ingest_requests_per_s": R / (ingest_ms * 1e-3)},
+        "result": {"cells_without_feasible_config": int((sel_h < 0).sum()), "total_energy_wh": float(we.sum() / 3600.0)},
+    }
+    if not args.no_cpu_baseline:
+        nwin = args.cpu_windows or max(1, min(NW, int(NW * 3.0e9 / (R * K))))
+        out["cpu_baseline"] = cpu_baseline(w, nwin)
+        out["cpu_baseline"]["host_cores"] = os.cpu_count()
+    prof.free()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

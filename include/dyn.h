@@ -208,6 +208,34 @@ int dyn_select_config(dyn_profile* profile, const dyn_space* space, const dyn_co
                       int32_t K, const dyn_objective* objective, int32_t n_window,
                       double window_s, const dyn_selection* out, void* hip_stream);
 
+/* dyn_eval_space and dyn_select_config in one pass: the selection is reduced inside the
+ * evaluation kernel (per wave of configurations) and finished by a small kernel, so the
+ * evaluated space is written once and not read back.  Outputs are identical to calling
+ * the two entry points one after the other with the same arguments.  `space` and `sel`
+ * DEVICE arrays as documented above; same workspace as dyn_eval_space.                  */
+int dyn_eval_select(dyn_profile* profile, const dyn_trace_view* trace, const dyn_config* cfg,
+                    int32_t K, const dyn_objective* objective, const dyn_space* space,
+                    const dyn_selection* sel, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+
+/* ------------------------------------------------------------- kernel timing (optional) --
+ * Measurement aid, not part of the method: when enabled, the library brackets each of its
+ * kernels with a pair of HIP events recorded on the stream the kernel is launched on, so
+ * that a caller can obtain per-kernel durations of its own timed region without a
+ * profiler.  Off by default (no events are recorded).                                   */
+#define DYN_K_CELL 0    /* per-cell aggregation + rank selection                        */
+#define DYN_K_SPACE 1   /* evaluation of the (cell, configuration) space                */
+#define DYN_K_SELECT 2  /* per-cell least-cost feasible configuration (or its fused finish) */
+#define DYN_K_TOTALS 3  /* per-window totals                                            */
+#define DYN_K_COUNT 4
+/* on != 0: create the event pool (up to `max_launches` launches per kernel are recorded,
+ * later ones are not) and start recording; on == 0: stop and destroy the pool.         */
+int dyn_timing_enable(int on, int32_t max_launches);
+/* Forget what was recorded so far (the pool is kept). */
+int dyn_timing_reset(void);
+/* Waits for the recorded events of `kernel` and returns their summed duration and count. */
+int dyn_timing_read(int32_t kernel, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,7 +15,9 @@ import torch
 
 __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_trace_ingest",
            "dyn_trace_ingest_workspace", "dyn_eval_space", "dyn_eval_space_workspace", "dyn_cell_stats",
-           "dyn_workspace_status", "dyn_select_config", "dyn_last_error", "lib_path",
+           "dyn_workspace_status", "dyn_select_config", "dyn_eval_select", "dyn_last_error", "lib_path",
+           "dyn_timing_enable", "dyn_timing_reset", "dyn_timing_read", "DYN_K_CELL", "DYN_K_SPACE", "DYN_K_SELECT",
+           "DYN_K_TOTALS",
            "DYN_F_FEASIBLE", "DYN_F_OVERLOAD", "DYN_F_TTFT", "DYN_F_TBT", "DYN_F_BUDGET", "DYN_F_EMPTY",
            "DYN_WS_BAD_OFFSETS", "DYN_WS_BAD_REQUEST"]
 
@@ -92,6 +94,32 @@ _lib.dyn_workspace_status.argtypes = [_vp, _vp, C.POINTER(C.c_uint32)]
 _lib.dyn_select_config.restype = C.c_int
 _lib.dyn_select_config.argtypes = [_vp, C.POINTER(_Space), C.POINTER(_Config), _i32, C.POINTER(_Objective), _i32,
                                    _f64, C.POINTER(_Selection), _vp]
+
+
+_lib.dyn_eval_select.restype = C.c_int
+_lib.dyn_eval_select.argtypes = [_vp, C.POINTER(_TraceView), C.POINTER(_Config), _i32, C.POINTER(_Objective),
+                                 C.POINTER(_Space), C.POINTER(_Selection), _vp, _sz, _vp]
+_lib.dyn_timing_enable.restype = C.c_int
+_lib.dyn_timing_enable.argtypes = [C.c_int, _i32]
+_lib.dyn_timing_reset.restype = C.c_int
+_lib.dyn_timing_read.restype = C.c_int
+_lib.dyn_timing_read.argtypes = [_i32, C.POINTER(C.c_double), C.POINTER(_i64)]
+DYN_K_CELL, DYN_K_SPACE, DYN_K_SELECT, DYN_K_TOTALS = 0, 1, 2, 3
+
+
+def dyn_timing_enable(on: bool, max_launches: int = 4096):
+    _check(_lib.dyn_timing_enable(1 if on else 0, max_launches), "dyn_timing_enable")
+
+
+def dyn_timing_reset():
+    _check(_lib.dyn_timing_reset(), "dyn_timing_reset")
+
+
+def dyn_timing_read(kernel: int):
+    """(summed duration in ms, number of launches) of one kernel since the last reset."""
+    ms, n = C.c_double(0.0), _i64(0)
+    _check(_lib.dyn_timing_read(kernel, C.byref(ms), C.byref(n)), "dyn_timing_read")
+    return ms.value, n.value
 
 
 class DynError(RuntimeError):
@@ -235,10 +263,28 @@ class Plan:
 __all__.append("Plan")
 
 
-def dyn_eval_space(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tensor, cell_off: torch.Tensor,
-                   n_window: int, window_s: float, plan: Plan, out: Optional[Dict[str, torch.Tensor]] = None,
-                   workspace: Optional[torch.Tensor] = None, stream=None):
-    """Returns (space dict of [cells, K] tensors, workspace)."""
+def _space_tensors(cells, K, dev):
+    return {"energy_j": torch.empty((cells, K), dtype=torch.float64, device=dev),
+            "p99_ttft_ms": torch.empty((cells, K), dtype=torch.float64, device=dev),
+            "p99_tbt_ms": torch.empty((cells, K), dtype=torch.float64, device=dev),
+            "flags": torch.empty((cells, K), dtype=torch.uint8, device=dev)}
+
+
+def _selection_tensors(cells, n_window, dev):
+    return {"sel": torch.empty(cells, dtype=torch.int32, device=dev),
+            "sel_energy_j": torch.empty(cells, dtype=torch.float64, device=dev),
+            "sel_cost": torch.empty(cells, dtype=torch.float64, device=dev),
+            "window_energy_j": torch.empty(n_window, dtype=torch.float64, device=dev),
+            "window_infeasible": torch.empty(n_window, dtype=torch.int32, device=dev)}
+
+
+def _selection_struct(out):
+    return _Selection(_dp(out["sel"], torch.int32), _dp(out["sel_energy_j"], torch.float64),
+                      _dp(out["sel_cost"], torch.float64), _dp(out["window_energy_j"], torch.float64),
+                      _dp(out["window_infeasible"], torch.int32))
+
+
+def _eval_args(profile, in_tok, out_tok, cell_off, n_window, window_s, plan, out, workspace):
     G, K = profile.n_class, plan.K
     if plan.n_class != G:
         raise ValueError("SLO arrays must have one entry per class")
@@ -247,10 +293,7 @@ def dyn_eval_space(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tensor
         raise ValueError("cell_off must have n_window*G + 1 entries")
     dev = cell_off.device
     if out is None:
-        out = {"energy_j": torch.empty((cells, K), dtype=torch.float64, device=dev),
-               "p99_ttft_ms": torch.empty((cells, K), dtype=torch.float64, device=dev),
-               "p99_tbt_ms": torch.empty((cells, K), dtype=torch.float64, device=dev),
-               "flags": torch.empty((cells, K), dtype=torch.uint8, device=dev)}
+        out = _space_tensors(cells, K, dev)
     if workspace is None:
         workspace = _workspace(dyn_eval_space_workspace(n_window, G, K), dev)
     tv = _TraceView(in_tok.numel(), n_window, float(window_s), _dp(in_tok, torch.int32, "in_tok"),
@@ -260,9 +303,33 @@ def dyn_eval_space(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tensor
     for v in out.values():
         if v.numel() != cells * K:
             raise ValueError("space tensors must hold n_window*G*K entries")
+    return tv, sp, out, workspace, cells, K
+
+
+def dyn_eval_space(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tensor, cell_off: torch.Tensor,
+                   n_window: int, window_s: float, plan: Plan, out: Optional[Dict[str, torch.Tensor]] = None,
+                   workspace: Optional[torch.Tensor] = None, stream=None):
+    """Returns (space dict of [cells, K] tensors, workspace)."""
+    tv, sp, out, workspace, cells, K = _eval_args(profile, in_tok, out_tok, cell_off, n_window, window_s, plan, out,
+                                                  workspace)
     _check(_lib.dyn_eval_space(profile.handle, C.byref(tv), plan.cfg, K, C.byref(plan.obj), C.byref(sp),
                                _dp(workspace), workspace.numel(), _stream(stream)), "dyn_eval_space")
     return out, workspace
+
+
+def dyn_eval_select(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tensor, cell_off: torch.Tensor,
+                    n_window: int, window_s: float, plan: Plan, out: Optional[Dict[str, torch.Tensor]] = None,
+                    sel: Optional[Dict[str, torch.Tensor]] = None, workspace: Optional[torch.Tensor] = None,
+                    stream=None):
+    """Evaluation and selection in one pass.  Returns (space, selection, workspace)."""
+    tv, sp, out, workspace, cells, K = _eval_args(profile, in_tok, out_tok, cell_off, n_window, window_s, plan, out,
+                                                  workspace)
+    if sel is None:
+        sel = _selection_tensors(cells, n_window, cell_off.device)
+    se = _selection_struct(sel)
+    _check(_lib.dyn_eval_select(profile.handle, C.byref(tv), plan.cfg, K, C.byref(plan.obj), C.byref(sp), C.byref(se),
+                                _dp(workspace), workspace.numel(), _stream(stream)), "dyn_eval_select")
+    return out, sel, workspace
 
 
 def dyn_cell_stats(workspace: torch.Tensor, n_window: int, n_class: int, stream=None):
@@ -290,16 +357,10 @@ def dyn_select_config(profile: Profile, space: Dict[str, torch.Tensor], n_window
     if space["energy_j"].numel() != cells * K or space["flags"].numel() != cells * K:
         raise ValueError("space tensors must hold n_window*G*K entries")
     if out is None:
-        out = {"sel": torch.empty(cells, dtype=torch.int32, device=dev),
-               "sel_energy_j": torch.empty(cells, dtype=torch.float64, device=dev),
-               "sel_cost": torch.empty(cells, dtype=torch.float64, device=dev),
-               "window_energy_j": torch.empty(n_window, dtype=torch.float64, device=dev),
-               "window_infeasible": torch.empty(n_window, dtype=torch.int32, device=dev)}
+        out = _selection_tensors(cells, n_window, dev)
     sp = _Space(_dp(space["energy_j"], torch.float64), _dp(space.get("p99_ttft_ms")), _dp(space.get("p99_tbt_ms")),
                 _dp(space["flags"], torch.uint8))
-    se = _Selection(_dp(out["sel"], torch.int32), _dp(out["sel_energy_j"], torch.float64),
-                    _dp(out["sel_cost"], torch.float64), _dp(out["window_energy_j"], torch.float64),
-                    _dp(out["window_infeasible"], torch.int32))
+    se = _selection_struct(out)
     _check(_lib.dyn_select_config(profile.handle, C.byref(sp), plan.cfg, K, C.byref(plan.obj), n_window,
                                   float(window_s), C.byref(se), _stream(stream)), "dyn_select_config")
     return out

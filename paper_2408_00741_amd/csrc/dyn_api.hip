@@ -24,7 +24,11 @@ bool hip_ok(hipError_t e, const char* what) {
   return false;
 }
 
-__global__ void zero_u32_kernel(uint32_t* p) { *p = 0u; }
+__global__ void init_word_header_kernel(WsHeader* h) {
+  h->status = 0u;
+  h->kind = DYN_WS_KIND_WORD;
+  h->cells = 0;
+}
 
 bool strictly_increasing(const double* g, int n) {
   for (int i = 0; i < n; ++i)
@@ -212,6 +216,27 @@ IngestWs ingest_ws_layout(int64_t n_req, int32_t n_model, int32_t n_in_bin, int3
 
 }  // namespace
 
+// ---- optional kernel timing ---------------------------------------------------------------
+namespace {
+struct TimerPool {
+  std::vector<hipEvent_t> start, stop;
+  int used = 0;
+};
+TimerPool g_timers[DYN_K_COUNT];
+bool g_timing = false;
+}  // namespace
+
+DynTimed::DynTimed(int kernel, hipStream_t s) : kernel_(kernel), s_(s), slot_(-1) {
+  if (!g_timing) return;
+  TimerPool& t = g_timers[kernel];
+  if (t.used >= (int)t.start.size()) return;
+  slot_ = t.used++;
+  (void)hipEventRecord(t.start[slot_], s_);
+}
+DynTimed::~DynTimed() {
+  if (slot_ >= 0) (void)hipEventRecord(g_timers[kernel_].stop[slot_], s_);
+}
+
 void dyn_set_error(const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -219,18 +244,99 @@ void dyn_set_error(const char* fmt, ...) {
   va_end(ap);
 }
 
-EvalWs dyn_eval_ws_layout(int64_t cells) {
+EvalWs dyn_eval_ws_layout(int64_t cells, int32_t K) {
   EvalWs w;
   size_t off = 0;
   const size_t c = (size_t)std::max<int64_t>(cells, 1);
-  w.status = off; off += 256;
+  w.n_wslot = std::max(K, 1) / DYN_WAVE + 4;   // >= n_tile * tile/64 for every tile width
+  w.header = off; off += 256;
   w.tin = off; off += align256(c * 8);
   w.tout = off; off += align256(c * 8);
   w.in_p99 = off; off += align256(c * 4);
   w.rec = off; off += align256(c * sizeof(CellRec));
+  w.cstat = off; off += align256(c);
+  w.part = off; off += align256(c * (size_t)w.n_wslot * sizeof(SelPart));
   w.total = off;
   return w;
 }
+
+namespace {
+
+__global__ __launch_bounds__(256) void or_cell_status_kernel(const uint8_t* __restrict__ cstat, int64_t cells,
+                                                             uint32_t* __restrict__ status) {
+  uint32_t v = 0;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < cells; i += (int64_t)gridDim.x * blockDim.x)
+    v |= cstat[i];
+  if (v) atomicOr(status, v);
+}
+
+int check_selection(const dyn_selection* out) {
+  if (!out->sel || !out->sel_energy_j || !out->sel_cost || !out->window_energy_j || !out->window_infeasible) {
+    dyn_set_error("a selection output array is NULL");
+    return DYN_E_NULL;
+  }
+  return DYN_OK;
+}
+
+// dyn_eval_space (sel == nullptr) and dyn_eval_select (sel != nullptr)
+int eval_impl(dyn_profile* p, const dyn_trace_view* t, const dyn_config* cfg, int32_t K, const dyn_objective* o,
+              const dyn_space* out, const dyn_selection* sel, void* workspace, size_t workspace_bytes,
+              void* hip_stream) {
+  if (!p || !t || !out || !workspace) { dyn_set_error("profile, trace, out or workspace is NULL"); return DYN_E_NULL; }
+  if (!out->energy_j || !out->p99_ttft_ms || !out->p99_tbt_ms || !out->flags) { dyn_set_error("an output array is NULL"); return DYN_E_NULL; }
+  int rc;
+  if (sel && (rc = check_selection(sel)) != DYN_OK) return rc;
+  if (t->n_req < 0 || t->n_req >= ((int64_t)1 << 31) || t->n_window < 1) { dyn_set_error("n_req or n_window out of range"); return DYN_E_SHAPE; }
+  if (!t->cell_off || (t->n_req > 0 && (!t->in_tok || !t->out_tok))) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
+  if (!(t->window_s > 0.0) || !isfinite(t->window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  const int64_t cells = (int64_t)t->n_window * p->G;
+  if (cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
+  if ((rc = check_device(p)) != DYN_OK) return rc;
+  if (K < 1 || K > DYN_MAX_CONFIGS) { dyn_set_error("K=%d outside [1, %d]", K, DYN_MAX_CONFIGS); return DYN_E_SHAPE; }
+  const EvalWs w = dyn_eval_ws_layout(cells, K);
+  if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) {
+    dyn_set_error("workspace misaligned or too small (%zu < %zu)", workspace_bytes, w.total);
+    return DYN_E_WORKSPACE;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  if ((rc = prepare_configs(p, cfg, K, s)) != DYN_OK) return rc;
+  if ((rc = prepare_objective(p, o, s)) != DYN_OK) return rc;
+
+  char* base = (char*)workspace;
+  if (!hip_ok(dyn_launch_cell_aggregate(t->in_tok, t->out_tok, t->cell_off, t->n_req, cells, t->window_s, o->pct_num,
+                                        o->pct_den, (int64_t*)(base + w.tin), (int64_t*)(base + w.tout),
+                                        (int32_t*)(base + w.in_p99), (CellRec*)(base + w.rec),
+                                        (uint8_t*)(base + w.cstat), (WsHeader*)(base + w.header), s),
+              "cell aggregate launch"))
+    return DYN_E_DEVICE;
+
+  SpaceArgs a;
+  a.pf = p->d_pf; a.tb = p->d_tb; a.pw = p->d_pw; a.ml = p->d_ml; a.rg = p->d_rg;
+  a.jstart = p->d_jstart; a.n_bucket = p->n_bucket; a.bucket_scale = p->bucket_scale;
+  a.G = p->G; a.n_tp_f = p->n_tp * p->n_f; a.n_rho = p->n_rho;
+  a.cfg = p->d_cfg; a.K = K; a.tile = p->tile; a.n_tile = p->n_tile; a.n_slot = p->n_slot;
+  a.tile_rows = p->d_tile_rows;
+  a.slo_ttft = p->d_slo_ttft; a.slo_tbt = p->d_slo_tbt; a.budget = p->d_budget;
+  a.rec = (const CellRec*)(base + w.rec); a.n_window = t->n_window; a.window_s = t->window_s;
+  // enough blocks to fill the chip several times over, long enough runs to amortise staging
+  const int64_t cell_tiles = cells * p->n_tile;
+  a.win_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(32, cell_tiles / 4096));
+  a.energy = out->energy_j; a.p99_ttft = out->p99_ttft_ms; a.p99_tbt = out->p99_tbt_ms; a.flags = out->flags;
+  a.pw0 = p->d_pw0; a.idle_w = o->idle_cost_weight;
+  a.part = sel ? (SelPart*)(base + w.part) : nullptr; a.n_wslot = w.n_wslot;
+  if (!hip_ok(dyn_launch_space(a, s), "space launch")) return DYN_E_DEVICE;
+  if (sel) {
+    FinishArgs f;
+    f.part = a.part; f.n_wslot = w.n_wslot; f.n_used = p->n_tile * (p->tile / DYN_WAVE);
+    f.n_window = t->n_window; f.G = p->G;
+    f.sel = sel->sel; f.sel_energy = sel->sel_energy_j; f.sel_cost = sel->sel_cost;
+    f.win_energy = sel->window_energy_j; f.win_inf = sel->window_infeasible;
+    if (!hip_ok(dyn_launch_finish(f, s), "finish launch")) return DYN_E_DEVICE;
+  }
+  return DYN_OK;
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -380,63 +486,28 @@ int dyn_trace_ingest(const double* t_s, const int32_t* in_tok, const int32_t* ou
   if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) return DYN_E_DEVICE;
   if (e->n_in_bin > 1 && !hip_ok(hipMemcpy(base + w.in_edge, e->in_edge, (size_t)e->n_model * (e->n_in_bin - 1) * 4, hipMemcpyHostToDevice), "copy edges")) return DYN_E_DEVICE;
   if (e->n_out_bin > 1 && !hip_ok(hipMemcpy(base + w.out_edge, e->out_edge, (size_t)e->n_model * (e->n_out_bin - 1) * 4, hipMemcpyHostToDevice), "copy edges")) return DYN_E_DEVICE;
-  hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(1), 0, s, a.status);
+  hipLaunchKernelGGL(init_word_header_kernel, dim3(1), dim3(1), 0, s, (WsHeader*)a.status);
   if (!hip_ok(hipGetLastError(), "launch")) return DYN_E_DEVICE;
   if (!hip_ok(dyn_launch_ingest(a, s), "ingest launch")) return DYN_E_DEVICE;
   return DYN_OK;
 }
 
 size_t dyn_eval_space_workspace(int32_t n_window, int32_t n_class, int32_t n_config) {
-  (void)n_config;
-  if (n_window < 1 || n_class < 1) return 0;
-  return dyn_eval_ws_layout((int64_t)n_window * n_class).total;
+  if (n_window < 1 || n_class < 1 || n_config < 1) return 0;
+  return dyn_eval_ws_layout((int64_t)n_window * n_class, n_config).total;
 }
 
 int dyn_eval_space(dyn_profile* p, const dyn_trace_view* t, const dyn_config* cfg, int32_t K,
                    const dyn_objective* o, const dyn_space* out, void* workspace, size_t workspace_bytes,
                    void* hip_stream) {
-  if (!p || !t || !out || !workspace) { dyn_set_error("profile, trace, out or workspace is NULL"); return DYN_E_NULL; }
-  if (!out->energy_j || !out->p99_ttft_ms || !out->p99_tbt_ms || !out->flags) { dyn_set_error("an output array is NULL"); return DYN_E_NULL; }
-  if (t->n_req < 0 || t->n_req >= ((int64_t)1 << 31) || t->n_window < 1) { dyn_set_error("n_req or n_window out of range"); return DYN_E_SHAPE; }
-  if (!t->cell_off || (t->n_req > 0 && (!t->in_tok || !t->out_tok))) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
-  if (!(t->window_s > 0.0) || !isfinite(t->window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
-  const int64_t cells = (int64_t)t->n_window * p->G;
-  if (cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
-  int rc = check_device(p);
-  if (rc) return rc;
-  const EvalWs w = dyn_eval_ws_layout(cells);
-  if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) {
-    dyn_set_error("workspace misaligned or too small (%zu < %zu)", workspace_bytes, w.total);
-    return DYN_E_WORKSPACE;
-  }
-  hipStream_t s = (hipStream_t)hip_stream;
-  if ((rc = prepare_configs(p, cfg, K, s)) != DYN_OK) return rc;
-  if ((rc = prepare_objective(p, o, s)) != DYN_OK) return rc;
+  return eval_impl(p, t, cfg, K, o, out, nullptr, workspace, workspace_bytes, hip_stream);
+}
 
-  char* base = (char*)workspace;
-  uint32_t* status = (uint32_t*)(base + w.status);
-  hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(1), 0, s, status);
-  if (!hip_ok(hipGetLastError(), "launch")) return DYN_E_DEVICE;
-  if (!hip_ok(dyn_launch_cell_aggregate(t->in_tok, t->out_tok, t->cell_off, t->n_req, cells, t->window_s, o->pct_num,
-                                        o->pct_den, (int64_t*)(base + w.tin), (int64_t*)(base + w.tout),
-                                        (int32_t*)(base + w.in_p99), (CellRec*)(base + w.rec), status, s),
-              "cell aggregate launch"))
-    return DYN_E_DEVICE;
-
-  SpaceArgs a;
-  a.pf = p->d_pf; a.tb = p->d_tb; a.pw = p->d_pw; a.ml = p->d_ml; a.rg = p->d_rg;
-  a.jstart = p->d_jstart; a.n_bucket = p->n_bucket; a.bucket_scale = p->bucket_scale;
-  a.G = p->G; a.n_tp_f = p->n_tp * p->n_f; a.n_rho = p->n_rho;
-  a.cfg = p->d_cfg; a.K = K; a.tile = p->tile; a.n_tile = p->n_tile; a.n_slot = p->n_slot;
-  a.tile_rows = p->d_tile_rows;
-  a.slo_ttft = p->d_slo_ttft; a.slo_tbt = p->d_slo_tbt; a.budget = p->d_budget;
-  a.rec = (const CellRec*)(base + w.rec); a.n_window = t->n_window; a.window_s = t->window_s;
-  // enough blocks to fill the chip several times over, long enough runs to amortise staging
-  const int64_t cell_tiles = cells * p->n_tile;
-  a.win_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(32, cell_tiles / 4096));
-  a.energy = out->energy_j; a.p99_ttft = out->p99_ttft_ms; a.p99_tbt = out->p99_tbt_ms; a.flags = out->flags;
-  if (!hip_ok(dyn_launch_space(a, s), "space launch")) return DYN_E_DEVICE;
-  return DYN_OK;
+int dyn_eval_select(dyn_profile* p, const dyn_trace_view* t, const dyn_config* cfg, int32_t K,
+                    const dyn_objective* o, const dyn_space* out, const dyn_selection* sel, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+  if (!sel) { dyn_set_error("selection is NULL"); return DYN_E_NULL; }
+  return eval_impl(p, t, cfg, K, o, out, sel, workspace, workspace_bytes, hip_stream);
 }
 
 int dyn_cell_stats(const void* workspace, size_t workspace_bytes, int32_t n_window, int32_t n_class,
@@ -444,7 +515,7 @@ int dyn_cell_stats(const void* workspace, size_t workspace_bytes, int32_t n_wind
   if (!workspace) { dyn_set_error("workspace is NULL"); return DYN_E_NULL; }
   if (n_window < 1 || n_class < 1) { dyn_set_error("n_window or n_class < 1"); return DYN_E_SHAPE; }
   const int64_t cells = (int64_t)n_window * n_class;
-  const EvalWs w = dyn_eval_ws_layout(cells);
+  const EvalWs w = dyn_eval_ws_layout(cells, 1);   // the aggregates precede everything that depends on K
   if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) { dyn_set_error("workspace misaligned or too small"); return DYN_E_WORKSPACE; }
   hipStream_t s = (hipStream_t)hip_stream;
   const char* base = (const char*)workspace;
@@ -457,8 +528,25 @@ int dyn_cell_stats(const void* workspace, size_t workspace_bytes, int32_t n_wind
 int dyn_workspace_status(const void* workspace, void* hip_stream, uint32_t* status) {
   if (!workspace || !status) { dyn_set_error("workspace or status is NULL"); return DYN_E_NULL; }
   hipStream_t s = (hipStream_t)hip_stream;
-  if (!hip_ok(hipMemcpyAsync(status, workspace, 4, hipMemcpyDeviceToHost, s), "copy status")) return DYN_E_DEVICE;
+  WsHeader h;
+  if (!hip_ok(hipMemcpyAsync(&h, workspace, sizeof(h), hipMemcpyDeviceToHost, s), "copy status")) return DYN_E_DEVICE;
   if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) return DYN_E_DEVICE;
+  if (h.kind == DYN_WS_KIND_CELLS) {
+    // evaluation workspace: OR the per-cell status bytes into the header word, then read it
+    if (h.cells < 1 || h.cells >= ((int64_t)1 << 30)) { dyn_set_error("workspace header is corrupt"); return DYN_E_WORKSPACE; }
+    const EvalWs w = dyn_eval_ws_layout(h.cells, 1);
+    const char* base = (const char*)workspace;
+    uint32_t* word = (uint32_t*)const_cast<char*>(base + w.header);
+    const int blocks = (int)std::min<int64_t>(1024, (h.cells + 255) / 256);
+    hipLaunchKernelGGL(or_cell_status_kernel, dim3(blocks), dim3(256), 0, s, (const uint8_t*)(base + w.cstat), h.cells, word);
+    if (!hip_ok(hipGetLastError(), "launch")) return DYN_E_DEVICE;
+    if (!hip_ok(hipMemcpyAsync(&h, workspace, sizeof(h), hipMemcpyDeviceToHost, s), "copy status")) return DYN_E_DEVICE;
+    if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) return DYN_E_DEVICE;
+  } else if (h.kind != DYN_WS_KIND_WORD) {
+    dyn_set_error("workspace holds no result yet");
+    return DYN_E_WORKSPACE;
+  }
+  *status = h.status;
   return DYN_OK;
 }
 
@@ -483,6 +571,46 @@ int dyn_select_config(dyn_profile* p, const dyn_space* space, const dyn_config* 
   a.sel = out->sel; a.sel_energy = out->sel_energy_j; a.sel_cost = out->sel_cost;
   a.win_energy = out->window_energy_j; a.win_inf = out->window_infeasible;
   if (!hip_ok(dyn_launch_select(a, s), "select launch")) return DYN_E_DEVICE;
+  return DYN_OK;
+}
+
+int dyn_timing_enable(int on, int32_t max_launches) {
+  g_timing = false;
+  for (TimerPool& t : g_timers) {
+    for (hipEvent_t e : t.start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : t.stop) (void)hipEventDestroy(e);
+    t.start.clear(); t.stop.clear(); t.used = 0;
+  }
+  if (!on) return DYN_OK;
+  if (max_launches < 1 || max_launches > (1 << 20)) { dyn_set_error("max_launches out of range"); return DYN_E_RANGE; }
+  for (TimerPool& t : g_timers) {
+    t.start.resize(max_launches); t.stop.resize(max_launches);
+    for (int i = 0; i < max_launches; ++i)
+      if (!hip_ok(hipEventCreate(&t.start[i]), "hipEventCreate") || !hip_ok(hipEventCreate(&t.stop[i]), "hipEventCreate"))
+        return DYN_E_DEVICE;
+  }
+  g_timing = true;
+  return DYN_OK;
+}
+
+int dyn_timing_reset(void) {
+  for (TimerPool& t : g_timers) t.used = 0;
+  return DYN_OK;
+}
+
+int dyn_timing_read(int32_t kernel, double* total_ms, int64_t* launches) {
+  if (!total_ms || !launches) { dyn_set_error("output pointer is NULL"); return DYN_E_NULL; }
+  if (kernel < 0 || kernel >= DYN_K_COUNT) { dyn_set_error("unknown kernel id %d", kernel); return DYN_E_RANGE; }
+  TimerPool& t = g_timers[kernel];
+  double sum = 0.0;
+  for (int i = 0; i < t.used; ++i) {
+    if (!hip_ok(hipEventSynchronize(t.stop[i]), "hipEventSynchronize")) return DYN_E_DEVICE;
+    float ms = 0.f;
+    if (!hip_ok(hipEventElapsedTime(&ms, t.start[i], t.stop[i]), "hipEventElapsedTime")) return DYN_E_DEVICE;
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = t.used;
   return DYN_OK;
 }
 

@@ -67,18 +67,36 @@ struct dyn_profile {
   int32_t* d_budget;   // [G]
 };
 
+// Per-(cell, wave of configurations) partial result of the fused selection.
+struct SelPart {
+  double cost;     // least cost among the wave's feasible configurations, +inf if none
+  double energy;   // energy of that configuration
+  int32_t k;       // its index, -1 if none
+  int32_t pad;
+};
+
+// Header at the start of every workspace.
+struct WsHeader {
+  uint32_t status;   // DYN_WS_* bits (final for an ingest workspace)
+  uint32_t kind;     // 1: `status` is final; 2: per-cell status bytes still have to be OR-ed in
+  int64_t cells;     // kind 2: number of per-cell status bytes
+};
+#define DYN_WS_KIND_WORD 1u
+#define DYN_WS_KIND_CELLS 2u
+
 // Layout of the evaluation workspace (offsets in bytes, all multiples of 256).
 struct EvalWs {
-  size_t status, tin, tout, in_p99, rec, total;
+  size_t header, tin, tout, in_p99, rec, cstat, part, total;
+  int32_t n_wslot;   // partial records per cell
 };
-EvalWs dyn_eval_ws_layout(int64_t cells);
+EvalWs dyn_eval_ws_layout(int64_t cells, int32_t K);
 
 // ---- kernel launchers (each returns a hipError_t from the launch) ------------------------
 hipError_t dyn_launch_cell_aggregate(const int32_t* in_tok, const int32_t* out_tok,
                                      const int64_t* cell_off, int64_t n_req, int64_t cells,
                                      double window_s, int32_t pct_num, int32_t pct_den,
                                      int64_t* tin, int64_t* tout, int32_t* in_p99, CellRec* rec,
-                                     uint32_t* status, hipStream_t s);
+                                     uint8_t* cstat, WsHeader* header, hipStream_t s);
 
 struct SpaceArgs {
   const double* pf; const double* tb; const double* pw; const double* ml; const double* rg;
@@ -90,8 +108,16 @@ struct SpaceArgs {
   const double* slo_ttft; const double* slo_tbt; const int32_t* budget;
   const CellRec* rec; int32_t n_window; int32_t win_per_block; double window_s;
   double* energy; double* p99_ttft; double* p99_tbt; uint8_t* flags;
+  // fused selection (part != nullptr): per-wave partial argmin of cost = energy + idle term
+  const double* pw0; double idle_w; SelPart* part; int32_t n_wslot;
 };
 hipError_t dyn_launch_space(const SpaceArgs& a, hipStream_t s);
+
+struct FinishArgs {   // reduces the partial records of every cell, then the window totals
+  const SelPart* part; int32_t n_wslot; int32_t n_used; int32_t n_window, G;
+  int32_t* sel; double* sel_energy; double* sel_cost; double* win_energy; int32_t* win_inf;
+};
+hipError_t dyn_launch_finish(const FinishArgs& a, hipStream_t s);
 
 struct SelectArgs {
   const double* energy; const uint8_t* flags; const DevCfg* cfg; int32_t K;
@@ -113,5 +139,14 @@ int64_t dyn_ingest_blocks(int64_t n_req);
 #define DYN_INGEST_MAX_BINS 1024
 
 void dyn_set_error(const char* fmt, ...);
+
+// Optional event bracket around one kernel launch (see dyn_timing_enable).
+struct DynTimed {
+  DynTimed(int kernel, hipStream_t s);
+  ~DynTimed();
+  int kernel_;
+  hipStream_t s_;
+  int slot_;
+};
 
 #endif  // DYN_INTERNAL_H_

@@ -181,7 +181,8 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void cell_aggregate_kerne
     const int32_t* __restrict__ in, const int32_t* __restrict__ out,
     const int64_t* __restrict__ cell_off, int64_t n_req, int64_t cells, double window_s,
     int32_t pct_num, int32_t pct_den, int64_t* __restrict__ tin, int64_t* __restrict__ tout,
-    int32_t* __restrict__ in_p99, CellRec* __restrict__ rec, uint32_t* __restrict__ status) {
+    int32_t* __restrict__ in_p99, CellRec* __restrict__ rec, uint8_t* __restrict__ cstat,
+    WsHeader* __restrict__ header) {
   __shared__ uint32_t hist_all[kWavesPerBlock][kHistBins];
   const int lane = threadIdx.x & (DYN_WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
@@ -221,7 +222,12 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void cell_aggregate_kerne
     cr.load = (double)(r.tin + r.tout) / window_s;
     cr.xp99 = m > 0 ? (double)(int32_t)r.p99 : -1.0;
     rec[c] = cr;
-    if (bad) atomicOr(status, bad);
+    cstat[c] = (uint8_t)bad;       // every cell writes its own byte: nothing to clear beforehand
+    if (c == 0) {                  // single writer of the header
+      header->status = 0u;
+      header->kind = DYN_WS_KIND_CELLS;
+      header->cells = cells;
+    }
   }
 }
 
@@ -231,10 +237,11 @@ hipError_t dyn_launch_cell_aggregate(const int32_t* in_tok, const int32_t* out_t
                                      const int64_t* cell_off, int64_t n_req, int64_t cells,
                                      double window_s, int32_t pct_num, int32_t pct_den,
                                      int64_t* tin, int64_t* tout, int32_t* in_p99, CellRec* rec,
-                                     uint32_t* status, hipStream_t s) {
+                                     uint8_t* cstat, WsHeader* header, hipStream_t s) {
   const int64_t blocks = (cells + kWavesPerBlock - 1) / kWavesPerBlock;
+  DynTimed timed(DYN_K_CELL, s);
   hipLaunchKernelGGL(cell_aggregate_kernel, dim3((unsigned)blocks), dim3(kWavesPerBlock * DYN_WAVE),
                      0, s, in_tok, out_tok, cell_off, n_req, cells, window_s, pct_num, pct_den, tin,
-                     tout, in_p99, rec, status);
+                     tout, in_p99, rec, cstat, header);
   return hipGetLastError();
 }

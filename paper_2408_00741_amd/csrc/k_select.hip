@@ -76,14 +76,89 @@ __global__ void window_totals_kernel(const int32_t* __restrict__ sel, const doub
   win_inf[w] = ninf;
 }
 
+// Fused path: every cell has n_used partial records in ascending configuration order; a
+// strict "<" scan keeps the lowest index among equal costs.  One block per window when the
+// classes of a window fit a block: the class results go through LDS and thread 0 adds them
+// in class order.
+__global__ __launch_bounds__(256) void finish_kernel(FinishArgs a) {
+  extern __shared__ double s_e[];          // [G] selected energy, NaN marks "no feasible configuration"
+  const int w = blockIdx.x;
+  for (int g = threadIdx.x; g < a.G; g += blockDim.x) {
+    const size_t cell = (size_t)w * a.G + g;
+    const SelPart* p = a.part + cell * (size_t)a.n_wslot;
+    double bc = __builtin_inf(), be = __builtin_inf();
+    int32_t bk = -1;
+    for (int i = 0; i < a.n_used; ++i) {
+      const SelPart q = p[i];
+      if (q.k >= 0 && (bk < 0 || q.cost < bc)) { bc = q.cost; be = q.energy; bk = q.k; }
+    }
+    a.sel[cell] = bk;
+    a.sel_energy[cell] = be;
+    a.sel_cost[cell] = bc;
+    s_e[g] = bk >= 0 ? be : __builtin_nan("");
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double e = 0.0;
+    int32_t ninf = 0;
+    for (int g = 0; g < a.G; ++g) {
+      const double v = s_e[g];
+      if (v == v) e += v; else ++ninf;
+    }
+    a.win_energy[w] = e;
+    a.win_inf[w] = ninf;
+  }
+}
+
+__global__ __launch_bounds__(256) void finish_cells_kernel(FinishArgs a) {   // classes beyond one block's LDS
+  const int64_t cells = (int64_t)a.n_window * a.G;
+  const int64_t cell = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (cell >= cells) return;
+  const SelPart* p = a.part + (size_t)cell * a.n_wslot;
+  double bc = __builtin_inf(), be = __builtin_inf();
+  int32_t bk = -1;
+  for (int i = 0; i < a.n_used; ++i) {
+    const SelPart q = p[i];
+    if (q.k >= 0 && (bk < 0 || q.cost < bc)) { bc = q.cost; be = q.energy; bk = q.k; }
+  }
+  a.sel[cell] = bk;
+  a.sel_energy[cell] = be;
+  a.sel_cost[cell] = bc;
+}
+
 }  // namespace
+
+hipError_t dyn_launch_finish(const FinishArgs& a, hipStream_t s) {
+  if (a.G <= 4096) {
+    DynTimed timed(DYN_K_SELECT, s);
+    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)a.n_window), dim3(a.G <= 64 ? 64 : 256), (size_t)a.G * sizeof(double),
+                       s, a);
+    return hipGetLastError();
+  }
+  const int64_t cells = (int64_t)a.n_window * a.G;
+  {
+    DynTimed timed(DYN_K_SELECT, s);
+    hipLaunchKernelGGL(finish_cells_kernel, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, s, a);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  DynTimed timed(DYN_K_TOTALS, s);
+  hipLaunchKernelGGL(window_totals_kernel, dim3((unsigned)((a.n_window + 127) / 128)), dim3(128), 0, s, a.sel,
+                     a.sel_energy, a.n_window, a.G, a.win_energy, a.win_inf);
+  return hipGetLastError();
+}
 
 hipError_t dyn_launch_select(const SelectArgs& a, hipStream_t s) {
   const int64_t cells = (int64_t)a.n_window * a.G;
   const int64_t blocks = (cells + kWavesPerBlock - 1) / kWavesPerBlock;
-  hipLaunchKernelGGL(select_kernel, dim3((unsigned)blocks), dim3(kWavesPerBlock * DYN_WAVE), 0, s, a);
-  hipError_t e = hipGetLastError();
+  hipError_t e;
+  {
+    DynTimed timed(DYN_K_SELECT, s);
+    hipLaunchKernelGGL(select_kernel, dim3((unsigned)blocks), dim3(kWavesPerBlock * DYN_WAVE), 0, s, a);
+    e = hipGetLastError();
+  }
   if (e != hipSuccess) return e;
+  DynTimed timed(DYN_K_TOTALS, s);
   hipLaunchKernelGGL(window_totals_kernel, dim3((unsigned)((a.n_window + 127) / 128)), dim3(128), 0, s,
                      a.sel, a.sel_energy, a.n_window, a.G, a.win_energy, a.win_inf);
   return hipGetLastError();

@@ -12,7 +12,32 @@
 
 namespace {
 
-template <bool LDS>
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov_f64(double x) {
+  const uint64_t b = (uint64_t)__double_as_longlong(x);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, 0xF, 0xF, false);
+  return __longlong_as_double((long long)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo));
+}
+__device__ __forceinline__ double readlane_f64(double x, int lane) {
+  const uint64_t b = (uint64_t)__double_as_longlong(x);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, lane);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), lane);
+  return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+__device__ __forceinline__ double min_no_nan(double a, double b) { return b < a ? b : a; }
+// Minimum over the 64 lanes of a fully active wave (no NaNs): rotations inside each row of
+// 16 lanes, then the four row minima are combined as scalars.
+__device__ __forceinline__ double wave_min_f64(double x) {
+  x = min_no_nan(x, dpp_mov_f64<0x121>(x));
+  x = min_no_nan(x, dpp_mov_f64<0x122>(x));
+  x = min_no_nan(x, dpp_mov_f64<0x124>(x));
+  x = min_no_nan(x, dpp_mov_f64<0x128>(x));
+  return min_no_nan(min_no_nan(readlane_f64(x, 0), readlane_f64(x, 16)),
+                    min_no_nan(readlane_f64(x, 32), readlane_f64(x, 48)));
+}
+
+template <bool LDS, bool SEL>
 __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
   extern __shared__ double smem[];
   // block -> (window chunk, class, tile); tile fastest
@@ -43,8 +68,12 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
   for (int i = threadIdx.x; i <= a.n_bucket; i += blockDim.x) s_js[i] = a.jstart[i];
   __syncthreads();
 
-  const int k = tile * a.tile + threadIdx.x;
-  if (threadIdx.x >= a.tile || k >= a.K) return;
+  const int k_raw = tile * a.tile + threadIdx.x;
+  // with the fused selection every lane of a wave stays alive (the wave reduction needs full
+  // waves); lanes past the last configuration compute on configuration K-1 and store nothing
+  const bool live = k_raw < a.K;
+  if (!SEL && !live) return;
+  const int k = live ? k_raw : a.K - 1;
 
   const DevCfg c = a.cfg[k];
   const bool two_rows = c.u != 0.0;
@@ -56,6 +85,14 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
   const double slo_ttft = a.slo_ttft[g], slo_tbt = a.slo_tbt[g];
   const int32_t bud = a.budget[g];
   const uint32_t fl_budget = (bud > 0 && c.gpus > bud) ? DYN_F_BUDGET : 0u;
+  double idle_term = 0.0;
+  if (SEL) {
+    const double* p0 = a.pw0 + (size_t)g * a.n_tp_f;
+    const double pw0 = two_rows ? omu * p0[c.row_lo] + c.u * p0[c.row_hi] : p0[c.row_lo];
+    idle_term = a.idle_w * ((c.nd * pw0) * a.window_s);
+  }
+  const int lane = threadIdx.x & (DYN_WAVE - 1);
+  const int wslot = tile * (a.tile / DYN_WAVE) + (int)(threadIdx.x / DYN_WAVE);
 
   const double *lo_pf, *lo_tb, *lo_pw, *hi_pf, *hi_tb, *hi_pw;
   if (LDS) {
@@ -110,11 +147,33 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
     if (!fl) fl = DYN_F_FEASIBLE;
     if (empty) fl |= DYN_F_EMPTY;
 
-    const size_t o = cell * (size_t)a.K + k;
-    a.energy[o] = e;
-    a.p99_ttft[o] = p_ttft;
-    a.p99_tbt[o] = p_tbt;
-    a.flags[o] = (uint8_t)fl;
+    if (live) {
+      const size_t o = cell * (size_t)a.K + k;
+      a.energy[o] = e;
+      a.p99_ttft[o] = p_ttft;
+      a.p99_tbt[o] = p_tbt;
+      a.flags[o] = (uint8_t)fl;
+    }
+    if (SEL) {
+      // least cost among this wave's feasible configurations; the lowest lane (= lowest
+      // index) wins ties.  A feasible configuration whose cost is +inf still wins over none.
+      const bool feas = live && (fl & DYN_F_FEASIBLE);
+      const double cost = e + idle_term;
+      const double mn = wave_min_f64(feas ? cost : __builtin_inf());
+      const uint64_t win = __ballot(feas && cost == mn);
+      const int wl = win ? __builtin_ctzll(win) : 0;        // wave-uniform
+      const double e_win = readlane_f64(e, wl);
+      if (lane == 0) {
+        SelPart p;
+        p.cost = __builtin_inf(); p.energy = __builtin_inf(); p.k = -1; p.pad = 0;
+        if (win) {
+          p.cost = mn;
+          p.energy = e_win;
+          p.k = k_raw + wl;          // lane 0 holds the wave's first configuration
+        }
+        a.part[cell * (size_t)a.n_wslot + wslot] = p;
+      }
+    }
   }
 }
 
@@ -125,11 +184,15 @@ hipError_t dyn_launch_space(const SpaceArgs& a, hipStream_t s) {
   const size_t blocks = (size_t)n_chunk * a.G * a.n_tile;
   const size_t tail = (size_t)a.n_rho * sizeof(double) + ((size_t)a.n_bucket + 1) * sizeof(int32_t);
   const size_t lds_tab = (size_t)a.n_slot * 3 * a.n_rho * sizeof(double);
+  DynTimed timed(DYN_K_SPACE, s);
+  const size_t lds = (a.n_slot > 0 ? lds_tab : 0) + tail;   // the host keeps this within 64 KB
+  const dim3 grid((unsigned)blocks), block(a.tile);
   if (a.n_slot > 0) {
-    const size_t lds = lds_tab + tail;   // the host keeps this within 64 KB
-    hipLaunchKernelGGL(space_kernel<true>, dim3((unsigned)blocks), dim3(a.tile), lds, s, a);
+    if (a.part) hipLaunchKernelGGL((space_kernel<true, true>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((space_kernel<true, false>), grid, block, lds, s, a);
   } else {
-    hipLaunchKernelGGL(space_kernel<false>, dim3((unsigned)blocks), dim3(a.tile), tail, s, a);
+    if (a.part) hipLaunchKernelGGL((space_kernel<false, true>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((space_kernel<false, false>), grid, block, lds, s, a);
   }
   return hipGetLastError();
 }

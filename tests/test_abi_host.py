@@ -26,7 +26,8 @@ def test_every_declared_symbol_is_exported(dyn):
     names = _declared()
     assert {"dyn_profile_load", "dyn_eval_space", "dyn_select_config", "dyn_trace_ingest", "dyn_profile_free",
             "dyn_cell_stats", "dyn_workspace_status", "dyn_last_error", "dyn_eval_space_workspace",
-            "dyn_trace_ingest_workspace"} <= set(names)
+            "dyn_trace_ingest_workspace", "dyn_eval_select", "dyn_timing_enable", "dyn_timing_read",
+            "dyn_timing_reset"} <= set(names)
     lib = C.CDLL(dyn.lib_path())
     for n in names:
         assert hasattr(lib, n), n

@@ -46,6 +46,14 @@ def gpu_eval(dyn, w, ins, outs, off, gpu_budget=None, prof=None, plan=None):
     r = {k: v.cpu().numpy() for k, v in space.items()}
     r.update({k: v.cpu().numpy() for k, v in sel.items()})
     r.update(tin=tin.cpu().numpy(), tout=tout.cpu().numpy(), in_p99=p99.cpu().numpy(), status=status)
+    # the fused entry point must give the same bits as the two calls above
+    space2, sel2, ws2 = dyn.dyn_eval_select(prof, ins, outs, off, w["n_window"], w["window_s"], plan)
+    assert dyn.dyn_workspace_status(ws2) == status
+    torch.cuda.synchronize()
+    for k, v in space2.items():
+        np.testing.assert_array_equal(v.cpu().numpy(), r[k], err_msg=f"fused {k}")
+    for k, v in sel2.items():
+        np.testing.assert_array_equal(v.cpu().numpy(), r[k], err_msg=f"fused {k}")
     if own:
         prof.free()
     return r
