@@ -44,7 +44,7 @@ hipError_t dev_alloc(T** p, size_t count) {
 }
 
 void free_profile_device(dyn_profile* p) {
-  void* ptrs[] = {p->d_pf, p->d_tb, p->d_pw, p->d_ml, p->d_pw0, p->d_rg, p->d_jstart, p->d_cfg,
+  void* ptrs[] = {p->d_pf, p->d_tb, p->d_pw, p->d_ml, p->d_pw0, p->d_gridpack, p->d_jstart, p->d_cfg,
                   p->d_tile_rows, p->d_slo_ttft, p->d_slo_tbt, p->d_budget};
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
@@ -115,7 +115,7 @@ int prepare_configs(dyn_profile* p, const dyn_config* cfg, int32_t K, hipStream_
     const int wa = (K + cand[a] - 1) / cand[a] * cand[a] - K, wb = (K + cand[b] - 1) / cand[b] * cand[b] - K;
     return wa < wb;
   });
-  const size_t lds_tail = (size_t)p->n_rho * sizeof(double) + ((size_t)p->n_bucket + 1) * sizeof(int32_t);
+  const size_t lds_tail = dyn_space_lds_tail(p->n_rho, p->n_bucket);
   std::vector<int32_t> rows;
   int tile = cand[order[0]], n_tile = (K + tile - 1) / tile, n_slot = 0;
   bool fits = false;
@@ -171,6 +171,7 @@ int prepare_objective(dyn_profile* p, const dyn_objective* o, hipStream_t s) {
     return DYN_E_RANGE;
   }
   if (!isfinite(o->idle_cost_weight)) { dyn_set_error("idle_cost_weight is not finite"); return DYN_E_NOTFINITE; }
+  if (o->idle_cost_weight < 0.0) { dyn_set_error("idle_cost_weight must be >= 0"); return DYN_E_RANGE; }
   const int G = p->G;
   for (int g = 0; g < G; ++g) {
     if (isnan(o->slo_ttft_ms[g]) || isnan(o->slo_tbt_ms[g])) { dyn_set_error("SLO of class %d is NaN", g); return DYN_E_NOTFINITE; }
@@ -311,8 +312,8 @@ int eval_impl(dyn_profile* p, const dyn_trace_view* t, const dyn_config* cfg, in
     return DYN_E_DEVICE;
 
   SpaceArgs a;
-  a.pf = p->d_pf; a.tb = p->d_tb; a.pw = p->d_pw; a.ml = p->d_ml; a.rg = p->d_rg;
-  a.jstart = p->d_jstart; a.n_bucket = p->n_bucket; a.bucket_scale = p->bucket_scale;
+  a.pf = p->d_pf; a.tb = p->d_tb; a.pw = p->d_pw; a.ml = p->d_ml; a.gridpack = p->d_gridpack;
+  a.jstart = p->d_jstart; a.n_bucket = p->n_bucket; a.bucket_scale = p->bucket_scale; a.one_step = p->one_step;
   a.G = p->G; a.n_tp_f = p->n_tp * p->n_f; a.n_rho = p->n_rho;
   a.cfg = p->d_cfg; a.K = K; a.tile = p->tile; a.n_tile = p->n_tile; a.n_slot = p->n_slot;
   a.tile_rows = p->d_tile_rows;
@@ -320,7 +321,7 @@ int eval_impl(dyn_profile* p, const dyn_trace_view* t, const dyn_config* cfg, in
   a.rec = (const CellRec*)(base + w.rec); a.n_window = t->n_window; a.window_s = t->window_s;
   // enough blocks to fill the chip several times over, long enough runs to amortise staging
   const int64_t cell_tiles = cells * p->n_tile;
-  a.win_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(32, cell_tiles / 4096));
+  a.win_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(DYN_MAX_WIN_PER_BLOCK, cell_tiles / 8192));
   a.energy = out->energy_j; a.p99_ttft = out->p99_ttft_ms; a.p99_tbt = out->p99_tbt_ms; a.flags = out->flags;
   a.pw0 = p->d_pw0; a.idle_w = o->idle_cost_weight;
   a.part = sel ? (SelPart*)(base + w.part) : nullptr; a.n_wslot = w.n_wslot;
@@ -378,31 +379,43 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   p->G = d->n_class; p->n_tp = d->n_tp; p->n_f = d->n_f; p->n_rho = d->n_rho;
   p->tp.assign(d->tp, d->tp + d->n_tp);
   p->fg.assign(d->f_mhz, d->f_mhz + d->n_f);
-  p->d_pf = p->d_tb = p->d_pw = p->d_ml = p->d_pw0 = p->d_rg = nullptr;
+  p->d_pf = p->d_tb = p->d_pw = p->d_ml = p->d_pw0 = p->d_gridpack = nullptr;
   p->d_jstart = nullptr; p->d_cfg = nullptr; p->d_tile_rows = nullptr;
   p->d_slo_ttft = p->d_slo_tbt = nullptr; p->d_budget = nullptr;
   p->obj_valid = false; p->tile = p->n_tile = p->n_slot = 0;
   hipStream_t s = (hipStream_t)hip_stream;
 
-  // bucket index over the load axis
+  // Bucket index over the load axis: bucket b covers [b, b+1) / bucket_scale and js[b] is the
+  // largest grid index i <= n_rho-2 with rho[i] <= b / bucket_scale.  The buckets are made
+  // fine enough (up to 4096 of them) that no two neighbouring buckets hold more than one
+  // grid point; then a bracket is at most one step away from its bucket's index.
   const double rho_max = d->rho[d->n_rho - 1];
-  p->n_bucket = std::min(4 * d->n_rho, 4096);
+  double min_gap = rho_max;
+  for (int q = 1; q < d->n_rho; ++q) min_gap = std::min(min_gap, d->rho[q] - d->rho[q - 1]);
+  const double want = 3.0 * rho_max / min_gap;            // bucket width <= a third of the narrowest interval
+  p->n_bucket = (int32_t)std::min(4096.0, std::max(16.0, ceil(want)));
+  p->one_step = (double)p->n_bucket >= want;
   p->bucket_scale = (double)p->n_bucket / rho_max;
   std::vector<int32_t> js(p->n_bucket + 1);
   for (int b = 0; b <= p->n_bucket; ++b) {
     const double x = (double)b / p->bucket_scale;
     int j = 0;
-    for (int q = 0; q < d->n_rho; ++q)
+    for (int q = 0; q < d->n_rho - 1; ++q)
       if (d->rho[q] <= x) j = q;
     js[b] = j;
   }
+  std::vector<double> gridpack(2 * (size_t)d->n_rho + 3, 0.0);
+  gridpack[0] = -INFINITY;
+  for (int q = 0; q < d->n_rho; ++q) gridpack[1 + q] = d->rho[q];
+  gridpack[d->n_rho + 1] = INFINITY;
+  for (int q = 0; q + 1 < d->n_rho; ++q) gridpack[d->n_rho + 3 + q] = 1.0 / (d->rho[q + 1] - d->rho[q]);
   std::vector<double> pw0(n_row);
   for (size_t r = 0; r < n_row; ++r) pw0[r] = d->power_w[r * d->n_rho];
 
   bool ok = hip_ok(hipGetDevice(&p->device), "hipGetDevice") &&
             hip_ok(dev_alloc(&p->d_pf, n_tab), "hipMalloc") && hip_ok(dev_alloc(&p->d_tb, n_tab), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_pw, n_tab), "hipMalloc") && hip_ok(dev_alloc(&p->d_ml, n_row), "hipMalloc") &&
-            hip_ok(dev_alloc(&p->d_pw0, n_row), "hipMalloc") && hip_ok(dev_alloc(&p->d_rg, d->n_rho), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_pw0, n_row), "hipMalloc") && hip_ok(dev_alloc(&p->d_gridpack, gridpack.size()), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_jstart, js.size()), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_cfg, DYN_MAX_CONFIGS), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_tile_rows, 2 * DYN_MAX_CONFIGS + 1024), "hipMalloc") &&
@@ -413,7 +426,7 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
        hip_ok(hipMemcpyAsync(p->d_pw, d->power_w, n_tab * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_ml, d->max_load_tps, n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_pw0, pw0.data(), n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
-       hip_ok(hipMemcpyAsync(p->d_rg, d->rho, (size_t)d->n_rho * 8, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_gridpack, gridpack.data(), gridpack.size() * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_jstart, js.data(), js.size() * 4, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize");
   if (!ok) {

@@ -32,6 +32,7 @@ struct CellRec {  // what the space kernel needs from a cell
 #define DYN_MAX_CONFIGS 65536     // capacity of a profile handle's configuration table
 #define DYN_MAX_TILE 256          // configurations per tile of the space kernel
 #define DYN_LDS_BUDGET (64 * 1024)
+#define DYN_MAX_WIN_PER_BLOCK 32  // windows one block of the space kernel walks
 
 // ---- host-side profile handle -----------------------------------------------------------
 // Besides the tables it owns the device copies of the last candidate list and objective
@@ -47,7 +48,10 @@ struct dyn_profile {
   double* d_pw;
   double* d_ml;   // [G][n_tp][n_f]
   double* d_pw0;  // [G][n_tp][n_f]  power at load 0 (first column of d_pw)
-  double* d_rg;   // [n_rho]
+  // load grid for the kernels: [-inf, rho[0..n_rho-1], +inf] followed by
+  // [0, 1/(rho[1]-rho[0]), ..., 1/(rho[n_rho-1]-rho[n_rho-2]), 0]
+  double* d_gridpack;   // [2*n_rho + 3]
+  bool one_step;        // every bracket is at most one step away from its bucket's index
   // bucket index over the load axis: bucket b covers [b, b+1) / bucket_scale and jstart[b]
   // is the largest grid index i with rg[i] <= b / bucket_scale
   int32_t* d_jstart;  // [n_bucket + 1]
@@ -99,8 +103,8 @@ hipError_t dyn_launch_cell_aggregate(const int32_t* in_tok, const int32_t* out_t
                                      uint8_t* cstat, WsHeader* header, hipStream_t s);
 
 struct SpaceArgs {
-  const double* pf; const double* tb; const double* pw; const double* ml; const double* rg;
-  const int32_t* jstart; int32_t n_bucket; double bucket_scale;
+  const double* pf; const double* tb; const double* pw; const double* ml; const double* gridpack;
+  const int32_t* jstart; int32_t n_bucket; double bucket_scale; bool one_step;
   int32_t G, n_tp_f /* n_tp*n_f */, n_rho;
   const DevCfg* cfg; int32_t K;
   int32_t tile, n_tile, n_slot;       // configurations per tile, tiles, LDS slots per tile
@@ -112,6 +116,7 @@ struct SpaceArgs {
   const double* pw0; double idle_w; SelPart* part; int32_t n_wslot;
 };
 hipError_t dyn_launch_space(const SpaceArgs& a, hipStream_t s);
+size_t dyn_space_lds_tail(int32_t n_rho, int32_t n_bucket);   // LDS bytes besides the table rows
 
 struct FinishArgs {   // reduces the partial records of every cell, then the window totals
   const SelPart* part; int32_t n_wslot; int32_t n_used; int32_t n_window, G;

@@ -8,36 +8,45 @@
 // ms/token, energy = instances x power x window, feasibility per Eq. 1.
 // Output rows are written with the configuration index fastest: 8-byte stores, 512
 // contiguous bytes per wave and array.
+//
+// The two divisions per entry (load / capacity, position inside the load bracket) have
+// divisors that do not depend on the window: their correctly rounded reciprocals are
+// computed once (per thread, per grid interval) and each quotient is then formed as
+// q = a*r, e = fma(-b, q, a), q + e*r, which is the closing step of the usual
+// Newton-Raphson division and returns the correctly rounded a/b.
+//
+// With the fused selection, each wave also reduces the least cost among its feasible
+// configurations (Section IV-B "Scale-up/down") and one lane writes a partial record.
 #include "dyn_internal.h"
 
 namespace {
 
 template <int CTRL>
-__device__ __forceinline__ double dpp_mov_f64(double x) {
-  const uint64_t b = (uint64_t)__double_as_longlong(x);
-  const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, 0xF, 0xF, false);
-  const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, 0xF, 0xF, false);
-  return __longlong_as_double((long long)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo));
+__device__ __forceinline__ uint32_t dpp_row_u32(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, false);
 }
-__device__ __forceinline__ double readlane_f64(double x, int lane) {
-  const uint64_t b = (uint64_t)__double_as_longlong(x);
-  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, lane);
-  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), lane);
-  return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
-}
-__device__ __forceinline__ double min_no_nan(double a, double b) { return b < a ? b : a; }
-// Minimum over the 64 lanes of a fully active wave (no NaNs): rotations inside each row of
-// 16 lanes, then the four row minima are combined as scalars.
-__device__ __forceinline__ double wave_min_f64(double x) {
-  x = min_no_nan(x, dpp_mov_f64<0x121>(x));
-  x = min_no_nan(x, dpp_mov_f64<0x122>(x));
-  x = min_no_nan(x, dpp_mov_f64<0x124>(x));
-  x = min_no_nan(x, dpp_mov_f64<0x128>(x));
-  return min_no_nan(min_no_nan(readlane_f64(x, 0), readlane_f64(x, 16)),
-                    min_no_nan(readlane_f64(x, 32), readlane_f64(x, 48)));
+// Minimum over the 64 lanes of a fully active wave: rotations inside each row of 16 lanes
+// leave the row minimum in every lane, the four row minima are combined as scalars.
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
+  x = min(x, dpp_row_u32<0x121>(x));  // row_ror:1
+  x = min(x, dpp_row_u32<0x122>(x));  // row_ror:2
+  x = min(x, dpp_row_u32<0x124>(x));  // row_ror:4
+  x = min(x, dpp_row_u32<0x128>(x));  // row_ror:8
+  const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
+  const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+  return min(min(a, b), min(c, d));
 }
 
-template <bool LDS, bool SEL>
+// a / b given rb = RN(1 / b): correctly rounded for normal operands and quotients.
+__device__ __forceinline__ double div_by(double a, double b, double rb) {
+  const double q = a * rb;
+  const double e = __builtin_fma(-b, q, a);
+  return __builtin_fma(e, rb, q);
+}
+
+// LDS: [table rows n_slot*3*n_rho] [padded load grid n_rho+2] [padded reciprocal spacings n_rho+1]
+//      [cell records win_per_block] [bucket index n_bucket+1 (int)]
+template <bool LDS, bool SEL, bool ONE_STEP>
 __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
   extern __shared__ double smem[];
   // block -> (window chunk, class, tile); tile fastest
@@ -46,26 +55,33 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
   const int chunk = blockIdx.x / (a.n_tile * a.G);
   const int n_rho = a.n_rho;
 
-  double* s_tab = smem;                                   // [n_slot][3][n_rho]
-  double* s_rg = smem + (LDS ? (size_t)a.n_slot * 3 * n_rho : 0);   // [n_rho]
-  int32_t* s_js = (int32_t*)(s_rg + n_rho);               // [n_bucket + 1]
+  double* s_tab = smem;                                              // [n_slot][3][n_rho]
+  double* s_rgp = smem + (LDS ? (size_t)a.n_slot * 3 * n_rho : 0);   // s_rgp[i+1] = rho[i]; -inf, +inf pads
+  double* s_rinv = s_rgp + (n_rho + 2);                              // s_rinv[i+1] = 1/(rho[i+1]-rho[i]); 0 pads
+  CellRec* s_rec = (CellRec*)(s_rinv + (n_rho + 1));                 // [win_per_block]
+  int32_t* s_js = (int32_t*)(s_rec + a.win_per_block);               // [n_bucket + 1]
 
+  const int w0 = chunk * a.win_per_block;
+  const int w1 = min(w0 + a.win_per_block, a.n_window);
   if (LDS) {
     const int per_slot = 3 * n_rho;
-    for (int i = threadIdx.x; i < a.n_slot * per_slot; i += blockDim.x) {
-      const int slot = i / per_slot, rem = i - slot * per_slot;
-      const int q = rem / n_rho, j = rem - q * n_rho;
-      const int row = a.tile_rows[tile * a.n_slot + slot];
-      double v = 0.0;
-      if (row >= 0) {
-        const double* src = q == 0 ? a.pf : (q == 1 ? a.tb : a.pw);
-        v = src[((size_t)g * a.n_tp_f + row) * n_rho + j];
+    for (int slot = 0; slot < a.n_slot; ++slot) {
+      const int row = a.tile_rows[tile * a.n_slot + slot];       // wave-uniform
+      for (int i = threadIdx.x; i < per_slot; i += blockDim.x) {
+        const int q = (i >= n_rho) + (i >= 2 * n_rho), j = i - q * n_rho;
+        double v = 0.0;
+        if (row >= 0) {
+          const double* src = q == 0 ? a.pf : (q == 1 ? a.tb : a.pw);
+          v = src[((size_t)g * a.n_tp_f + row) * n_rho + j];
+        }
+        s_tab[slot * per_slot + i] = v;
       }
-      s_tab[i] = v;
     }
   }
-  for (int i = threadIdx.x; i < n_rho; i += blockDim.x) s_rg[i] = a.rg[i];
+  for (int i = threadIdx.x; i < 2 * n_rho + 3; i += blockDim.x) s_rgp[i] = a.gridpack[i];
   for (int i = threadIdx.x; i <= a.n_bucket; i += blockDim.x) s_js[i] = a.jstart[i];
+  // the cells of this block's run of windows (load, P99 input length)
+  for (int i = threadIdx.x; i < w1 - w0; i += blockDim.x) s_rec[i] = a.rec[(size_t)(w0 + i) * a.G + g];
   __syncthreads();
 
   const int k_raw = tile * a.tile + threadIdx.x;
@@ -81,7 +97,8 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
   const double* mlrow = a.ml + (size_t)g * a.n_tp_f;
   const double ml = two_rows ? omu * mlrow[c.row_lo] + c.u * mlrow[c.row_hi] : mlrow[c.row_lo];
   const double den = c.nd * ml;
-  const double rho_max = s_rg[n_rho - 1];
+  const double rden = 1.0 / den;
+  const double rho_max = s_rgp[n_rho];
   const double slo_ttft = a.slo_ttft[g], slo_tbt = a.slo_tbt[g];
   const int32_t bud = a.budget[g];
   const uint32_t fl_budget = (bud > 0 && c.gpus > bud) ? DYN_F_BUDGET : 0u;
@@ -104,25 +121,32 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
     hi_pf = a.pf + oh; hi_tb = a.tb + oh; hi_pw = a.pw + oh;
   }
 
-  const int w0 = chunk * a.win_per_block;
-  const int w1 = min(w0 + a.win_per_block, a.n_window);
   for (int w = w0; w < w1; ++w) {
     const size_t cell = (size_t)w * a.G + g;
-    const CellRec rec = a.rec[cell];
+    const CellRec rec = s_rec[w - w0];
     const bool empty = rec.xp99 < 0.0;
 
-    const double rho = rec.load / den;
+    const double rho = div_by(rec.load, den, rden);
     const bool ov = rho > rho_max;
     const double rc = ov ? rho_max : rho;
-    // bracket: largest j with rg[j] <= rc, at most n_rho-2; start from the bucket index
+    // bracket: largest j with rho[j] <= rc, at most n_rho-2; start from the bucket index
     int b = (int)(rc * a.bucket_scale);
     b = b < 0 ? 0 : (b > a.n_bucket ? a.n_bucket : b);
-    int j = s_js[b];
-    while (j > 0 && s_rg[j] > rc) --j;
-    while (j < n_rho - 2 && s_rg[j + 1] <= rc) ++j;
-    if (j > n_rho - 2) j = n_rho - 2;
-    const double r0 = s_rg[j], r1 = s_rg[j + 1];
-    const double t = (rc - r0) / (r1 - r0);
+    int j = s_js[b];                                   // <= n_rho-2 by construction
+    double r0, r1, ri;
+    if (ONE_STEP) {
+      // the grid is coarse against the buckets: the bracket is j-1, j or j+1
+      const double g0 = s_rgp[j + 1], g1 = s_rgp[j + 2];
+      const bool down = g0 > rc && j > 0;
+      const bool up = !down && g1 <= rc && j < n_rho - 2;
+      j += up ? 1 : (down ? -1 : 0);
+      r0 = s_rgp[j + 1]; r1 = s_rgp[j + 2]; ri = s_rinv[j + 1];
+    } else {
+      while (j > 0 && s_rgp[j + 1] > rc) --j;
+      while (j < n_rho - 2 && s_rgp[j + 2] <= rc) ++j;
+      r0 = s_rgp[j + 1]; r1 = s_rgp[j + 2]; ri = s_rinv[j + 1];
+    }
+    const double t = div_by(rc - r0, r1 - r0, ri);
     const double omt = 1.0 - t;
 
     double pf = omt * lo_pf[j] + t * lo_pf[j + 1];
@@ -148,51 +172,66 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
     if (empty) fl |= DYN_F_EMPTY;
 
     if (live) {
-      const size_t o = cell * (size_t)a.K + k;
-      a.energy[o] = e;
-      a.p99_ttft[o] = p_ttft;
-      a.p99_tbt[o] = p_tbt;
-      a.flags[o] = (uint8_t)fl;
+      const size_t row = cell * (size_t)a.K;      // wave-uniform row start, lane offset k
+      (a.energy + row)[k] = e;
+      (a.p99_ttft + row)[k] = p_ttft;
+      (a.p99_tbt + row)[k] = p_tbt;
+      (a.flags + row)[k] = (uint8_t)fl;
     }
     if (SEL) {
-      // least cost among this wave's feasible configurations; the lowest lane (= lowest
-      // index) wins ties.  A feasible configuration whose cost is +inf still wins over none.
+      // Least cost among this wave's feasible configurations; costs are >= +0, so their bit
+      // patterns order like unsigned integers: minimum of the high words, then of the low
+      // words among the lanes that hold it.  The lowest lane (= lowest index) wins ties.
       const bool feas = live && (fl & DYN_F_FEASIBLE);
       const double cost = e + idle_term;
-      const double mn = wave_min_f64(feas ? cost : __builtin_inf());
-      const uint64_t win = __ballot(feas && cost == mn);
-      const int wl = win ? __builtin_ctzll(win) : 0;        // wave-uniform
-      const double e_win = readlane_f64(e, wl);
-      if (lane == 0) {
+      const uint64_t bits = (uint64_t)__double_as_longlong(cost);
+      const uint32_t hi = feas ? (uint32_t)(bits >> 32) : 0xFFFFFFFFu;
+      const uint32_t lo = feas ? (uint32_t)bits : 0xFFFFFFFFu;
+      const uint32_t mh = wave_min_u32(hi);
+      uint64_t win = __ballot(feas && hi == mh);
+      if (__popcll(win) > 1) {                     // wave-uniform: several lanes share the high word
+        const uint32_t mlo = wave_min_u32(hi == mh ? lo : 0xFFFFFFFFu);
+        win = __ballot(feas && hi == mh && lo == mlo);
+      }
+      const int wl = win ? __builtin_ctzll(win) : 0;     // wave-uniform
+      if (lane == wl) {
         SelPart p;
-        p.cost = __builtin_inf(); p.energy = __builtin_inf(); p.k = -1; p.pad = 0;
-        if (win) {
-          p.cost = mn;
-          p.energy = e_win;
-          p.k = k_raw + wl;          // lane 0 holds the wave's first configuration
-        }
+        p.cost = win ? cost : __builtin_inf();
+        p.energy = win ? e : __builtin_inf();
+        p.k = win ? k_raw : -1;
+        p.pad = 0;
         a.part[cell * (size_t)a.n_wslot + wslot] = p;
       }
     }
   }
 }
 
+template <bool LDS, bool SEL>
+void launch_one_step(const SpaceArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
+  if (a.one_step) hipLaunchKernelGGL((space_kernel<LDS, SEL, true>), grid, block, lds, s, a);
+  else hipLaunchKernelGGL((space_kernel<LDS, SEL, false>), grid, block, lds, s, a);
+}
+
 }  // namespace
+
+size_t dyn_space_lds_tail(int32_t n_rho, int32_t n_bucket) {
+  return (size_t)(2 * n_rho + 3) * sizeof(double) + (size_t)DYN_MAX_WIN_PER_BLOCK * sizeof(CellRec) +
+         ((size_t)n_bucket + 1) * sizeof(int32_t);
+}
 
 hipError_t dyn_launch_space(const SpaceArgs& a, hipStream_t s) {
   const int n_chunk = (a.n_window + a.win_per_block - 1) / a.win_per_block;
   const size_t blocks = (size_t)n_chunk * a.G * a.n_tile;
-  const size_t tail = (size_t)a.n_rho * sizeof(double) + ((size_t)a.n_bucket + 1) * sizeof(int32_t);
   const size_t lds_tab = (size_t)a.n_slot * 3 * a.n_rho * sizeof(double);
   DynTimed timed(DYN_K_SPACE, s);
-  const size_t lds = (a.n_slot > 0 ? lds_tab : 0) + tail;   // the host keeps this within 64 KB
+  const size_t lds = (a.n_slot > 0 ? lds_tab : 0) + dyn_space_lds_tail(a.n_rho, a.n_bucket);  // host keeps this <= 64 KB
   const dim3 grid((unsigned)blocks), block(a.tile);
   if (a.n_slot > 0) {
-    if (a.part) hipLaunchKernelGGL((space_kernel<true, true>), grid, block, lds, s, a);
-    else hipLaunchKernelGGL((space_kernel<true, false>), grid, block, lds, s, a);
+    if (a.part) launch_one_step<true, true>(a, grid, block, lds, s);
+    else launch_one_step<true, false>(a, grid, block, lds, s);
   } else {
-    if (a.part) hipLaunchKernelGGL((space_kernel<false, true>), grid, block, lds, s, a);
-    else hipLaunchKernelGGL((space_kernel<false, false>), grid, block, lds, s, a);
+    if (a.part) launch_one_step<false, true>(a, grid, block, lds, s);
+    else launch_one_step<false, false>(a, grid, block, lds, s);
   }
   return hipGetLastError();
 }
