@@ -44,7 +44,7 @@ hipError_t dev_alloc(T** p, size_t count) {
 }
 
 void free_profile_device(dyn_profile* p) {
-  void* ptrs[] = {p->d_pf, p->d_tb, p->d_pw, p->d_ml, p->d_pw0, p->d_gridpack, p->d_jstart, p->d_cfg,
+  void* ptrs[] = {p->d_tab, p->d_ml, p->d_pw0, p->d_gridpack, p->d_jstart, p->d_cfg,
                   p->d_tile_rows, p->d_slo_ttft, p->d_slo_tbt, p->d_budget};
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
@@ -312,16 +312,17 @@ int eval_impl(dyn_profile* p, const dyn_trace_view* t, const dyn_config* cfg, in
     return DYN_E_DEVICE;
 
   SpaceArgs a;
-  a.pf = p->d_pf; a.tb = p->d_tb; a.pw = p->d_pw; a.ml = p->d_ml; a.gridpack = p->d_gridpack;
+  a.tab = p->d_tab; a.ml = p->d_ml; a.gridpack = p->d_gridpack;
   a.jstart = p->d_jstart; a.n_bucket = p->n_bucket; a.bucket_scale = p->bucket_scale; a.one_step = p->one_step;
   a.G = p->G; a.n_tp_f = p->n_tp * p->n_f; a.n_rho = p->n_rho;
   a.cfg = p->d_cfg; a.K = K; a.tile = p->tile; a.n_tile = p->n_tile; a.n_slot = p->n_slot;
   a.tile_rows = p->d_tile_rows;
   a.slo_ttft = p->d_slo_ttft; a.slo_tbt = p->d_slo_tbt; a.budget = p->d_budget;
   a.rec = (const CellRec*)(base + w.rec); a.n_window = t->n_window; a.window_s = t->window_s;
-  // enough blocks to fill the chip several times over, long enough runs to amortise staging
+  // several rounds of resident blocks on 256 CUs, with runs of windows long enough to
+  // amortise the LDS staging (measured optimum on the one-day workload: 13 to 20 windows)
   const int64_t cell_tiles = cells * p->n_tile;
-  a.win_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(DYN_MAX_WIN_PER_BLOCK, cell_tiles / 8192));
+  a.win_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(DYN_MAX_WIN_PER_BLOCK, (cell_tiles + 8191) / 8192));
   a.energy = out->energy_j; a.p99_ttft = out->p99_ttft_ms; a.p99_tbt = out->p99_tbt_ms; a.flags = out->flags;
   a.pw0 = p->d_pw0; a.idle_w = o->idle_cost_weight;
   a.part = sel ? (SelPart*)(base + w.part) : nullptr; a.n_wslot = w.n_wslot;
@@ -379,7 +380,7 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   p->G = d->n_class; p->n_tp = d->n_tp; p->n_f = d->n_f; p->n_rho = d->n_rho;
   p->tp.assign(d->tp, d->tp + d->n_tp);
   p->fg.assign(d->f_mhz, d->f_mhz + d->n_f);
-  p->d_pf = p->d_tb = p->d_pw = p->d_ml = p->d_pw0 = p->d_gridpack = nullptr;
+  p->d_tab = p->d_ml = p->d_pw0 = p->d_gridpack = nullptr;
   p->d_jstart = nullptr; p->d_cfg = nullptr; p->d_tile_rows = nullptr;
   p->d_slo_ttft = p->d_slo_tbt = nullptr; p->d_budget = nullptr;
   p->obj_valid = false; p->tile = p->n_tile = p->n_slot = 0;
@@ -396,7 +397,7 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   p->n_bucket = (int32_t)std::min(4096.0, std::max(16.0, ceil(want)));
   p->one_step = (double)p->n_bucket >= want;
   p->bucket_scale = (double)p->n_bucket / rho_max;
-  std::vector<int32_t> js(p->n_bucket + 1);
+  std::vector<int32_t> js(p->n_bucket + 1);     // index n_bucket is reached only by rc == rho_max
   for (int b = 0; b <= p->n_bucket; ++b) {
     const double x = (double)b / p->bucket_scale;
     int j = 0;
@@ -409,21 +410,25 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   for (int q = 0; q < d->n_rho; ++q) gridpack[1 + q] = d->rho[q];
   gridpack[d->n_rho + 1] = INFINITY;
   for (int q = 0; q + 1 < d->n_rho; ++q) gridpack[d->n_rho + 3 + q] = 1.0 / (d->rho[q + 1] - d->rho[q]);
+  // one packed row per (class, TP, f): prefill | TBT | power
+  std::vector<double> packed(3 * n_tab);
+  for (size_t r = 0; r < n_row; ++r) {
+    memcpy(&packed[(3 * r + 0) * d->n_rho], d->prefill_ms_per_tok + r * d->n_rho, (size_t)d->n_rho * 8);
+    memcpy(&packed[(3 * r + 1) * d->n_rho], d->tbt_ms + r * d->n_rho, (size_t)d->n_rho * 8);
+    memcpy(&packed[(3 * r + 2) * d->n_rho], d->power_w + r * d->n_rho, (size_t)d->n_rho * 8);
+  }
   std::vector<double> pw0(n_row);
   for (size_t r = 0; r < n_row; ++r) pw0[r] = d->power_w[r * d->n_rho];
 
   bool ok = hip_ok(hipGetDevice(&p->device), "hipGetDevice") &&
-            hip_ok(dev_alloc(&p->d_pf, n_tab), "hipMalloc") && hip_ok(dev_alloc(&p->d_tb, n_tab), "hipMalloc") &&
-            hip_ok(dev_alloc(&p->d_pw, n_tab), "hipMalloc") && hip_ok(dev_alloc(&p->d_ml, n_row), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_tab, 3 * n_tab), "hipMalloc") && hip_ok(dev_alloc(&p->d_ml, n_row), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_pw0, n_row), "hipMalloc") && hip_ok(dev_alloc(&p->d_gridpack, gridpack.size()), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_jstart, js.size()), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_cfg, DYN_MAX_CONFIGS), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_tile_rows, 2 * DYN_MAX_CONFIGS + 1024), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_slo_ttft, p->G), "hipMalloc") && hip_ok(dev_alloc(&p->d_slo_tbt, p->G), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_budget, p->G), "hipMalloc");
-  ok = ok && hip_ok(hipMemcpyAsync(p->d_pf, d->prefill_ms_per_tok, n_tab * 8, hipMemcpyHostToDevice, s), "copy") &&
-       hip_ok(hipMemcpyAsync(p->d_tb, d->tbt_ms, n_tab * 8, hipMemcpyHostToDevice, s), "copy") &&
-       hip_ok(hipMemcpyAsync(p->d_pw, d->power_w, n_tab * 8, hipMemcpyHostToDevice, s), "copy") &&
+  ok = ok && hip_ok(hipMemcpyAsync(p->d_tab, packed.data(), 3 * n_tab * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_ml, d->max_load_tps, n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_pw0, pw0.data(), n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_gridpack, gridpack.data(), gridpack.size() * 8, hipMemcpyHostToDevice, s), "copy") &&

@@ -24,9 +24,11 @@ struct DevCfg {
   int32_t slot_lo, slot_hi;  // LDS slots of the two rows inside the configuration's tile
 };
 
-struct CellRec {  // what the space kernel needs from a cell
-  double load;    // (tin + tout) / window_s
-  double xp99;    // (double) in_p99, or -1.0 for an empty cell
+struct CellRec {  // what the space kernel needs from a cell (32 bytes)
+  double load;      // (tin + tout) / window_s
+  double xp99;      // (double) in_p99; 0 for an empty cell
+  double nonempty;  // 1.0, or 0.0 for an empty cell (exact multiplier for the cell's percentiles)
+  double pad;
 };
 
 #define DYN_MAX_CONFIGS 65536     // capacity of a profile handle's configuration table
@@ -42,10 +44,9 @@ struct dyn_profile {
   std::vector<int32_t> tp;   // host copies used to validate candidate configurations
   std::vector<double> fg;
   int device;
-  // device copies; tables keep the caller's [G][n_tp][n_f][n_rho] layout
-  double* d_pf;
-  double* d_tb;
-  double* d_pw;
+  // device copy of the tables, one packed row per (class, TP, f):
+  // [G][n_tp*n_f][3][n_rho] with the three tables (prefill, TBT, power) side by side
+  double* d_tab;
   double* d_ml;   // [G][n_tp][n_f]
   double* d_pw0;  // [G][n_tp][n_f]  power at load 0 (first column of d_pw)
   // load grid for the kernels: [-inf, rho[0..n_rho-1], +inf] followed by
@@ -103,7 +104,7 @@ hipError_t dyn_launch_cell_aggregate(const int32_t* in_tok, const int32_t* out_t
                                      uint8_t* cstat, WsHeader* header, hipStream_t s);
 
 struct SpaceArgs {
-  const double* pf; const double* tb; const double* pw; const double* ml; const double* gridpack;
+  const double* tab; const double* ml; const double* gridpack;
   const int32_t* jstart; int32_t n_bucket; double bucket_scale; bool one_step;
   int32_t G, n_tp_f /* n_tp*n_f */, n_rho;
   const DevCfg* cfg; int32_t K;

@@ -220,7 +220,9 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void cell_aggregate_kerne
     in_p99[c] = (int32_t)r.p99;
     CellRec cr;
     cr.load = (double)(r.tin + r.tout) / window_s;
-    cr.xp99 = m > 0 ? (double)(int32_t)r.p99 : -1.0;
+    cr.xp99 = (double)(int32_t)r.p99;
+    cr.nonempty = m > 0 ? 1.0 : 0.0;
+    cr.pad = 0.0;
     rec[c] = cr;
     cstat[c] = (uint8_t)bad;       // every cell writes its own byte: nothing to clear beforehand
     if (c == 0) {                  // single writer of the header

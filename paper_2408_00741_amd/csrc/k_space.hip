@@ -66,16 +66,9 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
   if (LDS) {
     const int per_slot = 3 * n_rho;
     for (int slot = 0; slot < a.n_slot; ++slot) {
-      const int row = a.tile_rows[tile * a.n_slot + slot];       // wave-uniform
-      for (int i = threadIdx.x; i < per_slot; i += blockDim.x) {
-        const int q = (i >= n_rho) + (i >= 2 * n_rho), j = i - q * n_rho;
-        double v = 0.0;
-        if (row >= 0) {
-          const double* src = q == 0 ? a.pf : (q == 1 ? a.tb : a.pw);
-          v = src[((size_t)g * a.n_tp_f + row) * n_rho + j];
-        }
-        s_tab[slot * per_slot + i] = v;
-      }
+      const int row = a.tile_rows[tile * a.n_slot + slot];       // wave-uniform; -1 = unused slot
+      const double* src = a.tab + ((size_t)g * a.n_tp_f + (row < 0 ? 0 : row)) * per_slot;
+      for (int i = threadIdx.x; i < per_slot; i += blockDim.x) s_tab[slot * per_slot + i] = src[i];
     }
   }
   for (int i = threadIdx.x; i < 2 * n_rho + 3; i += blockDim.x) s_rgp[i] = a.gridpack[i];
@@ -116,22 +109,21 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
     lo_pf = s_tab + (size_t)c.slot_lo * 3 * n_rho; lo_tb = lo_pf + n_rho; lo_pw = lo_tb + n_rho;
     hi_pf = s_tab + (size_t)c.slot_hi * 3 * n_rho; hi_tb = hi_pf + n_rho; hi_pw = hi_tb + n_rho;
   } else {
-    const size_t ol = ((size_t)g * a.n_tp_f + c.row_lo) * n_rho, oh = ((size_t)g * a.n_tp_f + c.row_hi) * n_rho;
-    lo_pf = a.pf + ol; lo_tb = a.tb + ol; lo_pw = a.pw + ol;
-    hi_pf = a.pf + oh; hi_tb = a.tb + oh; hi_pw = a.pw + oh;
+    lo_pf = a.tab + ((size_t)g * a.n_tp_f + c.row_lo) * 3 * n_rho; lo_tb = lo_pf + n_rho; lo_pw = lo_tb + n_rho;
+    hi_pf = a.tab + ((size_t)g * a.n_tp_f + c.row_hi) * 3 * n_rho; hi_tb = hi_pf + n_rho; hi_pw = hi_tb + n_rho;
   }
+  const uint32_t koff = (uint32_t)k * 8u;   // byte offset of this lane inside an output row
 
   for (int w = w0; w < w1; ++w) {
     const size_t cell = (size_t)w * a.G + g;
     const CellRec rec = s_rec[w - w0];
-    const bool empty = rec.xp99 < 0.0;
 
     const double rho = div_by(rec.load, den, rden);
     const bool ov = rho > rho_max;
     const double rc = ov ? rho_max : rho;
     // bracket: largest j with rho[j] <= rc, at most n_rho-2; start from the bucket index
-    int b = (int)(rc * a.bucket_scale);
-    b = b < 0 ? 0 : (b > a.n_bucket ? a.n_bucket : b);
+    // (rc <= rho_max keeps the bucket at or below n_bucket; a negative load maps to bucket 0)
+    const int b = (int)(fmax(rc, 0.0) * a.bucket_scale);
     int j = s_js[b];                                   // <= n_rho-2 by construction
     double r0, r1, ri;
     if (ONE_STEP) {
@@ -160,8 +152,8 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
       tb = omu * tb + c.u * tb_b;
       pw = omu * pw + c.u * pw_b;
     }
-    const double p_ttft = empty ? 0.0 : rec.xp99 * pf;
-    const double p_tbt = empty ? 0.0 : tb;
+    const double p_ttft = rec.xp99 * pf;        // an empty cell has xp99 == 0
+    const double p_tbt = tb * rec.nonempty;     // exact: times 1.0, or 0.0 for an empty cell
     const double e = (c.nd * pw) * a.window_s;
 
     uint32_t fl = fl_budget;
@@ -169,14 +161,15 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
     if (p_ttft > slo_ttft) fl |= DYN_F_TTFT;
     if (p_tbt > slo_tbt) fl |= DYN_F_TBT;
     if (!fl) fl = DYN_F_FEASIBLE;
-    if (empty) fl |= DYN_F_EMPTY;
+    if (rec.nonempty == 0.0) fl |= DYN_F_EMPTY;
 
     if (live) {
-      const size_t row = cell * (size_t)a.K;      // wave-uniform row start, lane offset k
-      (a.energy + row)[k] = e;
-      (a.p99_ttft + row)[k] = p_ttft;
-      (a.p99_tbt + row)[k] = p_tbt;
-      (a.flags + row)[k] = (uint8_t)fl;
+      const size_t row = cell * (size_t)a.K;      // wave-uniform row start + 32-bit lane offset
+      // streaming stores: the space is written once and is far larger than the caches
+      __builtin_nontemporal_store(e, (double*)((char*)(a.energy + row) + koff));
+      __builtin_nontemporal_store(p_ttft, (double*)((char*)(a.p99_ttft + row) + koff));
+      __builtin_nontemporal_store(p_tbt, (double*)((char*)(a.p99_tbt + row) + koff));
+      __builtin_nontemporal_store((uint8_t)fl, (a.flags + row) + (uint32_t)k);
     }
     if (SEL) {
       // Least cost among this wave's feasible configurations; costs are >= +0, so their bit
