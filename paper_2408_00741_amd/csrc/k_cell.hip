@@ -8,8 +8,11 @@
 // Cells of up to 2048 requests are held in registers (32 values per lane at most) and the
 // selection is a most-significant-bit-first search on the value: for every bit one
 // compare per register row and a scalar population count of the wave mask, no LDS and no
-// cross-lane traffic.  Larger cells are streamed again per 10-bit digit through a
-// per-wave LDS histogram (radix select).
+// cross-lane traffic.  The search interval is first narrowed to [lo, max], where lo is the
+// j-th largest of the 64 per-lane maxima (j = m - rank + 1; those maxima are elements of
+// the cell, so the j-th largest element cannot be below it): for a high percentile only a
+// few bits are left.  Larger cells are streamed from global memory by the whole block,
+// once for the sums and once per 10-bit digit, through an LDS histogram (radix select).
 #include "dyn_internal.h"
 
 namespace {
@@ -42,6 +45,16 @@ __device__ __forceinline__ uint32_t wave_or_u32(uint32_t x) {
   v |= dpp_mov<0x128>(v);
   return (uint32_t)(__builtin_amdgcn_readlane(v, 0) | __builtin_amdgcn_readlane(v, 16) |
                     __builtin_amdgcn_readlane(v, 32) | __builtin_amdgcn_readlane(v, 48));
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
+  x = max(x, (uint32_t)dpp_mov<0x121>((int)x));
+  x = max(x, (uint32_t)dpp_mov<0x122>((int)x));
+  x = max(x, (uint32_t)dpp_mov<0x124>((int)x));
+  x = max(x, (uint32_t)dpp_mov<0x128>((int)x));
+  const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
+  const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+  return max(max(a, b), max(c, d));
 }
 
 struct CellOut {
@@ -77,17 +90,33 @@ __device__ __forceinline__ CellOut cell_in_registers(const int32_t* __restrict__
   r.tin = ((int64_t)wave_sum_i32(hi_in) << 16) + (int64_t)wave_sum_i32(lo_in);
   r.tout = ((int64_t)wave_sum_i32(hi_out) << 16) + (int64_t)wave_sum_i32(lo_out);
   r.orv = wave_or_u32(orv);
-  // largest a with #{v < a} < rank, built from the top bit down
-  uint32_t ans = 0;
-  const int nb = 32 - __builtin_clz(r.orv | 1u);
+  // Answer = largest a with #{v < a} < rank.  It lies in [lo, top]: top = largest element,
+  // lo = 0, or for cells of several rows the j-th largest per-lane maximum, j = m - rank + 1.
+  uint32_t lo = 0, top = r.orv;
+  if (R >= 4) {
+    uint32_t lmax = 0;
+#pragma unroll
+    for (int i = 0; i < R; ++i) lmax = max(lmax, v[i] == 0xFFFFFFFFu ? 0u : v[i]);
+    top = wave_max_u32(lmax);
+    const int j = m - rank + 1;
+    if (j <= DYN_WAVE) {
+      const int nb = 32 - __builtin_clz(top | 1u);
+      for (int b = nb - 1; b >= 0; --b) {   // largest c with #{lane maxima >= c} >= j
+        const uint32_t cand = lo | (1u << b);
+        if (__popcll(__ballot(lmax >= cand)) >= j) lo = cand;
+      }
+    }
+  }
+  uint32_t d = 0;
+  const int nb = 32 - __builtin_clz((top - lo) | 1u);
   for (int b = nb - 1; b >= 0; --b) {
-    const uint32_t cand = ans | (1u << b);
+    const uint32_t cand = lo + (d | (1u << b));
     int below = 0;
 #pragma unroll
     for (int i = 0; i < R; ++i) below += __popcll(__ballot(v[i] < cand));
-    if (below < rank) ans = cand;
+    if (below < rank) d |= 1u << b;
   }
-  r.p99 = ans;
+  r.p99 = lo + d;
   return r;
 }
 
@@ -97,22 +126,45 @@ __device__ __forceinline__ int64_t wave_sum_i64(int64_t v) {
   return v;
 }
 
-// Streaming cell: any m.  hist = this wave's kHistBins counters in LDS.
-__device__ CellOut cell_streamed(const int32_t* __restrict__ in, const int32_t* __restrict__ out,
-                                 int64_t beg, int64_t m, int64_t rank, int lane, uint32_t* hist) {
+// Large cell, whole block: the 256 threads stream the cell from global memory once for the
+// sums and once per 10-bit digit of the selection (radix select through one LDS histogram).
+// Every thread returns the same result.  `hist` (kHistBins counters) and `xch` (16 words)
+// are LDS scratch; the caller guarantees nobody else uses them.
+__device__ CellOut cell_by_block(const int32_t* __restrict__ in, const int32_t* __restrict__ out, int64_t beg,
+                                 int64_t m, int64_t rank, uint32_t* hist, int64_t* xch) {
+  const int tid = threadIdx.x, lane = tid & (DYN_WAVE - 1), wave = tid / DYN_WAVE;
+  constexpr int nthr = kWavesPerBlock * DYN_WAVE;
   int64_t sin = 0, sout = 0;
   uint32_t orv = 0;
-  for (int64_t i = lane; i < m; i += DYN_WAVE) {
-    const int a = in[beg + i];
-    const int b = out[beg + i];
-    sin += a;
-    sout += b;
-    orv |= (uint32_t)a;
+  for (int64_t i0 = 0; i0 < m; i0 += 8 * nthr) {   // eight independent loads per array in flight
+    int a[8], b[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int64_t i = i0 + u * nthr + tid;
+      a[u] = i < m ? in[beg + i] : 0;
+      b[u] = i < m ? out[beg + i] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      sin += a[u];
+      sout += b[u];
+      orv |= (uint32_t)a[u];
+    }
   }
+  sin = wave_sum_i64(sin);
+  sout = wave_sum_i64(sout);
+  orv = wave_or_u32(orv);
+  __syncthreads();
+  if (lane == 0) { xch[wave * 3 + 0] = sin; xch[wave * 3 + 1] = sout; xch[wave * 3 + 2] = (int64_t)orv; }
+  __syncthreads();
   CellOut r;
-  r.tin = wave_sum_i64(sin);
-  r.tout = wave_sum_i64(sout);
-  r.orv = wave_or_u32(orv);
+  r.tin = r.tout = 0;
+  r.orv = 0;
+  for (int w = 0; w < kWavesPerBlock; ++w) {
+    r.tin += xch[w * 3 + 0];
+    r.tout += xch[w * 3 + 1];
+    r.orv |= (uint32_t)xch[w * 3 + 2];
+  }
 
   int hi_bit = 32 - __builtin_clz(r.orv | 1u);  // bits >= hi_bit of the answer are `prefix`
   uint32_t prefix = 0;
@@ -121,40 +173,46 @@ __device__ CellOut cell_streamed(const int32_t* __restrict__ in, const int32_t* 
     const int w = hi_bit < kHistBits ? hi_bit : kHistBits;
     const int shift = hi_bit - w;
     const uint32_t dmask = (1u << w) - 1u;
-    for (int b = lane; b < kHistBins; b += DYN_WAVE) hist[b] = 0;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    for (int64_t i = lane; i < m; i += DYN_WAVE) {
-      const uint32_t a = (uint32_t)in[beg + i];
-      const bool match = hi_bit >= 32 ? true : ((a >> hi_bit) == prefix);
-      if (match) __hip_atomic_fetch_add(&hist[(a >> shift) & dmask], 1u, __ATOMIC_RELAXED,
-                                        __HIP_MEMORY_SCOPE_WAVEFRONT);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    // lane l owns bins [16 l, 16 l + 16); find the bin where the running count reaches `need`
-    constexpr int per = kHistBins / DYN_WAVE;
-    uint32_t cnt[per];
-    int64_t mine = 0;
+    __syncthreads();
+    for (int b = tid; b < kHistBins; b += nthr) hist[b] = 0;
+    __syncthreads();
+    for (int64_t i0 = 0; i0 < m; i0 += 8 * nthr) {
+      uint32_t a[8];
 #pragma unroll
-    for (int q = 0; q < per; ++q) {
-      cnt[q] = hist[lane * per + q];
-      mine += cnt[q];
-    }
-    int64_t incl = mine;  // inclusive scan over lanes
+      for (int u = 0; u < 8; ++u) {
+        const int64_t i = i0 + u * nthr + tid;
+        a[u] = i < m ? (uint32_t)in[beg + i] : 0u;
+      }
 #pragma unroll
-    for (int d = 1; d < DYN_WAVE; d <<= 1) {
-      const int64_t up = __shfl_up(incl, d, DYN_WAVE);
-      if (lane >= d) incl += up;
+      for (int u = 0; u < 8; ++u) {
+        const int64_t i = i0 + u * nthr + tid;
+        const bool match = i < m && (hi_bit >= 32 ? true : ((a[u] >> hi_bit) == prefix));
+        if (match) atomicAdd(&hist[(a[u] >> shift) & dmask], 1u);
+      }
     }
-    const uint64_t reach = __ballot(incl >= need);
-    const int owner = __builtin_ctzll(reach);  // reach != 0 because need <= number of matches
-    // every lane searches its own bins; only the owner's answer is used
-    uint32_t digit = (uint32_t)(lane * per + per - 1);
-    int64_t below = 0;
-    {
+    __syncthreads();
+    if (wave == 0) {
+      // lane l owns bins [16 l, 16 l + 16); find the bin where the running count reaches `need`
+      constexpr int per = kHistBins / DYN_WAVE;
+      uint32_t cnt[per];
+      int64_t mine = 0;
+#pragma unroll
+      for (int q = 0; q < per; ++q) {
+        cnt[q] = hist[lane * per + q];
+        mine += cnt[q];
+      }
+      int64_t incl = mine;  // inclusive scan over lanes
+#pragma unroll
+      for (int d = 1; d < DYN_WAVE; d <<= 1) {
+        const int64_t up = __shfl_up(incl, d, DYN_WAVE);
+        if (lane >= d) incl += up;
+      }
+      const uint64_t reach = __ballot(incl >= need);
+      const int owner = reach ? __builtin_ctzll(reach) : DYN_WAVE - 1;  // reach != 0: need <= matches
       int64_t run = incl - mine;
       bool found = false;
+      uint32_t digit = (uint32_t)(lane * per + per - 1);
+      int64_t below = 0;
 #pragma unroll
       for (int q = 0; q < per; ++q) {
         const bool hit = !found && (run + cnt[q] >= need || q == per - 1);
@@ -165,71 +223,100 @@ __device__ CellOut cell_streamed(const int32_t* __restrict__ in, const int32_t* 
         }
         run += cnt[q];
       }
+      if (lane == owner) { xch[12] = (int64_t)digit; xch[13] = below; }
     }
-    digit = (uint32_t)__shfl((int)digit, owner, DYN_WAVE);
-    below = __shfl(below, owner, DYN_WAVE);
-    need -= below;
+    __syncthreads();
+    const uint32_t digit = (uint32_t)xch[12];
+    need -= xch[13];
     prefix = (prefix << w) | digit;
     hi_bit = shift;
-    __builtin_amdgcn_wave_barrier();
   }
+  __syncthreads();
   r.p99 = prefix;
   return r;
 }
 
-__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void cell_aggregate_kernel(
+__device__ __forceinline__ void write_cell(int64_t c, const CellOut& r, int64_t m, uint32_t bad, double window_s,
+                                           int64_t cells, int64_t* __restrict__ tin, int64_t* __restrict__ tout,
+                                           int32_t* __restrict__ in_p99, CellRec* __restrict__ rec,
+                                           uint8_t* __restrict__ cstat, WsHeader* __restrict__ header) {
+  tin[c] = r.tin;
+  tout[c] = r.tout;
+  in_p99[c] = (int32_t)r.p99;
+  CellRec cr;
+  cr.load = (double)(r.tin + r.tout) / window_s;
+  cr.xp99 = (double)(int32_t)r.p99;
+  cr.nonempty = m > 0 ? 1.0 : 0.0;
+  cr.pad = 0.0;
+  rec[c] = cr;
+  cstat[c] = (uint8_t)bad;       // every cell writes its own byte: nothing to clear beforehand
+  if (c == 0) {                  // single writer of the header
+    header->status = 0u;
+    header->kind = DYN_WS_KIND_CELLS;
+    header->cells = cells;
+  }
+}
+
+// Four consecutive cells per block, one wave each; cells beyond the register tiers are then
+// taken one after the other by the whole block.
+__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_waves_per_eu(5, 8))) void cell_aggregate_kernel(
     const int32_t* __restrict__ in, const int32_t* __restrict__ out,
     const int64_t* __restrict__ cell_off, int64_t n_req, int64_t cells, double window_s,
     int32_t pct_num, int32_t pct_den, int64_t* __restrict__ tin, int64_t* __restrict__ tout,
     int32_t* __restrict__ in_p99, CellRec* __restrict__ rec, uint8_t* __restrict__ cstat,
     WsHeader* __restrict__ header) {
-  __shared__ uint32_t hist_all[kWavesPerBlock][kHistBins];
+  __shared__ uint32_t s_hist[kHistBins];
+  __shared__ int64_t s_xch[16];
   const int lane = threadIdx.x & (DYN_WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
-  const int64_t c = (int64_t)blockIdx.x * kWavesPerBlock + wave;
-  if (c >= cells) return;
-  int64_t beg = cell_off[c], end = cell_off[c + 1];
-  uint32_t bad = 0;
-  if (beg < 0 || end < beg || end > n_req) {  // never read outside the trace
-    bad = DYN_WS_BAD_OFFSETS;
-    beg = end = 0;
+  const int64_t c0 = (int64_t)blockIdx.x * kWavesPerBlock;
+  // lane q of every wave holds offset q of the block's cells (kWavesPerBlock + 1 of them)
+  const int nc = (int)(cells - c0 < kWavesPerBlock ? cells - c0 : kWavesPerBlock);
+  const int64_t myoff = lane <= nc ? cell_off[c0 + lane] : 0;
+  uint32_t big_mask = 0;     // cells of this block left to the whole block (uniform over the block)
+#pragma unroll
+  for (int q = 0; q < kWavesPerBlock; ++q) {
+    const int64_t b = __shfl(myoff, q, DYN_WAVE), e = __shfl(myoff, q + 1, DYN_WAVE);
+    if (q < nc && b >= 0 && e >= b && e <= n_req && e - b > DYN_WAVE * kRegRowsMax) big_mask |= 1u << q;
   }
-  const int64_t m = end - beg;
-  CellOut r;
-  r.tin = r.tout = 0;
-  r.p99 = 0;
-  r.orv = 0;
-  if (m > 0) {
-    const int64_t rank = ((int64_t)pct_num * m + pct_den - 1) / pct_den;
-    if (m <= DYN_WAVE * kRegRowsMax) {
-      const int mi = (int)m, rk = (int)rank;
+  if (wave < nc && !((big_mask >> wave) & 1u)) {
+    const int64_t c = c0 + wave;
+    int64_t beg = __shfl(myoff, wave, DYN_WAVE), end = __shfl(myoff, wave + 1, DYN_WAVE);
+    uint32_t bad = 0;
+    if (beg < 0 || end < beg || end > n_req) {  // never read outside the trace
+      bad = DYN_WS_BAD_OFFSETS;
+      beg = end = 0;
+    }
+    const int mi = (int)(end - beg);
+    CellOut r;
+    r.tin = r.tout = 0;
+    r.p99 = 0;
+    r.orv = 0;
+    if (mi > 0) {
+      const int rk = (int)(((int64_t)pct_num * mi + pct_den - 1) / pct_den);
       if (mi <= 64 * 1) r = cell_in_registers<1>(in, out, beg, mi, rk, lane);
       else if (mi <= 64 * 2) r = cell_in_registers<2>(in, out, beg, mi, rk, lane);
+      else if (mi <= 64 * 3) r = cell_in_registers<3>(in, out, beg, mi, rk, lane);
       else if (mi <= 64 * 4) r = cell_in_registers<4>(in, out, beg, mi, rk, lane);
+      else if (mi <= 64 * 6) r = cell_in_registers<6>(in, out, beg, mi, rk, lane);
       else if (mi <= 64 * 8) r = cell_in_registers<8>(in, out, beg, mi, rk, lane);
+      else if (mi <= 64 * 12) r = cell_in_registers<12>(in, out, beg, mi, rk, lane);
       else if (mi <= 64 * 16) r = cell_in_registers<16>(in, out, beg, mi, rk, lane);
+      else if (mi <= 64 * 24) r = cell_in_registers<24>(in, out, beg, mi, rk, lane);
       else r = cell_in_registers<32>(in, out, beg, mi, rk, lane);
-    } else {
-      r = cell_streamed(in, out, beg, m, rank, lane, hist_all[wave]);
+      if (r.orv >> 31) bad |= DYN_WS_BAD_REQUEST;  // a negative token count
     }
-    if (r.orv >> 31) bad |= DYN_WS_BAD_REQUEST;  // a negative token count
+    if (lane == 0) write_cell(c, r, mi, bad, window_s, cells, tin, tout, in_p99, rec, cstat, header);
   }
-  if (lane == 0) {
-    tin[c] = r.tin;
-    tout[c] = r.tout;
-    in_p99[c] = (int32_t)r.p99;
-    CellRec cr;
-    cr.load = (double)(r.tin + r.tout) / window_s;
-    cr.xp99 = (double)(int32_t)r.p99;
-    cr.nonempty = m > 0 ? 1.0 : 0.0;
-    cr.pad = 0.0;
-    rec[c] = cr;
-    cstat[c] = (uint8_t)bad;       // every cell writes its own byte: nothing to clear beforehand
-    if (c == 0) {                  // single writer of the header
-      header->status = 0u;
-      header->kind = DYN_WS_KIND_CELLS;
-      header->cells = cells;
-    }
+  if (big_mask == 0) return;   // uniform over the block
+  for (int q = 0; q < kWavesPerBlock; ++q) {
+    if (!((big_mask >> q) & 1u)) continue;
+    const int64_t beg = __shfl(myoff, q, DYN_WAVE);
+    const int64_t m = __shfl(myoff, q + 1, DYN_WAVE) - beg;
+    const int64_t rank = ((int64_t)pct_num * m + pct_den - 1) / pct_den;
+    const CellOut r = cell_by_block(in, out, beg, m, rank, s_hist, s_xch);
+    const uint32_t bad = (r.orv >> 31) ? DYN_WS_BAD_REQUEST : 0u;
+    if (threadIdx.x == 0) write_cell(c0 + q, r, m, bad, window_s, cells, tin, tout, in_p99, rec, cstat, header);
   }
 }
 

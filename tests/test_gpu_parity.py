@@ -265,7 +265,7 @@ def test_worked_example_on_gpu(dyn, golden_dir):
 
 
 @pytest.mark.parametrize("m", [1, 2, 63, 64, 65, 99, 100, 101, 128, 129, 200, 511, 513, 1024, 1025, 2047, 2048,
-                               2049, 4097, 70_001])
+                               2049, 4095, 4096, 4097, 70_001])
 def test_rank_select_cell_sizes(dyn, m):
     """Every register tier, the tier boundaries and the streamed path; distinct and duplicate values."""
     prof, cfg = _worked()
@@ -300,6 +300,23 @@ def test_ragged_and_empty_cells(dyn):
     rep = assert_parity(w, g, o)
     assert rep["bit_exact"] and rep["sel_mismatch"] == 0
     assert ((g["flags"] & dyn.DYN_F_EMPTY) != 0).all(axis=1).tolist() == (sizes == 0).tolist()
+
+
+def test_mixed_small_and_large_cells(dyn):
+    """Cells from empty to several thousand requests side by side: staged runs that end at a large
+    cell, cells between the register tiers and the staging capacity, cells handled by a whole block."""
+    prof, cfg = _worked()
+    rng = np.random.default_rng(12)
+    for hi, n_cells in ((6000, 70), (1200, 150), (40, 333)):
+        sizes = rng.integers(0, hi, n_cells)
+        sizes[rng.integers(0, n_cells, 5)] = 0
+        off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+        n = int(off[-1])
+        x = rng.integers(1, 8193, n); y = rng.integers(1, 8193, n)
+        w, st, g = _single(dyn, prof, cfg, x, y, 100, 50, 1000.0, n_window=sizes.size, off=off, lam=0.1)
+        assert g["status"] == 0
+        rep = assert_parity(w, g, ora_eval(w, st))
+        assert rep["bit_exact"] and rep["sel_mismatch"] == 0
 
 
 def test_off_grid_frequencies_single_frequency_and_odd_k(dyn):
