@@ -57,11 +57,36 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
   return max(max(a, b), max(c, d));
 }
 
+__device__ __forceinline__ int64_t readlane_i64(int64_t x, int lane) {   // lane must be wave-uniform
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, lane);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)x >> 32), lane);
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 struct CellOut {
   int64_t tin, tout;
   uint32_t p99;
   uint32_t orv;
 };
+
+// Exact token sums of a register-sized cell the slow way (16-bit halves keep every partial
+// sum inside 32 bits: at most 32 values per lane, 2048 per wave); only needed when a token
+// count of 2^20 or more makes plain 32-bit sums unsafe.
+__device__ __forceinline__ void cell_sums_wide(const int32_t* __restrict__ in, const int32_t* __restrict__ out,
+                                               int64_t beg, int m, int lane, int64_t* tin, int64_t* tout) {
+  int lo_in = 0, hi_in = 0, lo_out = 0, hi_out = 0;
+#pragma unroll 1
+  for (int idx = lane; idx < m; idx += DYN_WAVE) {
+    const int a = in[beg + idx];
+    const int b = out[beg + idx];
+    lo_in += a & 0xFFFF;
+    hi_in += a >> 16;
+    lo_out += b & 0xFFFF;
+    hi_out += b >> 16;
+  }
+  *tin = ((int64_t)wave_sum_i32(hi_in) << 16) + (int64_t)wave_sum_i32(lo_in);
+  *tout = ((int64_t)wave_sum_i32(hi_out) << 16) + (int64_t)wave_sum_i32(lo_out);
+}
 
 // Register-resident cell: m <= 64*R requests.
 template <int R>
@@ -69,35 +94,29 @@ __device__ __forceinline__ CellOut cell_in_registers(const int32_t* __restrict__
                                                      const int32_t* __restrict__ out, int64_t beg,
                                                      int m, int rank, int lane) {
   uint32_t v[R];
-  int lo_in = 0, hi_in = 0, lo_out = 0, hi_out = 0;
-  uint32_t orv = 0;
+  uint32_t s_in = 0, s_out = 0, or_all = 0, lmax = 0;
 #pragma unroll
   for (int i = 0; i < R; ++i) {
     const int idx = i * DYN_WAVE + lane;
     const bool ok = idx < m;
-    const int a = ok ? in[beg + idx] : 0;
-    const int b = ok ? out[beg + idx] : 0;
-    v[i] = ok ? (uint32_t)a : 0xFFFFFFFFu;  // padding is never below a candidate value
-    orv |= (uint32_t)a;
-    // 16-bit halves keep every partial sum inside 32 bits: at most 32 values per lane,
-    // 2048 per wave
-    lo_in += a & 0xFFFF;
-    hi_in += a >> 16;
-    lo_out += b & 0xFFFF;
-    hi_out += b >> 16;
+    const uint32_t a = ok ? (uint32_t)in[beg + idx] : 0u;
+    const uint32_t b = ok ? (uint32_t)out[beg + idx] : 0u;
+    v[i] = ok ? a : 0xFFFFFFFFu;  // padding is never below a candidate value
+    or_all |= a | b;
+    lmax = max(lmax, a);
+    s_in += a;
+    s_out += b;
   }
   CellOut r;
-  r.tin = ((int64_t)wave_sum_i32(hi_in) << 16) + (int64_t)wave_sum_i32(lo_in);
-  r.tout = ((int64_t)wave_sum_i32(hi_out) << 16) + (int64_t)wave_sum_i32(lo_out);
-  r.orv = wave_or_u32(orv);
+  r.orv = wave_or_u32(or_all);
+  // at most 2048 values: if all are below 2^20 the 32-bit sums are exact (else redone below)
+  r.tin = (int64_t)(uint32_t)wave_sum_i32((int)s_in);
+  r.tout = (int64_t)(uint32_t)wave_sum_i32((int)s_out);
   // Answer = largest a with #{v < a} < rank.  It lies in [lo, top]: top = largest element,
   // lo = 0, or for cells of several rows the j-th largest per-lane maximum, j = m - rank + 1.
-  uint32_t lo = 0, top = r.orv;
+  const uint32_t top = wave_max_u32(lmax);
+  uint32_t lo = 0;
   if (R >= 4) {
-    uint32_t lmax = 0;
-#pragma unroll
-    for (int i = 0; i < R; ++i) lmax = max(lmax, v[i] == 0xFFFFFFFFu ? 0u : v[i]);
-    top = wave_max_u32(lmax);
     const int j = m - rank + 1;
     if (j <= DYN_WAVE) {
       const int nb = 32 - __builtin_clz(top | 1u);
@@ -117,6 +136,7 @@ __device__ __forceinline__ CellOut cell_in_registers(const int32_t* __restrict__
     if (below < rank) d |= 1u << b;
   }
   r.p99 = lo + d;
+  if (r.orv >= (1u << 20)) cell_sums_wide(in, out, beg, m, lane, &r.tin, &r.tout);
   return r;
 }
 
@@ -237,6 +257,7 @@ __device__ CellOut cell_by_block(const int32_t* __restrict__ in, const int32_t* 
 }
 
 __device__ __forceinline__ void write_cell(int64_t c, const CellOut& r, int64_t m, uint32_t bad, double window_s,
+                                           double r_window,
                                            int64_t cells, int64_t* __restrict__ tin, int64_t* __restrict__ tout,
                                            int32_t* __restrict__ in_p99, CellRec* __restrict__ rec,
                                            uint8_t* __restrict__ cstat, WsHeader* __restrict__ header) {
@@ -244,7 +265,12 @@ __device__ __forceinline__ void write_cell(int64_t c, const CellOut& r, int64_t 
   tout[c] = r.tout;
   in_p99[c] = (int32_t)r.p99;
   CellRec cr;
-  cr.load = (double)(r.tin + r.tout) / window_s;
+  {  // tokens / window_s, correctly rounded, from r_window = RN(1 / window_s)
+    const double tok = (double)(r.tin + r.tout);
+    const double q = tok * r_window;
+    const double e = __builtin_fma(-window_s, q, tok);
+    cr.load = __builtin_fma(e, r_window, q);
+  }
   cr.xp99 = (double)(int32_t)r.p99;
   cr.nonempty = m > 0 ? 1.0 : 0.0;
   cr.pad = 0.0;
@@ -261,7 +287,7 @@ __device__ __forceinline__ void write_cell(int64_t c, const CellOut& r, int64_t 
 // taken one after the other by the whole block.
 __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_waves_per_eu(5, 8))) void cell_aggregate_kernel(
     const int32_t* __restrict__ in, const int32_t* __restrict__ out,
-    const int64_t* __restrict__ cell_off, int64_t n_req, int64_t cells, double window_s,
+    const int64_t* __restrict__ cell_off, int64_t n_req, int64_t cells, double window_s, double r_window,
     int32_t pct_num, int32_t pct_den, int64_t* __restrict__ tin, int64_t* __restrict__ tout,
     int32_t* __restrict__ in_p99, CellRec* __restrict__ rec, uint8_t* __restrict__ cstat,
     WsHeader* __restrict__ header) {
@@ -273,15 +299,13 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
   // lane q of every wave holds offset q of the block's cells (kWavesPerBlock + 1 of them)
   const int nc = (int)(cells - c0 < kWavesPerBlock ? cells - c0 : kWavesPerBlock);
   const int64_t myoff = lane <= nc ? cell_off[c0 + lane] : 0;
-  uint32_t big_mask = 0;     // cells of this block left to the whole block (uniform over the block)
-#pragma unroll
-  for (int q = 0; q < kWavesPerBlock; ++q) {
-    const int64_t b = __shfl(myoff, q, DYN_WAVE), e = __shfl(myoff, q + 1, DYN_WAVE);
-    if (q < nc && b >= 0 && e >= b && e <= n_req && e - b > DYN_WAVE * kRegRowsMax) big_mask |= 1u << q;
-  }
+  const int64_t nxoff = __shfl_down(myoff, 1, DYN_WAVE);
+  // cells of this block left to the whole block (uniform over the block)
+  const uint32_t big_mask = (uint32_t)__ballot(lane < nc && myoff >= 0 && nxoff >= myoff && nxoff <= n_req &&
+                                               nxoff - myoff > DYN_WAVE * kRegRowsMax);
   if (wave < nc && !((big_mask >> wave) & 1u)) {
     const int64_t c = c0 + wave;
-    int64_t beg = __shfl(myoff, wave, DYN_WAVE), end = __shfl(myoff, wave + 1, DYN_WAVE);
+    int64_t beg = readlane_i64(myoff, wave), end = readlane_i64(nxoff, wave);
     uint32_t bad = 0;
     if (beg < 0 || end < beg || end > n_req) {  // never read outside the trace
       bad = DYN_WS_BAD_OFFSETS;
@@ -306,17 +330,17 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
       else r = cell_in_registers<32>(in, out, beg, mi, rk, lane);
       if (r.orv >> 31) bad |= DYN_WS_BAD_REQUEST;  // a negative token count
     }
-    if (lane == 0) write_cell(c, r, mi, bad, window_s, cells, tin, tout, in_p99, rec, cstat, header);
+    if (lane == 0) write_cell(c, r, mi, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
   }
   if (big_mask == 0) return;   // uniform over the block
   for (int q = 0; q < kWavesPerBlock; ++q) {
     if (!((big_mask >> q) & 1u)) continue;
-    const int64_t beg = __shfl(myoff, q, DYN_WAVE);
-    const int64_t m = __shfl(myoff, q + 1, DYN_WAVE) - beg;
+    const int64_t beg = readlane_i64(myoff, q);
+    const int64_t m = readlane_i64(nxoff, q) - beg;
     const int64_t rank = ((int64_t)pct_num * m + pct_den - 1) / pct_den;
     const CellOut r = cell_by_block(in, out, beg, m, rank, s_hist, s_xch);
     const uint32_t bad = (r.orv >> 31) ? DYN_WS_BAD_REQUEST : 0u;
-    if (threadIdx.x == 0) write_cell(c0 + q, r, m, bad, window_s, cells, tin, tout, in_p99, rec, cstat, header);
+    if (threadIdx.x == 0) write_cell(c0 + q, r, m, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
   }
 }
 
@@ -330,7 +354,7 @@ hipError_t dyn_launch_cell_aggregate(const int32_t* in_tok, const int32_t* out_t
   const int64_t blocks = (cells + kWavesPerBlock - 1) / kWavesPerBlock;
   DynTimed timed(DYN_K_CELL, s);
   hipLaunchKernelGGL(cell_aggregate_kernel, dim3((unsigned)blocks), dim3(kWavesPerBlock * DYN_WAVE),
-                     0, s, in_tok, out_tok, cell_off, n_req, cells, window_s, pct_num, pct_den, tin,
+                     0, s, in_tok, out_tok, cell_off, n_req, cells, window_s, 1.0 / window_s, pct_num, pct_den, tin,
                      tout, in_p99, rec, cstat, header);
   return hipGetLastError();
 }
