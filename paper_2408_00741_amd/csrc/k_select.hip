@@ -80,18 +80,32 @@ __global__ void window_totals_kernel(const int32_t* __restrict__ sel, const doub
 // strict "<" scan keeps the lowest index among equal costs.  One block per window when the
 // classes of a window fit a block: the class results go through LDS and thread 0 adds them
 // in class order.
+__device__ __forceinline__ void scan_partials(const SelPart* __restrict__ p, int n, double* bc, double* be, int32_t* bk) {
+  double c = __builtin_inf(), e = __builtin_inf();
+  int32_t k = -1;
+  int i = 0;
+  for (; i + 4 <= n; i += 4) {   // four independent loads in flight, compared in candidate order
+    const SelPart q0 = p[i], q1 = p[i + 1], q2 = p[i + 2], q3 = p[i + 3];
+    if (q0.k >= 0 && (k < 0 || q0.cost < c)) { c = q0.cost; e = q0.energy; k = q0.k; }
+    if (q1.k >= 0 && (k < 0 || q1.cost < c)) { c = q1.cost; e = q1.energy; k = q1.k; }
+    if (q2.k >= 0 && (k < 0 || q2.cost < c)) { c = q2.cost; e = q2.energy; k = q2.k; }
+    if (q3.k >= 0 && (k < 0 || q3.cost < c)) { c = q3.cost; e = q3.energy; k = q3.k; }
+  }
+  for (; i < n; ++i) {
+    const SelPart q = p[i];
+    if (q.k >= 0 && (k < 0 || q.cost < c)) { c = q.cost; e = q.energy; k = q.k; }
+  }
+  *bc = c; *be = e; *bk = k;
+}
+
 __global__ __launch_bounds__(256) void finish_kernel(FinishArgs a) {
   extern __shared__ double s_e[];          // [G] selected energy, NaN marks "no feasible configuration"
   const int w = blockIdx.x;
   for (int g = threadIdx.x; g < a.G; g += blockDim.x) {
     const size_t cell = (size_t)w * a.G + g;
-    const SelPart* p = a.part + cell * (size_t)a.n_wslot;
-    double bc = __builtin_inf(), be = __builtin_inf();
-    int32_t bk = -1;
-    for (int i = 0; i < a.n_used; ++i) {
-      const SelPart q = p[i];
-      if (q.k >= 0 && (bk < 0 || q.cost < bc)) { bc = q.cost; be = q.energy; bk = q.k; }
-    }
+    double bc, be;
+    int32_t bk;
+    scan_partials(a.part + cell * (size_t)a.n_wslot, a.n_used, &bc, &be, &bk);
     a.sel[cell] = bk;
     a.sel_energy[cell] = be;
     a.sel_cost[cell] = bc;
@@ -101,7 +115,17 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishArgs a) {
   if (threadIdx.x == 0) {
     double e = 0.0;
     int32_t ninf = 0;
-    for (int g = 0; g < a.G; ++g) {
+    int g = 0;
+    for (; g + 8 <= a.G; g += 8) {         // operands first, then the additions in class order
+      double v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] = s_e[g + q];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        if (v[q] == v[q]) e += v[q]; else ++ninf;
+      }
+    }
+    for (; g < a.G; ++g) {
       const double v = s_e[g];
       if (v == v) e += v; else ++ninf;
     }
@@ -114,13 +138,9 @@ __global__ __launch_bounds__(256) void finish_cells_kernel(FinishArgs a) {   // 
   const int64_t cells = (int64_t)a.n_window * a.G;
   const int64_t cell = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (cell >= cells) return;
-  const SelPart* p = a.part + (size_t)cell * a.n_wslot;
-  double bc = __builtin_inf(), be = __builtin_inf();
-  int32_t bk = -1;
-  for (int i = 0; i < a.n_used; ++i) {
-    const SelPart q = p[i];
-    if (q.k >= 0 && (bk < 0 || q.cost < bc)) { bc = q.cost; be = q.energy; bk = q.k; }
-  }
+  double bc, be;
+  int32_t bk;
+  scan_partials(a.part + (size_t)cell * a.n_wslot, a.n_used, &bc, &be, &bk);
   a.sel[cell] = bk;
   a.sel_energy[cell] = be;
   a.sel_cost[cell] = bc;
