@@ -461,6 +461,71 @@ def test_full_size_day_trace_sampled_cells(dyn):
     assert ((g["flags"] & dyn.DYN_F_EMPTY) != 0).all(axis=1).tolist() == (m == 0).tolist()
 
 
+@pytest.mark.parametrize("idx", [3, 4])
+def test_full_size_week_traces_sampled_cells(dyn, idx):
+    """The one-week workloads at full size (5*10^7 requests x 1152 configurations; 10^8 requests, four models,
+    2048 configurations with the idle-cost term) through ingest and the fused entry point; a sample of cells is
+    checked element by element against the oracle, the rest through properties computed on the device."""
+    w = make(SPECS[idx])
+    tr = w["trace"]
+    G, NW, K = w["n_class"], w["n_window"], w["configs"]["n_inst"].size
+    cells = G * NW
+    ins, outs, off, ws_i = gpu_ingest(dyn, w)
+    assert dyn.dyn_workspace_status(ws_i) == 0
+    del ws_i
+    off_h = off.cpu().numpy()
+    assert off_h[0] == 0 and off_h[-1] == tr["t_s"].size and (np.diff(off_h) >= 0).all()
+    prof = dyn.dyn_profile_load(w["profile"])
+    plan = dyn.Plan(w["configs"], w["slos"], w["pct"], None, w["idle_cost_weight"])
+    space, sel, ws = dyn.dyn_eval_select(prof, ins, outs, off, NW, w["window_s"], plan)
+    assert dyn.dyn_workspace_status(ws) == 0
+    tin, tout, p99 = dyn.dyn_cell_stats(ws, NW, G)
+    torch.cuda.synchronize()
+    assert int(tin.sum()) == int(tr["in_tok"].astype(np.int64).sum())
+    assert int(tout.sum()) == int(tr["out_tok"].astype(np.int64).sum())
+    m = np.diff(off_h)
+    rng = np.random.default_rng(idx)
+    ids = np.unique(np.concatenate([[0, cells - 1, int(np.argmax(m))], np.nonzero(m == 0)[0][:4],
+                                    np.nonzero(m > 4096)[0][:3], rng.integers(0, cells, 24)])).astype(np.int64)
+    # the sampled cells' requests, re-based so that the oracle sees a small trace
+    ins_h, outs_h = ins.cpu().numpy(), outs.cpu().numpy()
+    sub_in = np.concatenate([ins_h[off_h[c]:off_h[c + 1]] for c in ids]) if ids.size else np.zeros(0, np.int32)
+    sub_out = np.concatenate([outs_h[off_h[c]:off_h[c + 1]] for c in ids])
+    # one pseudo-window per sampled cell and class: cell j of the sub-trace sits at (window j, class g_j)
+    sub_off = np.zeros(ids.size * G + 1, np.int64)
+    pos = 0
+    for j, c in enumerate(ids):
+        g = int(c % G)
+        sub_off[j * G + g] = pos
+        pos += int(m[c])
+        sub_off[j * G + g + 1:] = pos
+    st = {"in_tok": sub_in, "out_tok": sub_out, "cell_off": sub_off}
+    o = oracle.evaluate(w["profile"], st, ids.size, w["window_s"], w["configs"], w["slos"], w["pct"], None,
+                        w["idle_cost_weight"], cell_ids=np.arange(ids.size) * G + (ids % G))
+    idt = torch.from_numpy(ids).cuda()
+    g_ = {k: v.index_select(0, idt).cpu().numpy() for k, v in space.items()}
+    g_.update({k: sel[k].index_select(0, idt).cpu().numpy() for k in ("sel", "sel_energy_j", "sel_cost")})
+    g_.update(tin=tin.index_select(0, idt).cpu().numpy(), tout=tout.index_select(0, idt).cpu().numpy(),
+              in_p99=p99.index_select(0, idt).cpu().numpy())
+    rep = assert_parity(w, g_, o, check_windows=False)
+    print(f"workload {idx} full size:", rep, "cells sampled", ids.size)
+    assert rep["bit_exact"] and rep["sel_mismatch"] == 0
+    # properties over every cell, computed on the device
+    s_ = sel["sel"].long()
+    has = s_ >= 0
+    rows = torch.nonzero(has).squeeze(1)
+    picked_fl = space["flags"][rows, s_[rows]]
+    assert bool(((picked_fl & 1) == 1).all())                                   # infeasible is never selected
+    assert bool((space["energy_j"][rows, s_[rows]] == sel["sel_energy_j"][rows]).all())
+    assert bool(((space["flags"] & 1).any(dim=1) == has).all())
+    empty = torch.from_numpy(m == 0).cuda()
+    assert bool((((space["flags"] & 32) != 0).all(dim=1) == empty).all())
+    we = torch.where(has, sel["sel_energy_j"], torch.zeros_like(sel["sel_energy_j"])).view(NW, G).sum(dim=1)
+    assert bool(((sel["window_energy_j"] - we).abs() <= 1e-12 * we).all())
+    assert bool((sel["window_infeasible"] == (~has).view(NW, G).sum(dim=1).int()).all())
+    prof.free()
+
+
 def test_ingest_full_size_windows_against_oracle(dyn):
     """First and last windows of the one-day trace through the oracle's own ingestion."""
     w = make(SPECS[2])
