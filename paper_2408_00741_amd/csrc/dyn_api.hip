@@ -115,7 +115,7 @@ int prepare_configs(dyn_profile* p, const dyn_config* cfg, int32_t K, hipStream_
     const int wa = (K + cand[a] - 1) / cand[a] * cand[a] - K, wb = (K + cand[b] - 1) / cand[b] * cand[b] - K;
     return wa < wb;
   });
-  const size_t lds_tail = dyn_space_lds_tail(p->n_rho, p->n_bucket);
+  const size_t lds_tail = dyn_space_lds_tail(p->n_rho, p->n_bucket, DYN_MAX_WIN_PER_BLOCK);
   std::vector<int32_t> rows;
   int tile = cand[order[0]], n_tile = (K + tile - 1) / tile, n_slot = 0;
   bool fits = false;

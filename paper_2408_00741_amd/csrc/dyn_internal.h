@@ -117,7 +117,7 @@ struct SpaceArgs {
   const double* pw0; double idle_w; SelPart* part; int32_t n_wslot;
 };
 hipError_t dyn_launch_space(const SpaceArgs& a, hipStream_t s);
-size_t dyn_space_lds_tail(int32_t n_rho, int32_t n_bucket);   // LDS bytes besides the table rows
+size_t dyn_space_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t win_per_block);   // LDS bytes besides the table rows
 
 struct FinishArgs {   // reduces the partial records of every cell, then the window totals
   const SelPart* part; int32_t n_wslot; int32_t n_used; int32_t n_window, G;

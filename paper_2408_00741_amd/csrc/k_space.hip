@@ -45,7 +45,7 @@ __device__ __forceinline__ double div_by(double a, double b, double rb) {
 }
 
 // LDS: [table rows n_slot*3*n_rho] [padded load grid n_rho+2] [padded reciprocal spacings n_rho+1]
-//      [cell records win_per_block] [bucket index n_bucket+1 (int)]
+//      [cell records win_per_block] [bucket index n_bucket+1 (16-bit)]
 template <bool LDS, bool SEL, bool ONE_STEP>
 __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
   extern __shared__ double smem[];
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
   double* s_rgp = smem + (LDS ? (size_t)a.n_slot * 3 * n_rho : 0);   // s_rgp[i+1] = rho[i]; -inf, +inf pads
   double* s_rinv = s_rgp + (n_rho + 2);                              // s_rinv[i+1] = 1/(rho[i+1]-rho[i]); 0 pads
   CellRec* s_rec = (CellRec*)(s_rinv + (n_rho + 1));                 // [win_per_block]
-  int32_t* s_js = (int32_t*)(s_rec + a.win_per_block);               // [n_bucket + 1]
+  uint16_t* s_js = (uint16_t*)(s_rec + a.win_per_block);             // [n_bucket + 1]
 
   const int w0 = chunk * a.win_per_block;
   const int w1 = min(w0 + a.win_per_block, a.n_window);
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void space_kernel(SpaceArgs a) {
     }
   }
   for (int i = threadIdx.x; i < 2 * n_rho + 3; i += blockDim.x) s_rgp[i] = a.gridpack[i];
-  for (int i = threadIdx.x; i <= a.n_bucket; i += blockDim.x) s_js[i] = a.jstart[i];
+  for (int i = threadIdx.x; i <= a.n_bucket; i += blockDim.x) s_js[i] = (uint16_t)a.jstart[i];
   // the cells of this block's run of windows (load, P99 input length)
   for (int i = threadIdx.x; i < w1 - w0; i += blockDim.x) s_rec[i] = a.rec[(size_t)(w0 + i) * a.G + g];
   __syncthreads();
@@ -207,9 +207,9 @@ void launch_one_step(const SpaceArgs& a, dim3 grid, dim3 block, size_t lds, hipS
 
 }  // namespace
 
-size_t dyn_space_lds_tail(int32_t n_rho, int32_t n_bucket) {
-  return (size_t)(2 * n_rho + 3) * sizeof(double) + (size_t)DYN_MAX_WIN_PER_BLOCK * sizeof(CellRec) +
-         ((size_t)n_bucket + 1) * sizeof(int32_t);
+size_t dyn_space_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t win_per_block) {
+  return (size_t)(2 * n_rho + 3) * sizeof(double) + (size_t)win_per_block * sizeof(CellRec) +
+         ((size_t)n_bucket + 1) * sizeof(uint16_t);
 }
 
 hipError_t dyn_launch_space(const SpaceArgs& a, hipStream_t s) {
@@ -217,7 +217,7 @@ hipError_t dyn_launch_space(const SpaceArgs& a, hipStream_t s) {
   const size_t blocks = (size_t)n_chunk * a.G * a.n_tile;
   const size_t lds_tab = (size_t)a.n_slot * 3 * a.n_rho * sizeof(double);
   DynTimed timed(DYN_K_SPACE, s);
-  const size_t lds = (a.n_slot > 0 ? lds_tab : 0) + dyn_space_lds_tail(a.n_rho, a.n_bucket);  // host keeps this <= 64 KB
+  const size_t lds = (a.n_slot > 0 ? lds_tab : 0) + dyn_space_lds_tail(a.n_rho, a.n_bucket, a.win_per_block);  // host keeps this <= 64 KB
   const dim3 grid((unsigned)blocks), block(a.tile);
   if (a.n_slot > 0) {
     if (a.part) launch_one_step<true, true>(a, grid, block, lds, s);
