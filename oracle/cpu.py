@@ -105,6 +105,42 @@ def evaluate(profile: Dict[str, np.ndarray], sorted_trace: Dict[str, np.ndarray]
     return r
 
 
+def evaluate_ticks(profile: Dict[str, np.ndarray], fine_trace: Dict[str, np.ndarray], n_window: int, n_tick: int,
+                   tick_s: float, configs: Dict[str, np.ndarray], slos: Dict[str, np.ndarray], pct=(99, 100),
+                   gpu_budget: Optional[np.ndarray] = None, idle_cost_weight: float = 0.0) -> Dict[str, np.ndarray]:
+    """Tick-level evaluation; `fine_trace` is sorted by (w*n_tick + tick)*G + class."""
+    lib = _load()
+    lib.dynoracle_eval_ticks.restype = C.c_int
+    tp = _c(profile["tp"], np.int32); fg = _c(profile["f_mhz"], np.float64)
+    rg = _c(profile["rho"], np.float64)
+    PF = _c(profile["prefill_ms_per_tok"], np.float64); TB = _c(profile["tbt_ms"], np.float64)
+    PW = _c(profile["power_w"], np.float64); ML = _c(profile["max_load_tps"], np.float64)
+    G = PF.shape[0]
+    ins = _c(fine_trace["in_tok"], np.int32); outs = _c(fine_trace["out_tok"], np.int32)
+    off = _c(fine_trace["cell_off"], np.int64)
+    assert off.size == n_window * n_tick * G + 1
+    cn = _c(configs["n_inst"], np.int32); ct = _c(configs["tp_index"], np.int32)
+    cf = _c(configs["f_mhz"], np.float64)
+    K = cn.size
+    st = _c(slos["slo_ttft_ms"], np.float64); sb = _c(slos["slo_tbt_ms"], np.float64)
+    bud = None if gpu_budget is None else _c(gpu_budget, np.int32)
+    cells = n_window * G
+    r = {"energy_j": np.empty((cells, K)), "p99_ttft_ms": np.empty((cells, K)), "p99_tbt_ms": np.empty((cells, K)),
+         "flags": np.empty((cells, K), np.uint8), "cost": np.empty((cells, K)), "m": np.empty(cells, np.int64),
+         "sel": np.empty(cells, np.int32), "sel_energy_j": np.empty(cells), "sel_cost": np.empty(cells)}
+    rc = lib.dynoracle_eval_ticks(
+        C.c_int32(G), C.c_int32(tp.size), _ptr(tp), C.c_int32(fg.size), _ptr(fg), C.c_int32(rg.size), _ptr(rg),
+        _ptr(PF), _ptr(TB), _ptr(PW), _ptr(ML),
+        C.c_int64(ins.size), C.c_int32(n_window), C.c_int32(n_tick), C.c_double(tick_s), _ptr(ins), _ptr(outs),
+        _ptr(off), C.c_int32(K), _ptr(cn), _ptr(ct), _ptr(cf), _ptr(st), _ptr(sb), C.c_int32(pct[0]),
+        C.c_int32(pct[1]), _ptr(bud), C.c_double(idle_cost_weight),
+        _ptr(r["energy_j"]), _ptr(r["p99_ttft_ms"]), _ptr(r["p99_tbt_ms"]), _ptr(r["flags"]), _ptr(r["cost"]),
+        _ptr(r["m"]), _ptr(r["sel"]), _ptr(r["sel_energy_j"]), _ptr(r["sel_cost"]))
+    if rc != 0:
+        raise ValueError(f"dynoracle_eval_ticks failed: {rc}")
+    return r
+
+
 def window_totals(sel: np.ndarray, sel_energy_j: np.ndarray, n_window: int, n_class: int):
     lib = _load()
     s = _c(sel, np.int32); e = _c(sel_energy_j, np.float64)

@@ -280,6 +280,137 @@ int dynoracle_eval(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f, cons
   return ORC_OK;
 }
 
+// Tick-level load inside a window (the instance manager re-tunes the frequency every few
+// seconds under the current load, Section IV-B "Scale-up/down"; the paper's large-scale
+// results come from a discrete-time simulator, Section V): every window is split into
+// n_tick ticks of tick_s seconds, each request is served under the load of its own tick.
+// Reading: the trace is sorted by fine cell = (w*n_tick + tick)*G + class (ticks are
+// sub-windows: tick index = floor(t / tick_s)); per tick the class's load is its tokens /
+// tick_s and the profile lookup is the one of dynoracle_eval; a request's TTFT is its
+// input length x the prefill ms/token of its tick, its TBT the TBT of its tick; the
+// window's energy is the sum over ticks (in tick order) of n x power(tick) x tick_s; the
+// overload flag is raised if any tick exceeds the profiled load range; the idle-cost term
+// uses the window length n_tick x tick_s.  With n_tick == 1 every output equals
+// dynoracle_eval's.  Outputs are indexed by coarse cell w*G + class (all of them).
+int dynoracle_eval_ticks(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f, const double* fg,
+                         int32_t n_rho, const double* rg, const double* PF, const double* TB,
+                         const double* PW, const double* ML,
+                         int64_t n_req, int32_t n_window, int32_t n_tick, double tick_s,
+                         const int32_t* in_tok, const int32_t* out_tok, const int64_t* fine_off,
+                         int32_t K, const int32_t* cfg_n, const int32_t* cfg_tp_index, const double* cfg_f,
+                         const double* slo_ttft, const double* slo_tbt, int32_t pct_num, int32_t pct_den,
+                         const int32_t* gpu_budget, double idle_cost_weight,
+                         double* energy_j, double* p99_ttft_ms, double* p99_tbt_ms, uint8_t* flags,
+                         double* cost_out, int64_t* m_out, int32_t* sel_out, double* sel_energy_j,
+                         double* sel_cost) {
+  if (!tp || !fg || !rg || !PF || !TB || !PW || !ML || !fine_off || !cfg_n || !cfg_tp_index || !cfg_f ||
+      !slo_ttft || !slo_tbt)
+    return ORC_E_NULL;
+  if (n_req > 0 && (!in_tok || !out_tok)) return ORC_E_NULL;
+  if (G < 1 || n_tp < 1 || n_f < 1 || n_rho < 2 || K < 1 || n_window < 1 || n_tick < 1) return ORC_E_SHAPE;
+  if (!(tick_s > 0.0) || pct_num < 1 || pct_den < 1 || pct_num > pct_den) return ORC_E_RANGE;
+  if (!increasing(fg, n_f) || !increasing(rg, n_rho)) return ORC_E_ORDER;
+  if (rg[0] != 0.0) return ORC_E_RANGE;
+  for (int k = 0; k < K; ++k) {
+    if (cfg_n[k] < 1 || cfg_tp_index[k] < 0 || cfg_tp_index[k] >= n_tp) return ORC_E_RANGE;
+    if (!(cfg_f[k] >= fg[0]) || !(cfg_f[k] <= fg[n_f - 1])) return ORC_E_RANGE;
+  }
+  const double INF = std::numeric_limits<double>::infinity();
+  const double window_s = (double)n_tick * tick_s;
+  std::vector<int> fi(K);
+  std::vector<double> u(K);
+  for (int k = 0; k < K; ++k) {
+    if (n_f == 1) { fi[k] = 0; u[k] = 0.0; continue; }
+    fi[k] = bracket(fg, n_f, cfg_f[k]);
+    u[k] = (cfg_f[k] - fg[fi[k]]) / (fg[fi[k] + 1] - fg[fi[k]]);
+  }
+  auto tab = [&](const double* X, int g, int ti, int f, int j) -> double {
+    return X[(((int64_t)g * n_tp + ti) * n_f + f) * n_rho + j];
+  };
+  std::vector<double> ttft, tbt, e_cost(K), e_energy(K);
+  std::vector<uint8_t> e_flags(K);
+  for (int w = 0; w < n_window; ++w) {
+    for (int g = 0; g < G; ++g) {
+      const int64_t c = (int64_t)w * G + g;
+      int64_t m = 0;
+      for (int q = 0; q < n_tick; ++q) {
+        const int64_t f = ((int64_t)w * n_tick + q) * G + g;
+        if (fine_off[f] < 0 || fine_off[f + 1] < fine_off[f] || fine_off[f + 1] > n_req) return ORC_E_ORDER;
+        m += fine_off[f + 1] - fine_off[f];
+      }
+      const int64_t rank = (m > 0) ? ((int64_t)pct_num * m + pct_den - 1) / pct_den : 0;
+      if (m_out) m_out[c] = m;
+      for (int k = 0; k < K; ++k) {
+        const int ti = cfg_tp_index[k], f0 = fi[k];
+        const double uk = u[k], nk = (double)cfg_n[k];
+        const double* mlrow = ML + ((int64_t)g * n_tp + ti) * n_f;
+        const double ml = (n_f == 1) ? mlrow[0] : (1.0 - uk) * mlrow[f0] + uk * mlrow[f0 + 1];
+        ttft.clear();
+        tbt.clear();
+        double E = 0.0;
+        bool any_ov = false;
+        for (int q = 0; q < n_tick; ++q) {
+          const int64_t f = ((int64_t)w * n_tick + q) * G + g;
+          const int64_t beg = fine_off[f], end = fine_off[f + 1];
+          int64_t tok = 0;
+          for (int64_t r = beg; r < end; ++r) tok += (int64_t)in_tok[r] + out_tok[r];
+          const double L = (double)tok / tick_s;
+          const double rho = L / (nk * ml);
+          const bool ov = rho > rg[n_rho - 1];
+          any_ov = any_ov || ov;
+          const double rc = ov ? rg[n_rho - 1] : rho;
+          const int j = bracket(rg, n_rho, rc);
+          const double t = (rc - rg[j]) / (rg[j + 1] - rg[j]);
+          double val[3];
+          const double* X[3] = {PF, TB, PW};
+          for (int x = 0; x < 3; ++x) {
+            const double a = (1.0 - t) * tab(X[x], g, ti, f0, j) + t * tab(X[x], g, ti, f0, j + 1);
+            if (n_f == 1) { val[x] = a; continue; }
+            const double b = (1.0 - t) * tab(X[x], g, ti, f0 + 1, j) + t * tab(X[x], g, ti, f0 + 1, j + 1);
+            val[x] = (1.0 - uk) * a + uk * b;
+          }
+          for (int64_t r = beg; r < end; ++r) {   // every request of the tick under this configuration
+            ttft.push_back((double)in_tok[r] * val[0]);
+            tbt.push_back(val[1]);
+          }
+          E += (nk * val[2]) * tick_s;
+        }
+        double p_ttft = 0.0, p_tbt = 0.0;
+        if (m > 0) {
+          std::sort(ttft.begin(), ttft.end());
+          std::sort(tbt.begin(), tbt.end());
+          p_ttft = ttft[(size_t)(rank - 1)];
+          p_tbt = tbt[(size_t)(rank - 1)];
+        }
+        const double pw0 = (n_f == 1) ? tab(PW, g, ti, 0, 0)
+                                      : (1.0 - uk) * tab(PW, g, ti, f0, 0) + uk * tab(PW, g, ti, f0 + 1, 0);
+        const double cost = E + idle_cost_weight * ((nk * pw0) * window_s);
+        uint8_t fl = 0;
+        if (any_ov) fl |= 2;
+        if (p_ttft > slo_ttft[g]) fl |= 4;
+        if (p_tbt > slo_tbt[g]) fl |= 8;
+        if (gpu_budget && gpu_budget[g] > 0 && (int64_t)cfg_n[k] * tp[ti] > gpu_budget[g]) fl |= 16;
+        if (m == 0) fl |= 32;
+        if (!(fl & (2 | 4 | 8 | 16))) fl |= 1;
+        e_energy[k] = E; e_cost[k] = cost; e_flags[k] = fl;
+        const int64_t o = c * K + k;
+        if (energy_j) energy_j[o] = E;
+        if (p99_ttft_ms) p99_ttft_ms[o] = p_ttft;
+        if (p99_tbt_ms) p99_tbt_ms[o] = p_tbt;
+        if (flags) flags[o] = fl;
+        if (cost_out) cost_out[o] = cost;
+      }
+      int best = -1;
+      for (int k = 0; k < K; ++k)
+        if ((e_flags[k] & 1) && (best < 0 || e_cost[k] < e_cost[best])) best = k;
+      if (sel_out) sel_out[c] = best;
+      if (sel_energy_j) sel_energy_j[c] = best < 0 ? INF : e_energy[best];
+      if (sel_cost) sel_cost[c] = best < 0 ? INF : e_cost[best];
+    }
+  }
+  return ORC_OK;
+}
+
 // Objective summed over the pools of a window (Eq. 1 sums over instance types; here one
 // pool per class), classes added in index order; cells without a feasible configuration
 // are counted, not added.

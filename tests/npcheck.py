@@ -87,3 +87,65 @@ def np_eval(profile, st, n_window, window_s, configs, slos, pct=(99, 100), gpu_b
                 best, best_cost = k, cost
         out["sel"][c] = best
     return out
+
+
+def np_eval_ticks(profile, fine, n_window, n_tick, tick_s, configs, slos, pct=(99, 100), gpu_budget=None,
+                  idle_cost_weight=0.0):
+    """Tick-level variant: every request is served under the load of its own tick (sub-window)."""
+    tp = profile["tp"]; fg = profile["f_mhz"]; rg = profile["rho"]
+    PF, TB, PW, ML = (profile[k] for k in ("prefill_ms_per_tok", "tbt_ms", "power_w", "max_load_tps"))
+    G = PF.shape[0]
+    K = configs["n_inst"].size
+    off = fine["cell_off"]
+    cells = n_window * G
+    out = {k: np.zeros((cells, K)) for k in ("energy_j", "p99_ttft_ms", "p99_tbt_ms", "cost")}
+    out["flags"] = np.zeros((cells, K), np.uint8)
+    out["sel"] = np.full(cells, -1, np.int32)
+
+    def look(X, g, ti, f, r):
+        if fg.size == 1:
+            return float(np.interp(r, rg, X[g, ti, 0]))
+        hit = np.nonzero(fg == f)[0]
+        if hit.size:
+            return float(np.interp(r, rg, X[g, ti, hit[0]]))
+        return float(RegularGridInterpolator((fg, rg), X[g, ti])((f, r)))
+
+    for w in range(n_window):
+        for g in range(G):
+            c = w * G + g
+            segs = []
+            for q in range(n_tick):
+                f = (w * n_tick + q) * G + g
+                segs.append((fine["in_tok"][off[f]:off[f + 1]].astype(np.int64),
+                             fine["out_tok"][off[f]:off[f + 1]].astype(np.int64)))
+            m = sum(x.size for x, _ in segs)
+            rank = int(math.ceil(Fraction(pct[0] * m, pct[1])))
+            best, best_cost = -1, math.inf
+            for k in range(K):
+                n = int(configs["n_inst"][k]); ti = int(configs["tp_index"][k]); f = float(configs["f_mhz"][k])
+                cap = float(np.interp(f, fg, ML[g, ti])) if fg.size > 1 else float(ML[g, ti, 0])
+                ttft, tbt, e, over = [], [], 0.0, False
+                for x, y in segs:
+                    load = float(Fraction(int(x.sum() + y.sum())) / Fraction(float(tick_s)))
+                    rho = load / (n * cap)
+                    over = over or rho > rg[-1]
+                    r = min(rho, rg[-1])
+                    ttft.extend((x * look(PF, g, ti, f, r)).tolist())
+                    tbt.extend([look(TB, g, ti, f, r)] * x.size)
+                    e += n * look(PW, g, ti, f, r) * tick_s
+                p1 = sorted(ttft)[rank - 1] if m else 0.0
+                p2 = sorted(tbt)[rank - 1] if m else 0.0
+                cost = e + idle_cost_weight * n * look(PW, g, ti, f, 0.0) * (n_tick * tick_s)
+                fl = 0
+                if over: fl |= 2
+                if p1 > slos["slo_ttft_ms"][g]: fl |= 4
+                if p2 > slos["slo_tbt_ms"][g]: fl |= 8
+                if gpu_budget is not None and gpu_budget[g] > 0 and n * int(tp[ti]) > gpu_budget[g]: fl |= 16
+                if m == 0: fl |= 32
+                if not fl & 30: fl |= 1
+                out["energy_j"][c, k] = e; out["p99_ttft_ms"][c, k] = p1; out["p99_tbt_ms"][c, k] = p2
+                out["cost"][c, k] = cost; out["flags"][c, k] = fl
+                if fl & 1 and cost < best_cost:
+                    best, best_cost = k, cost
+            out["sel"][c] = best
+    return out

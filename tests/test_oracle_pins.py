@@ -408,6 +408,63 @@ def test_scaling_inputs_and_ttft_slo_together_keeps_selection(small_hour):
     np.testing.assert_allclose(r3["p99_ttft_ms"], 3 * r["p99_ttft_ms"], rtol=1e-12)
 
 
+# ------------------------------------------------------------------- tick-level variant
+def test_ticks_with_one_tick_per_window_equal_the_window_level_result(small_hour):
+    w, st, r = small_hour
+    t = oracle.evaluate_ticks(w["profile"], st, w["n_window"], 1, w["window_s"], w["configs"], w["slos"], w["pct"])
+    for k in ("energy_j", "p99_ttft_ms", "p99_tbt_ms", "flags", "cost", "sel", "sel_energy_j", "sel_cost", "m"):
+        np.testing.assert_array_equal(t[k], r[k], err_msg=k)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_ticks_against_numpy_brute_force(seed):
+    rng = np.random.default_rng(300 + seed)
+    n_f, n_rho, G = int(rng.integers(1, 4)), int(rng.integers(2, 6)), 2
+    fg = np.sort(rng.uniform(500, 2000, n_f)); rg = np.concatenate([[0.0], np.sort(rng.uniform(0.05, 0.95, n_rho - 1))])
+    shape = (G, 2, n_f, n_rho)
+    prof = _profile([2, 4], fg, rg, rng.uniform(0.05, 0.3, shape), np.sort(rng.uniform(10, 150, shape), axis=-1),
+                    np.sort(rng.uniform(100, 3000, shape), axis=-1), rng.uniform(100, 900, shape[:3]))
+    fcand = list(fg) + ([float(rng.uniform(fg[0], fg[-1]))] if n_f > 1 else [])
+    cfg = _configs([(int(rng.integers(1, 5)), int(rng.integers(0, 2)), float(rng.choice(fcand))) for _ in range(9)])
+    NW, T, tick = 3, 4, 5.0
+    R = 150
+    tr = {"t_s": rng.uniform(0, NW * T * tick, R), "in_tok": rng.integers(1, 600, R).astype(np.int32),
+          "out_tok": rng.integers(1, 300, R).astype(np.int32), "model": np.zeros(R, np.int32)}
+    tr["t_s"][tr["t_s"] >= 2 * T * tick] = 3.0            # last window empty, one tick crowded
+    edges = {"in_edge": np.asarray([[200]], np.int32), "out_edge": np.zeros((1, 0), np.int32)}
+    slo = {"slo_ttft_ms": rng.uniform(20, 120, G), "slo_tbt_ms": rng.uniform(40, 140, G)}
+    bud = np.asarray([0, 8], np.int32)
+    fine = oracle.ingest(tr, edges, NW * T, tick)
+    a = oracle.evaluate_ticks(prof, fine, NW, T, tick, cfg, slo, (99, 100), bud, 0.1)
+    b = npcheck.np_eval_ticks(prof, npcheck.np_ingest(tr, edges, NW * T, tick), NW, T, tick, cfg, slo, (99, 100), bud, 0.1)
+    for k in ("energy_j", "p99_ttft_ms", "p99_tbt_ms", "cost"):
+        np.testing.assert_allclose(a[k], b[k], rtol=1e-12, atol=0)
+    np.testing.assert_array_equal(a["flags"], b["flags"])
+    np.testing.assert_array_equal(a["sel"], b["sel"])
+    assert (a["flags"] & 2).any() and (a["flags"] & 1).any() and (a["flags"] & 32).any()
+
+
+def test_ticks_single_busy_tick_reduces_to_that_tick():
+    """If all requests of a window fall into one tick, the percentiles are those of the window-level
+    evaluation of that tick alone (load = tokens / tick length)."""
+    w = make(SPECS[0].scaled(400, 1), with_trace=False)
+    rng = np.random.default_rng(5)
+    T, tick = 6, 10.0
+    tr = {"t_s": rng.uniform(20.0, 30.0, 400), "in_tok": rng.integers(1, 8193, 400).astype(np.int32),
+          "out_tok": rng.integers(1, 2000, 400).astype(np.int32), "model": np.zeros(400, np.int32)}
+    fine = oracle.ingest(tr, w["edges"], T, tick)
+    t = oracle.evaluate_ticks(w["profile"], fine, 1, T, tick, w["configs"], w["slos"], w["pct"])
+    G = w["n_class"]
+    only = oracle.evaluate(w["profile"], fine, T, tick, w["configs"], w["slos"], w["pct"],
+                           cell_ids=np.arange(2 * G, 3 * G))
+    np.testing.assert_array_equal(t["p99_ttft_ms"], only["p99_ttft_ms"])
+    np.testing.assert_array_equal(t["p99_tbt_ms"], only["p99_tbt_ms"])
+    # energy: the busy tick's energy plus five idle ticks
+    idle = oracle.evaluate(w["profile"], {"in_tok": np.zeros(0, np.int32), "out_tok": np.zeros(0, np.int32),
+                                          "cell_off": np.zeros(G + 1, np.int64)}, 1, tick, w["configs"], w["slos"])
+    np.testing.assert_allclose(t["energy_j"], only["energy_j"] + 5 * idle["energy_j"], rtol=1e-13)
+
+
 # ----------------------------------------------------------- planted mistakes are caught
 def test_pins_catch_planted_mistakes():
     """Sanity of the pins themselves: perturbing the inputs the way a typical slip would
