@@ -162,6 +162,7 @@ typedef struct {
 /* Status bits kept in the first 4 bytes of a workspace. */
 #define DYN_WS_BAD_OFFSETS 1u /* cell_off not monotone / outside [0, n_req]: cell treated as empty */
 #define DYN_WS_BAD_REQUEST 2u /* ingest: timestamp or model index out of range          */
+#define DYN_WS_TICK_RANK 4u   /* tick evaluation: a cell's percentile lies deeper than DYN_TICK_DEPTH */
 
 /* Bytes of workspace dyn_eval_space needs (a multiple of 256). */
 size_t dyn_eval_space_workspace(int32_t n_window, int32_t n_class, int32_t n_config);
@@ -218,6 +219,35 @@ int dyn_eval_select(dyn_profile* profile, const dyn_trace_view* trace, const dyn
                     const dyn_selection* sel, void* workspace, size_t workspace_bytes,
                     void* hip_stream);
 
+/* ----------------------------------------------------------- tick-level load in a window --
+ * Section IV-B "Scale-up/down": inside a window the instance manager follows the load at
+ * a finer grain (every few seconds) than the window the configuration is chosen for.  Here
+ * every window is split into n_tick ticks of tick_s seconds; each request is served under
+ * the load of its own tick: per tick the load is that tick's tokens / tick_s and the
+ * tables are looked up at it; per-request TTFT = input tokens * the tick's prefill
+ * ms/token, per-request TBT = the tick's TBT; the percentiles are taken over all requests
+ * of the (window, class) cell; energy = sum over the ticks, in time order, of
+ * (n_inst * power) * tick_s; a configuration is overloaded when it is in any tick; the
+ * idle term of the cost uses the window length (double) n_tick * tick_s.  With
+ * n_tick == 1 every output equals dyn_eval_select's.
+ *
+ * `fine` is the trace sorted by tick: the result of dyn_trace_ingest with
+ * n_window * n_tick windows of tick_s seconds (fine->n_window = n_window * n_tick,
+ * fine->window_s = tick_s; tick q of window w is fine window w * n_tick + q).
+ * `space` and `sel` are indexed by the coarse cell w * G + g: [n_window*G][K], [n_window*G]
+ * and [n_window].  1 <= n_tick <= DYN_TICK_LIMIT, else DYN_E_SHAPE.
+ * The percentile of a cell with m requests is its j-th largest value, j = m - rank + 1;
+ * cells with j > DYN_TICK_DEPTH (m >= 6400 at P99) are not evaluated: their percentiles
+ * are +inf, their TTFT and TBT flags are set and DYN_WS_TICK_RANK is raised in the
+ * workspace status.  Workspace: dyn_eval_ticks_workspace bytes, DEVICE, 256-byte aligned. */
+#define DYN_TICK_LIMIT 16
+#define DYN_TICK_DEPTH 64
+size_t dyn_eval_ticks_workspace(int32_t n_window, int32_t n_tick, int32_t n_class, int32_t n_config);
+int dyn_eval_select_ticks(dyn_profile* profile, const dyn_trace_view* fine, int32_t n_tick,
+                          const dyn_config* cfg, int32_t K, const dyn_objective* objective,
+                          const dyn_space* space, const dyn_selection* sel, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------- kernel timing (optional) --
  * Measurement aid, not part of the method: when enabled, the library brackets each of its
  * kernels with a pair of HIP events recorded on the stream the kernel is launched on, so
@@ -227,7 +257,9 @@ int dyn_eval_select(dyn_profile* profile, const dyn_trace_view* trace, const dyn
 #define DYN_K_SPACE 1   /* evaluation of the (cell, configuration) space                */
 #define DYN_K_SELECT 2  /* per-cell least-cost feasible configuration (or its fused finish) */
 #define DYN_K_TOTALS 3  /* per-window totals                                            */
-#define DYN_K_COUNT 4
+#define DYN_K_TICK_TOP 4   /* tick evaluation: largest input lengths per tick             */
+#define DYN_K_TICK_SPACE 5 /* tick evaluation of the (cell, configuration) space           */
+#define DYN_K_COUNT 6
 /* on != 0: create the event pool (up to `max_launches` launches per kernel are recorded,
  * later ones are not) and start recording; on == 0: stop and destroy the pool.         */
 int dyn_timing_enable(int on, int32_t max_launches);

@@ -19,10 +19,12 @@ __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_t
            "dyn_timing_enable", "dyn_timing_reset", "dyn_timing_read", "DYN_K_CELL", "DYN_K_SPACE", "DYN_K_SELECT",
            "DYN_K_TOTALS",
            "DYN_F_FEASIBLE", "DYN_F_OVERLOAD", "DYN_F_TTFT", "DYN_F_TBT", "DYN_F_BUDGET", "DYN_F_EMPTY",
-           "DYN_WS_BAD_OFFSETS", "DYN_WS_BAD_REQUEST"]
+           "DYN_WS_BAD_OFFSETS", "DYN_WS_BAD_REQUEST", "DYN_WS_TICK_RANK", "dyn_eval_select_ticks",
+           "dyn_eval_ticks_workspace", "DYN_K_TICK_TOP", "DYN_K_TICK_SPACE", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
 
 DYN_F_FEASIBLE, DYN_F_OVERLOAD, DYN_F_TTFT, DYN_F_TBT, DYN_F_BUDGET, DYN_F_EMPTY = 1, 2, 4, 8, 16, 32
-DYN_WS_BAD_OFFSETS, DYN_WS_BAD_REQUEST = 1, 2
+DYN_WS_BAD_OFFSETS, DYN_WS_BAD_REQUEST, DYN_WS_TICK_RANK = 1, 2, 4
+DYN_TICK_LIMIT, DYN_TICK_DEPTH = 16, 64
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -99,12 +101,17 @@ _lib.dyn_select_config.argtypes = [_vp, C.POINTER(_Space), C.POINTER(_Config), _
 _lib.dyn_eval_select.restype = C.c_int
 _lib.dyn_eval_select.argtypes = [_vp, C.POINTER(_TraceView), C.POINTER(_Config), _i32, C.POINTER(_Objective),
                                  C.POINTER(_Space), C.POINTER(_Selection), _vp, _sz, _vp]
+_lib.dyn_eval_ticks_workspace.restype = _sz
+_lib.dyn_eval_ticks_workspace.argtypes = [_i32, _i32, _i32, _i32]
+_lib.dyn_eval_select_ticks.restype = C.c_int
+_lib.dyn_eval_select_ticks.argtypes = [_vp, C.POINTER(_TraceView), _i32, C.POINTER(_Config), _i32,
+                                       C.POINTER(_Objective), C.POINTER(_Space), C.POINTER(_Selection), _vp, _sz, _vp]
 _lib.dyn_timing_enable.restype = C.c_int
 _lib.dyn_timing_enable.argtypes = [C.c_int, _i32]
 _lib.dyn_timing_reset.restype = C.c_int
 _lib.dyn_timing_read.restype = C.c_int
 _lib.dyn_timing_read.argtypes = [_i32, C.POINTER(C.c_double), C.POINTER(_i64)]
-DYN_K_CELL, DYN_K_SPACE, DYN_K_SELECT, DYN_K_TOTALS = 0, 1, 2, 3
+DYN_K_CELL, DYN_K_SPACE, DYN_K_SELECT, DYN_K_TOTALS, DYN_K_TICK_TOP, DYN_K_TICK_SPACE = 0, 1, 2, 3, 4, 5
 
 
 def dyn_timing_enable(on: bool, max_launches: int = 4096):
@@ -329,6 +336,46 @@ def dyn_eval_select(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tenso
     se = _selection_struct(sel)
     _check(_lib.dyn_eval_select(profile.handle, C.byref(tv), plan.cfg, K, C.byref(plan.obj), C.byref(sp), C.byref(se),
                                 _dp(workspace), workspace.numel(), _stream(stream)), "dyn_eval_select")
+    return out, sel, workspace
+
+
+def dyn_eval_ticks_workspace(n_window: int, n_tick: int, n_class: int, n_config: int) -> int:
+    return int(_lib.dyn_eval_ticks_workspace(n_window, n_tick, n_class, n_config))
+
+
+def dyn_eval_select_ticks(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tensor, cell_off: torch.Tensor,
+                          n_window: int, n_tick: int, tick_s: float, plan: Plan,
+                          out: Optional[Dict[str, torch.Tensor]] = None, sel: Optional[Dict[str, torch.Tensor]] = None,
+                          workspace: Optional[torch.Tensor] = None, stream=None):
+    """Tick-level evaluation and selection.  The trace arrays are those of dyn_trace_ingest with
+    n_window*n_tick windows of tick_s seconds; outputs are per coarse cell.  Returns (space, selection, workspace)."""
+    G, K = profile.n_class, plan.K
+    if plan.n_class != G:
+        raise ValueError("SLO arrays must have one entry per class")
+    cells = n_window * G
+    if cell_off.numel() != cells * n_tick + 1:
+        raise ValueError("cell_off must have n_window*n_tick*G + 1 entries")
+    dev = cell_off.device
+    if out is None:
+        out = _space_tensors(cells, K, dev)
+    if sel is None:
+        sel = _selection_tensors(cells, n_window, dev)
+    if workspace is None:
+        nbytes = dyn_eval_ticks_workspace(n_window, n_tick, G, K)
+        if nbytes == 0:
+            raise DynError(-2, "dyn_eval_ticks_workspace")
+        workspace = _workspace(nbytes, dev)
+    for v in out.values():
+        if v.numel() != cells * K:
+            raise ValueError("space tensors must hold n_window*G*K entries")
+    tv = _TraceView(in_tok.numel(), n_window * n_tick, float(tick_s), _dp(in_tok, torch.int32, "in_tok"),
+                    _dp(out_tok, torch.int32, "out_tok"), _dp(cell_off, torch.int64, "cell_off"))
+    sp = _Space(_dp(out["energy_j"], torch.float64), _dp(out["p99_ttft_ms"], torch.float64),
+                _dp(out["p99_tbt_ms"], torch.float64), _dp(out["flags"], torch.uint8))
+    se = _selection_struct(sel)
+    _check(_lib.dyn_eval_select_ticks(profile.handle, C.byref(tv), n_tick, plan.cfg, K, C.byref(plan.obj), C.byref(sp),
+                                      C.byref(se), _dp(workspace), workspace.numel(), _stream(stream)),
+           "dyn_eval_select_ticks")
     return out, sel, workspace
 
 

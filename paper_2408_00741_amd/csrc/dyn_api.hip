@@ -10,7 +10,7 @@
 #include <algorithm>
 #include <new>
 
-#include "dyn_internal.h"
+#include "dyn_ticks.h"
 
 namespace {
 
@@ -256,6 +256,18 @@ EvalWs dyn_eval_ws_layout(int64_t cells, int32_t K) {
   w.in_p99 = off; off += align256(c * 4);
   w.rec = off; off += align256(c * sizeof(CellRec));
   w.cstat = off; off += align256(c);
+  w.part = off; off += align256(c * (size_t)w.n_wslot * sizeof(SelPart));
+  w.total = off;
+  return w;
+}
+
+TickWs dyn_tick_ws_layout(int64_t coarse_cells, int32_t n_tick, int32_t K) {
+  TickWs w;
+  w.fine = dyn_eval_ws_layout(coarse_cells * n_tick, 1);
+  const size_t c = (size_t)std::max<int64_t>(coarse_cells, 1);
+  w.n_wslot = std::max(K, 1) / DYN_WAVE + 4;
+  size_t off = w.fine.part;
+  w.top = off; off += align256(c * (size_t)n_tick * DYN_TICK_TOP * sizeof(int32_t));
   w.part = off; off += align256(c * (size_t)w.n_wslot * sizeof(SelPart));
   w.total = off;
   return w;
@@ -526,6 +538,78 @@ int dyn_eval_select(dyn_profile* p, const dyn_trace_view* t, const dyn_config* c
                     size_t workspace_bytes, void* hip_stream) {
   if (!sel) { dyn_set_error("selection is NULL"); return DYN_E_NULL; }
   return eval_impl(p, t, cfg, K, o, out, sel, workspace, workspace_bytes, hip_stream);
+}
+
+size_t dyn_eval_ticks_workspace(int32_t n_window, int32_t n_tick, int32_t n_class, int32_t n_config) {
+  if (n_window < 1 || n_tick < 1 || n_tick > DYN_TICK_LIMIT || n_class < 1 || n_config < 1) return 0;
+  return dyn_tick_ws_layout((int64_t)n_window * n_class, n_tick, n_config).total;
+}
+
+int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tick, const dyn_config* cfg, int32_t K,
+                          const dyn_objective* o, const dyn_space* out, const dyn_selection* sel, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  if (!p || !t || !out || !sel || !workspace) { dyn_set_error("profile, trace, space, sel or workspace is NULL"); return DYN_E_NULL; }
+  if (!out->energy_j || !out->p99_ttft_ms || !out->p99_tbt_ms || !out->flags) { dyn_set_error("an output array is NULL"); return DYN_E_NULL; }
+  int rc;
+  if ((rc = check_selection(sel)) != DYN_OK) return rc;
+  if (n_tick < 1 || n_tick > DYN_TICK_LIMIT) { dyn_set_error("n_tick=%d outside [1, %d]", n_tick, DYN_TICK_LIMIT); return DYN_E_SHAPE; }
+  if (t->n_req < 0 || t->n_req >= ((int64_t)1 << 31) || t->n_window < 1) { dyn_set_error("n_req or n_window out of range"); return DYN_E_SHAPE; }
+  if (t->n_window % n_tick != 0) { dyn_set_error("fine n_window=%d is not a multiple of n_tick=%d", t->n_window, n_tick); return DYN_E_SHAPE; }
+  if (!t->cell_off || (t->n_req > 0 && (!t->in_tok || !t->out_tok))) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
+  if (!(t->window_s > 0.0) || !isfinite(t->window_s)) { dyn_set_error("tick length must be finite and > 0"); return DYN_E_RANGE; }
+  const int32_t n_window = t->n_window / n_tick;
+  const int64_t cells = (int64_t)n_window * p->G, fine_cells = cells * n_tick;
+  if (fine_cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * n_tick * classes must stay below 2^30"); return DYN_E_SHAPE; }
+  if ((rc = check_device(p)) != DYN_OK) return rc;
+  if (K < 1 || K > DYN_MAX_CONFIGS) { dyn_set_error("K=%d outside [1, %d]", K, DYN_MAX_CONFIGS); return DYN_E_SHAPE; }
+  const TickWs w = dyn_tick_ws_layout(cells, n_tick, K);
+  if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) {
+    dyn_set_error("workspace misaligned or too small (%zu < %zu)", workspace_bytes, w.total);
+    return DYN_E_WORKSPACE;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  if ((rc = prepare_configs(p, cfg, K, s)) != DYN_OK) return rc;
+  if ((rc = prepare_objective(p, o, s)) != DYN_OK) return rc;
+
+  char* base = (char*)workspace;
+  // per-tick aggregates: the fine trace's cells are the ticks, so the load of a fine cell is tokens / tick_s
+  if (!hip_ok(dyn_launch_cell_aggregate(t->in_tok, t->out_tok, t->cell_off, t->n_req, fine_cells, t->window_s, o->pct_num,
+                                        o->pct_den, (int64_t*)(base + w.fine.tin), (int64_t*)(base + w.fine.tout),
+                                        (int32_t*)(base + w.fine.in_p99), (CellRec*)(base + w.fine.rec),
+                                        (uint8_t*)(base + w.fine.cstat), (WsHeader*)(base + w.fine.header), s),
+              "cell aggregate launch"))
+    return DYN_E_DEVICE;
+  if (!hip_ok(dyn_launch_tick_top(t->in_tok, t->cell_off, t->n_req, n_window, n_tick, p->G, o->pct_num, o->pct_den,
+                                  (int32_t*)(base + w.top), s),
+              "tick candidates launch"))
+    return DYN_E_DEVICE;
+
+  TickArgs ta;
+  SpaceArgs& a = ta.s;
+  a.tab = p->d_tab; a.ml = p->d_ml; a.gridpack = p->d_gridpack;
+  a.jstart = p->d_jstart; a.n_bucket = p->n_bucket; a.bucket_scale = p->bucket_scale; a.one_step = p->one_step;
+  a.G = p->G; a.n_tp_f = p->n_tp * p->n_f; a.n_rho = p->n_rho;
+  a.cfg = p->d_cfg; a.K = K; a.tile = p->tile; a.n_tile = p->n_tile; a.n_slot = p->n_slot;
+  a.tile_rows = p->d_tile_rows;
+  a.slo_ttft = p->d_slo_ttft; a.slo_tbt = p->d_slo_tbt; a.budget = p->d_budget;
+  a.rec = (const CellRec*)(base + w.fine.rec); a.n_window = n_window; a.window_s = t->window_s;
+  const int64_t cell_tiles = cells * p->n_tile;
+  a.win_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(DYN_MAX_WIN_PER_BLOCK, (cell_tiles + 8191) / 8192));
+  a.energy = out->energy_j; a.p99_ttft = out->p99_ttft_ms; a.p99_tbt = out->p99_tbt_ms; a.flags = out->flags;
+  a.pw0 = p->d_pw0; a.idle_w = o->idle_cost_weight;
+  a.part = (SelPart*)(base + w.part); a.n_wslot = w.n_wslot;
+  ta.n_tick = n_tick; ta.tick_s = t->window_s; ta.window_s = (double)n_tick * t->window_s;
+  ta.fine_off = t->cell_off; ta.n_req = t->n_req; ta.top = (const int32_t*)(base + w.top);
+  ta.cstat = (uint8_t*)(base + w.fine.cstat); ta.pct_num = o->pct_num; ta.pct_den = o->pct_den;
+  if (!hip_ok(dyn_launch_tick_space(ta, s), "tick space launch")) return DYN_E_DEVICE;
+
+  FinishArgs f;
+  f.part = a.part; f.n_wslot = w.n_wslot; f.n_used = p->n_tile * (p->tile / DYN_WAVE);
+  f.n_window = n_window; f.G = p->G;
+  f.sel = sel->sel; f.sel_energy = sel->sel_energy_j; f.sel_cost = sel->sel_cost;
+  f.win_energy = sel->window_energy_j; f.win_inf = sel->window_infeasible;
+  if (!hip_ok(dyn_launch_finish(f, s), "finish launch")) return DYN_E_DEVICE;
+  return DYN_OK;
 }
 
 int dyn_cell_stats(const void* workspace, size_t workspace_bytes, int32_t n_window, int32_t n_class,

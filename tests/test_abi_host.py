@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported(dyn):
     assert {"dyn_profile_load", "dyn_eval_space", "dyn_select_config", "dyn_trace_ingest", "dyn_profile_free",
             "dyn_cell_stats", "dyn_workspace_status", "dyn_last_error", "dyn_eval_space_workspace",
             "dyn_trace_ingest_workspace", "dyn_eval_select", "dyn_timing_enable", "dyn_timing_read",
-            "dyn_timing_reset"} <= set(names)
+            "dyn_timing_reset", "dyn_eval_select_ticks", "dyn_eval_ticks_workspace"} <= set(names)
     lib = C.CDLL(dyn.lib_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -43,6 +43,10 @@ def test_workspace_sizes(dyn):
     b = dyn.dyn_trace_ingest_workspace(10_000_000, 1440, 25)
     assert b % 256 == 0 and b >= 4 * 4 * 10_000_000
     assert dyn.dyn_trace_ingest_workspace(0, 1, 1) > 0
+    c = dyn.dyn_eval_ticks_workspace(1440, 12, 25, 576)
+    assert c % 256 == 0 and c >= 36000 * 12 * (64 * 4 + 53)
+    assert dyn.dyn_eval_ticks_workspace(1440, 17, 25, 576) == 0      # beyond DYN_TICK_LIMIT
+    assert dyn.dyn_eval_ticks_workspace(1440, 0, 25, 576) == 0
 
 
 def _prof():

@@ -1,0 +1,231 @@
+"""Tick-level evaluation (load followed inside a window) on a real MI355X against the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import SPECS, make
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+KEYS = ("energy_j", "p99_ttft_ms", "p99_tbt_ms", "flags", "sel", "sel_energy_j", "sel_cost")
+
+
+@pytest.fixture(scope="module")
+def dyn():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2408_00741_amd as d
+    return d
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def gpu_ticks(dyn, w, n_tick, gpu_budget=None, trace=None, pct=None):
+    """Sorts the trace by tick on the GPU, then evaluates.  Returns (results, fine trace on the host)."""
+    tr = trace or w["trace"]
+    tick_s = w["window_s"] / n_tick
+    ins, outs, off, iws = dyn.dyn_trace_ingest(_dev(tr["t_s"]), _dev(tr["in_tok"]), _dev(tr["out_tok"]),
+                                               _dev(tr["model"]), w["edges"], w["n_window"] * n_tick, tick_s)
+    assert dyn.dyn_workspace_status(iws) == 0
+    prof = dyn.dyn_profile_load(w["profile"])
+    plan = dyn.Plan(w["configs"], w["slos"], pct or w["pct"], gpu_budget, w["idle_cost_weight"])
+    space, sel, ws = dyn.dyn_eval_select_ticks(prof, ins, outs, off, w["n_window"], n_tick, tick_s, plan)
+    status = dyn.dyn_workspace_status(ws)
+    torch.cuda.synchronize()
+    r = {k: v.cpu().numpy() for k, v in space.items()}
+    r.update({k: v.cpu().numpy() for k, v in sel.items()})
+    r["status"] = status
+    fine = {"in_tok": ins.cpu().numpy(), "out_tok": outs.cpu().numpy(), "cell_off": off.cpu().numpy()}
+    prof.free()
+    return r, fine
+
+
+def ora_ticks(w, fine, n_tick, gpu_budget=None, pct=None):
+    return oracle.evaluate_ticks(w["profile"], fine, w["n_window"], n_tick, w["window_s"] / n_tick, w["configs"],
+                                 w["slos"], pct or w["pct"], gpu_budget, w["idle_cost_weight"])
+
+
+def assert_same(w, g, o, skip_cells=None):
+    keep = np.ones(o["sel"].size, bool)
+    if skip_cells is not None:
+        keep[skip_cells] = False
+    for k in KEYS:
+        np.testing.assert_array_equal(g[k][keep], o[k][keep], err_msg=k)
+    if skip_cells is None:
+        we, wi = oracle.window_totals(o["sel"], o["sel_energy_j"], w["n_window"], w["n_class"])
+        np.testing.assert_array_equal(g["window_energy_j"], we)
+        np.testing.assert_array_equal(g["window_infeasible"], wi)
+
+
+CASES = {
+    "cfg0-T12": (SPECS[0], 12),
+    "cfg0-T16": (SPECS[0], 16),
+    "cfg0-T7": (SPECS[0], 7),
+    "cfg1-60k-T12": (SPECS[1].scaled(60_000, 48), 12),
+    "cfg2-300k-T12": (SPECS[2].scaled(300_000, 40), 12),
+    "cfg3-100k-T4": (SPECS[3].scaled(100_001, 9), 4),
+    "cfg4-250k-T6": (SPECS[4].scaled(250_000, 24), 6),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_ticks_match_oracle(dyn, name):
+    spec, T = CASES[name]
+    w = make(spec)
+    g, fine = gpu_ticks(dyn, w, T)
+    # the fine trace itself is the oracle's (stable order)
+    of = oracle.ingest(w["trace"], w["edges"], w["n_window"] * T, w["window_s"] / T)
+    for k in ("in_tok", "out_tok", "cell_off"):
+        np.testing.assert_array_equal(fine[k], of[k], err_msg=k)
+    o = ora_ticks(w, of, T)
+    deep = np.nonzero(o["m"] - np.ceil(w["pct"][0] * o["m"] / w["pct"][1]) + 1 > dyn.DYN_TICK_DEPTH)[0]
+    assert (g["status"] & dyn.DYN_WS_TICK_RANK != 0) == (deep.size > 0)
+    assert deep.size < o["sel"].size // 2, "the case is meant to exercise the evaluated cells"
+    assert_same(w, g, o, skip_cells=deep if deep.size else None)
+    assert (o["flags"] & 1).any() and (o["flags"] & 6).any()
+    if deep.size:
+        assert np.all(np.isinf(g["p99_ttft_ms"][deep])) and np.all(g["flags"][deep] & 12 == 12)
+        assert np.all(g["sel"][deep] == -1)
+        np.testing.assert_array_equal(g["energy_j"][deep], o["energy_j"][deep])
+
+
+def test_one_tick_equals_window_level_entry_point(dyn):
+    w = make(SPECS[0])
+    tr = w["trace"]
+    ins, outs, off, _ = dyn.dyn_trace_ingest(_dev(tr["t_s"]), _dev(tr["in_tok"]), _dev(tr["out_tok"]),
+                                             _dev(tr["model"]), w["edges"], w["n_window"], w["window_s"])
+    prof = dyn.dyn_profile_load(w["profile"])
+    plan = dyn.Plan(w["configs"], w["slos"], w["pct"], None, w["idle_cost_weight"])
+    a_space, a_sel, _ = dyn.dyn_eval_select(prof, ins, outs, off, w["n_window"], w["window_s"], plan)
+    b_space, b_sel, ws = dyn.dyn_eval_select_ticks(prof, ins, outs, off, w["n_window"], 1, w["window_s"], plan)
+    status = dyn.dyn_workspace_status(ws)
+    torch.cuda.synchronize()
+    m = np.diff(off.cpu().numpy())
+    deep = m - np.ceil(99 * m / 100) + 1 > dyn.DYN_TICK_DEPTH
+    assert (status != 0) == bool(deep.any())
+    for k in a_space:
+        np.testing.assert_array_equal(a_space[k].cpu().numpy()[~deep], b_space[k].cpu().numpy()[~deep], err_msg=k)
+    for k in ("sel", "sel_energy_j", "sel_cost"):
+        np.testing.assert_array_equal(a_sel[k].cpu().numpy()[~deep], b_sel[k].cpu().numpy()[~deep], err_msg=k)
+    prof.free()
+
+
+def _random_case(seed, n_req, NW, T, tick, in_hi=600, crowd=None):
+    rng = np.random.default_rng(700 + seed)
+    n_f, n_rho, G = int(rng.integers(1, 4)), int(rng.integers(2, 7)), 2
+    fg = np.sort(rng.uniform(500, 2000, n_f))
+    rg = np.concatenate([[0.0], np.sort(rng.uniform(0.05, 0.95, n_rho - 1))])
+    shape = (G, 2, n_f, n_rho)
+    prof = {"tp": np.asarray([2, 4], np.int32), "f_mhz": fg, "rho": rg,
+            "prefill_ms_per_tok": rng.uniform(0.05, 0.3, shape), "tbt_ms": np.sort(rng.uniform(10, 150, shape), axis=-1),
+            "power_w": np.sort(rng.uniform(100, 3000, shape), axis=-1), "max_load_tps": rng.uniform(100, 900, shape[:3])}
+    fcand = list(fg) + ([float(rng.uniform(fg[0], fg[-1]))] if n_f > 1 else [])
+    K = 70
+    cfg = {"n_inst": rng.integers(1, 9, K).astype(np.int32), "tp_index": rng.integers(0, 2, K).astype(np.int32),
+           "f_mhz": rng.choice(fcand, K)}
+    t = rng.uniform(0, NW * T * tick, n_req)
+    if crowd is not None:
+        t[: n_req // 2] = rng.uniform(crowd * tick, (crowd + 1) * tick, n_req // 2)   # half of the trace in one tick
+    tr = {"t_s": t, "in_tok": rng.integers(0, in_hi, n_req).astype(np.int32),
+          "out_tok": rng.integers(1, 300, n_req).astype(np.int32), "model": np.zeros(n_req, np.int32)}
+    w = {"profile": prof, "configs": cfg, "trace": tr, "n_window": NW, "window_s": T * tick, "n_class": G,
+         "edges": {"in_edge": np.asarray([[in_hi // 3]], np.int32), "out_edge": np.zeros((1, 0), np.int32)},
+         "slos": {"slo_ttft_ms": rng.uniform(20, 120, G), "slo_tbt_ms": rng.uniform(40, 140, G)},
+         "pct": (99, 100), "idle_cost_weight": 0.1}
+    return w
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_profiles_with_budget_and_idle_cost(dyn, seed):
+    w = _random_case(seed, 4000, 5, 4 + seed, 5.0, crowd=3 if seed % 2 else None)
+    bud = np.asarray([0, 12], np.int32)
+    g, fine = gpu_ticks(dyn, w, w_ticks(w, 5.0), bud)
+    o = ora_ticks(w, fine, w_ticks(w, 5.0), bud)
+    assert g["status"] == 0
+    assert_same(w, g, o)
+    assert (o["flags"] & 16).any()
+
+
+def w_ticks(w, tick):
+    return int(round(w["window_s"] / tick))
+
+
+@pytest.mark.parametrize("pct", [(50, 100), (9, 10), (1, 1), (1, 100)])
+def test_other_percentiles(dyn, pct):
+    """Median, P90, maximum and minimum: j = m - rank + 1 up to the whole cell."""
+    w = _random_case(11, 360, 6, 5, 5.0)     # about 30 requests per cell
+    g, fine = gpu_ticks(dyn, w, 5, pct=pct)
+    o = ora_ticks(w, fine, 5, pct=pct)
+    assert g["status"] == 0
+    assert_same(w, g, o)
+
+
+def test_many_equal_lengths_and_zero_lengths(dyn):
+    w = _random_case(3, 3000, 4, 8, 5.0, in_hi=3)    # input lengths 0, 1, 2 only: ties everywhere
+    g, fine = gpu_ticks(dyn, w, 8)
+    o = ora_ticks(w, fine, 8)
+    assert g["status"] == 0
+    assert_same(w, g, o)
+
+
+def test_deepest_supported_rank(dyn):
+    """One cell with exactly j = DYN_TICK_DEPTH (m = 6399 at P99) is evaluated; one more request is not."""
+    for extra, expect in ((0, 0), (1, 4)):
+        w = _random_case(5, 6399 + extra, 1, 8, 5.0)
+        w["edges"] = {"in_edge": np.zeros((1, 0), np.int32), "out_edge": np.zeros((1, 0), np.int32)}   # one class
+        for k in ("prefill_ms_per_tok", "tbt_ms", "power_w", "max_load_tps"):
+            w["profile"][k] = w["profile"][k][:1]
+        w["slos"] = {k: v[:1] for k, v in w["slos"].items()}
+        w["n_class"] = 1
+        g, fine = gpu_ticks(dyn, w, 8)
+        assert g["status"] == expect
+        o = ora_ticks(w, fine, 8)
+        if expect == 0:
+            assert_same(w, g, o)
+        else:
+            np.testing.assert_array_equal(g["energy_j"], o["energy_j"])
+            assert np.all(np.isinf(g["p99_ttft_ms"])) and np.all(g["sel"] == -1)
+
+
+def test_empty_trace_and_empty_ticks(dyn):
+    w = _random_case(7, 60, 3, 6, 5.0)
+    w["trace"]["t_s"][:] = np.random.default_rng(1).uniform(31.0, 34.0, 60)   # everything in one tick of window 1
+    g, fine = gpu_ticks(dyn, w, 6)
+    o = ora_ticks(w, fine, 6)
+    assert g["status"] == 0
+    assert_same(w, g, o)
+    assert (o["flags"] & 32).any()
+    none = {k: v[:0] for k, v in w["trace"].items()}
+    g, fine = gpu_ticks(dyn, w, 6, trace=none)
+    o = ora_ticks(w, fine, 6)
+    assert_same(w, g, o)
+    assert np.all(o["flags"] & 32)
+
+
+def test_argument_errors(dyn):
+    w = _random_case(0, 100, 2, 4, 5.0)
+    tr = w["trace"]
+    ins, outs, off, _ = dyn.dyn_trace_ingest(_dev(tr["t_s"]), _dev(tr["in_tok"]), _dev(tr["out_tok"]),
+                                             _dev(tr["model"]), w["edges"], 8, 5.0)
+    prof = dyn.dyn_profile_load(w["profile"])
+    plan = dyn.Plan(w["configs"], w["slos"])
+    ws = torch.empty(dyn.dyn_eval_ticks_workspace(2, 4, 2, 70), dtype=torch.uint8, device="cuda")
+    with pytest.raises(dyn.DynError) as e:      # workspace of the wrong size
+        dyn.dyn_eval_select_ticks(prof, ins, outs, off, 2, 4, 5.0, plan, workspace=ws[:4096])
+    assert e.value.status == -6
+    with pytest.raises(dyn.DynError) as e:      # more ticks than the kernels are built for
+        dyn.dyn_eval_select_ticks(prof, ins, outs, torch.zeros(2 * 17 * 2 + 1, dtype=torch.int64, device="cuda"), 2, 17,
+                                  5.0, plan, workspace=ws)
+    assert e.value.status == -2
+    with pytest.raises(dyn.DynError) as e:
+        dyn.dyn_eval_select_ticks(prof, ins, outs, off, 2, 4, 0.0, plan, workspace=ws)
+    assert e.value.status == -3
+    # and the same buffers still work afterwards
+    space, sel, _ = dyn.dyn_eval_select_ticks(prof, ins, outs, off, 2, 4, 5.0, plan, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.isfinite(space["energy_j"].cpu().numpy()).all()
+    prof.free()
