@@ -47,17 +47,23 @@ def recorded_traffic(workload_index):
     return None
 
 
-def cpu_baseline(w, n_sample_windows):
+def cpu_baseline(w, n_sample_windows, ticks=0):
     """The CPU oracle, as it stands, on the first windows of the same workload (one thread)."""
     import numpy as np
     import oracle
     tr = w["trace"]
     hi = int(np.searchsorted(tr["t_s"], n_sample_windows * w["window_s"]))
     sub = {k: v[:hi] for k, v in tr.items()}
-    st = oracle.ingest(sub, w["edges"], n_sample_windows, w["window_s"])
-    t0 = time.perf_counter()
-    oracle.evaluate(w["profile"], st, n_sample_windows, w["window_s"], w["configs"], w["slos"], w["pct"], None,
-                    w["idle_cost_weight"], want_space=False)
+    if ticks:
+        st = oracle.ingest(sub, w["edges"], n_sample_windows * ticks, w["window_s"] / ticks)
+        t0 = time.perf_counter()
+        oracle.evaluate_ticks(w["profile"], st, n_sample_windows, ticks, w["window_s"] / ticks, w["configs"], w["slos"],
+                              w["pct"], None, w["idle_cost_weight"])
+    else:
+        st = oracle.ingest(sub, w["edges"], n_sample_windows, w["window_s"])
+        t0 = time.perf_counter()
+        oracle.evaluate(w["profile"], st, n_sample_windows, w["window_s"], w["configs"], w["slos"], w["pct"], None,
+                        w["idle_cost_weight"], want_space=False)
     dt = time.perf_counter() - t0
     k = w["configs"]["n_inst"].size
     return {"value": hi * k / dt, "unit": "evals/s", "cores": 1, "kind": "oracle",
@@ -72,6 +78,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="workload index (0..4); the headline is 2")
     ap.add_argument("--unfused", action="store_true", help="dyn_eval_space + dyn_select_config as two calls")
+    ap.add_argument("--ticks", type=int, default=0,
+                    help="tick-level variant: split every window into this many ticks (dyn_eval_select_ticks); "
+                         "0 = the window-level headline path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events (roofline.achieved is then null)")
@@ -114,12 +123,14 @@ def main():
 
     # ---- one-time set-up, timed separately: upload, ingestion, profile load
     t_s, x, y, mdl = dev(tr["t_s"]), dev(tr["in_tok"]), dev(tr["out_tok"]), dev(tr["model"])
-    ws_ing = torch.empty(dyn.dyn_trace_ingest_workspace(R, NW, G), dtype=torch.uint8, device="cuda")
-    dyn.dyn_trace_ingest(t_s, x, y, mdl, w["edges"], NW, w["window_s"], workspace=ws_ing)   # warm-up
+    T = max(args.ticks, 1)                  # the trace is sorted by tick when ticks are asked for
+    NWF, len_s = NW * T, w["window_s"] / T
+    ws_ing = torch.empty(dyn.dyn_trace_ingest_workspace(R, NWF, G), dtype=torch.uint8, device="cuda")
+    dyn.dyn_trace_ingest(t_s, x, y, mdl, w["edges"], NWF, len_s, workspace=ws_ing)   # warm-up
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    ins, outs, off, _ = dyn.dyn_trace_ingest(t_s, x, y, mdl, w["edges"], NW, w["window_s"], workspace=ws_ing)
+    ins, outs, off, _ = dyn.dyn_trace_ingest(t_s, x, y, mdl, w["edges"], NWF, len_s, workspace=ws_ing)
     e1.record()
     torch.cuda.synchronize()
     ingest_ms = e0.elapsed_time(e1)
@@ -139,9 +150,13 @@ def main():
            "sel_cost": torch.empty(cells, dtype=torch.float64, device="cuda"),
            "window_energy_j": torch.empty(NW, dtype=torch.float64, device="cuda"),
            "window_infeasible": torch.empty(NW, dtype=torch.int32, device="cuda")}
-    ws = torch.empty(dyn.dyn_eval_space_workspace(NW, G, K), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(dyn.dyn_eval_ticks_workspace(NW, T, G, K) if args.ticks else dyn.dyn_eval_space_workspace(NW, G, K),
+                     dtype=torch.uint8, device="cuda")
 
-    if args.unfused:
+    if args.ticks:
+        def step():
+            dyn.dyn_eval_select_ticks(prof, ins, outs, off, NW, T, len_s, plan, out=space, sel=sel, workspace=ws)
+    elif args.unfused:
         def step():
             dyn.dyn_eval_space(prof, ins, outs, off, NW, w["window_s"], plan, out=space, workspace=ws)
             dyn.dyn_select_config(prof, space, NW, w["window_s"], plan, out=sel)
@@ -161,12 +176,13 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
-    assert dyn.dyn_workspace_status(ws) == 0
+    status = dyn.dyn_workspace_status(ws)
+    assert status == 0 or (args.ticks and status == dyn.DYN_WS_TICK_RANK), status
 
     # ---- the same `steps` steps again with the library's per-kernel HIP events switched on (recorded
     # on the stream the kernels are launched on).  The event records themselves cost about 20 us per
     # step on this machine, which is why they are kept out of the throughput region above.
-    ktime = {"cell": 0.0, "space": 0.0, "select": 0.0, "totals": 0.0}
+    ktime = {"cell": 0.0, "space": 0.0, "select": 0.0, "totals": 0.0, "tick_top": 0.0, "tick_space": 0.0, "tick_merge": 0.0}
     ms_per_step_events = None
     if not args.no_kernel_events:
         dyn.dyn_timing_enable(True, args.steps)
@@ -177,18 +193,20 @@ def main():
         torch.cuda.synchronize()
         ms_per_step_events = (time.perf_counter() - t0) / args.steps * 1e3
         for name, kid in (("cell", dyn.DYN_K_CELL), ("space", dyn.DYN_K_SPACE), ("select", dyn.DYN_K_SELECT),
-                          ("totals", dyn.DYN_K_TOTALS)):
+                          ("totals", dyn.DYN_K_TOTALS), ("tick_top", dyn.DYN_K_TICK_TOP),
+                          ("tick_space", dyn.DYN_K_TICK_SPACE), ("tick_merge", dyn.DYN_K_TICK_MERGE)):
             ms, n = dyn.dyn_timing_read(kid)
             ktime[name] = ms / max(n, 1)
         dyn.dyn_timing_enable(False)
 
     # ---- roofline of the dominant kernel (space evaluation): 25 B written per (cell, configuration)
     space_bytes = 25.0 * cells * K
-    space_gbps = space_bytes / (ktime["space"] * 1e-3) / 1e9 if ktime["space"] > 0 else None
+    space_ms = ktime["tick_space"] + ktime["tick_merge"] if args.ticks else ktime["space"]
+    space_gbps = space_bytes / (space_ms * 1e-3) / 1e9 if space_ms > 0 else None
     # whole path, algorithmic bytes: read the request stream and offsets once, write the space,
     # re-read energy + flags for the selection, write the selection and the window totals
     path_bytes = (8.0 * R + 8.0 * (cells + 1) + 25.0 * cells * K + (9.0 * cells * K if args.unfused else 0.0)
-                  + 20.0 * cells + 12.0 * NW)
+                  + 20.0 * cells + 12.0 * NW + (8.0 * cells * (T - 1) if args.ticks else 0.0))
     path_gbps = path_bytes / (ms_per_step * 1e-3) / 1e9
 
     sel_h = sel["sel"].cpu().numpy()
@@ -202,20 +220,23 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {spec.name}: {R} requests, {NW} windows x {G} classes = "
                                f"{cells} cells, {K} configurations", "requests": R, "cells": cells, "configs": K,
-                   "entry_points": "dyn_eval_space+dyn_select_config" if args.unfused else "dyn_eval_select"},
-        "roofline": {"bound": "hbm", "kernel": "space_kernel", "achieved": space_gbps, "peak": HBM_PEAK_GBPS,
+                   "ticks_per_window": args.ticks,
+                   "entry_points": "dyn_eval_select_ticks" if args.ticks else
+                                   "dyn_eval_space+dyn_select_config" if args.unfused else "dyn_eval_select"},
+        "roofline": {"bound": "hbm", "kernel": "tick_space_kernel" if args.ticks else "space_kernel",
+                     "achieved": space_gbps, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": space_gbps / HBM_PEAK_GBPS if space_gbps else None,
-                     "traffic": None if args.unfused else recorded_traffic(args.config),
-                     "algorithmic_bytes_per_launch": space_bytes, "avg_launch_ms": ktime["space"]},
+                     "traffic": None if (args.unfused or args.ticks) else recorded_traffic(args.config),
+                     "algorithmic_bytes_per_launch": space_bytes, "avg_launch_ms": space_ms},
         "kernel_ms": ktime, "ms_per_step_with_kernel_events": ms_per_step_events,
         "path": {"algorithmic_bytes": path_bytes, "gbps": path_gbps, "frac_of_hbm_peak": path_gbps / HBM_PEAK_GBPS},
         "setup": {"ingest_ms": ingest_ms, "profile_load_ms": profile_load_ms, "generate_s": gen_s,
                   "ingest_requests_per_s": R / (ingest_ms * 1e-3)},
-        "result": {"cells_without_feasible_config": int((sel_h < 0).sum()), "total_energy_wh": float(we.sum() / 3600.0)},
+        "result": {"workspace_status": status, "cells_without_feasible_config": int((sel_h < 0).sum()), "total_energy_wh": float(we.sum() / 3600.0)},
     }
     if not args.no_cpu_baseline:
         nwin = args.cpu_windows or max(1, min(NW, int(NW * 3.0e9 / (R * K))))
-        out["cpu_baseline"] = cpu_baseline(w, nwin)
+        out["cpu_baseline"] = cpu_baseline(w, nwin, args.ticks)
         out["cpu_baseline"]["host_cores"] = os.cpu_count()
     prof.free()
     print(json.dumps(out))

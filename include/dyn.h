@@ -257,9 +257,10 @@ int dyn_eval_select_ticks(dyn_profile* profile, const dyn_trace_view* fine, int3
 #define DYN_K_SPACE 1   /* evaluation of the (cell, configuration) space                */
 #define DYN_K_SELECT 2  /* per-cell least-cost feasible configuration (or its fused finish) */
 #define DYN_K_TOTALS 3  /* per-window totals                                            */
-#define DYN_K_TICK_TOP 4   /* tick evaluation: largest input lengths per tick             */
-#define DYN_K_TICK_SPACE 5 /* tick evaluation of the (cell, configuration) space           */
-#define DYN_K_COUNT 6
+#define DYN_K_TICK_TOP 4   /* tick evaluation: per-tick loads and largest input lengths   */
+#define DYN_K_TICK_SPACE 5 /* tick evaluation of the (cell, configuration) space: cells whose percentile is at most 16 deep */
+#define DYN_K_TICK_MERGE 6 /* the same for the remaining cells                             */
+#define DYN_K_COUNT 7
 /* on != 0: create the event pool (up to `max_launches` launches per kernel are recorded,
  * later ones are not) and start recording; on == 0: stop and destroy the pool.         */
 int dyn_timing_enable(int on, int32_t max_launches);

@@ -20,7 +20,7 @@ __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_t
            "DYN_K_TOTALS",
            "DYN_F_FEASIBLE", "DYN_F_OVERLOAD", "DYN_F_TTFT", "DYN_F_TBT", "DYN_F_BUDGET", "DYN_F_EMPTY",
            "DYN_WS_BAD_OFFSETS", "DYN_WS_BAD_REQUEST", "DYN_WS_TICK_RANK", "dyn_eval_select_ticks",
-           "dyn_eval_ticks_workspace", "DYN_K_TICK_TOP", "DYN_K_TICK_SPACE", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
+           "dyn_eval_ticks_workspace", "DYN_K_TICK_TOP", "DYN_K_TICK_SPACE", "DYN_K_TICK_MERGE", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
 
 DYN_F_FEASIBLE, DYN_F_OVERLOAD, DYN_F_TTFT, DYN_F_TBT, DYN_F_BUDGET, DYN_F_EMPTY = 1, 2, 4, 8, 16, 32
 DYN_WS_BAD_OFFSETS, DYN_WS_BAD_REQUEST, DYN_WS_TICK_RANK = 1, 2, 4
@@ -111,7 +111,7 @@ _lib.dyn_timing_enable.argtypes = [C.c_int, _i32]
 _lib.dyn_timing_reset.restype = C.c_int
 _lib.dyn_timing_read.restype = C.c_int
 _lib.dyn_timing_read.argtypes = [_i32, C.POINTER(C.c_double), C.POINTER(_i64)]
-DYN_K_CELL, DYN_K_SPACE, DYN_K_SELECT, DYN_K_TOTALS, DYN_K_TICK_TOP, DYN_K_TICK_SPACE = 0, 1, 2, 3, 4, 5
+DYN_K_CELL, DYN_K_SPACE, DYN_K_SELECT, DYN_K_TOTALS, DYN_K_TICK_TOP, DYN_K_TICK_SPACE, DYN_K_TICK_MERGE = range(7)
 
 
 def dyn_timing_enable(on: bool, max_launches: int = 4096):

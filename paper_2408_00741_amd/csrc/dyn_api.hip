@@ -44,7 +44,7 @@ hipError_t dev_alloc(T** p, size_t count) {
 }
 
 void free_profile_device(dyn_profile* p) {
-  void* ptrs[] = {p->d_tab, p->d_ml, p->d_pw0, p->d_gridpack, p->d_jstart, p->d_cfg,
+  void* ptrs[] = {p->d_tab, p->d_ml, p->d_pw0, p->d_gridpack, p->d_jstart, p->d_tstart, p->d_thr, p->d_cfg,
                   p->d_tile_rows, p->d_slo_ttft, p->d_slo_tbt, p->d_budget};
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
@@ -159,6 +159,8 @@ int prepare_configs(dyn_profile* p, const dyn_config* cfg, int32_t K, hipStream_
               "copy tile rows"))
     return DYN_E_DEVICE;
   p->tile = tile; p->n_tile = n_tile; p->n_slot = n_slot;
+  p->any_two_rows = false;
+  for (int k = 0; k < K; ++k) p->any_two_rows = p->any_two_rows || dc[k].u != 0.0;
   p->cfg_host.assign(cfg, cfg + K);
   return DYN_OK;
 }
@@ -269,6 +271,8 @@ TickWs dyn_tick_ws_layout(int64_t coarse_cells, int32_t n_tick, int32_t K) {
   size_t off = w.fine.part;
   w.top = off; off += align256(c * (size_t)n_tick * DYN_TICK_TOP * sizeof(int32_t));
   w.part = off; off += align256(c * (size_t)w.n_wslot * sizeof(SelPart));
+  w.merge_count = off; off += 256;
+  w.merge_list = off; off += align256(c * sizeof(uint32_t));
   w.total = off;
   return w;
 }
@@ -393,9 +397,9 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   p->tp.assign(d->tp, d->tp + d->n_tp);
   p->fg.assign(d->f_mhz, d->f_mhz + d->n_f);
   p->d_tab = p->d_ml = p->d_pw0 = p->d_gridpack = nullptr;
-  p->d_jstart = nullptr; p->d_cfg = nullptr; p->d_tile_rows = nullptr;
+  p->d_jstart = nullptr; p->d_tstart = nullptr; p->d_thr = nullptr; p->d_cfg = nullptr; p->d_tile_rows = nullptr;
   p->d_slo_ttft = p->d_slo_tbt = nullptr; p->d_budget = nullptr;
-  p->obj_valid = false; p->tile = p->n_tile = p->n_slot = 0;
+  p->obj_valid = false; p->tile = p->n_tile = p->n_slot = 0; p->any_two_rows = false;
   hipStream_t s = (hipStream_t)hip_stream;
 
   // Bucket index over the load axis: bucket b covers [b, b+1) / bucket_scale and js[b] is the
@@ -417,6 +421,18 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
       if (d->rho[q] <= x) j = q;
     js[b] = j;
   }
+  // The same buckets seen through the kernels' bucket arithmetic (monotone in x): a grid point
+  // whose bucket is below that of x is below x, one whose bucket is above is above x, and
+  // only a point in x's own bucket has to be compared.
+  std::vector<int32_t> tstart(p->n_bucket + 1, 0);
+  std::vector<double> thr(p->n_bucket + 1, INFINITY);
+  p->single_point = (int)(rho_max * p->bucket_scale) <= p->n_bucket;
+  for (int q = 1; q + 1 < d->n_rho && p->single_point; ++q) {
+    const int b = (int)(d->rho[q] * p->bucket_scale);
+    if (b < 0 || b > p->n_bucket || thr[b] != INFINITY) { p->single_point = false; break; }
+    thr[b] = d->rho[q];
+    for (int c = b + 1; c <= p->n_bucket; ++c) tstart[c] += 1;
+  }
   std::vector<double> gridpack(2 * (size_t)d->n_rho + 3, 0.0);
   gridpack[0] = -INFINITY;
   for (int q = 0; q < d->n_rho; ++q) gridpack[1 + q] = d->rho[q];
@@ -436,6 +452,7 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
             hip_ok(dev_alloc(&p->d_tab, 3 * n_tab), "hipMalloc") && hip_ok(dev_alloc(&p->d_ml, n_row), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_pw0, n_row), "hipMalloc") && hip_ok(dev_alloc(&p->d_gridpack, gridpack.size()), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_jstart, js.size()), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_tstart, tstart.size()), "hipMalloc") && hip_ok(dev_alloc(&p->d_thr, thr.size()), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_cfg, DYN_MAX_CONFIGS), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_tile_rows, 2 * DYN_MAX_CONFIGS + 1024), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_slo_ttft, p->G), "hipMalloc") && hip_ok(dev_alloc(&p->d_slo_tbt, p->G), "hipMalloc") &&
@@ -445,6 +462,8 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
        hip_ok(hipMemcpyAsync(p->d_pw0, pw0.data(), n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_gridpack, gridpack.data(), gridpack.size() * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_jstart, js.data(), js.size() * 4, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_tstart, tstart.data(), tstart.size() * 4, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_thr, thr.data(), thr.size() * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize");
   if (!ok) {
     free_profile_device(p);
@@ -572,17 +591,15 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   if ((rc = prepare_objective(p, o, s)) != DYN_OK) return rc;
 
   char* base = (char*)workspace;
-  // per-tick aggregates: the fine trace's cells are the ticks, so the load of a fine cell is tokens / tick_s
-  if (!hip_ok(dyn_launch_cell_aggregate(t->in_tok, t->out_tok, t->cell_off, t->n_req, fine_cells, t->window_s, o->pct_num,
-                                        o->pct_den, (int64_t*)(base + w.fine.tin), (int64_t*)(base + w.fine.tout),
-                                        (int32_t*)(base + w.fine.in_p99), (CellRec*)(base + w.fine.rec),
-                                        (uint8_t*)(base + w.fine.cstat), (WsHeader*)(base + w.fine.header), s),
-              "cell aggregate launch"))
-    return DYN_E_DEVICE;
-  if (!hip_ok(dyn_launch_tick_top(t->in_tok, t->cell_off, t->n_req, n_window, n_tick, p->G, o->pct_num, o->pct_den,
-                                  (int32_t*)(base + w.top), s),
-              "tick candidates launch"))
-    return DYN_E_DEVICE;
+  TickCellArgs ca;
+  ca.in = t->in_tok; ca.out = t->out_tok; ca.fine_off = t->cell_off; ca.n_req = t->n_req;
+  ca.n_window = n_window; ca.n_tick = n_tick; ca.G = p->G;
+  ca.tick_s = t->window_s; ca.r_tick = 1.0 / t->window_s;
+  ca.pct_num = o->pct_num; ca.pct_den = o->pct_den;
+  ca.rec = (TickRec*)(base + w.fine.rec); ca.top = (int32_t*)(base + w.top);
+  ca.cstat = (uint8_t*)(base + w.fine.cstat); ca.header = (WsHeader*)(base + w.fine.header);
+  ca.merge_count = (uint32_t*)(base + w.merge_count);
+  if (!hip_ok(dyn_launch_tick_cell(ca, s), "tick cell launch")) return DYN_E_DEVICE;
 
   TickArgs ta;
   SpaceArgs& a = ta.s;
@@ -592,15 +609,17 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   a.cfg = p->d_cfg; a.K = K; a.tile = p->tile; a.n_tile = p->n_tile; a.n_slot = p->n_slot;
   a.tile_rows = p->d_tile_rows;
   a.slo_ttft = p->d_slo_ttft; a.slo_tbt = p->d_slo_tbt; a.budget = p->d_budget;
-  a.rec = (const CellRec*)(base + w.fine.rec); a.n_window = n_window; a.window_s = t->window_s;
+  a.rec = nullptr; a.n_window = n_window; a.window_s = t->window_s;
   const int64_t cell_tiles = cells * p->n_tile;
   a.win_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(DYN_MAX_WIN_PER_BLOCK, (cell_tiles + 8191) / 8192));
   a.energy = out->energy_j; a.p99_ttft = out->p99_ttft_ms; a.p99_tbt = out->p99_tbt_ms; a.flags = out->flags;
   a.pw0 = p->d_pw0; a.idle_w = o->idle_cost_weight;
   a.part = (SelPart*)(base + w.part); a.n_wslot = w.n_wslot;
   ta.n_tick = n_tick; ta.tick_s = t->window_s; ta.window_s = (double)n_tick * t->window_s;
-  ta.fine_off = t->cell_off; ta.n_req = t->n_req; ta.top = (const int32_t*)(base + w.top);
-  ta.cstat = (uint8_t*)(base + w.fine.cstat); ta.pct_num = o->pct_num; ta.pct_den = o->pct_den;
+  ta.rec = (const TickRec*)(base + w.fine.rec); ta.top = (const int32_t*)(base + w.top);
+  ta.merge_count = (uint32_t*)(base + w.merge_count); ta.merge_list = (uint32_t*)(base + w.merge_list);
+  ta.tstart = p->d_tstart; ta.thr = p->d_thr; ta.single_point = p->single_point; ta.any_two_rows = p->any_two_rows;
+  ta.pct_num = o->pct_num; ta.pct_den = o->pct_den;
   if (!hip_ok(dyn_launch_tick_space(ta, s), "tick space launch")) return DYN_E_DEVICE;
 
   FinishArgs f;

@@ -58,11 +58,19 @@ struct dyn_profile {
   int32_t* d_jstart;  // [n_bucket + 1]
   int32_t n_bucket;
   double bucket_scale;
+  // the same buckets by what the kernels' own bucket arithmetic b(x) = (int)(x * bucket_scale)
+  // returns: tstart[b] = number of interior grid points (1 .. n_rho-2) whose bucket is below b,
+  // thr[b] = the interior grid point whose bucket is b (+inf if none).  When no bucket holds
+  // two of them (single_point), the bracket of x is tstart[b(x)] + (x >= thr[b(x)]).
+  int32_t* d_tstart;  // [n_bucket + 1]
+  double* d_thr;      // [n_bucket + 1]
+  bool single_point;
   // plan: candidate list
   std::vector<dyn_config> cfg_host;   // what d_cfg currently holds
   DevCfg* d_cfg;                      // [DYN_MAX_CONFIGS]
   int32_t* d_tile_rows;               // [2*DYN_MAX_CONFIGS + 1024]
   int32_t tile, n_tile, n_slot;       // n_slot == 0: table rows are read from global memory
+  bool any_two_rows;                  // some candidate's frequency lies between two profiled ones
   // plan: objective
   std::vector<double> slo_ttft_host, slo_tbt_host;
   std::vector<int32_t> budget_host;
