@@ -114,31 +114,33 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
   double load_l = 0.0;
   uint32_t neg_mask = 0;                        // ticks holding a negative token count
   int32_t* buf = s_buf[wave];
-  // first row of tick 0, then always one tick ahead
-  int64_t beg = readlane_i64(beg_l, 0);
-  int32_t n = __builtin_amdgcn_readlane(cnt_l, 0);
-  int32_t x = lane < n ? a.in[beg + lane] : -1;
-  int32_t y = lane < n ? a.out[beg + lane] : 0;
+  // (x, y) always hold the row after the one being processed: the next row of the same tick,
+  // else the first row of the next tick
+  int32_t x, y;
+  auto fetch = [&](int64_t at, int32_t left) {   // `left` requests from `at` on, one per lane
+    x = lane < left ? a.in[at + lane] : -1;
+    y = lane < left ? a.out[at + lane] : 0;
+  };
+  fetch(readlane_i64(beg_l, 0), __builtin_amdgcn_readlane(cnt_l, 0));
   for (int q = 0; q < T; ++q) {
-    const int64_t beg_q = beg;
-    const int32_t n_q = n;
-    int32_t cx = x, cy = y;
+    const int64_t beg_q = readlane_i64(beg_l, q);
+    const int32_t n_q = __builtin_amdgcn_readlane(cnt_l, q);
+    int64_t beg_n = 0;
+    int32_t n_n = 0;
     if (q + 1 < T) {
-      beg = readlane_i64(beg_l, q + 1);
-      n = __builtin_amdgcn_readlane(cnt_l, q + 1);
-      x = lane < n ? a.in[beg + lane] : -1;
-      y = lane < n ? a.out[beg + lane] : 0;
+      beg_n = readlane_i64(beg_l, q + 1);
+      n_n = __builtin_amdgcn_readlane(cnt_l, q + 1);
     }
+    if (n_q == 0) fetch(beg_n, n_n);              // nothing was fetched for an empty tick
     uint64_t acc = 0;
     uint32_t orv = 0;
     int32_t best = -1;                            // input lengths are >= 0
     for (int32_t r0 = 0; r0 < n_q; r0 += DYN_WAVE) {
       const int nrow = n_q - r0 < DYN_WAVE ? n_q - r0 : DYN_WAVE;
       const bool have = lane < nrow;
-      if (r0 > 0) {
-        cx = have ? a.in[beg_q + r0 + lane] : -1;
-        cy = have ? a.out[beg_q + r0 + lane] : 0;
-      }
+      const int32_t cx = x, cy = y;
+      if (r0 + DYN_WAVE < n_q) fetch(beg_q + r0 + DYN_WAVE, n_q - r0 - DYN_WAVE);
+      else fetch(beg_n, n_n);
       acc += have ? (uint64_t)((int64_t)cx + (int64_t)cy) : 0;
       orv |= have ? (uint32_t)(cx | cy) : 0u;
       if (keep == 0) continue;
@@ -547,7 +549,7 @@ __device__ __forceinline__ void emit_cell(const SpaceArgs& sa, const CfgState& s
 //      [per window of the block, per tick: load] [the same: request count] [per window: plan]
 //      [two buffers of candidate lists, [position][tick]] [bucket index (16-bit)]
 template <bool LDS, bool SINGLE, bool TWO>
-__global__ __launch_bounds__(DYN_MAX_TILE) void tick_space_kernel(TickArgs a) {
+__global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4, 4))) void tick_space_kernel(TickArgs a) {
   constexpr int NPRE = kFastDepth * DYN_TICK_MAX / DYN_WAVE;   // blocks have at least 64 threads
   extern __shared__ double smem[];
   const SpaceArgs& sa = a.s;
@@ -686,7 +688,11 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_merge_kernel(TickArgs a) {
     }
     double e, p_ttft, p_tbt;
     bool ov;
-    walk_ticks_merge<DYN_TICK_MAX, SINGLE, TWO>(st.L, T, j, s_load, s_cnt, s_top, st.nd, a.tick_s, &e, &p_ttft, &p_tbt, &ov);
+    // the ticks are unrolled: take the smallest instance that holds them (block-uniform)
+    if (T <= 4) walk_ticks_merge<4, SINGLE, TWO>(st.L, T, j, s_load, s_cnt, s_top, st.nd, a.tick_s, &e, &p_ttft, &p_tbt, &ov);
+    else if (T <= 8) walk_ticks_merge<8, SINGLE, TWO>(st.L, T, j, s_load, s_cnt, s_top, st.nd, a.tick_s, &e, &p_ttft, &p_tbt, &ov);
+    else if (T <= 12) walk_ticks_merge<12, SINGLE, TWO>(st.L, T, j, s_load, s_cnt, s_top, st.nd, a.tick_s, &e, &p_ttft, &p_tbt, &ov);
+    else walk_ticks_merge<DYN_TICK_MAX, SINGLE, TWO>(st.L, T, j, s_load, s_cnt, s_top, st.nd, a.tick_s, &e, &p_ttft, &p_tbt, &ov);
     emit_cell(sa, st, cell, false, ov, e, p_ttft, p_tbt);
   }
 }

@@ -229,3 +229,44 @@ def test_argument_errors(dyn):
     torch.cuda.synchronize()
     assert np.isfinite(space["energy_j"].cpu().numpy()).all()
     prof.free()
+
+
+def test_full_size_day_trace_sampled_windows(dyn):
+    """The one-day workload at full size (10^7 requests, 36000 cells x 576 configurations, 12 ticks of 5 s
+    per window) in the launch configuration the benchmark's --ticks mode times.  The oracle evaluates
+    three runs of windows (start, the evening peak with the deepest percentiles, end), each as a trace of
+    its own; the rest is checked through properties that hold at any size."""
+    w = make(SPECS[2])
+    T = 12
+    NW, G, K = w["n_window"], w["n_class"], w["configs"]["n_inst"].size
+    g, fine = gpu_ticks(dyn, w, T)
+    assert g["status"] == 0
+    off = fine["cell_off"]
+    assert off[0] == 0 and off[-1] == w["trace"]["t_s"].size and (np.diff(off) >= 0).all()
+    m = np.diff(off).reshape(NW, T, G).sum(axis=1)
+    peak = int(np.argmax(m.sum(axis=1)))
+    for wa in (0, max(0, min(NW - 6, peak - 3)), NW - 6):
+        wb = wa + 6
+        lo, hi = wa * T * G, wb * T * G
+        sub = {"in_tok": fine["in_tok"][off[lo]:off[hi]], "out_tok": fine["out_tok"][off[lo]:off[hi]],
+               "cell_off": off[lo:hi + 1] - off[lo]}
+        o = oracle.evaluate_ticks(w["profile"], sub, wb - wa, T, w["window_s"] / T, w["configs"], w["slos"], w["pct"],
+                                  None, w["idle_cost_weight"])
+        for k in KEYS:
+            np.testing.assert_array_equal(g[k][wa * G:wb * G], o[k], err_msg=f"{k} windows {wa}..{wb}")
+        we, wi = oracle.window_totals(o["sel"], o["sel_energy_j"], wb - wa, G)
+        np.testing.assert_array_equal(g["window_energy_j"][wa:wb], we)
+        np.testing.assert_array_equal(g["window_infeasible"][wa:wb], wi)
+    j = m - np.ceil(99 * m / 100) + 1
+    assert j.max() > 16, "the workload is meant to reach the merge path"
+    feas = (g["flags"] & 1).astype(bool)
+    sel = g["sel"]
+    has = sel >= 0
+    assert (feas.any(axis=1) == has).all()
+    masked = np.where(feas, g["energy_j"], np.inf)              # idle_cost_weight is 0 for this workload
+    assert w["idle_cost_weight"] == 0.0
+    np.testing.assert_array_equal(masked.argmin(axis=1)[has], sel[has])
+    np.testing.assert_array_equal(masked.min(axis=1)[has], g["sel_energy_j"][has])
+    assert ((g["flags"] & dyn.DYN_F_EMPTY) != 0).all(axis=1).tolist() == (m.reshape(-1) == 0).tolist()
+    # a window's energy under tick-level load: never below the least energy any configuration has at zero load
+    assert np.isfinite(g["energy_j"]).all() and (g["energy_j"] > 0).all()
