@@ -141,6 +141,43 @@ def evaluate_ticks(profile: Dict[str, np.ndarray], fine_trace: Dict[str, np.ndar
     return r
 
 
+def mixed(profile: Dict[str, np.ndarray], sorted_trace: Dict[str, np.ndarray], n_window: int, window_s: float,
+          n_share: int, n_max, slos: Dict[str, np.ndarray], pct=(99, 100),
+          gpu_budget: Optional[np.ndarray] = None, want_types: bool = False) -> Dict[str, np.ndarray]:
+    """Mixed pools (Eq. 1 in full): least-energy assignment of instances, frequencies and load shares per cell."""
+    lib = _load()
+    lib.dynoracle_mixed.restype = C.c_int
+    tp = _c(profile["tp"], np.int32); fg = _c(profile["f_mhz"], np.float64)
+    rg = _c(profile["rho"], np.float64)
+    PF = _c(profile["prefill_ms_per_tok"], np.float64); TB = _c(profile["tbt_ms"], np.float64)
+    PW = _c(profile["power_w"], np.float64); ML = _c(profile["max_load_tps"], np.float64)
+    G = PF.shape[0]
+    ins = _c(sorted_trace["in_tok"], np.int32); outs = _c(sorted_trace["out_tok"], np.int32)
+    off = _c(sorted_trace["cell_off"], np.int64)
+    assert off.size == n_window * G + 1
+    nm = _c(n_max, np.int32)
+    assert nm.size == tp.size
+    st = _c(slos["slo_ttft_ms"], np.float64); sb = _c(slos["slo_tbt_ms"], np.float64)
+    bud = None if gpu_budget is None else _c(gpu_budget, np.int32)
+    cells = n_window * G
+    n_entry = int(nm.sum()) * n_share
+    r = {"energy_j": np.empty(cells), "n_inst": np.empty((cells, tp.size), np.int32),
+         "f_index": np.empty((cells, tp.size), np.int32), "share": np.empty((cells, tp.size), np.int32),
+         "n_optimal": np.empty(cells, np.int64)}
+    if want_types:
+        r["type_energy"] = np.empty((cells, n_entry)); r["type_f"] = np.empty((cells, n_entry), np.int32)
+    rc = lib.dynoracle_mixed(
+        C.c_int32(G), C.c_int32(tp.size), _ptr(tp), C.c_int32(fg.size), _ptr(fg), C.c_int32(rg.size), _ptr(rg),
+        _ptr(PF), _ptr(TB), _ptr(PW), _ptr(ML),
+        C.c_int64(ins.size), C.c_int32(n_window), C.c_double(window_s), _ptr(ins), _ptr(outs), _ptr(off),
+        C.c_int32(n_share), _ptr(nm), _ptr(st), _ptr(sb), C.c_int32(pct[0]), C.c_int32(pct[1]), _ptr(bud),
+        _ptr(r["energy_j"]), _ptr(r["n_inst"]), _ptr(r["f_index"]), _ptr(r["share"]), _ptr(r["n_optimal"]),
+        _ptr(r.get("type_energy")), _ptr(r.get("type_f")))
+    if rc != 0:
+        raise ValueError(f"dynoracle_mixed failed: {rc}")
+    return r
+
+
 def window_totals(sel: np.ndarray, sel_energy_j: np.ndarray, n_window: int, n_class: int):
     lib = _load()
     s = _c(sel, np.int32); e = _c(sel_energy_j, np.float64)

@@ -411,6 +411,152 @@ int dynoracle_eval_ticks(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f
   return ORC_OK;
 }
 
+// Pools that mix instance types (Eq. 1 in full): per (window, class) cell choose how many
+// instances of every tensor parallelism run (N^TP), at which frequency (f^TP) and which part
+// of the load each type takes (L^TP), so that the total energy is least while the GPUs used
+// stay within the budget, the assigned loads add up to the pool's load and every type that is
+// used meets the SLO under its load.
+// Readings: the load is split in n_share equal shares, type i takes a_i of them (a_i >= 1
+// exactly when the type is used, sum a_i = n_share) and its n_i instances share that part
+// equally (fair share, as for Eq. 1): per-instance load = (L * a_i / n_share) / n_i; the
+// frequencies are the profiled ones; every type serves requests of the whole cell, so the
+// percentiles of a type are taken over all requests of the cell under that type's tables;
+// total energy = 0 + E_0 + E_1 + ... over the used types in type order, E_i = n_i x power x
+// window; the budget of a class (0 = none) bounds sum n_i x tp_i.
+// The frequency of a type is chosen as the instance manager does it (Section IV-B
+// "Scale-up/down"): drop the frequencies that violate the SLO or leave the profiled load
+// range, then take the least energy (lowest frequency index on ties); this is independent
+// of the other types, so the search enumerates (n_i, a_i) for every type and adds the
+// types' least energies.  Options of a type are visited as "unused", then n ascending, a
+// ascending, types nested in index order; the first assignment of least energy is kept and
+// n_optimal counts the assignments that reach it.
+// type_energy (may be null): [cells][sum_i n_max_i * n_share] the per-type least energies,
+// entry (i, n, a) at offset(i) + (n-1)*n_share + (a-1), +inf if no frequency is admissible;
+// type_f the chosen frequency index (-1 if none).
+int dynoracle_mixed(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f, const double* fg,
+                    int32_t n_rho, const double* rg, const double* PF, const double* TB,
+                    const double* PW, const double* ML,
+                    int64_t n_req, int32_t n_window, double window_s, const int32_t* in_tok,
+                    const int32_t* out_tok, const int64_t* cell_off,
+                    int32_t n_share, const int32_t* n_max,
+                    const double* slo_ttft, const double* slo_tbt, int32_t pct_num, int32_t pct_den,
+                    const int32_t* gpu_budget,
+                    double* energy_j, int32_t* n_inst, int32_t* f_index, int32_t* share,
+                    int64_t* n_optimal, double* type_energy, int32_t* type_f) {
+  if (!tp || !fg || !rg || !PF || !TB || !PW || !ML || !cell_off || !n_max || !slo_ttft || !slo_tbt ||
+      !energy_j || !n_inst || !f_index || !share)
+    return ORC_E_NULL;
+  if (n_req > 0 && (!in_tok || !out_tok)) return ORC_E_NULL;
+  if (G < 1 || n_tp < 1 || n_f < 1 || n_rho < 2 || n_window < 1 || n_share < 1) return ORC_E_SHAPE;
+  if (!(window_s > 0.0) || pct_num < 1 || pct_den < 1 || pct_num > pct_den) return ORC_E_RANGE;
+  if (!increasing(fg, n_f) || !increasing(rg, n_rho) || rg[0] != 0.0) return ORC_E_ORDER;
+  int64_t n_entry = 0;
+  std::vector<int64_t> off(n_tp);
+  for (int i = 0; i < n_tp; ++i) {
+    if (n_max[i] < 0 || tp[i] < 1) return ORC_E_RANGE;
+    off[i] = n_entry;
+    n_entry += (int64_t)n_max[i] * n_share;
+  }
+  const int64_t cells = (int64_t)n_window * G;
+  const double INF = std::numeric_limits<double>::infinity();
+  auto tab = [&](const double* X, int g, int ti, int f, int j) -> double {
+    return X[(((int64_t)g * n_tp + ti) * n_f + f) * n_rho + j];
+  };
+  std::vector<double> lat, C((size_t)n_entry);
+  std::vector<int32_t> F((size_t)n_entry);
+  std::vector<int32_t> cur_n(n_tp), cur_a(n_tp), best_n(n_tp), best_a(n_tp);
+  for (int64_t c = 0; c < cells; ++c) {
+    const int g = (int)(c % G);
+    const int64_t beg = cell_off[c], end = cell_off[c + 1];
+    if (beg < 0 || end < beg || end > n_req) return ORC_E_ORDER;
+    const int64_t m = end - beg;
+    int64_t tin = 0, tout = 0;
+    for (int64_t r = beg; r < end; ++r) { tin += in_tok[r]; tout += out_tok[r]; }
+    const double L = (double)(tin + tout) / window_s;
+    const int64_t rank = (m > 0) ? ((int64_t)pct_num * m + pct_den - 1) / pct_den : 0;
+
+    // least energy of every (type, instances, shares) over the admissible frequencies
+    for (int i = 0; i < n_tp; ++i)
+      for (int n = 1; n <= n_max[i]; ++n)
+        for (int a = 1; a <= n_share; ++a) {
+          double best = INF;
+          int32_t bf = -1;
+          const double Ls = (L * (double)a) / (double)n_share;
+          for (int f = 0; f < n_f; ++f) {
+            const double ml = ML[((int64_t)g * n_tp + i) * n_f + f];
+            const double rho = Ls / ((double)n * ml);
+            const bool ov = rho > rg[n_rho - 1];
+            const double rc = ov ? rg[n_rho - 1] : rho;
+            const int j = bracket(rg, n_rho, rc);
+            const double t = (rc - rg[j]) / (rg[j + 1] - rg[j]);
+            const double pf = (1.0 - t) * tab(PF, g, i, f, j) + t * tab(PF, g, i, f, j + 1);
+            const double tb = (1.0 - t) * tab(TB, g, i, f, j) + t * tab(TB, g, i, f, j + 1);
+            const double pw = (1.0 - t) * tab(PW, g, i, f, j) + t * tab(PW, g, i, f, j + 1);
+            const double E = ((double)n * pw) * window_s;
+            double p_ttft = 0.0, p_tbt = 0.0;
+            if (m > 0) {
+              lat.resize((size_t)m);
+              for (int64_t r = 0; r < m; ++r) lat[(size_t)r] = (double)in_tok[beg + r] * pf;
+              std::nth_element(lat.begin(), lat.begin() + (rank - 1), lat.end());
+              p_ttft = lat[(size_t)(rank - 1)];
+              p_tbt = tb;
+            }
+            const bool ok = !ov && !(p_ttft > slo_ttft[g]) && !(p_tbt > slo_tbt[g]);
+            if (ok && (bf < 0 || E < best)) { best = E; bf = f; }
+          }
+          const int64_t e = off[i] + (int64_t)(n - 1) * n_share + (a - 1);
+          C[(size_t)e] = best;
+          F[(size_t)e] = bf;
+          if (type_energy) type_energy[c * n_entry + e] = best;
+          if (type_f) type_f[c * n_entry + e] = bf;
+        }
+
+    // every assignment of instances and shares to the types
+    double best_e = INF;
+    int64_t n_best = 0;
+    const int64_t budget = (gpu_budget && gpu_budget[g] > 0) ? gpu_budget[g] : -1;
+    // iterative nested loops over the types: position i holds option index o_i in
+    // [0, n_max_i * n_share]: 0 = unused, else n = (o-1)/n_share + 1, a = (o-1)%n_share + 1
+    std::vector<int64_t> opt(n_tp, 0);
+    while (true) {
+      int64_t a_sum = 0, gpus = 0;
+      bool fin = true;
+      double E = 0.0;
+      for (int i = 0; i < n_tp; ++i) {
+        if (opt[i] == 0) { cur_n[i] = 0; cur_a[i] = 0; continue; }
+        cur_n[i] = (int32_t)((opt[i] - 1) / n_share + 1);
+        cur_a[i] = (int32_t)((opt[i] - 1) % n_share + 1);
+        a_sum += cur_a[i];
+        gpus += (int64_t)cur_n[i] * tp[i];
+        const double ci = C[(size_t)(off[i] + opt[i] - 1)];
+        if (!(ci < INF)) fin = false;
+        E += ci;
+      }
+      if (fin && a_sum == n_share && (budget < 0 || gpus <= budget)) {
+        if (E < best_e) { best_e = E; n_best = 1; best_n = cur_n; best_a = cur_a; }
+        else if (E == best_e) ++n_best;
+      }
+      // next assignment: the last type varies fastest
+      int i = n_tp - 1;
+      while (i >= 0) {
+        if (opt[i] < (int64_t)n_max[i] * n_share) { ++opt[i]; break; }
+        opt[i] = 0;
+        --i;
+      }
+      if (i < 0) break;
+    }
+    energy_j[c] = best_e;
+    if (n_optimal) n_optimal[c] = n_best;
+    for (int i = 0; i < n_tp; ++i) {
+      const bool used = n_best > 0 && best_n[i] > 0;
+      n_inst[c * n_tp + i] = used ? best_n[i] : 0;
+      share[c * n_tp + i] = used ? best_a[i] : 0;
+      f_index[c * n_tp + i] = used ? F[(size_t)(off[i] + (int64_t)(best_n[i] - 1) * n_share + (best_a[i] - 1))] : -1;
+    }
+  }
+  return ORC_OK;
+}
+
 // Objective summed over the pools of a window (Eq. 1 sums over instance types; here one
 // pool per class), classes added in index order; cells without a feasible configuration
 // are counted, not added.

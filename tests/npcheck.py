@@ -149,3 +149,62 @@ def np_eval_ticks(profile, fine, n_window, n_tick, tick_s, configs, slos, pct=(9
                     best, best_cost = k, cost
             out["sel"][c] = best
     return out
+
+
+def np_mixed(profile, st, n_window, window_s, n_share, n_max, slos, pct=(99, 100), gpu_budget=None):
+    """Eq. 1 by brute force: every (instances, frequency, shares) of every type at once, nothing factored."""
+    import itertools
+    tp = profile["tp"]; fg = profile["f_mhz"]; rg = profile["rho"]
+    PF, TB, PW, ML = (profile[k] for k in ("prefill_ms_per_tok", "tbt_ms", "power_w", "max_load_tps"))
+    G = PF.shape[0]
+    off = st["cell_off"]
+    cells = n_window * G
+    energy = np.full(cells, np.inf)
+    pick = [None] * cells
+    n_opt = np.zeros(cells, np.int64)
+    options = []
+    for i in range(tp.size):
+        o = [None]
+        o += [(n, f, a) for n in range(1, int(n_max[i]) + 1) for f in range(fg.size) for a in range(1, n_share + 1)]
+        options.append(o)
+    for c in range(cells):
+        g = c % G
+        x = st["in_tok"][off[c]:off[c + 1]].astype(np.int64)
+        y = st["out_tok"][off[c]:off[c + 1]].astype(np.int64)
+        m = x.size
+        load = float(Fraction(int(x.sum() + y.sum())) / Fraction(float(window_s)))
+        rank = int(math.ceil(Fraction(pct[0] * m, pct[1])))
+        # per type option: (energy, admissible)
+        val = []
+        for i in range(tp.size):
+            v = {}
+            for o in options[i][1:]:
+                n, f, a = o
+                rho = load * a / n_share / (n * ML[g, i, f])
+                r = min(rho, rg[-1])
+                pf, tb, pw = (float(np.interp(r, rg, X[g, i, f])) for X in (PF, TB, PW))
+                ttft = float(np.sort(x * pf)[rank - 1]) if m else 0.0
+                ok = rho <= rg[-1] and ttft <= slos["slo_ttft_ms"][g] and (tb if m else 0.0) <= slos["slo_tbt_ms"][g]
+                v[o] = (n * pw * window_s, ok)
+            val.append(v)
+        best = []
+        for combo in itertools.product(*options):
+            used = [(i, o) for i, o in enumerate(combo) if o is not None]
+            if sum(o[2] for _, o in used) != n_share:
+                continue
+            if gpu_budget is not None and gpu_budget[g] > 0 and sum(o[0] * int(tp[i]) for i, o in used) > gpu_budget[g]:
+                continue
+            if not all(val[i][o][1] for i, o in used):
+                continue
+            e = 0.0
+            for i, o in used:
+                e += val[i][o][0]
+            best.append((e, combo))
+        if best:
+            emin = min(e for e, _ in best)
+            energy[c] = emin
+            # distinct (instances, shares) assignments reaching the minimum (the frequency is a dependent choice)
+            keys = {tuple((o[0], o[2]) if o else (0, 0) for o in cb) for e, cb in best if e == emin}
+            n_opt[c] = len(keys)
+            pick[c] = sorted(keys)
+    return {"energy_j": energy, "assignments": pick, "n_optimal": n_opt}

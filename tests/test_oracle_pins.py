@@ -465,6 +465,150 @@ def test_ticks_single_busy_tick_reduces_to_that_tick():
     np.testing.assert_allclose(t["energy_j"], only["energy_j"] + 5 * idle["energy_j"], rtol=1e-13)
 
 
+# ---------------------------------------------------------------- mixed pools (Eq. 1 in full)
+def test_mixed_search_reproduces_bold_cells_of_paper_tables(golden_dir):
+    """One instance of each type at most and one share: the search must land on the printed least-energy
+    cell among the non-grey ones, with that cell's energy."""
+    n = 0
+    for line in open(os.path.join(golden_dir, "paper_energy_tables.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        _tab, _label, vals, bold = [s.strip() for s in line.split(";")]
+        vals = vals.split()
+        grey = np.asarray([v == "-" for v in vals]).reshape(1, 3, 4)
+        wh = np.asarray([float(v) if v != "-" else 0.01 for v in vals]).reshape(1, 3, 4)   # grey cells look cheap
+        PW = np.repeat(wh[..., None], 2, axis=-1)
+        TB = np.repeat(np.where(grey, 500.0, 50.0)[..., None], 2, axis=-1)               # grey = SLO violated
+        prof = _profile([2, 4, 8], [800, 1200, 1600, 2000], [0.0, 1.0], np.full((1, 3, 4, 2), 0.01), TB, PW,
+                        np.full((1, 3, 4), 1e9))
+        st = _one_cell([100, 200], [10, 20])
+        slo = {"slo_ttft_ms": np.asarray([1e9]), "slo_tbt_ms": np.asarray([100.0])}
+        r = oracle.mixed(prof, st, 1, 1.0, 1, [1, 1, 1], slo)
+        ti, fi = divmod(int(bold), 4)
+        assert r["n_inst"][0].tolist() == [1 if i == ti else 0 for i in range(3)], (_tab, _label)
+        assert r["f_index"][0, ti] == fi and r["share"][0, ti] == 1
+        np.testing.assert_allclose(r["energy_j"][0], float(vals[int(bold)]), rtol=1e-14)   # (1-t) v + t v
+        n += 1
+    assert n == 18
+
+
+def _forced_mix():
+    # two types, one frequency, load grid {0, 1}: power and TBT linear in the per-instance load
+    PW = np.asarray([[[[100.0, 200.0]], [[300.0, 360.0]]]])
+    TB = np.asarray([[[[10.0, 20.0]], [[10.0, 110.0]]]])
+    prof = _profile([2, 4], [1000], [0.0, 1.0], np.full((1, 2, 1, 2), 0.001), TB, PW, np.asarray([[[100.0], [300.0]]]))
+    st = _one_cell([100, 100], [50, 150])               # 400 tokens in 2 s: L = 200 tokens/s
+    slo = {"slo_ttft_ms": np.asarray([1e9]), "slo_tbt_ms": np.asarray([30.0])}
+    return prof, st, slo
+
+
+def test_mixed_hand_worked_example():
+    """L = 200 tok/s in 4 shares of 50.  Type 0 (TP2, 100 tok/s per instance): E = (100 n + 50 a) W, needs
+    a <= 2 n.  Type 1 (TP4, 300 tok/s): E = (300 n + 10 a) W, TBT = 10 + 100 a/(6 n) <= 30 needs a <= 1.2 n."""
+    prof, st, slo = _forced_mix()
+    W = 2.0
+    # enough of everything: type 0 alone with two instances (400 W) beats every mix and type 1 alone (needs 4: 1240 W)
+    r = oracle.mixed(prof, st, 1, W, 4, [4, 4], slo)
+    assert r["n_inst"][0].tolist() == [2, 0] and r["share"][0].tolist() == [4, 0] and r["f_index"][0].tolist() == [0, -1]
+    np.testing.assert_allclose(r["energy_j"][0], 400.0 * W, rtol=1e-14)
+    assert r["n_optimal"][0] == 1
+    # one TP2 instance at most: it can carry two shares; the other two need two TP4 instances (a <= 1.2 n)
+    r = oracle.mixed(prof, st, 1, W, 4, [1, 2], slo)
+    assert r["n_inst"][0].tolist() == [1, 2] and r["share"][0].tolist() == [2, 2] and r["f_index"][0].tolist() == [0, 0]
+    np.testing.assert_allclose(r["energy_j"][0], (200.0 + 620.0) * W, rtol=1e-14)
+    # a budget of 8 GPUs rules that out (2 + 8 = 10 GPUs) and nothing else carries the load
+    r = oracle.mixed(prof, st, 1, W, 4, [1, 2], slo, gpu_budget=np.asarray([8], np.int32))
+    assert np.isinf(r["energy_j"][0]) and r["n_inst"][0].tolist() == [0, 0] and r["f_index"][0].tolist() == [-1, -1]
+    assert r["n_optimal"][0] == 0
+    # four TP4 instances allowed and no TP2: a = 4 needs n >= 4 (a <= 1.2 n)
+    r = oracle.mixed(prof, st, 1, W, 4, [0, 4], slo)
+    assert r["n_inst"][0].tolist() == [0, 4] and r["share"][0].tolist() == [0, 4]
+    np.testing.assert_allclose(r["energy_j"][0], 1240.0 * W, rtol=1e-14)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_mixed_against_full_brute_force(seed):
+    """Nothing factored: every (instances, frequency, shares) of every type in one product, NumPy arithmetic."""
+    rng = np.random.default_rng(900 + seed)
+    n_tp, n_f, n_rho, G = 2 + seed % 2, 1 + seed % 3, 3, 2
+    fg = np.sort(rng.uniform(500, 2000, n_f)); rg = np.concatenate([[0.0], np.sort(rng.uniform(0.1, 0.95, n_rho - 1))])
+    shape = (G, n_tp, n_f, n_rho)
+    prof = _profile([2, 4, 8][:n_tp], fg, rg, rng.uniform(0.05, 0.3, shape), np.sort(rng.uniform(10, 150, shape), axis=-1),
+                    np.sort(rng.uniform(100, 3000, shape), axis=-1), rng.uniform(200, 900, shape[:3]))
+    R, NW, W = 60, 2, 10.0
+    tr = {"t_s": rng.uniform(0, NW * W, R), "in_tok": rng.integers(1, 400, R).astype(np.int32),
+          "out_tok": rng.integers(1, 200, R).astype(np.int32), "model": np.zeros(R, np.int32)}
+    tr["t_s"][tr["t_s"] > 15.0] = 1.0                      # window 1 nearly empty for class mix
+    edges = {"in_edge": np.asarray([[150]], np.int32), "out_edge": np.zeros((1, 0), np.int32)}
+    slo = {"slo_ttft_ms": rng.uniform(40, 120, G), "slo_tbt_ms": rng.uniform(60, 140, G)}
+    bud = np.asarray([0, 10], np.int32)
+    n_max = [2, 2, 1][:n_tp]
+    S = 3
+    st = oracle.ingest(tr, edges, NW, W)
+    a = oracle.mixed(prof, st, NW, W, S, n_max, slo, (99, 100), bud)
+    b = npcheck.np_mixed(prof, npcheck.np_ingest(tr, edges, NW, W), NW, W, S, n_max, slo, (99, 100), bud)
+    fin = np.isfinite(b["energy_j"])
+    assert (np.isfinite(a["energy_j"]) == fin).all() and fin.any()
+    np.testing.assert_allclose(a["energy_j"][fin], b["energy_j"][fin], rtol=1e-12)
+    for c in np.nonzero(fin)[0]:
+        assert tuple(zip(a["n_inst"][c].tolist(), a["share"][c].tolist())) in b["assignments"][c]
+    np.testing.assert_array_equal(a["n_optimal"][fin], b["n_optimal"][fin])
+
+
+def test_mixed_with_one_share_is_the_best_single_type(small_hour):
+    """All load on one type: the search is the window-level selection over (instances, TP, profiled f)."""
+    w, st, _ = small_hour
+    prof = w["profile"]
+    n_max = [6] * prof["tp"].size
+    cfg = _configs([(n, ti, f) for ti in range(prof["tp"].size) for n in range(1, 7) for f in prof["f_mhz"]])
+    bud = np.full(w["n_class"], 16, np.int32)
+    a = oracle.mixed(prof, st, w["n_window"], w["window_s"], 1, n_max, w["slos"], w["pct"], bud)
+    b = oracle.evaluate(prof, st, w["n_window"], w["window_s"], cfg, w["slos"], w["pct"], bud, 0.0)
+    np.testing.assert_array_equal(a["energy_j"], b["sel_energy_j"])
+    has = b["sel"] >= 0
+    assert has.any()
+    k = b["sel"][has]
+    ti = cfg["tp_index"][k]
+    rows = np.nonzero(has)[0]
+    uniq = a["n_optimal"][rows] == 1
+    np.testing.assert_array_equal(a["n_inst"][rows, ti][uniq], cfg["n_inst"][k][uniq])
+    assert (a["n_inst"][~has] == 0).all() and (a["f_index"][~has] == -1).all()
+
+
+def test_mixed_invariants(small_hour):
+    w, st, _ = small_hour
+    prof = w["profile"]
+    T = prof["tp"].size
+    S = 4
+    base = oracle.mixed(prof, st, w["n_window"], w["window_s"], S, [3] * T, w["slos"], w["pct"], None, want_types=True)
+    used = base["n_inst"] > 0
+    fin = np.isfinite(base["energy_j"])
+    assert fin.any()
+    assert (base["share"][fin].sum(axis=1) == S).all() and ((base["share"] > 0) == used).all()
+    assert ((base["f_index"] >= 0) == used).all()
+    # the optimum is the sum of its types' table entries, added in type order from zero
+    offs = np.concatenate([[0], np.cumsum([3 * S] * T)])
+    for c in np.nonzero(fin)[0][:200]:
+        e = 0.0
+        for i in range(T):
+            if base["n_inst"][c, i]:
+                ent = offs[i] + (base["n_inst"][c, i] - 1) * S + base["share"][c, i] - 1
+                e += base["type_energy"][c, ent]
+                assert base["type_f"][c, ent] == base["f_index"][c, i]
+        assert e == base["energy_j"][c]
+    # more instances allowed / a looser budget never cost more; a single type never beats the mix
+    more = oracle.mixed(prof, st, w["n_window"], w["window_s"], S, [4] * T, w["slos"], w["pct"], None)
+    assert (more["energy_j"] <= base["energy_j"]).all()
+    tight = oracle.mixed(prof, st, w["n_window"], w["window_s"], S, [3] * T, w["slos"], w["pct"],
+                         np.full(w["n_class"], 8, np.int32))
+    assert (tight["energy_j"] >= base["energy_j"]).all()
+    assert ((tight["n_inst"] * prof["tp"][None, :]).sum(axis=1) <= 8).all()
+    for i in range(T):
+        only = [3 if q == i else 0 for q in range(T)]
+        one = oracle.mixed(prof, st, w["n_window"], w["window_s"], S, only, w["slos"], w["pct"], None)
+        assert (one["energy_j"] >= base["energy_j"]).all()
+
+
 # ----------------------------------------------------------- planted mistakes are caught
 def test_pins_catch_planted_mistakes():
     """Sanity of the pins themselves: perturbing the inputs the way a typical slip would
