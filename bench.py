@@ -48,14 +48,20 @@ def recorded_traffic(workload_index):
     return None
 
 
-def cpu_baseline(w, n_sample_windows, ticks=0):
+def cpu_baseline(w, n_sample_windows, ticks=0, mixed=None):
     """The CPU oracle, as it stands, on the first windows of the same workload (one thread)."""
     import numpy as np
     import oracle
     tr = w["trace"]
     hi = int(np.searchsorted(tr["t_s"], n_sample_windows * w["window_s"]))
     sub = {k: v[:hi] for k, v in tr.items()}
-    if ticks:
+    k = w["configs"]["n_inst"].size
+    if mixed:
+        n_share, n_max, budget, k = mixed
+        st = oracle.ingest(sub, w["edges"], n_sample_windows, w["window_s"])
+        t0 = time.perf_counter()
+        oracle.mixed(w["profile"], st, n_sample_windows, w["window_s"], n_share, n_max, w["slos"], w["pct"], budget)
+    elif ticks:
         st = oracle.ingest(sub, w["edges"], n_sample_windows * ticks, w["window_s"] / ticks)
         t0 = time.perf_counter()
         oracle.evaluate_ticks(w["profile"], st, n_sample_windows, ticks, w["window_s"] / ticks, w["configs"], w["slos"],
@@ -66,7 +72,6 @@ def cpu_baseline(w, n_sample_windows, ticks=0):
         oracle.evaluate(w["profile"], st, n_sample_windows, w["window_s"], w["configs"], w["slos"], w["pct"], None,
                         w["idle_cost_weight"], want_space=False)
     dt = time.perf_counter() - t0
-    k = w["configs"]["n_inst"].size
     return {"value": hi * k / dt, "unit": "evals/s", "cores": 1, "kind": "oracle",
             "sample": f"first {n_sample_windows} of {w['n_window']} windows ({hi} requests x {k} configurations, "
                       f"{dt:.1f} s, single thread)"}
@@ -82,6 +87,10 @@ def main():
     ap.add_argument("--ticks", type=int, default=0,
                     help="tick-level variant: split every window into this many ticks (dyn_eval_select_ticks); "
                          "0 = the window-level headline path")
+    ap.add_argument("--mixed", type=int, default=0,
+                    help="mixed-pool search (dyn_eval_select_mixed) with this many load shares; per type up to "
+                         "--mixed-gpus / TP instances, and a budget of --mixed-gpus GPUs per class")
+    ap.add_argument("--mixed-gpus", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events (roofline.achieved is then null)")
@@ -154,7 +163,23 @@ def main():
     ws = torch.empty(dyn.dyn_eval_ticks_workspace(NW, T, G, K) if args.ticks else dyn.dyn_eval_space_workspace(NW, G, K),
                      dtype=torch.uint8, device="cuda")
 
-    if args.ticks:
+    if args.mixed:
+        assert not args.ticks, "--mixed and --ticks are separate modes"
+        tp = w["profile"]["tp"]
+        n_max = [max(1, args.mixed_gpus // int(t)) for t in tp]
+        mplan = dyn.MixedPlan(args.mixed, n_max, w["slos"], w["pct"], np.full(G, args.mixed_gpus, np.int32))
+        ws = torch.empty(dyn.dyn_mixed_workspace(prof, NW, mplan), dtype=torch.uint8, device="cuda")
+        msel = {"energy_j": torch.empty(cells, dtype=torch.float64, device="cuda"),
+                "n_inst": torch.empty((cells, tp.size), dtype=torch.int32, device="cuda"),
+                "f_index": torch.empty((cells, tp.size), dtype=torch.int32, device="cuda"),
+                "share": torch.empty((cells, tp.size), dtype=torch.int32, device="cuda"),
+                "window_energy_j": sel["window_energy_j"], "window_infeasible": sel["window_infeasible"]}
+        n_entry = int(sum(n_max)) * args.mixed
+        K = n_entry * int(w["profile"]["f_mhz"].size)     # (type, instances, shares, frequency) evaluated per cell
+
+        def step():
+            dyn.dyn_eval_select_mixed(prof, ins, outs, off, NW, w["window_s"], mplan, out=msel, workspace=ws)
+    elif args.ticks:
         def step():
             dyn.dyn_eval_select_ticks(prof, ins, outs, off, NW, T, len_s, plan, out=space, sel=sel, workspace=ws)
     elif args.unfused:
@@ -183,7 +208,8 @@ def main():
     # ---- the same `steps` steps again with the library's per-kernel HIP events switched on (recorded
     # on the stream the kernels are launched on).  The event records themselves cost about 20 us per
     # step on this machine, which is why they are kept out of the throughput region above.
-    ktime = {"cell": 0.0, "space": 0.0, "select": 0.0, "totals": 0.0, "tick_top": 0.0, "tick_space": 0.0, "tick_merge": 0.0}
+    ktime = {"cell": 0.0, "space": 0.0, "select": 0.0, "totals": 0.0, "tick_top": 0.0, "tick_space": 0.0, "tick_merge": 0.0,
+             "mixed_types": 0.0, "mixed_combine": 0.0}
     ms_per_step_events = None
     if not args.no_kernel_events:
         dyn.dyn_timing_enable(True, args.steps)
@@ -195,7 +221,8 @@ def main():
         ms_per_step_events = (time.perf_counter() - t0) / args.steps * 1e3
         for name, kid in (("cell", dyn.DYN_K_CELL), ("space", dyn.DYN_K_SPACE), ("select", dyn.DYN_K_SELECT),
                           ("totals", dyn.DYN_K_TOTALS), ("tick_top", dyn.DYN_K_TICK_TOP),
-                          ("tick_space", dyn.DYN_K_TICK_SPACE), ("tick_merge", dyn.DYN_K_TICK_MERGE)):
+                          ("tick_space", dyn.DYN_K_TICK_SPACE), ("tick_merge", dyn.DYN_K_TICK_MERGE),
+                          ("mixed_types", dyn.DYN_K_MIXED_TYPES), ("mixed_combine", dyn.DYN_K_MIXED_COMBINE)):
             ms, n = dyn.dyn_timing_read(kid)
             ktime[name] = ms / max(n, 1)
         dyn.dyn_timing_enable(False)
@@ -210,7 +237,18 @@ def main():
                   + 20.0 * cells + 12.0 * NW + (8.0 * cells * (T - 1) if args.ticks else 0.0))
     path_gbps = path_bytes / (ms_per_step * 1e-3) / 1e9
 
-    if args.ticks:
+    if args.mixed:
+        # instruction-bound: the method's arithmetic is 18 fp64 operations per (cell, type, instances, shares,
+        # frequency) look-up (share of the load, table look-up, energy, TTFT multiply)
+        space_ms = ktime["mixed_types"]
+        flops = 18.0 * cells * K
+        tf = flops / (space_ms * 1e-3) / 1e12 if space_ms > 0 else None
+        roofline = {"bound": "alu", "kernel": "mixed_type_kernel", "achieved": tf, "peak": FP64_VECTOR_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": tf / FP64_VECTOR_PEAK_TFLOPS if tf else None, "traffic": None,
+                    "algorithmic_flops_per_launch": flops, "avg_launch_ms": space_ms}
+        path_bytes = 8.0 * R + 8.0 * (cells + 1) + 2 * 9.0 * cells * n_entry + (8.0 + 12.0 * tp.size) * cells + 12.0 * NW
+        path_gbps = path_bytes / (ms_per_step * 1e-3) / 1e9
+    elif args.ticks:
         # instruction-bound: per (cell, configuration, tick) the method's arithmetic is 17 fp64 operations for the
         # table look-up and the energy term + 1 multiply for the tick's largest candidate
         flops = 18.0 * cells * K * T
@@ -226,7 +264,11 @@ def main():
                     "traffic": None if args.unfused else recorded_traffic(args.config),
                     "algorithmic_bytes_per_launch": space_bytes, "avg_launch_ms": space_ms}
 
-    sel_h = sel["sel"].cpu().numpy()
+    if args.mixed:
+        en = msel["energy_j"].cpu().numpy()
+        sel_h = np.where(np.isfinite(en), 0, -1)
+    else:
+        sel_h = sel["sel"].cpu().numpy()
     we = sel["window_energy_j"].cpu().numpy()
     out = {
         "metric": "(request x config) evals/sec at 1 MI355X; achieved HBM GB/s vs peak",
@@ -237,8 +279,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {spec.name}: {R} requests, {NW} windows x {G} classes = "
                                f"{cells} cells, {K} configurations", "requests": R, "cells": cells, "configs": K,
-                   "ticks_per_window": args.ticks,
-                   "entry_points": "dyn_eval_select_ticks" if args.ticks else
+                   "ticks_per_window": args.ticks, "mixed_shares": args.mixed,
+                   "entry_points": "dyn_eval_select_mixed" if args.mixed else "dyn_eval_select_ticks" if args.ticks else
                                    "dyn_eval_space+dyn_select_config" if args.unfused else "dyn_eval_select"},
         "roofline": roofline,
         "kernel_ms": ktime, "ms_per_step_with_kernel_events": ms_per_step_events,
@@ -248,8 +290,9 @@ def main():
         "result": {"workspace_status": status, "cells_without_feasible_config": int((sel_h < 0).sum()), "total_energy_wh": float(we.sum() / 3600.0)},
     }
     if not args.no_cpu_baseline:
-        nwin = args.cpu_windows or max(1, min(NW, int(NW * 3.0e9 / (R * K))))
-        out["cpu_baseline"] = cpu_baseline(w, nwin, args.ticks)
+        nwin = args.cpu_windows or max(1, min(NW, int(NW * (5.0e9 if args.mixed else 3.0e9) / (R * K))))
+        mixed = (args.mixed, n_max, np.full(G, args.mixed_gpus, np.int32), K) if args.mixed else None
+        out["cpu_baseline"] = cpu_baseline(w, nwin, args.ticks, mixed)
         out["cpu_baseline"]["host_cores"] = os.cpu_count()
     prof.free()
     print(json.dumps(out))

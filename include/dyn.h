@@ -248,6 +248,43 @@ int dyn_eval_select_ticks(dyn_profile* profile, const dyn_trace_view* fine, int3
                           const dyn_space* space, const dyn_selection* sel, void* workspace,
                           size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------- pools that mix instance types (Eq. 1) --
+ * Eq. 1 in full: per (window, class) cell choose the number of instances of every tensor
+ * parallelism (N^TP), their frequency (f^TP) and the part of the load each type takes
+ * (L^TP) so that the total energy is least, the GPUs used stay within the class's budget,
+ * the parts add up to the load and every used type meets the SLO under its part.
+ * The load is split in n_share equal shares; type i takes a_i >= 1 of them exactly when it
+ * is used (sum a_i = n_share) and its n_i instances share that part equally: per-instance
+ * load = (L * a_i / n_share) / n_i.  Frequencies are the profiled ones.  Per type the
+ * frequency is chosen as in Section IV-B "Scale-up/down" (drop what violates the SLO or
+ * leaves the profiled load range, then least energy, lowest frequency on ties); the
+ * percentiles of a type are taken over all requests of the cell under that type's tables.
+ * Total energy = 0 + E_0 + E_1 + ... over the used types in type order,
+ * E_i = n_i * power * window_s.  objective->gpu_budget[g] > 0 bounds sum n_i * tp_i;
+ * objective->idle_cost_weight is not used.
+ * Limits: n_share <= DYN_MIXED_MAX_SHARES, profile n_tp <= DYN_MIXED_MAX_TYPES and
+ * n_f <= 16, n_max[i] in [0, 255]; the per-cell state (GPU units x shares) must fit in LDS,
+ * else DYN_E_SHAPE.  Outputs DEVICE, caller-owned: where several assignments reach the least
+ * energy any one of them is returned.                                                    */
+#define DYN_MIXED_MAX_TYPES 8
+#define DYN_MIXED_MAX_SHARES 16
+typedef struct {
+  int32_t n_share;        /* S: equal shares the pool's load is split into                */
+  const int32_t* n_max;   /* HOST [n_tp] most instances of each type considered (0 = type not used) */
+} dyn_mixed_space;
+typedef struct {
+  double* energy_j;           /* [cells] least total energy, +inf if no assignment is feasible */
+  int32_t* n_inst;            /* [cells][n_tp] instances of each type (0 = type unused)   */
+  int32_t* f_index;           /* [cells][n_tp] index into the profile's f_mhz, -1 if unused */
+  int32_t* share;             /* [cells][n_tp] shares given to each type (sum = n_share)  */
+  double* window_energy_j;    /* [n_window] sum over the classes with an assignment, g ascending */
+  int32_t* window_infeasible; /* [n_window] classes without one                           */
+} dyn_mixed_selection;
+size_t dyn_mixed_workspace(const dyn_profile* profile, int32_t n_window, const dyn_mixed_space* space);
+int dyn_eval_select_mixed(dyn_profile* profile, const dyn_trace_view* trace, const dyn_mixed_space* space,
+                          const dyn_objective* objective, const dyn_mixed_selection* out,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------- kernel timing (optional) --
  * Measurement aid, not part of the method: when enabled, the library brackets each of its
  * kernels with a pair of HIP events recorded on the stream the kernel is launched on, so
@@ -260,7 +297,9 @@ int dyn_eval_select_ticks(dyn_profile* profile, const dyn_trace_view* fine, int3
 #define DYN_K_TICK_TOP 4   /* tick evaluation: per-tick loads and largest input lengths   */
 #define DYN_K_TICK_SPACE 5 /* tick evaluation of the (cell, configuration) space: cells whose percentile is at most 16 deep */
 #define DYN_K_TICK_MERGE 6 /* the same for the remaining cells                             */
-#define DYN_K_COUNT 7
+#define DYN_K_MIXED_TYPES 7   /* mixed pools: per-type least energies                      */
+#define DYN_K_MIXED_COMBINE 8 /* mixed pools: assignment of instances and shares          */
+#define DYN_K_COUNT 9
 /* on != 0: create the event pool (up to `max_launches` launches per kernel are recorded,
  * later ones are not) and start recording; on == 0: stop and destroy the pool.         */
 int dyn_timing_enable(int on, int32_t max_launches);

@@ -20,7 +20,8 @@ __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_t
            "DYN_K_TOTALS",
            "DYN_F_FEASIBLE", "DYN_F_OVERLOAD", "DYN_F_TTFT", "DYN_F_TBT", "DYN_F_BUDGET", "DYN_F_EMPTY",
            "DYN_WS_BAD_OFFSETS", "DYN_WS_BAD_REQUEST", "DYN_WS_TICK_RANK", "dyn_eval_select_ticks",
-           "dyn_eval_ticks_workspace", "DYN_K_TICK_TOP", "DYN_K_TICK_SPACE", "DYN_K_TICK_MERGE", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
+           "dyn_eval_ticks_workspace", "DYN_K_TICK_TOP", "DYN_K_TICK_SPACE", "DYN_K_TICK_MERGE", "DYN_K_MIXED_TYPES", "DYN_K_MIXED_COMBINE",
+           "MixedPlan", "dyn_mixed_workspace", "dyn_eval_select_mixed", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
 
 DYN_F_FEASIBLE, DYN_F_OVERLOAD, DYN_F_TTFT, DYN_F_TBT, DYN_F_BUDGET, DYN_F_EMPTY = 1, 2, 4, 8, 16, 32
 DYN_WS_BAD_OFFSETS, DYN_WS_BAD_REQUEST, DYN_WS_TICK_RANK = 1, 2, 4
@@ -74,6 +75,15 @@ class _Selection(C.Structure):
                 ("window_infeasible", _vp)]
 
 
+class _MixedSpace(C.Structure):
+    _fields_ = [("n_share", _i32), ("n_max", _vp)]
+
+
+class _MixedSelection(C.Structure):
+    _fields_ = [("energy_j", _vp), ("n_inst", _vp), ("f_index", _vp), ("share", _vp), ("window_energy_j", _vp),
+                ("window_infeasible", _vp)]
+
+
 _lib.dyn_last_error.restype = C.c_char_p
 _lib.dyn_profile_load.restype = C.c_int
 _lib.dyn_profile_load.argtypes = [C.POINTER(_ProfileDesc), _vp, C.POINTER(_vp)]
@@ -106,12 +116,18 @@ _lib.dyn_eval_ticks_workspace.argtypes = [_i32, _i32, _i32, _i32]
 _lib.dyn_eval_select_ticks.restype = C.c_int
 _lib.dyn_eval_select_ticks.argtypes = [_vp, C.POINTER(_TraceView), _i32, C.POINTER(_Config), _i32,
                                        C.POINTER(_Objective), C.POINTER(_Space), C.POINTER(_Selection), _vp, _sz, _vp]
+_lib.dyn_mixed_workspace.restype = _sz
+_lib.dyn_mixed_workspace.argtypes = [_vp, _i32, C.POINTER(_MixedSpace)]
+_lib.dyn_eval_select_mixed.restype = C.c_int
+_lib.dyn_eval_select_mixed.argtypes = [_vp, C.POINTER(_TraceView), C.POINTER(_MixedSpace), C.POINTER(_Objective),
+                                       C.POINTER(_MixedSelection), _vp, _sz, _vp]
 _lib.dyn_timing_enable.restype = C.c_int
 _lib.dyn_timing_enable.argtypes = [C.c_int, _i32]
 _lib.dyn_timing_reset.restype = C.c_int
 _lib.dyn_timing_read.restype = C.c_int
 _lib.dyn_timing_read.argtypes = [_i32, C.POINTER(C.c_double), C.POINTER(_i64)]
-DYN_K_CELL, DYN_K_SPACE, DYN_K_SELECT, DYN_K_TOTALS, DYN_K_TICK_TOP, DYN_K_TICK_SPACE, DYN_K_TICK_MERGE = range(7)
+(DYN_K_CELL, DYN_K_SPACE, DYN_K_SELECT, DYN_K_TOTALS, DYN_K_TICK_TOP, DYN_K_TICK_SPACE, DYN_K_TICK_MERGE,
+ DYN_K_MIXED_TYPES, DYN_K_MIXED_COMBINE) = range(9)
 
 
 def dyn_timing_enable(on: bool, max_launches: int = 4096):
@@ -377,6 +393,58 @@ def dyn_eval_select_ticks(profile: Profile, in_tok: torch.Tensor, out_tok: torch
                                       C.byref(se), _dp(workspace), workspace.numel(), _stream(stream)),
            "dyn_eval_select_ticks")
     return out, sel, workspace
+
+
+class MixedPlan:
+    """Marshalled mixed-pool search space (shares, instances per type) and objective (host side only)."""
+
+    def __init__(self, n_share, n_max, slos, pct=(99, 100), gpu_budget=None):
+        self._n_max = _host(n_max, np.int32)
+        self.space = _MixedSpace(int(n_share), _hp(self._n_max))
+        self.obj, self._keep = _objective(slos, pct, gpu_budget, 0.0)
+        self.n_class = self._keep[0].size
+        self.n_tp = self._n_max.size
+
+
+def dyn_mixed_workspace(profile: Profile, n_window: int, plan: MixedPlan) -> int:
+    return int(_lib.dyn_mixed_workspace(profile.handle, n_window, C.byref(plan.space)))
+
+
+def dyn_eval_select_mixed(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tensor, cell_off: torch.Tensor,
+                          n_window: int, window_s: float, plan: MixedPlan,
+                          out: Optional[Dict[str, torch.Tensor]] = None, workspace: Optional[torch.Tensor] = None,
+                          stream=None):
+    """Least-energy assignment of instances, frequencies and load shares per cell.  Returns (selection, workspace)."""
+    G, T = profile.n_class, profile.n_tp
+    if plan.n_class != G or plan.n_tp != T:
+        raise ValueError("SLO arrays need one entry per class and n_max one per TP degree")
+    cells = n_window * G
+    if cell_off.numel() != cells + 1:
+        raise ValueError("cell_off must have n_window*G + 1 entries")
+    dev = cell_off.device
+    if out is None:
+        out = {"energy_j": torch.empty(cells, dtype=torch.float64, device=dev),
+               "n_inst": torch.empty((cells, T), dtype=torch.int32, device=dev),
+               "f_index": torch.empty((cells, T), dtype=torch.int32, device=dev),
+               "share": torch.empty((cells, T), dtype=torch.int32, device=dev),
+               "window_energy_j": torch.empty(n_window, dtype=torch.float64, device=dev),
+               "window_infeasible": torch.empty(n_window, dtype=torch.int32, device=dev)}
+    if workspace is None:
+        nbytes = dyn_mixed_workspace(profile, n_window, plan)
+        if nbytes == 0:
+            raise DynError(-2, "dyn_mixed_workspace")
+        workspace = _workspace(nbytes, dev)
+    tv = _TraceView(in_tok.numel(), n_window, float(window_s), _dp(in_tok, torch.int32, "in_tok"),
+                    _dp(out_tok, torch.int32, "out_tok"), _dp(cell_off, torch.int64, "cell_off"))
+    se = _MixedSelection(_dp(out["energy_j"], torch.float64), _dp(out["n_inst"], torch.int32),
+                         _dp(out["f_index"], torch.int32), _dp(out["share"], torch.int32),
+                         _dp(out["window_energy_j"], torch.float64), _dp(out["window_infeasible"], torch.int32))
+    for k in ("n_inst", "f_index", "share"):
+        if out[k].numel() != cells * T:
+            raise ValueError("selection tensors must hold n_window*G*n_tp entries")
+    _check(_lib.dyn_eval_select_mixed(profile.handle, C.byref(tv), C.byref(plan.space), C.byref(plan.obj), C.byref(se),
+                                      _dp(workspace), workspace.numel(), _stream(stream)), "dyn_eval_select_mixed")
+    return out, workspace
 
 
 def dyn_cell_stats(workspace: torch.Tensor, n_window: int, n_class: int, stream=None):

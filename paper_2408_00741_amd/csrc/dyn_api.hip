@@ -9,8 +9,10 @@
 
 #include <algorithm>
 #include <new>
+#include <numeric>
 
 #include "dyn_ticks.h"
+#include "dyn_mixed.h"
 
 namespace {
 
@@ -628,6 +630,131 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   f.sel = sel->sel; f.sel_energy = sel->sel_energy_j; f.sel_cost = sel->sel_cost;
   f.win_energy = sel->window_energy_j; f.win_inf = sel->window_infeasible;
   if (!hip_ok(dyn_launch_finish(f, s), "finish launch")) return DYN_E_DEVICE;
+  return DYN_OK;
+}
+
+namespace {
+
+struct MixedWs {
+  EvalWs cell;       // header .. cstat (per-cell aggregates); cell.part is where type_energy starts
+  size_t type_energy, type_f, ok, total;
+};
+struct MixedPlan {
+  MixedTypes types;
+  int32_t n_entry, unit, u_max;
+};
+// Checks the request against the profile and lays the entries out.  Returns DYN_OK or an error status.
+int plan_mixed(const dyn_profile* p, const dyn_mixed_space* m, MixedPlan* out) {
+  if (!m || !m->n_max) { dyn_set_error("mixed space or n_max is NULL"); return DYN_E_NULL; }
+  if (m->n_share < 1 || m->n_share > DYN_MIXED_MAX_SHARES) { dyn_set_error("n_share=%d outside [1, %d]", m->n_share, DYN_MIXED_MAX_SHARES); return DYN_E_SHAPE; }
+  if (p->n_tp > DYN_MIXED_MAX_TYPES || p->n_f > DYN_MIXED_FREQ_LANES) { dyn_set_error("profile has more than %d types or %d frequencies", DYN_MIXED_MAX_TYPES, DYN_MIXED_FREQ_LANES); return DYN_E_SHAPE; }
+  MixedTypes& t = out->types;
+  memset(&t, 0, sizeof(t));
+  t.n_tp = p->n_tp;
+  int32_t unit = 0;
+  for (int i = 0; i < p->n_tp; ++i) {
+    if (m->n_max[i] < 0 || m->n_max[i] > 255) { dyn_set_error("n_max[%d]=%d outside [0, 255]", i, m->n_max[i]); return DYN_E_RANGE; }
+    t.n_max[i] = m->n_max[i];
+    t.off[i + 1] = t.off[i] + m->n_max[i] * m->n_share;
+    if (m->n_max[i] > 0) unit = std::gcd(unit, p->tp[i]);
+  }
+  if (unit == 0) { dyn_set_error("every n_max is 0"); return DYN_E_SHAPE; }
+  int64_t u_max = 0;
+  for (int i = 0; i < p->n_tp; ++i) {
+    t.units[i] = p->tp[i] / unit;
+    u_max += (int64_t)t.n_max[i] * (t.n_max[i] > 0 ? t.units[i] : 0);
+  }
+  out->n_entry = t.off[p->n_tp];
+  out->unit = unit;
+  out->u_max = (int32_t)std::min<int64_t>(u_max, 1 << 20);
+  return DYN_OK;
+}
+MixedWs mixed_ws_layout(int64_t cells, int32_t n_entry) {
+  MixedWs w;
+  w.cell = dyn_eval_ws_layout(cells, 1);
+  const size_t c = (size_t)std::max<int64_t>(cells, 1);
+  size_t off = w.cell.part;
+  w.type_energy = off; off += align256(c * (size_t)n_entry * sizeof(double));
+  w.type_f = off; off += align256(c * (size_t)n_entry);
+  w.ok = off; off += align256(c * sizeof(int32_t));
+  w.total = off;
+  return w;
+}
+
+}  // namespace
+
+size_t dyn_mixed_workspace(const dyn_profile* p, int32_t n_window, const dyn_mixed_space* m) {
+  MixedPlan mp;
+  if (!p || n_window < 1 || plan_mixed(p, m, &mp) != DYN_OK) return 0;
+  return mixed_ws_layout((int64_t)n_window * p->G, mp.n_entry).total;
+}
+
+int dyn_eval_select_mixed(dyn_profile* p, const dyn_trace_view* t, const dyn_mixed_space* m, const dyn_objective* o,
+                          const dyn_mixed_selection* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!p || !t || !m || !o || !out || !workspace) { dyn_set_error("profile, trace, space, objective, out or workspace is NULL"); return DYN_E_NULL; }
+  if (!out->energy_j || !out->n_inst || !out->f_index || !out->share || !out->window_energy_j || !out->window_infeasible) {
+    dyn_set_error("an output array is NULL");
+    return DYN_E_NULL;
+  }
+  if (t->n_req < 0 || t->n_req >= ((int64_t)1 << 31) || t->n_window < 1) { dyn_set_error("n_req or n_window out of range"); return DYN_E_SHAPE; }
+  if (!t->cell_off || (t->n_req > 0 && (!t->in_tok || !t->out_tok))) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
+  if (!(t->window_s > 0.0) || !isfinite(t->window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  const int64_t cells = (int64_t)t->n_window * p->G;
+  if (cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
+  int rc;
+  if ((rc = check_device(p)) != DYN_OK) return rc;
+  MixedPlan mp;
+  if ((rc = plan_mixed(p, m, &mp)) != DYN_OK) return rc;
+  // the dynamic programme's state must fit one block's LDS for the largest budget in use
+  int32_t u_need = 0;
+  for (int g = 0; g < p->G; ++g) {
+    const int32_t b = o->gpu_budget ? o->gpu_budget[g] : 0;
+    u_need = std::max(u_need, b > 0 ? std::min(b / mp.unit, mp.u_max) : mp.u_max);
+  }
+  if (dyn_mixed_combine_lds(p->n_tp, mp.n_entry, u_need, m->n_share) > DYN_LDS_BUDGET) {
+    dyn_set_error("the assignment state (%d GPU units x %d shares, %d entries) does not fit in LDS: set a GPU budget or lower n_max / n_share",
+                  u_need + 1, m->n_share + 1, mp.n_entry);
+    return DYN_E_SHAPE;
+  }
+  const MixedWs w = mixed_ws_layout(cells, mp.n_entry);
+  if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) {
+    dyn_set_error("workspace misaligned or too small (%zu < %zu)", workspace_bytes, w.total);
+    return DYN_E_WORKSPACE;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  if ((rc = prepare_objective(p, o, s)) != DYN_OK) return rc;
+
+  char* base = (char*)workspace;
+  if (!hip_ok(dyn_launch_cell_aggregate(t->in_tok, t->out_tok, t->cell_off, t->n_req, cells, t->window_s, o->pct_num,
+                                        o->pct_den, (int64_t*)(base + w.cell.tin), (int64_t*)(base + w.cell.tout),
+                                        (int32_t*)(base + w.cell.in_p99), (CellRec*)(base + w.cell.rec),
+                                        (uint8_t*)(base + w.cell.cstat), (WsHeader*)(base + w.cell.header), s),
+              "cell aggregate launch"))
+    return DYN_E_DEVICE;
+
+  MixedTypeArgs ta;
+  ta.tab = p->d_tab; ta.ml = p->d_ml; ta.gridpack = p->d_gridpack;
+  ta.jstart = p->d_jstart; ta.tstart = p->d_tstart; ta.thr = p->d_thr; ta.n_bucket = p->n_bucket; ta.bucket_scale = p->bucket_scale;
+  ta.G = p->G; ta.n_tp = p->n_tp; ta.n_f = p->n_f; ta.n_rho = p->n_rho;
+  ta.slo_ttft = p->d_slo_ttft; ta.slo_tbt = p->d_slo_tbt;
+  ta.rec = (const CellRec*)(base + w.cell.rec); ta.n_window = t->n_window; ta.window_s = t->window_s;
+  ta.win_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(DYN_MAX_WIN_PER_BLOCK, (cells * p->n_tp + 4095) / 4096));
+  ta.n_share = m->n_share; ta.r_share = 1.0 / (double)m->n_share;
+  ta.types = mp.types; ta.n_group = 0;
+  ta.type_energy = (double*)(base + w.type_energy); ta.type_f = (int8_t*)(base + w.type_f);
+  if (!hip_ok(dyn_launch_mixed_types(ta, p->single_point, s), "mixed types launch")) return DYN_E_DEVICE;
+
+  MixedCombineArgs ca;
+  ca.type_energy = ta.type_energy; ca.type_f = ta.type_f; ca.budget = p->d_budget;
+  ca.G = p->G; ca.cells = cells; ca.n_share = m->n_share; ca.unit = mp.unit; ca.u_max = u_need;
+  ca.types = mp.types;
+  ca.energy = out->energy_j; ca.n_inst = out->n_inst; ca.f_index = out->f_index; ca.share = out->share;
+  ca.ok = (int32_t*)(base + w.ok);
+  if (!hip_ok(dyn_launch_mixed_combine(ca, s), "mixed combine launch")) return DYN_E_DEVICE;
+  if (!hip_ok(dyn_launch_window_totals(ca.ok, out->energy_j, t->n_window, p->G, out->window_energy_j,
+                                       out->window_infeasible, s),
+              "window totals launch"))
+    return DYN_E_DEVICE;
   return DYN_OK;
 }
 

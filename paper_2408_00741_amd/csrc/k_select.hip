@@ -2,7 +2,7 @@
 // violates the SLO, then take the minimum energy), one wavefront per cell striding the
 // configuration axis, then the per-window totals of the objective (Eq. 1 sums over the
 // pools).  cost = energy + idle_cost_weight * n * power(load 0) * window.
-#include "dyn_internal.h"
+#include "dyn_mixed.h"
 
 namespace {
 
@@ -165,6 +165,14 @@ hipError_t dyn_launch_finish(const FinishArgs& a, hipStream_t s) {
   DynTimed timed(DYN_K_TOTALS, s);
   hipLaunchKernelGGL(window_totals_kernel, dim3((unsigned)((a.n_window + 127) / 128)), dim3(128), 0, s, a.sel,
                      a.sel_energy, a.n_window, a.G, a.win_energy, a.win_inf);
+  return hipGetLastError();
+}
+
+hipError_t dyn_launch_window_totals(const int32_t* sel, const double* sel_energy, int32_t n_window, int32_t G,
+                                    double* win_energy, int32_t* win_inf, hipStream_t s) {
+  DynTimed timed(DYN_K_TOTALS, s);
+  hipLaunchKernelGGL(window_totals_kernel, dim3((unsigned)((n_window + 127) / 128)), dim3(128), 0, s, sel, sel_energy,
+                     n_window, G, win_energy, win_inf);
   return hipGetLastError();
 }
 

@@ -12,61 +12,15 @@
 // then finds, per (cell, configuration), the j-th largest of the scaled lists.  The TBT
 // percentile is the j-th largest of the ticks' TBT values weighted by their request counts.
 #include "dyn_ticks.h"
+#include "dyn_device.h"
 
 namespace {
 
 constexpr int kWavesPerBlock = 4;
 constexpr int kFastDepth = 16;      // j up to here: sorted-list path of the evaluation kernel
-
-template <int CTRL>
-__device__ __forceinline__ int dpp_mov(int v) {
-  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
-}
-// Reductions over the 64 lanes of a fully active wave (wave-uniform result): rotations by
-// 1, 2, 4, 8 inside each row of 16 lanes, then the four row results from lanes 0, 16, 32, 48.
-__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x) {
-  int v = (int)x;
-  v += dpp_mov<0x121>(v);
-  v += dpp_mov<0x122>(v);
-  v += dpp_mov<0x124>(v);
-  v += dpp_mov<0x128>(v);
-  return (uint32_t)(__builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
-                    __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48));
-}
-__device__ __forceinline__ int wave_max_i32(int v) {
-  v = max(v, dpp_mov<0x121>(v));
-  v = max(v, dpp_mov<0x122>(v));
-  v = max(v, dpp_mov<0x124>(v));
-  v = max(v, dpp_mov<0x128>(v));
-  return max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
-             max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
-}
-__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
-  x = min(x, (uint32_t)dpp_mov<0x121>((int)x));
-  x = min(x, (uint32_t)dpp_mov<0x122>((int)x));
-  x = min(x, (uint32_t)dpp_mov<0x124>((int)x));
-  x = min(x, (uint32_t)dpp_mov<0x128>((int)x));
-  const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
-  const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
-  return min(min(a, b), min(c, d));
-}
-__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t x) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, DYN_WAVE);
-  return __builtin_amdgcn_readfirstlane((uint32_t)x) |
-         ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(x >> 32)) << 32);
-}
-__device__ __forceinline__ int64_t readlane_i64(int64_t x, int lane) {   // lane must be wave-uniform
-  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, lane);
-  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)x >> 32), lane);
-  return (int64_t)(((uint64_t)hi << 32) | lo);
-}
-// a / b given rb = RN(1 / b): correctly rounded for normal operands and quotients.
-__device__ __forceinline__ double div_by(double a, double b, double rb) {
-  const double q = a * rb;
-  const double e = __builtin_fma(-b, q, a);
-  return __builtin_fma(e, rb, q);
-}
+// LDS stride of a staged table row in doubles: odd, so that lanes reading the same load bracket of
+// different rows do not all fall into one bank
+#define DYN_SLOT_STRIDE(n_rho) ((3 * (n_rho)) | 1)
 
 // ---- per-tick loads and candidate lists ------------------------------------------------------
 // One wave per (window, class) cell walks the cell's ticks.  Lane q holds tick q's offsets;
@@ -215,65 +169,6 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
 }
 
 // ---- evaluation of the (cell, configuration) space -----------------------------------------------
-struct Lookup {          // per-thread constants of the table look-up
-  double den, rden, rho_max, bucket_scale, omu, u;
-  const double *lo, *hi;         // the configuration's two table rows: [3][n_rho] prefill, TBT, power
-  const double *rgp, *rinv;      // padded load grid and reciprocal spacings
-  const uint16_t* js;            // bucket index
-  const double* thr;             // SINGLE: the grid point inside each bucket
-  int n_rho;
-};
-
-// Plain v_max_f64 / v_min_f64 of two values known not to be NaN (no quieting of the operands).
-__device__ __forceinline__ double max_num(double a, double b) {
-  double r;
-  asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-  return r;
-}
-__device__ __forceinline__ double min_num(double a, double b) {
-  double r;
-  asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-  return r;
-}
-
-// Tables at (f, min(rho, rho_max)) for load `load` (>= 0): the window-level kernel's arithmetic.
-// SINGLE: every bucket of the load axis holds at most one interior grid point, so the bracket
-// is the bucket's start index plus one comparison; otherwise the bracket is searched from the
-// bucket's index.  TWO: both frequency rows are combined (weight 0 on the upper row leaves
-// the lower row's value unchanged, so lanes with a profiled frequency may run it too).
-template <bool SINGLE, bool TWO>
-__device__ __forceinline__ bool tick_lookup(const Lookup& L, double load, double* pf, double* tb, double* pw) {
-  const double rho = div_by(load, L.den, L.rden);
-  const bool ov = rho > L.rho_max;
-  const double rc = ov ? L.rho_max : rho;
-  int jj;
-  if (SINGLE) {
-    const int b = (int)(rc * L.bucket_scale);
-    jj = (int)L.js[b] + (rc >= L.thr[b] ? 1 : 0);
-  } else {
-    jj = L.js[(int)(fmax(rc, 0.0) * L.bucket_scale)];
-    while (jj > 0 && L.rgp[jj + 1] > rc) --jj;
-    while (jj < L.n_rho - 2 && L.rgp[jj + 2] <= rc) ++jj;
-  }
-  const double r0 = L.rgp[jj + 1], r1 = L.rgp[jj + 2];
-  const double t = div_by(rc - r0, r1 - r0, L.rinv[jj + 1]);
-  const double omt = 1.0 - t;
-  const int n_rho = L.n_rho;
-  double x_pf = omt * L.lo[jj] + t * L.lo[jj + 1];
-  double x_tb = omt * L.lo[n_rho + jj] + t * L.lo[n_rho + jj + 1];
-  double x_pw = omt * L.lo[2 * n_rho + jj] + t * L.lo[2 * n_rho + jj + 1];
-  if (TWO) {
-    const double b_pf = omt * L.hi[jj] + t * L.hi[jj + 1];
-    const double b_tb = omt * L.hi[n_rho + jj] + t * L.hi[n_rho + jj + 1];
-    const double b_pw = omt * L.hi[2 * n_rho + jj] + t * L.hi[2 * n_rho + jj + 1];
-    x_pf = L.omu * x_pf + L.u * b_pf;
-    x_tb = L.omu * x_tb + L.u * b_tb;
-    x_pw = L.omu * x_pw + L.u * b_pw;
-  }
-  *pf = x_pf; *tb = x_tb; *pw = x_pw;
-  return ov;
-}
-
 // A tick's candidates (descending input lengths x its prefill time) against the sorted list
 // s[0] >= ... >= s[JF-1]: once one of them cannot enter the list in any lane, the rest of
 // that tick cannot either.
@@ -306,8 +201,8 @@ __device__ __forceinline__ void walk_ticks_short(const Lookup& L, int T, int j, 
   int q = 0;
   for (; q + 2 <= T; q += 2) {
     double pf0, tb0, pw0, pf1, tb1, pw1;
-    const bool o0 = tick_lookup<SINGLE, TWO>(L, s_load[q], &pf0, &tb0, &pw0);
-    const bool o1 = tick_lookup<SINGLE, TWO>(L, s_load[q + 1], &pf1, &tb1, &pw1);
+    const bool o0 = table_lookup<SINGLE, TWO>(L, s_load[q], &pf0, &tb0, &pw0);
+    const bool o1 = table_lookup<SINGLE, TWO>(L, s_load[q + 1], &pf1, &tb1, &pw1);
     ov = ov | o0 | o1;
     e += (nd * pw0) * tick_s;                    // ticks in time order
     e += (nd * pw1) * tick_s;
@@ -323,7 +218,7 @@ __device__ __forceinline__ void walk_ticks_short(const Lookup& L, int T, int j, 
   }
   if (q < T) {
     double pf0, tb0, pw0;
-    ov = ov | tick_lookup<SINGLE, TWO>(L, s_load[q], &pf0, &tb0, &pw0);
+    ov = ov | table_lookup<SINGLE, TWO>(L, s_load[q], &pf0, &tb0, &pw0);
     e += (nd * pw0) * tick_s;
     const int c0 = s_cnt[q];
     if (c0 > 0) {
@@ -352,7 +247,7 @@ __device__ __forceinline__ void walk_ticks_merge(const Lookup& L, int T, int j, 
     tb[q] = ninf;
     if (q < T) {
       double pw;
-      ov = tick_lookup<SINGLE, TWO>(L, s_load[q], &pf[q], &tb[q], &pw) | ov;
+      ov = table_lookup<SINGLE, TWO>(L, s_load[q], &pf[q], &tb[q], &pw) | ov;
       e += (nd * pw) * tick_s;
       if (s_cnt[q] > 0) nonempty |= 1u << q;
     }
@@ -460,8 +355,8 @@ __device__ __forceinline__ void load_config(const TickArgs& a, int g, int tile, 
   L.bucket_scale = sa.bucket_scale;
   L.rgp = s_rgp; L.rinv = s_rinv; L.js = s_js; L.thr = s_thr; L.n_rho = n_rho;
   if (LDS) {      // kept apart so that the address space of the rows is known at compile time
-    L.lo = s_tab + (size_t)c.slot_lo * 3 * n_rho;
-    L.hi = s_tab + (size_t)c.slot_hi * 3 * n_rho;
+    L.lo = s_tab + (size_t)c.slot_lo * DYN_SLOT_STRIDE(n_rho);
+    L.hi = s_tab + (size_t)c.slot_hi * DYN_SLOT_STRIDE(n_rho);
   } else {
     L.lo = sa.tab + (grow + c.row_lo) * 3 * n_rho;
     L.hi = sa.tab + (grow + c.row_hi) * 3 * n_rho;
@@ -487,7 +382,7 @@ __device__ __forceinline__ void stage_rows(const SpaceArgs& sa, int g, int tile,
   for (int i = threadIdx.x; i < total; i += blockDim.x) {
     const int slot = i / per_slot;
     const int row = rows[slot];
-    s_tab[i] = base[(size_t)(row < 0 ? 0 : row) * per_slot + (i - slot * per_slot)];
+    s_tab[slot * DYN_SLOT_STRIDE(sa.n_rho) + (i - slot * per_slot)] = base[(size_t)(row < 0 ? 0 : row) * per_slot + (i - slot * per_slot)];
   }
 }
 template <bool SINGLE>
@@ -561,7 +456,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
   const int w1 = min(w0 + sa.win_per_block, sa.n_window);
 
   double* s_tab = smem;
-  double* s_rgp = smem + (LDS ? (size_t)sa.n_slot * 3 * n_rho : 0);
+  double* s_rgp = smem + (LDS ? (size_t)sa.n_slot * DYN_SLOT_STRIDE(n_rho) : 0);
   double* s_rinv = s_rgp + (n_rho + 2);
   double* s_thr = s_rinv + (n_rho + 1);                         // [n_bucket + 1] when SINGLE
   double* s_load = s_thr + (SINGLE ? sa.n_bucket + 1 : 0);      // [win_per_block][T]
@@ -648,7 +543,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_merge_kernel(TickArgs a) {
   const SpaceArgs& sa = a.s;
   const int n_rho = sa.n_rho, T = a.n_tick;
   double* s_tab = smem;
-  double* s_rgp = smem + (LDS ? (size_t)sa.n_slot * 3 * n_rho : 0);
+  double* s_rgp = smem + (LDS ? (size_t)sa.n_slot * DYN_SLOT_STRIDE(n_rho) : 0);
   double* s_rinv = s_rgp + (n_rho + 2);
   double* s_thr = s_rinv + (n_rho + 1);
   double* s_load = s_thr + (SINGLE ? sa.n_bucket + 1 : 0);      // [T]
@@ -735,7 +630,7 @@ hipError_t dyn_launch_tick_space(const TickArgs& a, hipStream_t s) {
   const SpaceArgs& sa = a.s;
   const int n_chunk = (sa.n_window + sa.win_per_block - 1) / sa.win_per_block;
   const dim3 grid((unsigned)((size_t)n_chunk * sa.G * sa.n_tile)), block(sa.tile);
-  const size_t tab = (size_t)sa.n_slot * 3 * sa.n_rho * sizeof(double);
+  const size_t tab = (size_t)sa.n_slot * DYN_SLOT_STRIDE(sa.n_rho) * sizeof(double);
   // Preferences when LDS is short: keep the table rows in LDS first, the per-bucket grid
   // points second (without them the bracket is searched; without the rows the tables are
   // read from global memory).
