@@ -178,6 +178,24 @@ def mixed(profile: Dict[str, np.ndarray], sorted_trace: Dict[str, np.ndarray], n
     return r
 
 
+def select_path(space_cost: np.ndarray, feasible: np.ndarray, n_window: int, n_class: int, layout, transition):
+    """Least-total sequence of configurations per class with transition costs between consecutive windows.
+    space_cost, feasible: [cells, K]; layout: [K]; transition: [n_layout, n_layout] (from, to).
+    Returns (sel [cells], path_cost [n_class])."""
+    lib = _load()
+    lib.dynoracle_select_path.restype = C.c_int
+    cost = _c(space_cost, np.float64); feas = _c(feasible, np.uint8)
+    K = cost.shape[1]
+    lay = _c(layout, np.int32); tr = _c(transition, np.float64)
+    assert cost.shape == feas.shape == (n_window * n_class, K) and lay.size == K and tr.shape[0] == tr.shape[1]
+    sel = np.empty(n_window * n_class, np.int32); pc = np.empty(n_class)
+    rc = lib.dynoracle_select_path(C.c_int32(n_window), C.c_int32(n_class), C.c_int32(K), _ptr(cost), _ptr(feas),
+                                   C.c_int32(tr.shape[0]), _ptr(lay), _ptr(tr), _ptr(sel), _ptr(pc))
+    if rc != 0:
+        raise ValueError(f"dynoracle_select_path failed: {rc}")
+    return sel, pc
+
+
 def window_totals(sel: np.ndarray, sel_energy_j: np.ndarray, n_window: int, n_class: int):
     lib = _load()
     s = _c(sel, np.int32); e = _c(sel_energy_j, np.float64)

@@ -557,6 +557,81 @@ int dynoracle_mixed(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f, con
   return ORC_OK;
 }
 
+// Selection that accounts for the cost of changing the configuration between consecutive
+// windows (Section IV-B "Accounting for the overheads": the transition overheads are kept in
+// an Overhead Table and weighed against the energy a new configuration saves; Table VI lists
+// the re-sharding overheads between the layouts of a server).
+// Reading: per class, the configurations k_w of the windows w = 0 .. NW-1 are chosen together
+// so that  sum_w cost(w, k_w) + sum_{w >= 1} transition[layout(k_{w-1})][layout(k_w)]  is
+// least, cost(w, k) as in the per-window selection (energy + idle term) and only feasible
+// configurations allowed.  The total of a sequence is accumulated in time order,
+// V = cost(0, k_0); V = (V + transition) + cost(w, k_w).  A window without any feasible
+// configuration gets -1; the sequence ends before it and a new one starts after it without a
+// transition; the class's total adds the sequences' totals in time order starting from 0.
+// The minimum over all sequences is found window by window (rounded addition is monotone, so
+// extending the cheapest way to reach k' is the cheapest extension): for every k the least
+// of V_prev[k'] + transition over all k' (lowest k' on ties), then + cost; at the end of a
+// sequence the least V (lowest k) and the chain of predecessors.
+// space_cost [cells][K]: cost(w, k); feasible [cells][K]: != 0 where allowed.
+int dynoracle_select_path(int32_t n_window, int32_t G, int32_t K, const double* space_cost,
+                          const uint8_t* feasible, int32_t n_layout, const int32_t* layout,
+                          const double* transition, int32_t* sel, double* path_cost) {
+  if (!space_cost || !feasible || !layout || !transition || !sel || !path_cost) return ORC_E_NULL;
+  if (n_window < 1 || G < 1 || K < 1 || n_layout < 1) return ORC_E_SHAPE;
+  for (int k = 0; k < K; ++k)
+    if (layout[k] < 0 || layout[k] >= n_layout) return ORC_E_RANGE;
+  for (int64_t i = 0; i < (int64_t)n_layout * n_layout; ++i)
+    if (!std::isfinite(transition[i]) || transition[i] < 0.0) return ORC_E_NOTFINITE;
+  const double INF = std::numeric_limits<double>::infinity();
+  std::vector<double> V(K), Vn(K);
+  std::vector<int32_t> pred((size_t)n_window * K);
+  for (int g = 0; g < G; ++g) {
+    double total = 0.0;
+    int w = 0;
+    while (w < n_window) {
+      // skip windows without a feasible configuration
+      auto any = [&](int ww) {
+        for (int k = 0; k < K; ++k)
+          if (feasible[((int64_t)ww * G + g) * K + k]) return true;
+        return false;
+      };
+      if (!any(w)) { sel[(int64_t)w * G + g] = -1; ++w; continue; }
+      const int w_beg = w;
+      for (int k = 0; k < K; ++k) {
+        const int64_t o = ((int64_t)w * G + g) * K + k;
+        V[k] = feasible[o] ? space_cost[o] : INF;
+      }
+      int w_end = w + 1;
+      for (; w_end < n_window && any(w_end); ++w_end) {
+        for (int k = 0; k < K; ++k) {
+          const int64_t o = ((int64_t)w_end * G + g) * K + k;
+          double best = INF;
+          int32_t bp = -1;
+          for (int kp = 0; kp < K; ++kp) {
+            const double c = V[kp] + transition[(int64_t)layout[kp] * n_layout + layout[k]];
+            if (c < best) { best = c; bp = kp; }
+          }
+          pred[(size_t)w_end * K + k] = bp;
+          Vn[k] = feasible[o] ? best + space_cost[o] : INF;
+        }
+        V.swap(Vn);
+      }
+      // end of the sequence [w_beg, w_end): least total, then its chain of predecessors
+      int kb = -1;
+      for (int k = 0; k < K; ++k)
+        if (V[k] < INF && (kb < 0 || V[k] < V[kb])) kb = k;
+      total += V[kb];
+      for (int ww = w_end - 1; ww >= w_beg; --ww) {
+        sel[(int64_t)ww * G + g] = kb;
+        if (ww > w_beg) kb = pred[(size_t)ww * K + kb];
+      }
+      w = w_end;
+    }
+    path_cost[g] = total;
+  }
+  return ORC_OK;
+}
+
 // Objective summed over the pools of a window (Eq. 1 sums over instance types; here one
 // pool per class), classes added in index order; cells without a feasible configuration
 // are counted, not added.

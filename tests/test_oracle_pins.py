@@ -609,6 +609,137 @@ def test_mixed_invariants(small_hour):
         assert (one["energy_j"] >= base["energy_j"]).all()
 
 
+# ------------------------------------------------- selection with transition overheads
+def _reshard_table(golden_dir):
+    names, rows = [], []
+    for line in open(os.path.join(golden_dir, "paper_reshard_overheads.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        parts = line.split()
+        names.append(parts[0]); rows.append([float(v) for v in parts[1:]])
+    return names, np.asarray(rows)
+
+
+def test_path_with_the_papers_reshard_table(golden_dir):
+    """One candidate per layout of Table VI; transition cost = printed multiple of T times a price per T."""
+    names, tab = _reshard_table(golden_dir)
+    assert names == ["TP2", "4TP2", "TP4", "TP2+TP4", "2TP4", "TP8"] and tab.shape == (6, 6)
+    assert tab[0].tolist() == [0, 4, 2, 2, 2, 1] and tab[1].tolist() == [0] * 6 and tab[5].tolist() == [1, 1, 1, 1, 1, 0]
+    lay = np.arange(6, dtype=np.int32)
+    feas = np.ones((3, 6), np.uint8)
+    TP2, FOUR, TP8 = 0, 1, 5
+    cost = np.full((3, 6), 20.0)
+    cost[0, TP2] = 10.0; cost[1, TP2] = 13.0; cost[1, TP8] = 10.0; cost[2, TP2] = 10.0
+    sel, pc = oracle.select_path(cost, feas, 3, 1, lay, tab * 1.0)       # 1 J per T: two switches pay off (32 < 33)
+    assert sel.tolist() == [TP2, TP8, TP2] and pc[0] == 32.0
+    sel, pc = oracle.select_path(cost, feas, 3, 1, lay, tab * 2.0)       # 2 J per T: they do not (34 > 33)
+    assert sel.tolist() == [TP2, TP2, TP2] and pc[0] == 33.0
+    # the table is not symmetric: TP2 -> 4TP2 costs 4T, 4TP2 -> TP2 nothing
+    cost = np.full((2, 6), 20.0)
+    cost[0, TP2] = 10.0; cost[1, TP2] = 8.0; cost[1, FOUR] = 5.0
+    sel, pc = oracle.select_path(cost, feas[:2], 2, 1, lay, tab * 1.0)
+    assert sel.tolist() == [TP2, TP2] and pc[0] == 18.0                   # 10 + 4 + 5 = 19 would be the switch
+    sel, pc = oracle.select_path(cost, feas[:2], 2, 1, lay, tab.T * 1.0)   # the transposed table would switch
+    assert sel.tolist() == [TP2, FOUR] and pc[0] == 15.0
+    cost = np.full((2, 6), 20.0)
+    cost[0, FOUR] = 10.0; cost[1, FOUR] = 8.0; cost[1, TP2] = 5.0
+    sel, pc = oracle.select_path(cost, feas[:2], 2, 1, lay, tab * 1.0)
+    assert sel.tolist() == [FOUR, TP2] and pc[0] == 15.0
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_path_against_enumeration_of_all_sequences(seed):
+    import itertools
+    rng = np.random.default_rng(1300 + seed)
+    NW, G, K, NL = int(rng.integers(2, 6)), 2, int(rng.integers(2, 5)), int(rng.integers(1, 4))
+    cost = rng.uniform(1, 10, (NW * G, K))
+    feas = (rng.uniform(0, 1, (NW * G, K)) < 0.7).astype(np.uint8)
+    if seed % 2:
+        feas[(NW // 2) * G + 1] = 0                          # class 1 has a window without any feasible candidate
+    lay = rng.integers(0, NL, K).astype(np.int32)
+    tr = rng.uniform(0, 4, (NL, NL)); tr[np.diag_indices(NL)] = 0.0
+    sel, pc = oracle.select_path(cost, feas, NW, G, lay, tr)
+    for g in range(G):
+        ok = [feas[w * G + g].any() for w in range(NW)]
+        total, w = 0.0, 0
+        while w < NW:
+            if not ok[w]:
+                assert sel[w * G + g] == -1
+                w += 1
+                continue
+            e = w
+            while e < NW and ok[e]:
+                e += 1
+            best, best_seq = np.inf, []
+            for seq in itertools.product(range(K), repeat=e - w):
+                if not all(feas[(w + i) * G + g, k] for i, k in enumerate(seq)):
+                    continue
+                v = cost[w * G + g, seq[0]]
+                for i in range(1, len(seq)):
+                    v = (v + tr[lay[seq[i - 1]], lay[seq[i]]]) + cost[(w + i) * G + g, seq[i]]
+                if v < best:
+                    best, best_seq = v, [seq]
+                elif v == best:
+                    best_seq.append(seq)
+            total += best
+            assert tuple(sel[(w + i) * G + g] for i in range(e - w)) in best_seq
+            w = e
+        assert pc[g] == total
+
+
+def test_path_without_overheads_is_the_per_window_selection(small_hour):
+    w, st, r = small_hour
+    K = w["configs"]["n_inst"].size
+    lay = (np.arange(K) % 7).astype(np.int32)
+    feas = (r["flags"] & 1).astype(np.uint8)
+    sel, pc = oracle.select_path(r["cost"], feas, w["n_window"], w["n_class"], lay, np.zeros((7, 7)))
+    np.testing.assert_array_equal(sel, r["sel"])
+    for g in range(w["n_class"]):
+        tot = 0.0
+        run = None
+        for ww in range(w["n_window"]):               # sequences are summed first, then added to the class total
+            c = ww * w["n_class"] + g
+            if r["sel"][c] < 0:
+                if run is not None:
+                    tot += run; run = None
+                continue
+            run = r["sel_cost"][c] if run is None else (run + 0.0) + r["sel_cost"][c]
+        if run is not None:
+            tot += run
+        assert pc[g] == tot
+
+
+def test_path_with_prohibitive_overheads_keeps_one_layout(small_hour):
+    w, st, r = small_hour
+    cfg = w["configs"]
+    lay = cfg["tp_index"].astype(np.int32)
+    NL = int(lay.max()) + 1
+    tr = np.full((NL, NL), 1e15); tr[np.diag_indices(NL)] = 0.0
+    feas = (r["flags"] & 1).astype(np.uint8)
+    sel, pc = oracle.select_path(r["cost"], feas, w["n_window"], w["n_class"], lay, tr)
+    G = w["n_class"]
+    for g in range(G):
+        ks = sel[g::G]
+        ks = ks[ks >= 0]
+        if ks.size and np.isfinite(pc[g]) and pc[g] < 1e15:
+            assert np.unique(lay[ks]).size == 1
+            # and it is the cheapest single layout: per window the least feasible cost inside that layout
+            best = np.inf
+            for l in range(NL):
+                tot, okl = 0.0, True
+                for ww in range(w["n_window"]):
+                    c = ww * G + g
+                    if not feas[c].any():
+                        continue
+                    m = feas[c].astype(bool) & (lay == l)
+                    if not m.any():
+                        okl = False; break
+                    tot += r["cost"][c][m].min()
+                if okl:
+                    best = min(best, tot)
+            np.testing.assert_allclose(pc[g], best, rtol=1e-12)
+
+
 # ----------------------------------------------------------- planted mistakes are caught
 def test_pins_catch_planted_mistakes():
     """Sanity of the pins themselves: perturbing the inputs the way a typical slip would
