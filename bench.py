@@ -48,7 +48,7 @@ def recorded_traffic(workload_index):
     return None
 
 
-def cpu_baseline(w, n_sample_windows, ticks=0, mixed=None):
+def cpu_baseline(w, n_sample_windows, ticks=0, mixed=None, path=None):
     """The CPU oracle, as it stands, on the first windows of the same workload (one thread)."""
     import numpy as np
     import oracle
@@ -66,6 +66,12 @@ def cpu_baseline(w, n_sample_windows, ticks=0, mixed=None):
         t0 = time.perf_counter()
         oracle.evaluate_ticks(w["profile"], st, n_sample_windows, ticks, w["window_s"] / ticks, w["configs"], w["slos"],
                               w["pct"], None, w["idle_cost_weight"])
+    elif path:
+        st = oracle.ingest(sub, w["edges"], n_sample_windows, w["window_s"])
+        t0 = time.perf_counter()
+        r = oracle.evaluate(w["profile"], st, n_sample_windows, w["window_s"], w["configs"], w["slos"], w["pct"], None,
+                            w["idle_cost_weight"])
+        oracle.select_path(r["cost"], (r["flags"] & 1).astype(np.uint8), n_sample_windows, w["n_class"], path[0], path[1])
     else:
         st = oracle.ingest(sub, w["edges"], n_sample_windows, w["window_s"])
         t0 = time.perf_counter()
@@ -91,6 +97,10 @@ def main():
                     help="mixed-pool search (dyn_eval_select_mixed) with this many load shares; per type up to "
                          "--mixed-gpus / TP instances, and a budget of --mixed-gpus GPUs per class")
     ap.add_argument("--mixed-gpus", type=int, default=32)
+    ap.add_argument("--path", action="store_true",
+                    help="dyn_eval_space + dyn_select_path: selection with transition overheads between consecutive "
+                         "windows (layout = (TP, instances); overhead = 1 %% of the median selected energy per GPU "
+                         "of difference between the layouts)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events (roofline.achieved is then null)")
@@ -163,7 +173,27 @@ def main():
     ws = torch.empty(dyn.dyn_eval_ticks_workspace(NW, T, G, K) if args.ticks else dyn.dyn_eval_space_workspace(NW, G, K),
                      dtype=torch.uint8, device="cuda")
 
-    if args.mixed:
+    if args.path:
+        assert not args.ticks and not args.mixed, "--path, --mixed and --ticks are separate modes"
+        cfgs = w["configs"]
+        key = cfgs["tp_index"].astype(np.int64) * 100000 + cfgs["n_inst"]
+        uniq, lay = np.unique(key, return_inverse=True)
+        lay = lay.astype(np.int32)
+        gpus = w["profile"]["tp"][uniq // 100000].astype(np.int64) * (uniq % 100000)
+        dyn.dyn_eval_space(prof, ins, outs, off, NW, w["window_s"], plan, out=space, workspace=ws)
+        e0 = dyn.dyn_select_config(prof, space, NW, w["window_s"], plan)["sel_energy_j"]
+        e0 = e0[torch.isfinite(e0)]
+        unit_j = float(e0.median()) * 0.01 if e0.numel() else 1.0
+        trans = unit_j * np.abs(gpus[:, None] - gpus[None, :]).astype(np.float64)
+        ws_path = torch.empty(dyn.dyn_select_path_workspace(NW, G, K, uniq.size), dtype=torch.uint8, device="cuda")
+        psel = {"sel": sel["sel"], "sel_energy_j": sel["sel_energy_j"],
+                "path_cost": torch.empty(G, dtype=torch.float64, device="cuda"),
+                "window_energy_j": sel["window_energy_j"], "window_infeasible": sel["window_infeasible"]}
+
+        def step():
+            dyn.dyn_eval_space(prof, ins, outs, off, NW, w["window_s"], plan, out=space, workspace=ws)
+            dyn.dyn_select_path(prof, space, NW, w["window_s"], plan, lay, trans, out=psel, workspace=ws_path)
+    elif args.mixed:
         assert not args.ticks, "--mixed and --ticks are separate modes"
         tp = w["profile"]["tp"]
         n_max = [max(1, args.mixed_gpus // int(t)) for t in tp]
@@ -209,7 +239,7 @@ def main():
     # on the stream the kernels are launched on).  The event records themselves cost about 20 us per
     # step on this machine, which is why they are kept out of the throughput region above.
     ktime = {"cell": 0.0, "space": 0.0, "select": 0.0, "totals": 0.0, "tick_top": 0.0, "tick_space": 0.0, "tick_merge": 0.0,
-             "mixed_types": 0.0, "mixed_combine": 0.0}
+             "mixed_types": 0.0, "mixed_combine": 0.0, "path": 0.0}
     ms_per_step_events = None
     if not args.no_kernel_events:
         dyn.dyn_timing_enable(True, args.steps)
@@ -222,7 +252,8 @@ def main():
         for name, kid in (("cell", dyn.DYN_K_CELL), ("space", dyn.DYN_K_SPACE), ("select", dyn.DYN_K_SELECT),
                           ("totals", dyn.DYN_K_TOTALS), ("tick_top", dyn.DYN_K_TICK_TOP),
                           ("tick_space", dyn.DYN_K_TICK_SPACE), ("tick_merge", dyn.DYN_K_TICK_MERGE),
-                          ("mixed_types", dyn.DYN_K_MIXED_TYPES), ("mixed_combine", dyn.DYN_K_MIXED_COMBINE)):
+                          ("mixed_types", dyn.DYN_K_MIXED_TYPES), ("mixed_combine", dyn.DYN_K_MIXED_COMBINE),
+                          ("path", dyn.DYN_K_PATH)):
             ms, n = dyn.dyn_timing_read(kid)
             ktime[name] = ms / max(n, 1)
         dyn.dyn_timing_enable(False)
@@ -233,7 +264,7 @@ def main():
     space_gbps = space_bytes / (space_ms * 1e-3) / 1e9 if space_ms > 0 else None
     # whole path, algorithmic bytes: read the request stream and offsets once, write the space,
     # re-read energy + flags for the selection, write the selection and the window totals
-    path_bytes = (8.0 * R + 8.0 * (cells + 1) + 25.0 * cells * K + (9.0 * cells * K if args.unfused else 0.0)
+    path_bytes = (8.0 * R + 8.0 * (cells + 1) + 25.0 * cells * K + (9.0 * cells * K if (args.unfused or args.path) else 0.0)
                   + 20.0 * cells + 12.0 * NW + (8.0 * cells * (T - 1) if args.ticks else 0.0))
     path_gbps = path_bytes / (ms_per_step * 1e-3) / 1e9
 
@@ -261,7 +292,7 @@ def main():
     else:
         roofline = {"bound": "hbm", "kernel": "space_kernel", "achieved": space_gbps, "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": space_gbps / HBM_PEAK_GBPS if space_gbps else None,
-                    "traffic": None if args.unfused else recorded_traffic(args.config),
+                    "traffic": None if (args.unfused or args.path) else recorded_traffic(args.config),
                     "algorithmic_bytes_per_launch": space_bytes, "avg_launch_ms": space_ms}
 
     if args.mixed:
@@ -280,7 +311,7 @@ def main():
         "config": {"workload": f"configs[{args.config}] {spec.name}: {R} requests, {NW} windows x {G} classes = "
                                f"{cells} cells, {K} configurations", "requests": R, "cells": cells, "configs": K,
                    "ticks_per_window": args.ticks, "mixed_shares": args.mixed,
-                   "entry_points": "dyn_eval_select_mixed" if args.mixed else "dyn_eval_select_ticks" if args.ticks else
+                   "entry_points": "dyn_eval_space+dyn_select_path" if args.path else "dyn_eval_select_mixed" if args.mixed else "dyn_eval_select_ticks" if args.ticks else
                                    "dyn_eval_space+dyn_select_config" if args.unfused else "dyn_eval_select"},
         "roofline": roofline,
         "kernel_ms": ktime, "ms_per_step_with_kernel_events": ms_per_step_events,
@@ -290,9 +321,9 @@ def main():
         "result": {"workspace_status": status, "cells_without_feasible_config": int((sel_h < 0).sum()), "total_energy_wh": float(we.sum() / 3600.0)},
     }
     if not args.no_cpu_baseline:
-        nwin = args.cpu_windows or max(1, min(NW, int(NW * (5.0e9 if args.mixed else 3.0e9) / (R * K))))
+        nwin = args.cpu_windows or max(1, min(NW, int(NW * (5.0e9 if args.mixed else 1.5e9 if args.path else 3.0e9) / (R * K))))
         mixed = (args.mixed, n_max, np.full(G, args.mixed_gpus, np.int32), K) if args.mixed else None
-        out["cpu_baseline"] = cpu_baseline(w, nwin, args.ticks, mixed)
+        out["cpu_baseline"] = cpu_baseline(w, nwin, args.ticks, mixed, (lay, trans) if args.path else None)
         out["cpu_baseline"]["host_cores"] = os.cpu_count()
     prof.free()
     print(json.dumps(out))

@@ -285,6 +285,39 @@ int dyn_eval_select_mixed(dyn_profile* profile, const dyn_trace_view* trace, con
                           const dyn_objective* objective, const dyn_mixed_selection* out,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------- selection with transition overheads across windows --
+ * Section IV-B "Accounting for the overheads": the cost of changing the configuration is
+ * weighed against the energy the new one saves (Table VI: re-sharding overheads between the
+ * layouts of a server).  Per class the configurations of all windows are chosen together so
+ * that  sum_w cost(w, k_w) + sum_{w>=1} transition_j[layout[k_{w-1}]][layout[k_w]]  is least;
+ * cost and feasibility as in dyn_select_config (reads space->energy_j and space->flags).
+ * The total of a sequence is accumulated in time order: V = cost(0, k_0);
+ * V = (V + transition) + cost(w, k_w).  A window without a feasible configuration gets -1,
+ * ends the sequence before it and the next window starts a new one without a transition;
+ * path_cost[g] adds the sequences' totals in time order from 0.  Where several sequences
+ * reach the least total any one of them is returned.
+ * `layout` HOST [K] in [0, n_layout); `transition_j` HOST [n_layout][n_layout], row = from,
+ * finite and >= 0.  Limits: K <= 2048 and the per-class state (K totals, the transition
+ * table) must fit in LDS: (K + n_layout^2) * 8 bytes + small <= 64 KB, else DYN_E_SHAPE.
+ * Workspace DEVICE, 256-byte aligned, dyn_select_path_workspace bytes.                    */
+typedef struct {
+  int32_t n_layout;
+  const int32_t* layout;
+  const double* transition_j;
+} dyn_transitions;
+typedef struct {
+  int32_t* sel;               /* [cells] chosen configuration, -1 where the window has none */
+  double* sel_energy_j;       /* [cells] its energy, +inf where sel == -1                  */
+  double* path_cost;          /* [G] total cost of the class's sequences incl. transitions */
+  double* window_energy_j;    /* [n_window] as in dyn_selection                            */
+  int32_t* window_infeasible; /* [n_window]                                                */
+} dyn_path_selection;
+size_t dyn_select_path_workspace(int32_t n_window, int32_t n_class, int32_t n_config, int32_t n_layout);
+int dyn_select_path(dyn_profile* profile, const dyn_space* space, const dyn_config* cfg, int32_t K,
+                    const dyn_objective* objective, const dyn_transitions* transitions,
+                    int32_t n_window, double window_s, const dyn_path_selection* out,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------- kernel timing (optional) --
  * Measurement aid, not part of the method: when enabled, the library brackets each of its
  * kernels with a pair of HIP events recorded on the stream the kernel is launched on, so
@@ -299,7 +332,8 @@ int dyn_eval_select_mixed(dyn_profile* profile, const dyn_trace_view* trace, con
 #define DYN_K_TICK_MERGE 6 /* the same for the remaining cells                             */
 #define DYN_K_MIXED_TYPES 7   /* mixed pools: per-type least energies                      */
 #define DYN_K_MIXED_COMBINE 8 /* mixed pools: assignment of instances and shares          */
-#define DYN_K_COUNT 9
+#define DYN_K_PATH 9          /* selection with transition overheads                     */
+#define DYN_K_COUNT 10
 /* on != 0: create the event pool (up to `max_launches` launches per kernel are recorded,
  * later ones are not) and start recording; on == 0: stop and destroy the pool.         */
 int dyn_timing_enable(int on, int32_t max_launches);

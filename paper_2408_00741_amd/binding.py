@@ -21,7 +21,8 @@ __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_t
            "DYN_F_FEASIBLE", "DYN_F_OVERLOAD", "DYN_F_TTFT", "DYN_F_TBT", "DYN_F_BUDGET", "DYN_F_EMPTY",
            "DYN_WS_BAD_OFFSETS", "DYN_WS_BAD_REQUEST", "DYN_WS_TICK_RANK", "dyn_eval_select_ticks",
            "dyn_eval_ticks_workspace", "DYN_K_TICK_TOP", "DYN_K_TICK_SPACE", "DYN_K_TICK_MERGE", "DYN_K_MIXED_TYPES", "DYN_K_MIXED_COMBINE",
-           "MixedPlan", "dyn_mixed_workspace", "dyn_eval_select_mixed", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
+           "MixedPlan", "dyn_mixed_workspace", "dyn_eval_select_mixed", "DYN_K_PATH", "dyn_select_path_workspace",
+           "dyn_select_path", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
 
 DYN_F_FEASIBLE, DYN_F_OVERLOAD, DYN_F_TTFT, DYN_F_TBT, DYN_F_BUDGET, DYN_F_EMPTY = 1, 2, 4, 8, 16, 32
 DYN_WS_BAD_OFFSETS, DYN_WS_BAD_REQUEST, DYN_WS_TICK_RANK = 1, 2, 4
@@ -35,7 +36,7 @@ def lib_path() -> str:
 
 
 if not os.path.exists(lib_path()):
-    raise ImportError(f"{lib_path()} is missing: build it with `python -m paper_2408_00741_amd` "
+    raise ImportError(f"{lib_path()} is missing: build it with `python paper_2408_00741_amd/build.py` "
                       "(there is no fallback implementation)")
 _lib = C.CDLL(lib_path())
 
@@ -84,6 +85,15 @@ class _MixedSelection(C.Structure):
                 ("window_infeasible", _vp)]
 
 
+class _Transitions(C.Structure):
+    _fields_ = [("n_layout", _i32), ("layout", _vp), ("transition_j", _vp)]
+
+
+class _PathSelection(C.Structure):
+    _fields_ = [("sel", _vp), ("sel_energy_j", _vp), ("path_cost", _vp), ("window_energy_j", _vp),
+                ("window_infeasible", _vp)]
+
+
 _lib.dyn_last_error.restype = C.c_char_p
 _lib.dyn_profile_load.restype = C.c_int
 _lib.dyn_profile_load.argtypes = [C.POINTER(_ProfileDesc), _vp, C.POINTER(_vp)]
@@ -121,13 +131,18 @@ _lib.dyn_mixed_workspace.argtypes = [_vp, _i32, C.POINTER(_MixedSpace)]
 _lib.dyn_eval_select_mixed.restype = C.c_int
 _lib.dyn_eval_select_mixed.argtypes = [_vp, C.POINTER(_TraceView), C.POINTER(_MixedSpace), C.POINTER(_Objective),
                                        C.POINTER(_MixedSelection), _vp, _sz, _vp]
+_lib.dyn_select_path_workspace.restype = _sz
+_lib.dyn_select_path_workspace.argtypes = [_i32, _i32, _i32, _i32]
+_lib.dyn_select_path.restype = C.c_int
+_lib.dyn_select_path.argtypes = [_vp, C.POINTER(_Space), C.POINTER(_Config), _i32, C.POINTER(_Objective),
+                                 C.POINTER(_Transitions), _i32, _f64, C.POINTER(_PathSelection), _vp, _sz, _vp]
 _lib.dyn_timing_enable.restype = C.c_int
 _lib.dyn_timing_enable.argtypes = [C.c_int, _i32]
 _lib.dyn_timing_reset.restype = C.c_int
 _lib.dyn_timing_read.restype = C.c_int
 _lib.dyn_timing_read.argtypes = [_i32, C.POINTER(C.c_double), C.POINTER(_i64)]
 (DYN_K_CELL, DYN_K_SPACE, DYN_K_SELECT, DYN_K_TOTALS, DYN_K_TICK_TOP, DYN_K_TICK_SPACE, DYN_K_TICK_MERGE,
- DYN_K_MIXED_TYPES, DYN_K_MIXED_COMBINE) = range(9)
+ DYN_K_MIXED_TYPES, DYN_K_MIXED_COMBINE, DYN_K_PATH) = range(10)
 
 
 def dyn_timing_enable(on: bool, max_launches: int = 4096):
@@ -444,6 +459,42 @@ def dyn_eval_select_mixed(profile: Profile, in_tok: torch.Tensor, out_tok: torch
             raise ValueError("selection tensors must hold n_window*G*n_tp entries")
     _check(_lib.dyn_eval_select_mixed(profile.handle, C.byref(tv), C.byref(plan.space), C.byref(plan.obj), C.byref(se),
                                       _dp(workspace), workspace.numel(), _stream(stream)), "dyn_eval_select_mixed")
+    return out, workspace
+
+
+def dyn_select_path_workspace(n_window: int, n_class: int, n_config: int, n_layout: int) -> int:
+    return int(_lib.dyn_select_path_workspace(n_window, n_class, n_config, n_layout))
+
+
+def dyn_select_path(profile: Profile, space: Dict[str, torch.Tensor], n_window: int, window_s: float, plan: Plan,
+                    layout, transition_j, out: Optional[Dict[str, torch.Tensor]] = None,
+                    workspace: Optional[torch.Tensor] = None, stream=None):
+    """Selection with transition overheads between consecutive windows.  Returns (selection, workspace)."""
+    G, K = profile.n_class, plan.K
+    cells = n_window * G
+    dev = space["energy_j"].device
+    if space["energy_j"].numel() != cells * K or space["flags"].numel() != cells * K:
+        raise ValueError("space tensors must hold n_window*G*K entries")
+    lay = _host(layout, np.int32); tr = _host(transition_j, np.float64)
+    if lay.size != K or tr.ndim != 2 or tr.shape[0] != tr.shape[1]:
+        raise ValueError("layout needs K entries and transition_j must be square")
+    if out is None:
+        out = {"sel": torch.empty(cells, dtype=torch.int32, device=dev),
+               "sel_energy_j": torch.empty(cells, dtype=torch.float64, device=dev),
+               "path_cost": torch.empty(G, dtype=torch.float64, device=dev),
+               "window_energy_j": torch.empty(n_window, dtype=torch.float64, device=dev),
+               "window_infeasible": torch.empty(n_window, dtype=torch.int32, device=dev)}
+    if workspace is None:
+        workspace = _workspace(max(256, dyn_select_path_workspace(n_window, G, K, tr.shape[0])), dev)
+    sp = _Space(_dp(space["energy_j"], torch.float64), _dp(space.get("p99_ttft_ms")), _dp(space.get("p99_tbt_ms")),
+                _dp(space["flags"], torch.uint8))
+    tt = _Transitions(int(tr.shape[0]), _hp(lay), _hp(tr))
+    se = _PathSelection(_dp(out["sel"], torch.int32), _dp(out["sel_energy_j"], torch.float64),
+                        _dp(out["path_cost"], torch.float64), _dp(out["window_energy_j"], torch.float64),
+                        _dp(out["window_infeasible"], torch.int32))
+    _check(_lib.dyn_select_path(profile.handle, C.byref(sp), plan.cfg, K, C.byref(plan.obj), C.byref(tt), n_window,
+                                float(window_s), C.byref(se), _dp(workspace), workspace.numel(), _stream(stream)),
+           "dyn_select_path")
     return out, workspace
 
 

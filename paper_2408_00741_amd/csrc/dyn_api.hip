@@ -13,6 +13,7 @@
 
 #include "dyn_ticks.h"
 #include "dyn_mixed.h"
+#include "dyn_path.h"
 
 namespace {
 
@@ -752,6 +753,90 @@ int dyn_eval_select_mixed(dyn_profile* p, const dyn_trace_view* t, const dyn_mix
   ca.ok = (int32_t*)(base + w.ok);
   if (!hip_ok(dyn_launch_mixed_combine(ca, s), "mixed combine launch")) return DYN_E_DEVICE;
   if (!hip_ok(dyn_launch_window_totals(ca.ok, out->energy_j, t->n_window, p->G, out->window_energy_j,
+                                       out->window_infeasible, s),
+              "window totals launch"))
+    return DYN_E_DEVICE;
+  return DYN_OK;
+}
+
+namespace {
+struct PathWs { size_t layout, order, seg, transition, pred, kend, total; };
+PathWs path_ws_layout(int32_t n_window, int32_t G, int32_t K, int32_t n_layout) {
+  PathWs w;
+  size_t off = 0;
+  w.layout = off; off += align256((size_t)K * sizeof(int32_t));
+  w.order = off; off += align256((size_t)K * sizeof(int32_t));
+  w.seg = off; off += align256(((size_t)n_layout + 1) * sizeof(int32_t));
+  w.transition = off; off += align256((size_t)n_layout * n_layout * sizeof(double));
+  w.pred = off; off += align256((size_t)G * n_window * n_layout * sizeof(int32_t));
+  w.kend = off; off += align256((size_t)G * n_window * sizeof(int32_t));
+  w.total = off;
+  return w;
+}
+}  // namespace
+
+size_t dyn_select_path_workspace(int32_t n_window, int32_t n_class, int32_t n_config, int32_t n_layout) {
+  if (n_window < 1 || n_class < 1 || n_config < 1 || n_layout < 1) return 0;
+  return path_ws_layout(n_window, n_class, n_config, n_layout).total;
+}
+
+int dyn_select_path(dyn_profile* p, const dyn_space* space, const dyn_config* cfg, int32_t K, const dyn_objective* o,
+                    const dyn_transitions* tr, int32_t n_window, double window_s, const dyn_path_selection* out,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!p || !space || !o || !tr || !out || !workspace) { dyn_set_error("profile, space, objective, transitions, out or workspace is NULL"); return DYN_E_NULL; }
+  if (!space->energy_j || !space->flags) { dyn_set_error("space->energy_j or space->flags is NULL"); return DYN_E_NULL; }
+  if (!out->sel || !out->sel_energy_j || !out->path_cost || !out->window_energy_j || !out->window_infeasible) { dyn_set_error("an output array is NULL"); return DYN_E_NULL; }
+  if (!tr->layout || !tr->transition_j) { dyn_set_error("layout or transition_j is NULL"); return DYN_E_NULL; }
+  if (n_window < 1) { dyn_set_error("n_window < 1"); return DYN_E_SHAPE; }
+  if (!(window_s > 0.0) || !isfinite(window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  if (!isfinite(o->idle_cost_weight)) { dyn_set_error("idle_cost_weight is not finite"); return DYN_E_NOTFINITE; }
+  if (o->idle_cost_weight < 0.0) { dyn_set_error("idle_cost_weight must be >= 0"); return DYN_E_RANGE; }
+  if ((int64_t)n_window * p->G >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
+  if (K < 1 || K > DYN_PATH_MAX_CONFIGS || tr->n_layout < 1 || tr->n_layout > 255 || dyn_path_lds(K, tr->n_layout) > DYN_LDS_BUDGET) {
+    dyn_set_error("K=%d (at most %d), n_layout=%d: the per-class state does not fit in registers and LDS", K, DYN_PATH_MAX_CONFIGS, tr->n_layout);
+    return DYN_E_SHAPE;
+  }
+  for (int k = 0; k < K; ++k)
+    if (tr->layout[k] < 0 || tr->layout[k] >= tr->n_layout) { dyn_set_error("layout[%d]=%d outside [0, %d)", k, tr->layout[k], tr->n_layout); return DYN_E_RANGE; }
+  for (int64_t i = 0; i < (int64_t)tr->n_layout * tr->n_layout; ++i) {
+    if (!isfinite(tr->transition_j[i])) { dyn_set_error("transition_j[%lld] is not finite", (long long)i); return DYN_E_NOTFINITE; }
+    if (tr->transition_j[i] < 0.0) { dyn_set_error("transition_j[%lld] < 0", (long long)i); return DYN_E_RANGE; }
+  }
+  int rc = check_device(p);
+  if (rc) return rc;
+  const PathWs w = path_ws_layout(n_window, p->G, K, tr->n_layout);
+  if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) {
+    dyn_set_error("workspace misaligned or too small (%zu < %zu)", workspace_bytes, w.total);
+    return DYN_E_WORKSPACE;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  if ((rc = prepare_configs(p, cfg, K, s)) != DYN_OK) return rc;
+  char* base = (char*)workspace;
+  // candidates sorted by (layout, index): a layout's candidates are then one contiguous run
+  std::vector<int32_t> order(K), seg(tr->n_layout + 1, 0);
+  for (int k = 0; k < K; ++k) seg[tr->layout[k] + 1] += 1;
+  for (int l = 0; l < tr->n_layout; ++l) seg[l + 1] += seg[l];
+  {
+    std::vector<int32_t> fill(seg.begin(), seg.end() - 1);
+    for (int k = 0; k < K; ++k) order[fill[tr->layout[k]]++] = k;
+  }
+  // the host tables are small; they are copied before the call returns
+  if (!hip_ok(hipMemcpyAsync(base + w.layout, tr->layout, (size_t)K * sizeof(int32_t), hipMemcpyHostToDevice, s), "copy layout") ||
+      !hip_ok(hipMemcpyAsync(base + w.order, order.data(), (size_t)K * sizeof(int32_t), hipMemcpyHostToDevice, s), "copy order") ||
+      !hip_ok(hipMemcpyAsync(base + w.seg, seg.data(), seg.size() * sizeof(int32_t), hipMemcpyHostToDevice, s), "copy segments") ||
+      !hip_ok(hipMemcpyAsync(base + w.transition, tr->transition_j, (size_t)tr->n_layout * tr->n_layout * sizeof(double),
+                             hipMemcpyHostToDevice, s), "copy transitions") ||
+      !hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize"))
+    return DYN_E_DEVICE;
+  PathArgs a;
+  a.energy = space->energy_j; a.flags = space->flags; a.cfg = p->d_cfg; a.K = K; a.pw0 = p->d_pw0;
+  a.G = p->G; a.n_tp_f = p->n_tp * p->n_f; a.n_window = n_window; a.window_s = window_s; a.idle_w = o->idle_cost_weight;
+  a.n_layout = tr->n_layout; a.layout = (const int32_t*)(base + w.layout); a.transition = (const double*)(base + w.transition);
+  a.order = (const int32_t*)(base + w.order); a.seg_start = (const int32_t*)(base + w.seg);
+  a.pred = (int32_t*)(base + w.pred); a.kend = (int32_t*)(base + w.kend);
+  a.sel = out->sel; a.sel_energy = out->sel_energy_j; a.path_cost = out->path_cost;
+  if (!hip_ok(dyn_launch_path(a, s), "path launch")) return DYN_E_DEVICE;
+  if (!hip_ok(dyn_launch_window_totals(out->sel, out->sel_energy_j, n_window, p->G, out->window_energy_j,
                                        out->window_infeasible, s),
               "window totals launch"))
     return DYN_E_DEVICE;
