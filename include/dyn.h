@@ -318,6 +318,39 @@ int dyn_select_path(dyn_profile* profile, const dyn_space* space, const dyn_conf
                     int32_t n_window, double window_s, const dyn_path_selection* out,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---------------------------------------------------------- cost and carbon of a selection --
+ * Section VI "Cost and Carbon Emission": the user's cost follows the GPU servers in use over
+ * time and the energy bill; operational CO2 is each interval's energy times the grid's
+ * carbon intensity at that time.  Per window: GPUs = sum over the classes with a selection
+ * (sel >= 0) of n_inst * tp; GPU-hours = ((double) GPUs * window_s) / 3600; GPU cost =
+ * GPU-hours * gpu_hour_price; kWh = window_energy_j / 3.6e6; energy cost = kWh * kwh_price;
+ * carbon = kWh * carbon_g_per_kwh[w]; servers = ceil(GPUs / gpus_per_server).
+ * totals[5] = {GPU-hours, GPU cost, energy cost, carbon in g, servers summed over the
+ * windows}, each added in window order from 0.
+ * `sel` DEVICE [n_window*G] and `window_energy_j` DEVICE [n_window] as a selection entry point
+ * returns them; `carbon_g_per_kwh` DEVICE [n_window]; outputs DEVICE; `cfg` HOST [K] (the
+ * candidate list the selection indexes).  Workspace DEVICE, 256-byte aligned,
+ * dyn_account_workspace bytes; its status word reports sel values >= K (DYN_WS_BAD_REQUEST),
+ * which count as no selection.                                                           */
+typedef struct {
+  double gpu_hour_price;       /* currency per GPU-hour                                   */
+  double kwh_price;            /* currency per kWh                                        */
+  const double* carbon_g_per_kwh; /* DEVICE [n_window]                                    */
+  int32_t gpus_per_server;     /* >= 1                                                    */
+} dyn_rates;
+typedef struct {
+  int64_t* gpus;       /* [n_window] */
+  double* gpu_cost;    /* [n_window] */
+  double* energy_cost; /* [n_window] */
+  double* carbon_g;    /* [n_window] */
+  double* totals;      /* [5]        */
+} dyn_accounting;
+size_t dyn_account_workspace(int32_t n_window);
+int dyn_account(dyn_profile* profile, const int32_t* sel, const double* window_energy_j,
+                const dyn_config* cfg, int32_t K, int32_t n_window, double window_s,
+                const dyn_rates* rates, const dyn_accounting* out, void* workspace,
+                size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------- kernel timing (optional) --
  * Measurement aid, not part of the method: when enabled, the library brackets each of its
  * kernels with a pair of HIP events recorded on the stream the kernel is launched on, so

@@ -196,6 +196,25 @@ def select_path(space_cost: np.ndarray, feasible: np.ndarray, n_window: int, n_c
     return sel, pc
 
 
+def account(configs: Dict[str, np.ndarray], tp, sel: np.ndarray, window_energy_j: np.ndarray, n_window: int, n_class: int,
+            window_s: float, gpu_hour_price: float, kwh_price: float, carbon_g_per_kwh, gpus_per_server: int = 8):
+    """Cost and carbon of a selection; see dynoracle_account."""
+    lib = _load()
+    lib.dynoracle_account.restype = C.c_int
+    cn = _c(configs["n_inst"], np.int32); ct = _c(configs["tp_index"], np.int32); tpa = _c(tp, np.int32)
+    s_ = _c(sel, np.int32); we = _c(window_energy_j, np.float64); ci = _c(carbon_g_per_kwh, np.float64)
+    assert s_.size == n_window * n_class and we.size == n_window and ci.size == n_window
+    r = {"gpus": np.empty(n_window, np.int64), "gpu_cost": np.empty(n_window), "energy_cost": np.empty(n_window),
+         "carbon_g": np.empty(n_window), "totals": np.empty(5)}
+    rc = lib.dynoracle_account(C.c_int32(n_window), C.c_int32(n_class), C.c_int32(cn.size), _ptr(cn), _ptr(ct), _ptr(tpa),
+                               _ptr(s_), _ptr(we), C.c_double(window_s), C.c_double(gpu_hour_price), C.c_double(kwh_price),
+                               _ptr(ci), C.c_int32(gpus_per_server), _ptr(r["gpus"]), _ptr(r["gpu_cost"]),
+                               _ptr(r["energy_cost"]), _ptr(r["carbon_g"]), _ptr(r["totals"]))
+    if rc != 0:
+        raise ValueError(f"dynoracle_account failed: {rc}")
+    return r
+
+
 def window_totals(sel: np.ndarray, sel_energy_j: np.ndarray, n_window: int, n_class: int):
     lib = _load()
     s = _c(sel, np.int32); e = _c(sel_energy_j, np.float64)

@@ -632,6 +632,43 @@ int dynoracle_select_path(int32_t n_window, int32_t G, int32_t K, const double* 
   return ORC_OK;
 }
 
+// Cost and carbon of a selection (Section VI "Cost and Carbon Emission": the user's cost follows
+// the number of GPU servers over time and the energy bill; operational CO2 is the energy of each
+// interval times the grid's carbon intensity at that time).
+// Per window: GPUs in use = sum over the classes with a selection of n_inst x tp; servers =
+// ceil(GPUs / gpus_per_server); GPU-hours = ((double) GPUs x window_s) / 3600; GPU cost =
+// GPU-hours x gpu_hour_price; kWh = window energy / 3.6e6; energy cost = kWh x kwh_price;
+// carbon = kWh x carbon intensity of the window (g/kWh).  Totals are summed in window order
+// from 0: {GPU-hours, GPU cost, energy cost, carbon in g, servers summed over the windows}.
+int dynoracle_account(int32_t n_window, int32_t G, int32_t K, const int32_t* cfg_n, const int32_t* cfg_tp_index,
+                      const int32_t* tp, const int32_t* sel, const double* window_energy_j, double window_s,
+                      double gpu_hour_price, double kwh_price, const double* carbon_g_per_kwh, int32_t gpus_per_server,
+                      int64_t* gpus, double* gpu_cost, double* energy_cost, double* carbon_g, double* totals) {
+  if (!cfg_n || !cfg_tp_index || !tp || !sel || !window_energy_j || !carbon_g_per_kwh || !gpus || !gpu_cost ||
+      !energy_cost || !carbon_g || !totals)
+    return ORC_E_NULL;
+  if (n_window < 1 || G < 1 || K < 1 || gpus_per_server < 1) return ORC_E_SHAPE;
+  double t_hours = 0.0, t_gpu = 0.0, t_energy = 0.0, t_carbon = 0.0, t_servers = 0.0;
+  for (int w = 0; w < n_window; ++w) {
+    int64_t used = 0;
+    for (int g = 0; g < G; ++g) {
+      const int32_t k = sel[(int64_t)w * G + g];
+      if (k >= K) return ORC_E_RANGE;
+      if (k >= 0) used += (int64_t)cfg_n[k] * tp[cfg_tp_index[k]];
+    }
+    const double hours = ((double)used * window_s) / 3600.0;
+    const double kwh = window_energy_j[w] / 3.6e6;
+    gpus[w] = used;
+    gpu_cost[w] = hours * gpu_hour_price;
+    energy_cost[w] = kwh * kwh_price;
+    carbon_g[w] = kwh * carbon_g_per_kwh[w];
+    t_hours += hours; t_gpu += gpu_cost[w]; t_energy += energy_cost[w]; t_carbon += carbon_g[w];
+    t_servers += (double)((used + gpus_per_server - 1) / gpus_per_server);
+  }
+  totals[0] = t_hours; totals[1] = t_gpu; totals[2] = t_energy; totals[3] = t_carbon; totals[4] = t_servers;
+  return ORC_OK;
+}
+
 // Objective summed over the pools of a window (Eq. 1 sums over instance types; here one
 // pool per class), classes added in index order; cells without a feasible configuration
 // are counted, not added.

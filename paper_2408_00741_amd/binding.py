@@ -22,7 +22,7 @@ __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_t
            "DYN_WS_BAD_OFFSETS", "DYN_WS_BAD_REQUEST", "DYN_WS_TICK_RANK", "dyn_eval_select_ticks",
            "dyn_eval_ticks_workspace", "DYN_K_TICK_TOP", "DYN_K_TICK_SPACE", "DYN_K_TICK_MERGE", "DYN_K_MIXED_TYPES", "DYN_K_MIXED_COMBINE",
            "MixedPlan", "dyn_mixed_workspace", "dyn_eval_select_mixed", "DYN_K_PATH", "dyn_select_path_workspace",
-           "dyn_select_path", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
+           "dyn_select_path", "dyn_account_workspace", "dyn_account", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
 
 DYN_F_FEASIBLE, DYN_F_OVERLOAD, DYN_F_TTFT, DYN_F_TBT, DYN_F_BUDGET, DYN_F_EMPTY = 1, 2, 4, 8, 16, 32
 DYN_WS_BAD_OFFSETS, DYN_WS_BAD_REQUEST, DYN_WS_TICK_RANK = 1, 2, 4
@@ -94,6 +94,14 @@ class _PathSelection(C.Structure):
                 ("window_infeasible", _vp)]
 
 
+class _Rates(C.Structure):
+    _fields_ = [("gpu_hour_price", _f64), ("kwh_price", _f64), ("carbon_g_per_kwh", _vp), ("gpus_per_server", _i32)]
+
+
+class _Accounting(C.Structure):
+    _fields_ = [("gpus", _vp), ("gpu_cost", _vp), ("energy_cost", _vp), ("carbon_g", _vp), ("totals", _vp)]
+
+
 _lib.dyn_last_error.restype = C.c_char_p
 _lib.dyn_profile_load.restype = C.c_int
 _lib.dyn_profile_load.argtypes = [C.POINTER(_ProfileDesc), _vp, C.POINTER(_vp)]
@@ -136,6 +144,11 @@ _lib.dyn_select_path_workspace.argtypes = [_i32, _i32, _i32, _i32]
 _lib.dyn_select_path.restype = C.c_int
 _lib.dyn_select_path.argtypes = [_vp, C.POINTER(_Space), C.POINTER(_Config), _i32, C.POINTER(_Objective),
                                  C.POINTER(_Transitions), _i32, _f64, C.POINTER(_PathSelection), _vp, _sz, _vp]
+_lib.dyn_account_workspace.restype = _sz
+_lib.dyn_account_workspace.argtypes = [_i32]
+_lib.dyn_account.restype = C.c_int
+_lib.dyn_account.argtypes = [_vp, _vp, _vp, C.POINTER(_Config), _i32, _i32, _f64, C.POINTER(_Rates),
+                             C.POINTER(_Accounting), _vp, _sz, _vp]
 _lib.dyn_timing_enable.restype = C.c_int
 _lib.dyn_timing_enable.argtypes = [C.c_int, _i32]
 _lib.dyn_timing_reset.restype = C.c_int
@@ -496,6 +509,32 @@ def dyn_select_path(profile: Profile, space: Dict[str, torch.Tensor], n_window: 
                                 float(window_s), C.byref(se), _dp(workspace), workspace.numel(), _stream(stream)),
            "dyn_select_path")
     return out, workspace
+
+
+def dyn_account_workspace(n_window: int) -> int:
+    return int(_lib.dyn_account_workspace(n_window))
+
+
+def dyn_account(profile: Profile, sel: torch.Tensor, window_energy_j: torch.Tensor, plan: Plan, n_window: int,
+                window_s: float, gpu_hour_price: float, kwh_price: float, carbon_g_per_kwh: torch.Tensor,
+                gpus_per_server: int = 8, stream=None):
+    """Cost and carbon of a selection.  Returns (dict of per-window tensors + totals[5], workspace)."""
+    dev = sel.device
+    if sel.numel() != n_window * profile.n_class or window_energy_j.numel() != n_window or carbon_g_per_kwh.numel() != n_window:
+        raise ValueError("sel needs n_window*G entries, window_energy_j and carbon_g_per_kwh n_window")
+    out = {"gpus": torch.empty(n_window, dtype=torch.int64, device=dev),
+           "gpu_cost": torch.empty(n_window, dtype=torch.float64, device=dev),
+           "energy_cost": torch.empty(n_window, dtype=torch.float64, device=dev),
+           "carbon_g": torch.empty(n_window, dtype=torch.float64, device=dev),
+           "totals": torch.empty(5, dtype=torch.float64, device=dev)}
+    ws = _workspace(dyn_account_workspace(n_window), dev)
+    rates = _Rates(float(gpu_hour_price), float(kwh_price), _dp(carbon_g_per_kwh, torch.float64), int(gpus_per_server))
+    acc = _Accounting(_dp(out["gpus"], torch.int64), _dp(out["gpu_cost"], torch.float64), _dp(out["energy_cost"], torch.float64),
+                      _dp(out["carbon_g"], torch.float64), _dp(out["totals"], torch.float64))
+    _check(_lib.dyn_account(profile.handle, _dp(sel, torch.int32), _dp(window_energy_j, torch.float64), plan.cfg, plan.K,
+                            n_window, float(window_s), C.byref(rates), C.byref(acc), _dp(ws), ws.numel(), _stream(stream)),
+           "dyn_account")
+    return out, ws
 
 
 def dyn_cell_stats(workspace: torch.Tensor, n_window: int, n_class: int, stream=None):

@@ -14,6 +14,7 @@
 #include "dyn_ticks.h"
 #include "dyn_mixed.h"
 #include "dyn_path.h"
+#include "dyn_account.h"
 
 namespace {
 
@@ -840,6 +841,39 @@ int dyn_select_path(dyn_profile* p, const dyn_space* space, const dyn_config* cf
                                        out->window_infeasible, s),
               "window totals launch"))
     return DYN_E_DEVICE;
+  return DYN_OK;
+}
+
+size_t dyn_account_workspace(int32_t n_window) {
+  if (n_window < 1) return 0;
+  return 256 + 2 * align256((size_t)n_window * sizeof(double));
+}
+
+int dyn_account(dyn_profile* p, const int32_t* sel, const double* window_energy_j, const dyn_config* cfg, int32_t K,
+                int32_t n_window, double window_s, const dyn_rates* r, const dyn_accounting* out, void* workspace,
+                size_t workspace_bytes, void* hip_stream) {
+  if (!p || !sel || !window_energy_j || !r || !out || !workspace) { dyn_set_error("profile, sel, window_energy_j, rates, out or workspace is NULL"); return DYN_E_NULL; }
+  if (!r->carbon_g_per_kwh || !out->gpus || !out->gpu_cost || !out->energy_cost || !out->carbon_g || !out->totals) { dyn_set_error("an array is NULL"); return DYN_E_NULL; }
+  if (n_window < 1 || r->gpus_per_server < 1) { dyn_set_error("n_window or gpus_per_server < 1"); return DYN_E_SHAPE; }
+  if (!(window_s > 0.0) || !isfinite(window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  if (!isfinite(r->gpu_hour_price) || !isfinite(r->kwh_price)) { dyn_set_error("a price is not finite"); return DYN_E_NOTFINITE; }
+  int rc = check_device(p);
+  if (rc) return rc;
+  const size_t per = align256((size_t)n_window * sizeof(double));
+  if (((uintptr_t)workspace & 255) || workspace_bytes < 256 + 2 * per) { dyn_set_error("workspace misaligned or too small"); return DYN_E_WORKSPACE; }
+  hipStream_t s = (hipStream_t)hip_stream;
+  if ((rc = prepare_configs(p, cfg, K, s)) != DYN_OK) return rc;
+  char* base = (char*)workspace;
+  hipLaunchKernelGGL(init_word_header_kernel, dim3(1), dim3(1), 0, s, (WsHeader*)base);
+  if (!hip_ok(hipGetLastError(), "launch")) return DYN_E_DEVICE;
+  AccountArgs a;
+  a.sel = sel; a.window_energy = window_energy_j; a.carbon = r->carbon_g_per_kwh;
+  a.cfg = p->d_cfg; a.K = K; a.G = p->G; a.n_window = n_window; a.window_s = window_s;
+  a.gpu_hour_price = r->gpu_hour_price; a.kwh_price = r->kwh_price; a.gpus_per_server = r->gpus_per_server;
+  a.gpus = out->gpus; a.gpu_cost = out->gpu_cost; a.energy_cost = out->energy_cost; a.carbon_g = out->carbon_g; a.totals = out->totals;
+  a.hours = (double*)(base + 256); a.servers = (double*)(base + 256 + per);
+  a.status = &((WsHeader*)base)->status;
+  if (!hip_ok(dyn_launch_account(a, s), "account launch")) return DYN_E_DEVICE;
   return DYN_OK;
 }
 

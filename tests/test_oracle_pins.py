@@ -740,6 +740,47 @@ def test_path_with_prohibitive_overheads_keeps_one_layout(small_hour):
             np.testing.assert_allclose(pc[g], best, rtol=1e-12)
 
 
+# ----------------------------------------------------------------------- cost and carbon
+def test_account_reproduces_the_papers_cost_and_carbon_figures():
+    """Section "Cost and Carbon Emission": 40 -> 24.6 GPU servers on average is a 38.5 % cost reduction and saves
+    $1362.7 per hour; 5 t -> 3.1 t of CO2 per week is 38 %."""
+    cfg = _configs([(1, 0, 1000.0)])                      # one candidate: one 8-GPU server
+    tp = [8]
+    NW, W = 1000, 3600.0
+    price = 1362.7 / (40 - 24.6)                          # $ per server-hour implied by the printed saving
+    ci = np.full(NW, 400.0)
+    base_sel = np.zeros(NW * 40, np.int32)                # 40 servers all the time
+    dyn_sel = np.where(np.arange(NW * 40) % 40 < 24, 0, -1).astype(np.int32)
+    dyn_sel[(np.arange(NW * 40) % 40 == 24) & (np.arange(NW * 40) // 40 < 600)] = 0     # 24.6 on average
+    e_base = np.full(NW, 5.0e6 / 400.0 * 3.6e6 / NW)       # 5 t at 400 g/kWh over the period
+    e_dyn = e_base * (3.1 / 5.0)
+    a = oracle.account(cfg, tp, base_sel, e_base, NW, 40, W, price / 8, 0.0, ci)
+    b = oracle.account(cfg, tp, dyn_sel, e_dyn, NW, 40, W, price / 8, 0.0, ci)
+    assert a["totals"][4] / NW == 40.0 and abs(b["totals"][4] / NW - 24.6) < 1e-12
+    np.testing.assert_allclose(1 - b["totals"][1] / a["totals"][1], 0.385, atol=5e-4)
+    np.testing.assert_allclose((a["totals"][1] - b["totals"][1]) / NW, 1362.7, rtol=1e-12)    # $ per hour (1-hour windows)
+    np.testing.assert_allclose(a["totals"][3], 5.0e6, rtol=1e-12)
+    np.testing.assert_allclose(b["totals"][3], 3.1e6, rtol=1e-12)
+    np.testing.assert_allclose(1 - b["totals"][3] / a["totals"][3], 0.38, atol=1e-12)
+
+
+def test_account_against_numpy(small_hour):
+    w, st, r = small_hour
+    rng = np.random.default_rng(3)
+    NW, G = w["n_window"], w["n_class"]
+    cfg, tp = w["configs"], w["profile"]["tp"]
+    we, wi = oracle.window_totals(r["sel"], r["sel_energy_j"], NW, G)
+    ci = rng.uniform(100, 600, NW)
+    a = oracle.account(cfg, tp, r["sel"], we, NW, G, w["window_s"], 11.0, 0.12, ci, 8)
+    used = np.where(r["sel"] >= 0, cfg["n_inst"][r["sel"]] * tp[cfg["tp_index"][r["sel"]]], 0).reshape(NW, G).sum(axis=1)
+    np.testing.assert_array_equal(a["gpus"], used)
+    np.testing.assert_allclose(a["gpu_cost"], used * w["window_s"] / 3600 * 11.0, rtol=1e-14)
+    np.testing.assert_allclose(a["energy_cost"], we / 3.6e6 * 0.12, rtol=1e-14)
+    np.testing.assert_allclose(a["carbon_g"], we / 3.6e6 * ci, rtol=1e-14)
+    np.testing.assert_allclose(a["totals"], [used.sum() * w["window_s"] / 3600, a["gpu_cost"].sum(), a["energy_cost"].sum(),
+                                            a["carbon_g"].sum(), np.ceil(used / 8).sum()], rtol=1e-12)
+
+
 # ----------------------------------------------------------- planted mistakes are caught
 def test_pins_catch_planted_mistakes():
     """Sanity of the pins themselves: perturbing the inputs the way a typical slip would
