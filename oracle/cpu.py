@@ -215,6 +215,38 @@ def account(configs: Dict[str, np.ndarray], tp, sel: np.ndarray, window_energy_j
     return r
 
 
+def hierarchy(profile: Dict[str, np.ndarray], coarse: Dict[str, np.ndarray], fine: Dict[str, np.ndarray], n_window: int,
+              n_tick: int, tick_s: float, epoch_windows: int, tp_ref: int, f_ref: int, gpus_per_node: int,
+              lay_n, lay_tp, slos: Dict[str, np.ndarray], pct=(99, 100)) -> Dict[str, np.ndarray]:
+    """Scale-out / shard / frequency controllers, top down; see dynoracle_hierarchy."""
+    lib = _load()
+    lib.dynoracle_hierarchy.restype = C.c_int
+    tp = _c(profile["tp"], np.int32); fg = _c(profile["f_mhz"], np.float64); rg = _c(profile["rho"], np.float64)
+    PF = _c(profile["prefill_ms_per_tok"], np.float64); TB = _c(profile["tbt_ms"], np.float64)
+    PW = _c(profile["power_w"], np.float64); ML = _c(profile["max_load_tps"], np.float64)
+    G = PF.shape[0]
+    ic = _c(coarse["in_tok"], np.int32); oc = _c(coarse["out_tok"], np.int32); co = _c(coarse["cell_off"], np.int64)
+    if_ = _c(fine["in_tok"], np.int32); of_ = _c(fine["out_tok"], np.int32); fo = _c(fine["cell_off"], np.int64)
+    assert co.size == n_window * G + 1 and fo.size == n_window * n_tick * G + 1 and ic.size == if_.size
+    ln = _c(lay_n, np.int32); lt = _c(lay_tp, np.int32)
+    st = _c(slos["slo_ttft_ms"], np.float64); sb = _c(slos["slo_tbt_ms"], np.float64)
+    n_epoch = (n_window + epoch_windows - 1) // epoch_windows
+    cells = n_window * G
+    r = {"nodes": np.empty((n_epoch, G), np.int32), "layout_sel": np.empty(cells, np.int32),
+         "f_sel": np.empty((n_window * n_tick, G), np.int32), "energy_j": np.empty(cells),
+         "violations": np.empty(cells, np.int32)}
+    rc = lib.dynoracle_hierarchy(
+        C.c_int32(G), C.c_int32(tp.size), _ptr(tp), C.c_int32(fg.size), _ptr(fg), C.c_int32(rg.size), _ptr(rg),
+        _ptr(PF), _ptr(TB), _ptr(PW), _ptr(ML), C.c_int64(ic.size), C.c_int32(n_window), C.c_int32(n_tick),
+        C.c_double(tick_s), _ptr(ic), _ptr(oc), _ptr(co), _ptr(if_), _ptr(of_), _ptr(fo), C.c_int32(epoch_windows),
+        C.c_int32(tp_ref), C.c_int32(f_ref), C.c_int32(gpus_per_node), C.c_int32(ln.size), _ptr(ln), _ptr(lt), _ptr(st),
+        _ptr(sb), C.c_int32(pct[0]), C.c_int32(pct[1]), _ptr(r["nodes"]), _ptr(r["layout_sel"]), _ptr(r["f_sel"]),
+        _ptr(r["energy_j"]), _ptr(r["violations"]))
+    if rc != 0:
+        raise ValueError(f"dynoracle_hierarchy failed: {rc}")
+    return r
+
+
 def window_totals(sel: np.ndarray, sel_energy_j: np.ndarray, n_window: int, n_class: int):
     lib = _load()
     s = _c(sel, np.int32); e = _c(sel_energy_j, np.float64)

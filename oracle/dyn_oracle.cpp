@@ -669,6 +669,146 @@ int dynoracle_account(int32_t n_window, int32_t G, int32_t K, const int32_t* cfg
   return ORC_OK;
 }
 
+// The three controllers of Section IV-B on a trace, top down.
+//   Scale-out/in (every epoch of `epoch_windows` windows): nodes = ceil(PL / ML) per class, PL =
+//     the peak of the class's load over the epoch's windows, ML = the largest profiled load of
+//     one node at the reference configuration (tp_ref, f_ref: "TP8 at 1980 MHz"): instances per
+//     node (gpus_per_node / tp) x max_load_tps x last load-grid point.
+//   Shard-up/down (every window): among the layouts (n_inst, tp_index) of the list with
+//     n_inst x tp <= nodes x gpus_per_node, evaluated at f_ref under the window's load, the one of
+//     least energy that meets the SLO (percentiles over the window's requests); -1 if none.
+//   Scale-up/down (every tick of the window): for that layout, among the profiled frequencies,
+//     drop those that violate the SLO under the tick's load (percentiles over the tick's
+//     requests) or leave the profiled load range, then take the least power (lowest frequency
+//     on ties); if none is left the tick runs at f_ref and is counted as a violation.
+//   Energy of a (window, class) = sum over its ticks in time order of (n x power) x tick_s.
+// Readings: the load predictor is exact (the epoch's true peak); at least one node per class;
+// a window whose class has no admissible layout has energy +inf and no frequencies (-1).
+// coarse_off / fine_off: offsets of the trace sorted by window*G + class and by
+// (window*n_tick + tick)*G + class; both index the same requests (in_c/out_c, in_f/out_f).
+int dynoracle_hierarchy(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f, const double* fg,
+                        int32_t n_rho, const double* rg, const double* PF, const double* TB,
+                        const double* PW, const double* ML,
+                        int64_t n_req, int32_t n_window, int32_t n_tick, double tick_s,
+                        const int32_t* in_c, const int32_t* out_c, const int64_t* coarse_off,
+                        const int32_t* in_f, const int32_t* out_f, const int64_t* fine_off,
+                        int32_t epoch_windows, int32_t tp_ref, int32_t f_ref, int32_t gpus_per_node,
+                        int32_t n_layout, const int32_t* lay_n, const int32_t* lay_tp,
+                        const double* slo_ttft, const double* slo_tbt, int32_t pct_num, int32_t pct_den,
+                        int32_t* nodes, int32_t* layout_sel, int32_t* f_sel, double* energy_j,
+                        int32_t* violations) {
+  if (!tp || !fg || !rg || !PF || !TB || !PW || !ML || !coarse_off || !fine_off || !lay_n || !lay_tp ||
+      !slo_ttft || !slo_tbt || !nodes || !layout_sel || !f_sel || !energy_j || !violations)
+    return ORC_E_NULL;
+  if (n_req > 0 && (!in_c || !out_c || !in_f || !out_f)) return ORC_E_NULL;
+  if (G < 1 || n_tp < 1 || n_f < 1 || n_rho < 2 || n_window < 1 || n_tick < 1 || epoch_windows < 1 ||
+      n_layout < 1 || gpus_per_node < 1)
+    return ORC_E_SHAPE;
+  if (tp_ref < 0 || tp_ref >= n_tp || f_ref < 0 || f_ref >= n_f || !(tick_s > 0.0)) return ORC_E_RANGE;
+  for (int l = 0; l < n_layout; ++l)
+    if (lay_n[l] < 1 || lay_tp[l] < 0 || lay_tp[l] >= n_tp) return ORC_E_RANGE;
+  const double INF = std::numeric_limits<double>::infinity();
+  const double window_s = (double)n_tick * tick_s;
+  const int n_epoch = (n_window + epoch_windows - 1) / epoch_windows;
+  auto tab = [&](const double* X, int g, int ti, int f, int j) -> double {
+    return X[(((int64_t)g * n_tp + ti) * n_f + f) * n_rho + j];
+  };
+  // profile at (class, tp, f) for a per-instance load fraction: returns overload
+  auto look = [&](int g, int ti, int f, double load, double n, double* pf, double* tb, double* pw) -> bool {
+    const double ml = ML[((int64_t)g * n_tp + ti) * n_f + f];
+    const double rho = load / (n * ml);
+    const bool ov = rho > rg[n_rho - 1];
+    const double rc = ov ? rg[n_rho - 1] : rho;
+    const int j = bracket(rg, n_rho, rc);
+    const double t = (rc - rg[j]) / (rg[j + 1] - rg[j]);
+    *pf = (1.0 - t) * tab(PF, g, ti, f, j) + t * tab(PF, g, ti, f, j + 1);
+    *tb = (1.0 - t) * tab(TB, g, ti, f, j) + t * tab(TB, g, ti, f, j + 1);
+    *pw = (1.0 - t) * tab(PW, g, ti, f, j) + t * tab(PW, g, ti, f, j + 1);
+    return ov;
+  };
+  // nearest-rank percentile of in_r * pf over a run of requests (0 for an empty run)
+  std::vector<double> lat;
+  auto p_ttft = [&](const int32_t* in, int64_t beg, int64_t end, double pf) -> double {
+    const int64_t m = end - beg;
+    if (m <= 0) return 0.0;
+    const int64_t rank = ((int64_t)pct_num * m + pct_den - 1) / pct_den;
+    lat.resize((size_t)m);
+    for (int64_t r = 0; r < m; ++r) lat[(size_t)r] = (double)in[beg + r] * pf;
+    std::nth_element(lat.begin(), lat.begin() + (rank - 1), lat.end());
+    return lat[(size_t)(rank - 1)];
+  };
+  auto load_of = [&](const int32_t* in, const int32_t* out, int64_t beg, int64_t end, double secs) -> double {
+    int64_t tok = 0;
+    for (int64_t r = beg; r < end; ++r) tok += (int64_t)in[r] + out[r];
+    return (double)tok / secs;
+  };
+
+  for (int e = 0; e < n_epoch; ++e)
+    for (int g = 0; g < G; ++g) {
+      double peak = 0.0;
+      for (int w = e * epoch_windows; w < std::min(n_window, (e + 1) * epoch_windows); ++w) {
+        const int64_t c = (int64_t)w * G + g;
+        const double L = load_of(in_c, out_c, coarse_off[c], coarse_off[c + 1], window_s);
+        if (L > peak) peak = L;
+      }
+      const int inst = std::max(1, gpus_per_node / tp[tp_ref]);
+      const double ml_node = ((double)inst * ML[((int64_t)g * n_tp + tp_ref) * n_f + f_ref]) * rg[n_rho - 1];
+      const double q = std::ceil(peak / ml_node);
+      nodes[(int64_t)e * G + g] = q < 1.0 ? 1 : (q > 2147483647.0 ? 2147483647 : (int32_t)q);
+    }
+
+  for (int w = 0; w < n_window; ++w)
+    for (int g = 0; g < G; ++g) {
+      const int64_t c = (int64_t)w * G + g;
+      const int64_t beg = coarse_off[c], end = coarse_off[c + 1];
+      const int64_t m = end - beg;
+      const double L = load_of(in_c, out_c, beg, end, window_s);
+      const int64_t budget = (int64_t)nodes[(int64_t)(w / epoch_windows) * G + g] * gpus_per_node;
+      int best = -1;
+      double best_e = INF;
+      for (int l = 0; l < n_layout; ++l) {
+        if ((int64_t)lay_n[l] * tp[lay_tp[l]] > budget) continue;
+        double pf, tb, pw;
+        const bool ov = look(g, lay_tp[l], f_ref, L, (double)lay_n[l], &pf, &tb, &pw);
+        const double tt = p_ttft(in_c, beg, end, pf);
+        const double bt = m > 0 ? tb : 0.0;
+        if (ov || tt > slo_ttft[g] || bt > slo_tbt[g]) continue;
+        const double E = ((double)lay_n[l] * pw) * window_s;
+        if (best < 0 || E < best_e) { best = l; best_e = E; }
+      }
+      layout_sel[c] = best;
+      double E = 0.0;
+      int32_t viol = 0;
+      for (int q = 0; q < n_tick; ++q) {
+        const int64_t f = ((int64_t)w * n_tick + q) * G + g;
+        if (best < 0) { f_sel[f] = -1; continue; }
+        const int64_t fb = fine_off[f], fe = fine_off[f + 1];
+        const double Lt = load_of(in_f, out_f, fb, fe, tick_s);
+        int bf = -1;
+        double bp = INF;
+        for (int fi = 0; fi < n_f; ++fi) {
+          double pf, tb, pw;
+          const bool ov = look(g, lay_tp[best], fi, Lt, (double)lay_n[best], &pf, &tb, &pw);
+          const double tt = p_ttft(in_f, fb, fe, pf);
+          const double bt = fe > fb ? tb : 0.0;
+          if (ov || tt > slo_ttft[g] || bt > slo_tbt[g]) continue;
+          if (bf < 0 || pw < bp) { bf = fi; bp = pw; }
+        }
+        if (bf < 0) {                       // nothing admissible: highest-performance frequency, counted
+          double pf, tb;
+          look(g, lay_tp[best], f_ref, Lt, (double)lay_n[best], &pf, &tb, &bp);
+          bf = f_ref;
+          ++viol;
+        }
+        f_sel[f] = bf;
+        E += ((double)lay_n[best] * bp) * tick_s;
+      }
+      energy_j[c] = best < 0 ? INF : E;
+      violations[c] = viol;
+    }
+  return ORC_OK;
+}
+
 // Objective summed over the pools of a window (Eq. 1 sums over instance types; here one
 // pool per class), classes added in index order; cells without a feasible configuration
 // are counted, not added.

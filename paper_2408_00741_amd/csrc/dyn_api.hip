@@ -623,7 +623,6 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   ta.rec = (const TickRec*)(base + w.fine.rec); ta.top = (const int32_t*)(base + w.top);
   ta.merge_count = (uint32_t*)(base + w.merge_count); ta.merge_list = (uint32_t*)(base + w.merge_list);
   ta.tstart = p->d_tstart; ta.thr = p->d_thr; ta.single_point = p->single_point; ta.any_two_rows = p->any_two_rows;
-  ta.pct_num = o->pct_num; ta.pct_den = o->pct_den;
   if (!hip_ok(dyn_launch_tick_space(ta, s), "tick space launch")) return DYN_E_DEVICE;
 
   FinishArgs f;
@@ -742,7 +741,7 @@ int dyn_eval_select_mixed(dyn_profile* p, const dyn_trace_view* t, const dyn_mix
   ta.rec = (const CellRec*)(base + w.cell.rec); ta.n_window = t->n_window; ta.window_s = t->window_s;
   ta.win_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(DYN_MAX_WIN_PER_BLOCK, (cells * p->n_tp + 4095) / 4096));
   ta.n_share = m->n_share; ta.r_share = 1.0 / (double)m->n_share;
-  ta.types = mp.types; ta.n_group = 0;
+  ta.types = mp.types;
   ta.type_energy = (double*)(base + w.type_energy); ta.type_f = (int8_t*)(base + w.type_f);
   if (!hip_ok(dyn_launch_mixed_types(ta, p->single_point, s), "mixed types launch")) return DYN_E_DEVICE;
 

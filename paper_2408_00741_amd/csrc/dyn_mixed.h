@@ -21,7 +21,6 @@ struct MixedTypeArgs {            // per-type least energies over the admissible
   const CellRec* rec; int32_t n_window; int32_t win_per_block; double window_s;
   int32_t n_share; double r_share;        // r_share = RN(1 / n_share)
   MixedTypes types;
-  int32_t n_group;                        // groups of 16 entries over all types
   double* type_energy;                    // [cells][n_entry]
   int8_t* type_f;                         // [cells][n_entry]
 };

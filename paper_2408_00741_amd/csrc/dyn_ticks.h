@@ -37,7 +37,6 @@ struct TickArgs {
   double window_s;         // (double) n_tick * tick_s
   const TickRec* rec;      // [cells][n_tick]
   const int32_t* top;      // [cells][DYN_TICK_TOP][n_tick]
-  int32_t pct_num, pct_den;
   const int32_t* tstart; const double* thr; bool single_point;   // threshold form of the bucket index
   bool any_two_rows;
   uint32_t* merge_count;   // number of cells on merge_list

@@ -208,3 +208,74 @@ def np_mixed(profile, st, n_window, window_s, n_share, n_max, slos, pct=(99, 100
             n_opt[c] = len(keys)
             pick[c] = sorted(keys)
     return {"energy_j": energy, "assignments": pick, "n_optimal": n_opt}
+
+
+def np_hierarchy(profile, tr, edges, n_window, n_tick, tick_s, epoch_windows, tp_ref, f_ref, gpus_per_node, lay_n, lay_tp,
+                 slos, pct=(99, 100)):
+    """Scale-out / shard / frequency controllers from the raw trace, NumPy arithmetic."""
+    tp = profile["tp"]; fg = profile["f_mhz"]; rg = profile["rho"]
+    PF, TB, PW, ML = (profile[k] for k in ("prefill_ms_per_tok", "tbt_ms", "power_w", "max_load_tps"))
+    G = PF.shape[0]
+    W = n_tick * tick_s
+    coarse = np_ingest(tr, edges, n_window, W)
+    fine = np_ingest(tr, edges, n_window * n_tick, tick_s)
+
+    def run(st, c):
+        o = st["cell_off"]
+        return st["in_tok"][o[c]:o[c + 1]].astype(np.int64), st["out_tok"][o[c]:o[c + 1]].astype(np.int64)
+
+    def pct_of(v):
+        if v.size == 0:
+            return 0.0
+        return float(np.sort(v)[int(math.ceil(Fraction(pct[0] * v.size, pct[1]))) - 1])
+
+    def admissible(g, ti, f, n, x, y, secs):
+        load = float(x.sum() + y.sum()) / secs
+        rho = load / (n * ML[g, ti, f])
+        r = min(rho, rg[-1])
+        pf, tb, pw = (float(np.interp(r, rg, X[g, ti, f])) for X in (PF, TB, PW))
+        ok = rho <= rg[-1] and pct_of(x * pf) <= slos["slo_ttft_ms"][g] and (tb if x.size else 0.0) <= slos["slo_tbt_ms"][g]
+        return ok, pw
+
+    n_epoch = -(-n_window // epoch_windows)
+    nodes = np.zeros((n_epoch, G), np.int32)
+    for e in range(n_epoch):
+        for g in range(G):
+            peak = 0.0
+            for w in range(e * epoch_windows, min(n_window, (e + 1) * epoch_windows)):
+                x, y = run(coarse, w * G + g)
+                peak = max(peak, float(x.sum() + y.sum()) / W)
+            cap = max(1, gpus_per_node // int(tp[tp_ref])) * ML[g, tp_ref, f_ref] * rg[-1]
+            nodes[e, g] = max(1, math.ceil(peak / cap))
+    lay = np.full(n_window * G, -1, np.int32)
+    fsel = np.full((n_window * n_tick, G), -1, np.int32)
+    energy = np.full(n_window * G, np.inf)
+    viol = np.zeros(n_window * G, np.int32)
+    for w in range(n_window):
+        for g in range(G):
+            c = w * G + g
+            x, y = run(coarse, c)
+            best, be = -1, np.inf
+            for l in range(len(lay_n)):
+                if lay_n[l] * int(tp[lay_tp[l]]) > nodes[w // epoch_windows, g] * gpus_per_node:
+                    continue
+                ok, pw = admissible(g, lay_tp[l], f_ref, lay_n[l], x, y, W)
+                if ok and lay_n[l] * pw * W < be:
+                    best, be = l, lay_n[l] * pw * W
+            lay[c] = best
+            if best < 0:
+                continue
+            e = 0.0
+            for q in range(n_tick):
+                xf, yf = run(fine, (w * n_tick + q) * G + g)
+                cand = [(pw, f) for f in range(fg.size) for ok, pw in [admissible(g, lay_tp[best], f, lay_n[best], xf, yf, tick_s)] if ok]
+                if cand:
+                    pw, f = min(cand)
+                else:
+                    _, pw = admissible(g, lay_tp[best], f_ref, lay_n[best], xf, yf, tick_s)
+                    f = f_ref
+                    viol[c] += 1
+                fsel[w * n_tick + q, g] = f
+                e += lay_n[best] * pw * tick_s
+            energy[c] = e
+    return {"nodes": nodes, "layout_sel": lay, "f_sel": fsel, "energy_j": energy, "violations": viol}

@@ -360,6 +360,30 @@ def test_table_rows_beyond_lds_fall_back_to_global_reads(dyn):
     assert rep["bit_exact"] and rep["sel_mismatch"] == 0
 
 
+def test_largest_candidate_list(dyn):
+    """65536 candidates, the capacity of a profile handle's candidate table (one more is refused)."""
+    rng = np.random.default_rng(41)
+    G, n_tp, n_f, n_rho, K = 2, 3, 6, 12, 65536
+    fg = np.linspace(600, 2000, n_f); rg = np.concatenate([[0.0], np.sort(rng.uniform(0.05, 0.95, n_rho - 1))])
+    shape = (G, n_tp, n_f, n_rho)
+    prof = _profile([2, 4, 8], fg, rg, rng.uniform(0.05, 0.3, shape), np.sort(rng.uniform(10, 150, shape), axis=-1),
+                    np.sort(rng.uniform(100, 3000, shape), axis=-1), rng.uniform(20, 400, shape[:3]))
+    f = np.where(rng.random(K) < 0.7, rng.choice(fg, K), rng.uniform(fg[0], fg[-1], K))
+    cfg = {"n_inst": rng.integers(1, 200, K).astype(np.int32), "tp_index": rng.integers(0, n_tp, K).astype(np.int32),
+           "f_mhz": f}
+    sizes = np.asarray([130, 0, 77, 1])
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    x = rng.integers(1, 600, off[-1]); y = rng.integers(1, 300, off[-1])
+    w, st, g = _single(dyn, prof, cfg, x, y, np.asarray([80.0, 50.0]), np.asarray([90.0, 70.0]), 30.0, lam=0.02, n_window=2,
+                       off=off, budget=np.asarray([0, 400], np.int32))
+    rep = assert_parity(w, g, ora_eval(w, st, np.asarray([0, 400], np.int32)))
+    assert rep["bit_exact"] and rep["sel_mismatch"] == 0
+    cfg1 = {k: np.concatenate([v, v[:1]]) for k, v in cfg.items()}
+    with pytest.raises(dyn.DynError) as e:
+        _single(dyn, prof, cfg1, x, y, np.asarray([80.0, 50.0]), np.asarray([90.0, 70.0]), 30.0, n_window=2, off=off)
+    assert e.value.status == -2
+
+
 def test_device_side_checks_raise_status_not_faults(dyn):
     prof, cfg = _worked()
     x = np.arange(1, 11); y = np.ones(10)

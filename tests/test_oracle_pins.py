@@ -781,6 +781,75 @@ def test_account_against_numpy(small_hour):
                                             a["carbon_g"].sum(), np.ceil(used / 8).sum()], rtol=1e-12)
 
 
+# ------------------------------------------------------------ hierarchy of controllers
+def _hier_case(seed, n_tick=3, n_f=3, R=500, NW=5):
+    rng = np.random.default_rng(1700 + seed)
+    n_tp, n_rho, G = 3, 4, 2
+    fg = np.sort(rng.uniform(600, 2000, n_f)); rg = np.concatenate([[0.0], np.sort(rng.uniform(0.1, 0.95, n_rho - 1))])
+    shape = (G, n_tp, n_f, n_rho)
+    prof = _profile([2, 4, 8], fg, rg, rng.uniform(0.02, 0.1, shape), np.sort(rng.uniform(10, 150, shape), axis=-1),
+                    np.sort(rng.uniform(100, 3000, shape), axis=-1), rng.uniform(300, 1500, shape[:3]))
+    tick = 5.0
+    tr = {"t_s": rng.uniform(0, NW * n_tick * tick, R), "in_tok": rng.integers(1, 500, R).astype(np.int32),
+          "out_tok": rng.integers(1, 300, R).astype(np.int32), "model": np.zeros(R, np.int32)}
+    edges = {"in_edge": np.asarray([[200]], np.int32), "out_edge": np.zeros((1, 0), np.int32)}
+    slo = {"slo_ttft_ms": rng.uniform(25, 70, G), "slo_tbt_ms": rng.uniform(80, 150, G)}
+    lay_n = rng.integers(1, 6, 9).astype(np.int32); lay_tp = rng.integers(0, n_tp, 9).astype(np.int32)
+    return prof, tr, edges, slo, lay_n, lay_tp, NW, n_tick, tick
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_hierarchy_against_numpy(seed):
+    prof, tr, edges, slo, lay_n, lay_tp, NW, T, tick = _hier_case(seed)
+    coarse = oracle.ingest(tr, edges, NW, T * tick); fine = oracle.ingest(tr, edges, NW * T, tick)
+    a = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 2, 2, prof["f_mhz"].size - 1, 8, lay_n, lay_tp, slo)
+    b = npcheck.np_hierarchy(prof, tr, edges, NW, T, tick, 2, 2, prof["f_mhz"].size - 1, 8, lay_n, lay_tp, slo)
+    for k in ("nodes", "layout_sel", "f_sel", "violations"):
+        np.testing.assert_array_equal(a[k], b[k], err_msg=k)
+    fin = np.isfinite(b["energy_j"])
+    assert (np.isfinite(a["energy_j"]) == fin).all() and fin.any()
+    np.testing.assert_allclose(a["energy_j"][fin], b["energy_j"][fin], rtol=1e-12)
+
+
+def test_hierarchy_node_count_is_ceil_of_peak_over_node_capacity():
+    """Section IV-B "Scale-out/in": nodes = ceil(PL / ML), on a trace whose load is known in closed form."""
+    prof, _, edges, slo, lay_n, lay_tp, _, _, _ = _hier_case(0)
+    prof = dict(prof)
+    prof["max_load_tps"] = np.full_like(prof["max_load_tps"], 125.0)
+    NW, T, tick = 6, 2, 10.0                               # 20-second windows, epochs of 3 windows
+    # class 0 (input < 200): window w holds 10*(w+1) requests of 100+100 tokens -> load 100*(w+1) tokens/s
+    ts, ins = [], []
+    for w in range(NW):
+        ts += [w * 20.0 + 0.5] * (10 * (w + 1)); ins += [100] * (10 * (w + 1))
+    tr = {"t_s": np.asarray(ts), "in_tok": np.asarray(ins, np.int32), "out_tok": np.full(len(ts), 100, np.int32),
+          "model": np.zeros(len(ts), np.int32)}
+    coarse = oracle.ingest(tr, edges, NW, T * tick); fine = oracle.ingest(tr, edges, NW * T, tick)
+    r = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 3, 2, 0, 8, lay_n, lay_tp, slo)
+    cap = 1 * 125.0 * prof["rho"][-1]                        # one TP8 instance per 8-GPU node
+    assert r["nodes"][:, 0].tolist() == [int(np.ceil(300.0 / cap)), int(np.ceil(600.0 / cap))]
+    assert r["nodes"][:, 1].tolist() == [1, 1]               # an idle class keeps one node
+    r2 = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 3, 0, 0, 8, lay_n, lay_tp, slo)    # reference TP2: four instances per node
+    assert r2["nodes"][:, 0].tolist() == [int(np.ceil(300.0 / (4 * cap))), int(np.ceil(600.0 / (4 * cap)))]
+
+
+def test_hierarchy_with_one_tick_and_one_frequency_is_the_window_level_selection(small_hour):
+    """Nothing left for the lower controllers to decide and a budget that never binds: the shard level is the
+    per-window selection over the layouts."""
+    w, st, _ = small_hour
+    prof = {k: (v[:, :, :1] if k in ("prefill_ms_per_tok", "tbt_ms", "power_w", "max_load_tps") else v) for k, v in w["profile"].items()}
+    prof["f_mhz"] = w["profile"]["f_mhz"][:1]
+    T = prof["tp"].size
+    lay = [(n, ti) for ti in range(T) for n in range(1, 9)]
+    lay_n = np.asarray([l[0] for l in lay], np.int32); lay_tp = np.asarray([l[1] for l in lay], np.int32)
+    cfg = _configs([(n, ti, float(prof["f_mhz"][0])) for n, ti in lay])
+    NW, W = w["n_window"], w["window_s"]
+    h = oracle.hierarchy(prof, st, st, NW, 1, W, 2, T - 1, 0, 10 ** 6, lay_n, lay_tp, w["slos"], w["pct"])
+    e = oracle.evaluate(prof, st, NW, W, cfg, w["slos"], w["pct"])
+    np.testing.assert_array_equal(h["layout_sel"], e["sel"])
+    np.testing.assert_array_equal(h["energy_j"], e["sel_energy_j"])
+    assert (h["violations"] == 0).all() and (h["f_sel"].reshape(-1)[e["sel"] >= 0] == 0).all()
+
+
 # ----------------------------------------------------------- planted mistakes are caught
 def test_pins_catch_planted_mistakes():
     """Sanity of the pins themselves: perturbing the inputs the way a typical slip would
