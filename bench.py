@@ -48,7 +48,7 @@ def recorded_traffic(workload_index):
     return None
 
 
-def cpu_baseline(w, n_sample_windows, ticks=0, mixed=None, path=None):
+def cpu_baseline(w, n_sample_windows, ticks=0, mixed=None, path=None, hier=None):
     """The CPU oracle, as it stands, on the first windows of the same workload (one thread)."""
     import numpy as np
     import oracle
@@ -56,7 +56,14 @@ def cpu_baseline(w, n_sample_windows, ticks=0, mixed=None, path=None):
     hi = int(np.searchsorted(tr["t_s"], n_sample_windows * w["window_s"]))
     sub = {k: v[:hi] for k, v in tr.items()}
     k = w["configs"]["n_inst"].size
-    if mixed:
+    if hier:
+        T, epoch, tp_ref, f_ref, gpn, lay_n, lay_tp, k = hier
+        st = oracle.ingest(sub, w["edges"], n_sample_windows, w["window_s"])
+        fine = oracle.ingest(sub, w["edges"], n_sample_windows * T, w["window_s"] / T)
+        t0 = time.perf_counter()
+        oracle.hierarchy(w["profile"], st, fine, n_sample_windows, T, w["window_s"] / T, epoch, tp_ref, f_ref, gpn, lay_n, lay_tp,
+                         w["slos"], w["pct"])
+    elif mixed:
         n_share, n_max, budget, k = mixed
         st = oracle.ingest(sub, w["edges"], n_sample_windows, w["window_s"])
         t0 = time.perf_counter()
@@ -101,6 +108,11 @@ def main():
                     help="dyn_eval_space + dyn_select_path: selection with transition overheads between consecutive "
                          "windows (layout = (TP, instances); overhead = 1 %% of the median selected energy per GPU "
                          "of difference between the layouts)")
+    ap.add_argument("--hierarchy", type=int, default=0,
+                    help="the three controllers top down (dyn_hierarchy) with this many ticks per window: epochs of "
+                         "--epoch-windows windows, 8-GPU nodes, layouts = the (instances, TP) pairs of the workload's "
+                         "configurations, reference = the largest TP at the highest frequency")
+    ap.add_argument("--epoch-windows", type=int, default=6)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events (roofline.achieved is then null)")
@@ -143,7 +155,7 @@ def main():
 
     # ---- one-time set-up, timed separately: upload, ingestion, profile load
     t_s, x, y, mdl = dev(tr["t_s"]), dev(tr["in_tok"]), dev(tr["out_tok"]), dev(tr["model"])
-    T = max(args.ticks, 1)                  # the trace is sorted by tick when ticks are asked for
+    T = max(args.ticks, args.hierarchy, 1)  # the trace is sorted by tick when ticks are asked for
     NWF, len_s = NW * T, w["window_s"] / T
     ws_ing = torch.empty(dyn.dyn_trace_ingest_workspace(R, NWF, G), dtype=torch.uint8, device="cuda")
     dyn.dyn_trace_ingest(t_s, x, y, mdl, w["edges"], NWF, len_s, workspace=ws_ing)   # warm-up
@@ -155,6 +167,8 @@ def main():
     torch.cuda.synchronize()
     ingest_ms = e0.elapsed_time(e1)
     assert dyn.dyn_workspace_status(ws_ing) == 0
+    if args.hierarchy:                      # the controllers also need the window-level order
+        coarse = dyn.dyn_trace_ingest(t_s, x, y, mdl, w["edges"], NW, w["window_s"])[:3]
     del t_s, x, y, mdl, ws_ing
     t0 = time.perf_counter()
     prof = dyn.dyn_profile_load(w["profile"])
@@ -173,7 +187,22 @@ def main():
     ws = torch.empty(dyn.dyn_eval_ticks_workspace(NW, T, G, K) if args.ticks else dyn.dyn_eval_space_workspace(NW, G, K),
                      dtype=torch.uint8, device="cuda")
 
-    if args.path:
+    if args.hierarchy:
+        assert not args.ticks and not args.mixed and not args.path, "--hierarchy is a mode of its own"
+        cfgs = w["configs"]
+        uniq = np.unique(cfgs["tp_index"].astype(np.int64) * 100000 + cfgs["n_inst"])
+        lay_n, lay_tp = (uniq % 100000).astype(np.int32), (uniq // 100000).astype(np.int32)
+        n_f = int(w["profile"]["f_mhz"].size)
+        hier_args = (T, args.epoch_windows, int(w["profile"]["tp"].size) - 1, n_f - 1, 8, lay_n, lay_tp)
+        K = int(lay_n.size) + n_f           # candidates looked at per request: layouts per window + frequencies per tick
+        ws = torch.empty(dyn.dyn_hierarchy_workspace(NW, T, G, lay_n.size), dtype=torch.uint8, device="cuda")
+        hout, _ = dyn.dyn_hierarchy(prof, coarse, (ins, outs, off), NW, T, len_s, *hier_args[1:], w["slos"], w["pct"], workspace=ws)
+        hout["window_energy_j"], hout["window_infeasible"] = sel["window_energy_j"], sel["window_infeasible"]
+
+        def step():
+            dyn.dyn_hierarchy(prof, coarse, (ins, outs, off), NW, T, len_s, *hier_args[1:], w["slos"], w["pct"], out=hout,
+                              workspace=ws)
+    elif args.path:
         assert not args.ticks and not args.mixed, "--path, --mixed and --ticks are separate modes"
         cfgs = w["configs"]
         key = cfgs["tp_index"].astype(np.int64) * 100000 + cfgs["n_inst"]
@@ -239,7 +268,7 @@ def main():
     # on the stream the kernels are launched on).  The event records themselves cost about 20 us per
     # step on this machine, which is why they are kept out of the throughput region above.
     ktime = {"cell": 0.0, "space": 0.0, "select": 0.0, "totals": 0.0, "tick_top": 0.0, "tick_space": 0.0, "tick_merge": 0.0,
-             "mixed_types": 0.0, "mixed_combine": 0.0, "path": 0.0}
+             "mixed_types": 0.0, "mixed_combine": 0.0, "path": 0.0, "hierarchy": 0.0}
     ms_per_step_events = None
     if not args.no_kernel_events:
         dyn.dyn_timing_enable(True, args.steps)
@@ -253,7 +282,7 @@ def main():
                           ("totals", dyn.DYN_K_TOTALS), ("tick_top", dyn.DYN_K_TICK_TOP),
                           ("tick_space", dyn.DYN_K_TICK_SPACE), ("tick_merge", dyn.DYN_K_TICK_MERGE),
                           ("mixed_types", dyn.DYN_K_MIXED_TYPES), ("mixed_combine", dyn.DYN_K_MIXED_COMBINE),
-                          ("path", dyn.DYN_K_PATH)):
+                          ("path", dyn.DYN_K_PATH), ("hierarchy", dyn.DYN_K_HIER)):
             ms, n = dyn.dyn_timing_read(kid)
             ktime[name] = ms / max(n, 1)
         dyn.dyn_timing_enable(False)
@@ -268,7 +297,17 @@ def main():
                   + 20.0 * cells + 12.0 * NW + (8.0 * cells * (T - 1) if args.ticks else 0.0))
     path_gbps = path_bytes / (ms_per_step * 1e-3) / 1e9
 
-    if args.mixed:
+    if args.hierarchy:
+        # the two aggregations (by window and by tick) dominate: each reads the 8-byte request records once
+        cell_ms = ktime["cell"]            # average over the two launches of a step
+        gbps = 8.0 * R / (cell_ms * 1e-3) / 1e9 if cell_ms > 0 else None
+        roofline = {"bound": "hbm", "kernel": "cell_aggregate_kernel (twice per step)", "achieved": gbps, "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS if gbps else None, "traffic": None,
+                    "algorithmic_bytes_per_launch": 8.0 * R, "avg_launch_ms": cell_ms}
+        n_ep = -(-NW // args.epoch_windows)
+        path_bytes = 2 * 8.0 * R + 8.0 * (cells + 1) * (T + 1) + 4.0 * cells * T + 16.0 * cells + 4.0 * n_ep * G + 12.0 * NW
+        path_gbps = path_bytes / (ms_per_step * 1e-3) / 1e9
+    elif args.mixed:
         # instruction-bound: the method's arithmetic is 18 fp64 operations per (cell, type, instances, shares,
         # frequency) look-up (share of the load, table look-up, energy, TTFT multiply)
         space_ms = ktime["mixed_types"]
@@ -295,7 +334,9 @@ def main():
                     "traffic": None if (args.unfused or args.path) else recorded_traffic(args.config),
                     "algorithmic_bytes_per_launch": space_bytes, "avg_launch_ms": space_ms}
 
-    if args.mixed:
+    if args.hierarchy:
+        sel_h = hout["layout_sel"].cpu().numpy()
+    elif args.mixed:
         en = msel["energy_j"].cpu().numpy()
         sel_h = np.where(np.isfinite(en), 0, -1)
     else:
@@ -310,8 +351,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {spec.name}: {R} requests, {NW} windows x {G} classes = "
                                f"{cells} cells, {K} configurations", "requests": R, "cells": cells, "configs": K,
-                   "ticks_per_window": args.ticks, "mixed_shares": args.mixed,
-                   "entry_points": "dyn_eval_space+dyn_select_path" if args.path else "dyn_eval_select_mixed" if args.mixed else "dyn_eval_select_ticks" if args.ticks else
+                   "ticks_per_window": args.ticks or args.hierarchy, "mixed_shares": args.mixed,
+                   "entry_points": "dyn_hierarchy" if args.hierarchy else "dyn_eval_space+dyn_select_path" if args.path else "dyn_eval_select_mixed" if args.mixed else "dyn_eval_select_ticks" if args.ticks else
                                    "dyn_eval_space+dyn_select_config" if args.unfused else "dyn_eval_select"},
         "roofline": roofline,
         "kernel_ms": ktime, "ms_per_step_with_kernel_events": ms_per_step_events,
@@ -323,7 +364,10 @@ def main():
     if not args.no_cpu_baseline:
         nwin = args.cpu_windows or max(1, min(NW, int(NW * (5.0e9 if args.mixed else 1.5e9 if args.path else 1.0e10) / (R * K))))
         mixed = (args.mixed, n_max, np.full(G, args.mixed_gpus, np.int32), K) if args.mixed else None
-        out["cpu_baseline"] = cpu_baseline(w, nwin, args.ticks, mixed, (lay, trans) if args.path else None)
+        if args.hierarchy:
+            nwin = args.cpu_windows or NW
+        out["cpu_baseline"] = cpu_baseline(w, nwin, args.ticks, mixed, (lay, trans) if args.path else None,
+                                           hier_args + (K,) if args.hierarchy else None)
         out["cpu_baseline"]["host_cores"] = os.cpu_count()
     prof.free()
     print(json.dumps(out))

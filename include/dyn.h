@@ -351,6 +351,50 @@ int dyn_account(dyn_profile* profile, const int32_t* sel, const double* window_e
                 const dyn_rates* rates, const dyn_accounting* out, void* workspace,
                 size_t workspace_bytes, void* hip_stream);
 
+/* --------------------------------------------------------- the hierarchy of controllers --
+ * Section IV-B "Hierarchical Control": instead of one global search, three controllers set
+ * one knob each, top down, each assuming the ones below run at the highest performance.
+ *   Scale-out/in, every epoch of `epoch_windows` windows: nodes = ceil(PL / ML) per class,
+ *     PL = the peak of the class's load over the epoch's windows (the load predictor is taken
+ *     to be exact), ML = the largest profiled load of one node at the reference
+ *     configuration (tp_ref_index, f_ref_index; the paper's TP8 at 1980 MHz):
+ *     (gpus_per_node / tp) instances * max_load_tps * last load-grid point; at least 1 node.
+ *   Shard-up/down, every window: among the layouts (lay_n[l] instances of TP lay_tp_index[l])
+ *     with n * tp <= nodes * gpus_per_node, evaluated at f_ref under the window's load with
+ *     the percentiles over the window's requests, the one of least energy that meets the
+ *     SLO (lowest l on ties); -1 and energy +inf if none.
+ *   Scale-up/down, every tick: for that layout, among the profiled frequencies, drop those
+ *     that violate the SLO under the tick's load (percentiles over the tick's requests) or
+ *     leave the profiled load range, then take the least power (lowest frequency on ties);
+ *     if none is left the tick runs at f_ref and counts as a violation.
+ *   Energy of a (window, class) = sum over its ticks in time order of (n * power) * tick_s.
+ * `coarse` is the trace sorted by window (n_window windows of n_tick * tick_s seconds), `fine`
+ * the same requests sorted by tick (n_window * n_tick windows of tick_s seconds), both as
+ * dyn_trace_ingest returns them.  lay_n / lay_tp_index HOST [n_layout].  Outputs DEVICE.
+ * objective->gpu_budget and idle_cost_weight are not used.                                */
+typedef struct {
+  int32_t epoch_windows;
+  int32_t tp_ref_index, f_ref_index;
+  int32_t gpus_per_node;
+  int32_t n_layout;
+  const int32_t* lay_n;
+  const int32_t* lay_tp_index;
+} dyn_controllers;
+typedef struct {
+  int32_t* nodes;             /* [n_epoch][G], n_epoch = ceil(n_window / epoch_windows)    */
+  int32_t* layout_sel;        /* [n_window*G] index into the layout list, -1 if none       */
+  int32_t* f_sel;             /* [n_window*n_tick][G] index into the profile's f_mhz, -1   */
+  double* energy_j;           /* [n_window*G], +inf where layout_sel == -1                 */
+  int32_t* violations;        /* [n_window*G] ticks that had to run at f_ref               */
+  double* window_energy_j;    /* [n_window] */
+  int32_t* window_infeasible; /* [n_window] */
+} dyn_hierarchy_out;
+size_t dyn_hierarchy_workspace(int32_t n_window, int32_t n_tick, int32_t n_class, int32_t n_layout);
+int dyn_hierarchy(dyn_profile* profile, const dyn_trace_view* coarse, const dyn_trace_view* fine,
+                  int32_t n_tick, const dyn_controllers* controllers, const dyn_objective* objective,
+                  const dyn_hierarchy_out* out, void* workspace, size_t workspace_bytes,
+                  void* hip_stream);
+
 /* ------------------------------------------------------------- kernel timing (optional) --
  * Measurement aid, not part of the method: when enabled, the library brackets each of its
  * kernels with a pair of HIP events recorded on the stream the kernel is launched on, so
@@ -366,7 +410,8 @@ int dyn_account(dyn_profile* profile, const int32_t* sel, const double* window_e
 #define DYN_K_MIXED_TYPES 7   /* mixed pools: per-type least energies                      */
 #define DYN_K_MIXED_COMBINE 8 /* mixed pools: assignment of instances and shares          */
 #define DYN_K_PATH 9          /* selection with transition overheads                     */
-#define DYN_K_COUNT 10
+#define DYN_K_HIER 10         /* the four kernels of the controller hierarchy            */
+#define DYN_K_COUNT 11
 /* on != 0: create the event pool (up to `max_launches` launches per kernel are recorded,
  * later ones are not) and start recording; on == 0: stop and destroy the pool.         */
 int dyn_timing_enable(int on, int32_t max_launches);

@@ -22,7 +22,7 @@ __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_t
            "DYN_WS_BAD_OFFSETS", "DYN_WS_BAD_REQUEST", "DYN_WS_TICK_RANK", "dyn_eval_select_ticks",
            "dyn_eval_ticks_workspace", "DYN_K_TICK_TOP", "DYN_K_TICK_SPACE", "DYN_K_TICK_MERGE", "DYN_K_MIXED_TYPES", "DYN_K_MIXED_COMBINE",
            "MixedPlan", "dyn_mixed_workspace", "dyn_eval_select_mixed", "DYN_K_PATH", "dyn_select_path_workspace",
-           "dyn_select_path", "dyn_account_workspace", "dyn_account", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
+           "dyn_select_path", "dyn_account_workspace", "dyn_account", "dyn_hierarchy_workspace", "dyn_hierarchy", "DYN_K_HIER", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
 
 DYN_F_FEASIBLE, DYN_F_OVERLOAD, DYN_F_TTFT, DYN_F_TBT, DYN_F_BUDGET, DYN_F_EMPTY = 1, 2, 4, 8, 16, 32
 DYN_WS_BAD_OFFSETS, DYN_WS_BAD_REQUEST, DYN_WS_TICK_RANK = 1, 2, 4
@@ -102,6 +102,16 @@ class _Accounting(C.Structure):
     _fields_ = [("gpus", _vp), ("gpu_cost", _vp), ("energy_cost", _vp), ("carbon_g", _vp), ("totals", _vp)]
 
 
+class _Controllers(C.Structure):
+    _fields_ = [("epoch_windows", _i32), ("tp_ref_index", _i32), ("f_ref_index", _i32), ("gpus_per_node", _i32),
+                ("n_layout", _i32), ("lay_n", _vp), ("lay_tp_index", _vp)]
+
+
+class _HierarchyOut(C.Structure):
+    _fields_ = [("nodes", _vp), ("layout_sel", _vp), ("f_sel", _vp), ("energy_j", _vp), ("violations", _vp),
+                ("window_energy_j", _vp), ("window_infeasible", _vp)]
+
+
 _lib.dyn_last_error.restype = C.c_char_p
 _lib.dyn_profile_load.restype = C.c_int
 _lib.dyn_profile_load.argtypes = [C.POINTER(_ProfileDesc), _vp, C.POINTER(_vp)]
@@ -149,13 +159,18 @@ _lib.dyn_account_workspace.argtypes = [_i32]
 _lib.dyn_account.restype = C.c_int
 _lib.dyn_account.argtypes = [_vp, _vp, _vp, C.POINTER(_Config), _i32, _i32, _f64, C.POINTER(_Rates),
                              C.POINTER(_Accounting), _vp, _sz, _vp]
+_lib.dyn_hierarchy_workspace.restype = _sz
+_lib.dyn_hierarchy_workspace.argtypes = [_i32, _i32, _i32, _i32]
+_lib.dyn_hierarchy.restype = C.c_int
+_lib.dyn_hierarchy.argtypes = [_vp, C.POINTER(_TraceView), C.POINTER(_TraceView), _i32, C.POINTER(_Controllers),
+                               C.POINTER(_Objective), C.POINTER(_HierarchyOut), _vp, _sz, _vp]
 _lib.dyn_timing_enable.restype = C.c_int
 _lib.dyn_timing_enable.argtypes = [C.c_int, _i32]
 _lib.dyn_timing_reset.restype = C.c_int
 _lib.dyn_timing_read.restype = C.c_int
 _lib.dyn_timing_read.argtypes = [_i32, C.POINTER(C.c_double), C.POINTER(_i64)]
 (DYN_K_CELL, DYN_K_SPACE, DYN_K_SELECT, DYN_K_TOTALS, DYN_K_TICK_TOP, DYN_K_TICK_SPACE, DYN_K_TICK_MERGE,
- DYN_K_MIXED_TYPES, DYN_K_MIXED_COMBINE, DYN_K_PATH) = range(10)
+ DYN_K_MIXED_TYPES, DYN_K_MIXED_COMBINE, DYN_K_PATH, DYN_K_HIER) = range(11)
 
 
 def dyn_timing_enable(on: bool, max_launches: int = 4096):
@@ -535,6 +550,50 @@ def dyn_account(profile: Profile, sel: torch.Tensor, window_energy_j: torch.Tens
                             n_window, float(window_s), C.byref(rates), C.byref(acc), _dp(ws), ws.numel(), _stream(stream)),
            "dyn_account")
     return out, ws
+
+
+def dyn_hierarchy_workspace(n_window: int, n_tick: int, n_class: int, n_layout: int) -> int:
+    return int(_lib.dyn_hierarchy_workspace(n_window, n_tick, n_class, n_layout))
+
+
+def dyn_hierarchy(profile: Profile, coarse, fine, n_window: int, n_tick: int, tick_s: float, epoch_windows: int,
+                  tp_ref_index: int, f_ref_index: int, gpus_per_node: int, lay_n, lay_tp_index, slos, pct=(99, 100),
+                  out: Optional[Dict[str, torch.Tensor]] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """The three controllers top down.  `coarse` / `fine` are (in_tok, out_tok, cell_off) tensor triples of the trace
+    sorted by window and by tick.  Returns (dict of output tensors, workspace)."""
+    G = profile.n_class
+    cells = n_window * G
+    ci, co_, coff = coarse
+    fi, fo_, foff = fine
+    if coff.numel() != cells + 1 or foff.numel() != cells * n_tick + 1:
+        raise ValueError("cell_off sizes do not match n_window, n_tick and the classes")
+    dev = coff.device
+    ln = _host(lay_n, np.int32); lt = _host(lay_tp_index, np.int32)
+    n_epoch = -(-n_window // max(int(epoch_windows), 1))      # the library rejects epoch_windows < 1
+    out = out or {"nodes": torch.empty((n_epoch, G), dtype=torch.int32, device=dev),
+           "layout_sel": torch.empty(cells, dtype=torch.int32, device=dev),
+           "f_sel": torch.empty((n_window * n_tick, G), dtype=torch.int32, device=dev),
+           "energy_j": torch.empty(cells, dtype=torch.float64, device=dev),
+           "violations": torch.empty(cells, dtype=torch.int32, device=dev),
+           "window_energy_j": torch.empty(n_window, dtype=torch.float64, device=dev),
+           "window_infeasible": torch.empty(n_window, dtype=torch.int32, device=dev)}
+    want = {"nodes": (n_epoch * G, torch.int32), "layout_sel": (cells, torch.int32), "f_sel": (cells * n_tick, torch.int32),
+            "energy_j": (cells, torch.float64), "violations": (cells, torch.int32),
+            "window_energy_j": (n_window, torch.float64), "window_infeasible": (n_window, torch.int32)}
+    for k, (n, dt) in want.items():
+        if out[k].numel() != n or out[k].dtype != dt:
+            raise ValueError(f"out[{k!r}] must hold {n} elements of {dt}")
+    if workspace is None:
+        workspace = _workspace(dyn_hierarchy_workspace(n_window, n_tick, G, ln.size), dev)
+    obj, keep = _objective(slos, pct, None, 0.0)
+    tc = _TraceView(ci.numel(), n_window, float(tick_s) * n_tick, _dp(ci, torch.int32), _dp(co_, torch.int32), _dp(coff, torch.int64))
+    tf = _TraceView(fi.numel(), n_window * n_tick, float(tick_s), _dp(fi, torch.int32), _dp(fo_, torch.int32), _dp(foff, torch.int64))
+    ctl = _Controllers(int(epoch_windows), int(tp_ref_index), int(f_ref_index), int(gpus_per_node), int(ln.size), _hp(ln), _hp(lt))
+    ho = _HierarchyOut(*[_dp(out[k]) for k in ("nodes", "layout_sel", "f_sel", "energy_j", "violations", "window_energy_j",
+                                               "window_infeasible")])
+    _check(_lib.dyn_hierarchy(profile.handle, C.byref(tc), C.byref(tf), n_tick, C.byref(ctl), C.byref(obj), C.byref(ho),
+                              _dp(workspace), workspace.numel(), _stream(stream)), "dyn_hierarchy")
+    return out, workspace
 
 
 def dyn_cell_stats(workspace: torch.Tensor, n_window: int, n_class: int, stream=None):

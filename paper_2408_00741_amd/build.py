@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdyn.so")
-SOURCES = ["dyn_api.hip", "k_ingest.hip", "k_cell.hip", "k_space.hip", "k_select.hip", "k_ticks.hip", "k_mixed.hip", "k_path.hip", "k_account.hip"]
+SOURCES = ["dyn_api.hip", "k_ingest.hip", "k_cell.hip", "k_space.hip", "k_select.hip", "k_ticks.hip", "k_mixed.hip", "k_path.hip", "k_account.hip", "k_hier.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-result",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

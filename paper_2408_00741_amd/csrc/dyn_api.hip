@@ -15,6 +15,7 @@
 #include "dyn_mixed.h"
 #include "dyn_path.h"
 #include "dyn_account.h"
+#include "dyn_hier.h"
 
 namespace {
 
@@ -873,6 +874,92 @@ int dyn_account(dyn_profile* p, const int32_t* sel, const double* window_energy_
   a.hours = (double*)(base + 256); a.servers = (double*)(base + 256 + per);
   a.status = &((WsHeader*)base)->status;
   if (!hip_ok(dyn_launch_account(a, s), "account launch")) return DYN_E_DEVICE;
+  return DYN_OK;
+}
+
+namespace {
+struct HierWs {
+  EvalWs coarse;                 // header .. cstat of the window-level aggregation (first: its header is the workspace's)
+  size_t fine_base; EvalWs fine; // the tick-level aggregation, offsets relative to fine_base
+  size_t tp, lay_n, lay_tp, ok, tick_energy, tick_viol, total;
+};
+HierWs hier_ws_layout(int64_t cells, int32_t n_tick, int32_t n_tp, int32_t n_layout) {
+  HierWs w;
+  w.coarse = dyn_eval_ws_layout(cells, 1);
+  w.fine_base = w.coarse.part;
+  w.fine = dyn_eval_ws_layout(cells * n_tick, 1);
+  size_t off = w.fine_base + w.fine.part;
+  const size_t c = (size_t)std::max<int64_t>(cells, 1);
+  w.tp = off; off += align256((size_t)n_tp * 4);
+  w.lay_n = off; off += align256((size_t)n_layout * 4);
+  w.lay_tp = off; off += align256((size_t)n_layout * 4);
+  w.ok = off; off += align256(c * 4);
+  w.tick_energy = off; off += align256(c * n_tick * 8);
+  w.tick_viol = off; off += align256(c * n_tick);
+  w.total = off;
+  return w;
+}
+}  // namespace
+
+size_t dyn_hierarchy_workspace(int32_t n_window, int32_t n_tick, int32_t n_class, int32_t n_layout) {
+  if (n_window < 1 || n_tick < 1 || n_class < 1 || n_layout < 1) return 0;
+  return hier_ws_layout((int64_t)n_window * n_class, n_tick, 64, n_layout).total;
+}
+
+int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view* tf, int32_t n_tick, const dyn_controllers* c,
+                  const dyn_objective* o, const dyn_hierarchy_out* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!p || !tc || !tf || !c || !o || !out || !workspace) { dyn_set_error("an argument is NULL"); return DYN_E_NULL; }
+  if (!out->nodes || !out->layout_sel || !out->f_sel || !out->energy_j || !out->violations || !out->window_energy_j || !out->window_infeasible) { dyn_set_error("an output array is NULL"); return DYN_E_NULL; }
+  if (!c->lay_n || !c->lay_tp_index) { dyn_set_error("the layout list is NULL"); return DYN_E_NULL; }
+  if (n_tick < 1 || tc->n_window < 1 || tf->n_window != (int64_t)tc->n_window * n_tick || tc->n_req != tf->n_req || tc->n_req < 0 || tc->n_req >= ((int64_t)1 << 31)) {
+    dyn_set_error("the tick-level trace must hold n_window * n_tick windows of the same requests");
+    return DYN_E_SHAPE;
+  }
+  if (!tc->cell_off || !tf->cell_off || (tc->n_req > 0 && (!tc->in_tok || !tc->out_tok || !tf->in_tok || !tf->out_tok))) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
+  if (!(tf->window_s > 0.0) || !isfinite(tf->window_s)) { dyn_set_error("tick length must be finite and > 0"); return DYN_E_RANGE; }
+  if (c->epoch_windows < 1 || c->gpus_per_node < 1 || c->n_layout < 1 || p->n_tp > 64) { dyn_set_error("epoch_windows, gpus_per_node or n_layout < 1"); return DYN_E_SHAPE; }
+  if (c->tp_ref_index < 0 || c->tp_ref_index >= p->n_tp || c->f_ref_index < 0 || c->f_ref_index >= p->n_f) { dyn_set_error("reference configuration outside the profile"); return DYN_E_RANGE; }
+  for (int l = 0; l < c->n_layout; ++l)
+    if (c->lay_n[l] < 1 || c->lay_tp_index[l] < 0 || c->lay_tp_index[l] >= p->n_tp) { dyn_set_error("layout %d is not valid", l); return DYN_E_RANGE; }
+  const int64_t cells = (int64_t)tc->n_window * p->G, fine_cells = cells * n_tick;
+  if (fine_cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * n_tick * classes must stay below 2^30"); return DYN_E_SHAPE; }
+  int rc;
+  if ((rc = check_device(p)) != DYN_OK) return rc;
+  const HierWs w = hier_ws_layout(cells, n_tick, 64, c->n_layout);
+  if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) { dyn_set_error("workspace misaligned or too small (%zu < %zu)", workspace_bytes, w.total); return DYN_E_WORKSPACE; }
+  hipStream_t s = (hipStream_t)hip_stream;
+  if ((rc = prepare_objective(p, o, s)) != DYN_OK) return rc;
+  char* base = (char*)workspace;
+  char* fb = base + w.fine_base;
+  if (!hip_ok(hipMemcpyAsync(base + w.tp, p->tp.data(), (size_t)p->n_tp * 4, hipMemcpyHostToDevice, s), "copy") ||
+      !hip_ok(hipMemcpyAsync(base + w.lay_n, c->lay_n, (size_t)c->n_layout * 4, hipMemcpyHostToDevice, s), "copy") ||
+      !hip_ok(hipMemcpyAsync(base + w.lay_tp, c->lay_tp_index, (size_t)c->n_layout * 4, hipMemcpyHostToDevice, s), "copy") ||
+      !hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize"))
+    return DYN_E_DEVICE;
+  const double window_s = (double)n_tick * tf->window_s;
+  // tick level first: the window-level aggregation then (re)writes the workspace's header
+  if (!hip_ok(dyn_launch_cell_aggregate(tf->in_tok, tf->out_tok, tf->cell_off, tf->n_req, fine_cells, tf->window_s, o->pct_num, o->pct_den,
+                                        (int64_t*)(fb + w.fine.tin), (int64_t*)(fb + w.fine.tout), (int32_t*)(fb + w.fine.in_p99),
+                                        (CellRec*)(fb + w.fine.rec), (uint8_t*)(fb + w.fine.cstat), (WsHeader*)(fb + w.fine.header), s), "cell aggregate launch") ||
+      !hip_ok(dyn_launch_cell_aggregate(tc->in_tok, tc->out_tok, tc->cell_off, tc->n_req, cells, window_s, o->pct_num, o->pct_den,
+                                        (int64_t*)(base + w.coarse.tin), (int64_t*)(base + w.coarse.tout), (int32_t*)(base + w.coarse.in_p99),
+                                        (CellRec*)(base + w.coarse.rec), (uint8_t*)(base + w.coarse.cstat), (WsHeader*)(base + w.coarse.header), s), "cell aggregate launch"))
+    return DYN_E_DEVICE;
+  HierArgs a;
+  a.tab = p->d_tab; a.ml = p->d_ml; a.gridpack = p->d_gridpack; a.jstart = p->d_jstart; a.n_bucket = p->n_bucket; a.bucket_scale = p->bucket_scale;
+  a.G = p->G; a.n_tp = p->n_tp; a.n_f = p->n_f; a.n_rho = p->n_rho; a.tp = (const int32_t*)(base + w.tp);
+  a.slo_ttft = p->d_slo_ttft; a.slo_tbt = p->d_slo_tbt;
+  a.rec_c = (const CellRec*)(base + w.coarse.rec); a.rec_f = (const CellRec*)(fb + w.fine.rec);
+  a.cstat_c = (const uint8_t*)(base + w.coarse.cstat); a.cstat_f = (const uint8_t*)(fb + w.fine.cstat); a.status = &((WsHeader*)(base + w.coarse.header))->status;
+  a.n_window = tc->n_window; a.n_tick = n_tick; a.tick_s = tf->window_s; a.window_s = window_s;
+  a.epoch_windows = c->epoch_windows; a.n_epoch = (tc->n_window + c->epoch_windows - 1) / c->epoch_windows;
+  a.tp_ref = c->tp_ref_index; a.f_ref = c->f_ref_index; a.gpus_per_node = c->gpus_per_node;
+  a.n_layout = c->n_layout; a.lay_n = (const int32_t*)(base + w.lay_n); a.lay_tp = (const int32_t*)(base + w.lay_tp);
+  a.nodes = out->nodes; a.layout_sel = out->layout_sel; a.f_sel = out->f_sel; a.energy = out->energy_j; a.violations = out->violations;
+  a.ok = (int32_t*)(base + w.ok); a.tick_energy = (double*)(base + w.tick_energy); a.tick_viol = (uint8_t*)(base + w.tick_viol);
+  if (!hip_ok(dyn_launch_hierarchy(a, s), "hierarchy launch")) return DYN_E_DEVICE;
+  if (!hip_ok(dyn_launch_window_totals(a.ok, out->energy_j, tc->n_window, p->G, out->window_energy_j, out->window_infeasible, s), "window totals launch"))
+    return DYN_E_DEVICE;
   return DYN_OK;
 }
 

@@ -1,0 +1,30 @@
+// Internal declarations of the controller hierarchy (not part of the ABI).
+#ifndef DYN_HIER_H_
+#define DYN_HIER_H_
+
+#include "dyn_internal.h"
+
+struct HierArgs {
+  // profile
+  const double* tab; const double* ml; const double* gridpack; const int32_t* jstart; int32_t n_bucket; double bucket_scale;
+  int32_t G, n_tp, n_f, n_rho;
+  const int32_t* tp;            // DEVICE [n_tp] GPUs per instance
+  const double* slo_ttft; const double* slo_tbt;
+  // trace aggregates
+  const CellRec* rec_c;         // [n_window * G] window level
+  const CellRec* rec_f;         // [n_window * n_tick * G] tick level
+  const uint8_t* cstat_c;       // status bytes of the window-level aggregation
+  const uint8_t* cstat_f;       // status bytes of the tick-level aggregation
+  uint32_t* status;             // status word of the workspace header
+  int32_t n_window, n_tick; double tick_s, window_s;
+  // controllers
+  int32_t epoch_windows, n_epoch, tp_ref, f_ref, gpus_per_node;
+  int32_t n_layout; const int32_t* lay_n; const int32_t* lay_tp;   // DEVICE [n_layout]
+  // outputs and scratch
+  int32_t* nodes; int32_t* layout_sel; int32_t* f_sel; double* energy; int32_t* violations; int32_t* ok;
+  double* tick_energy;          // workspace [fine cells]
+  uint8_t* tick_viol;           // workspace [fine cells]
+};
+hipError_t dyn_launch_hierarchy(const HierArgs& a, hipStream_t s);
+
+#endif  // DYN_HIER_H_

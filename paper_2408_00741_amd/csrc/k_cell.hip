@@ -88,6 +88,50 @@ __device__ __forceinline__ void cell_sums_wide(const int32_t* __restrict__ in, c
   *tout = ((int64_t)wave_sum_i32(hi_out) << 16) + (int64_t)wave_sum_i32(lo_out);
 }
 
+// Reduction of a register-resident cell of m <= 64*R requests: v[i] = input tokens of request
+// i*64 + lane (0xFFFFFFFF beyond m); s_in / s_out / or_all / lmax = the lane's sums, OR and
+// largest input over its requests.
+template <int R>
+__device__ __forceinline__ CellOut cell_reduce(const uint32_t (&v)[R], uint32_t s_in, uint32_t s_out, uint32_t or_all,
+                                               uint32_t lmax, const int32_t* __restrict__ in,
+                                               const int32_t* __restrict__ out, int64_t beg, int m, int rank, int lane) {
+  CellOut r;
+  r.orv = wave_or_u32(or_all);
+  // at most 2048 values: if all are below 2^20 the 32-bit sums are exact (else redone below)
+  r.tin = (int64_t)(uint32_t)wave_sum_i32((int)s_in);
+  r.tout = (int64_t)(uint32_t)wave_sum_i32((int)s_out);
+  // Answer = largest a with #{v < a} < rank.  It lies in [lo, top]: top = largest element,
+  // lo = 0, or for cells of several rows the j-th largest per-lane maximum, j = m - rank + 1.
+  const uint32_t top = wave_max_u32(lmax);
+  if (rank == m) {                          // the nearest rank of a small cell is its last: the maximum
+    r.p99 = top;
+  } else {
+    uint32_t lo = 0;
+    if (R >= 4) {
+      const int j = m - rank + 1;
+      if (j <= DYN_WAVE) {
+        const int nb = 32 - __builtin_clz(top | 1u);
+        for (int b = nb - 1; b >= 0; --b) {   // largest c with #{lane maxima >= c} >= j
+          const uint32_t cand = lo | (1u << b);
+          if (__popcll(__ballot(lmax >= cand)) >= j) lo = cand;
+        }
+      }
+    }
+    uint32_t d = 0;
+    const int nb = 32 - __builtin_clz((top - lo) | 1u);
+    for (int b = nb - 1; b >= 0; --b) {
+      const uint32_t cand = lo + (d | (1u << b));
+      int below = 0;
+#pragma unroll
+      for (int i = 0; i < R; ++i) below += __popcll(__ballot(v[i] < cand));
+      if (below < rank) d |= 1u << b;
+    }
+    r.p99 = lo + d;
+  }
+  if (r.orv >= (1u << 20)) cell_sums_wide(in, out, beg, m, lane, &r.tin, &r.tout);
+  return r;
+}
+
 // Register-resident cell: m <= 64*R requests.
 template <int R>
 __device__ __forceinline__ CellOut cell_in_registers(const int32_t* __restrict__ in,
@@ -107,37 +151,22 @@ __device__ __forceinline__ CellOut cell_in_registers(const int32_t* __restrict__
     s_in += a;
     s_out += b;
   }
-  CellOut r;
-  r.orv = wave_or_u32(or_all);
-  // at most 2048 values: if all are below 2^20 the 32-bit sums are exact (else redone below)
-  r.tin = (int64_t)(uint32_t)wave_sum_i32((int)s_in);
-  r.tout = (int64_t)(uint32_t)wave_sum_i32((int)s_out);
-  // Answer = largest a with #{v < a} < rank.  It lies in [lo, top]: top = largest element,
-  // lo = 0, or for cells of several rows the j-th largest per-lane maximum, j = m - rank + 1.
-  const uint32_t top = wave_max_u32(lmax);
-  uint32_t lo = 0;
-  if (R >= 4) {
-    const int j = m - rank + 1;
-    if (j <= DYN_WAVE) {
-      const int nb = 32 - __builtin_clz(top | 1u);
-      for (int b = nb - 1; b >= 0; --b) {   // largest c with #{lane maxima >= c} >= j
-        const uint32_t cand = lo | (1u << b);
-        if (__popcll(__ballot(lmax >= cand)) >= j) lo = cand;
-      }
-    }
-  }
-  uint32_t d = 0;
-  const int nb = 32 - __builtin_clz((top - lo) | 1u);
-  for (int b = nb - 1; b >= 0; --b) {
-    const uint32_t cand = lo + (d | (1u << b));
-    int below = 0;
-#pragma unroll
-    for (int i = 0; i < R; ++i) below += __popcll(__ballot(v[i] < cand));
-    if (below < rank) d |= 1u << b;
-  }
-  r.p99 = lo + d;
-  if (r.orv >= (1u << 20)) cell_sums_wide(in, out, beg, m, lane, &r.tin, &r.tout);
-  return r;
+  return cell_reduce<R>(v, s_in, s_out, or_all, lmax, in, out, beg, m, rank, lane);
+}
+
+// Any register-sized cell (0 < mi <= 64 * kRegRowsMax) by one wave.
+__device__ __forceinline__ CellOut cell_by_wave(const int32_t* __restrict__ in, const int32_t* __restrict__ out,
+                                                int64_t beg, int mi, int rk, int lane) {
+  if (mi <= 64 * 1) return cell_in_registers<1>(in, out, beg, mi, rk, lane);
+  if (mi <= 64 * 2) return cell_in_registers<2>(in, out, beg, mi, rk, lane);
+  if (mi <= 64 * 3) return cell_in_registers<3>(in, out, beg, mi, rk, lane);
+  if (mi <= 64 * 4) return cell_in_registers<4>(in, out, beg, mi, rk, lane);
+  if (mi <= 64 * 6) return cell_in_registers<6>(in, out, beg, mi, rk, lane);
+  if (mi <= 64 * 8) return cell_in_registers<8>(in, out, beg, mi, rk, lane);
+  if (mi <= 64 * 12) return cell_in_registers<12>(in, out, beg, mi, rk, lane);
+  if (mi <= 64 * 16) return cell_in_registers<16>(in, out, beg, mi, rk, lane);
+  if (mi <= 64 * 24) return cell_in_registers<24>(in, out, beg, mi, rk, lane);
+  return cell_in_registers<32>(in, out, beg, mi, rk, lane);
 }
 
 __device__ __forceinline__ int64_t wave_sum_i64(int64_t v) {
@@ -150,22 +179,23 @@ __device__ __forceinline__ int64_t wave_sum_i64(int64_t v) {
 // sums and once per 10-bit digit of the selection (radix select through one LDS histogram).
 // Every thread returns the same result.  `hist` (kHistBins counters) and `xch` (16 words)
 // are LDS scratch; the caller guarantees nobody else uses them.
-__device__ CellOut cell_by_block(const int32_t* __restrict__ in, const int32_t* __restrict__ out, int64_t beg,
+template <int U>   // U independent loads per array in flight
+__device__ __forceinline__ CellOut cell_by_block(const int32_t* __restrict__ in, const int32_t* __restrict__ out, int64_t beg,
                                  int64_t m, int64_t rank, uint32_t* hist, int64_t* xch) {
   const int tid = threadIdx.x, lane = tid & (DYN_WAVE - 1), wave = tid / DYN_WAVE;
   constexpr int nthr = kWavesPerBlock * DYN_WAVE;
   int64_t sin = 0, sout = 0;
   uint32_t orv = 0;
-  for (int64_t i0 = 0; i0 < m; i0 += 8 * nthr) {   // eight independent loads per array in flight
-    int a[8], b[8];
+  for (int64_t i0 = 0; i0 < m; i0 += U * nthr) {
+    int a[U], b[U];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int64_t i = i0 + u * nthr + tid;
       a[u] = i < m ? in[beg + i] : 0;
       b[u] = i < m ? out[beg + i] : 0;
     }
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < U; ++u) {
       sin += a[u];
       sout += b[u];
       orv |= (uint32_t)a[u];
@@ -196,15 +226,15 @@ __device__ CellOut cell_by_block(const int32_t* __restrict__ in, const int32_t* 
     __syncthreads();
     for (int b = tid; b < kHistBins; b += nthr) hist[b] = 0;
     __syncthreads();
-    for (int64_t i0 = 0; i0 < m; i0 += 8 * nthr) {
-      uint32_t a[8];
+    for (int64_t i0 = 0; i0 < m; i0 += U * nthr) {
+      uint32_t a[U];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < U; ++u) {
         const int64_t i = i0 + u * nthr + tid;
         a[u] = i < m ? (uint32_t)in[beg + i] : 0u;
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < U; ++u) {
         const int64_t i = i0 + u * nthr + tid;
         const bool match = i < m && (hi_bit >= 32 ? true : ((a[u] >> hi_bit) == prefix));
         if (match) atomicAdd(&hist[(a[u] >> shift) & dmask], 1u);
@@ -318,16 +348,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
     r.orv = 0;
     if (mi > 0) {
       const int rk = (int)(((int64_t)pct_num * mi + pct_den - 1) / pct_den);
-      if (mi <= 64 * 1) r = cell_in_registers<1>(in, out, beg, mi, rk, lane);
-      else if (mi <= 64 * 2) r = cell_in_registers<2>(in, out, beg, mi, rk, lane);
-      else if (mi <= 64 * 3) r = cell_in_registers<3>(in, out, beg, mi, rk, lane);
-      else if (mi <= 64 * 4) r = cell_in_registers<4>(in, out, beg, mi, rk, lane);
-      else if (mi <= 64 * 6) r = cell_in_registers<6>(in, out, beg, mi, rk, lane);
-      else if (mi <= 64 * 8) r = cell_in_registers<8>(in, out, beg, mi, rk, lane);
-      else if (mi <= 64 * 12) r = cell_in_registers<12>(in, out, beg, mi, rk, lane);
-      else if (mi <= 64 * 16) r = cell_in_registers<16>(in, out, beg, mi, rk, lane);
-      else if (mi <= 64 * 24) r = cell_in_registers<24>(in, out, beg, mi, rk, lane);
-      else r = cell_in_registers<32>(in, out, beg, mi, rk, lane);
+      r = cell_by_wave(in, out, beg, mi, rk, lane);
       if (r.orv >> 31) bad |= DYN_WS_BAD_REQUEST;  // a negative token count
     }
     if (lane == 0) write_cell(c, r, mi, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
@@ -338,7 +359,161 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
     const int64_t beg = readlane_i64(myoff, q);
     const int64_t m = readlane_i64(nxoff, q) - beg;
     const int64_t rank = ((int64_t)pct_num * m + pct_den - 1) / pct_den;
-    const CellOut r = cell_by_block(in, out, beg, m, rank, s_hist, s_xch);
+    const CellOut r = cell_by_block<8>(in, out, beg, m, rank, s_hist, s_xch);
+    const uint32_t bad = (r.orv >> 31) ? DYN_WS_BAD_REQUEST : 0u;
+    if (threadIdx.x == 0) write_cell(c0 + q, r, m, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
+  }
+}
+
+// Traces cut into many small cells (a tick-level view: a few dozen requests per cell): one wave
+// per cell would spend its life waiting for two dependent loads.  Here a wave takes CW
+// consecutive cells.  Their requests are one contiguous run of the trace: if it has at most
+// 64 * kSmallRowsMax requests the wave loads it whole (coalesced, every load in flight at once),
+// reduces cell after cell over the register rows the cell touches, and lanes 0..CW-1 write one
+// cell each.  Otherwise the wave takes its cells one at a time (those beyond 64 * kSmallRowsMax
+// requests are left to the whole block).
+constexpr int kSmallRowsMax = 8;
+
+// Cell [rb, re) of a run held in registers (a[i], b[i] = input / output tokens of request
+// i*64 + lane of the run, 0 beyond it).  0 <= rb < re <= 64 * RS.
+template <int RS>
+__device__ __forceinline__ CellOut cell_of_run(const uint32_t (&a)[RS], const uint32_t (&b)[RS], int rb, int re, int rank,
+                                               const int32_t* __restrict__ in, const int32_t* __restrict__ out,
+                                               int64_t beg, int lane) {
+  uint32_t s_in = 0, s_out = 0, or_all = 0, lmax = 0;
+#pragma unroll
+  for (int i = 0; i < RS; ++i) {
+    if (re <= i * DYN_WAVE || rb >= (i + 1) * DYN_WAVE) continue;    // uniform: the cell does not touch this row
+    const int pos = i * DYN_WAVE + lane;
+    const bool inc = pos >= rb && pos < re;
+    const uint32_t va = inc ? a[i] : 0u, vb = inc ? b[i] : 0u;
+    s_in += va;
+    s_out += vb;
+    or_all |= va | vb;
+    lmax = max(lmax, va);
+  }
+  CellOut r;
+  r.orv = wave_or_u32(or_all);
+  r.tin = (int64_t)(uint32_t)wave_sum_i32((int)s_in);    // exact below 2^20 per value (else redone below)
+  r.tout = (int64_t)(uint32_t)wave_sum_i32((int)s_out);
+  const uint32_t top = wave_max_u32(lmax);
+  const int m = re - rb;
+  if (rank == m) {                          // the nearest rank of a small cell is its last: the maximum
+    r.p99 = top;
+  } else {                                  // largest value with fewer than `rank` elements below it
+    uint32_t d = 0;
+    const int nb = 32 - __builtin_clz(top | 1u);
+    for (int bit = nb - 1; bit >= 0; --bit) {
+      const uint32_t cand = d | (1u << bit);
+      int below = 0;
+#pragma unroll
+      for (int i = 0; i < RS; ++i) {
+        if (re <= i * DYN_WAVE || rb >= (i + 1) * DYN_WAVE) continue;
+        const int pos = i * DYN_WAVE + lane;
+        below += __popcll(__ballot(pos >= rb && pos < re && a[i] < cand));
+      }
+      if (below < rank) d = cand;
+    }
+    r.p99 = d;
+  }
+  if (r.orv >= (1u << 20)) cell_sums_wide(in, out, beg, m, lane, &r.tin, &r.tout);
+  return r;
+}
+
+template <int CW>
+__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_waves_per_eu(6, 8))) void cell_aggregate_small_kernel(
+    const int32_t* __restrict__ in, const int32_t* __restrict__ out,
+    const int64_t* __restrict__ cell_off, int64_t n_req, int64_t cells, double window_s, double r_window,
+    int32_t pct_num, int32_t pct_den, int64_t* __restrict__ tin, int64_t* __restrict__ tout,
+    int32_t* __restrict__ in_p99, CellRec* __restrict__ rec, uint8_t* __restrict__ cstat,
+    WsHeader* __restrict__ header) {
+  constexpr int CB = kWavesPerBlock * CW;        // cells per block
+  constexpr int RS = kSmallRowsMax;
+  static_assert(CB + 1 <= DYN_WAVE && CB <= 32, "one lane per offset, one mask bit per cell");
+  __shared__ uint32_t s_hist[kHistBins];
+  __shared__ int64_t s_xch[16];
+  const int lane = threadIdx.x & (DYN_WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
+  const int64_t c0 = (int64_t)blockIdx.x * CB;
+  const int nc = (int)(cells - c0 < CB ? cells - c0 : CB);
+  const int64_t myoff = lane <= nc ? cell_off[c0 + lane] : 0;
+  const int64_t nxoff = __shfl_down(myoff, 1, DYN_WAVE);
+  const bool good = lane < nc && myoff >= 0 && nxoff >= myoff && nxoff <= n_req;   // never read outside the trace
+  const int64_t len = good ? nxoff - myoff : 0;
+  const uint32_t good_mask = (uint32_t)__ballot(good);
+  const uint32_t big_mask = (uint32_t)__ballot(len > DYN_WAVE * RS);
+  const int len32 = (int)(len > 0x7FFFFFFF ? 0x7FFFFFFF : len);
+
+  const int q0 = wave * CW;
+  const int nq = nc - q0 < CW ? nc - q0 : CW;    // cells of this wave (<= 0: none)
+  CellOut mine;                                  // lane u keeps the result of the wave's cell u
+  mine.tin = mine.tout = 0;
+  mine.p99 = 0;
+  mine.orv = 0;
+  int my_m = 0;
+  uint32_t my_bad = 0;
+  if (nq > 0) {
+    const uint32_t grp = ((1u << nq) - 1u) << q0;          // nq <= CW < 32
+    const int64_t sb = readlane_i64(myoff, q0), se = readlane_i64(myoff, q0 + nq);
+    if ((good_mask & grp) == grp && se - sb <= DYN_WAVE * RS) {
+      // every offset of the group is in order: 0 <= sb <= each cell's bounds <= se <= n_req
+      const int span = (int)(se - sb);
+      uint32_t a[RS], b[RS];
+#pragma unroll
+      for (int i = 0; i < RS; ++i) {
+        const int pos = i * DYN_WAVE + lane;
+        a[i] = pos < span ? (uint32_t)in[sb + pos] : 0u;
+        b[i] = pos < span ? (uint32_t)out[sb + pos] : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < CW; ++u) {
+        if (u >= nq) break;
+        const int64_t beg = readlane_i64(myoff, q0 + u);
+        const int mi = __builtin_amdgcn_readlane(len32, q0 + u);
+        if (mi == 0) continue;                   // an empty cell keeps the zeros
+        const int rb = (int)(beg - sb);
+        const int rk = (int)(((int64_t)pct_num * mi + pct_den - 1) / pct_den);
+        const CellOut r = cell_of_run<RS>(a, b, rb, rb + mi, rk, in, out, beg, lane);
+        if (lane == u) { mine = r; my_m = mi; my_bad = (r.orv >> 31) ? DYN_WS_BAD_REQUEST : 0u; }
+      }
+    } else {
+#pragma unroll 1
+      for (int u = 0; u < nq; ++u) {
+        const int q = q0 + u;
+        if ((big_mask >> q) & 1u) continue;      // uniform over the wave
+        CellOut r;
+        r.tin = r.tout = 0;
+        r.p99 = 0;
+        r.orv = 0;
+        uint32_t bad = 0;
+        int mi = 0;
+        if (!((good_mask >> q) & 1u)) {
+          bad = DYN_WS_BAD_OFFSETS;
+        } else {
+          const int64_t beg = readlane_i64(myoff, q);
+          mi = __builtin_amdgcn_readlane(len32, q);
+          if (mi > 0) {
+            const int rk = (int)(((int64_t)pct_num * mi + pct_den - 1) / pct_den);
+            if (mi <= 64 * 1) r = cell_in_registers<1>(in, out, beg, mi, rk, lane);
+            else if (mi <= 64 * 2) r = cell_in_registers<2>(in, out, beg, mi, rk, lane);
+            else if (mi <= 64 * 4) r = cell_in_registers<4>(in, out, beg, mi, rk, lane);
+            else r = cell_in_registers<RS>(in, out, beg, mi, rk, lane);
+            if (r.orv >> 31) bad |= DYN_WS_BAD_REQUEST;
+          }
+        }
+        if (lane == u) { mine = r; my_m = mi; my_bad = bad; }
+      }
+    }
+  }
+  if (lane < nq && !((big_mask >> (q0 + lane)) & 1u))
+    write_cell(c0 + q0 + lane, mine, my_m, my_bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
+  if (big_mask == 0) return;   // uniform over the block
+  for (int q = 0; q < CB; ++q) {
+    if (!((big_mask >> q) & 1u)) continue;
+    const int64_t beg = readlane_i64(myoff, q);
+    const int64_t m = readlane_i64(nxoff, q) - beg;
+    const int64_t rank = ((int64_t)pct_num * m + pct_den - 1) / pct_den;
+    const CellOut r = cell_by_block<2>(in, out, beg, m, rank, s_hist, s_xch);
     const uint32_t bad = (r.orv >> 31) ? DYN_WS_BAD_REQUEST : 0u;
     if (threadIdx.x == 0) write_cell(c0 + q, r, m, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
   }
@@ -351,8 +526,16 @@ hipError_t dyn_launch_cell_aggregate(const int32_t* in_tok, const int32_t* out_t
                                      double window_s, int32_t pct_num, int32_t pct_den,
                                      int64_t* tin, int64_t* tout, int32_t* in_p99, CellRec* rec,
                                      uint8_t* cstat, WsHeader* header, hipStream_t s) {
-  const int64_t blocks = (cells + kWavesPerBlock - 1) / kWavesPerBlock;
   DynTimed timed(DYN_K_CELL, s);
+  constexpr int kSmallCells = 8;                 // cells per wave of the many-small-cells kernel
+  if (n_req / 48 <= cells) {                     // a few dozen requests per cell on average
+    const int64_t per = kWavesPerBlock * kSmallCells;
+    hipLaunchKernelGGL(cell_aggregate_small_kernel<kSmallCells>, dim3((unsigned)((cells + per - 1) / per)),
+                       dim3(kWavesPerBlock * DYN_WAVE), 0, s, in_tok, out_tok, cell_off, n_req, cells, window_s,
+                       1.0 / window_s, pct_num, pct_den, tin, tout, in_p99, rec, cstat, header);
+    return hipGetLastError();
+  }
+  const int64_t blocks = (cells + kWavesPerBlock - 1) / kWavesPerBlock;
   hipLaunchKernelGGL(cell_aggregate_kernel, dim3((unsigned)blocks), dim3(kWavesPerBlock * DYN_WAVE),
                      0, s, in_tok, out_tok, cell_off, n_req, cells, window_s, 1.0 / window_s, pct_num, pct_den, tin,
                      tout, in_p99, rec, cstat, header);
