@@ -365,121 +365,116 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
   }
 }
 
-// Traces cut into many small cells (a tick-level view: a few dozen requests per cell): one wave
-// per cell would spend its life waiting for two dependent loads.  Here a wave takes CW
-// consecutive cells.  Their requests are one contiguous run of the trace: if it has at most
-// 64 * kSmallRowsMax requests the wave loads it whole (coalesced, every load in flight at once),
-// reduces cell after cell over the register rows the cell touches, and lanes 0..CW-1 write one
-// cell each.  Otherwise the wave takes its cells one at a time (those beyond 64 * kSmallRowsMax
-// requests are left to the whole block).
-constexpr int kSmallRowsMax = 8;
+// Traces cut into many small cells (a tick-level view: a few dozen requests per cell).  A wave
+// per cell spends its life waiting for two dependent loads and its 64 lanes reduce a handful
+// of values.  Here a wave takes kTinyCells consecutive cells.  Their requests are one contiguous
+// run of the trace: if it has at most kTinyCap requests the wave copies it to LDS (coalesced,
+// all loads in flight at once) and kTinyLanes lanes per cell walk the cell's requests, each
+// keeping sums, the OR and the two largest inputs; a quad exchange combines them.  That
+// settles every cell whose nearest rank is its largest or second-largest input (any cell of
+// fewer than 200 requests at the 99th percentile); the others, cells with token counts of
+// 2^20 or more, and groups whose run does not fit are taken one cell at a time by the wave
+// (cells beyond 64 * kRegRowsMax requests by the whole block, after a block barrier).
+constexpr int kTinyCells = 16;
+constexpr int kTinyLanes = DYN_WAVE / kTinyCells;
+constexpr int kTinyCap = 1024;
+static_assert(kTinyLanes == 4, "the quad exchange below combines four lanes");
 
-// Cell [rb, re) of a run held in registers (a[i], b[i] = input / output tokens of request
-// i*64 + lane of the run, 0 beyond it).  0 <= rb < re <= 64 * RS.
-template <int RS>
-__device__ __forceinline__ CellOut cell_of_run(const uint32_t (&a)[RS], const uint32_t (&b)[RS], int rb, int re, int rank,
-                                               const int32_t* __restrict__ in, const int32_t* __restrict__ out,
-                                               int64_t beg, int lane) {
-  uint32_t s_in = 0, s_out = 0, or_all = 0, lmax = 0;
-#pragma unroll
-  for (int i = 0; i < RS; ++i) {
-    if (re <= i * DYN_WAVE || rb >= (i + 1) * DYN_WAVE) continue;    // uniform: the cell does not touch this row
-    const int pos = i * DYN_WAVE + lane;
-    const bool inc = pos >= rb && pos < re;
-    const uint32_t va = inc ? a[i] : 0u, vb = inc ? b[i] : 0u;
-    s_in += va;
-    s_out += vb;
-    or_all |= va | vb;
-    lmax = max(lmax, va);
-  }
-  CellOut r;
-  r.orv = wave_or_u32(or_all);
-  r.tin = (int64_t)(uint32_t)wave_sum_i32((int)s_in);    // exact below 2^20 per value (else redone below)
-  r.tout = (int64_t)(uint32_t)wave_sum_i32((int)s_out);
-  const uint32_t top = wave_max_u32(lmax);
-  const int m = re - rb;
-  if (rank == m) {                          // the nearest rank of a small cell is its last: the maximum
-    r.p99 = top;
-  } else {                                  // largest value with fewer than `rank` elements below it
-    uint32_t d = 0;
-    const int nb = 32 - __builtin_clz(top | 1u);
-    for (int bit = nb - 1; bit >= 0; --bit) {
-      const uint32_t cand = d | (1u << bit);
-      int below = 0;
-#pragma unroll
-      for (int i = 0; i < RS; ++i) {
-        if (re <= i * DYN_WAVE || rb >= (i + 1) * DYN_WAVE) continue;
-        const int pos = i * DYN_WAVE + lane;
-        below += __popcll(__ballot(pos >= rb && pos < re && a[i] < cand));
-      }
-      if (below < rank) d = cand;
-    }
-    r.p99 = d;
-  }
-  if (r.orv >= (1u << 20)) cell_sums_wide(in, out, beg, m, lane, &r.tin, &r.tout);
-  return r;
-}
-
-template <int CW>
-__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_waves_per_eu(6, 8))) void cell_aggregate_small_kernel(
+__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_waves_per_eu(4, 4))) void cell_aggregate_tiny_kernel(
     const int32_t* __restrict__ in, const int32_t* __restrict__ out,
     const int64_t* __restrict__ cell_off, int64_t n_req, int64_t cells, double window_s, double r_window,
     int32_t pct_num, int32_t pct_den, int64_t* __restrict__ tin, int64_t* __restrict__ tout,
     int32_t* __restrict__ in_p99, CellRec* __restrict__ rec, uint8_t* __restrict__ cstat,
     WsHeader* __restrict__ header) {
-  constexpr int CB = kWavesPerBlock * CW;        // cells per block
-  constexpr int RS = kSmallRowsMax;
-  static_assert(CB + 1 <= DYN_WAVE && CB <= 32, "one lane per offset, one mask bit per cell");
+  __shared__ uint2 s_run[kWavesPerBlock][kTinyCap];
+  __shared__ int64_t s_off[kWavesPerBlock][kTinyCells + 1];
+  __shared__ uint32_t s_big[kWavesPerBlock];
   __shared__ uint32_t s_hist[kHistBins];
   __shared__ int64_t s_xch[16];
   const int lane = threadIdx.x & (DYN_WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
-  const int64_t c0 = (int64_t)blockIdx.x * CB;
-  const int nc = (int)(cells - c0 < CB ? cells - c0 : CB);
-  const int64_t myoff = lane <= nc ? cell_off[c0 + lane] : 0;
+  const int64_t c0 = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * kTinyCells;
+  const int nq = cells - c0 < kTinyCells ? (int)(cells - c0 > 0 ? cells - c0 : 0) : kTinyCells;   // cells of this wave
+  const int64_t myoff = (nq > 0 && lane <= nq) ? cell_off[c0 + lane] : 0;
   const int64_t nxoff = __shfl_down(myoff, 1, DYN_WAVE);
-  const bool good = lane < nc && myoff >= 0 && nxoff >= myoff && nxoff <= n_req;   // never read outside the trace
+  const bool good = lane < nq && myoff >= 0 && nxoff >= myoff && nxoff <= n_req;   // never read outside the trace
   const int64_t len = good ? nxoff - myoff : 0;
   const uint32_t good_mask = (uint32_t)__ballot(good);
-  const uint32_t big_mask = (uint32_t)__ballot(len > DYN_WAVE * RS);
+  const uint32_t big_mask = (uint32_t)__ballot(len > DYN_WAVE * kRegRowsMax);
   const int len32 = (int)(len > 0x7FFFFFFF ? 0x7FFFFFFF : len);
+  if (lane <= kTinyCells) s_off[wave][lane] = myoff;
+  if (lane == 0) s_big[wave] = big_mask;
 
-  const int q0 = wave * CW;
-  const int nq = nc - q0 < CW ? nc - q0 : CW;    // cells of this wave (<= 0: none)
-  CellOut mine;                                  // lane u keeps the result of the wave's cell u
+  const int u = lane / kTinyLanes, sub = lane % kTinyLanes;   // this lane's cell of the wave, and its share of it
+  CellOut mine;                                  // lane kTinyLanes * u keeps the result of cell u
   mine.tin = mine.tout = 0;
   mine.p99 = 0;
   mine.orv = 0;
   int my_m = 0;
   uint32_t my_bad = 0;
   if (nq > 0) {
-    const uint32_t grp = ((1u << nq) - 1u) << q0;          // nq <= CW < 32
-    const int64_t sb = readlane_i64(myoff, q0), se = readlane_i64(myoff, q0 + nq);
-    if ((good_mask & grp) == grp && se - sb <= DYN_WAVE * RS) {
+    const uint32_t grp = (1u << nq) - 1u;
+    const int64_t sb = readlane_i64(myoff, 0), se = readlane_i64(myoff, nq);
+    if ((good_mask & grp) == grp && se - sb <= kTinyCap) {
       // every offset of the group is in order: 0 <= sb <= each cell's bounds <= se <= n_req
       const int span = (int)(se - sb);
-      uint32_t a[RS], b[RS];
-#pragma unroll
-      for (int i = 0; i < RS; ++i) {
-        const int pos = i * DYN_WAVE + lane;
-        a[i] = pos < span ? (uint32_t)in[sb + pos] : 0u;
-        b[i] = pos < span ? (uint32_t)out[sb + pos] : 0u;
+      uint2* run = s_run[wave];
+#pragma unroll 4
+      for (int pos = lane; pos < span; pos += DYN_WAVE) run[pos] = make_uint2((uint32_t)in[sb + pos], (uint32_t)out[sb + pos]);
+      // the run is read back by other lanes of this wave only
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      const int64_t ob = __shfl(myoff, u, DYN_WAVE), oe = __shfl(myoff, u + 1, DYN_WAVE);
+      const int m = u < nq ? (int)(oe - ob) : 0;
+      const int rb = u < nq ? (int)(ob - sb) : 0;
+      uint32_t s_in = 0, s_out = 0, orv = 0, t1 = 0, t2 = 0;   // t1 >= t2: the two largest inputs so far
+      for (int i = rb + sub; i < rb + m; i += kTinyLanes) {
+        const uint2 v = run[i];
+        s_in += v.x;
+        s_out += v.y;
+        orv |= v.x | v.y;
+        t2 = max(t2, min(t1, v.x));
+        t1 = max(t1, v.x);
       }
 #pragma unroll
-      for (int u = 0; u < CW; ++u) {
-        if (u >= nq) break;
-        const int64_t beg = readlane_i64(myoff, q0 + u);
-        const int mi = __builtin_amdgcn_readlane(len32, q0 + u);
-        if (mi == 0) continue;                   // an empty cell keeps the zeros
-        const int rb = (int)(beg - sb);
-        const int rk = (int)(((int64_t)pct_num * mi + pct_den - 1) / pct_den);
-        const CellOut r = cell_of_run<RS>(a, b, rb, rb + mi, rk, in, out, beg, lane);
-        if (lane == u) { mine = r; my_m = mi; my_bad = (r.orv >> 31) ? DYN_WS_BAD_REQUEST : 0u; }
+      for (int step = 0; step < 2; ++step) {     // lanes sub ^ 1, then sub ^ 2
+        const uint32_t o_in = step ? (uint32_t)dpp_mov<0x4E>((int)s_in) : (uint32_t)dpp_mov<0xB1>((int)s_in);
+        const uint32_t o_out = step ? (uint32_t)dpp_mov<0x4E>((int)s_out) : (uint32_t)dpp_mov<0xB1>((int)s_out);
+        const uint32_t o_or = step ? (uint32_t)dpp_mov<0x4E>((int)orv) : (uint32_t)dpp_mov<0xB1>((int)orv);
+        const uint32_t o1 = step ? (uint32_t)dpp_mov<0x4E>((int)t1) : (uint32_t)dpp_mov<0xB1>((int)t1);
+        const uint32_t o2 = step ? (uint32_t)dpp_mov<0x4E>((int)t2) : (uint32_t)dpp_mov<0xB1>((int)t2);
+        s_in += o_in;
+        s_out += o_out;
+        orv |= o_or;
+        t2 = max(max(t2, o2), min(t1, o1));
+        t1 = max(t1, o1);
       }
+      // nearest rank ceil(pct * m) counted from the top: j = 1 is the largest input
+      const int rk = m > 0 ? (int)(((int64_t)pct_num * m + pct_den - 1) / pct_den) : 0;
+      const int j = m - rk + 1;
+      // at most 1024 values: 32-bit sums are exact if all are below 2^20
+      const bool again = m > 0 && (orv >= (1u << 20) || j > 2);
+      mine.tin = (int64_t)s_in;
+      mine.tout = (int64_t)s_out;
+      mine.p99 = j == 1 ? t1 : t2;
+      mine.orv = orv;
+      my_m = m;
+      uint64_t todo = __ballot(sub == 0 && again);
+      while (todo) {                             // uniform over the wave
+        const int l = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        const int q = l / kTinyLanes;
+        const int64_t beg = readlane_i64(myoff, q);
+        const int mi = __builtin_amdgcn_readlane(len32, q);
+        const int rk1 = (int)(((int64_t)pct_num * mi + pct_den - 1) / pct_den);
+        const CellOut r = cell_by_wave(in, out, beg, mi, rk1, lane);
+        if (lane == l) mine = r;
+      }
+      if (mine.orv >> 31) my_bad = DYN_WS_BAD_REQUEST;   // a negative token count
     } else {
 #pragma unroll 1
-      for (int u = 0; u < nq; ++u) {
-        const int q = q0 + u;
+      for (int q = 0; q < nq; ++q) {
         if ((big_mask >> q) & 1u) continue;      // uniform over the wave
         CellOut r;
         r.tin = r.tout = 0;
@@ -494,29 +489,30 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
           mi = __builtin_amdgcn_readlane(len32, q);
           if (mi > 0) {
             const int rk = (int)(((int64_t)pct_num * mi + pct_den - 1) / pct_den);
-            if (mi <= 64 * 1) r = cell_in_registers<1>(in, out, beg, mi, rk, lane);
-            else if (mi <= 64 * 2) r = cell_in_registers<2>(in, out, beg, mi, rk, lane);
-            else if (mi <= 64 * 4) r = cell_in_registers<4>(in, out, beg, mi, rk, lane);
-            else r = cell_in_registers<RS>(in, out, beg, mi, rk, lane);
+            r = cell_by_wave(in, out, beg, mi, rk, lane);
             if (r.orv >> 31) bad |= DYN_WS_BAD_REQUEST;
           }
         }
-        if (lane == u) { mine = r; my_m = mi; my_bad = bad; }
+        if (lane == q * kTinyLanes) { mine = r; my_m = mi; my_bad = bad; }
       }
     }
   }
-  if (lane < nq && !((big_mask >> (q0 + lane)) & 1u))
-    write_cell(c0 + q0 + lane, mine, my_m, my_bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
-  if (big_mask == 0) return;   // uniform over the block
-  for (int q = 0; q < CB; ++q) {
-    if (!((big_mask >> q) & 1u)) continue;
-    const int64_t beg = readlane_i64(myoff, q);
-    const int64_t m = readlane_i64(nxoff, q) - beg;
-    const int64_t rank = ((int64_t)pct_num * m + pct_den - 1) / pct_den;
-    const CellOut r = cell_by_block<2>(in, out, beg, m, rank, s_hist, s_xch);
-    const uint32_t bad = (r.orv >> 31) ? DYN_WS_BAD_REQUEST : 0u;
-    if (threadIdx.x == 0) write_cell(c0 + q, r, m, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
-  }
+  if (sub == 0 && u < nq && !((big_mask >> u) & 1u))
+    write_cell(c0 + u, mine, my_m, my_bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
+  __syncthreads();             // every wave of the block arrives here: s_off and s_big are complete
+  if ((s_big[0] | s_big[1] | s_big[2] | s_big[3]) == 0) return;   // uniform over the block
+  static_assert(kWavesPerBlock == 4, "the line above names the block's four waves");
+  for (int w = 0; w < kWavesPerBlock; ++w)
+    for (int q = 0; q < kTinyCells; ++q) {
+      if (!((s_big[w] >> q) & 1u)) continue;
+      const int64_t beg = s_off[w][q];
+      const int64_t m = s_off[w][q + 1] - beg;
+      const int64_t rank = ((int64_t)pct_num * m + pct_den - 1) / pct_den;
+      const CellOut r = cell_by_block<2>(in, out, beg, m, rank, s_hist, s_xch);
+      const uint32_t bad = (r.orv >> 31) ? DYN_WS_BAD_REQUEST : 0u;
+      const int64_t c = ((int64_t)blockIdx.x * kWavesPerBlock + w) * kTinyCells + q;
+      if (threadIdx.x == 0) write_cell(c, r, m, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
+    }
 }
 
 }  // namespace
@@ -527,10 +523,9 @@ hipError_t dyn_launch_cell_aggregate(const int32_t* in_tok, const int32_t* out_t
                                      int64_t* tin, int64_t* tout, int32_t* in_p99, CellRec* rec,
                                      uint8_t* cstat, WsHeader* header, hipStream_t s) {
   DynTimed timed(DYN_K_CELL, s);
-  constexpr int kSmallCells = 8;                 // cells per wave of the many-small-cells kernel
   if (n_req / 48 <= cells) {                     // a few dozen requests per cell on average
-    const int64_t per = kWavesPerBlock * kSmallCells;
-    hipLaunchKernelGGL(cell_aggregate_small_kernel<kSmallCells>, dim3((unsigned)((cells + per - 1) / per)),
+    const int64_t per = kWavesPerBlock * kTinyCells;
+    hipLaunchKernelGGL(cell_aggregate_tiny_kernel, dim3((unsigned)((cells + per - 1) / per)),
                        dim3(kWavesPerBlock * DYN_WAVE), 0, s, in_tok, out_tok, cell_off, n_req, cells, window_s,
                        1.0 / window_s, pct_num, pct_den, tin, tout, in_p99, rec, cstat, header);
     return hipGetLastError();

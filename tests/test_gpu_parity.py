@@ -319,6 +319,61 @@ def test_mixed_small_and_large_cells(dyn):
         assert rep["bit_exact"] and rep["sel_mismatch"] == 0
 
 
+@pytest.mark.parametrize("pct", [(99, 100), (1, 2), (1, 1), (1, 100), (9, 10)])
+def test_many_small_cells_with_outliers(dyn, pct):
+    """A tick-like cut (a few dozen requests per cell on average, several cells per wave) with everything
+    that leaves the common path mixed in: cells whose nearest rank is not among the two largest inputs,
+    runs of cells too long to stage, cells for one wave alone and for a whole block, token counts of 2^20
+    and more, empty stretches, and a last group that is not full."""
+    prof, cfg = _worked()
+    rng = np.random.default_rng(13 + pct[0])
+    sizes = rng.integers(0, 60, 3001)
+    sizes[rng.integers(0, sizes.size, 300)] = 0
+    sizes[rng.integers(0, sizes.size, 40)] = rng.integers(100, 1000, 40)
+    sizes[rng.integers(0, sizes.size, 8)] = rng.integers(1025, 2049, 8)
+    sizes[[17, 1500, 2999]] = [2049, 5000, 3000]
+    sizes[100:140] = 0
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(off[-1])
+    assert n // 48 <= sizes.size
+    x = rng.integers(1, 8193, n); y = rng.integers(1, 8193, n)
+    for c in (5, 640, 1501, 2500, 2999):                   # wide values: sums beyond 32 bits per lane
+        x[off[c]:off[c + 1]] = rng.integers(2 ** 20, 2 ** 30, sizes[c])
+        y[off[c]:off[c + 1]] = rng.integers(0, 2 ** 30, sizes[c])
+    w, st, g = _single(dyn, prof, cfg, x, y, 100, 50, 1000.0, n_window=sizes.size, off=off, lam=0.1, pct=pct)
+    assert g["status"] == 0
+    xs = x.astype(np.int64); ys = y.astype(np.int64)
+    for c in range(sizes.size):
+        seg = xs[off[c]:off[c + 1]]
+        assert g["tin"][c] == seg.sum() and g["tout"][c] == ys[off[c]:off[c + 1]].sum(), c
+        if seg.size:
+            assert g["in_p99"][c] == np.sort(seg)[-(-pct[0] * seg.size // pct[1]) - 1], (c, seg.size)
+    rep = assert_parity(w, g, ora_eval(w, st))
+    assert rep["bit_exact"] and rep["sel_mismatch"] == 0
+
+
+def test_small_cells_bad_offsets_and_negative_tokens_are_reported_per_cell(dyn):
+    prof, cfg = _worked()
+    rng = np.random.default_rng(14)
+    sizes = rng.integers(0, 40, 200)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(off[-1])
+    x = rng.integers(1, 8193, n); y = rng.integers(1, 8193, n)
+    good = _single(dyn, prof, cfg, x, y, 100, 50, 1000.0, n_window=sizes.size, off=off)[2]
+    bad_off = off.copy(); bad_off[70] = off[90]            # cells 69 and 70 now have offsets out of order
+    g = _single(dyn, prof, cfg, x, y, 100, 50, 1000.0, n_window=sizes.size, off=bad_off)[2]
+    assert g["status"] & dyn.DYN_WS_BAD_OFFSETS
+    keep = np.ones(sizes.size, bool); keep[[69, 70]] = False
+    np.testing.assert_array_equal(g["tin"][keep], good["tin"][keep])
+    np.testing.assert_array_equal(g["in_p99"][keep], good["in_p99"][keep])
+    x2 = x.copy(); x2[off[33]] = -5
+    g = _single(dyn, prof, cfg, x2, y, 100, 50, 1000.0, n_window=sizes.size, off=off)[2]
+    assert g["status"] & dyn.DYN_WS_BAD_REQUEST
+    keep = np.ones(sizes.size, bool); keep[33] = False
+    np.testing.assert_array_equal(g["tin"][keep], good["tin"][keep])
+    np.testing.assert_array_equal(g["in_p99"][keep], good["in_p99"][keep])
+
+
 def test_off_grid_frequencies_single_frequency_and_odd_k(dyn):
     rng = np.random.default_rng(21)
     G, n_tp = 3, 2
