@@ -371,7 +371,8 @@ int dyn_account(dyn_profile* profile, const int32_t* sel, const double* window_e
  * `coarse` is the trace sorted by window (n_window windows of n_tick * tick_s seconds), `fine`
  * the same requests sorted by tick (n_window * n_tick windows of tick_s seconds), both as
  * dyn_trace_ingest returns them.  lay_n / lay_tp_index HOST [n_layout].  Outputs DEVICE.
- * objective->gpu_budget and idle_cost_weight are not used.                                */
+ * objective->gpu_budget and idle_cost_weight are not used.  Profiles of more than 64 TP
+ * degrees or 4096 classes are refused (DYN_E_SHAPE).                                       */
 typedef struct {
   int32_t epoch_windows;
   int32_t tp_ref_index, f_ref_index;

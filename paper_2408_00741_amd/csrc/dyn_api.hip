@@ -881,7 +881,7 @@ namespace {
 struct HierWs {
   EvalWs coarse;                 // header .. cstat of the window-level aggregation (first: its header is the workspace's)
   size_t fine_base; EvalWs fine; // the tick-level aggregation, offsets relative to fine_base
-  size_t tp, lay_n, lay_tp, ok, tick_energy, tick_viol, total;
+  size_t tp, lay_n, lay_tp, tick_energy, tick_viol, total;
 };
 HierWs hier_ws_layout(int64_t cells, int32_t n_tick, int32_t n_tp, int32_t n_layout) {
   HierWs w;
@@ -893,7 +893,6 @@ HierWs hier_ws_layout(int64_t cells, int32_t n_tick, int32_t n_tp, int32_t n_lay
   w.tp = off; off += align256((size_t)n_tp * 4);
   w.lay_n = off; off += align256((size_t)n_layout * 4);
   w.lay_tp = off; off += align256((size_t)n_layout * 4);
-  w.ok = off; off += align256(c * 4);
   w.tick_energy = off; off += align256(c * n_tick * 8);
   w.tick_viol = off; off += align256(c * n_tick);
   w.total = off;
@@ -917,7 +916,8 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
   }
   if (!tc->cell_off || !tf->cell_off || (tc->n_req > 0 && (!tc->in_tok || !tc->out_tok || !tf->in_tok || !tf->out_tok))) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
   if (!(tf->window_s > 0.0) || !isfinite(tf->window_s)) { dyn_set_error("tick length must be finite and > 0"); return DYN_E_RANGE; }
-  if (c->epoch_windows < 1 || c->gpus_per_node < 1 || c->n_layout < 1 || p->n_tp > 64) { dyn_set_error("epoch_windows, gpus_per_node or n_layout < 1"); return DYN_E_SHAPE; }
+  if (c->epoch_windows < 1 || c->gpus_per_node < 1 || c->n_layout < 1) { dyn_set_error("epoch_windows, gpus_per_node or n_layout < 1"); return DYN_E_SHAPE; }
+  if (p->n_tp > 64 || p->G > 4096) { dyn_set_error("dyn_hierarchy takes profiles of up to 64 TP degrees and 4096 classes"); return DYN_E_SHAPE; }
   if (c->tp_ref_index < 0 || c->tp_ref_index >= p->n_tp || c->f_ref_index < 0 || c->f_ref_index >= p->n_f) { dyn_set_error("reference configuration outside the profile"); return DYN_E_RANGE; }
   for (int l = 0; l < c->n_layout; ++l)
     if (c->lay_n[l] < 1 || c->lay_tp_index[l] < 0 || c->lay_tp_index[l] >= p->n_tp) { dyn_set_error("layout %d is not valid", l); return DYN_E_RANGE; }
@@ -946,7 +946,7 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
                                         (CellRec*)(base + w.coarse.rec), (uint8_t*)(base + w.coarse.cstat), (WsHeader*)(base + w.coarse.header), s), "cell aggregate launch"))
     return DYN_E_DEVICE;
   HierArgs a;
-  a.tab = p->d_tab; a.ml = p->d_ml; a.gridpack = p->d_gridpack; a.jstart = p->d_jstart; a.n_bucket = p->n_bucket; a.bucket_scale = p->bucket_scale;
+  a.tab = p->d_tab; a.ml = p->d_ml; a.gridpack = p->d_gridpack; a.jstart = p->d_jstart; a.tstart = p->d_tstart; a.thr = p->d_thr; a.n_bucket = p->n_bucket; a.bucket_scale = p->bucket_scale;
   a.G = p->G; a.n_tp = p->n_tp; a.n_f = p->n_f; a.n_rho = p->n_rho; a.tp = (const int32_t*)(base + w.tp);
   a.slo_ttft = p->d_slo_ttft; a.slo_tbt = p->d_slo_tbt;
   a.rec_c = (const CellRec*)(base + w.coarse.rec); a.rec_f = (const CellRec*)(fb + w.fine.rec);
@@ -956,10 +956,9 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
   a.tp_ref = c->tp_ref_index; a.f_ref = c->f_ref_index; a.gpus_per_node = c->gpus_per_node;
   a.n_layout = c->n_layout; a.lay_n = (const int32_t*)(base + w.lay_n); a.lay_tp = (const int32_t*)(base + w.lay_tp);
   a.nodes = out->nodes; a.layout_sel = out->layout_sel; a.f_sel = out->f_sel; a.energy = out->energy_j; a.violations = out->violations;
-  a.ok = (int32_t*)(base + w.ok); a.tick_energy = (double*)(base + w.tick_energy); a.tick_viol = (uint8_t*)(base + w.tick_viol);
-  if (!hip_ok(dyn_launch_hierarchy(a, s), "hierarchy launch")) return DYN_E_DEVICE;
-  if (!hip_ok(dyn_launch_window_totals(a.ok, out->energy_j, tc->n_window, p->G, out->window_energy_j, out->window_infeasible, s), "window totals launch"))
-    return DYN_E_DEVICE;
+  a.win_energy = out->window_energy_j; a.win_inf = out->window_infeasible;
+  a.tick_energy = (double*)(base + w.tick_energy); a.tick_viol = (uint8_t*)(base + w.tick_viol);
+  if (!hip_ok(dyn_launch_hierarchy(a, p->single_point, s), "hierarchy launch")) return DYN_E_DEVICE;
   return DYN_OK;
 }
 

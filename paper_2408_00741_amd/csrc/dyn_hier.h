@@ -6,7 +6,8 @@
 
 struct HierArgs {
   // profile
-  const double* tab; const double* ml; const double* gridpack; const int32_t* jstart; int32_t n_bucket; double bucket_scale;
+  const double* tab; const double* ml; const double* gridpack; const int32_t* jstart; const int32_t* tstart; const double* thr;
+  int32_t n_bucket; double bucket_scale;
   int32_t G, n_tp, n_f, n_rho;
   const int32_t* tp;            // DEVICE [n_tp] GPUs per instance
   const double* slo_ttft; const double* slo_tbt;
@@ -21,10 +22,11 @@ struct HierArgs {
   int32_t epoch_windows, n_epoch, tp_ref, f_ref, gpus_per_node;
   int32_t n_layout; const int32_t* lay_n; const int32_t* lay_tp;   // DEVICE [n_layout]
   // outputs and scratch
-  int32_t* nodes; int32_t* layout_sel; int32_t* f_sel; double* energy; int32_t* violations; int32_t* ok;
+  int32_t* nodes; int32_t* layout_sel; int32_t* f_sel; double* energy; int32_t* violations;
+  double* win_energy; int32_t* win_inf;   // [n_window] totals over the classes
   double* tick_energy;          // workspace [fine cells]
   uint8_t* tick_viol;           // workspace [fine cells]
 };
-hipError_t dyn_launch_hierarchy(const HierArgs& a, hipStream_t s);
+hipError_t dyn_launch_hierarchy(const HierArgs& a, bool single_point, hipStream_t s);
 
 #endif  // DYN_HIER_H_

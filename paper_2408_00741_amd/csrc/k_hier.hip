@@ -1,76 +1,107 @@
 // The three controllers of Section IV-B, top down, on the aggregates of a trace:
-//   hier_nodes_kernel   scale-out/in: nodes = ceil(peak load of the epoch / largest profiled load of one
-//                       node at the reference configuration), at least one;
-//   hier_shard_kernel   shard-up/down: per (window, class) the layout (instances, TP) of least energy at
-//                       the reference frequency among those that fit the nodes' GPUs and meet the SLO;
+//   hier_shard_kernel   scale-out/in and shard-up/down.  Per (window, class): the node count of the
+//                       window's epoch = ceil(peak load of the epoch / largest profiled load of one node
+//                       at the reference configuration), at least one; then the layout (instances, TP)
+//                       of least energy at the reference frequency among those that fit the nodes' GPUs
+//                       and meet the SLO;
 //   hier_freq_kernel    scale-up/down: per tick the frequency of least power among those that meet the
 //                       SLO under the tick's load (the reference frequency, counted, if none does);
-//   hier_sum_kernel     energy of a (window, class) = its ticks' energies added in time order.
-// Table look-ups read global memory: the work is a few million look-ups per call.
+//   hier_sum_kernel     energy of a (window, class) = its ticks' energies added in time order; window
+//                       totals = the classes' energies added in class order.
+// The tables stay in global memory (they are a few hundred KB and live in L2; copying a class's tables
+// to LDS per block was measured to cost more than the look-ups it serves).  Two things matter instead:
+// threads of a block share the class, so that a wave's gathers fall into a few table rows, and the
+// frequency kernel takes its look-ups four at a time, level by level (capacity -> bucket -> grid points
+// and table values), so that a thread waits for three rounds of loads per four frequencies, not twelve.
 #include "dyn_hier.h"
+#include "dyn_device.h"
 
 namespace {
 
+constexpr int kShardWaves = 4;          // (window, class) cells per block of the shard kernel, one wave each
+constexpr int kFreqThreads = 256;
+constexpr int kFreqChunk = 4;           // look-ups a thread of the frequency kernel has in flight
+
 struct Looked { double pf, tb, pw; bool ov; };
 
-// Tables of class g, row (ti, f), at per-instance load `load / n`: bracket = largest i with grid[i] <= x
-// clamped to n_rho-2, linear in between; values at the last point when the load is beyond it.
+// Bracket of a clamped load fraction rc: largest grid index i <= n_rho-2 with grid[i] <= rc.
+// SINGLE: no bucket holds more than one interior grid point; the index is then the number of interior
+// points in lower buckets plus one comparison with the bucket's own point.
+template <bool SINGLE>
+__device__ __forceinline__ int bracket(const HierArgs& a, double rc) {
+  const double* grid = a.gridpack + 1;
+  const int b = min((int)(fmax(rc, 0.0) * a.bucket_scale), a.n_bucket);
+  if (SINGLE) return a.tstart[b] + (rc >= a.thr[b] ? 1 : 0);
+  int j = a.jstart[b];
+  while (j > 0 && grid[j] > rc) --j;
+  while (j < a.n_rho - 2 && grid[j + 1] <= rc) ++j;
+  return j;
+}
+
+// Linear interpolation in table row `row` (class, TP, frequency) between grid points j and j+1.
+__device__ __forceinline__ void interpolate(const HierArgs& a, size_t row, int j, double rc, Looked* r) {
+  const double* grid = a.gridpack + 1;
+  const double* rinv = a.gridpack + a.n_rho + 3;             // RN(1 / spacing)
+  const double g0 = grid[j], g1 = grid[j + 1];
+  const double t = div_by(rc - g0, g1 - g0, rinv[j]);
+  const double omt = 1.0 - t;
+  const double* v = a.tab + row * 3 * a.n_rho;
+  r->pf = omt * v[j] + t * v[j + 1];
+  r->tb = omt * v[a.n_rho + j] + t * v[a.n_rho + j + 1];
+  r->pw = omt * v[2 * a.n_rho + j] + t * v[2 * a.n_rho + j + 1];
+}
+
+// Row (g, ti, f) at per-instance load `load / n`; values at the last grid point when the load is beyond it.
+template <bool SINGLE>
 __device__ __forceinline__ Looked look_up(const HierArgs& a, int g, int ti, int f, double load, double n) {
-  const double ml = a.ml[((size_t)g * a.n_tp + ti) * a.n_f + f];
-  const double rho = load / (n * ml);
-  const double* rg = a.gridpack + 1;                         // gridpack = [-inf, grid, +inf, ...]
-  const double rho_max = rg[a.n_rho - 1];
+  const size_t row = ((size_t)g * a.n_tp + ti) * a.n_f + f;
+  const double rho = load / (n * a.ml[row]);
+  const double rho_max = a.gridpack[a.n_rho];
   Looked r;
   r.ov = rho > rho_max;
   const double rc = r.ov ? rho_max : rho;
-  int j = a.jstart[min((int)(fmax(rc, 0.0) * a.bucket_scale), a.n_bucket)];
-  while (j > 0 && rg[j] > rc) --j;
-  while (j < a.n_rho - 2 && rg[j + 1] <= rc) ++j;
-  const double t = (rc - rg[j]) / (rg[j + 1] - rg[j]);
-  const double omt = 1.0 - t;
-  const double* row = a.tab + (((size_t)g * a.n_tp + ti) * a.n_f + f) * 3 * a.n_rho;
-  r.pf = omt * row[j] + t * row[j + 1];
-  r.tb = omt * row[a.n_rho + j] + t * row[a.n_rho + j + 1];
-  r.pw = omt * row[2 * a.n_rho + j] + t * row[2 * a.n_rho + j + 1];
+  interpolate(a, row, bracket<SINGLE>(a, rc), rc, &r);
   return r;
 }
 
-__global__ __launch_bounds__(128) void hier_nodes_kernel(HierArgs a) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= a.n_epoch * a.G) return;
-  const int e = i / a.G, g = i - e * a.G;
-  double peak = 0.0;
-  const int w1 = min(a.n_window, (e + 1) * a.epoch_windows);
-  for (int w = e * a.epoch_windows; w < w1; ++w) {
-    const double l = a.rec_c[(size_t)w * a.G + g].load;
-    if (l > peak) peak = l;
-  }
-  const int inst = max(1, a.gpus_per_node / a.tp[a.tp_ref]);
-  const double rho_max = a.gridpack[a.n_rho];
-  const double ml_node = ((double)inst * a.ml[((size_t)g * a.n_tp + a.tp_ref) * a.n_f + a.f_ref]) * rho_max;
-  const double q = ceil(peak / ml_node);
-  a.nodes[i] = q < 1.0 ? 1 : (q > 2147483647.0 ? 2147483647 : (int32_t)q);
+__device__ __forceinline__ double wave_max_f64(double v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v = fmax(v, __shfl_xor(v, d, DYN_WAVE));
+  return v;
 }
 
 // One wave per (window, class); lanes stride the layouts; the lowest index wins equal energies.
-__global__ __launch_bounds__(256) void hier_shard_kernel(HierArgs a) {
+template <bool SINGLE>
+__global__ __launch_bounds__(kShardWaves* DYN_WAVE) void hier_shard_kernel(HierArgs a) {
   const int lane = threadIdx.x & (DYN_WAVE - 1);
-  const int64_t cell = (int64_t)blockIdx.x * (blockDim.x / DYN_WAVE) + threadIdx.x / DYN_WAVE;
+  const int64_t cell = (int64_t)blockIdx.x * kShardWaves + threadIdx.x / DYN_WAVE;
   if (cell >= (int64_t)a.n_window * a.G) return;
   const int w = (int)(cell / a.G), g = (int)(cell % a.G);
   const CellRec rec = a.rec_c[cell];
   if (lane == 0 && a.cstat_c[cell]) atomicOr(a.status, (uint32_t)a.cstat_c[cell]);
-  const int64_t budget = (int64_t)a.nodes[(size_t)(w / a.epoch_windows) * a.G + g] * a.gpus_per_node;
+  // scale-out/in: the epoch's peak load over the capacity of one node at the reference configuration
+  const int e = w / a.epoch_windows;
+  const int e0 = e * a.epoch_windows, e1 = min(a.n_window, e0 + a.epoch_windows);
+  double peak = 0.0;
+  for (int i = e0 + lane; i < e1; i += DYN_WAVE) peak = fmax(peak, a.rec_c[(size_t)i * a.G + g].load);
+  peak = wave_max_f64(peak);
+  const int inst = max(1, a.gpus_per_node / a.tp[a.tp_ref]);
+  const double ml_node = ((double)inst * a.ml[((size_t)g * a.n_tp + a.tp_ref) * a.n_f + a.f_ref]) * a.gridpack[a.n_rho];
+  const double q = ceil(peak / ml_node);
+  const int32_t nodes = q < 1.0 ? 1 : (q > 2147483647.0 ? 2147483647 : (int32_t)q);
+  if (w == e0 && lane == 0) a.nodes[(size_t)e * a.G + g] = nodes;
+  const int64_t budget = (int64_t)nodes * a.gpus_per_node;
+  // shard-up/down at the reference frequency
   const double slo_t = a.slo_ttft[g], slo_b = a.slo_tbt[g];
   double best_e = __builtin_inf();
   int best = 0x7FFFFFFF;
   for (int l = lane; l < a.n_layout; l += DYN_WAVE) {
     const int n = a.lay_n[l], ti = a.lay_tp[l];
     if ((int64_t)n * a.tp[ti] > budget) continue;
-    const Looked r = look_up(a, g, ti, a.f_ref, rec.load, (double)n);
+    const Looked r = look_up<SINGLE>(a, g, ti, a.f_ref, rec.load, (double)n);
     if (r.ov || rec.xp99 * r.pf > slo_t || r.tb * rec.nonempty > slo_b) continue;
-    const double e = ((double)n * r.pw) * a.window_s;
-    if (best == 0x7FFFFFFF || e < best_e) { best_e = e; best = l; }   // l ascends per lane
+    const double en = ((double)n * r.pw) * a.window_s;
+    if (best == 0x7FFFFFFF || en < best_e) { best_e = en; best = l; }   // l ascends per lane
   }
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) {
@@ -81,13 +112,14 @@ __global__ __launch_bounds__(256) void hier_shard_kernel(HierArgs a) {
   if (lane == 0) a.layout_sel[cell] = best == 0x7FFFFFFF ? -1 : best;
 }
 
-// One thread per (window, tick, class).
-__global__ __launch_bounds__(128) void hier_freq_kernel(HierArgs a) {
-  const int64_t f = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t fine_cells = (int64_t)a.n_window * a.n_tick * a.G;
-  if (f >= fine_cells) return;
-  const int g = (int)(f % a.G);
-  const int64_t wt = f / a.G;
+// One thread per (window, tick, class).  A block stays within one class: its threads then read the same
+// few table rows, and a wave's look-up touches a handful of cache lines instead of one per lane.
+template <bool SINGLE>
+__global__ __launch_bounds__(kFreqThreads) void hier_freq_kernel(HierArgs a) {
+  const int g = blockIdx.x % a.G;
+  const int64_t wt = (int64_t)(blockIdx.x / a.G) * kFreqThreads + threadIdx.x;   // window * n_tick + tick
+  if (wt >= (int64_t)a.n_window * a.n_tick) return;
+  const int64_t f = wt * a.G + g;
   const int w = (int)(wt / a.n_tick);
   if (a.cstat_f[f]) atomicOr(a.status, (uint32_t)a.cstat_f[f]);
   const int l = a.layout_sel[(size_t)w * a.G + g];
@@ -99,50 +131,95 @@ __global__ __launch_bounds__(128) void hier_freq_kernel(HierArgs a) {
   }
   const CellRec rec = a.rec_f[f];
   const int n = a.lay_n[l], ti = a.lay_tp[l];
+  const double nd = (double)n;
   const double slo_t = a.slo_ttft[g], slo_b = a.slo_tbt[g];
+  const double rho_max = a.gridpack[a.n_rho];
+  const size_t row0 = ((size_t)g * a.n_tp + ti) * a.n_f;
   int bf = -1;
-  double bp = __builtin_inf();
-  for (int fi = 0; fi < a.n_f; ++fi) {
-    const Looked r = look_up(a, g, ti, fi, rec.load, (double)n);
-    if (r.ov || rec.xp99 * r.pf > slo_t || r.tb * rec.nonempty > slo_b) continue;
-    if (bf < 0 || r.pw < bp) { bf = fi; bp = r.pw; }
+  double bp = __builtin_inf(), pw_ref = 0.0;
+  for (int f0 = 0; f0 < a.n_f; f0 += kFreqChunk) {
+    double rc[kFreqChunk];
+    bool ov[kFreqChunk];
+    int j[kFreqChunk];
+    Looked r[kFreqChunk];
+#pragma unroll
+    for (int c = 0; c < kFreqChunk; ++c) {                   // level 1: capacities
+      const int fi = min(f0 + c, a.n_f - 1);
+      const double rho = rec.load / (nd * a.ml[row0 + fi]);
+      ov[c] = rho > rho_max;
+      rc[c] = ov[c] ? rho_max : rho;
+    }
+#pragma unroll
+    for (int c = 0; c < kFreqChunk; ++c) j[c] = bracket<SINGLE>(a, rc[c]);   // level 2: bucket index
+#pragma unroll
+    for (int c = 0; c < kFreqChunk; ++c)                     // level 3: grid points and table values
+      interpolate(a, row0 + min(f0 + c, a.n_f - 1), j[c], rc[c], &r[c]);
+#pragma unroll
+    for (int c = 0; c < kFreqChunk; ++c) {                   // ascending frequency: the lowest wins equal powers
+      const int fi = f0 + c;
+      if (fi >= a.n_f) break;
+      if (fi == a.f_ref) pw_ref = r[c].pw;
+      if (ov[c] || rec.xp99 * r[c].pf > slo_t || r[c].tb * rec.nonempty > slo_b) continue;
+      if (bf < 0 || r[c].pw < bp) { bf = fi; bp = r[c].pw; }
+    }
   }
   uint8_t viol = 0;
   if (bf < 0) {                                              // nothing admissible: the reference frequency, counted
-    bp = look_up(a, g, ti, a.f_ref, rec.load, (double)n).pw;
+    bp = pw_ref;
     bf = a.f_ref;
     viol = 1;
   }
   a.f_sel[f] = bf;
-  a.tick_energy[f] = ((double)n * bp) * a.tick_s;
+  a.tick_energy[f] = (nd * bp) * a.tick_s;
   a.tick_viol[f] = viol;
 }
 
-__global__ __launch_bounds__(128) void hier_sum_kernel(HierArgs a) {
-  const int64_t cell = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (cell >= (int64_t)a.n_window * a.G) return;
-  const int w = (int)(cell / a.G), g = (int)(cell % a.G);
-  const bool has = a.layout_sel[cell] >= 0;
-  double e = 0.0;
-  int32_t v = 0;
-  for (int q = 0; q < a.n_tick; ++q) {                       // time order
-    const size_t f = ((size_t)w * a.n_tick + q) * a.G + g;
-    e += a.tick_energy[f];
-    v += a.tick_viol[f];
+// One block per window: thread g adds the ticks of (window, g) in time order; thread 0 then adds the
+// classes in class order.
+__global__ __launch_bounds__(64) void hier_sum_kernel(HierArgs a) {
+  extern __shared__ double s_e[];                            // [G] energy, NaN marks "no layout"
+  const int w = blockIdx.x;
+  for (int g = threadIdx.x; g < a.G; g += blockDim.x) {
+    const size_t cell = (size_t)w * a.G + g;
+    const bool has = a.layout_sel[cell] >= 0;
+    double e = 0.0;
+    int32_t v = 0;
+    for (int q = 0; q < a.n_tick; ++q) {                     // time order
+      const size_t f = ((size_t)w * a.n_tick + q) * a.G + g;
+      e += a.tick_energy[f];
+      v += a.tick_viol[f];
+    }
+    a.energy[cell] = has ? e : __builtin_inf();
+    a.violations[cell] = has ? v : 0;
+    s_e[g] = has ? e : __builtin_nan("");
   }
-  a.energy[cell] = has ? e : __builtin_inf();
-  a.violations[cell] = has ? v : 0;
-  a.ok[cell] = has ? 0 : -1;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double e = 0.0;
+    int32_t ninf = 0;
+    for (int g = 0; g < a.G; ++g) {
+      const double x = s_e[g];
+      if (x == x) e += x; else ++ninf;
+    }
+    a.win_energy[w] = e;
+    a.win_inf[w] = ninf;
+  }
 }
 
 }  // namespace
 
-hipError_t dyn_launch_hierarchy(const HierArgs& a, hipStream_t s) {
+hipError_t dyn_launch_hierarchy(const HierArgs& a, bool single_point, hipStream_t s) {
   const int64_t cells = (int64_t)a.n_window * a.G, fine = cells * a.n_tick;
+  const unsigned shard_blocks = (unsigned)((cells + kShardWaves - 1) / kShardWaves);
+  const unsigned freq_blocks = (unsigned)(((fine / a.G + kFreqThreads - 1) / kFreqThreads) * a.G);
   DynTimed timed(DYN_K_HIER, s);
-  hipLaunchKernelGGL(hier_nodes_kernel, dim3((unsigned)((a.n_epoch * a.G + 127) / 128)), dim3(128), 0, s, a);
-  hipLaunchKernelGGL(hier_shard_kernel, dim3((unsigned)((cells + 3) / 4)), dim3(256), 0, s, a);
-  hipLaunchKernelGGL(hier_freq_kernel, dim3((unsigned)((fine + 127) / 128)), dim3(128), 0, s, a);
-  hipLaunchKernelGGL(hier_sum_kernel, dim3((unsigned)((cells + 127) / 128)), dim3(128), 0, s, a);
+  if (single_point) {
+    hipLaunchKernelGGL(hier_shard_kernel<true>, dim3(shard_blocks), dim3(kShardWaves * DYN_WAVE), 0, s, a);
+    hipLaunchKernelGGL(hier_freq_kernel<true>, dim3(freq_blocks), dim3(kFreqThreads), 0, s, a);
+  } else {
+    hipLaunchKernelGGL(hier_shard_kernel<false>, dim3(shard_blocks), dim3(kShardWaves * DYN_WAVE), 0, s, a);
+    hipLaunchKernelGGL(hier_freq_kernel<false>, dim3(freq_blocks), dim3(kFreqThreads), 0, s, a);
+  }
+  hipLaunchKernelGGL(hier_sum_kernel, dim3((unsigned)a.n_window), dim3(64), (size_t)a.G * sizeof(double), s, a);
   return hipGetLastError();
 }

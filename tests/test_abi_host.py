@@ -27,7 +27,9 @@ def test_every_declared_symbol_is_exported(dyn):
     assert {"dyn_profile_load", "dyn_eval_space", "dyn_select_config", "dyn_trace_ingest", "dyn_profile_free",
             "dyn_cell_stats", "dyn_workspace_status", "dyn_last_error", "dyn_eval_space_workspace",
             "dyn_trace_ingest_workspace", "dyn_eval_select", "dyn_timing_enable", "dyn_timing_read",
-            "dyn_timing_reset", "dyn_eval_select_ticks", "dyn_eval_ticks_workspace"} <= set(names)
+            "dyn_timing_reset", "dyn_eval_select_ticks", "dyn_eval_ticks_workspace", "dyn_eval_select_mixed",
+            "dyn_mixed_workspace", "dyn_select_path", "dyn_select_path_workspace", "dyn_account", "dyn_account_workspace",
+            "dyn_hierarchy", "dyn_hierarchy_workspace"} <= set(names)
     lib = C.CDLL(dyn.lib_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -47,6 +49,9 @@ def test_workspace_sizes(dyn):
     assert c % 256 == 0 and c >= 36000 * 12 * (64 * 4 + 53)
     assert dyn.dyn_eval_ticks_workspace(1440, 17, 25, 576) == 0      # beyond DYN_TICK_LIMIT
     assert dyn.dyn_eval_ticks_workspace(1440, 0, 25, 576) == 0
+    h = dyn.dyn_hierarchy_workspace(1440, 12, 25, 53)
+    assert h % 256 == 0 and h >= 36000 * 13 * 53            # both aggregations: 53 bytes per window and per tick cell
+    assert dyn.dyn_hierarchy_workspace(1440, 12, 25, 0) == 0 and dyn.dyn_hierarchy_workspace(1440, 0, 25, 53) == 0
 
 
 def _prof():

@@ -137,6 +137,21 @@ def test_more_than_64_layouts_and_ties(dyn):
     assert (o["layout_sel"] < 9).all()
 
 
+def test_load_grid_with_points_closer_than_a_bucket(dyn):
+    """Grid points 1e-5 apart: several fall into one bucket of the load-axis index, which then only
+    narrows the bracket search instead of deciding it."""
+    prof, tr, edges, slo, lay_n, lay_tp, NW, T, tick = _random_case(6, 4, 5, 6000, 8)
+    rng = np.random.default_rng(77)
+    rg = np.asarray([0.0, 0.2, 0.41, 0.41001, 0.41002, 0.41003, 0.7, 0.95])
+    shape = prof["tbt_ms"].shape[:3] + (rg.size,)
+    prof = dict(prof, rho=rg, prefill_ms_per_tok=rng.uniform(0.02, 0.1, shape),
+                tbt_ms=np.sort(rng.uniform(10, 150, shape), axis=-1), power_w=np.sort(rng.uniform(100, 3000, shape), axis=-1))
+    g, coarse, fine = gpu_hier(dyn, prof, tr, edges, NW, T, tick, 3, 2, 4, 8, lay_n, lay_tp, slo)
+    o = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 3, 2, 4, 8, lay_n, lay_tp, slo)
+    assert_same(g, o, NW, 2)
+    assert (o["layout_sel"] >= 0).any()
+
+
 def test_tight_slo_counts_violations_and_marks_infeasible_windows(dyn):
     w = make(SPECS[0])
     P = w["profile"]
