@@ -682,6 +682,12 @@ int dynoracle_account(int32_t n_window, int32_t G, int32_t K, const int32_t* cfg
 //     requests) or leave the profiled load range, then take the least power (lowest frequency
 //     on ties); if none is left the tick runs at f_ref and is counted as a violation.
 //   Energy of a (window, class) = sum over its ticks in time order of (n x power) x tick_s.
+//   With a transition table (Section IV-B "Accounting for the overheads", Table VI): the shard
+//     controller weighs the energy a layout saves against the overhead of getting there.  Per
+//     class the layouts of all windows are then chosen together, as dynoracle_select_path does
+//     with cost = the layout's energy at f_ref over the window, feasible = fits the nodes' GPUs
+//     and meets the SLO, one candidate per layout; path_cost[g] = that class's total.  Without a
+//     table (NULL) every window takes its own least-energy layout and path_cost is not written.
 // Readings: the load predictor is exact (the epoch's true peak); at least one node per class;
 // a window whose class has no admissible layout has energy +inf and no frequencies (-1).
 // coarse_off / fine_off: offsets of the trace sorted by window*G + class and by
@@ -695,11 +701,12 @@ int dynoracle_hierarchy(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f,
                         int32_t epoch_windows, int32_t tp_ref, int32_t f_ref, int32_t gpus_per_node,
                         int32_t n_layout, const int32_t* lay_n, const int32_t* lay_tp,
                         const double* slo_ttft, const double* slo_tbt, int32_t pct_num, int32_t pct_den,
-                        int32_t* nodes, int32_t* layout_sel, int32_t* f_sel, double* energy_j,
-                        int32_t* violations) {
+                        const double* transition, int32_t* nodes, int32_t* layout_sel, int32_t* f_sel,
+                        double* energy_j, int32_t* violations, double* path_cost) {
   if (!tp || !fg || !rg || !PF || !TB || !PW || !ML || !coarse_off || !fine_off || !lay_n || !lay_tp ||
       !slo_ttft || !slo_tbt || !nodes || !layout_sel || !f_sel || !energy_j || !violations)
     return ORC_E_NULL;
+  if (transition && !path_cost) return ORC_E_NULL;
   if (n_req > 0 && (!in_c || !out_c || !in_f || !out_f)) return ORC_E_NULL;
   if (G < 1 || n_tp < 1 || n_f < 1 || n_rho < 2 || n_window < 1 || n_tick < 1 || epoch_windows < 1 ||
       n_layout < 1 || gpus_per_node < 1)
@@ -757,6 +764,10 @@ int dynoracle_hierarchy(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f,
       nodes[(int64_t)e * G + g] = q < 1.0 ? 1 : (q > 2147483647.0 ? 2147483647 : (int32_t)q);
     }
 
+  // shard-up/down: energy and admissibility of every layout at the reference frequency
+  const int64_t cells = (int64_t)n_window * G;
+  std::vector<double> lay_e((size_t)cells * n_layout, INF);
+  std::vector<uint8_t> lay_ok((size_t)cells * n_layout, 0);
   for (int w = 0; w < n_window; ++w)
     for (int g = 0; g < G; ++g) {
       const int64_t c = (int64_t)w * G + g;
@@ -774,9 +785,24 @@ int dynoracle_hierarchy(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f,
         const double bt = m > 0 ? tb : 0.0;
         if (ov || tt > slo_ttft[g] || bt > slo_tbt[g]) continue;
         const double E = ((double)lay_n[l] * pw) * window_s;
+        lay_e[(size_t)c * n_layout + l] = E;
+        lay_ok[(size_t)c * n_layout + l] = 1;
         if (best < 0 || E < best_e) { best = l; best_e = E; }
       }
       layout_sel[c] = best;
+    }
+  if (transition) {                         // the windows' layouts chosen together, one candidate per layout
+    std::vector<int32_t> ident(n_layout);
+    for (int l = 0; l < n_layout; ++l) ident[l] = l;
+    const int rc = dynoracle_select_path(n_window, G, n_layout, lay_e.data(), lay_ok.data(), n_layout, ident.data(),
+                                         transition, layout_sel, path_cost);
+    if (rc != ORC_OK) return rc;
+  }
+
+  for (int w = 0; w < n_window; ++w)
+    for (int g = 0; g < G; ++g) {
+      const int64_t c = (int64_t)w * G + g;
+      const int best = layout_sel[c];
       double E = 0.0;
       int32_t viol = 0;
       for (int q = 0; q < n_tick; ++q) {

@@ -850,6 +850,112 @@ def test_hierarchy_with_one_tick_and_one_frequency_is_the_window_level_selection
     assert (h["violations"] == 0).all() and (h["f_sel"].reshape(-1)[e["sel"] >= 0] == 0).all()
 
 
+def _hier_shard_space(prof, coarse, NW, W, lay_n, lay_tp, slo, f_ref):
+    """Energy and feasibility of every layout at the reference frequency, through oracle.evaluate."""
+    cfg = _configs([(int(n), int(t), float(prof["f_mhz"][f_ref])) for n, t in zip(lay_n, lay_tp)])
+    e = oracle.evaluate(prof, coarse, NW, W, cfg, slo, (99, 100))
+    return e["energy_j"], (e["flags"] & 1).astype(bool)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_hierarchy_with_a_zero_overhead_table_is_the_plain_hierarchy(seed):
+    prof, tr, edges, slo, lay_n, lay_tp, NW, T, tick = _hier_case(seed)
+    coarse = oracle.ingest(tr, edges, NW, T * tick); fine = oracle.ingest(tr, edges, NW * T, tick)
+    f_ref = prof["f_mhz"].size - 1
+    a = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 2, 2, f_ref, 8, lay_n, lay_tp, slo)
+    b = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 2, 2, f_ref, 8, lay_n, lay_tp, slo,
+                         transition=np.zeros((lay_n.size, lay_n.size)))
+    for k in ("nodes", "layout_sel", "f_sel", "violations", "energy_j"):
+        np.testing.assert_array_equal(a[k], b[k], err_msg=k)
+
+
+@pytest.mark.parametrize("seed", [2, 5, 6, 7])
+def test_hierarchy_shard_sequence_against_enumeration(seed):
+    """Section IV-B "Accounting for the overheads": every sequence of layouts over the windows is enumerated; the
+    least total of energies at the reference frequency plus transition overheads is the controller's."""
+    import itertools
+    prof, tr, edges, slo, lay_n, lay_tp, _, T, tick = _hier_case(seed, NW=4)
+    NW = 4
+    lay_n, lay_tp = lay_n[:5], lay_tp[:5]
+    L = lay_n.size
+    rng = np.random.default_rng(900 + seed)
+    coarse = oracle.ingest(tr, edges, NW, T * tick); fine = oracle.ingest(tr, edges, NW * T, tick)
+    f_ref = prof["f_mhz"].size - 1
+    E, ok = _hier_shard_space(prof, coarse, NW, T * tick, lay_n, lay_tp, slo, f_ref)
+    scale = np.median(E[ok]) if ok.any() else 1.0
+    trans = rng.uniform(0, 1.5, (L, L)) * scale
+    np.fill_diagonal(trans, 0.0)
+    h = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 2, 2, f_ref, 10 ** 6, lay_n, lay_tp, slo, transition=trans)
+    plain = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 2, 2, f_ref, 10 ** 6, lay_n, lay_tp, slo)
+    assert (h["layout_sel"] != plain["layout_sel"]).any()       # the overheads change the outcome on these seeds
+    G = 2
+    for g in range(G):
+        feas_w = [w for w in range(NW) if ok[w * G + g].any()]
+        assert [w for w in range(NW) if h["layout_sel"][w * G + g] >= 0] == feas_w
+        best = None
+        for seq in itertools.product(range(L), repeat=len(feas_w)):
+            if not all(ok[w * G + g, l] for w, l in zip(feas_w, seq)):
+                continue
+            total, V, prev_w = 0.0, None, None
+            for w, l in zip(feas_w, seq):
+                if prev_w is not None and w == prev_w + 1:
+                    V = (V + trans[prev_l, l]) + E[w * G + g, l]
+                else:                                       # a new run of feasible windows
+                    if V is not None:
+                        total += V
+                    V = E[w * G + g, l]
+                prev_w, prev_l = w, l
+            if V is not None:
+                total += V
+            if best is None or total < best:
+                best = total
+        assert (best if best is not None else 0.0) == h["path_cost"][g]
+        # the controller's own sequence reaches that total
+        seq = [h["layout_sel"][w * G + g] for w in feas_w]
+        total, V, prev_w = 0.0, None, None
+        for w, l in zip(feas_w, seq):
+            if prev_w is not None and w == prev_w + 1:
+                V = (V + trans[prev_l, l]) + E[w * G + g, l]
+            else:
+                if V is not None:
+                    total += V
+                V = E[w * G + g, l]
+            prev_w, prev_l = w, l
+        if V is not None:
+            total += V
+        assert total == h["path_cost"][g]
+
+
+def test_hierarchy_with_prohibitive_overheads_keeps_one_layout_per_run():
+    prof, tr, edges, slo, lay_n, lay_tp, NW, T, tick = _hier_case(2, NW=8, R=900)
+    coarse = oracle.ingest(tr, edges, NW, T * tick); fine = oracle.ingest(tr, edges, NW * T, tick)
+    f_ref = prof["f_mhz"].size - 1
+    L = lay_n.size
+    trans = np.full((L, L), 1e30); np.fill_diagonal(trans, 0.0)
+    # identical layouts listed twice would be a free change of index: make the list unique first
+    _, first = np.unique(np.stack([lay_n, lay_tp]), axis=1, return_index=True)
+    keep = np.sort(first)
+    lay_n, lay_tp = lay_n[keep], lay_tp[keep]
+    trans = trans[np.ix_(keep, keep)]
+    h = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 2, 2, f_ref, 10 ** 6, lay_n, lay_tp, slo, transition=trans)
+    E, ok = _hier_shard_space(prof, coarse, NW, T * tick, lay_n, lay_tp, slo, f_ref)
+    sel = h["layout_sel"].reshape(NW, 2)
+    for g in range(2):
+        w = 0
+        while w < NW:
+            if sel[w, g] < 0:
+                w += 1
+                continue
+            w1 = w
+            while w1 < NW and sel[w1, g] >= 0:
+                w1 += 1
+            common = [l for l in range(lay_n.size) if all(ok[ww * 2 + g, l] for ww in range(w, w1))]
+            if common:                                      # some layout serves the whole run: it is kept throughout
+                assert len(set(sel[w:w1, g].tolist())) == 1
+            w = w1
+    assert (sel >= 0).any()
+
+
 # ----------------------------------------------------------- planted mistakes are caught
 def test_pins_catch_planted_mistakes():
     """Sanity of the pins themselves: perturbing the inputs the way a typical slip would
