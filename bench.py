@@ -57,12 +57,12 @@ def cpu_baseline(w, n_sample_windows, ticks=0, mixed=None, path=None, hier=None)
     sub = {k: v[:hi] for k, v in tr.items()}
     k = w["configs"]["n_inst"].size
     if hier:
-        T, epoch, tp_ref, f_ref, gpn, lay_n, lay_tp, k = hier
+        T, epoch, tp_ref, f_ref, gpn, lay_n, lay_tp, trans, k = hier
         st = oracle.ingest(sub, w["edges"], n_sample_windows, w["window_s"])
         fine = oracle.ingest(sub, w["edges"], n_sample_windows * T, w["window_s"] / T)
         t0 = time.perf_counter()
         oracle.hierarchy(w["profile"], st, fine, n_sample_windows, T, w["window_s"] / T, epoch, tp_ref, f_ref, gpn, lay_n, lay_tp,
-                         w["slos"], w["pct"])
+                         w["slos"], w["pct"], transition=trans)
     elif mixed:
         n_share, n_max, budget, k = mixed
         st = oracle.ingest(sub, w["edges"], n_sample_windows, w["window_s"])
@@ -113,6 +113,9 @@ def main():
                          "--epoch-windows windows, 8-GPU nodes, layouts = the (instances, TP) pairs of the workload's "
                          "configurations, reference = the largest TP at the highest frequency")
     ap.add_argument("--epoch-windows", type=int, default=6)
+    ap.add_argument("--overheads", action="store_true",
+                    help="with --hierarchy: the shard controller weighs re-sharding overheads (2 %% of the median window "
+                         "energy per GPU of difference between two layouts)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events (roofline.achieved is then null)")
@@ -198,10 +201,16 @@ def main():
         ws = torch.empty(dyn.dyn_hierarchy_workspace(NW, T, G, lay_n.size), dtype=torch.uint8, device="cuda")
         hout, _ = dyn.dyn_hierarchy(prof, coarse, (ins, outs, off), NW, T, len_s, *hier_args[1:], w["slos"], w["pct"], workspace=ws)
         hout["window_energy_j"], hout["window_infeasible"] = sel["window_energy_j"], sel["window_infeasible"]
+        hier_trans = None
+        if args.overheads:
+            e0 = hout["energy_j"][torch.isfinite(hout["energy_j"])]
+            gpus = lay_n.astype(np.int64) * w["profile"]["tp"][lay_tp]
+            hier_trans = 0.02 * float(e0.median()) * np.abs(gpus[:, None] - gpus[None, :]).astype(np.float64)
+            hout["path_cost"] = torch.empty(G, dtype=torch.float64, device="cuda")
 
         def step():
             dyn.dyn_hierarchy(prof, coarse, (ins, outs, off), NW, T, len_s, *hier_args[1:], w["slos"], w["pct"], out=hout,
-                              workspace=ws)
+                              workspace=ws, transition_j=hier_trans)
     elif args.path:
         assert not args.ticks and not args.mixed, "--path, --mixed and --ticks are separate modes"
         cfgs = w["configs"]
@@ -352,7 +361,7 @@ def main():
         "config": {"workload": f"configs[{args.config}] {spec.name}: {R} requests, {NW} windows x {G} classes = "
                                f"{cells} cells, {K} configurations", "requests": R, "cells": cells, "configs": K,
                    "ticks_per_window": args.ticks or args.hierarchy, "mixed_shares": args.mixed,
-                   "entry_points": "dyn_hierarchy" if args.hierarchy else "dyn_eval_space+dyn_select_path" if args.path else "dyn_eval_select_mixed" if args.mixed else "dyn_eval_select_ticks" if args.ticks else
+                   "entry_points": ("dyn_hierarchy+overheads" if args.overheads else "dyn_hierarchy") if args.hierarchy else "dyn_eval_space+dyn_select_path" if args.path else "dyn_eval_select_mixed" if args.mixed else "dyn_eval_select_ticks" if args.ticks else
                                    "dyn_eval_space+dyn_select_config" if args.unfused else "dyn_eval_select"},
         "roofline": roofline,
         "kernel_ms": ktime, "ms_per_step_with_kernel_events": ms_per_step_events,
@@ -367,7 +376,7 @@ def main():
         if args.hierarchy:
             nwin = args.cpu_windows or NW
         out["cpu_baseline"] = cpu_baseline(w, nwin, args.ticks, mixed, (lay, trans) if args.path else None,
-                                           hier_args + (K,) if args.hierarchy else None)
+                                           hier_args + (hier_trans, K) if args.hierarchy else None)
         out["cpu_baseline"]["host_cores"] = os.cpu_count()
     prof.free()
     print(json.dumps(out))

@@ -368,6 +368,14 @@ int dyn_account(dyn_profile* profile, const int32_t* sel, const double* window_e
  *     leave the profiled load range, then take the least power (lowest frequency on ties);
  *     if none is left the tick runs at f_ref and counts as a violation.
  *   Energy of a (window, class) = sum over its ticks in time order of (n * power) * tick_s.
+ *   With controllers->transition_j (Section IV-B "Accounting for the overheads", Table VI;
+ *     HOST [n_layout][n_layout] joules, from -> to, finite and >= 0): the shard controller
+ *     chooses the layouts of all windows of a class together, as dyn_select_path does with one
+ *     candidate per layout, cost = the layout's energy at f_ref over the window and feasible =
+ *     fits the nodes' GPUs and meets the SLO; out->path_cost[g] (DEVICE [G], required then) =
+ *     that class's total of energies and overheads.  Where several sequences reach the least
+ *     total any one of them is returned.  Limits as for dyn_select_path with K = n_layout.
+ *     NULL: every window takes its own least-energy layout and path_cost is not written.
  * `coarse` is the trace sorted by window (n_window windows of n_tick * tick_s seconds), `fine`
  * the same requests sorted by tick (n_window * n_tick windows of tick_s seconds), both as
  * dyn_trace_ingest returns them.  lay_n / lay_tp_index HOST [n_layout].  Outputs DEVICE.
@@ -380,6 +388,7 @@ typedef struct {
   int32_t n_layout;
   const int32_t* lay_n;
   const int32_t* lay_tp_index;
+  const double* transition_j; /* HOST [n_layout][n_layout] or NULL */
 } dyn_controllers;
 typedef struct {
   int32_t* nodes;             /* [n_epoch][G], n_epoch = ceil(n_window / epoch_windows)    */
@@ -389,6 +398,7 @@ typedef struct {
   int32_t* violations;        /* [n_window*G] ticks that had to run at f_ref               */
   double* window_energy_j;    /* [n_window] */
   int32_t* window_infeasible; /* [n_window] */
+  double* path_cost;          /* [G], only with transition_j; may be NULL without */
 } dyn_hierarchy_out;
 size_t dyn_hierarchy_workspace(int32_t n_window, int32_t n_tick, int32_t n_class, int32_t n_layout);
 int dyn_hierarchy(dyn_profile* profile, const dyn_trace_view* coarse, const dyn_trace_view* fine,

@@ -881,7 +881,7 @@ namespace {
 struct HierWs {
   EvalWs coarse;                 // header .. cstat of the window-level aggregation (first: its header is the workspace's)
   size_t fine_base; EvalWs fine; // the tick-level aggregation, offsets relative to fine_base
-  size_t tp, lay_n, lay_tp, tick_energy, tick_viol, total;
+  size_t tp, lay_n, lay_tp, tick_energy, tick_viol, lay_energy, lay_flags, sel_energy, path, total;
 };
 HierWs hier_ws_layout(int64_t cells, int32_t n_tick, int32_t n_tp, int32_t n_layout) {
   HierWs w;
@@ -895,6 +895,11 @@ HierWs hier_ws_layout(int64_t cells, int32_t n_tick, int32_t n_tp, int32_t n_lay
   w.lay_tp = off; off += align256((size_t)n_layout * 4);
   w.tick_energy = off; off += align256(c * n_tick * 8);
   w.tick_viol = off; off += align256(c * n_tick);
+  // only used with a transition table: the layouts' space and the sequence selection's own workspace
+  w.lay_energy = off; off += align256(c * n_layout * 8);
+  w.lay_flags = off; off += align256(c * n_layout);
+  w.sel_energy = off; off += align256(c * 8);
+  w.path = off;
   w.total = off;
   return w;
 }
@@ -902,7 +907,8 @@ HierWs hier_ws_layout(int64_t cells, int32_t n_tick, int32_t n_tp, int32_t n_lay
 
 size_t dyn_hierarchy_workspace(int32_t n_window, int32_t n_tick, int32_t n_class, int32_t n_layout) {
   if (n_window < 1 || n_tick < 1 || n_class < 1 || n_layout < 1) return 0;
-  return hier_ws_layout((int64_t)n_window * n_class, n_tick, 64, n_layout).total;
+  return hier_ws_layout((int64_t)n_window * n_class, n_tick, 64, n_layout).total +
+         path_ws_layout(n_window, n_class, n_layout, n_layout).total;
 }
 
 int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view* tf, int32_t n_tick, const dyn_controllers* c,
@@ -926,11 +932,34 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
   int rc;
   if ((rc = check_device(p)) != DYN_OK) return rc;
   const HierWs w = hier_ws_layout(cells, n_tick, 64, c->n_layout);
-  if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) { dyn_set_error("workspace misaligned or too small (%zu < %zu)", workspace_bytes, w.total); return DYN_E_WORKSPACE; }
+  const PathWs pw = path_ws_layout(tc->n_window, p->G, c->n_layout, c->n_layout);
+  if (c->transition_j) {
+    if (!out->path_cost) { dyn_set_error("out->path_cost is NULL"); return DYN_E_NULL; }
+    if (c->n_layout > DYN_PATH_MAX_CONFIGS || c->n_layout > 255 || dyn_path_lds(c->n_layout, c->n_layout) > DYN_LDS_BUDGET) {
+      dyn_set_error("n_layout=%d: the sequence selection's per-class state does not fit in LDS", c->n_layout);
+      return DYN_E_SHAPE;
+    }
+    for (int64_t i = 0; i < (int64_t)c->n_layout * c->n_layout; ++i) {
+      if (!isfinite(c->transition_j[i])) { dyn_set_error("transition_j[%lld] is not finite", (long long)i); return DYN_E_NOTFINITE; }
+      if (c->transition_j[i] < 0.0) { dyn_set_error("transition_j[%lld] < 0", (long long)i); return DYN_E_RANGE; }
+    }
+  }
+  if (((uintptr_t)workspace & 255) || workspace_bytes < w.total + pw.total) { dyn_set_error("workspace misaligned or too small (%zu < %zu)", workspace_bytes, w.total + pw.total); return DYN_E_WORKSPACE; }
   hipStream_t s = (hipStream_t)hip_stream;
   if ((rc = prepare_objective(p, o, s)) != DYN_OK) return rc;
   char* base = (char*)workspace;
   char* fb = base + w.fine_base;
+  char* pb = base + w.path;
+  if (c->transition_j) {        // one candidate per layout: the sorted order is the identity
+    std::vector<int32_t> ident(c->n_layout + 1);
+    for (int l = 0; l <= c->n_layout; ++l) ident[l] = l;
+    if (!hip_ok(hipMemcpyAsync(pb + pw.layout, ident.data(), (size_t)c->n_layout * 4, hipMemcpyHostToDevice, s), "copy") ||
+        !hip_ok(hipMemcpyAsync(pb + pw.order, ident.data(), (size_t)c->n_layout * 4, hipMemcpyHostToDevice, s), "copy") ||
+        !hip_ok(hipMemcpyAsync(pb + pw.seg, ident.data(), ((size_t)c->n_layout + 1) * 4, hipMemcpyHostToDevice, s), "copy") ||
+        !hip_ok(hipMemcpyAsync(pb + pw.transition, c->transition_j, (size_t)c->n_layout * c->n_layout * 8, hipMemcpyHostToDevice, s), "copy") ||
+        !hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize"))   // `ident` lives until here
+      return DYN_E_DEVICE;
+  }
   if (!hip_ok(hipMemcpyAsync(base + w.tp, p->tp.data(), (size_t)p->n_tp * 4, hipMemcpyHostToDevice, s), "copy") ||
       !hip_ok(hipMemcpyAsync(base + w.lay_n, c->lay_n, (size_t)c->n_layout * 4, hipMemcpyHostToDevice, s), "copy") ||
       !hip_ok(hipMemcpyAsync(base + w.lay_tp, c->lay_tp_index, (size_t)c->n_layout * 4, hipMemcpyHostToDevice, s), "copy") ||
@@ -957,8 +986,21 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
   a.n_layout = c->n_layout; a.lay_n = (const int32_t*)(base + w.lay_n); a.lay_tp = (const int32_t*)(base + w.lay_tp);
   a.nodes = out->nodes; a.layout_sel = out->layout_sel; a.f_sel = out->f_sel; a.energy = out->energy_j; a.violations = out->violations;
   a.win_energy = out->window_energy_j; a.win_inf = out->window_infeasible;
+  a.lay_energy = c->transition_j ? (double*)(base + w.lay_energy) : nullptr;
+  a.lay_flags = c->transition_j ? (uint8_t*)(base + w.lay_flags) : nullptr;
   a.tick_energy = (double*)(base + w.tick_energy); a.tick_viol = (uint8_t*)(base + w.tick_viol);
-  if (!hip_ok(dyn_launch_hierarchy(a, p->single_point, s), "hierarchy launch")) return DYN_E_DEVICE;
+  if (!hip_ok(dyn_launch_hier_shard(a, p->single_point, s), "hierarchy launch")) return DYN_E_DEVICE;
+  if (c->transition_j) {        // the windows' layouts chosen together; overwrites layout_sel
+    PathArgs pa;
+    pa.energy = a.lay_energy; pa.flags = a.lay_flags; pa.cfg = nullptr; pa.K = c->n_layout; pa.pw0 = p->d_pw0;
+    pa.G = p->G; pa.n_tp_f = p->n_tp * p->n_f; pa.n_window = tc->n_window; pa.window_s = window_s; pa.idle_w = 0.0;
+    pa.n_layout = c->n_layout; pa.layout = (const int32_t*)(pb + pw.layout); pa.transition = (const double*)(pb + pw.transition);
+    pa.order = (const int32_t*)(pb + pw.order); pa.seg_start = (const int32_t*)(pb + pw.seg);
+    pa.pred = (int32_t*)(pb + pw.pred); pa.kend = (int32_t*)(pb + pw.kend);
+    pa.sel = out->layout_sel; pa.sel_energy = (double*)(base + w.sel_energy); pa.path_cost = out->path_cost;
+    if (!hip_ok(dyn_launch_path(pa, s), "path launch")) return DYN_E_DEVICE;
+  }
+  if (!hip_ok(dyn_launch_hier_ticks(a, p->single_point, s), "hierarchy launch")) return DYN_E_DEVICE;
   return DYN_OK;
 }
 

@@ -24,9 +24,14 @@ struct HierArgs {
   // outputs and scratch
   int32_t* nodes; int32_t* layout_sel; int32_t* f_sel; double* energy; int32_t* violations;
   double* win_energy; int32_t* win_inf;   // [n_window] totals over the classes
+  double* lay_energy;           // workspace [cells][n_layout] or NULL: every layout's energy at the reference frequency
+  uint8_t* lay_flags;           // workspace [cells][n_layout]: DYN_F_FEASIBLE where the layout fits and meets the SLO
   double* tick_energy;          // workspace [fine cells]
   uint8_t* tick_viol;           // workspace [fine cells]
 };
-hipError_t dyn_launch_hierarchy(const HierArgs& a, bool single_point, hipStream_t s);
+// window level: node counts, per-window layouts and (lay_energy != NULL) every layout's energy and admissibility
+hipError_t dyn_launch_hier_shard(const HierArgs& a, bool single_point, hipStream_t s);
+// tick level: frequencies under layout_sel, energies, window totals
+hipError_t dyn_launch_hier_ticks(const HierArgs& a, bool single_point, hipStream_t s);
 
 #endif  // DYN_HIER_H_

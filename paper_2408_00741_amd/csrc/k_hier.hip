@@ -97,11 +97,18 @@ __global__ __launch_bounds__(kShardWaves* DYN_WAVE) void hier_shard_kernel(HierA
   int best = 0x7FFFFFFF;
   for (int l = lane; l < a.n_layout; l += DYN_WAVE) {
     const int n = a.lay_n[l], ti = a.lay_tp[l];
-    if ((int64_t)n * a.tp[ti] > budget) continue;
-    const Looked r = look_up<SINGLE>(a, g, ti, a.f_ref, rec.load, (double)n);
-    if (r.ov || rec.xp99 * r.pf > slo_t || r.tb * rec.nonempty > slo_b) continue;
-    const double en = ((double)n * r.pw) * a.window_s;
-    if (best == 0x7FFFFFFF || en < best_e) { best_e = en; best = l; }   // l ascends per lane
+    bool ok = (int64_t)n * a.tp[ti] <= budget;
+    double en = __builtin_inf();
+    if (ok) {
+      const Looked r = look_up<SINGLE>(a, g, ti, a.f_ref, rec.load, (double)n);
+      ok = !(r.ov || rec.xp99 * r.pf > slo_t || r.tb * rec.nonempty > slo_b);
+      en = ((double)n * r.pw) * a.window_s;
+    }
+    if (a.lay_energy) {                                      // the sequence selection takes it from here
+      a.lay_energy[(size_t)cell * a.n_layout + l] = en;
+      a.lay_flags[(size_t)cell * a.n_layout + l] = ok ? (uint8_t)DYN_F_FEASIBLE : (uint8_t)0;
+    }
+    if (ok && (best == 0x7FFFFFFF || en < best_e)) { best_e = en; best = l; }   // l ascends per lane
   }
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) {
@@ -208,18 +215,21 @@ __global__ __launch_bounds__(64) void hier_sum_kernel(HierArgs a) {
 
 }  // namespace
 
-hipError_t dyn_launch_hierarchy(const HierArgs& a, bool single_point, hipStream_t s) {
-  const int64_t cells = (int64_t)a.n_window * a.G, fine = cells * a.n_tick;
+hipError_t dyn_launch_hier_shard(const HierArgs& a, bool single_point, hipStream_t s) {
+  const int64_t cells = (int64_t)a.n_window * a.G;
   const unsigned shard_blocks = (unsigned)((cells + kShardWaves - 1) / kShardWaves);
-  const unsigned freq_blocks = (unsigned)(((fine / a.G + kFreqThreads - 1) / kFreqThreads) * a.G);
   DynTimed timed(DYN_K_HIER, s);
-  if (single_point) {
-    hipLaunchKernelGGL(hier_shard_kernel<true>, dim3(shard_blocks), dim3(kShardWaves * DYN_WAVE), 0, s, a);
-    hipLaunchKernelGGL(hier_freq_kernel<true>, dim3(freq_blocks), dim3(kFreqThreads), 0, s, a);
-  } else {
-    hipLaunchKernelGGL(hier_shard_kernel<false>, dim3(shard_blocks), dim3(kShardWaves * DYN_WAVE), 0, s, a);
-    hipLaunchKernelGGL(hier_freq_kernel<false>, dim3(freq_blocks), dim3(kFreqThreads), 0, s, a);
-  }
+  if (single_point) hipLaunchKernelGGL(hier_shard_kernel<true>, dim3(shard_blocks), dim3(kShardWaves * DYN_WAVE), 0, s, a);
+  else hipLaunchKernelGGL(hier_shard_kernel<false>, dim3(shard_blocks), dim3(kShardWaves * DYN_WAVE), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t dyn_launch_hier_ticks(const HierArgs& a, bool single_point, hipStream_t s) {
+  const int64_t ticks = (int64_t)a.n_window * a.n_tick;
+  const unsigned freq_blocks = (unsigned)(((ticks + kFreqThreads - 1) / kFreqThreads) * a.G);
+  DynTimed timed(DYN_K_HIER, s);
+  if (single_point) hipLaunchKernelGGL(hier_freq_kernel<true>, dim3(freq_blocks), dim3(kFreqThreads), 0, s, a);
+  else hipLaunchKernelGGL(hier_freq_kernel<false>, dim3(freq_blocks), dim3(kFreqThreads), 0, s, a);
   hipLaunchKernelGGL(hier_sum_kernel, dim3((unsigned)a.n_window), dim3(64), (size_t)a.G * sizeof(double), s, a);
   return hipGetLastError();
 }

@@ -49,9 +49,9 @@ def test_workspace_sizes(dyn):
     assert c % 256 == 0 and c >= 36000 * 12 * (64 * 4 + 53)
     assert dyn.dyn_eval_ticks_workspace(1440, 17, 25, 576) == 0      # beyond DYN_TICK_LIMIT
     assert dyn.dyn_eval_ticks_workspace(1440, 0, 25, 576) == 0
-    h = dyn.dyn_hierarchy_workspace(1440, 12, 25, 53)
+    h = dyn.dyn_hierarchy_workspace(1440, 12, 25, 48)
     assert h % 256 == 0 and h >= 36000 * 13 * 53            # both aggregations: 53 bytes per window and per tick cell
-    assert dyn.dyn_hierarchy_workspace(1440, 12, 25, 0) == 0 and dyn.dyn_hierarchy_workspace(1440, 0, 25, 53) == 0
+    assert dyn.dyn_hierarchy_workspace(1440, 12, 25, 0) == 0 and dyn.dyn_hierarchy_workspace(1440, 0, 25, 48) == 0
 
 
 def _prof():

@@ -32,14 +32,14 @@ def _layouts(w, n_max):
 
 
 def gpu_hier(dyn, profile, tr, edges, n_window, n_tick, tick_s, epoch_windows, tp_ref, f_ref, gpn, lay_n, lay_tp, slos,
-             pct=(99, 100)):
+             pct=(99, 100), transition=None):
     d = [_dev(tr[k]) for k in ("t_s", "in_tok", "out_tok", "model")]
     ci, co, coff, ws1 = dyn.dyn_trace_ingest(*d, edges, n_window, tick_s * n_tick)
     fi, fo, foff, ws2 = dyn.dyn_trace_ingest(*d, edges, n_window * n_tick, tick_s)
     assert dyn.dyn_workspace_status(ws1) == 0 and dyn.dyn_workspace_status(ws2) == 0
     prof = dyn.dyn_profile_load(profile)
     out, ws = dyn.dyn_hierarchy(prof, (ci, co, coff), (fi, fo, foff), n_window, n_tick, tick_s, epoch_windows, tp_ref, f_ref,
-                                gpn, lay_n, lay_tp, slos, pct)
+                                gpn, lay_n, lay_tp, slos, pct, transition_j=transition)
     status = dyn.dyn_workspace_status(ws)
     torch.cuda.synchronize()
     r = {k: v.cpu().numpy() for k, v in out.items()}
@@ -92,6 +92,56 @@ def test_hierarchy_matches_oracle(dyn, name):
     assert (o["layout_sel"] >= 0).any()
     # the case exercises the lower controller: some tick runs below the reference frequency
     assert (o["f_sel"][o["f_sel"] >= 0] < f_ref).any()
+
+
+def _gpu_overheads(w, lay_n, lay_tp, unit_j):
+    """Overhead table in the shape of the paper's Table VI: proportional to the GPUs whose weights move."""
+    gpus = lay_n.astype(np.int64) * w["profile"]["tp"][lay_tp]
+    return unit_j * np.abs(gpus[:, None] - gpus[None, :]).astype(np.float64)
+
+
+@pytest.mark.parametrize("name", ["cfg0-T12", "cfg1-60k-T12", "cfg2-300k-T12", "cfg4-250k-T6", "cfg2-day-T12"])
+def test_hierarchy_with_overheads_matches_oracle(dyn, name):
+    spec, T, epoch, n_max, gpn = CASES[name]
+    w = make(spec)
+    lay_n, lay_tp = _layouts(w, min(n_max, 16))           # the sequence selection keeps n_layout^2 overheads in LDS
+    P = w["profile"]
+    tp_ref, f_ref = P["tp"].size - 1, P["f_mhz"].size - 1
+    tick = w["window_s"] / T
+    args = (P, w["trace"], w["edges"], w["n_window"], T, tick, epoch, tp_ref, f_ref, gpn, lay_n, lay_tp, w["slos"], w["pct"])
+    plain, coarse, fine = gpu_hier(dyn, *args)
+    e = plain["energy_j"][np.isfinite(plain["energy_j"])]
+    trans = _gpu_overheads(w, lay_n, lay_tp, 0.02 * float(np.median(e)))
+    g, _, _ = gpu_hier(dyn, *args, transition=trans)
+    o = oracle.hierarchy(P, coarse, fine, w["n_window"], T, tick, epoch, tp_ref, f_ref, gpn, lay_n, lay_tp, w["slos"], w["pct"],
+                         transition=trans)
+    np.testing.assert_array_equal(g["path_cost"], o["path_cost"])
+    assert_same(g, o, w["n_window"], w["n_class"])
+    if w["n_window"] > 1:
+        changes = lambda a: int((np.diff(a["layout_sel"].reshape(w["n_window"], -1), axis=0) != 0).sum())
+        assert changes(g) < changes(plain)                # the overheads do remove layout changes
+    # a zero table is the plain hierarchy
+    z, _, _ = gpu_hier(dyn, *args, transition=np.zeros_like(trans))
+    for k in INT_KEYS + ("energy_j", "window_energy_j", "window_infeasible"):
+        np.testing.assert_array_equal(z[k], plain[k], err_msg=k)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4, 6, 8])
+def test_random_overheads(dyn, seed):
+    """Load that rises and falls over 16 windows (layouts change, some windows have no admissible layout, so the
+    sequences have gaps) and a random, asymmetric overhead table."""
+    prof, tr, edges, slo, lay_n, lay_tp, NW, T, tick = _random_case(seed, 3, 3, 6000, 16)
+    rng = np.random.default_rng(900 + seed)
+    tr = dict(tr, t_s=NW * T * tick * rng.beta(2.0, 3.0, tr["t_s"].size))
+    slo = {k: v * 1.6 for k, v in slo.items()}
+    plain, coarse, fine = gpu_hier(dyn, prof, tr, edges, NW, T, tick, 4, 2, 2, 8, lay_n, lay_tp, slo)
+    fin = plain["energy_j"][np.isfinite(plain["energy_j"])]
+    trans = rng.uniform(0, 0.3, (lay_n.size, lay_n.size)) * np.median(fin); np.fill_diagonal(trans, 0.0)
+    g, _, _ = gpu_hier(dyn, prof, tr, edges, NW, T, tick, 4, 2, 2, 8, lay_n, lay_tp, slo, transition=trans)
+    o = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 4, 2, 2, 8, lay_n, lay_tp, slo, transition=trans)
+    np.testing.assert_array_equal(g["path_cost"], o["path_cost"])
+    assert_same(g, o, NW, 2)
+    assert (g["layout_sel"] != plain["layout_sel"]).any() and (g["layout_sel"] < 0).any()
 
 
 def _random_case(seed, n_tick, n_f, R, NW):
@@ -199,6 +249,17 @@ def test_argument_errors(dyn):
     ws = torch.empty(256, dtype=torch.uint8, device="cuda")
     with pytest.raises(dyn.DynError):
         dyn.dyn_hierarchy(prof, c, f, **args, workspace=ws)
+    many_n = np.tile(lay_n, 40); many_tp = np.tile(lay_tp, 40)         # 240 layouts: fine without overheads, too many with
+    dyn.dyn_hierarchy(prof, c, f, **{**args, "lay_n": many_n, "lay_tp_index": many_tp})
+    with pytest.raises(dyn.DynError):
+        dyn.dyn_hierarchy(prof, c, f, **{**args, "lay_n": many_n, "lay_tp_index": many_tp},
+                          transition_j=np.zeros((many_n.size, many_n.size)))
+    bad_t = np.zeros((lay_n.size, lay_n.size)); bad_t[0, 1] = -1.0
+    with pytest.raises(dyn.DynError):
+        dyn.dyn_hierarchy(prof, c, f, **args, transition_j=bad_t)
+    bad_t[0, 1] = np.nan
+    with pytest.raises(dyn.DynError):
+        dyn.dyn_hierarchy(prof, c, f, **args, transition_j=bad_t)
     out, _ = dyn.dyn_hierarchy(prof, c, f, **args)
     torch.cuda.synchronize()
     assert out["nodes"].min().item() >= 1
