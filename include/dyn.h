@@ -297,8 +297,9 @@ int dyn_eval_select_mixed(dyn_profile* profile, const dyn_trace_view* trace, con
  * path_cost[g] adds the sequences' totals in time order from 0.  Where several sequences
  * reach the least total any one of them is returned.
  * `layout` HOST [K] in [0, n_layout); `transition_j` HOST [n_layout][n_layout], row = from,
- * finite and >= 0.  Limits: K <= 2048 and the per-class state (K totals, the transition
- * table) must fit in LDS: (K + n_layout^2) * 8 bytes + small <= 64 KB, else DYN_E_SHAPE.
+ * finite and >= 0.  Limits: up to 64 layouts any K the profile handle takes; beyond that
+ * n_layout <= 255, K <= 2048 and the per-class state (K totals, the transition table) must
+ * fit in LDS: (K + n_layout^2) * 8 bytes + small <= 64 KB, else DYN_E_SHAPE.
  * Workspace DEVICE, 256-byte aligned, dyn_select_path_workspace bytes.                    */
 typedef struct {
   int32_t n_layout;

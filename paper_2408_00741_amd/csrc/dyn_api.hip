@@ -761,7 +761,7 @@ int dyn_eval_select_mixed(dyn_profile* p, const dyn_trace_view* t, const dyn_mix
 }
 
 namespace {
-struct PathWs { size_t layout, order, seg, transition, pred, kend, total; };
+struct PathWs { size_t layout, order, seg, transition, pred, kend, min_cost, min_k, total; };
 PathWs path_ws_layout(int32_t n_window, int32_t G, int32_t K, int32_t n_layout) {
   PathWs w;
   size_t off = 0;
@@ -771,6 +771,9 @@ PathWs path_ws_layout(int32_t n_window, int32_t G, int32_t K, int32_t n_layout) 
   w.transition = off; off += align256((size_t)n_layout * n_layout * sizeof(double));
   w.pred = off; off += align256((size_t)G * n_window * n_layout * sizeof(int32_t));
   w.kend = off; off += align256((size_t)G * n_window * sizeof(int32_t));
+  const size_t per_layout = n_layout <= DYN_WAVE ? (size_t)G * n_window * n_layout : 0;   // the wave-per-class route only
+  w.min_cost = off; off += align256(per_layout * sizeof(double));
+  w.min_k = off; off += align256(per_layout * sizeof(int32_t));
   w.total = off;
   return w;
 }
@@ -793,8 +796,8 @@ int dyn_select_path(dyn_profile* p, const dyn_space* space, const dyn_config* cf
   if (!isfinite(o->idle_cost_weight)) { dyn_set_error("idle_cost_weight is not finite"); return DYN_E_NOTFINITE; }
   if (o->idle_cost_weight < 0.0) { dyn_set_error("idle_cost_weight must be >= 0"); return DYN_E_RANGE; }
   if ((int64_t)n_window * p->G >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
-  if (K < 1 || K > DYN_PATH_MAX_CONFIGS || tr->n_layout < 1 || tr->n_layout > 255 || dyn_path_lds(K, tr->n_layout) > DYN_LDS_BUDGET) {
-    dyn_set_error("K=%d (at most %d), n_layout=%d: the per-class state does not fit in registers and LDS", K, DYN_PATH_MAX_CONFIGS, tr->n_layout);
+  if (!dyn_path_fits(K, tr->n_layout)) {
+    dyn_set_error("K=%d, n_layout=%d: beyond 64 layouts the per-class state (K <= %d candidates, n_layout^2 overheads) must fit in LDS", K, tr->n_layout, DYN_PATH_MAX_CONFIGS);
     return DYN_E_SHAPE;
   }
   for (int k = 0; k < K; ++k)
@@ -835,6 +838,7 @@ int dyn_select_path(dyn_profile* p, const dyn_space* space, const dyn_config* cf
   a.n_layout = tr->n_layout; a.layout = (const int32_t*)(base + w.layout); a.transition = (const double*)(base + w.transition);
   a.order = (const int32_t*)(base + w.order); a.seg_start = (const int32_t*)(base + w.seg);
   a.pred = (int32_t*)(base + w.pred); a.kend = (int32_t*)(base + w.kend);
+  a.min_cost = (double*)(base + w.min_cost); a.min_k = (int32_t*)(base + w.min_k);
   a.sel = out->sel; a.sel_energy = out->sel_energy_j; a.path_cost = out->path_cost;
   if (!hip_ok(dyn_launch_path(a, s), "path launch")) return DYN_E_DEVICE;
   if (!hip_ok(dyn_launch_window_totals(out->sel, out->sel_energy_j, n_window, p->G, out->window_energy_j,
@@ -935,7 +939,7 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
   const PathWs pw = path_ws_layout(tc->n_window, p->G, c->n_layout, c->n_layout);
   if (c->transition_j) {
     if (!out->path_cost) { dyn_set_error("out->path_cost is NULL"); return DYN_E_NULL; }
-    if (c->n_layout > DYN_PATH_MAX_CONFIGS || c->n_layout > 255 || dyn_path_lds(c->n_layout, c->n_layout) > DYN_LDS_BUDGET) {
+    if (!dyn_path_fits(c->n_layout, c->n_layout)) {
       dyn_set_error("n_layout=%d: the sequence selection's per-class state does not fit in LDS", c->n_layout);
       return DYN_E_SHAPE;
     }
@@ -997,6 +1001,7 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
     pa.n_layout = c->n_layout; pa.layout = (const int32_t*)(pb + pw.layout); pa.transition = (const double*)(pb + pw.transition);
     pa.order = (const int32_t*)(pb + pw.order); pa.seg_start = (const int32_t*)(pb + pw.seg);
     pa.pred = (int32_t*)(pb + pw.pred); pa.kend = (int32_t*)(pb + pw.kend);
+    pa.min_cost = (double*)(pb + pw.min_cost); pa.min_k = (int32_t*)(pb + pw.min_k);
     pa.sel = out->layout_sel; pa.sel_energy = (double*)(base + w.sel_energy); pa.path_cost = out->path_cost;
     if (!hip_ok(dyn_launch_path(pa, s), "path launch")) return DYN_E_DEVICE;
   }

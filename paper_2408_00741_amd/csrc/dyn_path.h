@@ -17,9 +17,12 @@ struct PathArgs {
   const double* transition;     // DEVICE [n_layout][n_layout] (from, to)
   int32_t* pred;                // workspace [G][n_window][n_layout]
   int32_t* kend;                // workspace [G][n_window]
+  double* min_cost;             // workspace [cells][n_layout] (n_layout <= 64): least cost of a layout's candidates
+  int32_t* min_k;               // workspace [cells][n_layout]: the candidate that has it
   int32_t* sel; double* sel_energy; double* path_cost;
 };
 hipError_t dyn_launch_path(const PathArgs& a, hipStream_t s);
 size_t dyn_path_lds(int32_t K, int32_t n_layout);
+bool dyn_path_fits(int32_t K, int32_t n_layout);   // what dyn_launch_path can take
 
 #endif  // DYN_PATH_H_

@@ -196,6 +196,33 @@ def test_full_size_day_trace(dyn):
     prof.free()
 
 
+@pytest.mark.parametrize("NL,K", [(64, 64), (64, 3000), (66, 300), (17, 33), (33, 500), (49, 49)])
+def test_layout_counts_around_the_route_boundaries(dyn, NL, K):
+    """Up to 64 layouts one wave walks a class (register tiers of 16, 32, 48 and 64 layouts, any number of
+    candidates); beyond that a block does, with the candidates in registers and the overheads in LDS."""
+    rng = np.random.default_rng(NL * 1000 + K)
+    w = make(SPECS[0])
+    G = w["n_class"]
+    NW = 70
+    cfg = {"n_inst": rng.integers(1, 5, K).astype(np.int32), "tp_index": rng.integers(0, w["profile"]["tp"].size, K).astype(np.int32),
+           "f_mhz": rng.choice(w["profile"]["f_mhz"], K)}
+    energy = np.round(rng.uniform(1, 50, (NW * G, K)), 3)
+    flags = np.where(rng.uniform(0, 1, (NW * G, K)) < 0.5, 1, 4).astype(np.uint8)
+    flags[(NW // 2) * G:(NW // 2) * G + G] = 8                 # one window without candidates, for every class
+    lay = rng.permutation(np.arange(K) % NL).astype(np.int32)   # every layout is used
+    tr = np.round(rng.uniform(0, 6, (NL, NL)), 3)
+    tr[np.diag_indices(NL)] = 0.0
+    feas = (flags & 1).astype(np.uint8)
+    o_sel, o_pc = oracle.select_path(energy, feas, NW, G, lay, tr)
+    prof = dyn.dyn_profile_load(w["profile"])
+    plan = dyn.Plan(cfg, w["slos"], w["pct"], None, 0.0)
+    g = run_path(dyn, prof, plan, energy, flags, NW, 60.0, lay, tr)
+    same = check(g, o_sel, o_pc, energy, feas, energy, lay, tr, NW, G)
+    print("layouts", NL, "K", K, "exact sequences:", same, "of", G)
+    assert same == G
+    prof.free()
+
+
 def test_argument_errors(dyn):
     w = make(SPECS[0])
     K = w["configs"]["n_inst"].size
