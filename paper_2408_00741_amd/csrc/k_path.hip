@@ -6,8 +6,10 @@
 // layouts l of (least total ending in l) + transition[l][l'] - equal to the least over all
 // predecessors because rounded addition is monotone.
 //
-// One block per class walks the windows in time order (the recurrence is sequential, so the
-// time per window is what counts).  The candidates are visited in an order sorted by layout
+// Two routes.  Up to 64 layouts (further down): a parallel pre-pass reduces every (window, class) to
+// its layouts' least costs, then one block per class walks the windows with a lane per layout.
+// More layouts (next): one block per class walks the windows in time order (the recurrence is
+// sequential, so the time per window is what counts).  The candidates are visited in an order sorted by layout
 // (built on the host), a fixed number per thread, their costs loaded one window ahead; per
 // window: (A) totals of the sequences ending in each candidate, (B) one thread per layout takes
 // the least of its contiguous run of candidates, (C) the cheapest arrival in every layout of
@@ -16,7 +18,6 @@
 // destination layout) in the workspace and traced back at the end in runs of windows staged
 // through LDS.
 #include "dyn_path.h"
-#include "dyn_device.h"
 static_assert(DYN_PATH_MAX_CONFIGS == 256 * 8, "candidates are held in registers, a fixed number per thread");
 
 namespace {
@@ -217,15 +218,18 @@ __global__ __launch_bounds__(kThreads) void path_kernel(PathArgs a) {
 }
 
 
-// ---- up to 64 layouts: one wave per class, no barriers ----------------------------------------
+// ---- up to 64 layouts ----------------------------------------------------------------------------
 // The step through the layouts needs, per window, only the least cost of every layout and the
 // candidate that has it (adding a layout's arrival total to its candidates' costs keeps their
 // order: rounded addition is monotone).  Those are independent of the recurrence:
 // path_min_kernel takes them for all windows at once.  path_chain_kernel then walks the windows
-// with one lane per layout: the totals of the window's sequences are broadcast lane by lane
-// (v_readlane) against the lane's own column of the transition table, held in registers.
+// with one lane per layout.  What the walk costs is the latency of one window's dependent steps,
+// so it touches global memory only a chunk of windows at a time, keeps its lanes' entries of the
+// transition table in registers, and avoids data-dependent branches (a load inside a branch per
+// source costs an LDS round trip each).
 constexpr int kChainRun = 64;
-constexpr int kChainChunk = 16;                            // windows per visit to global memory; at most 16 (register arrays)
+constexpr int kChainChunk = 16;                            // windows per visit to global memory
+constexpr int kChainWaves = 8;                             // measured: 2 waves 2.4 ms, 4 waves 1.7 ms, 8 waves 1.5 ms, 16 waves 2.0 ms (one day, 48 layouts)
 
 // thread = (cell, layout): least cost among the layout's candidates, lowest candidate among equals
 __global__ __launch_bounds__(256) void path_min_kernel(PathArgs a) {
@@ -255,149 +259,155 @@ __global__ __launch_bounds__(256) void path_min_kernel(PathArgs a) {
   a.min_k[i] = bk;
 }
 
-// predecessor records: (candidate << 6) | its layout, -1: none
+// One block of kChainWaves waves per class; lane = destination layout in every wave, and wave q owns the source
+// layouts [q * LMAX/kChainWaves, (q + 1) * LMAX/kChainWaves) with its lanes' entries of those rows of the table in registers.
+// Per window every wave forms the window's totals itself (all waves carry the same state), publishes
+// them in its own LDS strip, takes the least arrival total over its sources and, among the sources that
+// reach it, the lowest candidate; the waves' partial results meet in LDS behind the window's only block
+// barrier and every wave merges them (least total, then lowest candidate: the same answer as one pass over
+// all sources).  Predecessor records: (candidate << 6) | its layout, -1: none.
 template <int LMAX>
-__global__ __launch_bounds__(DYN_WAVE) void path_chain_kernel(PathArgs a) {
+__global__ __launch_bounds__(kChainWaves* DYN_WAVE) void path_chain_kernel(PathArgs a) {
+  constexpr int SPW = LMAX / kChainWaves;                    // sources per wave
   __shared__ int32_t s_bp[kChainRun * LMAX];
   __shared__ int32_t s_sel[kChainRun];
   __shared__ double s_c[(kChainChunk + 1) * DYN_WAVE];       // the chunk's least costs by (window, layout), one window more
   __shared__ int32_t s_k[kChainChunk * DYN_WAVE];            // and the candidates that have them
   __shared__ int32_t s_pr[kChainChunk * DYN_WAVE];           // the chunk's predecessor records
   __shared__ int32_t s_ke[kChainChunk];
-  __shared__ double s_v[DYN_WAVE];                           // the window's totals by layout
-  __shared__ uint32_t s_pk[DYN_WAVE];                        // (candidate << 6) | layout, all ones where nothing ends
-  const int g = blockIdx.x, lane = threadIdx.x;
+  __shared__ double s_v[kChainWaves][DYN_WAVE];              // per wave: the window's totals by layout
+  __shared__ uint32_t s_pk[kChainWaves][DYN_WAVE];           // per wave: (candidate << 6) | layout, all ones where nothing ends
+  __shared__ double s_m[2][kChainWaves][DYN_WAVE];           // by window parity: every wave's least arrival total per destination
+  __shared__ uint32_t s_p[2][kChainWaves][DYN_WAVE];         // and the packed candidate that reaches it
+  const int g = blockIdx.x, lane = threadIdx.x & (DYN_WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
   const int NL = a.n_layout, NW = a.n_window, G = a.G, K = a.K;
   const double inf = __builtin_inf();
   const bool on = lane < NL;
-  // overhead of going from layout ls to this lane's, in registers: four arrays of 16 (one array of 64
-  // would be placed in scratch memory)
-  double t0[16], t1[16], t2[16], t3[16];
+  double t[SPW];                                             // overhead of going from this wave's source q to this lane's layout
 #pragma unroll
-  for (int q = 0; q < 16; ++q) {
-    t0[q] = (on && q < NL) ? a.transition[(size_t)q * NL + lane] : inf;
-    t1[q] = (LMAX > 16 && on && 16 + q < NL) ? a.transition[(size_t)(16 + q) * NL + lane] : inf;
-    t2[q] = (LMAX > 32 && on && 32 + q < NL) ? a.transition[(size_t)(32 + q) * NL + lane] : inf;
-    t3[q] = (LMAX > 48 && on && 48 + q < NL) ? a.transition[(size_t)(48 + q) * NL + lane] : inf;
+  for (int q = 0; q < SPW; ++q) {
+    const int ls = wave * SPW + q;
+    t[q] = (on && ls < NL) ? a.transition[(size_t)ls * NL + lane] : inf;   // layouts beyond NL never win
   }
   int32_t* bp = a.pred + (size_t)g * NW * NL;                // [NW][NL]: where the cheapest arrival in layout l at window w comes from
   int32_t* kend = a.kend + (size_t)g * NW;                   // [NW]: -1 gap, best end where a sequence ends, 0 otherwise
   auto row = [&](int w) { return ((size_t)w * G + g) * NL + lane; };
 
-  double total = 0.0, arrive = inf;
+  double total = 0.0, arrive = inf;                          // the same in every wave
   bool first = true;
-  // One window: c_cur / k_cur = the layouts' least costs and their candidates in window w, c_nxt = the costs
-  // of window w + 1 (only asked whether any is finite).
-  auto step = [&](int w, int slot, double c_cur, int k_cur, double c_nxt) __attribute__((always_inline)) {
-    // least total of the sequences that end in window w in this lane's layout
-    const double v = (first || !(c_cur < inf)) ? c_cur : arrive + c_cur;
-    const int vk = k_cur;
-    const bool gap = __ballot(v < inf) == 0;                 // no feasible candidate in this window
-    // cheapest arrival in this lane's layout in window w + 1.  Every lane publishes its total and its
-    // candidate (packed with its layout, all ones where nothing ends there) in LDS; every lane then reads all
-    // of them (broadcast reads) against its own column of the table: first the least arrival total, then,
-    // among the sources that reach it, the lowest candidate.  Layouts beyond NL hold +inf / all ones and a
-    // column entry of +inf: they never win and need no test.
-    s_v[lane] = v;
-    const uint32_t s_pk_mine = (v < inf) ? (((uint32_t)vk << 6) | (uint32_t)lane) : 0xFFFFFFFFu;
-    s_pk[lane] = s_pk_mine;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    // arrival totals from every source (kept for the second pass), least of them in four independent chains
-    double a0[16], a1[16], a2[16], a3[16];
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      a0[q] = s_v[q] + t0[q];
-      a1[q] = LMAX > 16 ? s_v[16 + q] + t1[q] : inf;
-      a2[q] = LMAX > 32 ? s_v[32 + q] + t2[q] : inf;
-      a3[q] = LMAX > 48 ? s_v[48 + q] + t3[q] : inf;
-    }
-    double m0 = inf, m1 = inf, m2 = inf, m3 = inf;           // sums are never NaN here: plain minima
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      m0 = fmin(m0, a0[q]);
-      if (LMAX > 16) m1 = fmin(m1, a1[q]);
-      if (LMAX > 32) m2 = fmin(m2, a2[q]);
-      if (LMAX > 48) m3 = fmin(m3, a3[q]);
-    }
-    const double bv = fmin(fmin(m0, m1), fmin(m2, m3));
-    uint32_t p0 = 0xFFFFFFFFu, p1 = 0xFFFFFFFFu, p2 = 0xFFFFFFFFu, p3 = 0xFFFFFFFFu;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      p0 = min(p0, a0[q] == bv ? s_pk[q] : 0xFFFFFFFFu);
-      if (LMAX > 16) p1 = min(p1, a1[q] == bv ? s_pk[16 + q] : 0xFFFFFFFFu);
-      if (LMAX > 32) p2 = min(p2, a2[q] == bv ? s_pk[32 + q] : 0xFFFFFFFFu);
-      if (LMAX > 48) p3 = min(p3, a3[q] == bv ? s_pk[48 + q] : 0xFFFFFFFFu);
-    }
-    const uint32_t bp_rec = min(min(p0, p1), min(p2, p3));   // all ones: nothing arrives (then bv is +inf)
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the next window's publication comes after these reads
-    __builtin_amdgcn_wave_barrier();
-    s_pr[slot * DYN_WAVE + lane] = (int32_t)bp_rec;          // how window w + 1 is entered in this lane's layout; -1: not at all
-    // a sequence ends here if the next window has no feasible candidate (its costs are all +inf) or does not exist
-    const bool ends = !gap && (w + 1 >= NW || __ballot(c_nxt < inf) == 0);
-    int32_t ke = gap ? -1 : 0;
-    if (ends) {                                              // wave-uniform: least total, then the lowest candidate
-      double ev = v;
-#pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) ev = fmin(ev, __shfl_xor(ev, d, DYN_WAVE));
-      uint32_t ep = (v == ev) ? s_pk_mine : 0xFFFFFFFFu;
-#pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) ep = min(ep, (uint32_t)__shfl_xor((int)ep, d, DYN_WAVE));
-      total += ev;                                           // the sequences' totals in time order
-      ke = (int32_t)ep;
-    }
-    if (lane == 0) s_ke[slot] = ke;
-    arrive = bv;
-    first = gap;
-  };
-  // Global memory is touched a chunk of windows at a time: the chunk's costs and candidates are loaded with all
-  // loads in flight at once and parked in LDS, the walk itself reads and writes LDS only, and the chunk's
-  // predecessor records are flushed afterwards (a load or store inside the walk would make every window wait
-  // for memory).
-  auto cost_of = [&](int w) { return (on && w < NW) ? a.min_cost[row(w)] : inf; };
-  auto cand_of = [&](int w) { return (on && w < NW) ? a.min_k[row(w)] : 0x7FFFFFFF; };
+  int par = 0;
 #pragma unroll 1
   for (int w0 = 0; w0 < NW; w0 += kChainChunk) {
-    {
-      double cc[kChainChunk];
-      int kk[kChainChunk];
+    // Global memory is touched a chunk of windows at a time: costs and candidates are parked in LDS, the
+    // walk itself reads and writes LDS only, the chunk's predecessor records are flushed afterwards.
+    __syncthreads();                                         // the previous chunk's flush has read s_pr / s_ke
 #pragma unroll
-      for (int i = 0; i < kChainChunk; ++i) { cc[i] = cost_of(w0 + i); kk[i] = cand_of(w0 + i); }
-      const double c_after = cost_of(w0 + kChainChunk);      // only asked whether the chunk's last window ends a sequence
-#pragma unroll
-      for (int i = 0; i < kChainChunk; ++i) { s_c[i * DYN_WAVE + lane] = cc[i]; s_k[i * DYN_WAVE + lane] = kk[i]; }
-      s_c[kChainChunk * DYN_WAVE + lane] = c_after;
+    for (int j = 0; j < (kChainChunk + 1 + kChainWaves - 1) / kChainWaves; ++j) {
+      const int i = j * kChainWaves + wave;                  // row of the chunk this wave loads
+      if (i <= kChainChunk) {
+        const bool in = on && w0 + i < NW;
+        s_c[i * DYN_WAVE + lane] = in ? a.min_cost[row(w0 + i)] : inf;
+        if (i < kChainChunk) s_k[i * DYN_WAVE + lane] = in ? a.min_k[row(w0 + i)] : 0x7FFFFFFF;
+      }
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __syncthreads();
     const int n = NW - w0 < kChainChunk ? NW - w0 : kChainChunk;
+    double c_nxt = s_c[lane];
+    int k_nxt = s_k[lane];
 #pragma unroll 1
-    for (int i = 0; i < n; ++i)
-      step(w0 + i, i, s_c[i * DYN_WAVE + lane], s_k[i * DYN_WAVE + lane], s_c[(i + 1) * DYN_WAVE + lane]);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    for (int i = 0; i < n; ++i)
+    for (int i = 0; i < n; ++i) {
+      const double c_cur = c_nxt;
+      const int k_cur = k_nxt;
+      c_nxt = s_c[(i + 1) * DYN_WAVE + lane];                // read a window ahead: out of the way of this window's chain of LDS round trips
+      k_nxt = s_k[(i + 1 < kChainChunk ? i + 1 : i) * DYN_WAVE + lane];
+      // least total of the sequences that end in this window in this lane's layout
+      const double v = (first || !(c_cur < inf)) ? c_cur : arrive + c_cur;
+      const uint32_t pk = (v < inf) ? (((uint32_t)k_cur << 6) | (uint32_t)lane) : 0xFFFFFFFFu;
+      const bool gap = __ballot(v < inf) == 0;               // no feasible candidate in this window
+      s_v[wave][lane] = v;
+      s_pk[wave][lane] = pk;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // read back by this wave's other lanes only
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      // this wave's sources: least arrival total, then the lowest candidate among the sources that reach it
+      double arr[SPW];
+      uint32_t spk[SPW];
+#pragma unroll
+      for (int q = 0; q < SPW; ++q) {
+        arr[q] = s_v[wave][wave * SPW + q] + t[q];
+        spk[q] = s_pk[wave][wave * SPW + q];
+        asm volatile("" : "+v"(spk[q]));                     // loaded here, with the totals: not inside a branch per source later
+      }
+      double m0 = inf, m1 = inf;                             // sums are never NaN here: plain minima
+#pragma unroll
+      for (int q = 0; q < SPW; q += 2) { m0 = fmin(m0, arr[q]); if (q + 1 < SPW) m1 = fmin(m1, arr[q + 1]); }
+      const double m = fmin(m0, m1);
+      uint32_t p0 = 0xFFFFFFFFu, p1 = 0xFFFFFFFFu;
+#pragma unroll
+      for (int q = 0; q < SPW; q += 2) {
+        p0 = min(p0, arr[q] == m ? spk[q] : 0xFFFFFFFFu);
+        if (q + 1 < SPW) p1 = min(p1, arr[q + 1] == m ? spk[q + 1] : 0xFFFFFFFFu);
+      }
+      s_m[par][wave][lane] = m;
+      s_p[par][wave][lane] = min(p0, p1);
+      lds_barrier();                                         // the window's only block barrier (partials alternate by parity)
+      double pm[kChainWaves];
+      uint32_t pp[kChainWaves];
+#pragma unroll
+      for (int q = 0; q < kChainWaves; ++q) {
+        pm[q] = s_m[par][q][lane];
+        pp[q] = s_p[par][q][lane];
+        asm volatile("" : "+v"(pp[q]));
+      }
+      double bv = pm[0];
+#pragma unroll
+      for (int q = 1; q < kChainWaves; ++q) bv = fmin(bv, pm[q]);
+      uint32_t bp_rec = 0xFFFFFFFFu;                         // all ones: nothing arrives (then bv is +inf)
+#pragma unroll
+      for (int q = 0; q < kChainWaves; ++q) bp_rec = min(bp_rec, pm[q] == bv ? pp[q] : 0xFFFFFFFFu);
+      par ^= 1;
+      // a sequence ends here if the next window has no feasible candidate (its costs are all +inf) or does not exist
+      const bool ends = !gap && (w0 + i + 1 >= NW || __ballot(c_nxt < inf) == 0);
+      int32_t ke = gap ? -1 : 0;
+      if (ends) {                                            // wave-uniform: least total, then the lowest candidate
+        double ev = v;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) ev = fmin(ev, __shfl_xor(ev, d, DYN_WAVE));
+        uint32_t ep = (v == ev) ? pk : 0xFFFFFFFFu;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) ep = min(ep, (uint32_t)__shfl_xor((int)ep, d, DYN_WAVE));
+        total += ev;                                         // the sequences' totals in time order
+        ke = (int32_t)ep;
+      }
+      if (wave == 0) {
+        s_pr[i * DYN_WAVE + lane] = (int32_t)bp_rec;         // how the next window is entered in this lane's layout; -1: not at all
+        if (lane == 0) s_ke[i] = ke;
+      }
+      arrive = bv;
+      first = gap;
+    }
+    __syncthreads();
+    for (int i = wave; i < n; i += kChainWaves)
       if (on && w0 + i + 1 < NW) bp[(size_t)(w0 + i + 1) * NL + lane] = s_pr[i * DYN_WAVE + lane];
-    if (lane < n) kend[w0 + lane] = s_ke[lane];
+    if (threadIdx.x < n) kend[w0 + threadIdx.x] = s_ke[threadIdx.x];
   }
-  if (lane == 0) a.path_cost[g] = total;
-  // make the predecessor records visible to this wave's own later loads
+  if (threadIdx.x == 0) a.path_cost[g] = total;
+  // make the predecessor records visible to this block's own later loads
   __threadfence();
+  __syncthreads();
 
   // trace back, a run of windows at a time from the end
-  int carry_k = -1, carry_l = 0;                             // lane 0: -1 = the next window starts a sequence
+  constexpr int nthr = kChainWaves * DYN_WAVE;
+  int carry_k = -1, carry_l = 0;                             // thread 0: -1 = the next window starts a sequence
   for (int hi = NW; hi > 0; hi -= kChainRun) {
     const int lo = hi > kChainRun ? hi - kChainRun : 0;
     const int n_row = (hi < NW ? hi : NW - 1) - lo;          // predecessor records of the windows lo+1 .. hi
-    for (int i = lane; i < n_row * NL; i += DYN_WAVE)
-      s_bp[i] = __hip_atomic_load(&bp[(size_t)(lo + 1) * NL + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (int i = lane; i < hi - lo; i += DYN_WAVE)
-      s_sel[i] = __hip_atomic_load(&kend[lo + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // records written by this block before the barrier above: plain loads, all in flight together
+    for (int i = threadIdx.x; i < n_row * NL; i += nthr) s_bp[i] = bp[(size_t)(lo + 1) * NL + i];
+    for (int i = threadIdx.x; i < hi - lo; i += nthr) s_sel[i] = kend[lo + i];
     __syncthreads();
-    if (lane == 0) {
+    if (threadIdx.x == 0) {
       for (int w = hi - 1; w >= lo; --w) {
         const int ke = s_sel[w - lo];
         int rec;
@@ -410,7 +420,7 @@ __global__ __launch_bounds__(DYN_WAVE) void path_chain_kernel(PathArgs a) {
       }
     }
     __syncthreads();
-    for (int i = lane; i < hi - lo; i += DYN_WAVE) {
+    for (int i = threadIdx.x; i < hi - lo; i += nthr) {
       const int k = s_sel[i];
       const size_t cell = (size_t)(lo + i) * G + g;
       a.sel[cell] = k;
@@ -440,10 +450,10 @@ hipError_t dyn_launch_path(const PathArgs& a, hipStream_t s) {
   if (a.n_layout <= DYN_WAVE) {
     const int64_t n = (int64_t)a.n_window * a.G * a.n_layout;
     hipLaunchKernelGGL(path_min_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a);
-    if (a.n_layout <= 16) hipLaunchKernelGGL(path_chain_kernel<16>, dim3((unsigned)a.G), dim3(DYN_WAVE), 0, s, a);
-    else if (a.n_layout <= 32) hipLaunchKernelGGL(path_chain_kernel<32>, dim3((unsigned)a.G), dim3(DYN_WAVE), 0, s, a);
-    else if (a.n_layout <= 48) hipLaunchKernelGGL(path_chain_kernel<48>, dim3((unsigned)a.G), dim3(DYN_WAVE), 0, s, a);
-    else hipLaunchKernelGGL(path_chain_kernel<64>, dim3((unsigned)a.G), dim3(DYN_WAVE), 0, s, a);
+    if (a.n_layout <= 16) hipLaunchKernelGGL(path_chain_kernel<16>, dim3((unsigned)a.G), dim3(kChainWaves * DYN_WAVE), 0, s, a);
+    else if (a.n_layout <= 32) hipLaunchKernelGGL(path_chain_kernel<32>, dim3((unsigned)a.G), dim3(kChainWaves * DYN_WAVE), 0, s, a);
+    else if (a.n_layout <= 48) hipLaunchKernelGGL(path_chain_kernel<48>, dim3((unsigned)a.G), dim3(kChainWaves * DYN_WAVE), 0, s, a);
+    else hipLaunchKernelGGL(path_chain_kernel<64>, dim3((unsigned)a.G), dim3(kChainWaves * DYN_WAVE), 0, s, a);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(path_kernel, dim3((unsigned)a.G), dim3(kThreads), dyn_path_lds(a.K, a.n_layout), s, a);
