@@ -84,6 +84,19 @@ __device__ __forceinline__ void scan_partials(const SelPart* __restrict__ p, int
   double c = __builtin_inf(), e = __builtin_inf();
   int32_t k = -1;
   int i = 0;
+  if (n <= 16) {                 // the usual case: every record in flight at once, compared in candidate order
+    SelPart q[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      q[j].k = -1;
+      if (j < n) q[j] = p[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      if (q[j].k >= 0 && (k < 0 || q[j].cost < c)) { c = q[j].cost; e = q[j].energy; k = q[j].k; }
+    *bc = c; *be = e; *bk = k;
+    return;
+  }
   for (; i + 4 <= n; i += 4) {   // four independent loads in flight, compared in candidate order
     const SelPart q0 = p[i], q1 = p[i + 1], q2 = p[i + 2], q3 = p[i + 3];
     if (q0.k >= 0 && (k < 0 || q0.cost < c)) { c = q0.cost; e = q0.energy; k = q0.k; }
