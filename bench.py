@@ -6,7 +6,10 @@ aggregation + rank selection, evaluation of every (cell, configuration) pair, pe
 least-cost feasible configuration and per-window totals.  By default this is one call of
 dyn_eval_select (selection reduced inside the evaluation kernel); --unfused times
 dyn_eval_space followed by dyn_select_config instead.  Ingestion and profile upload are
-timed separately.
+timed separately.  Other entry points have modes of their own, each on the same workload and
+with the same JSON line: --ticks T (load followed tick by tick inside a window), --mixed S
+(pools that mix TP degrees), --path (selection with transition overheads between windows),
+--hierarchy T [--overheads] (the three controllers top down).
 
 Prints one JSON line.  `value` = requests x configurations / step time.
 """
