@@ -29,10 +29,11 @@ bool hip_ok(hipError_t e, const char* what) {
   return false;
 }
 
-__global__ void init_word_header_kernel(WsHeader* h) {
+__global__ void init_word_header_kernel(WsHeader* h) {   // header regions are 256 bytes
   h->status = 0u;
   h->kind = DYN_WS_KIND_WORD;
   h->cells = 0;
+  ((uint32_t*)h)[DYN_WS_HEADER_ORDER_WORD] = 0u;         // ingestion: "not in window order" flag
 }
 
 bool strictly_increasing(const double* g, int n) {
@@ -203,9 +204,9 @@ int prepare_objective(dyn_profile* p, const dyn_objective* o, hipStream_t s) {
 }
 
 struct IngestWs {
-  size_t status, in_edge, out_edge, key_a, key_b, in_tmp, out_tmp, hist, total;
+  size_t status, in_edge, out_edge, key_a, key_b, in_tmp, out_tmp, hist, win_off, total;
 };
-IngestWs ingest_ws_layout(int64_t n_req, int32_t n_model, int32_t n_in_bin, int32_t n_out_bin) {
+IngestWs ingest_ws_layout(int64_t n_req, int32_t n_model, int32_t n_in_bin, int32_t n_out_bin, int32_t n_window) {
   IngestWs w;
   size_t off = 0;
   w.status = off; off += 256;
@@ -218,6 +219,7 @@ IngestWs ingest_ws_layout(int64_t n_req, int32_t n_model, int32_t n_in_bin, int3
   w.out_tmp = off; off += align256(n * 4);
   const size_t nb = (size_t)dyn_ingest_blocks(n_req);
   w.hist = off; off += align256(((size_t)DYN_INGEST_MAX_BINS * nb + (DYN_INGEST_MAX_BINS * nb) / 4096 + 2) * 4);
+  w.win_off = off; off += align256(((size_t)std::max(n_window, 1) + 1) * sizeof(int64_t));
   w.total = off;
   return w;
 }
@@ -486,10 +488,9 @@ void dyn_profile_free(dyn_profile* p) {
 }
 
 size_t dyn_trace_ingest_workspace(int64_t n_req, int32_t n_window, int32_t n_class) {
-  (void)n_window;
   // edge tables are at most one int per class and axis
-  if (n_req < 0 || n_class < 1) return 0;
-  return ingest_ws_layout(n_req, n_class, 2, 2).total;
+  if (n_req < 0 || n_class < 1 || n_window < 1) return 0;
+  return ingest_ws_layout(n_req, n_class, 2, 2, n_window).total;
 }
 
 int dyn_trace_ingest(const double* t_s, const int32_t* in_tok, const int32_t* out_tok, const int32_t* model,
@@ -515,7 +516,7 @@ int dyn_trace_ingest(const double* t_s, const int32_t* in_tok, const int32_t* ou
     dyn_set_error("sorted outputs alias the inputs");
     return DYN_E_RANGE;
   }
-  const IngestWs w = ingest_ws_layout(n_req, e->n_model, e->n_in_bin, e->n_out_bin);
+  const IngestWs w = ingest_ws_layout(n_req, e->n_model, e->n_in_bin, e->n_out_bin, n_window);
   if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) {
     dyn_set_error("workspace misaligned or too small (%zu < %zu)", workspace_bytes, w.total);
     return DYN_E_WORKSPACE;
@@ -532,14 +533,22 @@ int dyn_trace_ingest(const double* t_s, const int32_t* in_tok, const int32_t* ou
   a.key_a = (uint32_t*)(base + w.key_a); a.key_b = (uint32_t*)(base + w.key_b);
   a.in_tmp = (int32_t*)(base + w.in_tmp); a.out_tmp = (int32_t*)(base + w.out_tmp);
   a.block_hist = (uint32_t*)(base + w.hist);
+  a.unsorted = (uint32_t*)(base + w.status) + DYN_WS_HEADER_ORDER_WORD;
+  a.force_sort = G > DYN_INGEST_MAX_BINS ? 1 : 0;   // the window route keeps one counter per class in LDS
+  a.win_off = (int64_t*)(base + w.win_off);
   a.n_block = dyn_ingest_blocks(n_req);
   int bits = 0;
   while (((int64_t)1 << bits) < cells) ++bits;
   a.key_bits = bits;
   // the edge lists are a few integers: a blocking copy keeps the host arrays free on return
   if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) return DYN_E_DEVICE;
-  if (e->n_in_bin > 1 && !hip_ok(hipMemcpy(base + w.in_edge, e->in_edge, (size_t)e->n_model * (e->n_in_bin - 1) * 4, hipMemcpyHostToDevice), "copy edges")) return DYN_E_DEVICE;
-  if (e->n_out_bin > 1 && !hip_ok(hipMemcpy(base + w.out_edge, e->out_edge, (size_t)e->n_model * (e->n_out_bin - 1) * 4, hipMemcpyHostToDevice), "copy edges")) return DYN_E_DEVICE;
+  {   // both lists in one copy: in_edge and out_edge are neighbours in the workspace
+    const size_t n_in = (size_t)e->n_model * (e->n_in_bin - 1), n_out = (size_t)e->n_model * (e->n_out_bin - 1);
+    std::vector<int32_t> stage((w.out_edge - w.in_edge) / 4 + n_out, 0);
+    if (n_in) memcpy(stage.data(), e->in_edge, n_in * 4);
+    if (n_out) memcpy(stage.data() + (w.out_edge - w.in_edge) / 4, e->out_edge, n_out * 4);
+    if (!hip_ok(hipMemcpy(base + w.in_edge, stage.data(), stage.size() * 4, hipMemcpyHostToDevice), "copy edges")) return DYN_E_DEVICE;
+  }
   hipLaunchKernelGGL(init_word_header_kernel, dim3(1), dim3(1), 0, s, (WsHeader*)a.status);
   if (!hip_ok(hipGetLastError(), "launch")) return DYN_E_DEVICE;
   if (!hip_ok(dyn_launch_ingest(a, s), "ingest launch")) return DYN_E_DEVICE;

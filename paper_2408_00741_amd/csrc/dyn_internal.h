@@ -94,6 +94,7 @@ struct WsHeader {
   uint32_t kind;     // 1: `status` is final; 2: per-cell status bytes still have to be OR-ed in
   int64_t cells;     // kind 2: number of per-cell status bytes
 };
+#define DYN_WS_HEADER_ORDER_WORD 8   // 32-bit word of a 256-byte header region used by the ingestion kernels
 #define DYN_WS_KIND_WORD 1u
 #define DYN_WS_KIND_CELLS 2u
 
@@ -147,6 +148,9 @@ struct IngestArgs {
   int32_t* in_sorted; int32_t* out_sorted; int64_t* cell_off;
   uint32_t* status; uint32_t* key_a; uint32_t* key_b; int32_t* in_tmp; int32_t* out_tmp;
   uint32_t* block_hist; int64_t n_block; int32_t key_bits;
+  uint32_t* unsorted;      // word in the workspace header: 0 while every request's window is >= the one before
+  int32_t force_sort;      // != 0: take the general sort whatever the order
+  int64_t* win_off;        // workspace [n_window + 1]
 };
 hipError_t dyn_launch_ingest(const IngestArgs& a, hipStream_t s);
 int64_t dyn_ingest_blocks(int64_t n_req);

@@ -3,6 +3,12 @@
 // least-significant-digit radix sort by key moves (input tokens, output tokens) into cell
 // order, and the cell offsets are read off the sorted keys.
 //
+// A trace that is already in window order (a request log is in time order) does not need the
+// general sort: the key kernel notices it (a flag in the workspace header stays 0; it also
+// writes where every window starts), the host reads the flag, and one block per window then
+// counts its requests by class and moves them, stably, to their cells (window_sort_kernel).
+// Any other trace takes the radix sort.
+//
 // One radix pass = per-block digit histogram -> exclusive scan of the (digit, block)
 // counters -> stable scatter.  Inside a block every wave owns a contiguous run of rows of
 // 64 requests and walks them in order; the position of a request among the requests of
@@ -18,7 +24,7 @@ constexpr int kScanChunk = 4096;                       // counters per block of 
 
 __global__ __launch_bounds__(256) void key_kernel(IngestArgs a) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= a.n_req) return;
+  if (i >= a.n_req) return;                    // the lanes that stay are a prefix of the wave: lane - 1 is among them
   uint32_t bad = 0;
   double wq = floor(a.t_s[i] / a.window_s);
   if (!(wq >= 0.0)) { bad = DYN_WS_BAD_REQUEST; wq = 0.0; }                      // negative or NaN
@@ -35,6 +41,24 @@ __global__ __launch_bounds__(256) void key_kernel(IngestArgs a) {
   const int64_t g = ((int64_t)mdl * a.n_in_bin + bi) * a.n_out_bin + bo;
   a.key_a[i] = (uint32_t)((int64_t)wq * G + g);
   if (bad) atomicOr(a.status, bad);
+  // Window order: compare with the request before (the neighbouring lane; the first lane of a wave recomputes it).
+  // Where the window changes the boundaries are written: in a trace in window order win_off[w] = number of
+  // requests in windows before w (the values are not used otherwise).
+  const int lane = threadIdx.x & (DYN_WAVE - 1);
+  double wp = __shfl_up(wq, 1, DYN_WAVE);
+  if (lane == 0 && i > 0) {
+    wp = floor(a.t_s[i - 1] / a.window_s);
+    if (!(wp >= 0.0)) wp = 0.0;
+    if (!(wp < (double)a.n_window)) wp = (double)(a.n_window - 1);
+  }
+  if (i == 0) wp = -1.0;
+  const bool dis = wp > wq;
+  for (int64_t w = (int64_t)wp + 1; w <= (int64_t)wq; ++w) a.win_off[w] = i;
+  if (i == a.n_req - 1)
+    for (int64_t w = (int64_t)wq + 1; w <= a.n_window; ++w) a.win_off[w] = a.n_req;
+  const uint64_t any = __ballot(dis);
+  if (any && lane == __builtin_ctzll(any) && __hip_atomic_load(a.unsorted, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u)
+    atomicOr(a.unsorted, 1u);
 }
 
 // digit counts of one block's tile -> block_hist[digit * n_block + block]
@@ -140,10 +164,13 @@ __global__ __launch_bounds__(kWaves* DYN_WAVE) void scatter_kernel(
   // phase 1: digit counts of each wave's run of rows
   const int64_t wbase = (int64_t)blockIdx.x * kTile + (int64_t)wave * (kRows * DYN_WAVE);
   uint32_t key[kRows];
+  int32_t vin[kRows], vout[kRows];                       // the payload, loaded with the keys: not one row at a time later
 #pragma unroll
   for (int r = 0; r < kRows; ++r) {
     const int64_t idx = wbase + r * DYN_WAVE + lane;
     key[r] = idx < n ? keys_in[idx] : 0u;
+    vin[r] = idx < n ? in_in[idx] : 0;
+    vout[r] = idx < n ? out_in[idx] : 0;
     if (idx < n) atomicAdd(&wcnt[wave][(key[r] >> shift) & mask], 1u);
   }
   __syncthreads();
@@ -182,8 +209,8 @@ __global__ __launch_bounds__(kWaves* DYN_WAVE) void scatter_kernel(
     __builtin_amdgcn_wave_barrier();
     if (valid) {
       if (keys_out) keys_out[pos] = key[r];
-      in_out[pos] = in_in[idx];
-      out_out[pos] = out_in[idx];
+      in_out[pos] = vin[r];
+      out_out[pos] = vout[r];
     }
   }
 }
@@ -199,17 +226,142 @@ __global__ __launch_bounds__(256) void offsets_kernel(const uint32_t* __restrict
   for (int64_t c = prev + 1; c <= cur; ++c) cell_off[c] = i;
 }
 
+// ---- a trace in window order ----------------------------------------------------------------
+// win_off[w] = number of requests in windows before w, read off the keys (window = key / G)
+__global__ __launch_bounds__(256) void window_offsets_kernel(const uint32_t* __restrict__ keys, int64_t n, uint32_t G,
+                                                             int32_t n_window, int64_t* __restrict__ win_off) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i > n) return;
+  const int64_t prev = i == 0 ? -1 : (int64_t)(keys[i - 1] / G);
+  int64_t cur = i == n ? n_window : (int64_t)(keys[i] / G);
+  if (cur > n_window) cur = n_window;
+  for (int64_t w = prev + 1; w <= cur; ++w) win_off[w] = i;
+}
+
+// One block per window: class totals of the window, their exclusive prefix (the window's cell offsets),
+// then a stable move tile by tile: every wave owns a contiguous run of rows of a tile and walks them in
+// order, a request's position = start of its class + requests of the class in earlier tiles and earlier
+// waves' runs + its rank among the lanes of its row with the same class (wave ballots).
+__global__ __launch_bounds__(kWaves* DYN_WAVE) void window_sort_kernel(
+    const uint32_t* __restrict__ keys, const int32_t* __restrict__ in_in, const int32_t* __restrict__ out_in,
+    int32_t* __restrict__ in_out, int32_t* __restrict__ out_out, const int64_t* __restrict__ win_off, int32_t G,
+    int32_t n_window, int64_t n, int64_t* __restrict__ cell_off) {
+  __shared__ uint32_t wcnt[kWaves][DYN_INGEST_MAX_BINS];
+  __shared__ uint32_t run[DYN_INGEST_MAX_BINS];          // next output position of every class, relative to the window's start
+  const int w = blockIdx.x;
+  const int lane = threadIdx.x & (DYN_WAVE - 1), wave = threadIdx.x / DYN_WAVE;
+  const int64_t beg = win_off[w], end = win_off[w + 1];
+  const uint32_t key0 = (uint32_t)w * (uint32_t)G;
+  int bits = 0;
+  while ((1 << bits) < G) ++bits;
+  for (int d = threadIdx.x; d < G; d += blockDim.x) run[d] = 0;
+  __syncthreads();
+  {                                                      // class totals of the window, four loads per thread in flight
+    int64_t i = beg + threadIdx.x;
+    for (; i + 3 * (int64_t)blockDim.x < end; i += 4 * (int64_t)blockDim.x) {
+      const uint32_t k0 = keys[i], k1 = keys[i + blockDim.x], k2 = keys[i + 2 * blockDim.x], k3 = keys[i + 3 * blockDim.x];
+      atomicAdd(&run[k0 - key0], 1u); atomicAdd(&run[k1 - key0], 1u); atomicAdd(&run[k2 - key0], 1u); atomicAdd(&run[k3 - key0], 1u);
+    }
+    for (; i < end; i += blockDim.x) atomicAdd(&run[keys[i] - key0], 1u);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {                                // exclusive prefix over the classes
+    uint32_t acc = 0;
+    for (int d = 0; d < G; ++d) {
+      const uint32_t c = run[d];
+      run[d] = acc;
+      acc += c;
+    }
+  }
+  __syncthreads();
+  for (int d = threadIdx.x; d < G; d += blockDim.x) cell_off[(int64_t)w * G + d] = beg + run[d];
+  if (w == n_window - 1 && threadIdx.x == 0) cell_off[(int64_t)n_window * G] = n;
+
+  for (int64_t tile = beg; tile < end; tile += kTile) {
+    for (int b = threadIdx.x; b < kWaves * G; b += blockDim.x) wcnt[b / G][b % G] = 0;
+    __syncthreads();
+    // phase 1: class counts of each wave's run of rows
+    const int64_t wbase = tile + (int64_t)wave * (kRows * DYN_WAVE);
+    uint32_t cls[kRows];
+    int32_t vin[kRows], vout[kRows];                     // the payload, loaded with the keys: not one row at a time later
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+      const int64_t idx = wbase + r * DYN_WAVE + lane;
+      cls[r] = idx < end ? keys[idx] - key0 : 0u;
+      vin[r] = idx < end ? in_in[idx] : 0;
+      vout[r] = idx < end ? out_in[idx] : 0;
+      if (idx < end) atomicAdd(&wcnt[wave][cls[r]], 1u);
+    }
+    __syncthreads();
+    // phase 2: per class, the first output position of each wave's requests
+    for (int d = threadIdx.x; d < G; d += blockDim.x) {
+      uint32_t pos = run[d];
+      for (int q = 0; q < kWaves; ++q) {
+        const uint32_t c = wcnt[q][d];
+        wcnt[q][d] = pos;
+        pos += c;
+      }
+      run[d] = pos;
+    }
+    __syncthreads();
+    // phase 3: rows in order; inside a row, rank among the lanes with the same class
+    uint32_t* my = wcnt[wave];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+      const int64_t idx = wbase + r * DYN_WAVE + lane;
+      const bool valid = idx < end;
+      if (__ballot(valid) == 0) break;                   // wave-uniform: nothing left in this run
+      const uint32_t d = cls[r];
+      uint64_t peers = __ballot(valid);
+      for (int b = 0; b < bits; ++b) {
+        const bool bit = (d >> b) & 1u;
+        const uint64_t bal = __ballot(bit);
+        peers &= bit ? bal : ~bal;
+      }
+      const int before = __popcll(peers & ((1ull << lane) - 1ull));
+      const int group = __popcll(peers);
+      uint32_t pos = 0;
+      if (valid) pos = my[d] + (uint32_t)before;
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      if (valid && before == group - 1) my[d] += (uint32_t)group;   // one lane per class advances it
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      if (valid) {
+        in_out[beg + pos] = vin[r];
+        out_out[beg + pos] = vout[r];
+      }
+    }
+    __syncthreads();
+  }
+}
+
 }  // namespace
 
 int64_t dyn_ingest_blocks(int64_t n_req) { return n_req > 0 ? (n_req + kTile - 1) / kTile : 1; }
 
 hipError_t dyn_launch_ingest(const IngestArgs& a, hipStream_t s) {
   const int64_t n = a.n_req;
-  const int64_t cells = (int64_t)a.n_window * a.n_model * a.n_in_bin * a.n_out_bin;
+  const int32_t G = a.n_model * a.n_in_bin * a.n_out_bin;
+  const int64_t cells = (int64_t)a.n_window * G;
   hipError_t e;
+  // Keys, and whether the trace is in window order already (the flag word was cleared with the header).  The
+  // answer picks the route, so it is read back here: this entry point synchronises with the stream anyway.
+  uint32_t unsorted = a.force_sort ? 1u : 0u;
   if (n > 0) {
     hipLaunchKernelGGL(key_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (!a.force_sort) {
+      if ((e = hipMemcpyAsync(&unsorted, a.unsorted, sizeof(uint32_t), hipMemcpyDeviceToHost, s)) != hipSuccess) return e;
+      if ((e = hipStreamSynchronize(s)) != hipSuccess) return e;
+    }
+  } else {
+    hipLaunchKernelGGL(window_offsets_kernel, dim3(1), dim3(256), 0, s, a.key_a, n, (uint32_t)G, a.n_window, a.win_off);
+  }
+  if (!unsorted) {            // in window order: one block per window moves its requests to their cells
+    hipLaunchKernelGGL(window_sort_kernel, dim3((unsigned)a.n_window), dim3(kWaves * DYN_WAVE), 0, s, a.key_a, a.in_tok,
+                       a.out_tok, a.in_sorted, a.out_sorted, a.win_off, G, a.n_window, n, a.cell_off);
+    return hipGetLastError();
   }
   const int passes = a.key_bits <= 0 ? 1 : (a.key_bits + 9) / 10;
   const int bits = a.key_bits <= 0 ? 1 : (a.key_bits + passes - 1) / passes;
@@ -218,30 +370,28 @@ hipError_t dyn_launch_ingest(const IngestArgs& a, hipStream_t s) {
   uint32_t* k_dst = a.key_b;
   const int32_t *i_src = a.in_tok, *o_src = a.out_tok;
   const uint32_t* sorted_keys = a.key_a;
-  if (n > 0) {
-    for (int p = 0; p < passes; ++p) {
-      const bool to_final = ((passes - 1 - p) % 2) == 0;
-      int32_t* i_dst = to_final ? a.in_sorted : a.in_tmp;
-      int32_t* o_dst = to_final ? a.out_sorted : a.out_tmp;
-      const int shift = p * bits;
-      const int64_t count = (int64_t)(1 << bits) * a.n_block;
-      const int64_t n_part = (count + kScanChunk - 1) / kScanChunk;
-      uint32_t* partial = a.block_hist + (size_t)DYN_INGEST_MAX_BINS * a.n_block;
-      hipLaunchKernelGGL(hist_kernel, dim3((unsigned)a.n_block), dim3(kWaves * DYN_WAVE), 0, s, k_src, n, shift,
-                         bits, a.block_hist, a.n_block);
-      hipLaunchKernelGGL(scan_reduce_kernel, dim3((unsigned)n_part), dim3(256), 0, s, a.block_hist, count, partial);
-      hipLaunchKernelGGL(scan_partials_kernel, dim3(1), dim3(256), 0, s, partial, n_part);
-      hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)n_part), dim3(256), 0, s, a.block_hist, count, partial);
-      hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)a.n_block), dim3(kWaves * DYN_WAVE), 0, s, k_src, i_src,
-                         o_src, k_dst, i_dst, o_dst, n, shift, bits, a.block_hist, a.n_block);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
-      sorted_keys = k_dst;
-      i_src = i_dst;
-      o_src = o_dst;
-      uint32_t* old_src = const_cast<uint32_t*>(k_src);   // both key buffers live in the workspace
-      k_src = k_dst;
-      k_dst = old_src;
-    }
+  for (int p = 0; p < passes; ++p) {
+    const bool to_final = ((passes - 1 - p) % 2) == 0;
+    int32_t* i_dst = to_final ? a.in_sorted : a.in_tmp;
+    int32_t* o_dst = to_final ? a.out_sorted : a.out_tmp;
+    const int shift = p * bits;
+    const int64_t count = (int64_t)(1 << bits) * a.n_block;
+    const int64_t n_part = (count + kScanChunk - 1) / kScanChunk;
+    uint32_t* partial = a.block_hist + (size_t)DYN_INGEST_MAX_BINS * a.n_block;
+    hipLaunchKernelGGL(hist_kernel, dim3((unsigned)a.n_block), dim3(kWaves * DYN_WAVE), 0, s, k_src, n, shift,
+                       bits, a.block_hist, a.n_block);
+    hipLaunchKernelGGL(scan_reduce_kernel, dim3((unsigned)n_part), dim3(256), 0, s, a.block_hist, count, partial);
+    hipLaunchKernelGGL(scan_partials_kernel, dim3(1), dim3(256), 0, s, partial, n_part);
+    hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)n_part), dim3(256), 0, s, a.block_hist, count, partial);
+    hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)a.n_block), dim3(kWaves * DYN_WAVE), 0, s, k_src, i_src,
+                       o_src, k_dst, i_dst, o_dst, n, shift, bits, a.block_hist, a.n_block);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    sorted_keys = k_dst;
+    i_src = i_dst;
+    o_src = o_dst;
+    uint32_t* old_src = const_cast<uint32_t*>(k_src);   // both key buffers live in the workspace
+    k_src = k_dst;
+    k_dst = old_src;
   }
   hipLaunchKernelGGL(offsets_kernel, dim3((unsigned)((n + 1 + 255) / 256)), dim3(256), 0, s, sorted_keys, n, cells,
                      a.cell_off);

@@ -174,6 +174,32 @@ def test_ingest_edge_cases(dyn):
     assert off.cpu().numpy()[-1] == 4
 
 
+@pytest.mark.parametrize("case", ["sorted", "one-swap", "reversed-windows", "sorted-many-classes", "sorted-empty-windows"])
+def test_ingest_routes(dyn, case):
+    """A trace in window order is moved window by window, any other one by the general sort; more classes than
+    the window route keeps counters for always take the sort.  Same result either way."""
+    rng = np.random.default_rng(21)
+    n, NW, W = 60_000, 7, 10.0
+    t = np.sort(rng.uniform(0, NW * W, n))
+    x = rng.integers(1, 8193, n).astype(np.int32); y = rng.integers(1, 8193, n).astype(np.int32)
+    edges = {"in_edge": np.asarray([[64, 512, 4096]], np.int32), "out_edge": np.asarray([[100, 1000]], np.int32)}
+    if case == "one-swap":                 # a single request out of window order, near the end
+        t[-10], t[-30000] = t[-30000], t[-10]
+    elif case == "reversed-windows":
+        t = t[::-1].copy()
+    elif case == "sorted-many-classes":    # 40 x 30 = 1200 classes
+        edges = {"in_edge": np.arange(100, 4000, 100, dtype=np.int32)[None, :39], "out_edge": np.arange(50, 1500, 50, dtype=np.int32)[None, :29]}
+    elif case == "sorted-empty-windows":   # nothing in windows 0, 3 and the last two
+        t = np.sort(np.concatenate([rng.uniform(W, 3 * W, n // 2), rng.uniform(4 * W, 5 * W, n - n // 2)]))
+    tr = {"t_s": t, "in_tok": x, "out_tok": y, "model": np.zeros(n, np.int32)}
+    st = oracle.ingest(tr, edges, NW, W)
+    ins, outs, off, ws = dyn.dyn_trace_ingest(_dev(t), _dev(x), _dev(y), None, edges, NW, W)
+    assert dyn.dyn_workspace_status(ws) == 0
+    np.testing.assert_array_equal(off.cpu().numpy(), st["cell_off"])
+    np.testing.assert_array_equal(ins.cpu().numpy(), st["in_tok"])
+    np.testing.assert_array_equal(outs.cpu().numpy(), st["out_tok"])
+
+
 # ------------------------------------------------------------------- evaluation + selection
 EVAL_CASES = {
     "cfg0-full": (SPECS[0], None),
