@@ -217,9 +217,11 @@ def account(configs: Dict[str, np.ndarray], tp, sel: np.ndarray, window_energy_j
 
 def hierarchy(profile: Dict[str, np.ndarray], coarse: Dict[str, np.ndarray], fine: Dict[str, np.ndarray], n_window: int,
               n_tick: int, tick_s: float, epoch_windows: int, tp_ref: int, f_ref: int, gpus_per_node: int,
-              lay_n, lay_tp, slos: Dict[str, np.ndarray], pct=(99, 100), transition=None) -> Dict[str, np.ndarray]:
+              lay_n, lay_tp, slos: Dict[str, np.ndarray], pct=(99, 100), transition=None,
+              spill: bool = False) -> Dict[str, np.ndarray]:
     """Scale-out / shard / frequency controllers, top down; see dynoracle_hierarchy.  `transition`
-    ([n_layout][n_layout] joules, from -> to) makes the shard controller weigh re-sharding overheads."""
+    ([n_layout][n_layout] joules, from -> to) makes the shard controller weigh re-sharding overheads;
+    `spill` applies the fragmentation rule (adds "keep" [n_epoch][G] and "served" [n_window*G])."""
     lib = _load()
     lib.dynoracle_hierarchy.restype = C.c_int
     tp = _c(profile["tp"], np.int32); fg = _c(profile["f_mhz"], np.float64); rg = _c(profile["rho"], np.float64)
@@ -235,7 +237,7 @@ def hierarchy(profile: Dict[str, np.ndarray], coarse: Dict[str, np.ndarray], fin
     cells = n_window * G
     r = {"nodes": np.empty((n_epoch, G), np.int32), "layout_sel": np.empty(cells, np.int32),
          "f_sel": np.empty((n_window * n_tick, G), np.int32), "energy_j": np.empty(cells),
-         "violations": np.empty(cells, np.int32)}
+         "violations": np.empty(cells, np.int32), "keep": np.empty((n_epoch, G)), "served": np.empty(cells)}
     tr = None
     if transition is not None:
         tr = _c(transition, np.float64)
@@ -246,9 +248,9 @@ def hierarchy(profile: Dict[str, np.ndarray], coarse: Dict[str, np.ndarray], fin
         _ptr(PF), _ptr(TB), _ptr(PW), _ptr(ML), C.c_int64(ic.size), C.c_int32(n_window), C.c_int32(n_tick),
         C.c_double(tick_s), _ptr(ic), _ptr(oc), _ptr(co), _ptr(if_), _ptr(of_), _ptr(fo), C.c_int32(epoch_windows),
         C.c_int32(tp_ref), C.c_int32(f_ref), C.c_int32(gpus_per_node), C.c_int32(ln.size), _ptr(ln), _ptr(lt), _ptr(st),
-        _ptr(sb), C.c_int32(pct[0]), C.c_int32(pct[1]), None if tr is None else _ptr(tr), _ptr(r["nodes"]),
-        _ptr(r["layout_sel"]), _ptr(r["f_sel"]), _ptr(r["energy_j"]), _ptr(r["violations"]),
-        None if tr is None else _ptr(r["path_cost"]))
+        _ptr(sb), C.c_int32(pct[0]), C.c_int32(pct[1]), None if tr is None else _ptr(tr), C.c_int32(1 if spill else 0),
+        _ptr(r["nodes"]), _ptr(r["layout_sel"]), _ptr(r["f_sel"]), _ptr(r["energy_j"]), _ptr(r["violations"]),
+        None if tr is None else _ptr(r["path_cost"]), _ptr(r["keep"]), _ptr(r["served"]))
     if rc != 0:
         raise ValueError(f"dynoracle_hierarchy failed: {rc}")
     return r

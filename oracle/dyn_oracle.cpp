@@ -688,6 +688,17 @@ int dynoracle_account(int32_t n_window, int32_t G, int32_t K, const int32_t* cfg
 //     with cost = the layout's energy at f_ref over the window, feasible = fits the nodes' GPUs
 //     and meets the SLO, one candidate per layout; path_cost[g] = that class's total.  Without a
 //     table (NULL) every window takes its own least-energy layout and path_cost is not written.
+//   With spill != 0 (Section IV-B "Handling fragmentation"): a pool whose peak does not fill its
+//     last node gets that node less, and the load the remaining nodes cannot carry goes to the
+//     pool of the next class; only the last class rounds up.  Per epoch, classes in ascending
+//     order: arriving load of a window A = own load + what the class below forwards; PL = peak
+//     of A; q = PL / ML.  If the class is not the last and 1 <= floor(q) < q: nodes = floor(q)
+//     and the pool keeps the fraction keep = ((floor(q) x ML) / PL) x (1 - 2^-40) of what
+//     arrives (the factor keeps the peak window inside the profiled range whatever the rounding
+//     of the later divisions); otherwise nodes = ceil(q), at least one, and keep = 1.  Served
+//     load S = keep x A in every window and tick of the epoch; forwarded = A - S.  The shard
+//     and frequency controllers see S; the percentiles stay those of the pool's own requests
+//     (forwarded requests are smaller than the pool's own).
 // Readings: the load predictor is exact (the epoch's true peak); at least one node per class;
 // a window whose class has no admissible layout has energy +inf and no frequencies (-1).
 // coarse_off / fine_off: offsets of the trace sorted by window*G + class and by
@@ -701,8 +712,9 @@ int dynoracle_hierarchy(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f,
                         int32_t epoch_windows, int32_t tp_ref, int32_t f_ref, int32_t gpus_per_node,
                         int32_t n_layout, const int32_t* lay_n, const int32_t* lay_tp,
                         const double* slo_ttft, const double* slo_tbt, int32_t pct_num, int32_t pct_den,
-                        const double* transition, int32_t* nodes, int32_t* layout_sel, int32_t* f_sel,
-                        double* energy_j, int32_t* violations, double* path_cost) {
+                        const double* transition, int32_t spill, int32_t* nodes, int32_t* layout_sel,
+                        int32_t* f_sel, double* energy_j, int32_t* violations, double* path_cost,
+                        double* keep, double* served) {
   if (!tp || !fg || !rg || !PF || !TB || !PW || !ML || !coarse_off || !fine_off || !lay_n || !lay_tp ||
       !slo_ttft || !slo_tbt || !nodes || !layout_sel || !f_sel || !energy_j || !violations)
     return ORC_E_NULL;
@@ -750,22 +762,55 @@ int dynoracle_hierarchy(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f,
     return (double)tok / secs;
   };
 
-  for (int e = 0; e < n_epoch; ++e)
+  // scale-out/in; served loads of every window and tick (equal to the own loads without spill)
+  const int64_t cells = (int64_t)n_window * G;
+  const int64_t fcells = cells * n_tick;
+  std::vector<double> S_c((size_t)cells), S_f((size_t)fcells), kept((size_t)n_epoch * G, 1.0);
+  const double guard = 1.0 - std::ldexp(1.0, -40);
+  for (int e = 0; e < n_epoch; ++e) {
+    const int w0 = e * epoch_windows, w1 = std::min(n_window, (e + 1) * epoch_windows);
+    std::vector<double> fwd((size_t)(w1 - w0), 0.0), A((size_t)(w1 - w0));
     for (int g = 0; g < G; ++g) {
       double peak = 0.0;
-      for (int w = e * epoch_windows; w < std::min(n_window, (e + 1) * epoch_windows); ++w) {
+      for (int w = w0; w < w1; ++w) {
         const int64_t c = (int64_t)w * G + g;
-        const double L = load_of(in_c, out_c, coarse_off[c], coarse_off[c + 1], window_s);
-        if (L > peak) peak = L;
+        A[(size_t)(w - w0)] = load_of(in_c, out_c, coarse_off[c], coarse_off[c + 1], window_s) + fwd[(size_t)(w - w0)];
+        if (A[(size_t)(w - w0)] > peak) peak = A[(size_t)(w - w0)];
       }
       const int inst = std::max(1, gpus_per_node / tp[tp_ref]);
       const double ml_node = ((double)inst * ML[((int64_t)g * n_tp + tp_ref) * n_f + f_ref]) * rg[n_rho - 1];
-      const double q = std::ceil(peak / ml_node);
-      nodes[(int64_t)e * G + g] = q < 1.0 ? 1 : (q > 2147483647.0 ? 2147483647 : (int32_t)q);
+      const double q = peak / ml_node;
+      const double fl = std::floor(q);
+      double k = 1.0;
+      if (spill && g < G - 1 && fl >= 1.0 && fl < q && fl < 2147483647.0) {
+        nodes[(int64_t)e * G + g] = (int32_t)fl;
+        k = ((fl * ml_node) / peak) * guard;
+      } else {
+        const double up = std::ceil(q);
+        nodes[(int64_t)e * G + g] = up < 1.0 ? 1 : (up > 2147483647.0 ? 2147483647 : (int32_t)up);
+      }
+      kept[(size_t)e * G + g] = k;
+      for (int w = w0; w < w1; ++w) {
+        const double s = k * A[(size_t)(w - w0)];
+        S_c[(size_t)((int64_t)w * G + g)] = s;
+        fwd[(size_t)(w - w0)] = A[(size_t)(w - w0)] - s;
+      }
     }
+  }
+  for (int64_t t = 0; t < (int64_t)n_window * n_tick; ++t) {
+    const int e = (int)(t / n_tick) / epoch_windows;
+    double fwd = 0.0;
+    for (int g = 0; g < G; ++g) {
+      const int64_t f = t * G + g;
+      const double a = load_of(in_f, out_f, fine_off[f], fine_off[f + 1], tick_s) + fwd;
+      S_f[(size_t)f] = kept[(size_t)e * G + g] * a;
+      fwd = a - S_f[(size_t)f];
+    }
+  }
+  if (keep) std::copy(kept.begin(), kept.end(), keep);
+  if (served) std::copy(S_c.begin(), S_c.end(), served);
 
   // shard-up/down: energy and admissibility of every layout at the reference frequency
-  const int64_t cells = (int64_t)n_window * G;
   std::vector<double> lay_e((size_t)cells * n_layout, INF);
   std::vector<uint8_t> lay_ok((size_t)cells * n_layout, 0);
   for (int w = 0; w < n_window; ++w)
@@ -773,7 +818,7 @@ int dynoracle_hierarchy(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f,
       const int64_t c = (int64_t)w * G + g;
       const int64_t beg = coarse_off[c], end = coarse_off[c + 1];
       const int64_t m = end - beg;
-      const double L = load_of(in_c, out_c, beg, end, window_s);
+      const double L = S_c[(size_t)c];
       const int64_t budget = (int64_t)nodes[(int64_t)(w / epoch_windows) * G + g] * gpus_per_node;
       int best = -1;
       double best_e = INF;
@@ -809,7 +854,7 @@ int dynoracle_hierarchy(int32_t G, int32_t n_tp, const int32_t* tp, int32_t n_f,
         const int64_t f = ((int64_t)w * n_tick + q) * G + g;
         if (best < 0) { f_sel[f] = -1; continue; }
         const int64_t fb = fine_off[f], fe = fine_off[f + 1];
-        const double Lt = load_of(in_f, out_f, fb, fe, tick_s);
+        const double Lt = S_f[(size_t)f];
         int bf = -1;
         double bp = INF;
         for (int fi = 0; fi < n_f; ++fi) {

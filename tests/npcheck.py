@@ -211,8 +211,10 @@ def np_mixed(profile, st, n_window, window_s, n_share, n_max, slos, pct=(99, 100
 
 
 def np_hierarchy(profile, tr, edges, n_window, n_tick, tick_s, epoch_windows, tp_ref, f_ref, gpus_per_node, lay_n, lay_tp,
-                 slos, pct=(99, 100)):
-    """Scale-out / shard / frequency controllers from the raw trace, NumPy arithmetic."""
+                 slos, pct=(99, 100), spill=False):
+    """Scale-out / shard / frequency controllers from the raw trace, NumPy arithmetic.  With `spill` a pool below the
+    last class that would not fill its last node gets one node less and passes the share of its arriving load that the
+    remaining nodes cannot carry on to the next class."""
     tp = profile["tp"]; fg = profile["f_mhz"]; rg = profile["rho"]
     PF, TB, PW, ML = (profile[k] for k in ("prefill_ms_per_tok", "tbt_ms", "power_w", "max_load_tps"))
     G = PF.shape[0]
@@ -229,8 +231,7 @@ def np_hierarchy(profile, tr, edges, n_window, n_tick, tick_s, epoch_windows, tp
             return 0.0
         return float(np.sort(v)[int(math.ceil(Fraction(pct[0] * v.size, pct[1]))) - 1])
 
-    def admissible(g, ti, f, n, x, y, secs):
-        load = float(x.sum() + y.sum()) / secs
+    def admissible(g, ti, f, n, x, load):
         rho = load / (n * ML[g, ti, f])
         r = min(rho, rg[-1])
         pf, tb, pw = (float(np.interp(r, rg, X[g, ti, f])) for X in (PF, TB, PW))
@@ -239,14 +240,27 @@ def np_hierarchy(profile, tr, edges, n_window, n_tick, tick_s, epoch_windows, tp
 
     n_epoch = -(-n_window // epoch_windows)
     nodes = np.zeros((n_epoch, G), np.int32)
+    keep = np.ones((n_epoch, G))
+    own_c = np.array([[float(sum(v.sum() for v in run(coarse, w * G + g))) / W for g in range(G)] for w in range(n_window)])
+    own_f = np.array([[float(sum(v.sum() for v in run(fine, t * G + g))) / tick_s for g in range(G)]
+                      for t in range(n_window * n_tick)])
+    srv_c = np.zeros_like(own_c); srv_f = np.zeros_like(own_f)
     for e in range(n_epoch):
+        ws = slice(e * epoch_windows, min(n_window, (e + 1) * epoch_windows))
+        ts = slice(ws.start * n_tick, ws.stop * n_tick)
+        pass_c = np.zeros(ws.stop - ws.start); pass_f = np.zeros(ts.stop - ts.start)
         for g in range(G):
-            peak = 0.0
-            for w in range(e * epoch_windows, min(n_window, (e + 1) * epoch_windows)):
-                x, y = run(coarse, w * G + g)
-                peak = max(peak, float(x.sum() + y.sum()) / W)
+            arr_c = own_c[ws, g] + pass_c; arr_f = own_f[ts, g] + pass_f
+            peak = max(0.0, arr_c.max())
             cap = max(1, gpus_per_node // int(tp[tp_ref])) * ML[g, tp_ref, f_ref] * rg[-1]
-            nodes[e, g] = max(1, math.ceil(peak / cap))
+            full = math.floor(peak / cap)
+            if spill and g < G - 1 and 1 <= full < peak / cap:
+                nodes[e, g] = full
+                keep[e, g] = full * cap / peak * (1.0 - 2.0 ** -40)
+            else:
+                nodes[e, g] = max(1, math.ceil(peak / cap))
+            srv_c[ws, g] = keep[e, g] * arr_c; srv_f[ts, g] = keep[e, g] * arr_f
+            pass_c = arr_c - srv_c[ws, g]; pass_f = arr_f - srv_f[ts, g]
     lay = np.full(n_window * G, -1, np.int32)
     fsel = np.full((n_window * n_tick, G), -1, np.int32)
     energy = np.full(n_window * G, np.inf)
@@ -259,7 +273,7 @@ def np_hierarchy(profile, tr, edges, n_window, n_tick, tick_s, epoch_windows, tp
             for l in range(len(lay_n)):
                 if lay_n[l] * int(tp[lay_tp[l]]) > nodes[w // epoch_windows, g] * gpus_per_node:
                     continue
-                ok, pw = admissible(g, lay_tp[l], f_ref, lay_n[l], x, y, W)
+                ok, pw = admissible(g, lay_tp[l], f_ref, lay_n[l], x, srv_c[w, g])
                 if ok and lay_n[l] * pw * W < be:
                     best, be = l, lay_n[l] * pw * W
             lay[c] = best
@@ -268,14 +282,15 @@ def np_hierarchy(profile, tr, edges, n_window, n_tick, tick_s, epoch_windows, tp
             e = 0.0
             for q in range(n_tick):
                 xf, yf = run(fine, (w * n_tick + q) * G + g)
-                cand = [(pw, f) for f in range(fg.size) for ok, pw in [admissible(g, lay_tp[best], f, lay_n[best], xf, yf, tick_s)] if ok]
+                cand = [(pw, f) for f in range(fg.size) for ok, pw in [admissible(g, lay_tp[best], f, lay_n[best], xf, srv_f[w * n_tick + q, g])] if ok]
                 if cand:
                     pw, f = min(cand)
                 else:
-                    _, pw = admissible(g, lay_tp[best], f_ref, lay_n[best], xf, yf, tick_s)
+                    _, pw = admissible(g, lay_tp[best], f_ref, lay_n[best], xf, srv_f[w * n_tick + q, g])
                     f = f_ref
                     viol[c] += 1
                 fsel[w * n_tick + q, g] = f
                 e += lay_n[best] * pw * tick_s
             energy[c] = e
-    return {"nodes": nodes, "layout_sel": lay, "f_sel": fsel, "energy_j": energy, "violations": viol}
+    return {"nodes": nodes, "layout_sel": lay, "f_sel": fsel, "energy_j": energy, "violations": viol, "keep": keep,
+            "served": srv_c.reshape(-1)}

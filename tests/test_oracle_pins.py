@@ -782,9 +782,9 @@ def test_account_against_numpy(small_hour):
 
 
 # ------------------------------------------------------------ hierarchy of controllers
-def _hier_case(seed, n_tick=3, n_f=3, R=500, NW=5):
+def _hier_case(seed, n_tick=3, n_f=3, R=500, NW=5, G=2):
     rng = np.random.default_rng(1700 + seed)
-    n_tp, n_rho, G = 3, 4, 2
+    n_tp, n_rho = 3, 4
     fg = np.sort(rng.uniform(600, 2000, n_f)); rg = np.concatenate([[0.0], np.sort(rng.uniform(0.1, 0.95, n_rho - 1))])
     shape = (G, n_tp, n_f, n_rho)
     prof = _profile([2, 4, 8], fg, rg, rng.uniform(0.02, 0.1, shape), np.sort(rng.uniform(10, 150, shape), axis=-1),
@@ -792,7 +792,8 @@ def _hier_case(seed, n_tick=3, n_f=3, R=500, NW=5):
     tick = 5.0
     tr = {"t_s": rng.uniform(0, NW * n_tick * tick, R), "in_tok": rng.integers(1, 500, R).astype(np.int32),
           "out_tok": rng.integers(1, 300, R).astype(np.int32), "model": np.zeros(R, np.int32)}
-    edges = {"in_edge": np.asarray([[200]], np.int32), "out_edge": np.zeros((1, 0), np.int32)}
+    edges = {"in_edge": np.asarray([[200 * (i + 1) // (G - 1) for i in range(G - 1)]], np.int32),
+             "out_edge": np.zeros((1, 0), np.int32)}
     slo = {"slo_ttft_ms": rng.uniform(25, 70, G), "slo_tbt_ms": rng.uniform(80, 150, G)}
     lay_n = rng.integers(1, 6, 9).astype(np.int32); lay_tp = rng.integers(0, n_tp, 9).astype(np.int32)
     return prof, tr, edges, slo, lay_n, lay_tp, NW, n_tick, tick
@@ -830,6 +831,85 @@ def test_hierarchy_node_count_is_ceil_of_peak_over_node_capacity():
     assert r["nodes"][:, 1].tolist() == [1, 1]               # an idle class keeps one node
     r2 = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 3, 0, 0, 8, lay_n, lay_tp, slo)    # reference TP2: four instances per node
     assert r2["nodes"][:, 0].tolist() == [int(np.ceil(300.0 / (4 * cap))), int(np.ceil(600.0 / (4 * cap)))]
+
+
+def _own_loads(coarse, NW, G, W):
+    o = coarse["cell_off"]
+    tok = np.concatenate([[0], np.cumsum(coarse["in_tok"].astype(np.int64) + coarse["out_tok"])])
+    return ((tok[o[1:]] - tok[o[:-1]]) / W).reshape(NW, G)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_hierarchy_with_spill_against_numpy(seed):
+    """Section IV-B "Handling fragmentation", three and four classes so that forwarded load is forwarded again."""
+    G = 3 + seed % 2
+    prof, tr, edges, slo, lay_n, lay_tp, NW, T, tick = _hier_case(40 + seed, R=900, G=G)
+    prof = dict(prof)
+    prof["max_load_tps"] = prof["max_load_tps"] * 0.25       # pools of a few nodes each
+    coarse = oracle.ingest(tr, edges, NW, T * tick); fine = oracle.ingest(tr, edges, NW * T, tick)
+    f_ref = prof["f_mhz"].size - 1
+    a = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 2, 2, f_ref, 8, lay_n, lay_tp, slo, spill=True)
+    b = npcheck.np_hierarchy(prof, tr, edges, NW, T, tick, 2, 2, f_ref, 8, lay_n, lay_tp, slo, spill=True)
+    for k in ("nodes", "layout_sel", "f_sel", "violations"):
+        np.testing.assert_array_equal(a[k], b[k], err_msg=k)
+    np.testing.assert_allclose(a["keep"], b["keep"], rtol=1e-14)
+    np.testing.assert_allclose(a["served"], b["served"], rtol=1e-13)
+    fin = np.isfinite(b["energy_j"])
+    assert (np.isfinite(a["energy_j"]) == fin).all() and fin.any()
+    np.testing.assert_allclose(a["energy_j"][fin], b["energy_j"][fin], rtol=1e-12)
+    plain = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 2, 2, f_ref, 8, lay_n, lay_tp, slo)
+    assert (a["keep"] < 1.0).any() and (a["nodes"] != plain["nodes"]).any()    # the rule did something here
+    # what the rule promises: load is moved, not lost; only the last class rounds up; no pool is driven beyond the
+    # capacity of its nodes at the reference configuration, and a pool that gave load away is full at its peak
+    own = _own_loads(coarse, NW, G, T * tick)
+    np.testing.assert_allclose(a["served"].reshape(NW, G).sum(axis=1), own.sum(axis=1), rtol=1e-12)
+    assert (a["keep"][:, -1] == 1.0).all() and (a["keep"] > 0.0).all() and (a["keep"] <= 1.0).all()
+    assert (plain["keep"] == 1.0).all() and np.array_equal(plain["served"].reshape(NW, G), own)
+    cap = prof["max_load_tps"][:, 2, f_ref] * prof["rho"][-1]
+    for e in range(a["nodes"].shape[0]):
+        peak = a["served"].reshape(NW, G)[2 * e:2 * e + 2].max(axis=0)
+        assert (peak <= a["nodes"][e] * cap).all()
+        gave = a["keep"][e] < 1.0
+        np.testing.assert_allclose(peak[gave], (a["nodes"][e] * cap)[gave], rtol=1e-11)
+        # ... and the reference layout on those nodes is inside the profiled load range in every window
+        assert (peak / (a["nodes"][e] * prof["max_load_tps"][:, 2, f_ref]) <= prof["rho"][-1]).all()
+    assert a["nodes"].sum() <= plain["nodes"].sum()
+
+
+def test_hierarchy_spill_on_known_loads():
+    """Loads in closed form: capacities of 100 tokens/s per node, pools arriving at 250, 120 + 50 and 60 + 70 tokens/s
+    get 2, 1 and (last class, rounded up) 2 nodes instead of 3, 2 and 1."""
+    prof, _, _, slo, lay_n, lay_tp, _, _, _ = _hier_case(0, G=3)
+    prof = dict(prof)
+    prof["max_load_tps"] = np.full_like(prof["max_load_tps"], 100.0 / prof["rho"][-1])
+    edges = {"in_edge": np.asarray([[200, 400]], np.int32), "out_edge": np.zeros((1, 0), np.int32)}
+    NW, T, tick = 4, 2, 10.0
+    ts, ins = [], []
+    for w in range(NW):
+        for n, x in ((25, 100), (6, 300), (2, 500)):       # 25 x 200, 6 x 400, 2 x 600 tokens per 20 s
+            ts += [w * 20.0 + 0.5] * n; ins += [x] * n
+    tr = {"t_s": np.asarray(ts), "in_tok": np.asarray(ins, np.int32), "out_tok": np.full(len(ts), 100, np.int32),
+          "model": np.zeros(len(ts), np.int32)}
+    coarse = oracle.ingest(tr, edges, NW, T * tick); fine = oracle.ingest(tr, edges, NW * T, tick)
+    np.testing.assert_array_equal(_own_loads(coarse, NW, 3, 20.0), [[250.0, 120.0, 60.0]] * NW)
+    plain = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 2, 2, 0, 8, lay_n, lay_tp, slo)
+    r = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 2, 2, 0, 8, lay_n, lay_tp, slo, spill=True)
+    assert plain["nodes"].tolist() == [[3, 2, 1]] * 2 and r["nodes"].tolist() == [[2, 1, 2]] * 2
+    np.testing.assert_allclose(r["keep"], [[200 / 250, 100 / 170, 1.0]] * 2, rtol=1e-11)
+    np.testing.assert_allclose(r["served"].reshape(NW, 3), [[200.0, 100.0, 130.0]] * NW, rtol=1e-11)
+
+
+def test_hierarchy_spill_without_a_full_node_changes_nothing():
+    """A pool that needs less than one node keeps it, and a pool that fills its nodes exactly has nothing left over."""
+    prof, tr, edges, slo, lay_n, lay_tp, NW, T, tick = _hier_case(3, G=3)
+    prof = dict(prof)
+    prof["max_load_tps"] = prof["max_load_tps"] * 1e3
+    coarse = oracle.ingest(tr, edges, NW, T * tick); fine = oracle.ingest(tr, edges, NW * T, tick)
+    a = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 2, 2, 0, 8, lay_n, lay_tp, slo)
+    b = oracle.hierarchy(prof, coarse, fine, NW, T, tick, 2, 2, 0, 8, lay_n, lay_tp, slo, spill=True)
+    assert (a["nodes"] == 1).all()
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k], err_msg=k)
 
 
 def test_hierarchy_with_one_tick_and_one_frequency_is_the_window_level_selection(small_hour):
