@@ -9,7 +9,7 @@ dyn_eval_space followed by dyn_select_config instead.  Ingestion and profile upl
 timed separately.  Other entry points have modes of their own, each on the same workload and
 with the same JSON line: --ticks T (load followed tick by tick inside a window), --mixed S
 (pools that mix TP degrees), --path (selection with transition overheads between windows),
---hierarchy T [--overheads] (the three controllers top down).
+--hierarchy T [--overheads] [--spill] (the three controllers top down).
 
 Prints one JSON line.  `value` = requests x configurations / step time.
 """
@@ -60,12 +60,12 @@ def cpu_baseline(w, n_sample_windows, ticks=0, mixed=None, path=None, hier=None)
     sub = {k: v[:hi] for k, v in tr.items()}
     k = w["configs"]["n_inst"].size
     if hier:
-        T, epoch, tp_ref, f_ref, gpn, lay_n, lay_tp, trans, k = hier
+        T, epoch, tp_ref, f_ref, gpn, lay_n, lay_tp, trans, spill, k = hier
         st = oracle.ingest(sub, w["edges"], n_sample_windows, w["window_s"])
         fine = oracle.ingest(sub, w["edges"], n_sample_windows * T, w["window_s"] / T)
         t0 = time.perf_counter()
         oracle.hierarchy(w["profile"], st, fine, n_sample_windows, T, w["window_s"] / T, epoch, tp_ref, f_ref, gpn, lay_n, lay_tp,
-                         w["slos"], w["pct"], transition=trans)
+                         w["slos"], w["pct"], transition=trans, spill=spill)
     elif mixed:
         n_share, n_max, budget, k = mixed
         st = oracle.ingest(sub, w["edges"], n_sample_windows, w["window_s"])
@@ -116,6 +116,11 @@ def main():
                          "--epoch-windows windows, 8-GPU nodes, layouts = the (instances, TP) pairs of the workload's "
                          "configurations, reference = the largest TP at the highest frequency")
     ap.add_argument("--epoch-windows", type=int, default=6)
+    ap.add_argument("--spill", action="store_true",
+                    help="with --hierarchy: the scale-out controller applies the fragmentation rule; the profile's "
+                         "capacities are scaled so that the busiest pool needs --peak-nodes nodes (the generated "
+                         "profile leaves most pools below one node, where the rule has nothing to do)")
+    ap.add_argument("--peak-nodes", type=float, default=6.5)
     ap.add_argument("--overheads", action="store_true",
                     help="with --hierarchy: the shard controller weighs re-sharding overheads (2 %% of the median window "
                          "energy per GPU of difference between two layouts)")
@@ -175,6 +180,13 @@ def main():
     assert dyn.dyn_workspace_status(ws_ing) == 0
     if args.hierarchy:                      # the controllers also need the window-level order
         coarse = dyn.dyn_trace_ingest(t_s, x, y, mdl, w["edges"], NW, w["window_s"])[:3]
+        if args.spill:                      # size the synthetic node capacities to pools of several nodes
+            tok = torch.cat([torch.zeros(1, dtype=torch.int64, device="cuda"), torch.cumsum(coarse[0].long() + coarse[1].long(), 0)])
+            load = ((tok[coarse[2][1:]] - tok[coarse[2][:-1]]).double() / w["window_s"]).reshape(NW, G).cpu().numpy()
+            P = dict(w["profile"])
+            cap = P["max_load_tps"][:, -1, -1] * P["rho"][-1]
+            P["max_load_tps"] = P["max_load_tps"] * float((load / cap).max() / args.peak_nodes)
+            w["profile"] = P
     del t_s, x, y, mdl, ws_ing
     t0 = time.perf_counter()
     prof = dyn.dyn_profile_load(w["profile"])
@@ -203,6 +215,7 @@ def main():
         K = int(lay_n.size) + n_f           # candidates looked at per request: layouts per window + frequencies per tick
         ws = torch.empty(dyn.dyn_hierarchy_workspace(NW, T, G, lay_n.size), dtype=torch.uint8, device="cuda")
         hout, _ = dyn.dyn_hierarchy(prof, coarse, (ins, outs, off), NW, T, len_s, *hier_args[1:], w["slos"], w["pct"], workspace=ws)
+        nodes_plain = int(hout["nodes"].sum().item())
         hout["window_energy_j"], hout["window_infeasible"] = sel["window_energy_j"], sel["window_infeasible"]
         hier_trans = None
         if args.overheads:
@@ -213,7 +226,7 @@ def main():
 
         def step():
             dyn.dyn_hierarchy(prof, coarse, (ins, outs, off), NW, T, len_s, *hier_args[1:], w["slos"], w["pct"], out=hout,
-                              workspace=ws, transition_j=hier_trans)
+                              workspace=ws, transition_j=hier_trans, spill=args.spill)
     elif args.path:
         assert not args.ticks and not args.mixed, "--path, --mixed and --ticks are separate modes"
         cfgs = w["configs"]
@@ -364,7 +377,7 @@ def main():
         "config": {"workload": f"configs[{args.config}] {spec.name}: {R} requests, {NW} windows x {G} classes = "
                                f"{cells} cells, {K} configurations", "requests": R, "cells": cells, "configs": K,
                    "ticks_per_window": args.ticks or args.hierarchy, "mixed_shares": args.mixed,
-                   "entry_points": ("dyn_hierarchy+overheads" if args.overheads else "dyn_hierarchy") if args.hierarchy else "dyn_eval_space+dyn_select_path" if args.path else "dyn_eval_select_mixed" if args.mixed else "dyn_eval_select_ticks" if args.ticks else
+                   "entry_points": ("dyn_hierarchy" + ("+overheads" if args.overheads else "") + ("+spill" if args.spill else "")) if args.hierarchy else "dyn_eval_space+dyn_select_path" if args.path else "dyn_eval_select_mixed" if args.mixed else "dyn_eval_select_ticks" if args.ticks else
                                    "dyn_eval_space+dyn_select_config" if args.unfused else "dyn_eval_select"},
         "roofline": roofline,
         "kernel_ms": ktime, "ms_per_step_with_kernel_events": ms_per_step_events,
@@ -373,13 +386,18 @@ def main():
                   "ingest_requests_per_s": R / (ingest_ms * 1e-3)},
         "result": {"workspace_status": status, "cells_without_feasible_config": int((sel_h < 0).sum()), "total_energy_wh": float(we.sum() / 3600.0)},
     }
+    if args.hierarchy:
+        out["result"]["nodes_over_all_epochs"] = int(hout["nodes"].sum().item())
+        if args.spill:
+            out["result"]["nodes_without_the_fragmentation_rule"] = nodes_plain
+            out["config"]["peak_nodes"] = args.peak_nodes
     if not args.no_cpu_baseline:
         nwin = args.cpu_windows or max(1, min(NW, int(NW * (5.0e9 if args.mixed else 1.5e9 if args.path else 1.0e10) / (R * K))))
         mixed = (args.mixed, n_max, np.full(G, args.mixed_gpus, np.int32), K) if args.mixed else None
         if args.hierarchy:
             nwin = args.cpu_windows or NW
         out["cpu_baseline"] = cpu_baseline(w, nwin, args.ticks, mixed, (lay, trans) if args.path else None,
-                                           hier_args + (hier_trans, K) if args.hierarchy else None)
+                                           hier_args + (hier_trans, args.spill, K) if args.hierarchy else None)
         out["cpu_baseline"]["host_cores"] = os.cpu_count()
     prof.free()
     print(json.dumps(out))

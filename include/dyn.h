@@ -377,6 +377,18 @@ int dyn_account(dyn_profile* profile, const int32_t* sel, const double* window_e
  *     that class's total of energies and overheads.  Where several sequences reach the least
  *     total any one of them is returned.  Limits as for dyn_select_path with K = n_layout.
  *     NULL: every window takes its own least-energy layout and path_cost is not written.
+ *   With controllers->spill != 0 (Section IV-B "Handling fragmentation"): a pool whose peak does
+ *     not fill its last node gets that node less and the load its other nodes cannot carry is
+ *     forwarded to the pool of the next class (classes are taken to be ordered by request
+ *     size); only the last class rounds up.  Per epoch, classes ascending: arriving load of a
+ *     window A = own load + what the class below forwards, PL = peak of A, q = PL / ML.  If the
+ *     class is not the last and 1 <= floor(q) < q: nodes = floor(q) and the pool serves the
+ *     fraction keep = ((floor(q) * ML) / PL) * (1 - 2^-40) of what arrives (the last factor
+ *     keeps the peak window inside the profiled load range whatever the later roundings);
+ *     otherwise nodes = ceil(q), at least 1, and keep = 1.  Served load S = keep * A in every
+ *     window and every tick of the epoch, forwarded load = A - S.  The shard and frequency
+ *     controllers see S; percentiles stay those of the pool's own requests.  out->keep
+ *     (DEVICE [n_epoch][G], may be NULL) receives the fractions; it is not written without spill.
  * `coarse` is the trace sorted by window (n_window windows of n_tick * tick_s seconds), `fine`
  * the same requests sorted by tick (n_window * n_tick windows of tick_s seconds), both as
  * dyn_trace_ingest returns them.  lay_n / lay_tp_index HOST [n_layout].  Outputs DEVICE.
@@ -387,6 +399,7 @@ typedef struct {
   int32_t tp_ref_index, f_ref_index;
   int32_t gpus_per_node;
   int32_t n_layout;
+  int32_t spill;              /* != 0: the fragmentation rule */
   const int32_t* lay_n;
   const int32_t* lay_tp_index;
   const double* transition_j; /* HOST [n_layout][n_layout] or NULL */
@@ -400,6 +413,7 @@ typedef struct {
   double* window_energy_j;    /* [n_window] */
   int32_t* window_infeasible; /* [n_window] */
   double* path_cost;          /* [G], only with transition_j; may be NULL without */
+  double* keep;               /* [n_epoch][G], only with spill; may be NULL                */
 } dyn_hierarchy_out;
 size_t dyn_hierarchy_workspace(int32_t n_window, int32_t n_tick, int32_t n_class, int32_t n_layout);
 int dyn_hierarchy(dyn_profile* profile, const dyn_trace_view* coarse, const dyn_trace_view* fine,

@@ -104,12 +104,12 @@ class _Accounting(C.Structure):
 
 class _Controllers(C.Structure):
     _fields_ = [("epoch_windows", _i32), ("tp_ref_index", _i32), ("f_ref_index", _i32), ("gpus_per_node", _i32),
-                ("n_layout", _i32), ("lay_n", _vp), ("lay_tp_index", _vp), ("transition_j", _vp)]
+                ("n_layout", _i32), ("spill", _i32), ("lay_n", _vp), ("lay_tp_index", _vp), ("transition_j", _vp)]
 
 
 class _HierarchyOut(C.Structure):
     _fields_ = [("nodes", _vp), ("layout_sel", _vp), ("f_sel", _vp), ("energy_j", _vp), ("violations", _vp),
-                ("window_energy_j", _vp), ("window_infeasible", _vp), ("path_cost", _vp)]
+                ("window_energy_j", _vp), ("window_infeasible", _vp), ("path_cost", _vp), ("keep", _vp)]
 
 
 _lib.dyn_last_error.restype = C.c_char_p
@@ -559,10 +559,11 @@ def dyn_hierarchy_workspace(n_window: int, n_tick: int, n_class: int, n_layout: 
 def dyn_hierarchy(profile: Profile, coarse, fine, n_window: int, n_tick: int, tick_s: float, epoch_windows: int,
                   tp_ref_index: int, f_ref_index: int, gpus_per_node: int, lay_n, lay_tp_index, slos, pct=(99, 100),
                   out: Optional[Dict[str, torch.Tensor]] = None, workspace: Optional[torch.Tensor] = None, stream=None,
-                  transition_j=None):
+                  transition_j=None, spill: bool = False):
     """The three controllers top down.  `coarse` / `fine` are (in_tok, out_tok, cell_off) tensor triples of the trace
     sorted by window and by tick.  `transition_j` ([n_layout][n_layout] joules, host) makes the shard controller weigh
-    re-sharding overheads (out["path_cost"] is then filled).  Returns (dict of output tensors, workspace)."""
+    re-sharding overheads (out["path_cost"] is then filled); `spill` applies the fragmentation rule (out["keep"] is
+    then filled).  Returns (dict of output tensors, workspace)."""
     G = profile.n_class
     cells = n_window * G
     ci, co_, coff = coarse
@@ -586,11 +587,15 @@ def dyn_hierarchy(profile: Profile, coarse, fine, n_window: int, n_tick: int, ti
            "window_infeasible": torch.empty(n_window, dtype=torch.int32, device=dev)}
     if tj is not None and "path_cost" not in out:
         out["path_cost"] = torch.empty(G, dtype=torch.float64, device=dev)
+    if spill and "keep" not in out:
+        out["keep"] = torch.empty((n_epoch, G), dtype=torch.float64, device=dev)
     want = {"nodes": (n_epoch * G, torch.int32), "layout_sel": (cells, torch.int32), "f_sel": (cells * n_tick, torch.int32),
             "energy_j": (cells, torch.float64), "violations": (cells, torch.int32),
             "window_energy_j": (n_window, torch.float64), "window_infeasible": (n_window, torch.int32)}
     if tj is not None:
         want["path_cost"] = (G, torch.float64)
+    if spill:
+        want["keep"] = (n_epoch * G, torch.float64)
     for k, (n, dt) in want.items():
         if out[k].numel() != n or out[k].dtype != dt:
             raise ValueError(f"out[{k!r}] must hold {n} elements of {dt}")
@@ -599,10 +604,10 @@ def dyn_hierarchy(profile: Profile, coarse, fine, n_window: int, n_tick: int, ti
     obj, keep = _objective(slos, pct, None, 0.0)
     tc = _TraceView(ci.numel(), n_window, float(tick_s) * n_tick, _dp(ci, torch.int32), _dp(co_, torch.int32), _dp(coff, torch.int64))
     tf = _TraceView(fi.numel(), n_window * n_tick, float(tick_s), _dp(fi, torch.int32), _dp(fo_, torch.int32), _dp(foff, torch.int64))
-    ctl = _Controllers(int(epoch_windows), int(tp_ref_index), int(f_ref_index), int(gpus_per_node), int(ln.size), _hp(ln), _hp(lt),
-                       _hp(tj))
+    ctl = _Controllers(int(epoch_windows), int(tp_ref_index), int(f_ref_index), int(gpus_per_node), int(ln.size),
+                       1 if spill else 0, _hp(ln), _hp(lt), _hp(tj))
     ho = _HierarchyOut(*[_dp(out[k]) for k in ("nodes", "layout_sel", "f_sel", "energy_j", "violations", "window_energy_j",
-                                               "window_infeasible")], _dp(out.get("path_cost")))
+                                               "window_infeasible")], _dp(out.get("path_cost")), _dp(out.get("keep") if spill else None))
     _check(_lib.dyn_hierarchy(profile.handle, C.byref(tc), C.byref(tf), n_tick, C.byref(ctl), C.byref(obj), C.byref(ho),
                               _dp(workspace), workspace.numel(), _stream(stream)), "dyn_hierarchy")
     return out, workspace

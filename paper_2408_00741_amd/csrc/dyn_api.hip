@@ -894,7 +894,7 @@ namespace {
 struct HierWs {
   EvalWs coarse;                 // header .. cstat of the window-level aggregation (first: its header is the workspace's)
   size_t fine_base; EvalWs fine; // the tick-level aggregation, offsets relative to fine_base
-  size_t tp, lay_n, lay_tp, tick_energy, tick_viol, lay_energy, lay_flags, sel_energy, path, total;
+  size_t tp, lay_n, lay_tp, tick_energy, tick_viol, served_c, served_f, keep, fwd, lay_energy, lay_flags, sel_energy, path, total;
 };
 HierWs hier_ws_layout(int64_t cells, int32_t n_tick, int32_t n_tp, int32_t n_layout) {
   HierWs w;
@@ -908,6 +908,11 @@ HierWs hier_ws_layout(int64_t cells, int32_t n_tick, int32_t n_tp, int32_t n_lay
   w.lay_tp = off; off += align256((size_t)n_layout * 4);
   w.tick_energy = off; off += align256(c * n_tick * 8);
   w.tick_viol = off; off += align256(c * n_tick);
+  // only used with the fragmentation rule (keep holds at most one entry per cell)
+  w.served_c = off; off += align256(c * 8);
+  w.served_f = off; off += align256(c * n_tick * 8);
+  w.keep = off; off += align256(c * 8);
+  w.fwd = off; off += align256(c * 8);
   // only used with a transition table: the layouts' space and the sequence selection's own workspace
   w.lay_energy = off; off += align256(c * n_layout * 8);
   w.lay_flags = off; off += align256(c * n_layout);
@@ -1002,6 +1007,12 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
   a.lay_energy = c->transition_j ? (double*)(base + w.lay_energy) : nullptr;
   a.lay_flags = c->transition_j ? (uint8_t*)(base + w.lay_flags) : nullptr;
   a.tick_energy = (double*)(base + w.tick_energy); a.tick_viol = (uint8_t*)(base + w.tick_viol);
+  a.served_c = a.served_f = a.keep = a.fwd = nullptr;
+  if (c->spill) {
+    a.served_c = (double*)(base + w.served_c); a.served_f = (double*)(base + w.served_f);
+    a.keep = out->keep ? out->keep : (double*)(base + w.keep); a.fwd = (double*)(base + w.fwd);
+    if (!hip_ok(dyn_launch_hier_spill(a, s), "hierarchy launch")) return DYN_E_DEVICE;
+  }
   if (!hip_ok(dyn_launch_hier_shard(a, p->single_point, s), "hierarchy launch")) return DYN_E_DEVICE;
   if (c->transition_j) {        // the windows' layouts chosen together; overwrites layout_sel
     PathArgs pa;

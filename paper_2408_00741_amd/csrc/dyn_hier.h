@@ -28,7 +28,14 @@ struct HierArgs {
   uint8_t* lay_flags;           // workspace [cells][n_layout]: DYN_F_FEASIBLE where the layout fits and meets the SLO
   double* tick_energy;          // workspace [fine cells]
   uint8_t* tick_viol;           // workspace [fine cells]
+  // fragmentation rule (all NULL without it): loads the pools serve after forwarding, kept fractions
+  double* served_c;             // workspace [cells]
+  double* served_f;             // workspace [fine cells]
+  double* keep;                 // [n_epoch][G]
+  double* fwd;                  // workspace [n_window]: load forwarded to the class in hand
 };
+// fragmentation rule: node counts, kept fractions and served loads of every window and tick (before the shard level)
+hipError_t dyn_launch_hier_spill(const HierArgs& a, hipStream_t s);
 // window level: node counts, per-window layouts and (lay_energy != NULL) every layout's energy and admissibility
 hipError_t dyn_launch_hier_shard(const HierArgs& a, bool single_point, hipStream_t s);
 // tick level: frequencies under layout_sel, energies, window totals

@@ -8,11 +8,16 @@
 //                       SLO under the tick's load (the reference frequency, counted, if none does);
 //   hier_sum_kernel     energy of a (window, class) = its ticks' energies added in time order; window
 //                       totals = the classes' energies added in class order.
+//   hier_spill_*        (fragmentation rule only) before the others: per epoch, classes in ascending order,
+//                       the node counts, the fraction of its arriving load every pool keeps and the loads the
+//                       pools serve in every window and tick once the rest has been forwarded to the next class.
 // The tables stay in global memory (they are a few hundred KB and live in L2; copying a class's tables
 // to LDS per block was measured to cost more than the look-ups it serves).  Two things matter instead:
 // threads of a block share the class, so that a wave's gathers fall into a few table rows, and the
 // frequency kernel takes its look-ups four at a time, level by level (capacity -> bucket -> grid points
 // and table values), so that a thread waits for three rounds of loads per four frequencies, not twelve.
+#include <algorithm>
+
 #include "dyn_hier.h"
 #include "dyn_device.h"
 
@@ -21,6 +26,8 @@ namespace {
 constexpr int kShardWaves = 4;          // (window, class) cells per block of the shard kernel, one wave each
 constexpr int kFreqThreads = 256;
 constexpr int kFreqChunk = 4;           // look-ups a thread of the frequency kernel has in flight
+constexpr int kSpillLds = 48 * 1024;    // an epoch's window loads are staged in LDS when they fit in this
+constexpr int kSpillRun = 8;            // classes whose tick loads a thread fetches ahead of the chain
 
 struct Looked { double pf, tb, pw; bool ov; };
 
@@ -70,6 +77,21 @@ __device__ __forceinline__ double wave_max_f64(double v) {
   return v;
 }
 
+// Largest value of each row of 16 lanes, in all of the row's lanes (rotations by 1, 2, 4 and 8 lanes).
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+  const uint64_t u = (uint64_t)__double_as_longlong(v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, CTRL, 0xF, 0xF, false);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), CTRL, 0xF, 0xF, false);
+  return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+__device__ __forceinline__ double row_max_f64(double v) {
+  v = fmax(v, dpp_f64<0x121>(v));
+  v = fmax(v, dpp_f64<0x122>(v));
+  v = fmax(v, dpp_f64<0x124>(v));
+  return fmax(v, dpp_f64<0x128>(v));
+}
+
 // One wave per (window, class); lanes stride the layouts; the lowest index wins equal energies.
 template <bool SINGLE>
 __global__ __launch_bounds__(kShardWaves* DYN_WAVE) void hier_shard_kernel(HierArgs a) {
@@ -82,14 +104,21 @@ __global__ __launch_bounds__(kShardWaves* DYN_WAVE) void hier_shard_kernel(HierA
   // scale-out/in: the epoch's peak load over the capacity of one node at the reference configuration
   const int e = w / a.epoch_windows;
   const int e0 = e * a.epoch_windows, e1 = min(a.n_window, e0 + a.epoch_windows);
-  double peak = 0.0;
-  for (int i = e0 + lane; i < e1; i += DYN_WAVE) peak = fmax(peak, a.rec_c[(size_t)i * a.G + g].load);
-  peak = wave_max_f64(peak);
-  const int inst = max(1, a.gpus_per_node / a.tp[a.tp_ref]);
-  const double ml_node = ((double)inst * a.ml[((size_t)g * a.n_tp + a.tp_ref) * a.n_f + a.f_ref]) * a.gridpack[a.n_rho];
-  const double q = ceil(peak / ml_node);
-  const int32_t nodes = q < 1.0 ? 1 : (q > 2147483647.0 ? 2147483647 : (int32_t)q);
-  if (w == e0 && lane == 0) a.nodes[(size_t)e * a.G + g] = nodes;
+  int32_t nodes;
+  double load = rec.load;
+  if (a.served_c) {                                          // fragmentation rule: both come from the spill kernels
+    nodes = a.nodes[(size_t)e * a.G + g];
+    load = a.served_c[cell];
+  } else {
+    double peak = 0.0;
+    for (int i = e0 + lane; i < e1; i += DYN_WAVE) peak = fmax(peak, a.rec_c[(size_t)i * a.G + g].load);
+    peak = wave_max_f64(peak);
+    const int inst = max(1, a.gpus_per_node / a.tp[a.tp_ref]);
+    const double ml_node = ((double)inst * a.ml[((size_t)g * a.n_tp + a.tp_ref) * a.n_f + a.f_ref]) * a.gridpack[a.n_rho];
+    const double q = ceil(peak / ml_node);
+    nodes = q < 1.0 ? 1 : (q > 2147483647.0 ? 2147483647 : (int32_t)q);
+    if (w == e0 && lane == 0) a.nodes[(size_t)e * a.G + g] = nodes;
+  }
   const int64_t budget = (int64_t)nodes * a.gpus_per_node;
   // shard-up/down at the reference frequency
   const double slo_t = a.slo_ttft[g], slo_b = a.slo_tbt[g];
@@ -100,7 +129,7 @@ __global__ __launch_bounds__(kShardWaves* DYN_WAVE) void hier_shard_kernel(HierA
     bool ok = (int64_t)n * a.tp[ti] <= budget;
     double en = __builtin_inf();
     if (ok) {
-      const Looked r = look_up<SINGLE>(a, g, ti, a.f_ref, rec.load, (double)n);
+      const Looked r = look_up<SINGLE>(a, g, ti, a.f_ref, load, (double)n);
       ok = !(r.ov || rec.xp99 * r.pf > slo_t || r.tb * rec.nonempty > slo_b);
       en = ((double)n * r.pw) * a.window_s;
     }
@@ -137,6 +166,7 @@ __global__ __launch_bounds__(kFreqThreads) void hier_freq_kernel(HierArgs a) {
     return;
   }
   const CellRec rec = a.rec_f[f];
+  const double load = a.served_f ? a.served_f[f] : rec.load;
   const int n = a.lay_n[l], ti = a.lay_tp[l];
   const double nd = (double)n;
   const double slo_t = a.slo_ttft[g], slo_b = a.slo_tbt[g];
@@ -152,7 +182,7 @@ __global__ __launch_bounds__(kFreqThreads) void hier_freq_kernel(HierArgs a) {
 #pragma unroll
     for (int c = 0; c < kFreqChunk; ++c) {                   // level 1: capacities
       const int fi = min(f0 + c, a.n_f - 1);
-      const double rho = rec.load / (nd * a.ml[row0 + fi]);
+      const double rho = load / (nd * a.ml[row0 + fi]);
       ov[c] = rho > rho_max;
       rc[c] = ov[c] ? rho_max : rho;
     }
@@ -179,6 +209,120 @@ __global__ __launch_bounds__(kFreqThreads) void hier_freq_kernel(HierArgs a) {
   a.f_sel[f] = bf;
   a.tick_energy[f] = (nd * bp) * a.tick_s;
   a.tick_viol[f] = viol;
+}
+
+// Fragmentation rule, window level.  One wave per epoch, lanes stride the epoch's windows, classes one after the
+// other: what a class forwards arrives at the next.  STAGED (at most one window per lane and the epoch's loads fit in
+// LDS): loads and node capacities are copied to LDS up front, the forwarded load stays in a register and the results
+// per class are collected in LDS, so the chain over the classes waits for LDS and a short wave reduction per class,
+// never for global memory.
+template <bool STAGED>
+__global__ __launch_bounds__(DYN_WAVE) void hier_spill_epoch_kernel(HierArgs a) {
+  extern __shared__ double s_spill[];                        // STAGED: loads [windows of the epoch][G], capacity, its reciprocal, keep [G] each, nodes [G]
+  const int e = blockIdx.x, lane = threadIdx.x;
+  const int e0 = e * a.epoch_windows, e1 = min(a.n_window, e0 + a.epoch_windows);
+  const int G = a.G;
+  const int inst = max(1, a.gpus_per_node / a.tp[a.tp_ref]);
+  const double rho_max = a.gridpack[a.n_rho];
+  const double guard = 1.0 - 0x1p-40;
+  double* s_load = s_spill;
+  double* s_cap = s_spill + (size_t)min(a.epoch_windows, a.n_window) * G;
+  double* s_rcap = s_cap + G;                                // RN(1 / capacity)
+  double* s_keep = s_rcap + G;
+  int32_t* s_nodes = (int32_t*)(s_keep + G);
+  if (STAGED) {
+    for (int i = lane; i < (e1 - e0) * G; i += DYN_WAVE) s_load[i] = a.rec_c[(size_t)e0 * G + i].load;
+    for (int g = lane; g < G; g += DYN_WAVE) {
+      s_cap[g] = ((double)inst * a.ml[((size_t)g * a.n_tp + a.tp_ref) * a.n_f + a.f_ref]) * rho_max;
+      s_rcap[g] = 1.0 / s_cap[g];
+    }
+    __syncthreads();
+  } else {
+    for (int i = e0 + lane; i < e1; i += DYN_WAVE) a.fwd[i] = 0.0;
+  }
+  const bool mine = e0 + lane < e1;                          // STAGED: this lane's window
+  double fwd = 0.0;
+  for (int g = 0; g < G; ++g) {
+    double arrive = 0.0, peak = 0.0, ml_node;
+    if (STAGED) {
+      if (mine) arrive = s_load[lane * G + g] + fwd;
+      peak = row_max_f64(arrive);                            // lanes without a window hold 0
+      if (e1 - e0 > 16) peak = fmax(peak, __shfl_xor(peak, 16, DYN_WAVE));
+      if (e1 - e0 > 32) peak = fmax(peak, __shfl_xor(peak, 32, DYN_WAVE));
+      ml_node = s_cap[g];
+    } else {
+      for (int i = e0 + lane; i < e1; i += DYN_WAVE) peak = fmax(peak, a.rec_c[(size_t)i * G + g].load + a.fwd[i]);
+      peak = wave_max_f64(peak);
+      ml_node = ((double)inst * a.ml[((size_t)g * a.n_tp + a.tp_ref) * a.n_f + a.f_ref]) * rho_max;
+    }
+    const double q = STAGED ? div_by(peak, ml_node, s_rcap[g]) : peak / ml_node;
+    const double fl = floor(q);
+    double keep = 1.0;
+    int32_t nodes;
+    if (g < G - 1 && fl >= 1.0 && fl < q && fl < 2147483647.0) {
+      nodes = (int32_t)fl;
+      keep = ((fl * ml_node) / peak) * guard;
+    } else {
+      const double up = ceil(q);
+      nodes = up < 1.0 ? 1 : (up > 2147483647.0 ? 2147483647 : (int32_t)up);
+    }
+    if (STAGED) {
+      if (lane == 0) { s_nodes[g] = nodes; s_keep[g] = keep; }
+      if (mine) {
+        const double served = keep * arrive;
+        s_load[lane * G + g] = served;
+        fwd = arrive - served;
+      }
+    } else {
+      if (lane == 0) {
+        a.nodes[(size_t)e * G + g] = nodes;
+        a.keep[(size_t)e * G + g] = keep;
+      }
+      for (int i = e0 + lane; i < e1; i += DYN_WAVE) {
+        const double arr = a.rec_c[(size_t)i * G + g].load + a.fwd[i];
+        const double served = keep * arr;
+        a.served_c[(size_t)i * G + g] = served;
+        a.fwd[i] = arr - served;                             // read again by this lane only
+      }
+    }
+  }
+  if (STAGED) {
+    __syncthreads();
+    for (int i = lane; i < (e1 - e0) * G; i += DYN_WAVE) a.served_c[(size_t)e0 * G + i] = s_load[i];
+    for (int g = lane; g < G; g += DYN_WAVE) {
+      a.nodes[(size_t)e * G + g] = s_nodes[g];
+      a.keep[(size_t)e * G + g] = s_keep[g];
+    }
+  }
+}
+
+// Fragmentation rule, tick level: one thread per tick walks the classes with the kept fractions of the tick's epoch;
+// the loads of kSpillRun classes are fetched together, ahead of the chain that links them.
+__global__ __launch_bounds__(DYN_WAVE) void hier_spill_tick_kernel(HierArgs a) {
+  const int64_t wt = (int64_t)blockIdx.x * DYN_WAVE + threadIdx.x;
+  if (wt >= (int64_t)a.n_window * a.n_tick) return;
+  const int e = (int)(wt / a.n_tick) / a.epoch_windows;
+  const double* keep = a.keep + (size_t)e * a.G;
+  const CellRec* rec = a.rec_f + (size_t)wt * a.G;
+  double* served_f = a.served_f + (size_t)wt * a.G;
+  double fwd = 0.0;
+  for (int g0 = 0; g0 < a.G; g0 += kSpillRun) {
+    double own[kSpillRun], k[kSpillRun];
+#pragma unroll
+    for (int c = 0; c < kSpillRun; ++c) {
+      const int g = min(g0 + c, a.G - 1);
+      own[c] = rec[g].load;
+      k[c] = keep[g];
+    }
+#pragma unroll
+    for (int c = 0; c < kSpillRun; ++c) {
+      if (g0 + c >= a.G) break;
+      const double arr = own[c] + fwd;
+      const double served = k[c] * arr;
+      served_f[g0 + c] = served;
+      fwd = arr - served;
+    }
+  }
 }
 
 // One block per window: thread g adds the ticks of (window, g) in time order; thread 0 then adds the
@@ -214,6 +358,18 @@ __global__ __launch_bounds__(64) void hier_sum_kernel(HierArgs a) {
 }
 
 }  // namespace
+
+hipError_t dyn_launch_hier_spill(const HierArgs& a, hipStream_t s) {
+  const int64_t ticks = (int64_t)a.n_window * a.n_tick;
+  const size_t lds = ((size_t)std::min(a.epoch_windows, a.n_window) * a.G + 3 * (size_t)a.G) * sizeof(double) + (size_t)a.G * sizeof(int32_t);
+  DynTimed timed(DYN_K_HIER, s);
+  if (a.epoch_windows <= DYN_WAVE && lds <= (size_t)kSpillLds)
+    hipLaunchKernelGGL(hier_spill_epoch_kernel<true>, dim3((unsigned)a.n_epoch), dim3(DYN_WAVE), lds, s, a);
+  else
+    hipLaunchKernelGGL(hier_spill_epoch_kernel<false>, dim3((unsigned)a.n_epoch), dim3(DYN_WAVE), 0, s, a);
+  hipLaunchKernelGGL(hier_spill_tick_kernel, dim3((unsigned)((ticks + DYN_WAVE - 1) / DYN_WAVE)), dim3(DYN_WAVE), 0, s, a);
+  return hipGetLastError();
+}
 
 hipError_t dyn_launch_hier_shard(const HierArgs& a, bool single_point, hipStream_t s) {
   const int64_t cells = (int64_t)a.n_window * a.G;

@@ -32,14 +32,14 @@ def _layouts(w, n_max):
 
 
 def gpu_hier(dyn, profile, tr, edges, n_window, n_tick, tick_s, epoch_windows, tp_ref, f_ref, gpn, lay_n, lay_tp, slos,
-             pct=(99, 100), transition=None):
+             pct=(99, 100), transition=None, spill=False):
     d = [_dev(tr[k]) for k in ("t_s", "in_tok", "out_tok", "model")]
     ci, co, coff, ws1 = dyn.dyn_trace_ingest(*d, edges, n_window, tick_s * n_tick)
     fi, fo, foff, ws2 = dyn.dyn_trace_ingest(*d, edges, n_window * n_tick, tick_s)
     assert dyn.dyn_workspace_status(ws1) == 0 and dyn.dyn_workspace_status(ws2) == 0
     prof = dyn.dyn_profile_load(profile)
     out, ws = dyn.dyn_hierarchy(prof, (ci, co, coff), (fi, fo, foff), n_window, n_tick, tick_s, epoch_windows, tp_ref, f_ref,
-                                gpn, lay_n, lay_tp, slos, pct, transition_j=transition)
+                                gpn, lay_n, lay_tp, slos, pct, transition_j=transition, spill=spill)
     status = dyn.dyn_workspace_status(ws)
     torch.cuda.synchronize()
     r = {k: v.cpu().numpy() for k, v in out.items()}
@@ -142,6 +142,62 @@ def test_random_overheads(dyn, seed):
     np.testing.assert_array_equal(g["path_cost"], o["path_cost"])
     assert_same(g, o, NW, 2)
     assert (g["layout_sel"] != plain["layout_sel"]).any() and (g["layout_sel"] < 0).any()
+
+
+def _node_capacity_for(w, T, nodes_at_peak):
+    """Profile of `w` with max_load_tps scaled so that the busiest (window, class) needs `nodes_at_peak` nodes: the
+    synthetic profiles leave most pools below one node, where the fragmentation rule has nothing to do."""
+    P = dict(w["profile"])
+    st = oracle.ingest(w["trace"], w["edges"], w["n_window"], w["window_s"])
+    o = st["cell_off"]
+    tok = np.concatenate([[0], np.cumsum(st["in_tok"].astype(np.int64) + st["out_tok"])])
+    load = ((tok[o[1:]] - tok[o[:-1]]) / w["window_s"]).reshape(w["n_window"], -1)
+    cap = P["max_load_tps"][:, -1, -1] * P["rho"][-1]
+    P["max_load_tps"] = P["max_load_tps"] * float((load / cap).max() / nodes_at_peak)
+    return P
+
+
+@pytest.mark.parametrize("name", ["cfg0-T12", "cfg0-T7-epoch1", "cfg1-60k-T12", "cfg2-300k-T12", "cfg4-250k-T6", "cfg2-day-T12"])
+def test_hierarchy_with_spill_matches_oracle(dyn, name):
+    """Section IV-B "Handling fragmentation": node counts, kept fractions and everything the lower controllers decide
+    under the loads left after forwarding, bit for bit."""
+    spec, T, epoch, n_max, gpn = CASES[name]
+    w = make(spec)
+    lay_n, lay_tp = _layouts(w, n_max)
+    P = _node_capacity_for(w, T, 6.5)
+    tp_ref, f_ref = P["tp"].size - 1, P["f_mhz"].size - 1
+    tick = w["window_s"] / T
+    args = (P, w["trace"], w["edges"], w["n_window"], T, tick, epoch, tp_ref, f_ref, gpn, lay_n, lay_tp, w["slos"], w["pct"])
+    g, coarse, fine = gpu_hier(dyn, *args, spill=True)
+    o = oracle.hierarchy(P, coarse, fine, w["n_window"], T, tick, epoch, tp_ref, f_ref, gpn, lay_n, lay_tp, w["slos"], w["pct"],
+                         spill=True)
+    np.testing.assert_array_equal(g["keep"], o["keep"])
+    assert_same(g, o, w["n_window"], w["n_class"])
+    plain, _, _ = gpu_hier(dyn, *args)
+    assert (o["keep"] < 1.0).any() and (o["keep"][:, -1] == 1.0).all()
+    assert g["nodes"].sum() < plain["nodes"].sum()        # fewer nodes in all: that is what the rule is for
+    assert (o["layout_sel"] >= 0).any()
+
+
+@pytest.mark.parametrize("seed,n_tick,NW,epoch", [(0, 3, 9, 2), (1, 2, 150, 70), (2, 4, 30, 1000), (3, 1, 7, 3)])
+def test_spill_on_random_cases(dyn, seed, n_tick, NW, epoch):
+    """Small capacities (pools of several nodes), epochs longer than a wave has lanes and longer than the trace, with
+    and without the overhead table."""
+    prof, tr, edges, slo, lay_n, lay_tp, NW, T, tick = _random_case(seed, n_tick, 3, 400 * NW, NW)
+    prof = dict(prof, max_load_tps=prof["max_load_tps"] * 0.3)
+    slo = {k: v * 1.5 for k, v in slo.items()}
+    g, coarse, fine = gpu_hier(dyn, prof, tr, edges, NW, T, tick, epoch, 2, 2, 8, lay_n, lay_tp, slo, spill=True)
+    o = oracle.hierarchy(prof, coarse, fine, NW, T, tick, epoch, 2, 2, 8, lay_n, lay_tp, slo, spill=True)
+    np.testing.assert_array_equal(g["keep"], o["keep"])
+    assert_same(g, o, NW, 2)
+    assert (o["keep"][:, 0] < 1.0).any()
+    fin = o["energy_j"][np.isfinite(o["energy_j"])]
+    trans = np.random.default_rng(seed).uniform(0, 0.2, (lay_n.size, lay_n.size)) * (np.median(fin) if fin.size else 1.0)
+    g, _, _ = gpu_hier(dyn, prof, tr, edges, NW, T, tick, epoch, 2, 2, 8, lay_n, lay_tp, slo, transition=trans, spill=True)
+    o = oracle.hierarchy(prof, coarse, fine, NW, T, tick, epoch, 2, 2, 8, lay_n, lay_tp, slo, transition=trans, spill=True)
+    np.testing.assert_array_equal(g["keep"], o["keep"])
+    np.testing.assert_array_equal(g["path_cost"], o["path_cost"])
+    assert_same(g, o, NW, 2)
 
 
 def _random_case(seed, n_tick, n_f, R, NW):
