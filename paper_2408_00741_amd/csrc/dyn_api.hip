@@ -770,7 +770,7 @@ int dyn_eval_select_mixed(dyn_profile* p, const dyn_trace_view* t, const dyn_mix
 }
 
 namespace {
-struct PathWs { size_t layout, order, seg, transition, pred, kend, min_cost, min_k, total; };
+struct PathWs { size_t layout, order, seg, transition, pred, kend, min_cost, min_k, exits, total; };
 PathWs path_ws_layout(int32_t n_window, int32_t G, int32_t K, int32_t n_layout) {
   PathWs w;
   size_t off = 0;
@@ -783,6 +783,7 @@ PathWs path_ws_layout(int32_t n_window, int32_t G, int32_t K, int32_t n_layout) 
   const size_t per_layout = n_layout <= DYN_WAVE ? (size_t)G * n_window * n_layout : 0;   // the wave-per-class route only
   w.min_cost = off; off += align256(per_layout * sizeof(double));
   w.min_k = off; off += align256(per_layout * sizeof(int32_t));
+  w.exits = off; off += align256((size_t)G * dyn_path_runs(n_window) * DYN_PATH_STATES * sizeof(int32_t));
   w.total = off;
   return w;
 }
@@ -847,7 +848,7 @@ int dyn_select_path(dyn_profile* p, const dyn_space* space, const dyn_config* cf
   a.n_layout = tr->n_layout; a.layout = (const int32_t*)(base + w.layout); a.transition = (const double*)(base + w.transition);
   a.order = (const int32_t*)(base + w.order); a.seg_start = (const int32_t*)(base + w.seg);
   a.pred = (int32_t*)(base + w.pred); a.kend = (int32_t*)(base + w.kend);
-  a.min_cost = (double*)(base + w.min_cost); a.min_k = (int32_t*)(base + w.min_k);
+  a.min_cost = (double*)(base + w.min_cost); a.min_k = (int32_t*)(base + w.min_k); a.exits = (int32_t*)(base + w.exits);
   a.sel = out->sel; a.sel_energy = out->sel_energy_j; a.path_cost = out->path_cost;
   if (!hip_ok(dyn_launch_path(a, s), "path launch")) return DYN_E_DEVICE;
   if (!hip_ok(dyn_launch_window_totals(out->sel, out->sel_energy_j, n_window, p->G, out->window_energy_j,
@@ -1021,7 +1022,7 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
     pa.n_layout = c->n_layout; pa.layout = (const int32_t*)(pb + pw.layout); pa.transition = (const double*)(pb + pw.transition);
     pa.order = (const int32_t*)(pb + pw.order); pa.seg_start = (const int32_t*)(pb + pw.seg);
     pa.pred = (int32_t*)(pb + pw.pred); pa.kend = (int32_t*)(pb + pw.kend);
-    pa.min_cost = (double*)(pb + pw.min_cost); pa.min_k = (int32_t*)(pb + pw.min_k);
+    pa.min_cost = (double*)(pb + pw.min_cost); pa.min_k = (int32_t*)(pb + pw.min_k); pa.exits = (int32_t*)(pb + pw.exits);
     pa.sel = out->layout_sel; pa.sel_energy = (double*)(base + w.sel_energy); pa.path_cost = out->path_cost;
     if (!hip_ok(dyn_launch_path(pa, s), "path launch")) return DYN_E_DEVICE;
   }

@@ -7,7 +7,8 @@
 // predecessors because rounded addition is monotone.
 //
 // Two routes.  Up to 64 layouts (further down): a parallel pre-pass reduces every (window, class) to
-// its layouts' least costs, then one block per class walks the windows with a lane per layout.
+// its layouts' least costs, one block per class walks the windows with a lane per layout keeping least
+// totals only, and the predecessors and the trace-back are taken afterwards, in parallel over the windows.
 // More layouts (next): one block per class walks the windows in time order (the recurrence is
 // sequential, so the time per window is what counts).  The candidates are visited in an order sorted by layout
 // (built on the host), a fixed number per thread, their costs loaded one window ahead; per
@@ -17,6 +18,8 @@
 // partial results combined; four LDS-only barriers per window.  Predecessors are kept per (window,
 // destination layout) in the workspace and traced back at the end in runs of windows staged
 // through LDS.
+#include <algorithm>
+
 #include "dyn_path.h"
 static_assert(DYN_PATH_MAX_CONFIGS == 256 * 8, "candidates are held in registers, a fixed number per thread");
 
@@ -222,14 +225,17 @@ __global__ __launch_bounds__(kThreads) void path_kernel(PathArgs a) {
 // The step through the layouts needs, per window, only the least cost of every layout and the
 // candidate that has it (adding a layout's arrival total to its candidates' costs keeps their
 // order: rounded addition is monotone).  Those are independent of the recurrence:
-// path_min_kernel takes them for all windows at once.  path_chain_kernel then walks the windows
-// with one lane per layout.  What the walk costs is the latency of one window's dependent steps,
-// so it touches global memory only a chunk of windows at a time, keeps its lanes' entries of the
-// transition table in registers, and avoids data-dependent branches (a load inside a branch per
-// source costs an LDS round trip each).
-constexpr int kChainRun = 64;
+// path_min_kernel takes them for all windows at once.  The recurrence itself only needs minima:
+// path_chain_kernel walks the windows with one lane per layout and keeps, per (window, layout), the
+// least total of the sequences that end there.  Which source and candidate reach a minimum is not part
+// of the recurrence; path_pred_kernel recomputes the same rounded sums from the stored totals for all
+// windows in parallel and records the predecessors (least total, then lowest candidate), and
+// path_trace_kernel follows them back.  What the walk costs is the instructions one window's step takes
+// in the block's waves (they share the four SIMDs of one compute unit), so the step holds nothing else:
+// global memory is touched a chunk of windows at a time and a source's total is a lane read.
 constexpr int kChainChunk = 16;                            // windows per visit to global memory
-constexpr int kChainWaves = 8;                             // measured: 2 waves 2.4 ms, 4 waves 1.7 ms, 8 waves 1.5 ms, 16 waves 2.0 ms (one day, 48 layouts)
+constexpr int kChainWaves = 8;
+constexpr int kEndMark = -2;                               // kend: a sequence ends in this window (before path_pred_kernel fills in its best end)
 
 // thread = (cell, layout): least cost among the layout's candidates, lowest candidate among equals
 __global__ __launch_bounds__(256) void path_min_kernel(PathArgs a) {
@@ -259,29 +265,29 @@ __global__ __launch_bounds__(256) void path_min_kernel(PathArgs a) {
   a.min_k[i] = bk;
 }
 
-// One block of kChainWaves waves per class; lane = destination layout in every wave, and wave q owns the source
-// layouts [q * LMAX/kChainWaves, (q + 1) * LMAX/kChainWaves) with its lanes' entries of those rows of the table in registers.
-// Per window every wave forms the window's totals itself (all waves carry the same state), publishes
-// them in its own LDS strip, takes the least arrival total over its sources and, among the sources that
-// reach it, the lowest candidate; the waves' partial results meet in LDS behind the window's only block
-// barrier and every wave merges them (least total, then lowest candidate: the same answer as one pass over
-// all sources).  Predecessor records: (candidate << 6) | its layout, -1: none.
-template <int LMAX>
-__global__ __launch_bounds__(kChainWaves* DYN_WAVE) void path_chain_kernel(PathArgs a) {
-  constexpr int SPW = LMAX / kChainWaves;                    // sources per wave
-  __shared__ int32_t s_bp[kChainRun * LMAX];
-  __shared__ int32_t s_sel[kChainRun];
-  __shared__ double s_c[(kChainChunk + 1) * DYN_WAVE];       // the chunk's least costs by (window, layout), one window more
-  __shared__ int32_t s_k[kChainChunk * DYN_WAVE];            // and the candidates that have them
-  __shared__ int32_t s_pr[kChainChunk * DYN_WAVE];           // the chunk's predecessor records
+__device__ __forceinline__ double readlane_f64(double v, int lane) {   // lane must be wave-uniform
+  const uint64_t u = (uint64_t)__double_as_longlong(v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, lane);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), lane);
+  return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+// One block of WAVES waves per class; lane = destination layout in every wave, and wave q owns the source
+// layouts [q * LMAX/WAVES, (q + 1) * LMAX/WAVES) with its lanes' entries of those rows of the table in registers.
+// Per window every wave forms the window's totals itself (all waves carry the same state), takes the least
+// arrival total over its sources; the waves' partial minima meet in LDS (atomic minimum per destination)
+// behind the window's only block barrier.  min_cost[window][layout] is overwritten by the least total
+// of the sequences that end there (+inf: none); kend[window] = -1: no feasible candidate, kEndMark: a
+// sequence ends here, 0 otherwise.
+template <int LMAX, int WAVES>
+__global__ __launch_bounds__(WAVES* DYN_WAVE) void path_chain_kernel(PathArgs a) {
+  constexpr int SPW = LMAX / WAVES;                          // sources per wave
+  __shared__ double s_c[(kChainChunk + 1) * DYN_WAVE];       // the chunk's least costs by (window, layout), one window more; totals once a window is done
   __shared__ int32_t s_ke[kChainChunk];
-  __shared__ double s_v[kChainWaves][DYN_WAVE];              // per wave: the window's totals by layout
-  __shared__ uint32_t s_pk[kChainWaves][DYN_WAVE];           // per wave: (candidate << 6) | layout, all ones where nothing ends
-  __shared__ double s_m[2][kChainWaves][DYN_WAVE];           // by window parity: every wave's least arrival total per destination
-  __shared__ uint32_t s_p[2][kChainWaves][DYN_WAVE];         // and the packed candidate that reaches it
+  __shared__ double s_best[3][DYN_WAVE];                     // least arrival total per destination: the waves' partial minima meet here (LDS atomic minimum); three buffers in turn
   const int g = blockIdx.x, lane = threadIdx.x & (DYN_WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
-  const int NL = a.n_layout, NW = a.n_window, G = a.G, K = a.K;
+  const int NL = a.n_layout, NW = a.n_window, G = a.G;
   const double inf = __builtin_inf();
   const bool on = lane < NL;
   double t[SPW];                                             // overhead of going from this wave's source q to this lane's layout
@@ -290,144 +296,206 @@ __global__ __launch_bounds__(kChainWaves* DYN_WAVE) void path_chain_kernel(PathA
     const int ls = wave * SPW + q;
     t[q] = (on && ls < NL) ? a.transition[(size_t)ls * NL + lane] : inf;   // layouts beyond NL never win
   }
-  int32_t* bp = a.pred + (size_t)g * NW * NL;                // [NW][NL]: where the cheapest arrival in layout l at window w comes from
-  int32_t* kend = a.kend + (size_t)g * NW;                   // [NW]: -1 gap, best end where a sequence ends, 0 otherwise
+  int32_t* kend = a.kend + (size_t)g * NW;
   auto row = [&](int w) { return ((size_t)w * G + g) * NL + lane; };
 
   double total = 0.0, arrive = inf;                          // the same in every wave
   bool first = true;
-  int par = 0;
+  int buf = 0;
+  if (wave == 0) s_best[0][lane] = inf;                      // ordered before its first use by the chunk loop's barriers
 #pragma unroll 1
   for (int w0 = 0; w0 < NW; w0 += kChainChunk) {
-    // Global memory is touched a chunk of windows at a time: costs and candidates are parked in LDS, the
-    // walk itself reads and writes LDS only, the chunk's predecessor records are flushed afterwards.
-    __syncthreads();                                         // the previous chunk's flush has read s_pr / s_ke
+    __syncthreads();                                         // the previous chunk's flush has read s_c / s_ke
 #pragma unroll
-    for (int j = 0; j < (kChainChunk + 1 + kChainWaves - 1) / kChainWaves; ++j) {
-      const int i = j * kChainWaves + wave;                  // row of the chunk this wave loads
-      if (i <= kChainChunk) {
-        const bool in = on && w0 + i < NW;
-        s_c[i * DYN_WAVE + lane] = in ? a.min_cost[row(w0 + i)] : inf;
-        if (i < kChainChunk) s_k[i * DYN_WAVE + lane] = in ? a.min_k[row(w0 + i)] : 0x7FFFFFFF;
-      }
+    for (int j = 0; j < (kChainChunk + 1 + WAVES - 1) / WAVES; ++j) {
+      const int i = j * WAVES + wave;                        // row of the chunk this wave loads
+      if (i <= kChainChunk) s_c[i * DYN_WAVE + lane] = (on && w0 + i < NW) ? a.min_cost[row(w0 + i)] : inf;
     }
     __syncthreads();
     const int n = NW - w0 < kChainChunk ? NW - w0 : kChainChunk;
     double c_nxt = s_c[lane];
-    int k_nxt = s_k[lane];
 #pragma unroll 1
     for (int i = 0; i < n; ++i) {
       const double c_cur = c_nxt;
-      const int k_cur = k_nxt;
-      c_nxt = s_c[(i + 1) * DYN_WAVE + lane];                // read a window ahead: out of the way of this window's chain of LDS round trips
-      k_nxt = s_k[(i + 1 < kChainChunk ? i + 1 : i) * DYN_WAVE + lane];
+      c_nxt = s_c[(i + 1) * DYN_WAVE + lane];                // read a window ahead, before this row is overwritten
       // least total of the sequences that end in this window in this lane's layout
       const double v = (first || !(c_cur < inf)) ? c_cur : arrive + c_cur;
-      const uint32_t pk = (v < inf) ? (((uint32_t)k_cur << 6) | (uint32_t)lane) : 0xFFFFFFFFu;
       const bool gap = __ballot(v < inf) == 0;               // no feasible candidate in this window
-      s_v[wave][lane] = v;
-      s_pk[wave][lane] = pk;
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // read back by this wave's other lanes only
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      // this wave's sources: least arrival total, then the lowest candidate among the sources that reach it
-      double arr[SPW];
-      uint32_t spk[SPW];
+      double m[SPW];                                         // sums are never NaN here: plain minima
 #pragma unroll
-      for (int q = 0; q < SPW; ++q) {
-        arr[q] = s_v[wave][wave * SPW + q] + t[q];
-        spk[q] = s_pk[wave][wave * SPW + q];
-        asm volatile("" : "+v"(spk[q]));                     // loaded here, with the totals: not inside a branch per source later
-      }
-      double m0 = inf, m1 = inf;                             // sums are never NaN here: plain minima
+      for (int q = 0; q < SPW; ++q) m[q] = readlane_f64(v, wave * SPW + q) + t[q];
 #pragma unroll
-      for (int q = 0; q < SPW; q += 2) { m0 = fmin(m0, arr[q]); if (q + 1 < SPW) m1 = fmin(m1, arr[q + 1]); }
-      const double m = fmin(m0, m1);
-      uint32_t p0 = 0xFFFFFFFFu, p1 = 0xFFFFFFFFu;
+      for (int d = 1; d < SPW; d *= 2)
 #pragma unroll
-      for (int q = 0; q < SPW; q += 2) {
-        p0 = min(p0, arr[q] == m ? spk[q] : 0xFFFFFFFFu);
-        if (q + 1 < SPW) p1 = min(p1, arr[q + 1] == m ? spk[q + 1] : 0xFFFFFFFFu);
-      }
-      s_m[par][wave][lane] = m;
-      s_p[par][wave][lane] = min(p0, p1);
-      lds_barrier();                                         // the window's only block barrier (partials alternate by parity)
-      double pm[kChainWaves];
-      uint32_t pp[kChainWaves];
-#pragma unroll
-      for (int q = 0; q < kChainWaves; ++q) {
-        pm[q] = s_m[par][q][lane];
-        pp[q] = s_p[par][q][lane];
-        asm volatile("" : "+v"(pp[q]));
-      }
-      double bv = pm[0];
-#pragma unroll
-      for (int q = 1; q < kChainWaves; ++q) bv = fmin(bv, pm[q]);
-      uint32_t bp_rec = 0xFFFFFFFFu;                         // all ones: nothing arrives (then bv is +inf)
-#pragma unroll
-      for (int q = 0; q < kChainWaves; ++q) bp_rec = min(bp_rec, pm[q] == bv ? pp[q] : 0xFFFFFFFFu);
-      par ^= 1;
+        for (int q = 0; q + d < SPW; q += 2 * d) m[q] = fmin(m[q], m[q + d]);
+      __hip_atomic_fetch_min(&s_best[buf][lane], m[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      const int nxt = buf == 2 ? 0 : buf + 1;
+      // the next window's buffer: last read two windows ago, behind the previous window's barrier for every wave
+      if (wave == WAVES - 1) s_best[nxt][lane] = inf;
+      lds_barrier();                                         // the window's only block barrier
+      if (wave == 0) s_c[i * DYN_WAVE + lane] = v;           // every wave has taken this row's costs before the barrier
+      const double bv = s_best[buf][lane];
+      buf = nxt;
       // a sequence ends here if the next window has no feasible candidate (its costs are all +inf) or does not exist
       const bool ends = !gap && (w0 + i + 1 >= NW || __ballot(c_nxt < inf) == 0);
-      int32_t ke = gap ? -1 : 0;
-      if (ends) {                                            // wave-uniform: least total, then the lowest candidate
+      if (ends) {                                            // wave-uniform
         double ev = v;
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) ev = fmin(ev, __shfl_xor(ev, d, DYN_WAVE));
-        uint32_t ep = (v == ev) ? pk : 0xFFFFFFFFu;
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) ep = min(ep, (uint32_t)__shfl_xor((int)ep, d, DYN_WAVE));
         total += ev;                                         // the sequences' totals in time order
-        ke = (int32_t)ep;
       }
-      if (wave == 0) {
-        s_pr[i * DYN_WAVE + lane] = (int32_t)bp_rec;         // how the next window is entered in this lane's layout; -1: not at all
-        if (lane == 0) s_ke[i] = ke;
-      }
+      if (threadIdx.x == 0) s_ke[i] = gap ? -1 : (ends ? kEndMark : 0);
       arrive = bv;
       first = gap;
     }
     __syncthreads();
-    for (int i = wave; i < n; i += kChainWaves)
-      if (on && w0 + i + 1 < NW) bp[(size_t)(w0 + i + 1) * NL + lane] = s_pr[i * DYN_WAVE + lane];
+    for (int i = wave; i < n; i += WAVES)
+      if (on) a.min_cost[row(w0 + i)] = s_c[i * DYN_WAVE + lane];
     if (threadIdx.x < n) kend[w0 + threadIdx.x] = s_ke[threadIdx.x];
   }
   if (threadIdx.x == 0) a.path_cost[g] = total;
-  // make the predecessor records visible to this block's own later loads
-  __threadfence();
-  __syncthreads();
+}
 
-  // trace back, a run of windows at a time from the end
-  constexpr int nthr = kChainWaves * DYN_WAVE;
-  int carry_k = -1, carry_l = 0;                             // thread 0: -1 = the next window starts a sequence
-  for (int hi = NW; hi > 0; hi -= kChainRun) {
-    const int lo = hi > kChainRun ? hi - kChainRun : 0;
-    const int n_row = (hi < NW ? hi : NW - 1) - lo;          // predecessor records of the windows lo+1 .. hi
-    // records written by this block before the barrier above: plain loads, all in flight together
-    for (int i = threadIdx.x; i < n_row * NL; i += nthr) s_bp[i] = bp[(size_t)(lo + 1) * NL + i];
-    for (int i = threadIdx.x; i < hi - lo; i += nthr) s_sel[i] = kend[lo + i];
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      for (int w = hi - 1; w >= lo; --w) {
-        const int ke = s_sel[w - lo];
-        int rec;
-        if (ke < 0) rec = -1;                                // no feasible candidate in this window
-        else if (carry_k < 0) rec = ke;                      // last window of a sequence: its best end
-        else rec = s_bp[(w - lo) * NL + carry_l];            // predecessor of the next window's choice
-        carry_k = rec < 0 ? -1 : (rec >> 6);
-        carry_l = rec < 0 ? 0 : (rec & 63);
-        s_sel[w - lo] = carry_k;
-      }
+// One wave per (window, class), lane = destination layout, the lane's column of the table in registers: where
+// the cheapest arrival in every layout of the next window comes from (least total + overhead, then the lowest
+// candidate among the sources that reach it), as (candidate << 6) | its layout, -1: none; and the best end of a
+// sequence that ends in this window.  The sums are those of the walk, from the same operands.
+template <int LMAX>
+__global__ __launch_bounds__(256) void path_pred_kernel(PathArgs a) {
+  const int lane = threadIdx.x & (DYN_WAVE - 1);
+  const int NL = a.n_layout, NW = a.n_window, G = a.G;
+  const double inf = __builtin_inf();
+  const bool on = lane < NL;
+  double t[LMAX];
+#pragma unroll
+  for (int l = 0; l < LMAX; ++l) t[l] = (on && l < NL) ? a.transition[(size_t)l * NL + lane] : inf;
+  const int64_t cells = (int64_t)NW * G;
+  const int64_t n_wave = (int64_t)gridDim.x * (blockDim.x / DYN_WAVE);
+  for (int64_t cell = (int64_t)blockIdx.x * (blockDim.x / DYN_WAVE) + threadIdx.x / DYN_WAVE; cell < cells; cell += n_wave) {
+    const int w = (int)(cell / G), g = (int)(cell % G);
+    const double v = on ? a.min_cost[(size_t)cell * NL + lane] : inf;
+    const int k = on ? a.min_k[(size_t)cell * NL + lane] : 0;
+    const uint32_t pk = (v < inf) ? (((uint32_t)k << 6) | (uint32_t)lane) : 0xFFFFFFFFu;
+    int32_t* kend = a.kend + (size_t)g * NW + w;
+    if (*kend == kEndMark) {                                 // wave-uniform
+      double ev = v;
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) ev = fmin(ev, __shfl_xor(ev, d, DYN_WAVE));
+      uint32_t ep = (v == ev) ? pk : 0xFFFFFFFFu;
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) ep = min(ep, (uint32_t)__shfl_xor((int)ep, d, DYN_WAVE));
+      if (lane == 0) *kend = (int32_t)ep;
     }
-    __syncthreads();
-    for (int i = threadIdx.x; i < hi - lo; i += nthr) {
-      const int k = s_sel[i];
-      const size_t cell = (size_t)(lo + i) * G + g;
-      a.sel[cell] = k;
-      a.sel_energy[cell] = k >= 0 ? a.energy[cell * K + k] : inf;
+    if (w + 1 >= NW) continue;
+    double m = inf;
+    uint32_t p = 0xFFFFFFFFu;                                // all ones: nothing arrives (then m is +inf)
+#pragma unroll
+    for (int l = 0; l < LMAX; ++l) {
+      const double arr = readlane_f64(v, l) + t[l];
+      const uint32_t sp = (uint32_t)__builtin_amdgcn_readlane((int)pk, l);
+      const bool better = arr < m || (arr == m && sp < p);
+      m = better ? arr : m;
+      p = better ? sp : p;
     }
-    __syncthreads();
+    if (on) a.pred[((size_t)g * NW + w + 1) * NL + lane] = (int32_t)p;
   }
+}
+
+// Trace-back.  A window's choice depends on the next window's only through a small state: the layout chosen there,
+// or "none" (the next window has no feasible candidate, starts a sequence, or does not exist).  Runs of
+// DYN_PATH_RUN windows are therefore followed back for every possible entry state at once (one thread per state;
+// path_trace_runs_kernel records the state each run is left with), a block then finds the state its run is really
+// entered with by chaining those records from the last run down to its own, follows its run once more from that
+// state and writes the selection (path_trace_write_kernel).  Both kernels stage a run's records in LDS.
+__device__ __forceinline__ int trace_step(int ke, int state, const int32_t* s_bp, int i, int NL) {
+  // record of window i of the run: -1 none, else (candidate << 6) | layout
+  if (ke < 0) return -1;                                     // no feasible candidate in this window
+  if (state == DYN_PATH_STATES - 1) return ke;               // last window of a sequence: its best end
+  return s_bp[i * NL + state];                               // predecessor of the next window's choice
+}
+
+__device__ __forceinline__ void trace_stage(const PathArgs& a, int g, int lo, int hi, int32_t* s_bp, int32_t* s_ke) {
+  const int NL = a.n_layout, NW = a.n_window;
+  const int32_t* bp = a.pred + (size_t)g * NW * NL;          // [NW][NL]: where the cheapest arrival in layout l at window w comes from
+  const int32_t* kend = a.kend + (size_t)g * NW;             // [NW]: -1 gap, best end where a sequence ends, 0 otherwise
+  const int n_row = (hi < NW ? hi : NW - 1) - lo;            // predecessor records of the windows lo+1 .. hi
+  for (int i = threadIdx.x; i < n_row * NL; i += blockDim.x) s_bp[i] = bp[(size_t)(lo + 1) * NL + i];
+  for (int i = n_row * NL + threadIdx.x; i < (hi - lo) * NL; i += blockDim.x) s_bp[i] = -1;   // nothing follows the last window
+  for (int i = threadIdx.x; i < hi - lo; i += blockDim.x) s_ke[i] = kend[lo + i];
+  __syncthreads();
+}
+
+// grid (runs, classes), 128 threads: thread s < DYN_PATH_STATES follows the run back from entry state s.
+__global__ __launch_bounds__(128) void path_trace_runs_kernel(PathArgs a) {
+  __shared__ int32_t s_bp[DYN_PATH_RUN * DYN_WAVE];
+  __shared__ int32_t s_ke[DYN_PATH_RUN];
+  const int r = blockIdx.x, g = blockIdx.y;
+  const int lo = r * DYN_PATH_RUN, hi = min(a.n_window, lo + DYN_PATH_RUN);
+  trace_stage(a, g, lo, hi, s_bp, s_ke);
+  int state = threadIdx.x;
+  if (state >= DYN_PATH_STATES) return;
+  if (state < DYN_PATH_STATES - 1 && state >= a.n_layout) state = DYN_PATH_STATES - 1;   // not a layout: never entered with
+  for (int i = hi - lo - 1; i >= 0; --i) {
+    const int rec = trace_step(s_ke[i], state, s_bp, i, a.n_layout);
+    state = rec < 0 ? DYN_PATH_STATES - 1 : (rec & 63);
+  }
+  a.exits[((size_t)g * gridDim.x + r) * DYN_PATH_STATES + threadIdx.x] = state;
+}
+
+// grid (runs, classes), 64 threads.
+__global__ __launch_bounds__(DYN_WAVE) void path_trace_write_kernel(PathArgs a) {
+  __shared__ int32_t s_bp[DYN_PATH_RUN * DYN_WAVE];
+  __shared__ int32_t s_ke[DYN_PATH_RUN];
+  __shared__ int32_t s_sel[DYN_PATH_RUN];
+  const int r = blockIdx.x, g = blockIdx.y, n_run = gridDim.x;
+  const int G = a.G, K = a.K;
+  const int lo = r * DYN_PATH_RUN, hi = min(a.n_window, lo + DYN_PATH_RUN);
+  trace_stage(a, g, lo, hi, s_bp, s_ke);
+  // the state this run is entered with: the later runs' records chained from the end.  The records of kHop runs
+  // are fetched together (lane s holds the record for entry state s), so a hop is a lane read, not a load.
+  constexpr int kHop = 16;
+  int state = DYN_PATH_STATES - 1;                           // nothing follows the last window; wave-uniform
+  for (int top = n_run - 1; top > r; top -= kHop) {
+    int by_layout[kHop], by_none[kHop];
+#pragma unroll
+    for (int j = 0; j < kHop; ++j) {
+      const int q = max(top - j, r + 1);                     // runs at or below r are not used
+      const int32_t* row = a.exits + ((size_t)g * n_run + q) * DYN_PATH_STATES;
+      by_layout[j] = row[threadIdx.x];
+      by_none[j] = row[DYN_PATH_STATES - 1];
+    }
+#pragma unroll
+    for (int j = 0; j < kHop; ++j)
+      if (top - j > r)
+        state = state == DYN_PATH_STATES - 1 ? by_none[j] : __builtin_amdgcn_readlane(by_layout[j], __builtin_amdgcn_readfirstlane(state));
+  }
+  if (threadIdx.x == 0) {
+    for (int i = hi - lo - 1; i >= 0; --i) {
+      const int rec = trace_step(s_ke[i], state, s_bp, i, a.n_layout);
+      state = rec < 0 ? DYN_PATH_STATES - 1 : (rec & 63);
+      s_sel[i] = rec < 0 ? -1 : (rec >> 6);
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < hi - lo; i += blockDim.x) {
+    const int k = s_sel[i];
+    const size_t cell = (size_t)(lo + i) * G + g;
+    a.sel[cell] = k;
+    a.sel_energy[cell] = k >= 0 ? a.energy[cell * K + k] : __builtin_inf();
+  }
+}
+
+template <int LMAX>
+void launch_layout_route(const PathArgs& a, hipStream_t s) {
+  const int64_t cells = (int64_t)a.n_window * a.G;
+  const int64_t n = cells * a.n_layout;
+  hipLaunchKernelGGL(path_min_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a);
+  hipLaunchKernelGGL((path_chain_kernel<LMAX, kChainWaves>), dim3((unsigned)a.G), dim3(kChainWaves * DYN_WAVE), 0, s, a);
+  const int64_t pred_blocks = std::min<int64_t>((cells + 3) / 4, 2048);
+  hipLaunchKernelGGL(path_pred_kernel<LMAX>, dim3((unsigned)pred_blocks), dim3(256), 0, s, a);
+  const dim3 runs((unsigned)dyn_path_runs(a.n_window), (unsigned)a.G);
+  hipLaunchKernelGGL(path_trace_runs_kernel, runs, dim3(128), 0, s, a);
+  hipLaunchKernelGGL(path_trace_write_kernel, runs, dim3(DYN_WAVE), 0, s, a);
 }
 
 }  // namespace
@@ -448,12 +516,10 @@ hipError_t dyn_launch_path(const PathArgs& a, hipStream_t s) {
   if (!dyn_path_fits(a.K, a.n_layout)) return hipErrorInvalidValue;
   DynTimed timed(DYN_K_PATH, s);
   if (a.n_layout <= DYN_WAVE) {
-    const int64_t n = (int64_t)a.n_window * a.G * a.n_layout;
-    hipLaunchKernelGGL(path_min_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a);
-    if (a.n_layout <= 16) hipLaunchKernelGGL(path_chain_kernel<16>, dim3((unsigned)a.G), dim3(kChainWaves * DYN_WAVE), 0, s, a);
-    else if (a.n_layout <= 32) hipLaunchKernelGGL(path_chain_kernel<32>, dim3((unsigned)a.G), dim3(kChainWaves * DYN_WAVE), 0, s, a);
-    else if (a.n_layout <= 48) hipLaunchKernelGGL(path_chain_kernel<48>, dim3((unsigned)a.G), dim3(kChainWaves * DYN_WAVE), 0, s, a);
-    else hipLaunchKernelGGL(path_chain_kernel<64>, dim3((unsigned)a.G), dim3(kChainWaves * DYN_WAVE), 0, s, a);
+    if (a.n_layout <= 16) launch_layout_route<16>(a, s);
+    else if (a.n_layout <= 32) launch_layout_route<32>(a, s);
+    else if (a.n_layout <= 48) launch_layout_route<48>(a, s);
+    else launch_layout_route<64>(a, s);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(path_kernel, dim3((unsigned)a.G), dim3(kThreads), dyn_path_lds(a.K, a.n_layout), s, a);
