@@ -10,6 +10,7 @@ timed separately.  Other entry points have modes of their own, each on the same 
 with the same JSON line: --ticks T (load followed tick by tick inside a window), --mixed S
 (pools that mix TP degrees), --path (selection with transition overheads between windows),
 --hierarchy T [--overheads] [--spill] (the three controllers top down).
+The headline mode also reports `pipelined`: the same steps with consecutive steps on alternating streams.
 
 Prints one JSON line.  `value` = requests x configurations / step time.
 """
@@ -124,6 +125,10 @@ def main():
     ap.add_argument("--overheads", action="store_true",
                     help="with --hierarchy: the shard controller weighs re-sharding overheads (2 %% of the median window "
                          "energy per GPU of difference between two layouts)")
+    ap.add_argument("--pipelined-streams", type=int, default=2,
+                    help="headline mode only: after the timed region, the same number of steps once more with consecutive "
+                         "steps alternating between this many streams and output sets (reported as `pipelined`, never as "
+                         "`value`); 0 or 1 = skip")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events (roofline.achieved is then null)")
@@ -312,6 +317,35 @@ def main():
             ktime[name] = ms / max(n, 1)
         dyn.dyn_timing_enable(False)
 
+    # ---- the same steps with consecutive steps on alternating streams (own outputs and workspace each): one step's
+    # aggregation and selection kernels then run beside another step's store-bound evaluation.  Reported next to the
+    # single-stream figure; `value` stays the single-stream one.
+    pipelined = None
+    headline = not (args.hierarchy or args.path or args.mixed or args.ticks or args.unfused)
+    if headline and args.pipelined_streams > 1:
+        n_s = args.pipelined_streams
+        sets = [(space, sel, ws)]
+        for _ in range(n_s - 1):
+            sets.append(({k: torch.empty_like(v) for k, v in space.items()}, {k: torch.empty_like(v) for k, v in sel.items()},
+                         torch.empty_like(ws)))
+        streams = [torch.cuda.Stream() for _ in range(n_s)]          # default priority
+
+        def run(n):
+            for i in range(n):
+                sp, se, wk = sets[i % n_s]
+                dyn.dyn_eval_select(prof, ins, outs, off, NW, w["window_s"], plan, out=sp, sel=se, workspace=wk,
+                                    stream=streams[i % n_s])
+        run(max(args.warmup, 2 * n_s))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(args.steps)
+        torch.cuda.synchronize()
+        p_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        same = all(torch.equal(sets[0][1]["sel"], s_[1]["sel"]) and torch.equal(sets[0][0]["flags"], s_[0]["flags"]) for s_ in sets[1:])
+        pipelined = {"streams": n_s, "ms_per_step": p_ms, "value": R * K / (p_ms * 1e-3), "unit": "evals/s",
+                     "same_results_on_every_stream": bool(same)}
+        del sets, streams
+
     # ---- roofline of the dominant kernel (space evaluation): 25 B written per (cell, configuration)
     space_bytes = 25.0 * cells * K
     space_ms = ktime["tick_space"] + ktime["tick_merge"] if args.ticks else ktime["space"]
@@ -380,7 +414,7 @@ def main():
                    "entry_points": ("dyn_hierarchy" + ("+overheads" if args.overheads else "") + ("+spill" if args.spill else "")) if args.hierarchy else "dyn_eval_space+dyn_select_path" if args.path else "dyn_eval_select_mixed" if args.mixed else "dyn_eval_select_ticks" if args.ticks else
                                    "dyn_eval_space+dyn_select_config" if args.unfused else "dyn_eval_select"},
         "roofline": roofline,
-        "kernel_ms": ktime, "ms_per_step_with_kernel_events": ms_per_step_events,
+        "kernel_ms": ktime, "ms_per_step_with_kernel_events": ms_per_step_events, "pipelined": pipelined,
         "path": {"algorithmic_bytes": path_bytes, "gbps": path_gbps, "frac_of_hbm_peak": path_gbps / HBM_PEAK_GBPS},
         "setup": {"ingest_ms": ingest_ms, "profile_load_ms": profile_load_ms, "generate_s": gen_s,
                   "ingest_requests_per_s": R / (ingest_ms * 1e-3)},
