@@ -522,6 +522,37 @@ def test_plan_changes_between_calls_are_picked_up(dyn):
     prof.free()
 
 
+def test_calls_in_flight_on_two_streams_give_the_same_bits(dyn):
+    """Steps on alternating streams with outputs and workspace of their own (one profile handle, one plan): every
+    step's results equal those of a step that ran alone."""
+    w = make(SPECS[2].scaled(400_000, 60))
+    ins, outs, off, _ = gpu_ingest(dyn, w)
+    prof = dyn.dyn_profile_load(w["profile"])
+    plan = dyn.Plan(w["configs"], w["slos"], w["pct"], None, w["idle_cost_weight"])
+    args = (prof, ins, outs, off, w["n_window"], w["window_s"], plan)
+    ref_space, ref_sel, ref_ws = dyn.dyn_eval_select(*args)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    sets = [dyn.dyn_eval_select(*args) for _ in streams]     # allocates the output sets; results overwritten below
+    torch.cuda.synchronize()
+    for s_ in sets:
+        for d in s_[:2]:
+            for v in d.values():
+                v.fill_(-1 if v.dtype != torch.uint8 else 255)
+    torch.cuda.synchronize()
+    for i in range(12):
+        sp, se, ws = sets[i % 2]
+        dyn.dyn_eval_select(*args, out=sp, sel=se, workspace=ws, stream=streams[i % 2])
+    torch.cuda.synchronize()
+    for sp, se, ws in sets:
+        assert dyn.dyn_workspace_status(ws) == dyn.dyn_workspace_status(ref_ws) == 0
+        for k in ref_space:
+            assert torch.equal(sp[k], ref_space[k]), k
+        for k in ref_sel:
+            assert torch.equal(se[k], ref_sel[k]), k
+    prof.free()
+
+
 # ------------------------------------------------------------- full size, sampled cells
 def test_full_size_day_trace_sampled_cells(dyn):
     """The benchmark workload (one-day trace, 10^7 requests, 36000 cells x 576 configurations) in the
