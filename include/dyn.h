@@ -77,7 +77,9 @@ typedef struct {
  * was last used with, so that repeated calls with the same candidates upload nothing.
  * A handle must not be used by two host threads at once, and a call that changes the
  * candidate list or the SLOs first waits for `hip_stream`; work still in flight on
- * another stream must not be using the same handle at that moment.
+ * another stream must not be using the same handle at that moment.  Calls with the same
+ * candidates and objective may be in flight on several streams at once when each has its
+ * own outputs and workspace (one call's aggregation then overlaps another's stores).
  * Limits: at most 65536 candidate configurations.                                      */
 typedef struct dyn_profile dyn_profile;
 
