@@ -223,6 +223,35 @@ def test_layout_counts_around_the_route_boundaries(dyn, NL, K):
     prof.free()
 
 
+@pytest.mark.parametrize("NW", [1, 2, 16, 17, 63, 64, 65, 128, 129, 1089, 1200])
+def test_window_counts_around_the_trace_back_runs(dyn, NW):
+    """The walk visits global memory 16 windows at a time and the trace-back follows runs of 64 windows, chaining the
+    runs' records 16 at a time: window counts on both sides of every one of those boundaries, with gaps in the sequences
+    and ties (costs on a coarse grid)."""
+    rng = np.random.default_rng(7000 + NW)
+    w = make(SPECS[0])
+    G = w["n_class"]
+    K, NL = 24, 7
+    cfg = {"n_inst": rng.integers(1, 5, K).astype(np.int32), "tp_index": rng.integers(0, w["profile"]["tp"].size, K).astype(np.int32),
+           "f_mhz": rng.choice(w["profile"]["f_mhz"], K)}
+    energy = np.round(rng.uniform(1, 50, (NW * G, K)), 1)
+    flags = np.where(rng.uniform(0, 1, (NW * G, K)) < 0.5, 1, 4).astype(np.uint8)
+    for _ in range(NW // 40 + 1):
+        flags[int(rng.integers(0, NW)) * G + int(rng.integers(0, G))] = 8
+    if NW > 64:
+        flags[63 * G:65 * G] = 8                           # a gap on both sides of the first run boundary, every class
+    lay = rng.permutation(np.arange(K) % NL).astype(np.int32)
+    tr = np.round(rng.uniform(0, 6, (NL, NL)), 1)
+    tr[np.diag_indices(NL)] = 0.0
+    feas = (flags & 1).astype(np.uint8)
+    o_sel, o_pc = oracle.select_path(energy, feas, NW, G, lay, tr)
+    prof = dyn.dyn_profile_load(w["profile"])
+    plan = dyn.Plan(cfg, w["slos"], w["pct"], None, 0.0)
+    g = run_path(dyn, prof, plan, energy, flags, NW, 60.0, lay, tr)
+    check(g, o_sel, o_pc, energy, feas, energy, lay, tr, NW, G)
+    prof.free()
+
+
 def test_argument_errors(dyn):
     w = make(SPECS[0])
     K = w["configs"]["n_inst"].size
