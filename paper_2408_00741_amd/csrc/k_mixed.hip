@@ -5,7 +5,7 @@
 // The load is split in n_share equal shares; type i takes a_i of them and its n_i instances
 // share that part equally.  The frequency of a type does not depend on the other types, so
 // the search has two steps:
-//   mixed_type_kernel     E_i(n, a) = least energy of n instances of type i carrying a shares
+//   mixed_type_*_kernel   E_i(n, a) = least energy of n instances of type i carrying a shares
 //                         over the frequencies that meet the SLO (Section IV-B "Scale-up/down":
 //                         filter, then least energy), for every (cell, i, n, a);
 //   mixed_combine_kernel  per cell a dynamic programme over the types, state = (GPUs used,
@@ -13,6 +13,8 @@
 // Rounded addition is monotone, so the minimum over the partial sums of a prefix followed by
 // one more addition is the minimum over the extended sums: the programme returns exactly the
 // least of the sums 0 + E_0 + E_1 + ... taken in type order, which is how the total is defined.
+#include <algorithm>
+
 #include "dyn_mixed.h"
 #include "dyn_device.h"
 
@@ -118,6 +120,92 @@ __global__ __launch_bounds__(256) void mixed_type_kernel(MixedTypeArgs a) {
   }
 }
 
+// The same per-type energies with the frequencies walked by the thread: a thread is (entry, window), takes its
+// share of the window's load once and keeps the least admissible energy over the frequencies in ascending order
+// (strictly less replaces: the lowest frequency among equals), so nothing crosses lanes and every lane stores.
+// The capacities n x max load and their reciprocals, which the other kernel forms per lane and pass, come from an
+// LDS table [n_max][n_f] built once per block.  Chosen when that table fits beside the rows.
+// LDS: as above, then [capacity n_max*n_f] [its reciprocal n_max*n_f]
+template <bool SINGLE>
+__global__ __launch_bounds__(256) void mixed_type_walk_kernel(MixedTypeArgs a) {
+  extern __shared__ double smem[];
+  const int n_rho = a.n_rho, n_f = a.n_f, S = a.n_share;
+  const int i = blockIdx.x % a.n_tp;
+  const int g = (blockIdx.x / a.n_tp) % a.G;
+  const int chunk = blockIdx.x / (a.n_tp * a.G);
+  const int n_max = a.types.n_max[i];
+  const int n_ent = n_max * S;                     // entries of this type
+  if (n_ent == 0) return;                          // block-uniform
+  const int w0 = chunk * a.win_per_block;
+  const int w1 = min(w0 + a.win_per_block, a.n_window);
+  const int n_entry = a.types.off[a.n_tp];
+
+  const int row_stride = (3 * n_rho) | 1;          // see mixed_type_kernel
+  double* s_tab = smem;
+  double* s_rgp = s_tab + (size_t)n_f * row_stride;
+  double* s_rinv = s_rgp + (n_rho + 2);
+  double* s_thr = s_rinv + (n_rho + 1);
+  CellRec* s_rec = (CellRec*)(s_thr + (SINGLE ? a.n_bucket + 1 : 0));
+  double* s_den = (double*)(s_rec + a.win_per_block);            // [n_max][n_f]
+  double* s_rden = s_den + (size_t)n_max * n_f;
+  uint16_t* s_js = (uint16_t*)(s_rden + (size_t)n_max * n_f);
+
+  {
+    const double* src = a.tab + ((size_t)g * a.n_tp + i) * n_f * 3 * n_rho;   // the type's rows are contiguous
+    for (int q = threadIdx.x; q < n_f * 3 * n_rho; q += blockDim.x) {
+      const int r = q / (3 * n_rho);
+      s_tab[r * row_stride + (q - r * 3 * n_rho)] = src[q];
+    }
+  }
+  for (int q = threadIdx.x; q < 2 * n_rho + 3; q += blockDim.x) s_rgp[q] = a.gridpack[q];
+  for (int q = threadIdx.x; q <= a.n_bucket; q += blockDim.x) {
+    s_js[q] = (uint16_t)(SINGLE ? a.tstart[q] : a.jstart[q]);
+    if (SINGLE) s_thr[q] = a.thr[q];
+  }
+  for (int q = threadIdx.x; q < w1 - w0; q += blockDim.x) s_rec[q] = a.rec[(size_t)(w0 + q) * a.G + g];
+  for (int q = threadIdx.x; q < n_max * n_f; q += blockDim.x) {
+    const int n = q / n_f + 1, f = q - (n - 1) * n_f;
+    const double den = (double)n * a.ml[((size_t)g * a.n_tp + i) * n_f + f];
+    s_den[q] = den;
+    s_rden[q] = 1.0 / den;
+  }
+  __syncthreads();
+
+  const double slo_ttft = a.slo_ttft[g], slo_tbt = a.slo_tbt[g];
+  Lookup L;
+  L.u = 0.0; L.omu = 1.0;
+  L.rho_max = s_rgp[n_rho];
+  L.bucket_scale = a.bucket_scale;
+  L.rgp = s_rgp; L.rinv = s_rinv; L.js = s_js; L.thr = s_thr; L.n_rho = n_rho;
+  const double sd = (double)S;
+  const int64_t n_pair = (int64_t)n_ent * (w1 - w0);              // (window, entry), entry fastest
+  for (int64_t idx = threadIdx.x; idx < n_pair; idx += blockDim.x) {
+    const int dw = (int)(idx / n_ent), e = (int)(idx - (int64_t)dw * n_ent);
+    const int n = e / S + 1, sh = e - (n - 1) * S + 1;
+    const double nd = (double)n, ad = (double)sh;
+    const CellRec rec = s_rec[dw];
+    const double ls = div_by(rec.load * ad, sd, a.r_share);      // the part of the load this type takes
+    const double* den = s_den + (size_t)(n - 1) * n_f;
+    const double* rden = s_rden + (size_t)(n - 1) * n_f;
+    double best = __builtin_inf();
+    int bf = -1;
+    for (int f = 0; f < n_f; ++f) {                              // ascending: the lowest frequency wins equal energies
+      L.den = den[f];
+      L.rden = rden[f];
+      L.lo = s_tab + (size_t)f * row_stride;
+      L.hi = L.lo;
+      double pf, tb, pw;
+      const bool ov = table_lookup<SINGLE, false>(L, ls, &pf, &tb, &pw);
+      const double en = (nd * pw) * a.window_s;
+      const bool ok = !ov && !(rec.xp99 * pf > slo_ttft) && !(tb * rec.nonempty > slo_tbt);
+      if (ok && en < best) { best = en; bf = f; }
+    }
+    const size_t o = ((size_t)(w0 + dw) * a.G + g) * n_entry + a.types.off[i] + e;
+    a.type_energy[o] = best;
+    a.type_f[o] = (int8_t)bf;
+  }
+}
+
 // One wave per cell.  LDS: [E_i(n, a) of the cell, n_entry] [D of the previous type] [D of this type]
 // [choice per type and state (16-bit: n << 8 | a)], states = (units of GPUs 0..U) x (shares 0..S).
 // SMAX >= n_share bounds the unrolled loop over the shares given to a type: the loads of one
@@ -194,6 +282,11 @@ size_t type_lds(const MixedTypeArgs& a, bool single) {
   return ((size_t)a.n_f * ((3 * a.n_rho) | 1) + 2 * a.n_rho + 3 + (single ? a.n_bucket + 1 : 0)) * sizeof(double) +
          (size_t)a.win_per_block * sizeof(CellRec) + ((size_t)a.n_bucket + 1) * sizeof(uint16_t) + 8;
 }
+size_t type_walk_lds(const MixedTypeArgs& a, bool single) {   // plus the capacities of the type with most instances
+  int n_max = 0;
+  for (int i = 0; i < a.n_tp; ++i) n_max = std::max(n_max, a.types.n_max[i]);
+  return type_lds(a, single) + (size_t)2 * n_max * a.n_f * sizeof(double);
+}
 
 }  // namespace
 
@@ -210,6 +303,12 @@ hipError_t dyn_launch_mixed_types(const MixedTypeArgs& a, bool single_point, hip
   const size_t lds = type_lds(a, single);
   if (lds > DYN_LDS_BUDGET) return hipErrorInvalidValue;
   DynTimed timed(DYN_K_MIXED_TYPES, s);
+  const size_t lds_walk = type_walk_lds(a, single);
+  if (lds_walk <= DYN_LDS_BUDGET) {
+    if (single) hipLaunchKernelGGL(mixed_type_walk_kernel<true>, grid, block, lds_walk, s, a);
+    else hipLaunchKernelGGL(mixed_type_walk_kernel<false>, grid, block, lds_walk, s, a);
+    return hipGetLastError();
+  }
   if (single) hipLaunchKernelGGL(mixed_type_kernel<true>, grid, block, lds, s, a);
   else hipLaunchKernelGGL(mixed_type_kernel<false>, grid, block, lds, s, a);
   return hipGetLastError();

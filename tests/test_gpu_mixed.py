@@ -104,6 +104,22 @@ def test_mixed_matches_oracle(dyn, name):
     assert (o["n_inst"] > 0).sum(axis=1).max() >= 1
 
 
+def test_many_instances_of_one_type(dyn):
+    """240 instances allowed for the smallest type: the per-type capacities no longer fit in LDS beside the table rows
+    (64 load points per row: 18 KB of rows + 46 KB of capacities) and the per-type energies come from the kernel that
+    forms them per lane; a budget keeps the assignment small."""
+    w = make(SPECS[2].scaled(6000, 4))
+    T = w["profile"]["tp"].size
+    S = 2
+    n_max = [240] + [2] * (T - 1)
+    budget = np.full(w["n_class"], 24, np.int32)
+    g, st = gpu_mixed(dyn, w, S, n_max, budget)
+    o = oracle.mixed(w["profile"], st, w["n_window"], w["window_s"], S, n_max, w["slos"], w["pct"], budget, want_types=True)
+    rep = check(w, g, o, S, n_max, budget)
+    print("unique / tied / infeasible cells:", rep)
+    assert rep[0] > 0
+
+
 def _random_case(seed):
     rng = np.random.default_rng(1100 + seed)
     n_tp, n_f, n_rho, G = int(rng.integers(1, 5)), int(rng.integers(1, 7)), int(rng.integers(2, 9)), 3
