@@ -14,6 +14,7 @@
 // 64 requests and walks them in order; the position of a request among the requests of
 // its row with the same digit comes from wave ballots, so arrival order is preserved.
 #include "dyn_internal.h"
+#include "dyn_device.h"
 
 namespace {
 
@@ -22,40 +23,83 @@ constexpr int kRows = 32;                              // rows of 64 requests pe
 constexpr int kTile = kWaves * kRows * DYN_WAVE;       // 8192 requests per block
 constexpr int kScanChunk = 4096;                       // counters per block of the scan kernels
 
-__global__ __launch_bounds__(256) void key_kernel(IngestArgs a) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= a.n_req) return;                    // the lanes that stay are a prefix of the wave: lane - 1 is among them
-  uint32_t bad = 0;
-  double wq = floor(a.t_s[i] / a.window_s);
-  if (!(wq >= 0.0)) { bad = DYN_WS_BAD_REQUEST; wq = 0.0; }                      // negative or NaN
-  if (!(wq < (double)a.n_window)) { bad = DYN_WS_BAD_REQUEST; wq = (double)(a.n_window - 1); }
-  int32_t mdl = a.model ? a.model[i] : 0;
-  if (mdl < 0 || mdl >= a.n_model) { bad = DYN_WS_BAD_REQUEST; mdl = 0; }
-  const int32_t x = a.in_tok[i], y = a.out_tok[i];
-  const int32_t* ie = a.d_in_edge + (size_t)mdl * (a.n_in_bin - 1);
-  const int32_t* oe = a.d_out_edge + (size_t)mdl * (a.n_out_bin - 1);
-  int bi = 0, bo = 0;
-  for (int e = 0; e < a.n_in_bin - 1; ++e) bi += (x >= ie[e]) ? 1 : 0;
-  for (int e = 0; e < a.n_out_bin - 1; ++e) bo += (y >= oe[e]) ? 1 : 0;
-  const int64_t G = (int64_t)a.n_model * a.n_in_bin * a.n_out_bin;
-  const int64_t g = ((int64_t)mdl * a.n_in_bin + bi) * a.n_out_bin + bo;
-  a.key_a[i] = (uint32_t)((int64_t)wq * G + g);
-  if (bad) atomicOr(a.status, bad);
-  // Window order: compare with the request before (the neighbouring lane; the first lane of a wave recomputes it).
-  // Where the window changes the boundaries are written: in a trace in window order win_off[w] = number of
-  // requests in windows before w (the values are not used otherwise).
-  const int lane = threadIdx.x & (DYN_WAVE - 1);
-  double wp = __shfl_up(wq, 1, DYN_WAVE);
-  if (lane == 0 && i > 0) {
-    wp = floor(a.t_s[i - 1] / a.window_s);
-    if (!(wp >= 0.0)) wp = 0.0;
-    if (!(wp < (double)a.n_window)) wp = (double)(a.n_window - 1);
+constexpr int kKeyRows = 4;                            // requests per thread of the key kernel (rows of 256)
+
+// Window of a timestamp: floor(t / window_s), the quotient formed from RN(1 / window_s) with one correction step
+// (the correctly rounded quotient, three instructions instead of a division); clamped, out-of-range flagged.
+__device__ __forceinline__ double window_of(double t, double window_s, double r_window, int32_t n_window, uint32_t* bad) {
+  double q = div_by(t, window_s, r_window);
+  if (q != q) q = t / window_s;                        // infinite timestamp or quotient: the correction step gives NaN
+  double wq = floor(q);
+  if (!(wq >= 0.0)) { *bad = DYN_WS_BAD_REQUEST; wq = 0.0; }                      // negative or NaN
+  if (!(wq < (double)n_window)) { *bad = DYN_WS_BAD_REQUEST; wq = (double)(n_window - 1); }
+  return wq;
+}
+
+// A block takes kKeyRows rows of 256 consecutive requests (all loads of a thread in flight together); the class
+// edges sit in LDS when they fit (lds_edges != 0).
+__global__ __launch_bounds__(256) void key_kernel(IngestArgs a, double r_window, int lds_edges) {
+  extern __shared__ int32_t s_edge[];                  // [n_model][n_in_bin - 1] then [n_model][n_out_bin - 1]
+  const int n_ie = a.n_in_bin - 1, n_oe = a.n_out_bin - 1;
+  const int32_t* in_edge = a.d_in_edge;
+  const int32_t* out_edge = a.d_out_edge;
+  if (lds_edges) {
+    for (int q = threadIdx.x; q < a.n_model * n_ie; q += blockDim.x) s_edge[q] = a.d_in_edge[q];
+    for (int q = threadIdx.x; q < a.n_model * n_oe; q += blockDim.x) s_edge[a.n_model * n_ie + q] = a.d_out_edge[q];
+    __syncthreads();
+    in_edge = s_edge;
+    out_edge = s_edge + a.n_model * n_ie;
   }
-  if (i == 0) wp = -1.0;
-  const bool dis = wp > wq;
-  for (int64_t w = (int64_t)wp + 1; w <= (int64_t)wq; ++w) a.win_off[w] = i;
-  if (i == a.n_req - 1)
-    for (int64_t w = (int64_t)wq + 1; w <= a.n_window; ++w) a.win_off[w] = a.n_req;
+  const int lane = threadIdx.x & (DYN_WAVE - 1);
+  const int64_t base = (int64_t)blockIdx.x * (kKeyRows * 256) + threadIdx.x;
+  double t[kKeyRows], tp[kKeyRows];
+  int32_t x[kKeyRows], y[kKeyRows], md[kKeyRows];
+#pragma unroll
+  for (int r = 0; r < kKeyRows; ++r) {
+    const int64_t i = base + r * 256;
+    const bool in = i < a.n_req;
+    t[r] = in ? a.t_s[i] : 0.0;
+    tp[r] = (in && lane == 0 && i > 0) ? a.t_s[i - 1] : 0.0;   // the request before a wave's first
+    x[r] = in ? a.in_tok[i] : 0;
+    y[r] = in ? a.out_tok[i] : 0;
+    md[r] = (in && a.model) ? a.model[i] : 0;
+  }
+  const int64_t G = (int64_t)a.n_model * a.n_in_bin * a.n_out_bin;
+  uint32_t bad = 0;
+  bool dis = false;
+#pragma unroll
+  for (int r = 0; r < kKeyRows; ++r) {
+    const int64_t i = base + r * 256;
+    const bool in = i < a.n_req;                       // the lanes that are in are a prefix of the wave: lane - 1 is among them
+    uint32_t bad_r = 0;
+    const double wq = window_of(t[r], a.window_s, r_window, a.n_window, &bad_r);
+    int32_t mdl = md[r];
+    if (mdl < 0 || mdl >= a.n_model) { bad_r = DYN_WS_BAD_REQUEST; mdl = 0; }
+    const int32_t* ie = in_edge + (size_t)mdl * n_ie;
+    const int32_t* oe = out_edge + (size_t)mdl * n_oe;
+    int bi = 0, bo = 0;
+    for (int e = 0; e < n_ie; ++e) bi += (x[r] >= ie[e]) ? 1 : 0;
+    for (int e = 0; e < n_oe; ++e) bo += (y[r] >= oe[e]) ? 1 : 0;
+    const int64_t g = ((int64_t)mdl * a.n_in_bin + bi) * a.n_out_bin + bo;
+    // Window order: compare with the request before (the neighbouring lane; the first lane of a wave recomputes it).
+    // Where the window changes the boundaries are written: in a trace in window order win_off[w] = number of
+    // requests in windows before w (the values are not used otherwise).
+    double wp = __shfl_up(wq, 1, DYN_WAVE);
+    if (lane == 0) {
+      uint32_t ignore = 0;
+      wp = window_of(tp[r], a.window_s, r_window, a.n_window, &ignore);
+    }
+    if (i == 0) wp = -1.0;
+    if (in) {
+      a.key_a[i] = (uint32_t)((int64_t)wq * G + g);
+      bad |= bad_r;
+      dis = dis || wp > wq;
+      for (int64_t w = (int64_t)wp + 1; w <= (int64_t)wq; ++w) a.win_off[w] = i;
+      if (i == a.n_req - 1)
+        for (int64_t w = (int64_t)wq + 1; w <= a.n_window; ++w) a.win_off[w] = a.n_req;
+    }
+  }
+  if (bad) atomicOr(a.status, bad);
   const uint64_t any = __ballot(dis);
   if (any && lane == __builtin_ctzll(any) && __hip_atomic_load(a.unsorted, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u)
     atomicOr(a.unsorted, 1u);
@@ -349,7 +393,10 @@ hipError_t dyn_launch_ingest(const IngestArgs& a, hipStream_t s) {
   // answer picks the route, so it is read back here: this entry point synchronises with the stream anyway.
   uint32_t unsorted = a.force_sort ? 1u : 0u;
   if (n > 0) {
-    hipLaunchKernelGGL(key_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a);
+    const size_t edge_bytes = (size_t)a.n_model * ((a.n_in_bin - 1) + (a.n_out_bin - 1)) * sizeof(int32_t);
+    const int lds_edges = edge_bytes <= 32 * 1024 ? 1 : 0;
+    hipLaunchKernelGGL(key_kernel, dim3((unsigned)((n + kKeyRows * 256 - 1) / (kKeyRows * 256))), dim3(256), lds_edges ? edge_bytes : 0, s, a,
+                       1.0 / a.window_s, lds_edges);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (!a.force_sort) {
       if ((e = hipMemcpyAsync(&unsorted, a.unsorted, sizeof(uint32_t), hipMemcpyDeviceToHost, s)) != hipSuccess) return e;
