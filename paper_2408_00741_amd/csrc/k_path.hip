@@ -230,11 +230,11 @@ __global__ __launch_bounds__(kThreads) void path_kernel(PathArgs a) {
 // least total of the sequences that end there.  Which source and candidate reach a minimum is not part
 // of the recurrence; path_pred_kernel recomputes the same rounded sums from the stored totals for all
 // windows in parallel and records the predecessors (least total, then lowest candidate), and
-// path_trace_kernel follows them back.  What the walk costs is the instructions one window's step takes
+// the two path_trace kernels follow them back, all runs of windows at once.  What the walk costs is the instructions one window's step takes
 // in the block's waves (they share the four SIMDs of one compute unit), so the step holds nothing else:
 // global memory is touched a chunk of windows at a time and a source's total is a lane read.
 constexpr int kChainChunk = 16;                            // windows per visit to global memory
-constexpr int kChainWaves = 8;
+constexpr int kChainWaves = 8;                             // measured on a day of windows and 48 layouts: 4 waves 811 us, 8 waves 740 us, 16 waves 788 us for the whole selection
 constexpr int kEndMark = -2;                               // kend: a sequence ends in this window (before path_pred_kernel fills in its best end)
 
 // thread = (cell, layout): least cost among the layout's candidates, lowest candidate among equals
