@@ -36,6 +36,11 @@ __global__ void init_word_header_kernel(WsHeader* h) {   // header regions are 2
   ((uint32_t*)h)[DYN_WS_HEADER_ORDER_WORD] = 0u;         // ingestion: "not in window order" flag
 }
 
+// Lengths of windows and ticks, capacities and grid spacings are kept inside this range so that the
+// reciprocal-based division of the kernels never meets a subnormal or infinite intermediate.
+constexpr double kMinScale = 1e-100, kMaxScale = 1e100;
+bool in_scale(double x) { return x >= kMinScale && x <= kMaxScale; }   // false for NaN
+
 bool strictly_increasing(const double* g, int n) {
   for (int i = 0; i < n; ++i)
     if (!isfinite(g[i])) return false;
@@ -312,7 +317,7 @@ int eval_impl(dyn_profile* p, const dyn_trace_view* t, const dyn_config* cfg, in
   if (sel && (rc = check_selection(sel)) != DYN_OK) return rc;
   if (t->n_req < 0 || t->n_req >= ((int64_t)1 << 31) || t->n_window < 1) { dyn_set_error("n_req or n_window out of range"); return DYN_E_SHAPE; }
   if (!t->cell_off || (t->n_req > 0 && (!t->in_tok || !t->out_tok))) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
-  if (!(t->window_s > 0.0) || !isfinite(t->window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  if (!in_scale(t->window_s)) { dyn_set_error("window_s must lie in [1e-100, 1e100]"); return DYN_E_RANGE; }
   const int64_t cells = (int64_t)t->n_window * p->G;
   if (cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
   if ((rc = check_device(p)) != DYN_OK) return rc;
@@ -393,10 +398,13 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
     }
   }
   for (size_t i = 0; i < n_row; ++i)
-    if (!isfinite(d->max_load_tps[i]) || !(d->max_load_tps[i] > 0.0)) {
-      dyn_set_error("max_load_tps[%zu] must be finite and > 0", i);
+    if (!in_scale(d->max_load_tps[i])) {
+      dyn_set_error("max_load_tps[%zu] must lie in [1e-100, 1e100]", i);
       return DYN_E_NOTFINITE;
     }
+  if (!(d->rho[d->n_rho - 1] <= kMaxScale)) { dyn_set_error("rho[] must stay below 1e100"); return DYN_E_RANGE; }
+  for (int q = 1; q < d->n_rho; ++q)
+    if (!(d->rho[q] - d->rho[q - 1] >= kMinScale)) { dyn_set_error("rho[] spacing below 1e-100"); return DYN_E_RANGE; }
 
   dyn_profile* p = new (std::nothrow) dyn_profile();
   if (!p) { dyn_set_error("out of host memory"); return DYN_E_DEVICE; }
@@ -502,7 +510,7 @@ int dyn_trace_ingest(const double* t_s, const int32_t* in_tok, const int32_t* ou
   if (n_req > 0 && (!t_s || !in_tok || !out_tok || !in_sorted || !out_sorted)) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
   if (e->n_model < 1 || e->n_in_bin < 1 || e->n_out_bin < 1 || n_window < 1) { dyn_set_error("class or window counts < 1"); return DYN_E_SHAPE; }
   if ((e->n_in_bin > 1 && !e->in_edge) || (e->n_out_bin > 1 && !e->out_edge)) { dyn_set_error("edge array is NULL"); return DYN_E_NULL; }
-  if (!(window_s > 0.0) || !isfinite(window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  if (!in_scale(window_s)) { dyn_set_error("window_s must lie in [1e-100, 1e100]"); return DYN_E_RANGE; }
   const int64_t G = (int64_t)e->n_model * e->n_in_bin * e->n_out_bin;
   const int64_t cells = G * n_window;
   if (G >= ((int64_t)1 << 30) || cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
@@ -589,7 +597,7 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   if (t->n_req < 0 || t->n_req >= ((int64_t)1 << 31) || t->n_window < 1) { dyn_set_error("n_req or n_window out of range"); return DYN_E_SHAPE; }
   if (t->n_window % n_tick != 0) { dyn_set_error("fine n_window=%d is not a multiple of n_tick=%d", t->n_window, n_tick); return DYN_E_SHAPE; }
   if (!t->cell_off || (t->n_req > 0 && (!t->in_tok || !t->out_tok))) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
-  if (!(t->window_s > 0.0) || !isfinite(t->window_s)) { dyn_set_error("tick length must be finite and > 0"); return DYN_E_RANGE; }
+  if (!in_scale(t->window_s)) { dyn_set_error("tick length must lie in [1e-100, 1e100]"); return DYN_E_RANGE; }
   const int32_t n_window = t->n_window / n_tick;
   const int64_t cells = (int64_t)n_window * p->G, fine_cells = cells * n_tick;
   if (fine_cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * n_tick * classes must stay below 2^30"); return DYN_E_SHAPE; }
@@ -709,7 +717,7 @@ int dyn_eval_select_mixed(dyn_profile* p, const dyn_trace_view* t, const dyn_mix
   }
   if (t->n_req < 0 || t->n_req >= ((int64_t)1 << 31) || t->n_window < 1) { dyn_set_error("n_req or n_window out of range"); return DYN_E_SHAPE; }
   if (!t->cell_off || (t->n_req > 0 && (!t->in_tok || !t->out_tok))) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
-  if (!(t->window_s > 0.0) || !isfinite(t->window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  if (!in_scale(t->window_s)) { dyn_set_error("window_s must lie in [1e-100, 1e100]"); return DYN_E_RANGE; }
   const int64_t cells = (int64_t)t->n_window * p->G;
   if (cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
   int rc;
@@ -802,10 +810,12 @@ int dyn_select_path(dyn_profile* p, const dyn_space* space, const dyn_config* cf
   if (!out->sel || !out->sel_energy_j || !out->path_cost || !out->window_energy_j || !out->window_infeasible) { dyn_set_error("an output array is NULL"); return DYN_E_NULL; }
   if (!tr->layout || !tr->transition_j) { dyn_set_error("layout or transition_j is NULL"); return DYN_E_NULL; }
   if (n_window < 1) { dyn_set_error("n_window < 1"); return DYN_E_SHAPE; }
-  if (!(window_s > 0.0) || !isfinite(window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  if (!in_scale(window_s)) { dyn_set_error("window_s must lie in [1e-100, 1e100]"); return DYN_E_RANGE; }
   if (!isfinite(o->idle_cost_weight)) { dyn_set_error("idle_cost_weight is not finite"); return DYN_E_NOTFINITE; }
   if (o->idle_cost_weight < 0.0) { dyn_set_error("idle_cost_weight must be >= 0"); return DYN_E_RANGE; }
   if ((int64_t)n_window * p->G >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
+  if (K < 1 || K > DYN_MAX_CONFIGS) { dyn_set_error("K=%d outside [1, %d]", K, DYN_MAX_CONFIGS); return DYN_E_SHAPE; }
+  if (tr->n_layout < 1) { dyn_set_error("n_layout < 1"); return DYN_E_SHAPE; }
   if (!dyn_path_fits(K, tr->n_layout)) {
     dyn_set_error("K=%d, n_layout=%d: beyond 64 layouts the per-class state (K <= %d candidates, n_layout^2 overheads) must fit in LDS", K, tr->n_layout, DYN_PATH_MAX_CONFIGS);
     return DYN_E_SHAPE;
@@ -869,7 +879,7 @@ int dyn_account(dyn_profile* p, const int32_t* sel, const double* window_energy_
   if (!p || !sel || !window_energy_j || !r || !out || !workspace) { dyn_set_error("profile, sel, window_energy_j, rates, out or workspace is NULL"); return DYN_E_NULL; }
   if (!r->carbon_g_per_kwh || !out->gpus || !out->gpu_cost || !out->energy_cost || !out->carbon_g || !out->totals) { dyn_set_error("an array is NULL"); return DYN_E_NULL; }
   if (n_window < 1 || r->gpus_per_server < 1) { dyn_set_error("n_window or gpus_per_server < 1"); return DYN_E_SHAPE; }
-  if (!(window_s > 0.0) || !isfinite(window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  if (!in_scale(window_s)) { dyn_set_error("window_s must lie in [1e-100, 1e100]"); return DYN_E_RANGE; }
   if (!isfinite(r->gpu_hour_price) || !isfinite(r->kwh_price)) { dyn_set_error("a price is not finite"); return DYN_E_NOTFINITE; }
   int rc = check_device(p);
   if (rc) return rc;
@@ -940,7 +950,7 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
     return DYN_E_SHAPE;
   }
   if (!tc->cell_off || !tf->cell_off || (tc->n_req > 0 && (!tc->in_tok || !tc->out_tok || !tf->in_tok || !tf->out_tok))) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
-  if (!(tf->window_s > 0.0) || !isfinite(tf->window_s)) { dyn_set_error("tick length must be finite and > 0"); return DYN_E_RANGE; }
+  if (!in_scale(tf->window_s)) { dyn_set_error("tick length must lie in [1e-100, 1e100]"); return DYN_E_RANGE; }
   if (c->epoch_windows < 1 || c->gpus_per_node < 1 || c->n_layout < 1) { dyn_set_error("epoch_windows, gpus_per_node or n_layout < 1"); return DYN_E_SHAPE; }
   if (p->n_tp > 64 || p->G > 4096) { dyn_set_error("dyn_hierarchy takes profiles of up to 64 TP degrees and 4096 classes"); return DYN_E_SHAPE; }
   if (c->tp_ref_index < 0 || c->tp_ref_index >= p->n_tp || c->f_ref_index < 0 || c->f_ref_index >= p->n_f) { dyn_set_error("reference configuration outside the profile"); return DYN_E_RANGE; }
@@ -1077,8 +1087,9 @@ int dyn_select_config(dyn_profile* p, const dyn_space* space, const dyn_config* 
   if (!space->energy_j || !space->flags) { dyn_set_error("space->energy_j or space->flags is NULL"); return DYN_E_NULL; }
   if (!out->sel || !out->sel_energy_j || !out->sel_cost || !out->window_energy_j || !out->window_infeasible) { dyn_set_error("an output array is NULL"); return DYN_E_NULL; }
   if (n_window < 1) { dyn_set_error("n_window < 1"); return DYN_E_SHAPE; }
-  if (!(window_s > 0.0) || !isfinite(window_s)) { dyn_set_error("window_s must be finite and > 0"); return DYN_E_RANGE; }
+  if (!in_scale(window_s)) { dyn_set_error("window_s must lie in [1e-100, 1e100]"); return DYN_E_RANGE; }
   if (!isfinite(o->idle_cost_weight)) { dyn_set_error("idle_cost_weight is not finite"); return DYN_E_NOTFINITE; }
+  if (o->idle_cost_weight < 0.0) { dyn_set_error("idle_cost_weight must be >= 0"); return DYN_E_RANGE; }
   if ((int64_t)n_window * p->G >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
   int rc = check_device(p);
   if (rc) return rc;

@@ -13,7 +13,7 @@
 // the cell, so the j-th largest element cannot be below it): for a high percentile only a
 // few bits are left.  Larger cells are streamed from global memory by the whole block,
 // once for the sums and once per 10-bit digit, through an LDS histogram (radix select).
-#include "dyn_internal.h"
+#include "dyn_device.h"
 
 namespace {
 
@@ -21,47 +21,6 @@ constexpr int kWavesPerBlock = 4;
 constexpr int kHistBits = 10;
 constexpr int kHistBins = 1 << kHistBits;
 constexpr int kRegRowsMax = 32;  // register path handles m <= 64 * kRegRowsMax
-
-template <int CTRL>
-__device__ __forceinline__ int dpp_mov(int v) {
-  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
-}
-// Sum over the 64 lanes of a fully active wave; the result is wave-uniform.
-// Rotations by 1, 2, 4, 8 inside each row of 16 lanes leave the row total in every lane
-// of the row; the four row totals are then read from lanes 0, 16, 32, 48.
-__device__ __forceinline__ int wave_sum_i32(int v) {
-  v += dpp_mov<0x121>(v);  // row_ror:1
-  v += dpp_mov<0x122>(v);  // row_ror:2
-  v += dpp_mov<0x124>(v);  // row_ror:4
-  v += dpp_mov<0x128>(v);  // row_ror:8
-  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
-         __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
-}
-__device__ __forceinline__ uint32_t wave_or_u32(uint32_t x) {
-  int v = (int)x;
-  v |= dpp_mov<0x121>(v);
-  v |= dpp_mov<0x122>(v);
-  v |= dpp_mov<0x124>(v);
-  v |= dpp_mov<0x128>(v);
-  return (uint32_t)(__builtin_amdgcn_readlane(v, 0) | __builtin_amdgcn_readlane(v, 16) |
-                    __builtin_amdgcn_readlane(v, 32) | __builtin_amdgcn_readlane(v, 48));
-}
-
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
-  x = max(x, (uint32_t)dpp_mov<0x121>((int)x));
-  x = max(x, (uint32_t)dpp_mov<0x122>((int)x));
-  x = max(x, (uint32_t)dpp_mov<0x124>((int)x));
-  x = max(x, (uint32_t)dpp_mov<0x128>((int)x));
-  const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
-  const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
-  return max(max(a, b), max(c, d));
-}
-
-__device__ __forceinline__ int64_t readlane_i64(int64_t x, int lane) {   // lane must be wave-uniform
-  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, lane);
-  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)x >> 32), lane);
-  return (int64_t)(((uint64_t)hi << 32) | lo);
-}
 
 struct CellOut {
   int64_t tin, tout;
@@ -169,12 +128,6 @@ __device__ __forceinline__ CellOut cell_by_wave(const int32_t* __restrict__ in, 
   return cell_in_registers<32>(in, out, beg, mi, rk, lane);
 }
 
-__device__ __forceinline__ int64_t wave_sum_i64(int64_t v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, DYN_WAVE);
-  return v;
-}
-
 // Large cell, whole block: the 256 threads stream the cell from global memory once for the
 // sums and once per 10-bit digit of the selection (radix select through one LDS histogram).
 // Every thread returns the same result.  `hist` (kHistBins counters) and `xch` (16 words)
@@ -198,7 +151,7 @@ __device__ __forceinline__ CellOut cell_by_block(const int32_t* __restrict__ in,
     for (int u = 0; u < U; ++u) {
       sin += a[u];
       sout += b[u];
-      orv |= (uint32_t)a[u];
+      orv |= (uint32_t)(a[u] | b[u]);
     }
   }
   sin = wave_sum_i64(sin);
@@ -295,12 +248,7 @@ __device__ __forceinline__ void write_cell(int64_t c, const CellOut& r, int64_t 
   tout[c] = r.tout;
   in_p99[c] = (int32_t)r.p99;
   CellRec cr;
-  {  // tokens / window_s, correctly rounded, from r_window = RN(1 / window_s)
-    const double tok = (double)(r.tin + r.tout);
-    const double q = tok * r_window;
-    const double e = __builtin_fma(-window_s, q, tok);
-    cr.load = __builtin_fma(e, r_window, q);
-  }
+  cr.load = div_by((double)(r.tin + r.tout), window_s, r_window);   // tokens / window_s, r_window = RN(1 / window_s)
   cr.xp99 = (double)(int32_t)r.p99;
   cr.nonempty = m > 0 ? 1.0 : 0.0;
   cr.pad = 0.0;

@@ -25,11 +25,12 @@ constexpr int kScanChunk = 4096;                       // counters per block of 
 
 constexpr int kKeyRows = 4;                            // requests per thread of the key kernel (rows of 256)
 
-// Window of a timestamp: floor(t / window_s), the quotient formed from RN(1 / window_s) with one correction step
-// (the correctly rounded quotient, three instructions instead of a division); clamped, out-of-range flagged.
+// Window of a timestamp: floor(t / window_s), the quotient formed from RN(1 / window_s) by div_by (correctly rounded
+// for timestamps whose quotient is a normal number; a handful of multiply-adds instead of a division).  Quotients that are
+// not finite, and tiny ones (below 2^-900, where a residual could underflow), take the IEEE division; clamped, out-of-range flagged.
 __device__ __forceinline__ double window_of(double t, double window_s, double r_window, int32_t n_window, uint32_t* bad) {
   double q = div_by(t, window_s, r_window);
-  if (q != q) q = t / window_s;                        // infinite timestamp or quotient: the correction step gives NaN
+  if (!(fabs(q) >= 0x1p-900 && fabs(q) <= 0x1p900)) q = t / window_s;   // also NaN: a residual step on an infinite product
   double wq = floor(q);
   if (!(wq >= 0.0)) { *bad = DYN_WS_BAD_REQUEST; wq = 0.0; }                      // negative or NaN
   if (!(wq < (double)n_window)) { *bad = DYN_WS_BAD_REQUEST; wq = (double)(n_window - 1); }

@@ -11,38 +11,14 @@
 //
 // The two divisions per entry (load / capacity, position inside the load bracket) have
 // divisors that do not depend on the window: their correctly rounded reciprocals are
-// computed once (per thread, per grid interval) and each quotient is then formed as
-// q = a*r, e = fma(-b, q, a), q + e*r, which is the closing step of the usual
-// Newton-Raphson division and returns the correctly rounded a/b.
+// computed once (per thread, per grid interval) and each quotient is then formed from the
+// reciprocal with two residual steps (div_by), which returns the correctly rounded a/b.
 //
 // With the fused selection, each wave also reduces the least cost among its feasible
 // configurations (Section IV-B "Scale-up/down") and one lane writes a partial record.
-#include "dyn_internal.h"
+#include "dyn_device.h"
 
 namespace {
-
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_row_u32(uint32_t x) {
-  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, false);
-}
-// Minimum over the 64 lanes of a fully active wave: rotations inside each row of 16 lanes
-// leave the row minimum in every lane, the four row minima are combined as scalars.
-__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
-  x = min(x, dpp_row_u32<0x121>(x));  // row_ror:1
-  x = min(x, dpp_row_u32<0x122>(x));  // row_ror:2
-  x = min(x, dpp_row_u32<0x124>(x));  // row_ror:4
-  x = min(x, dpp_row_u32<0x128>(x));  // row_ror:8
-  const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
-  const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
-  return min(min(a, b), min(c, d));
-}
-
-// a / b given rb = RN(1 / b): correctly rounded for normal operands and quotients.
-__device__ __forceinline__ double div_by(double a, double b, double rb) {
-  const double q = a * rb;
-  const double e = __builtin_fma(-b, q, a);
-  return __builtin_fma(e, rb, q);
-}
 
 // LDS: [table rows n_slot*3*n_rho] [padded load grid n_rho+2] [padded reciprocal spacings n_rho+1]
 //      [cell records win_per_block] [bucket index n_bucket+1 (16-bit)]

@@ -398,6 +398,11 @@ def test_small_cells_bad_offsets_and_negative_tokens_are_reported_per_cell(dyn):
     keep = np.ones(sizes.size, bool); keep[33] = False
     np.testing.assert_array_equal(g["tin"][keep], good["tin"][keep])
     np.testing.assert_array_equal(g["in_p99"][keep], good["in_p99"][keep])
+    # a negative output length inside a cell that the whole block takes (more than 2048 requests)
+    big = rng.integers(1, 8193, 5000); yb = rng.integers(1, 8193, 5000); yb[4321] = -7
+    g = _single(dyn, prof, cfg, big, yb, 100, 50, 1000.0)[2]
+    assert g["status"] & dyn.DYN_WS_BAD_REQUEST
+    assert g["tin"][0] == int(big.sum()) and g["tout"][0] == int(yb.sum())
 
 
 def test_off_grid_frequencies_single_frequency_and_odd_k(dyn):
