@@ -221,6 +221,24 @@ int dyn_eval_select(dyn_profile* profile, const dyn_trace_view* trace, const dyn
                     const dyn_selection* sel, void* workspace, size_t workspace_bytes,
                     void* hip_stream);
 
+/* dyn_eval_select for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same computation and outputs as
+ * dyn_eval_select, but the workspace is a fixed array of DYN_STATIC_WORKSPACE_BYTES that the
+ * library keeps on every GPU it runs on until the process ends; the call allocates and frees
+ * nothing.  n_window * G cells with K configurations must satisfy
+ * dyn_eval_space_workspace(n_window, G, K) <= DYN_STATIC_WORKSPACE_BYTES (the one-day workload
+ * of 36000 cells x 576 configurations needs 13.1 MB), else DYN_E_WORKSPACE and nothing is launched.
+ * `status` (DEVICE, one word, may be NULL) receives the DYN_WS_* bits of this call.
+ * All calls on one GPU share the array: calls that overlap in time on one GPU (two streams, two
+ * host threads) race; every call rewrites all of it that it reads, so nothing has to be cleared
+ * between calls.  As with dyn_eval_select, a candidate list or objective that differs from the one
+ * the profile handle holds is uploaded first, which waits for the stream: make the first call
+ * with a new list outside a graph capture.                                                */
+#define DYN_STATIC_WORKSPACE_BYTES (16u << 20)
+int dyn_eval_select_static(dyn_profile* profile, const dyn_trace_view* trace, const dyn_config* cfg,
+                           int32_t K, const dyn_objective* objective, const dyn_space* space,
+                           const dyn_selection* sel, uint32_t* status, void* hip_stream);
+
 /* ----------------------------------------------------------- tick-level load in a window --
  * Section IV-B "Scale-up/down": inside a window the instance manager follows the load at
  * a finer grain (every few seconds) than the window the configuration is chosen for.  Here

@@ -15,7 +15,8 @@ import torch
 
 __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_trace_ingest",
            "dyn_trace_ingest_workspace", "dyn_eval_space", "dyn_eval_space_workspace", "dyn_cell_stats",
-           "dyn_workspace_status", "dyn_select_config", "dyn_eval_select", "dyn_last_error", "lib_path",
+           "dyn_workspace_status", "dyn_select_config", "dyn_eval_select", "dyn_eval_select_static",
+           "DYN_STATIC_WORKSPACE_BYTES", "dyn_last_error", "lib_path",
            "dyn_timing_enable", "dyn_timing_reset", "dyn_timing_read", "DYN_K_CELL", "DYN_K_SPACE", "DYN_K_SELECT",
            "DYN_K_TOTALS",
            "DYN_F_FEASIBLE", "DYN_F_OVERLOAD", "DYN_F_TTFT", "DYN_F_TBT", "DYN_F_BUDGET", "DYN_F_EMPTY",
@@ -27,6 +28,7 @@ __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_t
 DYN_F_FEASIBLE, DYN_F_OVERLOAD, DYN_F_TTFT, DYN_F_TBT, DYN_F_BUDGET, DYN_F_EMPTY = 1, 2, 4, 8, 16, 32
 DYN_WS_BAD_OFFSETS, DYN_WS_BAD_REQUEST, DYN_WS_TICK_RANK = 1, 2, 4
 DYN_TICK_LIMIT, DYN_TICK_DEPTH = 16, 64
+DYN_STATIC_WORKSPACE_BYTES = 16 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -139,6 +141,9 @@ _lib.dyn_select_config.argtypes = [_vp, C.POINTER(_Space), C.POINTER(_Config), _
 _lib.dyn_eval_select.restype = C.c_int
 _lib.dyn_eval_select.argtypes = [_vp, C.POINTER(_TraceView), C.POINTER(_Config), _i32, C.POINTER(_Objective),
                                  C.POINTER(_Space), C.POINTER(_Selection), _vp, _sz, _vp]
+_lib.dyn_eval_select_static.restype = C.c_int
+_lib.dyn_eval_select_static.argtypes = [_vp, C.POINTER(_TraceView), C.POINTER(_Config), _i32, C.POINTER(_Objective),
+                                        C.POINTER(_Space), C.POINTER(_Selection), _vp, _vp]
 _lib.dyn_eval_ticks_workspace.restype = _sz
 _lib.dyn_eval_ticks_workspace.argtypes = [_i32, _i32, _i32, _i32]
 _lib.dyn_eval_select_ticks.restype = C.c_int
@@ -396,6 +401,23 @@ def dyn_eval_select(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tenso
     _check(_lib.dyn_eval_select(profile.handle, C.byref(tv), plan.cfg, K, C.byref(plan.obj), C.byref(sp), C.byref(se),
                                 _dp(workspace), workspace.numel(), _stream(stream)), "dyn_eval_select")
     return out, sel, workspace
+
+
+def dyn_eval_select_static(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tensor, cell_off: torch.Tensor,
+                           n_window: int, window_s: float, plan: Plan, out: Dict[str, torch.Tensor],
+                           sel: Dict[str, torch.Tensor], status: Optional[torch.Tensor] = None, stream=None):
+    """dyn_eval_select on the library's fixed workspace: nothing is allocated, here or in the library, so `out` and
+    `sel` (and `status`, one int32/uint32 word on the device, optional) are the caller's."""
+    if out is None or sel is None:
+        raise ValueError("dyn_eval_select_static allocates nothing: pass the output tensors")
+    dummy = cell_off                      # any device tensor: _eval_args allocates a workspace only when given None
+    tv, sp, out, _, cells, K = _eval_args(profile, in_tok, out_tok, cell_off, n_window, window_s, plan, out, dummy)
+    se = _selection_struct(sel)
+    if status is not None and (status.numel() != 1 or status.element_size() != 4):
+        raise ValueError("status must be one 32-bit word")
+    _check(_lib.dyn_eval_select_static(profile.handle, C.byref(tv), plan.cfg, K, C.byref(plan.obj), C.byref(sp),
+                                       C.byref(se), _dp(status), _stream(stream)), "dyn_eval_select_static")
+    return out, sel
 
 
 def dyn_eval_ticks_workspace(n_window: int, n_tick: int, n_class: int, n_config: int) -> int:

@@ -231,6 +231,45 @@ IngestWs ingest_ws_layout(int64_t n_req, int32_t n_model, int32_t n_in_bin, int3
 
 }  // namespace
 
+// ---- fixed workspace of dyn_eval_select_static ---------------------------------------------
+// One array per GPU the library runs on, held until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress: kernels and copies get the address that call
+// returns for the current device, never the name.
+static __device__ __align__(256) unsigned char scratch[DYN_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, once resolved
+
+// Address of the current device's copy of `scratch` (resolved once per device, with that device current).
+int scratch_address(void** out) {
+  int dev = -1;
+  if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return DYN_E_DEVICE;
+  if (dev < 0 || dev >= kMaxDevices) { dyn_set_error("device %d: the library keeps a fixed workspace on devices 0..%d only", dev, kMaxDevices - 1); return DYN_E_DEVICE; }
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (!hip_ok(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)")) return DYN_E_DEVICE;
+    if (!ptr || ((uintptr_t)ptr & 255)) { dyn_set_error("the fixed workspace has no usable device address"); return DYN_E_DEVICE; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return DYN_OK;
+}
+
+// OR of the per-cell status bytes, written (not accumulated) to *status by one block.
+__global__ __launch_bounds__(1024) void cell_status_word_kernel(const uint8_t* __restrict__ cstat, int64_t cells,
+                                                                uint32_t* __restrict__ status) {
+  __shared__ uint32_t s_or;
+  if (threadIdx.x == 0) s_or = 0u;
+  __syncthreads();
+  uint32_t v = 0;
+  for (int64_t i = threadIdx.x; i < cells; i += blockDim.x) v |= cstat[i];
+  if (v) atomicOr(&s_or, v);
+  __syncthreads();
+  if (threadIdx.x == 0) *status = s_or;
+}
+}  // namespace
+
 // ---- optional kernel timing ---------------------------------------------------------------
 namespace {
 struct TimerPool {
@@ -463,6 +502,8 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   std::vector<double> pw0(n_row);
   for (size_t r = 0; r < n_row; ++r) pw0[r] = d->power_w[r * d->n_rho];
 
+  void* fixed_ws = nullptr;
+  (void)scratch_address(&fixed_ws);   // set-up of dyn_eval_select_static on this device; that call reports a failure itself
   bool ok = hip_ok(hipGetDevice(&p->device), "hipGetDevice") &&
             hip_ok(dev_alloc(&p->d_tab, 3 * n_tab), "hipMalloc") && hip_ok(dev_alloc(&p->d_ml, n_row), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_pw0, n_row), "hipMalloc") && hip_ok(dev_alloc(&p->d_gridpack, gridpack.size()), "hipMalloc") &&
@@ -579,6 +620,33 @@ int dyn_eval_select(dyn_profile* p, const dyn_trace_view* t, const dyn_config* c
                     size_t workspace_bytes, void* hip_stream) {
   if (!sel) { dyn_set_error("selection is NULL"); return DYN_E_NULL; }
   return eval_impl(p, t, cfg, K, o, out, sel, workspace, workspace_bytes, hip_stream);
+}
+
+int dyn_eval_select_static(dyn_profile* p, const dyn_trace_view* t, const dyn_config* cfg, int32_t K,
+                           const dyn_objective* o, const dyn_space* out, const dyn_selection* sel,
+                           uint32_t* status, void* hip_stream) {
+  if (!sel) { dyn_set_error("selection is NULL"); return DYN_E_NULL; }
+  if (!p || !t) { dyn_set_error("profile or trace is NULL"); return DYN_E_NULL; }
+  if (t->n_window < 1 || K < 1) { dyn_set_error("n_window or K < 1"); return DYN_E_SHAPE; }
+  const int64_t cells = (int64_t)t->n_window * p->G;
+  if (cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
+  const EvalWs w = dyn_eval_ws_layout(cells, K);
+  if (w.total > (size_t)DYN_STATIC_WORKSPACE_BYTES) {
+    dyn_set_error("%lld cells x %d configurations need %zu bytes of workspace, the fixed one holds %zu: use dyn_eval_select with a workspace of the caller",
+                  (long long)cells, K, w.total, (size_t)DYN_STATIC_WORKSPACE_BYTES);
+    return DYN_E_WORKSPACE;
+  }
+  int rc;
+  if ((rc = check_device(p)) != DYN_OK) return rc;
+  void* ws = nullptr;
+  if ((rc = scratch_address(&ws)) != DYN_OK) return rc;
+  if ((rc = eval_impl(p, t, cfg, K, o, out, sel, ws, (size_t)DYN_STATIC_WORKSPACE_BYTES, hip_stream)) != DYN_OK) return rc;
+  if (status) {
+    hipLaunchKernelGGL(cell_status_word_kernel, dim3(1), dim3(1024), 0, (hipStream_t)hip_stream,
+                       (const uint8_t*)((const char*)ws + w.cstat), cells, status);
+    if (!hip_ok(hipGetLastError(), "status launch")) return DYN_E_DEVICE;
+  }
+  return DYN_OK;
 }
 
 size_t dyn_eval_ticks_workspace(int32_t n_window, int32_t n_tick, int32_t n_class, int32_t n_config) {
