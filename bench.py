@@ -94,6 +94,47 @@ def cpu_baseline(w, n_sample_windows, ticks=0, mixed=None, path=None, hier=None)
                       f"{dt:.1f} s, single thread)"}
 
 
+def oracle_every_cell(w, gpu_sorted, gpu_sel):
+    """The oracle over EVERY cell of the workload, its windows dealt to the host's cores (each task is one plain call of
+    the single-threaded oracle), on the oracle's own ingestion of the raw trace; then the GPU's selections against it.
+    Returns (all-core baseline entry, parity entry)."""
+    import numpy as np
+    import oracle
+    NW, G, k = w["n_window"], w["n_class"], w["configs"]["n_inst"].size
+    st = oracle.ingest(w["trace"], w["edges"], NW, w["window_s"])
+    same_trace = all(np.array_equal(gpu_sorted[i], st[n]) for i, n in enumerate(("in_tok", "out_tok", "cell_off")))
+    t0 = time.perf_counter()
+    o = oracle.evaluate_parallel(w["profile"], st, NW, w["window_s"], w["configs"], w["slos"], w["pct"], None,
+                                 w["idle_cost_weight"])
+    dt = time.perf_counter() - t0
+    R = w["trace"]["t_s"].size
+    allcores = {"value": R * k / dt, "unit": "evals/s", "cores": o["threads"], "kind": "oracle",
+                "sample": f"all {NW} windows ({R} requests x {k} configurations, {dt:.1f} s, windows dealt to "
+                          f"{o['threads']} threads)"}
+    bad = np.nonzero(gpu_sel["sel"] != o["sel"])[0]
+    excused = 0
+    if bad.size:       # ties within 1e-9 relative among oracle-feasible candidates are the stated tolerance
+        ob = oracle.evaluate(w["profile"], st, NW, w["window_s"], w["configs"], w["slos"], w["pct"], None,
+                             w["idle_cost_weight"], cell_ids=bad.astype(np.int64))
+        for i, c in enumerate(bad):
+            kg, ko = int(gpu_sel["sel"][c]), int(o["sel"][c])
+            if kg >= 0 and ko >= 0 and (ob["flags"][i, kg] & 1) and \
+                    abs(ob["cost"][i, kg] - ob["cost"][i, ko]) <= 1e-9 * abs(ob["cost"][i, ko]):
+                excused += 1
+    same = gpu_sel["sel"] == o["sel"]
+    fin = same & (o["sel"] >= 0)
+    rel = np.abs(gpu_sel["sel_energy_j"][fin] - o["sel_energy_j"][fin]) / np.abs(o["sel_energy_j"][fin])
+    we, wi = oracle.window_totals(o["sel"], o["sel_energy_j"], NW, G)
+    parity = {"cells": int(o["sel"].size), "sel_mismatch": int(bad.size), "excused": excused,
+              "sel_energy_max_rel_err": float(rel.max()) if rel.size else 0.0,
+              "sel_energy_bit_equal": bool(np.array_equal(gpu_sel["sel_energy_j"][same], o["sel_energy_j"][same])),
+              "window_energy_bit_equal": bool(np.array_equal(gpu_sel["window_energy_j"], we)),
+              "window_infeasible_equal": bool(np.array_equal(gpu_sel["window_infeasible"], wi)),
+              "gpu_ingest_equals_oracle_ingest": bool(same_trace),
+              "oracle": "every cell, on the oracle's own ingestion of the raw trace"}
+    return allcores, parity
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -294,6 +335,18 @@ def main():
     status = dyn.dyn_workspace_status(ws)
     assert status == 0 or (args.ticks and status == dyn.DYN_WS_TICK_RANK), status
 
+    # ---- the same step timed one by one with a pair of HIP events each, on the stream the kernels are launched on
+    # (torch's current stream is the one the binding hands to the library): the median of at least 20 repetitions
+    n_ev = max(args.steps, 20)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+    for e_a, e_b in pairs:
+        e_a.record()
+        step()
+        e_b.record()
+    torch.cuda.synchronize()
+    per_step = sorted(e_a.elapsed_time(e_b) for e_a, e_b in pairs)
+    ms_median = per_step[n_ev // 2]
+
     # ---- the same `steps` steps again with the library's per-kernel HIP events switched on (recorded
     # on the stream the kernels are launched on).  The event records themselves cost about 20 us per
     # step on this machine, which is why they are kept out of the throughput region above.
@@ -391,6 +444,8 @@ def main():
         roofline = {"bound": "hbm", "kernel": "space_kernel", "achieved": space_gbps, "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": space_gbps / HBM_PEAK_GBPS if space_gbps else None,
                     "traffic": None if (args.unfused or args.path) else recorded_traffic(args.config),
+                    "traffic_source": "profiles/space_kernel_traffic.json: FETCH_SIZE and WRITE_SIZE of two rocprofv3 --pmc runs of "
+                                      "this command, scaled by a plain copy; null once the kernel's sources have changed since",
                     "algorithmic_bytes_per_launch": space_bytes, "avg_launch_ms": space_ms}
 
     if args.hierarchy:
@@ -414,6 +469,7 @@ def main():
                    "entry_points": ("dyn_hierarchy" + ("+overheads" if args.overheads else "") + ("+spill" if args.spill else "")) if args.hierarchy else "dyn_eval_space+dyn_select_path" if args.path else "dyn_eval_select_mixed" if args.mixed else "dyn_eval_select_ticks" if args.ticks else
                                    "dyn_eval_space+dyn_select_config" if args.unfused else "dyn_eval_select"},
         "roofline": roofline,
+        "ms_per_step_median": ms_median, "median_over_event_timed_steps": n_ev,
         "kernel_ms": ktime, "ms_per_step_with_kernel_events": ms_per_step_events, "pipelined": pipelined,
         "path": {"algorithmic_bytes": path_bytes, "gbps": path_gbps, "frac_of_hbm_peak": path_gbps / HBM_PEAK_GBPS},
         "setup": {"ingest_ms": ingest_ms, "profile_load_ms": profile_load_ms, "generate_s": gen_s,
@@ -433,6 +489,11 @@ def main():
         out["cpu_baseline"] = cpu_baseline(w, nwin, args.ticks, mixed, (lay, trans) if args.path else None,
                                            hier_args + (hier_trans, args.spill, K) if args.hierarchy else None)
         out["cpu_baseline"]["host_cores"] = os.cpu_count()
+        if headline or args.unfused:   # the oracle over every cell on all cores; the selections of the timed steps against it
+            gpu_sel = {k_: v.cpu().numpy() for k_, v in sel.items()}
+            allc, par = oracle_every_cell(w, (ins.cpu().numpy(), outs.cpu().numpy(), off.cpu().numpy()), gpu_sel)
+            out["cpu_baseline"]["allcores"] = allc
+            out["parity"] = par
     prof.free()
     print(json.dumps(out))
 

@@ -105,6 +105,32 @@ def evaluate(profile: Dict[str, np.ndarray], sorted_trace: Dict[str, np.ndarray]
     return r
 
 
+def evaluate_parallel(profile, sorted_trace, n_window, window_s, configs, slos, pct=(99, 100), gpu_budget=None,
+                      idle_cost_weight=0.0, threads: Optional[int] = None, windows_per_task: int = 0,
+                      want_space: bool = False) -> Dict[str, np.ndarray]:
+    """evaluate() over every cell with the windows dealt to `threads` host threads (cells are independent; each
+    task is one plain call of the single-threaded oracle on a run of windows, and ctypes releases the
+    interpreter lock for its duration).  Same outputs as evaluate(), in cell order, plus "threads"."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    G = np.asarray(profile["prefill_ms_per_tok"]).shape[0]
+    threads = threads or min(32, os.cpu_count() or 1)
+    per = windows_per_task or max(1, n_window // (threads * 8))
+    tasks = [(w0, min(w0 + per, n_window)) for w0 in range(0, n_window, per)]
+
+    def run(t):
+        ids = np.arange(t[0] * G, t[1] * G, dtype=np.int64)
+        return evaluate(profile, sorted_trace, n_window, window_s, configs, slos, pct, gpu_budget, idle_cost_weight,
+                        cell_ids=ids, want_space=want_space)
+
+    _load()
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        parts = list(ex.map(run, tasks))
+    r = {k: np.concatenate([p_[k] for p_ in parts]) for k in parts[0]}
+    r["threads"] = threads
+    return r
+
+
 def evaluate_ticks(profile: Dict[str, np.ndarray], fine_trace: Dict[str, np.ndarray], n_window: int, n_tick: int,
                    tick_s: float, configs: Dict[str, np.ndarray], slos: Dict[str, np.ndarray], pct=(99, 100),
                    gpu_budget: Optional[np.ndarray] = None, idle_cost_weight: float = 0.0) -> Dict[str, np.ndarray]:

@@ -558,128 +558,110 @@ def test_calls_in_flight_on_two_streams_give_the_same_bits(dyn):
     prof.free()
 
 
-# ------------------------------------------------------------- full size, sampled cells
-def test_full_size_day_trace_sampled_cells(dyn):
-    """The benchmark workload (one-day trace, 10^7 requests, 36000 cells x 576 configurations) in the
-    benchmark's launch configuration; the oracle evaluates a sample of cells one by one, and
-    properties that hold at any size are checked over everything."""
-    w = make(SPECS[2])
-    tr = w["trace"]
-    ins, outs, off, ws = gpu_ingest(dyn, w)
-    assert dyn.dyn_workspace_status(ws) == 0
-    off_h = off.cpu().numpy()
-    assert off_h[0] == 0 and off_h[-1] == tr["t_s"].size and (np.diff(off_h) >= 0).all()
-    g = gpu_eval(dyn, w, ins, outs, off)
-    assert g["status"] == 0
-    cells = w["n_window"] * w["n_class"]
-    m = np.diff(off_h)
-    assert g["tin"].sum() == int(tr["in_tok"].astype(np.int64).sum())
-    assert g["tout"].sum() == int(tr["out_tok"].astype(np.int64).sum())
-    # sampled cells: the largest, the smallest non-empty, some empty, and random ones
-    rng = np.random.default_rng(0)
-    ids = np.unique(np.concatenate([[0, cells - 1, int(np.argmax(m))], np.nonzero(m == 0)[0][:5],
-                                    np.nonzero(m == 1)[0][:3], rng.integers(0, cells, 60)])).astype(np.int64)
-    st = {"in_tok": ins.cpu().numpy(), "out_tok": outs.cpu().numpy(), "cell_off": off_h}
-    # the sorted trace itself is checked against the oracle's ingestion on the sampled cells' windows
-    o = ora_eval(w, st, cell_ids=ids)
-    rep = assert_parity(w, g, o, cell_ids=ids, check_windows=False)
-    print("full-size sample:", rep, "cells sampled", ids.size)
-    assert rep["bit_exact"] and rep["sel_mismatch"] == 0
-    # size-independent properties
-    feas = (g["flags"] & 1).astype(bool)
-    sel = g["sel"]
-    has = sel >= 0
-    assert (feas.any(axis=1) == has).all()
-    assert feas[np.nonzero(has)[0], sel[has]].all()                       # infeasible is never selected
-    e_sel = g["energy_j"][np.nonzero(has)[0], sel[has]]
-    np.testing.assert_array_equal(e_sel, g["sel_energy_j"][has])
-    masked = np.where(feas, g["energy_j"], np.inf)
-    np.testing.assert_array_equal(masked.min(axis=1)[has], g["sel_energy_j"][has])
-    np.testing.assert_array_equal(masked.argmin(axis=1)[has], sel[has])   # lowest index among ties
-    we = np.where(has, g["sel_energy_j"], 0.0).reshape(w["n_window"], -1)
-    assert np.all(np.abs(g["window_energy_j"] - we.sum(axis=1)) <= 1e-12 * we.sum(axis=1))
-    np.testing.assert_array_equal(g["window_infeasible"], (~has).reshape(w["n_window"], -1).sum(axis=1))
-    assert ((g["flags"] & dyn.DYN_F_EMPTY) != 0).all(axis=1).tolist() == (m == 0).tolist()
+# ------------------------------------------------------------- full size, every cell
+def _excused(w, o_row, k_gpu, k_ora, g):
+    """The stated tolerance for a differing selection: both candidates feasible for the oracle and their oracle costs
+    within 1e-9 relative, or an oracle value of one of them within 1e-9 of a threshold (SLO, last load point)."""
+    if k_gpu < 0 or k_ora < 0:
+        ks = [k for k in (k_gpu, k_ora) if k >= 0]
+    else:
+        if (o_row["flags"][k_gpu] & 1) and abs(o_row["cost"][k_gpu] - o_row["cost"][k_ora]) <= RTOL * abs(o_row["cost"][k_ora]):
+            return True
+        ks = [k_gpu, k_ora]
+    st, sb = w["slos"]["slo_ttft_ms"][g], w["slos"]["slo_tbt_ms"][g]
+    return any(abs(o_row["p99_ttft_ms"][k] - st) <= RTOL * st or abs(o_row["p99_tbt_ms"][k] - sb) <= RTOL * sb for k in ks)
 
 
-@pytest.mark.parametrize("idx", [3, 4])
-def test_full_size_week_traces_sampled_cells(dyn, idx):
-    """The one-week workloads at full size (5*10^7 requests x 1152 configurations; 10^8 requests, four models,
-    2048 configurations with the idle-cost term) through ingest and the fused entry point; a sample of cells is
-    checked element by element against the oracle, the rest through properties computed on the device."""
+def compare_every_cell(w, st, g_sel, g_stats, o):
+    """g_sel: sel / sel_energy_j / sel_cost / window_* of the GPU (NumPy); g_stats: (tin, tout, in_p99); o: the
+    oracle over every cell.  Returns the counts the benchmark also prints."""
+    G, NW = w["n_class"], w["n_window"]
+    np.testing.assert_array_equal(g_stats[0], o["tin"])
+    np.testing.assert_array_equal(g_stats[1], o["tout"])
+    np.testing.assert_array_equal(g_stats[2], o["in_p99"])
+    bad = np.nonzero(g_sel["sel"] != o["sel"])[0]
+    excused = 0
+    if bad.size:
+        ob = oracle.evaluate(w["profile"], st, NW, w["window_s"], w["configs"], w["slos"], w["pct"], None,
+                             w["idle_cost_weight"], cell_ids=bad.astype(np.int64))
+        for i, c in enumerate(bad):
+            row = {k: ob[k][i] for k in ("flags", "cost", "p99_ttft_ms", "p99_tbt_ms")}
+            assert _excused(w, row, int(g_sel["sel"][c]), int(o["sel"][c]), int(c % G)), f"cell {c}: selection differs"
+            excused += 1
+    same = g_sel["sel"] == o["sel"]
+    fin = same & (o["sel"] >= 0)
+    for k in ("sel_energy_j", "sel_cost"):
+        a, b = g_sel[k][fin], o[k][fin]
+        assert np.all(np.abs(a - b) <= RTOL * np.abs(b)), k
+        assert np.all(np.isinf(g_sel[k][same & (o["sel"] < 0)]))
+    we, wi = oracle.window_totals(o["sel"], o["sel_energy_j"], NW, G)
+    clean = np.ones(NW, bool)
+    clean[np.unique(bad // G)] = False
+    assert np.all(np.abs(g_sel["window_energy_j"][clean] - we[clean]) <= RTOL * np.abs(we[clean]))
+    np.testing.assert_array_equal(g_sel["window_infeasible"][clean], wi[clean])
+    bit_equal = bool(np.array_equal(g_sel["sel_energy_j"][same], o["sel_energy_j"][same]) and
+                     np.array_equal(g_sel["sel_cost"][same], o["sel_cost"][same]) and
+                     np.array_equal(g_sel["window_energy_j"][clean], we[clean]))
+    return {"cells": int(o["sel"].size), "sel_mismatch": int(bad.size), "excused": excused, "bit_equal": bit_equal}
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_full_size_every_cell_against_the_oracle(dyn, idx):
+    """The named workloads at full size (one hour, one day, one week, one week with four models) in the launch
+    configuration the benchmark times.  The oracle ingests the raw trace itself and evaluates EVERY cell (its windows
+    dealt to the host's cores); compared: the sorted trace and offsets bit for bit, per cell the token sums, the
+    P99 input length, the selected configuration, its energy and cost, per window the totals.  On a sample of cells
+    the whole evaluated space is compared element by element as well."""
     w = make(SPECS[idx])
     tr = w["trace"]
     G, NW, K = w["n_class"], w["n_window"], w["configs"]["n_inst"].size
     cells = G * NW
+    st = oracle.ingest(tr, w["edges"], NW, w["window_s"])               # the oracle's own ingestion of the raw trace
     ins, outs, off, ws_i = gpu_ingest(dyn, w)
     assert dyn.dyn_workspace_status(ws_i) == 0
     del ws_i
-    off_h = off.cpu().numpy()
-    assert off_h[0] == 0 and off_h[-1] == tr["t_s"].size and (np.diff(off_h) >= 0).all()
+    assert torch.equal(off.cpu(), torch.from_numpy(st["cell_off"]))
+    assert torch.equal(ins.cpu(), torch.from_numpy(st["in_tok"]))
+    assert torch.equal(outs.cpu(), torch.from_numpy(st["out_tok"]))
     prof = dyn.dyn_profile_load(w["profile"])
     plan = dyn.Plan(w["configs"], w["slos"], w["pct"], None, w["idle_cost_weight"])
     space, sel, ws = dyn.dyn_eval_select(prof, ins, outs, off, NW, w["window_s"], plan)
     assert dyn.dyn_workspace_status(ws) == 0
     tin, tout, p99 = dyn.dyn_cell_stats(ws, NW, G)
     torch.cuda.synchronize()
-    assert int(tin.sum()) == int(tr["in_tok"].astype(np.int64).sum())
-    assert int(tout.sum()) == int(tr["out_tok"].astype(np.int64).sum())
-    m = np.diff(off_h)
+    o = oracle.evaluate_parallel(w["profile"], st, NW, w["window_s"], w["configs"], w["slos"], w["pct"], None,
+                                 w["idle_cost_weight"])
+    g_sel = {k: v.cpu().numpy() for k, v in sel.items()}
+    rep = compare_every_cell(w, st, g_sel, (tin.cpu().numpy(), tout.cpu().numpy(), p99.cpu().numpy()), o)
+    print(f"workload {idx} every cell:", rep, "oracle threads", o["threads"])
+    assert rep["sel_mismatch"] == 0 and rep["bit_equal"]
+    # the evaluated space element by element on a sample: largest cell, empty cells, cells the whole block takes, random
+    m = np.diff(st["cell_off"])
     rng = np.random.default_rng(idx)
-    ids = np.unique(np.concatenate([[0, cells - 1, int(np.argmax(m))], np.nonzero(m == 0)[0][:4],
-                                    np.nonzero(m > 4096)[0][:3], rng.integers(0, cells, 24)])).astype(np.int64)
-    # the sampled cells' requests, re-based so that the oracle sees a small trace
-    ins_h, outs_h = ins.cpu().numpy(), outs.cpu().numpy()
-    sub_in = np.concatenate([ins_h[off_h[c]:off_h[c + 1]] for c in ids]) if ids.size else np.zeros(0, np.int32)
-    sub_out = np.concatenate([outs_h[off_h[c]:off_h[c + 1]] for c in ids])
-    # one pseudo-window per sampled cell and class: cell j of the sub-trace sits at (window j, class g_j)
-    sub_off = np.zeros(ids.size * G + 1, np.int64)
-    pos = 0
-    for j, c in enumerate(ids):
-        g = int(c % G)
-        sub_off[j * G + g] = pos
-        pos += int(m[c])
-        sub_off[j * G + g + 1:] = pos
-    st = {"in_tok": sub_in, "out_tok": sub_out, "cell_off": sub_off}
-    o = oracle.evaluate(w["profile"], st, ids.size, w["window_s"], w["configs"], w["slos"], w["pct"], None,
-                        w["idle_cost_weight"], cell_ids=np.arange(ids.size) * G + (ids % G))
+    ids = np.unique(np.concatenate([[0, cells - 1, int(np.argmax(m))], np.nonzero(m == 0)[0][:4], np.nonzero(m == 1)[0][:3],
+                                    np.nonzero(m > 2048)[0][:3], rng.integers(0, cells, 40)])).astype(np.int64)
+    os_ = ora_eval(w, st, cell_ids=ids)
     idt = torch.from_numpy(ids).cuda()
     g_ = {k: v.index_select(0, idt).cpu().numpy() for k, v in space.items()}
     g_.update({k: sel[k].index_select(0, idt).cpu().numpy() for k in ("sel", "sel_energy_j", "sel_cost")})
     g_.update(tin=tin.index_select(0, idt).cpu().numpy(), tout=tout.index_select(0, idt).cpu().numpy(),
               in_p99=p99.index_select(0, idt).cpu().numpy())
-    rep = assert_parity(w, g_, o, check_windows=False)
-    print(f"workload {idx} full size:", rep, "cells sampled", ids.size)
+    rep = assert_parity(w, g_, os_, check_windows=False)
     assert rep["bit_exact"] and rep["sel_mismatch"] == 0
-    # properties over every cell, computed on the device
+    # the selection is the argmin of the evaluated space (over every cell, on the device)
     s_ = sel["sel"].long()
     has = s_ >= 0
     rows = torch.nonzero(has).squeeze(1)
-    picked_fl = space["flags"][rows, s_[rows]]
-    assert bool(((picked_fl & 1) == 1).all())                                   # infeasible is never selected
+    assert bool(((space["flags"][rows, s_[rows]] & 1) == 1).all())                  # infeasible is never selected
     assert bool((space["energy_j"][rows, s_[rows]] == sel["sel_energy_j"][rows]).all())
     assert bool(((space["flags"] & 1).any(dim=1) == has).all())
-    empty = torch.from_numpy(m == 0).cuda()
-    assert bool((((space["flags"] & 32) != 0).all(dim=1) == empty).all())
-    we = torch.where(has, sel["sel_energy_j"], torch.zeros_like(sel["sel_energy_j"])).view(NW, G).sum(dim=1)
-    assert bool(((sel["window_energy_j"] - we).abs() <= 1e-12 * we).all())
-    assert bool((sel["window_infeasible"] == (~has).view(NW, G).sum(dim=1).int()).all())
+    assert bool((((space["flags"] & 32) != 0).all(dim=1) == torch.from_numpy(m == 0).cuda()).all())
+    if idx <= 2:        # the two-call route (dyn_eval_space, dyn_select_config) gives the same bits at this size too
+        space2 = {k: torch.empty_like(v) for k, v in space.items()}
+        dyn.dyn_eval_space(prof, ins, outs, off, NW, w["window_s"], plan, out=space2, workspace=ws)
+        sel2 = dyn.dyn_select_config(prof, space2, NW, w["window_s"], plan)
+        for k in space:
+            assert torch.equal(space2[k], space[k]), k
+        for k in sel:
+            assert torch.equal(sel2[k], sel[k]), k
     prof.free()
-
-
-def test_ingest_full_size_windows_against_oracle(dyn):
-    """First and last windows of the one-day trace through the oracle's own ingestion."""
-    w = make(SPECS[2])
-    tr = w["trace"]
-    ins, outs, off, ws = gpu_ingest(dyn, w)
-    off_h = off.cpu().numpy(); ins_h = ins.cpu().numpy(); outs_h = outs.cpu().numpy()
-    G, NW, Wlen = w["n_class"], w["n_window"], w["window_s"]
-    for w0, w1 in ((0, 3), (700, 702), (NW - 2, NW)):
-        lo, hi = np.searchsorted(tr["t_s"], [w0 * Wlen, w1 * Wlen])
-        sub = {k: v[lo:hi].copy() for k, v in tr.items()}
-        # absolute times and all windows up to w1: the cells before window w0 stay empty
-        st = oracle.ingest(sub, w["edges"], w1, Wlen)
-        a, b = off_h[w0 * G], off_h[w1 * G]
-        np.testing.assert_array_equal(off_h[w0 * G:w1 * G + 1] - a, st["cell_off"][w0 * G:w1 * G + 1])
-        np.testing.assert_array_equal(ins_h[a:b], st["in_tok"])
-        np.testing.assert_array_equal(outs_h[a:b], st["out_tok"])

@@ -342,6 +342,18 @@ def test_nth_element_and_full_sort_agree(small_hour):
         np.testing.assert_array_equal(r[k], r2[k])
 
 
+def test_windows_dealt_to_threads_give_the_single_call_result(small_hour):
+    """The window-parallel driver only splits the list of cells: every output equals the one-call result."""
+    w, st, r = small_hour
+    for threads, per in ((3, 1), (2, 2), (5, 0)):
+        rp = oracle.evaluate_parallel(w["profile"], st, w["n_window"], w["window_s"], w["configs"], w["slos"], w["pct"],
+                                      threads=threads, windows_per_task=per, want_space=True)
+        assert rp.pop("threads") == threads
+        assert set(rp) == set(r)
+        for k in r:
+            np.testing.assert_array_equal(rp[k], r[k])
+
+
 def test_cell_sums_add_up(small_hour):
     w, st, r = small_hour
     assert r["m"].sum() == 20000
