@@ -248,7 +248,7 @@ def main():
            "sel_cost": torch.empty(cells, dtype=torch.float64, device="cuda"),
            "window_energy_j": torch.empty(NW, dtype=torch.float64, device="cuda"),
            "window_infeasible": torch.empty(NW, dtype=torch.int32, device="cuda")}
-    ws = torch.empty(dyn.dyn_eval_ticks_workspace(NW, T, G, K) if args.ticks else dyn.dyn_eval_space_workspace(NW, G, K),
+    ws = torch.empty(dyn.dyn_eval_ticks_workspace(R, NW, T, G, K) if args.ticks else dyn.dyn_eval_space_workspace(NW, G, K),
                      dtype=torch.uint8, device="cuda")
 
     if args.hierarchy:

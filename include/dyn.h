@@ -256,13 +256,15 @@ int dyn_eval_select_static(dyn_profile* profile, const dyn_trace_view* trace, co
  * fine->window_s = tick_s; tick q of window w is fine window w * n_tick + q).
  * `space` and `sel` are indexed by the coarse cell w * G + g: [n_window*G][K], [n_window*G]
  * and [n_window].  1 <= n_tick <= DYN_TICK_LIMIT, else DYN_E_SHAPE.
- * The percentile of a cell with m requests is its j-th largest value, j = m - rank + 1;
- * cells with j > DYN_TICK_DEPTH (m >= 6400 at P99) are not evaluated: their percentiles
- * are +inf, their TTFT and TBT flags are set and DYN_WS_TICK_RANK is raised in the
- * workspace status.  Workspace: dyn_eval_ticks_workspace bytes, DEVICE, 256-byte aligned. */
-#define DYN_TICK_LIMIT 16
-#define DYN_TICK_DEPTH 64
-size_t dyn_eval_ticks_workspace(int32_t n_window, int32_t n_tick, int32_t n_class, int32_t n_config);
+ * The percentile of a cell with m requests is its j-th largest value, j = m - rank + 1; any
+ * j up to DYN_TICK_DEPTH is evaluated (m < 819200 at P99).  A cell beyond that is not: its
+ * percentiles are +inf, its TTFT and TBT flags are set, sel = -1, and DYN_WS_TICK_RANK is
+ * raised in the workspace status (its energies are still written).
+ * Workspace: dyn_eval_ticks_workspace bytes (it depends on the number of requests: the
+ * per-tick candidate lists take 4 bytes per request), DEVICE, 256-byte aligned.          */
+#define DYN_TICK_LIMIT 64
+#define DYN_TICK_DEPTH 8192
+size_t dyn_eval_ticks_workspace(int64_t n_req, int32_t n_window, int32_t n_tick, int32_t n_class, int32_t n_config);
 int dyn_eval_select_ticks(dyn_profile* profile, const dyn_trace_view* fine, int32_t n_tick,
                           const dyn_config* cfg, int32_t K, const dyn_objective* objective,
                           const dyn_space* space, const dyn_selection* sel, void* workspace,
@@ -450,9 +452,9 @@ int dyn_hierarchy(dyn_profile* profile, const dyn_trace_view* coarse, const dyn_
 #define DYN_K_SPACE 1   /* evaluation of the (cell, configuration) space                */
 #define DYN_K_SELECT 2  /* per-cell least-cost feasible configuration (or its fused finish) */
 #define DYN_K_TOTALS 3  /* per-window totals                                            */
-#define DYN_K_TICK_TOP 4   /* tick evaluation: per-tick loads and largest input lengths   */
-#define DYN_K_TICK_SPACE 5 /* tick evaluation of the (cell, configuration) space: cells whose percentile is at most 16 deep */
-#define DYN_K_TICK_MERGE 6 /* the same for the remaining cells                             */
+#define DYN_K_TICK_TOP 4   /* tick evaluation: per-tick loads and candidate lists (cell and deep-cell kernels) */
+#define DYN_K_TICK_SPACE 5 /* tick evaluation of the (cell, configuration) space: the walk over the ticks */
+#define DYN_K_TICK_MERGE 6 /* the same for the (cell, tile) items the walk cannot settle    */
 #define DYN_K_MIXED_TYPES 7   /* mixed pools: per-type least energies                      */
 #define DYN_K_MIXED_COMBINE 8 /* mixed pools: assignment of instances and shares          */
 #define DYN_K_PATH 9          /* selection with transition overheads                     */

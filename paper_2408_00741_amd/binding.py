@@ -27,7 +27,7 @@ __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_t
 
 DYN_F_FEASIBLE, DYN_F_OVERLOAD, DYN_F_TTFT, DYN_F_TBT, DYN_F_BUDGET, DYN_F_EMPTY = 1, 2, 4, 8, 16, 32
 DYN_WS_BAD_OFFSETS, DYN_WS_BAD_REQUEST, DYN_WS_TICK_RANK = 1, 2, 4
-DYN_TICK_LIMIT, DYN_TICK_DEPTH = 16, 64
+DYN_TICK_LIMIT, DYN_TICK_DEPTH = 64, 8192
 DYN_STATIC_WORKSPACE_BYTES = 16 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -145,7 +145,7 @@ _lib.dyn_eval_select_static.restype = C.c_int
 _lib.dyn_eval_select_static.argtypes = [_vp, C.POINTER(_TraceView), C.POINTER(_Config), _i32, C.POINTER(_Objective),
                                         C.POINTER(_Space), C.POINTER(_Selection), _vp, _vp]
 _lib.dyn_eval_ticks_workspace.restype = _sz
-_lib.dyn_eval_ticks_workspace.argtypes = [_i32, _i32, _i32, _i32]
+_lib.dyn_eval_ticks_workspace.argtypes = [_i64, _i32, _i32, _i32, _i32]
 _lib.dyn_eval_select_ticks.restype = C.c_int
 _lib.dyn_eval_select_ticks.argtypes = [_vp, C.POINTER(_TraceView), _i32, C.POINTER(_Config), _i32,
                                        C.POINTER(_Objective), C.POINTER(_Space), C.POINTER(_Selection), _vp, _sz, _vp]
@@ -420,8 +420,8 @@ def dyn_eval_select_static(profile: Profile, in_tok: torch.Tensor, out_tok: torc
     return out, sel
 
 
-def dyn_eval_ticks_workspace(n_window: int, n_tick: int, n_class: int, n_config: int) -> int:
-    return int(_lib.dyn_eval_ticks_workspace(n_window, n_tick, n_class, n_config))
+def dyn_eval_ticks_workspace(n_req: int, n_window: int, n_tick: int, n_class: int, n_config: int) -> int:
+    return int(_lib.dyn_eval_ticks_workspace(n_req, n_window, n_tick, n_class, n_config))
 
 
 def dyn_eval_select_ticks(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tensor, cell_off: torch.Tensor,
@@ -442,7 +442,7 @@ def dyn_eval_select_ticks(profile: Profile, in_tok: torch.Tensor, out_tok: torch
     if sel is None:
         sel = _selection_tensors(cells, n_window, dev)
     if workspace is None:
-        nbytes = dyn_eval_ticks_workspace(n_window, n_tick, G, K)
+        nbytes = dyn_eval_ticks_workspace(in_tok.numel(), n_window, n_tick, G, K)
         if nbytes == 0:
             raise DynError(-2, "dyn_eval_ticks_workspace")
         workspace = _workspace(nbytes, dev)

@@ -314,16 +314,19 @@ EvalWs dyn_eval_ws_layout(int64_t cells, int32_t K) {
   return w;
 }
 
-TickWs dyn_tick_ws_layout(int64_t coarse_cells, int32_t n_tick, int32_t K) {
+TickWs dyn_tick_ws_layout(int64_t n_req, int64_t coarse_cells, int32_t n_tick, int32_t K) {
   TickWs w;
   w.fine = dyn_eval_ws_layout(coarse_cells * n_tick, 1);
   const size_t c = (size_t)std::max<int64_t>(coarse_cells, 1);
   w.n_wslot = std::max(K, 1) / DYN_WAVE + 4;
   size_t off = w.fine.part;
-  w.top = off; off += align256(c * (size_t)n_tick * DYN_TICK_TOP * sizeof(int32_t));
+  w.plan = off; off += align256(c * sizeof(TickPlan));
+  w.top = off; off += align256((size_t)std::max<int64_t>(n_req, 1) * sizeof(int32_t));
   w.part = off; off += align256(c * (size_t)w.n_wslot * sizeof(SelPart));
-  w.merge_count = off; off += 256;
-  w.merge_list = off; off += align256(c * sizeof(uint32_t));
+  w.counters = off; off += 256;
+  w.deep_list = off; off += align256(c * sizeof(uint32_t));
+  // one item per (cell, tile); a tile is at least 64 configurations wide
+  w.slow_list = off; off += align256(c * (size_t)((std::max(K, 1) + DYN_WAVE - 1) / DYN_WAVE) * sizeof(uint64_t));
   w.total = off;
   return w;
 }
@@ -649,9 +652,9 @@ int dyn_eval_select_static(dyn_profile* p, const dyn_trace_view* t, const dyn_co
   return DYN_OK;
 }
 
-size_t dyn_eval_ticks_workspace(int32_t n_window, int32_t n_tick, int32_t n_class, int32_t n_config) {
-  if (n_window < 1 || n_tick < 1 || n_tick > DYN_TICK_LIMIT || n_class < 1 || n_config < 1) return 0;
-  return dyn_tick_ws_layout((int64_t)n_window * n_class, n_tick, n_config).total;
+size_t dyn_eval_ticks_workspace(int64_t n_req, int32_t n_window, int32_t n_tick, int32_t n_class, int32_t n_config) {
+  if (n_req < 0 || n_window < 1 || n_tick < 1 || n_tick > DYN_TICK_LIMIT || n_class < 1 || n_config < 1) return 0;
+  return dyn_tick_ws_layout(n_req, (int64_t)n_window * n_class, n_tick, n_config).total;
 }
 
 int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tick, const dyn_config* cfg, int32_t K,
@@ -671,7 +674,7 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   if (fine_cells >= ((int64_t)1 << 30)) { dyn_set_error("n_window * n_tick * classes must stay below 2^30"); return DYN_E_SHAPE; }
   if ((rc = check_device(p)) != DYN_OK) return rc;
   if (K < 1 || K > DYN_MAX_CONFIGS) { dyn_set_error("K=%d outside [1, %d]", K, DYN_MAX_CONFIGS); return DYN_E_SHAPE; }
-  const TickWs w = dyn_tick_ws_layout(cells, n_tick, K);
+  const TickWs w = dyn_tick_ws_layout(t->n_req, cells, n_tick, K);
   if (((uintptr_t)workspace & 255) || workspace_bytes < w.total) {
     dyn_set_error("workspace misaligned or too small (%zu < %zu)", workspace_bytes, w.total);
     return DYN_E_WORKSPACE;
@@ -686,9 +689,9 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   ca.n_window = n_window; ca.n_tick = n_tick; ca.G = p->G;
   ca.tick_s = t->window_s; ca.r_tick = 1.0 / t->window_s;
   ca.pct_num = o->pct_num; ca.pct_den = o->pct_den;
-  ca.rec = (TickRec*)(base + w.fine.rec); ca.top = (int32_t*)(base + w.top);
+  ca.rec = (TickRec*)(base + w.fine.rec); ca.plan = (TickPlan*)(base + w.plan); ca.top = (int32_t*)(base + w.top);
   ca.cstat = (uint8_t*)(base + w.fine.cstat); ca.header = (WsHeader*)(base + w.fine.header);
-  ca.merge_count = (uint32_t*)(base + w.merge_count);
+  ca.counters = (uint32_t*)(base + w.counters); ca.deep_list = (uint32_t*)(base + w.deep_list);
   if (!hip_ok(dyn_launch_tick_cell(ca, s), "tick cell launch")) return DYN_E_DEVICE;
 
   TickArgs ta;
@@ -706,8 +709,8 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   a.pw0 = p->d_pw0; a.idle_w = o->idle_cost_weight;
   a.part = (SelPart*)(base + w.part); a.n_wslot = w.n_wslot;
   ta.n_tick = n_tick; ta.tick_s = t->window_s; ta.window_s = (double)n_tick * t->window_s;
-  ta.rec = (const TickRec*)(base + w.fine.rec); ta.top = (const int32_t*)(base + w.top);
-  ta.merge_count = (uint32_t*)(base + w.merge_count); ta.merge_list = (uint32_t*)(base + w.merge_list);
+  ta.rec = (const TickRec*)(base + w.fine.rec); ta.plan = (const TickPlan*)(base + w.plan); ta.top = (const int32_t*)(base + w.top);
+  ta.counters = (uint32_t*)(base + w.counters); ta.slow_list = (uint64_t*)(base + w.slow_list);
   ta.tstart = p->d_tstart; ta.thr = p->d_thr; ta.single_point = p->single_point; ta.any_two_rows = p->any_two_rows;
   if (!hip_ok(dyn_launch_tick_space(ta, s), "tick space launch")) return DYN_E_DEVICE;
 

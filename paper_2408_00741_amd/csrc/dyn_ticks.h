@@ -4,17 +4,30 @@
 
 #include "dyn_internal.h"
 
-#define DYN_TICK_MAX 16   // ticks per window the kernels are unrolled for
-#define DYN_TICK_TOP 64   // largest input lengths kept per fine cell (one wavefront's worth)
-static_assert(DYN_TICK_MAX == DYN_TICK_LIMIT && DYN_TICK_TOP == DYN_TICK_DEPTH && DYN_TICK_TOP == DYN_WAVE,
+#define DYN_TICK_MAX 64     // ticks per window: a wave's lane holds a tick in the cell kernel
+#define DYN_TICK_FAST 16    // percentile depth j up to which the evaluation kernel keeps a sorted list in registers
+#define DYN_TICK_WAVE 64    // depth up to which one wave of the cell kernel extracts the per-tick lists
+static_assert(DYN_TICK_MAX == DYN_TICK_LIMIT && DYN_TICK_MAX == DYN_WAVE && DYN_TICK_WAVE == DYN_WAVE,
               "the ABI's limits are the kernels' limits");
 
-struct TickRec {   // what the evaluation kernel needs from one tick of a cell (16 bytes)
+struct TickRec {   // one tick of a (window, class) cell (16 bytes)
   double load;     // (input + output tokens of the tick) / tick_s
+  uint32_t off;    // first request of the tick in the sorted trace = start of the tick's list in `top`
   int32_t cnt;     // requests in the tick
-  int32_t plan;    // of the whole cell: j in the low byte (0 = empty, DYN_TICK_TOP + 1 = not evaluated), DYN_PLAN_MERGE
 };
-#define DYN_PLAN_MERGE 0x100
+
+// What the cell kernel decides about a (window, class) cell.  The cell's percentile is its j-th largest
+// per-request value, j = m - rank + 1.
+struct TickPlan {
+  int32_t j;       // 0 = empty cell
+  int32_t xj;      // j-th largest input length of the whole cell
+  uint32_t flags;  // DYN_TP_*
+  uint32_t pad;
+};
+#define DYN_TP_DENSE 1u   // every non-empty tick holds at least j requests: the TBT percentile is the largest tick TBT
+#define DYN_TP_SMALL 2u   // the four non-empty ticks of largest TBT hold at least j requests, whichever they are
+#define DYN_TP_DEEP 4u    // j > DYN_TICK_WAVE: lists and xj come from the deep-cell kernel
+#define DYN_TP_SKIP 8u    // j > DYN_TICK_DEPTH: not evaluated
 
 struct TickCellArgs {
   const int32_t* in; const int32_t* out;
@@ -24,10 +37,12 @@ struct TickCellArgs {
   double tick_s, r_tick;     // r_tick = RN(1 / tick_s)
   int64_t pct_num, pct_den;
   TickRec* rec;              // [cells][n_tick]
-  int32_t* top;              // [cells][DYN_TICK_TOP][n_tick]; positions below min(j, cnt) are written
+  TickPlan* plan;            // [cells]
+  int32_t* top;              // [n_req]: per tick its min(j, cnt) largest input lengths, descending, at rec.off
   uint8_t* cstat;            // [fine cells] status bytes
   WsHeader* header;
-  uint32_t* merge_count;     // zeroed here
+  uint32_t* counters;        // [0] cells on deep_list, [1] items on slow_list; zeroed before the cell kernel
+  uint32_t* deep_list;       // [cells]
 };
 
 struct TickArgs {
@@ -36,21 +51,22 @@ struct TickArgs {
   double tick_s;
   double window_s;         // (double) n_tick * tick_s
   const TickRec* rec;      // [cells][n_tick]
-  const int32_t* top;      // [cells][DYN_TICK_TOP][n_tick]
+  const TickPlan* plan;    // [cells]
+  const int32_t* top;      // [n_req]
   const int32_t* tstart; const double* thr; bool single_point;   // threshold form of the bucket index
   bool any_two_rows;
-  uint32_t* merge_count;   // number of cells on merge_list
-  uint32_t* merge_list;    // [cells] cells left to tick_merge_kernel
+  uint32_t* counters;      // [1]: number of (cell, tile) items on slow_list
+  uint64_t* slow_list;     // [cells * n_tile] items cell * n_tile + tile left to the general kernel
 };
 
-// Workspace: the per-cell part of the evaluation workspace for the fine cells, then the
-// candidate lists, then the partial selection records of the coarse cells.
+// Workspace: the per-cell part of the evaluation workspace for the fine cells, then the plans, the
+// per-tick lists, the partial selection records of the coarse cells and the two work lists.
 struct TickWs {
-  EvalWs fine;      // header, rec (as TickRec) and cstat are used; fine.part is where `top` starts
-  size_t top, part, merge_count, merge_list, total;
+  EvalWs fine;      // header, rec (as TickRec) and cstat are used; fine.part is where `plan` starts
+  size_t plan, top, part, counters, deep_list, slow_list, total;
   int32_t n_wslot;
 };
-TickWs dyn_tick_ws_layout(int64_t coarse_cells, int32_t n_tick, int32_t K);
+TickWs dyn_tick_ws_layout(int64_t n_req, int64_t coarse_cells, int32_t n_tick, int32_t K);
 
 hipError_t dyn_launch_tick_cell(const TickCellArgs& a, hipStream_t s);
 hipError_t dyn_launch_tick_space(const TickArgs& a, hipStream_t s);

@@ -7,30 +7,57 @@
 // The per-request percentile still collapses, tick by tick: inside one tick TTFT is
 // input length x a non-negative constant, so the cell's j-th largest TTFT (j = m - rank + 1)
 // is among the j largest input lengths of each tick scaled by that tick's prefill time.
-// `tick_cell_kernel` produces, once per cell and independent of the configuration, every
-// tick's load and its j largest input lengths in descending order; `tick_space_kernel`
-// then finds, per (cell, configuration), the j-th largest of the scaled lists.  The TBT
-// percentile is the j-th largest of the ticks' TBT values weighted by their request counts.
+// The request stream is read once, independent of the configurations:
+//   tick_cell_kernel   per cell every tick's load, its min(j, count) largest input lengths in
+//                      descending order (j <= 64: kept sorted in a wave's lanes) and the cell's
+//                      j-th largest input length x_j; what the later kernels do with the cell;
+//   tick_deep_kernel   the same lists and x_j for the cells with j > 64 (a block per cell:
+//                      bitonic sort of a tick in LDS);
+//   tick_space_kernel  per (cell, configuration) a walk over the ticks: energy in time order,
+//                      the TBT percentile (largest tick TBT when every non-empty tick holds j
+//                      requests, else from the four largest tick TBTs), and the TTFT percentile:
+//                      j <= 16 through a sorted register list of the scaled candidates; j > 16
+//                      from the bracket [x_j * least, x_j * largest prefill time of the ticks],
+//                      which holds the percentile and is a single value whenever the prefill
+//                      time does not depend on the load;
+//   tick_general_kernel everything the walk cannot settle, (cell, tile) by (cell, tile): the
+//                      ticks' TBTs and prefill times kept in LDS, the TBT percentile by taking
+//                      ticks in descending TBT order, the TTFT percentile by bisecting the
+//                      bracket on the ticks' sorted lists.
+#include <type_traits>
+
 #include "dyn_ticks.h"
 #include "dyn_device.h"
 
 namespace {
 
 constexpr int kWavesPerBlock = 4;
-constexpr int kFastDepth = 16;      // j up to here: sorted-list path of the evaluation kernel
+constexpr int kFastDepth = DYN_TICK_FAST;
+constexpr int kDeepCap = DYN_TICK_DEPTH;     // largest j, and the largest tick the deep-cell kernel sorts in one go
+constexpr int kDeepBlocks = 512;
+constexpr int kGeneralBlocks = 1024;
+constexpr int kListCap = 4096;               // list entries of one cell the general kernel stages in LDS
+constexpr int kStripBytes = 32 * 1024;       // per-tick values of a block's configurations in the general kernel
+static_assert(kDeepCap == 8192, "the deep-cell kernel's LDS buffer");
 // LDS stride of a staged table row in doubles: odd, so that lanes reading the same load bracket of
 // different rows do not all fall into one bank
 #define DYN_SLOT_STRIDE(n_rho) ((3 * (n_rho)) | 1)
 
+__global__ void tick_init_kernel(uint32_t* counters) {
+  counters[0] = 0u;
+  counters[1] = 0u;
+}
+
 // ---- per-tick loads and candidate lists ------------------------------------------------------
 // One wave per (window, class) cell walks the cell's ticks.  Lane q holds tick q's offsets;
 // the cell's request count gives j.  Per tick the wave streams the tick's requests once:
-// token sum (the tick's load) and, unless the cell is empty or j exceeds DYN_TICK_TOP, the
-// j largest input lengths, kept sorted (descending) in the wave's lanes.  A row of 64 new
-// values is merged either by j rounds of "take the maximum of kept and new values" or, when
-// few new values can still enter the first j positions, by ranking: a value's position is the
-// number of values that beat it (kept values win ties against new ones, lower lanes against
-// higher ones), and the merged order is written through a 64-word LDS buffer.
+// token sum (the tick's load) and, for 0 < j <= 64, the j largest input lengths, kept sorted
+// (descending) in the wave's lanes.  A row of 64 new values is merged either by j rounds of
+// "take the maximum of kept and new values" or, when few new values can still enter the
+// first j positions, by ranking: a value's position is the number of values that beat it
+// (kept values win ties against new ones, lower lanes against higher ones), and the merged
+// order is written through a 64-word LDS buffer.  A second list, merged with every finished
+// tick's list, holds the j largest lengths of the whole cell: its last entry is x_j.
 __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(TickCellArgs a) {
   __shared__ int32_t s_buf[kWavesPerBlock][DYN_WAVE];
   const int lane = threadIdx.x & (DYN_WAVE - 1);
@@ -54,20 +81,79 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
   }
   const int64_t m_cell = (int64_t)wave_sum_u64((uint64_t)(uint32_t)cnt_l);
   const int64_t rank = (a.pct_num * m_cell + a.pct_den - 1) / a.pct_den;
-  const int64_t j64 = m_cell - rank + 1;
-  const bool deep = m_cell > 0 && j64 > DYN_TICK_TOP;
-  const int keep = (m_cell == 0 || deep) ? 0 : (int)j64;        // wave-uniform, 0 .. 64
+  const int64_t j64 = m_cell > 0 ? m_cell - rank + 1 : 0;
+  const bool skip = j64 > DYN_TICK_DEPTH;
+  const bool deep = !skip && j64 > DYN_TICK_WAVE;
+  const int keep = (skip || deep) ? 0 : (int)j64;               // wave-uniform, 0 .. 64
 
-  // what the evaluation kernel needs to know about the cell: j (0 = empty, DYN_TICK_TOP + 1 = not
-  // evaluated) and whether some non-empty tick holds fewer than j requests or j is beyond the
-  // short-list path (then the merge path takes the cell)
-  const uint32_t cmin = wave_min_u32(cnt_l > 0 ? (uint32_t)cnt_l : 0xFFFFFFFFu);
-  const int jc = m_cell == 0 ? 0 : (deep ? DYN_TICK_TOP + 1 : (int)j64);
-  const int32_t plan = jc | ((keep > 0 && (keep > kFastDepth || cmin < (uint32_t)keep)) ? DYN_PLAN_MERGE : 0);
+  // How the TBT percentile can be found: from the largest tick TBT when every non-empty tick holds
+  // j requests; from the four largest tick TBTs when any four non-empty ticks hold j between them
+  // (the four smallest counts do, or there are no more than four).
+  uint32_t flags = skip ? DYN_TP_SKIP : (deep ? DYN_TP_DEEP : 0u);
+  if (m_cell > 0) {
+    uint32_t cpos = cnt_l > 0 ? (uint32_t)cnt_l : 0xFFFFFFFFu;
+    if ((int64_t)wave_min_u32(cpos) >= j64) flags |= DYN_TP_DENSE;
+    int64_t s4 = 0;
+    bool all_in = false;
+    for (int r = 0; r < 4; ++r) {
+      const uint32_t mn = wave_min_u32(cpos);
+      if (mn == 0xFFFFFFFFu) { all_in = true; break; }
+      s4 += mn;
+      const uint64_t who = __ballot(cpos == mn);
+      if (lane == (int)__builtin_ctzll(who)) cpos = 0xFFFFFFFFu;
+    }
+    if (all_in || s4 >= j64) flags |= DYN_TP_SMALL;
+  }
+
+  int32_t* buf = s_buf[wave];
+  // Merges the values `cx` of the lanes with `mine` set into the descending list `best` (one entry per lane,
+  // -1 = none); the first `keep` positions of the result are exact.
+  auto merge = [&](int32_t best, int32_t cx, bool mine) -> int32_t {
+    uint64_t mask = __ballot(mine);
+    if (mask == 0) return best;
+    if (__popcll(mask) * 10 > keep * 16) {
+      // rounds of maximum extraction over kept and new values; a taken value leaves its lane
+      int32_t bv = best, cv = mine ? cx : -1, nb = -1;
+      for (int i = 0; i < keep; ++i) {
+        const int32_t mx = wave_max_i32(max(bv, cv));
+        if (mx < 0) break;
+        const uint64_t ub = __ballot(bv == mx);
+        if (ub) {
+          if (lane == (int)__builtin_ctzll(ub)) bv = -1;
+        } else {
+          const uint64_t uc = __ballot(cv == mx);
+          if (lane == (int)__builtin_ctzll(uc)) cv = -1;
+        }
+        if (lane == i) nb = mx;
+      }
+      return nb;
+    }
+    int rb = lane;      // position of my kept value: the kept values before it + new values above it
+    int rc = 0;         // position of my new value: kept values >= it + new values that beat it
+    while (mask) {
+      const int u = __builtin_ctzll(mask);
+      mask &= mask - 1;
+      const int32_t v = __builtin_amdgcn_readlane(cx, u);
+      const int n_ge = __popcll(__ballot(best >= v));
+      rb += (v > best) ? 1 : 0;
+      rc += (v > cx || (v == cx && u < lane)) ? 1 : 0;
+      if (lane == u) rc += n_ge;
+    }
+    // the positions are a permutation of 0 .. 63 + (new values): every slot below 64 is written once
+    if (rb < DYN_WAVE) buf[rb] = best;
+    if (mine && rc < DYN_WAVE) buf[rc] = cx;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int32_t merged = buf[lane];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    return merged;
+  };
 
   double load_l = 0.0;
-  uint32_t neg_mask = 0;                        // ticks holding a negative token count
-  int32_t* buf = s_buf[wave];
+  uint32_t neg_mask_lo = 0, neg_mask_hi = 0;    // ticks holding a negative token count
+  int32_t gbest = -1;                           // the j largest input lengths of the cell so far
+  bool g_empty = true;
   // (x, y) always hold the row after the one being processed: the next row of the same tick,
   // else the first row of the next tick
   int32_t x, y;
@@ -99,72 +185,158 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
       orv |= have ? (uint32_t)(cx | cy) : 0u;
       if (keep == 0) continue;
       const int32_t thr = __builtin_amdgcn_readlane(best, keep - 1);
-      const bool mine = have && cx > thr;          // a value <= thr has `keep` kept values ahead of it
-      uint64_t mask = __ballot(mine);
-      if (mask == 0) continue;
-      if (__popcll(mask) * 10 > keep * 16) {
-        // rounds of maximum extraction over kept and new values; a taken value leaves its lane
-        int32_t bv = best, cv = mine ? cx : -1, nb = -1;
-        for (int i = 0; i < keep; ++i) {
-          const int32_t mx = wave_max_i32(max(bv, cv));
-          if (mx < 0) break;
-          const uint64_t ub = __ballot(bv == mx);
-          if (ub) {
-            if (lane == (int)__builtin_ctzll(ub)) bv = -1;
-          } else {
-            const uint64_t uc = __ballot(cv == mx);
-            if (lane == (int)__builtin_ctzll(uc)) cv = -1;
-          }
-          if (lane == i) nb = mx;
-        }
-        best = nb;
-      } else {
-        int rb = lane;      // position of my kept value: the kept values before it + new values above it
-        int rc = 0;         // position of my new value: kept values >= it + new values that beat it
-        while (mask) {
-          const int u = __builtin_ctzll(mask);
-          mask &= mask - 1;
-          const int32_t v = __builtin_amdgcn_readlane(cx, u);
-          const int n_ge = __popcll(__ballot(best >= v));
-          rb += (v > best) ? 1 : 0;
-          rc += (v > cx || (v == cx && u < lane)) ? 1 : 0;
-          if (lane == u) rc += n_ge;
-        }
-        // the positions are a permutation of 0 .. 63 + (new values): every slot below 64 is written once
-        if (rb < DYN_WAVE) buf[rb] = best;
-        if (mine && rc < DYN_WAVE) buf[rc] = cx;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        best = buf[lane];
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-      }
+      best = merge(best, cx, have && cx > thr);    // a value <= thr has `keep` kept values ahead of it
     }
     // the tick's token sum: 32-bit lanes when every lane's sum is small enough for it
     uint64_t tok;
     if (__ballot((acc >> 25) != 0) == 0) tok = wave_sum_u32((uint32_t)acc);
     else tok = wave_sum_u64(acc);
-    if (__ballot((int32_t)orv < 0)) neg_mask |= 1u << q;
+    if (__ballot((int32_t)orv < 0)) {
+      if (q < 32) neg_mask_lo |= 1u << q; else neg_mask_hi |= 1u << (q - 32);
+    }
     if (lane == q) load_l = div_by((double)tok, a.tick_s, a.r_tick);
     const int n_top = keep < n_q ? keep : n_q;
-    if (lane < n_top) a.top[(c * DYN_TICK_TOP + lane) * T + q] = best;   // [cell][position][tick]
+    if (lane < n_top) a.top[beg_q + lane] = best;           // the tick's list sits where its requests start
+    if (n_top > 0) {
+      const int32_t mine_v = lane < n_top ? best : -1;
+      if (g_empty) {
+        gbest = mine_v;
+        g_empty = false;
+      } else {
+        const int32_t thr = __builtin_amdgcn_readlane(gbest, keep - 1);
+        gbest = merge(gbest, mine_v, mine_v > thr);
+      }
+    }
   }
   if (lane < T) {
     const int64_t f = f0 + (int64_t)lane * G;
     TickRec r;
     r.load = load_l;
+    r.off = (uint32_t)beg_l;                     // n_req < 2^31
     r.cnt = cnt_l;
-    r.plan = plan;
     a.rec[c * T + lane] = r;
+    const uint32_t neg = lane < 32 ? (neg_mask_lo >> lane) & 1u : (neg_mask_hi >> (lane - 32)) & 1u;
     // every fine cell writes its own status byte: nothing to clear beforehand
-    a.cstat[f] = (uint8_t)(bad_l | (((neg_mask >> lane) & 1u) ? DYN_WS_BAD_REQUEST : 0u) |
-                           ((deep && lane == 0) ? DYN_WS_TICK_RANK : 0u));
+    a.cstat[f] = (uint8_t)(bad_l | (neg ? DYN_WS_BAD_REQUEST : 0u) | ((skip && lane == 0) ? DYN_WS_TICK_RANK : 0u));
+  }
+  const int32_t xj = keep > 0 ? __builtin_amdgcn_readlane(gbest, keep - 1) : 0;
+  if (lane == 0) {
+    TickPlan p;
+    p.j = skip ? 0x7FFFFFFF : (int32_t)j64;
+    p.xj = xj < 0 ? 0 : xj;
+    p.flags = flags;
+    p.pad = 0;
+    a.plan[c] = p;
+    if (deep) a.deep_list[atomicAdd(&a.counters[0], 1u)] = (uint32_t)c;
   }
   if (c == 0 && lane == 0) {                     // single writer of the header
     a.header->status = 0u;
     a.header->kind = DYN_WS_KIND_CELLS;
     a.header->cells = cells * T;
-    *a.merge_count = 0u;                       // filled by the evaluation kernel that runs next
+  }
+}
+
+// ---- cells whose percentile lies more than 64 deep ------------------------------------------------
+// A block per listed cell.  x_j by a most-significant-bit-first search on the value, every step a
+// count over the cell's requests; then every tick's min(j, count) largest input lengths in descending
+// order: a tick of up to 8192 requests is sorted whole in LDS (bitonic), a larger one is first cut
+// down to its j largest (threshold by the same bit search, the values above it gathered, the rest of
+// the j places filled with the threshold itself).
+__global__ __launch_bounds__(256) void tick_deep_kernel(TickCellArgs a) {
+  __shared__ int32_t s_val[kDeepCap];
+  __shared__ uint32_t s_part[4];
+  __shared__ uint32_t s_fill;
+  const int tid = threadIdx.x, lane = tid & (DYN_WAVE - 1), wave = tid / DYN_WAVE;
+  const int T = a.n_tick;
+  const uint32_t n_deep = a.counters[0];         // complete: written by the kernel before this one
+  auto block_sum = [&](uint32_t v) -> uint32_t {
+    const uint32_t ws = wave_sum_u32(v);
+    __syncthreads();
+    if (lane == 0) s_part[wave] = ws;
+    __syncthreads();
+    return s_part[0] + s_part[1] + s_part[2] + s_part[3];
+  };
+  auto block_max = [&](int32_t v) -> int32_t {
+    const int32_t wm = wave_max_i32(v);
+    __syncthreads();
+    if (lane == 0) s_part[wave] = (uint32_t)wm;
+    __syncthreads();
+    return max(max((int32_t)s_part[0], (int32_t)s_part[1]), max((int32_t)s_part[2], (int32_t)s_part[3]));
+  };
+  // j-th largest value of the ticks q0 .. q1-1 of the cell (at least j values, all bits above `bits` clear)
+  auto jth_largest = [&](const TickRec* rec, int q0, int q1, int bits, int32_t j) -> int32_t {
+    int32_t v = 0;
+    for (int b = bits - 1; b >= 0; --b) {
+      const int32_t cand = v | (int32_t)(1u << b);
+      uint32_t n = 0;
+      for (int q = q0; q < q1; ++q) {
+        const TickRec r = rec[q];
+        const int32_t* src = a.in + r.off;
+        for (int i = tid; i < r.cnt; i += 256) n += src[i] >= cand ? 1u : 0u;
+      }
+      if (block_sum(n) >= (uint32_t)j) v = cand;
+    }
+    return v;
+  };
+  for (uint32_t it = blockIdx.x; it < n_deep; it += gridDim.x) {
+    const int64_t c = a.deep_list[it];
+    const int32_t j = a.plan[c].j;               // 64 < j <= 8192
+    const TickRec* rec = a.rec + c * T;
+    int32_t mx = 0;
+    for (int q = 0; q < T; ++q) {
+      const TickRec r = rec[q];
+      const int32_t* src = a.in + r.off;
+      for (int i = tid; i < r.cnt; i += 256) mx = max(mx, src[i]);
+    }
+    mx = block_max(mx);
+    const int bits = 32 - __builtin_clz((uint32_t)mx | 1u);   // mx >= 0: at most 31
+    const int32_t xj = jth_largest(rec, 0, T, bits, j);
+    if (tid == 0) a.plan[c].xj = xj;
+    for (int q = 0; q < T; ++q) {
+      const TickRec r = rec[q];
+      if (r.cnt == 0) continue;                  // block-uniform
+      const int32_t* src = a.in + r.off;
+      int n_sort, n_out;
+      if (r.cnt <= kDeepCap) {
+        n_sort = r.cnt;
+        n_out = r.cnt < j ? r.cnt : j;
+        for (int i = tid; i < r.cnt; i += 256) s_val[i] = src[i];
+      } else {                                   // more than 8192 requests, of which the j <= 8192 largest are wanted
+        const int32_t thr = jth_largest(rec, q, q + 1, bits, j);
+        if (tid == 0) s_fill = 0u;
+        __syncthreads();
+        for (int i = tid; i < r.cnt; i += 256) {
+          const int32_t v = src[i];
+          if (v > thr) {                         // fewer than j of them
+            const uint32_t at = atomicAdd(&s_fill, 1u);
+            if (at < (uint32_t)kDeepCap) s_val[at] = v;
+          }
+        }
+        __syncthreads();
+        const int got = (int)min(s_fill, (uint32_t)j);
+        for (int i = got + tid; i < j; i += 256) s_val[i] = thr;
+        n_sort = n_out = j;
+      }
+      int n2 = 2;
+      while (n2 < n_sort) n2 <<= 1;              // at most 8192
+      for (int i = n_sort + tid; i < n2; i += 256) s_val[i] = (int32_t)0x80000000;
+      __syncthreads();
+      for (int k = 2; k <= n2; k <<= 1)
+        for (int d = k >> 1; d > 0; d >>= 1) {
+          for (int i = tid; i < n2; i += 256) {
+            const int o = i ^ d;
+            if (o > i) {
+              const int32_t u = s_val[i], v = s_val[o];
+              const bool down = (i & k) == 0;    // descending runs first: the whole array ends descending
+              if (down ? u < v : u > v) { s_val[i] = v; s_val[o] = u; }
+            }
+          }
+          __syncthreads();
+        }
+      int32_t* dst = a.top + r.off;
+      for (int i = tid; i < n_out; i += 256) dst[i] = s_val[i];
+      __syncthreads();                           // s_val is reused by the next tick
+    }
   }
 }
 
@@ -186,18 +358,69 @@ __device__ __forceinline__ void offer_tick(double (&s)[JF], const int32_t* s_top
   }
 }
 
-// Cells whose j fits a short sorted list: the ticks are walked once, in time order, two at a
-// time so that the two look-ups overlap.  The list starts with JF - j copies of +inf, so its
-// last entry is the j-th largest of what was inserted.
-template <int JF, bool SINGLE, bool TWO>
-__device__ __forceinline__ void walk_ticks_short(const Lookup& L, int T, int j, const double* s_load, const int32_t* s_cnt,
-                                                 const int32_t* s_top, double nd, double tick_s, double* e_out,
-                                                 double* ttft_out, double* tbt_out, bool* ov_out) {
-  double s[JF];
+// The four largest tick TBTs with their request counts (descending; ties keep the earlier tick first).
+struct TbtTop {
+  double tb[4];
+  int32_t cnt[4];
+  __device__ __forceinline__ void clear() {
 #pragma unroll
-  for (int i = 0; i < JF; ++i) s[i] = i < JF - j ? __builtin_inf() : -__builtin_inf();
-  double e = 0.0, tbmax = -__builtin_inf();
+    for (int i = 0; i < 4; ++i) { tb[i] = -__builtin_inf(); cnt[i] = 0; }
+  }
+  __device__ __forceinline__ void offer(double v, int32_t c) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bool gt = v > tb[i];
+      const double tv = tb[i];
+      const int32_t tc = cnt[i];
+      tb[i] = gt ? v : tv;
+      cnt[i] = gt ? c : tc;
+      v = gt ? tv : v;
+      c = gt ? tc : c;
+    }
+  }
+  __device__ __forceinline__ double jth(int32_t j) const {    // the kept ticks hold at least j requests
+    double r = tb[3];
+    int32_t cum = 0;
+    bool found = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      cum += cnt[i];
+      const bool hit = !found && cum >= j;
+      r = hit ? tb[i] : r;
+      found = found || hit;
+    }
+    return r;
+  }
+};
+
+struct WalkOut {
+  double e, ttft, tbt, pf_min, pf_max;
+  bool ov;
+};
+
+// One walk over the ticks of a cell, in time order, two look-ups in flight.  JF > 0: the cell's j <= JF
+// largest scaled candidates through a sorted list that starts with JF - j copies of +inf, so that its last
+// entry is the j-th largest of what was inserted.  JF == 0: no candidates are read; the least and the
+// largest prefill time over the non-empty ticks are returned instead.  SPARSE: the TBT percentile from the
+// four largest tick TBTs, else the largest tick TBT.
+template <int JF, bool SPARSE, bool SINGLE, bool TWO>
+__device__ __forceinline__ WalkOut walk_ticks(const Lookup& L, int T, int j, const double* s_load, const int32_t* s_cnt,
+                                              const int32_t* s_top, double nd, double tick_s) {
+  constexpr int JL = JF > 0 ? JF : 1;
+  double s[JL];
+#pragma unroll
+  for (int i = 0; i < JL; ++i) s[i] = i < JL - j ? __builtin_inf() : -__builtin_inf();
+  double e = 0.0, tbmax = -__builtin_inf(), pf_min = __builtin_inf(), pf_max = -__builtin_inf();
+  TbtTop tt;
+  if (SPARSE) tt.clear();
   bool ov = false;
+  auto one = [&](int q, int c0, double pf0, double tb0) {
+    if (c0 > 0) {                                // block-uniform
+      if (SPARSE) tt.offer(tb0, c0); else tbmax = max_num(tbmax, tb0);
+      if (JF > 0) offer_tick<JL>(s, s_top, T, q, c0 < j ? c0 : j, pf0);
+      else { pf_min = min_num(pf_min, pf0); pf_max = max_num(pf_max, pf0); }
+    }
+  };
   int q = 0;
   for (; q + 2 <= T; q += 2) {
     double pf0, tb0, pw0, pf1, tb1, pw1;
@@ -206,118 +429,19 @@ __device__ __forceinline__ void walk_ticks_short(const Lookup& L, int T, int j, 
     ov = ov | o0 | o1;
     e += (nd * pw0) * tick_s;                    // ticks in time order
     e += (nd * pw1) * tick_s;
-    const int c0 = s_cnt[q], c1 = s_cnt[q + 1];
-    if (c0 > 0) {                                // block-uniform
-      tbmax = max_num(tbmax, tb0);
-      offer_tick<JF>(s, s_top, T, q, c0 < j ? c0 : j, pf0);
-    }
-    if (c1 > 0) {
-      tbmax = max_num(tbmax, tb1);
-      offer_tick<JF>(s, s_top, T, q + 1, c1 < j ? c1 : j, pf1);
-    }
+    one(q, s_cnt[q], pf0, tb0);
+    one(q + 1, s_cnt[q + 1], pf1, tb1);
   }
   if (q < T) {
     double pf0, tb0, pw0;
     ov = ov | table_lookup<SINGLE, TWO>(L, s_load[q], &pf0, &tb0, &pw0);
     e += (nd * pw0) * tick_s;
-    const int c0 = s_cnt[q];
-    if (c0 > 0) {
-      tbmax = max_num(tbmax, tb0);
-      offer_tick<JF>(s, s_top, T, q, c0 < j ? c0 : j, pf0);
-    }
+    one(q, s_cnt[q], pf0, tb0);
   }
-  *e_out = e; *ttft_out = s[JF - 1]; *tbt_out = tbmax; *ov_out = ov;
-}
-
-// All other cells: every tick's tables are kept (the ticks are unrolled), then the TBT
-// percentile takes ticks in descending TBT order until j requests are covered, and the TTFT
-// percentile is j steps of a merge of the ticks' scaled candidate lists.
-template <int TMAX, bool SINGLE, bool TWO>
-__device__ __forceinline__ void walk_ticks_merge(const Lookup& L, int T, int j, const double* s_load, const int32_t* s_cnt,
-                                                 const int32_t* s_top, double nd, double tick_s, double* e_out,
-                                                 double* ttft_out, double* tbt_out, bool* ov_out) {
-  const double ninf = -__builtin_inf();
-  double pf[TMAX], tb[TMAX];
-  double e = 0.0;
-  bool ov = false;
-  uint32_t nonempty = 0;
-#pragma unroll
-  for (int q = 0; q < TMAX; ++q) {
-    pf[q] = 0.0;
-    tb[q] = ninf;
-    if (q < T) {
-      double pw;
-      ov = table_lookup<SINGLE, TWO>(L, s_load[q], &pf[q], &tb[q], &pw) | ov;
-      e += (nd * pw) * tick_s;
-      if (s_cnt[q] > 0) nonempty |= 1u << q;
-    }
-  }
-  {
-    uint32_t avail = nonempty;        // a tick without requests contributes no TBT sample
-    int need = j;
-    double val = 0.0;
-    for (int it = 0; it < TMAX && need > 0; ++it) {
-      double best = ninf;
-      int bi = 0;
-#pragma unroll
-      for (int q = 0; q < TMAX; ++q) {
-        const bool better = ((avail >> q) & 1u) && tb[q] > best;
-        best = better ? tb[q] : best;
-        bi = better ? q : bi;
-      }
-      avail &= ~(1u << bi);
-      need -= s_cnt[bi];
-      val = best;
-    }
-    *tbt_out = val;
-  }
-  {
-    double h[TMAX];
-    int pos[TMAX];
-#pragma unroll
-    for (int q = 0; q < TMAX; ++q) {
-      pos[q] = 0;
-      h[q] = ((nonempty >> q) & 1u) ? (double)s_top[q] * pf[q] : ninf;
-    }
-    double val = 0.0;
-    for (int step = 0; step < j; ++step) {
-      double best = ninf, bpf = 0.0;
-      int bi = 0, bp = 0;
-#pragma unroll
-      for (int q = 0; q < TMAX; ++q) {
-        const bool better = h[q] > best;
-        best = better ? h[q] : best;
-        bi = better ? q : bi;
-        bp = better ? pos[q] : bp;
-        bpf = better ? pf[q] : bpf;
-      }
-      val = best;
-      const int np = bp + 1;   // staged while np < j; the merge ends before a later entry is needed
-      const bool more = np < s_cnt[bi] && np < j;
-      const double nh = more ? (double)s_top[np * T + bi] * bpf : ninf;
-#pragma unroll
-      for (int q = 0; q < TMAX; ++q) {
-        const bool hit = q == bi;
-        pos[q] = hit ? np : pos[q];
-        h[q] = hit ? nh : h[q];
-      }
-    }
-    *ttft_out = val;
-  }
-  *e_out = e; *ov_out = ov;
-}
-
-// What the cell kernel decided about one cell (block-uniform).
-struct CellPlan {
-  int j;           // 0 = empty cell
-  bool deep, by_merge;
-};
-__device__ __forceinline__ CellPlan plan_cell(int32_t plan) {
-  CellPlan p;
-  p.j = plan & 0xFF;                            // the percentile is the j-th largest value
-  p.deep = p.j > DYN_TICK_TOP;                  // beyond the extracted candidates: not evaluated
-  p.by_merge = (plan & DYN_PLAN_MERGE) != 0;
-  return p;
+  WalkOut r;
+  r.e = e; r.ov = ov; r.ttft = s[JL - 1]; r.pf_min = pf_min; r.pf_max = pf_max;
+  r.tbt = SPARSE ? tt.jth(j) : tbmax;
+  return r;
 }
 
 // Per-thread state of one configuration inside a (class, tile) block.
@@ -329,15 +453,15 @@ struct CfgState {
   bool live;
 };
 
-// The configuration's constants: `g` and `tile` are block-uniform; the table rows are either the
-// block's LDS copy (LDS) or global memory.
+// The constants of configuration k_raw (>= K: a copy of the last one that stores nothing): `g` is
+// block-uniform; the table rows are either the block's LDS copy (LDS) or global memory.
 template <bool LDS>
-__device__ __forceinline__ void load_config(const TickArgs& a, int g, int tile, const double* s_tab, const double* s_rgp,
+__device__ __forceinline__ void load_config(const TickArgs& a, int g, int k_raw, const double* s_tab, const double* s_rgp,
                                             const double* s_rinv, const double* s_thr, const uint16_t* s_js,
                                             CfgState* st) {
   const SpaceArgs& sa = a.s;
   const int n_rho = sa.n_rho;
-  st->k_raw = tile * sa.tile + threadIdx.x;
+  st->k_raw = k_raw;
   st->live = st->k_raw < sa.K;            // every lane stays alive for the wave reduction
   st->k = st->live ? st->k_raw : sa.K - 1;
   const DevCfg c = sa.cfg[st->k];
@@ -369,7 +493,7 @@ __device__ __forceinline__ void load_config(const TickArgs& a, int g, int tile, 
   const double pw0 = two_rows ? L.omu * p0_lo + c.u * p0_hi : p0_lo;
   st->idle_term = sa.idle_w * ((c.nd * pw0) * a.window_s);
   st->lane = threadIdx.x & (DYN_WAVE - 1);
-  st->wslot = tile * (sa.tile / DYN_WAVE) + (int)(threadIdx.x / DYN_WAVE);
+  st->wslot = st->k_raw / DYN_WAVE;       // tiles are multiples of 64 configurations wide
   st->koff = (uint32_t)st->k * 8u;
 }
 
@@ -434,18 +558,18 @@ __device__ __forceinline__ void emit_cell(const SpaceArgs& sa, const CfgState& s
   }
 }
 
-// Empty cells, cells beyond DYN_TICK_TOP (not evaluated) and cells with j <= kFastDepth whose
-// non-empty ticks all hold at least j requests (the TBT percentile is then the largest tick
-// TBT).  A block walks a run of windows of one (class, tile); the other cells are put on a
-// list for tick_merge_kernel.  The next cell's candidate lists are kept in flight (NPRE
-// registers per thread) while the current one is evaluated.
+// A block walks a run of windows of one (class, tile).  It settles every cell whose TBT percentile
+// the walk can find (DYN_TP_DENSE or DYN_TP_SMALL) and whose TTFT percentile is either within the
+// register list (j <= 16) or pinned by the bracket (the same value at both ends in every lane); the
+// other (cell, tile) items go on a list for tick_general_kernel.  The next cell's candidate lists
+// are kept in flight (NPRE registers per thread) while the current one is evaluated.
 // LDS: [table rows n_slot*3*n_rho] [padded load grid n_rho+2] [reciprocal spacings n_rho+1]
 //      [SINGLE: grid point per bucket, n_bucket+1]
-//      [per window of the block, per tick: load] [the same: request count] [per window: plan]
-//      [two buffers of candidate lists, [position][tick]] [bucket index (16-bit)]
-template <bool LDS, bool SINGLE, bool TWO>
+//      [per window of the block, per tick: load] [the same: request count] [the same: list offset]
+//      [per window: plan] [two buffers of candidate lists, [position][tick]] [bucket index (16-bit)]
+template <int TB, bool LDS, bool SINGLE, bool TWO>
 __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4, 4))) void tick_space_kernel(TickArgs a) {
-  constexpr int NPRE = kFastDepth * DYN_TICK_MAX / DYN_WAVE;   // blocks have at least 64 threads
+  constexpr int NPRE = kFastDepth * TB / DYN_WAVE;   // blocks have at least 64 threads; n_tick <= TB
   extern __shared__ double smem[];
   const SpaceArgs& sa = a.s;
   const int tile = blockIdx.x % sa.n_tile;
@@ -460,10 +584,11 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
   double* s_rinv = s_rgp + (n_rho + 2);
   double* s_thr = s_rinv + (n_rho + 1);                         // [n_bucket + 1] when SINGLE
   double* s_load = s_thr + (SINGLE ? sa.n_bucket + 1 : 0);      // [win_per_block][T]
-  int32_t* s_cnt = (int32_t*)(s_load + sa.win_per_block * T);   // [win_per_block][T] requests per tick
-  int32_t* s_plan = s_cnt + sa.win_per_block * T;               // [win_per_block]
-  int32_t* s_top = s_plan + sa.win_per_block;                   // [2][DYN_TICK_TOP][T]
-  uint16_t* s_js = (uint16_t*)(s_top + 2 * T * DYN_TICK_TOP);   // [n_bucket + 1]
+  TickPlan* s_plan = (TickPlan*)(s_load + sa.win_per_block * T);   // [win_per_block]
+  int32_t* s_cnt = (int32_t*)(s_plan + sa.win_per_block);       // [win_per_block][T] requests per tick
+  uint32_t* s_off = (uint32_t*)(s_cnt + sa.win_per_block * T);  // [win_per_block][T] start of the tick's list
+  int32_t* s_top = (int32_t*)(s_off + sa.win_per_block * T);    // [2][kFastDepth][T]
+  uint16_t* s_js = (uint16_t*)(s_top + 2 * T * kFastDepth);     // [n_bucket + 1]
 
   if (LDS) stage_rows(sa, g, tile, s_tab);
   stage_grid<SINGLE>(a, s_rgp, s_thr, s_js);
@@ -472,24 +597,33 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
     const TickRec r = a.rec[((size_t)(w0 + dw) * sa.G + g) * T + q];
     s_load[i] = r.load;
     s_cnt[i] = r.cnt;
-    if (q == 0) s_plan[dw] = r.plan;
+    s_off[i] = r.off;
   }
+  for (int i = threadIdx.x; i < w1 - w0; i += blockDim.x) s_plan[i] = a.plan[(size_t)(w0 + i) * sa.G + g];
   __syncthreads();
   CfgState st;
-  load_config<LDS>(a, g, tile, s_tab, s_rgp, s_rinv, s_thr, s_js, &st);
+  load_config<LDS>(a, g, tile * sa.tile + (int)threadIdx.x, s_tab, s_rgp, s_rinv, s_thr, s_js, &st);
 
-  // candidate lists of a cell: the first j * T words of its block of DYN_TICK_TOP * T
+  // which cells this kernel walks with a register list: their lists are staged [position][tick]
+  // (with the four-tick TBT list the register list is at most eight deep: both together at full depth spill)
+  auto listed = [&](const TickPlan& p) {
+    return p.j > 0 && (((p.flags & DYN_TP_DENSE) && p.j <= kFastDepth) || ((p.flags & DYN_TP_SMALL) && p.j <= kFastDepth / 2));
+  };
   int32_t pre[NPRE];
   auto prefetch = [&](int w) {
     if (w >= w1) return;
-    const CellPlan p = plan_cell(s_plan[w - w0]);
-    if (p.by_merge || p.j == 0 || p.deep) return;
-    const int32_t* src = a.top + ((size_t)w * sa.G + g) * DYN_TICK_TOP * T;
-    const int n = p.j * T;                     // at most kFastDepth * DYN_TICK_MAX
+    const TickPlan p = s_plan[w - w0];
+    if (!listed(p)) return;
+    const int n = p.j * T;                     // at most kFastDepth * TB
+    const int32_t* cnt_w = s_cnt + (w - w0) * T;
+    const uint32_t* off_w = s_off + (w - w0) * T;
 #pragma unroll
     for (int r = 0; r < NPRE; ++r) {
       const int i = threadIdx.x + r * blockDim.x;
-      if (i < n) pre[r] = src[i];
+      if (i < n) {
+        const int pos = i / T, q = i - pos * T;
+        pre[r] = pos < cnt_w[q] ? a.top[(size_t)off_w[q] + pos] : 0;   // a tick's list has min(j, count) entries
+      }
     }
   };
   prefetch(w0);
@@ -498,122 +632,258 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
     const size_t cell = (size_t)w * sa.G + g;
     const int32_t* cnt_w = s_cnt + (w - w0) * T;
     const double* load_w = s_load + (w - w0) * T;
-    const CellPlan pl = plan_cell(s_plan[w - w0]);
+    const TickPlan pl = s_plan[w - w0];
     const int j = pl.j;
-    const bool deep = pl.deep, empty = j == 0;
-    if (pl.by_merge) {                           // block-uniform: the other kernel takes this cell
-      if (tile == 0 && threadIdx.x == 0) a.merge_list[atomicAdd(a.merge_count, 1u)] = (uint32_t)cell;
+    const bool empty = j == 0, skip = (pl.flags & DYN_TP_SKIP) != 0;
+    const bool dense = (pl.flags & DYN_TP_DENSE) != 0;
+    const bool walkable = (pl.flags & DYN_TP_DENSE) || ((pl.flags & DYN_TP_SMALL) && (j <= kFastDepth / 2 || j > kFastDepth));
+    if (!empty && !skip && !walkable) {          // block-uniform: the TBT percentile needs all ticks
+      if (threadIdx.x == 0) a.slow_list[atomicAdd(&a.counters[1], 1u)] = (uint64_t)cell * sa.n_tile + tile;
       prefetch(w + 1);
       continue;
     }
     // two buffers: the lists of the cell before this one may still be read by slower waves
-    int32_t* top_w = s_top + buf * (T * DYN_TICK_TOP);
-    buf ^= 1;
-    if (!empty && !deep) {
+    int32_t* top_w = s_top + buf * (T * kFastDepth);
+    if (listed(pl)) {
+      buf ^= 1;
       const int n = j * T;
 #pragma unroll
       for (int r = 0; r < NPRE; ++r) {
         const int i = threadIdx.x + r * blockDim.x;
         if (i < n) top_w[i] = pre[r];
       }
+      __syncthreads();
     }
-    __syncthreads();
     prefetch(w + 1);
 
-    double e, p_ttft, p_tbt;
-    bool ov;
-    const int jl = deep ? 0 : j;               // no candidates are read for empty or unevaluated cells
-    if (jl <= 4) walk_ticks_short<4, SINGLE, TWO>(st.L, T, jl, load_w, cnt_w, top_w, st.nd, a.tick_s, &e, &p_ttft, &p_tbt, &ov);
-    else if (jl <= 8) walk_ticks_short<8, SINGLE, TWO>(st.L, T, jl, load_w, cnt_w, top_w, st.nd, a.tick_s, &e, &p_ttft, &p_tbt, &ov);
-    else walk_ticks_short<kFastDepth, SINGLE, TWO>(st.L, T, jl, load_w, cnt_w, top_w, st.nd, a.tick_s, &e, &p_ttft, &p_tbt, &ov);
-    if (empty) p_ttft = p_tbt = 0.0;
-    if (deep) p_ttft = p_tbt = __builtin_inf();   // reported through the status word
-    emit_cell(sa, st, cell, empty, ov, e, p_ttft, p_tbt);
+    WalkOut o;
+    bool settled = true;
+    if (empty || skip) {
+      o = walk_ticks<0, false, SINGLE, TWO>(st.L, T, 0, load_w, cnt_w, top_w, st.nd, a.tick_s);
+      o.ttft = o.tbt = empty ? 0.0 : __builtin_inf();   // a skipped cell is reported through the status word
+    } else if (j > kFastDepth) {
+      if (dense) o = walk_ticks<0, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
+      else o = walk_ticks<0, true, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
+      // the percentile lies in [x_j * least prefill time, x_j * largest prefill time] of the non-empty ticks
+      const double xj = (double)pl.xj;
+      const double lo = xj * o.pf_min, hi = xj * o.pf_max;
+      o.ttft = lo;
+      settled = __syncthreads_or(lo != hi ? 1 : 0) == 0;
+    } else if (dense) {
+      if (j <= 4) o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
+      else if (j <= 8) o = walk_ticks<8, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
+      else o = walk_ticks<kFastDepth, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
+    } else {
+      if (j <= 4) o = walk_ticks<4, true, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
+      else o = walk_ticks<kFastDepth / 2, true, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
+    }
+    if (!settled) {                              // block-uniform
+      if (threadIdx.x == 0) a.slow_list[atomicAdd(&a.counters[1], 1u)] = (uint64_t)cell * sa.n_tile + tile;
+      continue;
+    }
+    emit_cell(sa, st, cell, empty, o.ov, o.e, o.ttft, o.tbt);
   }
 }
 
-// The cells the kernel above listed, one (cell, tile) item at a time, items dealt round-robin
-// to a fixed grid so that runs of heavy cells spread over the chip.  The table rows and the
-// configuration are reloaded only when the item's (class, tile) differs from the previous one.
-// LDS: [table rows] [load grid] [reciprocal spacings] [SINGLE: grid point per bucket]
-//      [per tick: load] [per tick: request count] [candidate lists [position][tick]] [bucket index]
-template <bool LDS, bool SINGLE, bool TWO>
-__global__ __launch_bounds__(DYN_MAX_TILE) void tick_merge_kernel(TickArgs a) {
+// The (cell, tile) items the kernel above listed, dealt round-robin to a fixed grid so that runs of
+// heavy cells spread over the chip.  A block of NT threads takes the tile's configurations NT at a time.
+// Per configuration: the ticks' TBTs into an LDS strip and the TBT percentile by taking ticks in
+// descending TBT order until j requests are covered; the bracket of the TTFT percentile; where its ends
+// differ, the ticks' prefill times into the strip and a bisection of the bracket: a probe value v is
+// ranked in every tick's list (binary search on the scaled entries), and either at least j scaled
+// entries are >= v, then the least of them is a new lower end, or fewer, then the largest one below v
+// is a new upper end.  Both ends are values of the lists from then on, so the search ends with the
+// percentile itself.
+// LDS: [table rows] [load grid] [reciprocal spacings] [SINGLE: grid point per bucket] [strip NT x n_tick]
+//      [per tick: load] [per tick: count] [per tick: entries listed] [per tick: start of its list]
+//      [the cell's lists when they fit] [bucket index]
+template <int NT, bool LDS, bool SINGLE, bool TWO>
+__global__ __launch_bounds__(NT) void tick_general_kernel(TickArgs a) {
   extern __shared__ double smem[];
   const SpaceArgs& sa = a.s;
   const int n_rho = sa.n_rho, T = a.n_tick;
+  const int tid = threadIdx.x;
   double* s_tab = smem;
   double* s_rgp = smem + (LDS ? (size_t)sa.n_slot * DYN_SLOT_STRIDE(n_rho) : 0);
   double* s_rinv = s_rgp + (n_rho + 2);
   double* s_thr = s_rinv + (n_rho + 1);
-  double* s_load = s_thr + (SINGLE ? sa.n_bucket + 1 : 0);      // [T]
+  double* s_strip = s_thr + (SINGLE ? sa.n_bucket + 1 : 0);     // [T][NT]
+  double* s_load = s_strip + (size_t)T * NT;                    // [T]
   int32_t* s_cnt = (int32_t*)(s_load + T);                      // [T]
-  int32_t* s_top = s_cnt + T;                                   // [DYN_TICK_TOP][T]
-  uint16_t* s_js = (uint16_t*)(s_top + T * DYN_TICK_TOP);       // [n_bucket + 1]
+  int32_t* s_len = s_cnt + T;                                   // [T] min(j, count)
+  uint32_t* s_lbase = (uint32_t*)(s_len + T);                   // [T] start of the tick's list; [T]: lists staged in LDS?
+  int32_t* s_lists = (int32_t*)(s_lbase + T + 1);               // [kListCap]
+  uint16_t* s_js = (uint16_t*)(s_lists + kListCap);             // [n_bucket + 1]
 
-  const uint32_t n_item = *a.merge_count * (uint32_t)sa.n_tile;  // complete: written by the previous kernel
+  const uint64_t n_item = a.counters[1];                         // complete: written by the previous kernel
   if (blockIdx.x >= n_item) return;                              // block-uniform
   stage_grid<SINGLE>(a, s_rgp, s_thr, s_js);
-  CfgState st;
   int cur_g = -1, cur_tile = -1;
-  for (uint32_t item = blockIdx.x; item < n_item; item += gridDim.x) {
-    const size_t cell = a.merge_list[item / sa.n_tile];
-    const int tile = (int)(item % sa.n_tile);
+  for (uint64_t item = blockIdx.x; item < n_item; item += gridDim.x) {
+    const uint64_t packed = a.slow_list[item];
+    const size_t cell = (size_t)(packed / (uint64_t)sa.n_tile);
+    const int tile = (int)(packed % (uint64_t)sa.n_tile);
     const int g = (int)(cell % sa.G);
     __syncthreads();                           // the previous item's LDS data has been consumed
-    const bool fresh = g != cur_g || tile != cur_tile;
-    if (LDS && fresh) stage_rows(sa, g, tile, s_tab);
-    int j = 0;
-    {
+    if (LDS && (g != cur_g || tile != cur_tile)) stage_rows(sa, g, tile, s_tab);
+    cur_g = g;
+    cur_tile = tile;
+    const TickPlan pl = a.plan[cell];
+    const int j = pl.j;
+    if (tid == 0) {                            // where each tick's list is read from
       const TickRec* rec = a.rec + cell * T;
-      j = rec[0].plan & 0xFF;                  // 1 .. DYN_TICK_TOP for a listed cell
-      for (int q = threadIdx.x; q < T; q += blockDim.x) {
+      uint32_t total = 0;
+      for (int q = 0; q < T; ++q) total += (uint32_t)min(rec[q].cnt, j);
+      const bool fits = total <= (uint32_t)kListCap;
+      uint32_t at = 0;
+      for (int q = 0; q < T; ++q) {
         const TickRec r = rec[q];
         s_load[q] = r.load;
         s_cnt[q] = r.cnt;
+        s_len[q] = min(r.cnt, j);
+        s_lbase[q] = fits ? at : r.off;
+        at += (uint32_t)min(r.cnt, j);
       }
-      const int32_t* src = a.top + cell * DYN_TICK_TOP * T;
-      for (int i = threadIdx.x; i < j * T; i += blockDim.x) s_top[i] = src[i];
+      s_lbase[T] = fits ? 1u : 0u;
     }
     __syncthreads();
-    if (fresh) {
-      load_config<LDS>(a, g, tile, s_tab, s_rgp, s_rinv, s_thr, s_js, &st);
-      cur_g = g;
-      cur_tile = tile;
+    const bool staged = s_lbase[T] != 0u;
+    if (staged) {
+      const TickRec* rec = a.rec + cell * T;
+      for (int q = 0; q < T; ++q) {
+        const int32_t* src = a.top + rec[q].off;
+        int32_t* dst = s_lists + s_lbase[q];
+        for (int i = tid; i < s_len[q]; i += NT) dst[i] = src[i];
+      }
     }
-    double e, p_ttft, p_tbt;
-    bool ov;
-    // the ticks are unrolled: take the smallest instance that holds them (block-uniform)
-    if (T <= 4) walk_ticks_merge<4, SINGLE, TWO>(st.L, T, j, s_load, s_cnt, s_top, st.nd, a.tick_s, &e, &p_ttft, &p_tbt, &ov);
-    else if (T <= 8) walk_ticks_merge<8, SINGLE, TWO>(st.L, T, j, s_load, s_cnt, s_top, st.nd, a.tick_s, &e, &p_ttft, &p_tbt, &ov);
-    else if (T <= 12) walk_ticks_merge<12, SINGLE, TWO>(st.L, T, j, s_load, s_cnt, s_top, st.nd, a.tick_s, &e, &p_ttft, &p_tbt, &ov);
-    else walk_ticks_merge<DYN_TICK_MAX, SINGLE, TWO>(st.L, T, j, s_load, s_cnt, s_top, st.nd, a.tick_s, &e, &p_ttft, &p_tbt, &ov);
-    emit_cell(sa, st, cell, false, ov, e, p_ttft, p_tbt);
+    __syncthreads();
+    const int32_t* lists = staged ? s_lists : a.top;
+    const double xj = (double)pl.xj;
+
+    for (int sub = 0; sub < sa.tile; sub += NT) {
+      CfgState st;
+      load_config<LDS>(a, g, tile * sa.tile + sub + tid, s_tab, s_rgp, s_rinv, s_thr, s_js, &st);
+      // the ticks once: energy in time order, TBT of every tick kept, range of the prefill times
+      double e = 0.0, pf_min = __builtin_inf(), pf_max = -__builtin_inf();
+      bool ov = false;
+      for (int q = 0; q < T; ++q) {
+        double pf, tb, pw;
+        ov = table_lookup<SINGLE, TWO>(st.L, s_load[q], &pf, &tb, &pw) | ov;
+        e += (st.nd * pw) * a.tick_s;
+        s_strip[q * NT + tid] = tb;
+        if (s_cnt[q] > 0) { pf_min = min_num(pf_min, pf); pf_max = max_num(pf_max, pf); }
+      }
+      // TBT percentile: ticks in descending TBT order (equal values together) until j requests are covered
+      double p_tbt = 0.0;
+      {
+        int need = j;
+        double prev = __builtin_inf();
+        while (need > 0) {
+          double best = -__builtin_inf();
+          int c = 0;
+          for (int q = 0; q < T; ++q) {
+            const int cq = s_cnt[q];
+            if (cq == 0) continue;
+            const double v = s_strip[q * NT + tid];
+            const bool lt = v < prev;
+            const bool gt = lt && v > best;
+            const bool eq = lt && v == best;
+            c = gt ? cq : (eq ? c + cq : c);
+            best = gt ? v : best;
+          }
+          if (c == 0) break;                   // cannot happen: the cell holds at least j requests
+          need -= c;
+          prev = best;
+          p_tbt = best;
+        }
+      }
+      // TTFT percentile
+      double lo = xj * pf_min, hi = xj * pf_max;
+      bool open = lo != hi;
+      if (__syncthreads_or(open ? 1 : 0)) {
+        for (int q = 0; q < T; ++q) {          // the same look-ups again: this time the prefill times are kept
+          double pf, tb, pw;
+          table_lookup<SINGLE, TWO>(st.L, s_load[q], &pf, &tb, &pw);
+          s_strip[q * NT + tid] = pf;
+        }
+        while (open) {
+          double v = lo + (hi - lo) * 0.5;
+          if (!(v > lo)) v = hi;
+          int n_ge = 0;
+          double a_min = __builtin_inf(), b_max = -__builtin_inf();
+          for (int q = 0; q < T; ++q) {
+            const int len = s_len[q];
+            if (len == 0) continue;
+            const double pf = s_strip[q * NT + tid];
+            const int32_t* lq = lists + s_lbase[q];
+            int l = 0, h = len;                // entries [0, l) are >= v scaled, entries [h, len) are below
+            while (l < h) {
+              const int mid = (l + h) >> 1;
+              const bool ge = (double)lq[mid] * pf >= v;
+              l = ge ? mid + 1 : l;
+              h = ge ? h : mid;
+            }
+            n_ge += l;
+            if (l > 0) a_min = min_num(a_min, (double)lq[l - 1] * pf);
+            if (l < len) b_max = max_num(b_max, (double)lq[l] * pf);
+          }
+          if (n_ge >= j) lo = a_min; else hi = b_max;
+          open = lo < hi;                      // also ends a search that lost its bracket (never with consistent lists)
+        }
+      }
+      emit_cell(sa, st, cell, false, ov, e, lo, p_tbt);
+      __syncthreads();                         // the strip is rewritten by the next group of configurations
+    }
   }
 }
 
 size_t tick_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t n_tick, int32_t win_per_block, bool single) {
   return (size_t)(2 * n_rho + 3) * sizeof(double) + (single ? ((size_t)n_bucket + 1) * sizeof(double) : 0) +
-         (size_t)win_per_block * (n_tick * (sizeof(double) + sizeof(int32_t)) + sizeof(int32_t)) +
-         (size_t)2 * n_tick * DYN_TICK_TOP * sizeof(int32_t) + ((size_t)n_bucket + 1) * sizeof(uint16_t) + 8;
+         (size_t)win_per_block * (n_tick * (sizeof(double) + 2 * sizeof(int32_t)) + sizeof(TickPlan)) +
+         (size_t)2 * n_tick * kFastDepth * sizeof(int32_t) + ((size_t)n_bucket + 1) * sizeof(uint16_t) + 8;
 }
-
-constexpr int kMergeBlocks = 1024;
+size_t general_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t n_tick, int nt, bool single) {
+  return (size_t)(2 * n_rho + 3) * sizeof(double) + (single ? ((size_t)n_bucket + 1) * sizeof(double) : 0) +
+         (size_t)n_tick * nt * sizeof(double) + (size_t)n_tick * (sizeof(double) + 3 * sizeof(int32_t)) + sizeof(uint32_t) +
+         (size_t)kListCap * sizeof(int32_t) + ((size_t)n_bucket + 1) * sizeof(uint16_t) + 8;
+}
+// configurations a block of the general kernel takes at a time: the strip holds one double per (tick, configuration)
+int general_threads(int32_t n_tick) { return n_tick <= 16 ? 256 : (n_tick <= 32 ? 128 : 64); }
+static_assert(64 * DYN_TICK_MAX * sizeof(double) <= kStripBytes && 128 * 32 * sizeof(double) <= kStripBytes &&
+                  256 * 16 * sizeof(double) <= kStripBytes,
+              "the strip of the general kernel");
 
 template <bool LDS, bool SINGLE, bool TWO>
-void launch_both(const TickArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
-  {
-    DynTimed timed(DYN_K_TICK_SPACE, s);
-    hipLaunchKernelGGL((tick_space_kernel<LDS, SINGLE, TWO>), grid, block, lds, s, a);
-  }
-  // the merge kernel's LDS needs are within the first kernel's (one window, one list buffer)
-  DynTimed timed(DYN_K_TICK_MERGE, s);
-  hipLaunchKernelGGL((tick_merge_kernel<LDS, SINGLE, TWO>), dim3(kMergeBlocks), block, lds, s, a);
+void launch_space(const TickArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
+  DynTimed timed(DYN_K_TICK_SPACE, s);
+  if (a.n_tick <= 16) hipLaunchKernelGGL((tick_space_kernel<16, LDS, SINGLE, TWO>), grid, block, lds, s, a);
+  else hipLaunchKernelGGL((tick_space_kernel<DYN_TICK_MAX, LDS, SINGLE, TWO>), grid, block, lds, s, a);
 }
-template <bool LDS, bool SINGLE>
-void launch_rows(const TickArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
-  if (a.any_two_rows) launch_both<LDS, SINGLE, true>(a, grid, block, lds, s);
-  else launch_both<LDS, SINGLE, false>(a, grid, block, lds, s);
+template <bool LDS, bool SINGLE, bool TWO>
+void launch_general(const TickArgs& a, size_t lds, hipStream_t s) {
+  DynTimed timed(DYN_K_TICK_MERGE, s);
+  const int nt = general_threads(a.n_tick);
+  // a tile narrower than the block (64, 128 or 192 configurations) is walked by as many threads as it is wide
+  if (nt == 256 && a.s.tile % 256 == 0) hipLaunchKernelGGL((tick_general_kernel<256, LDS, SINGLE, TWO>), dim3(kGeneralBlocks), dim3(256), lds, s, a);
+  else if (nt >= 128 && a.s.tile % 128 == 0) hipLaunchKernelGGL((tick_general_kernel<128, LDS, SINGLE, TWO>), dim3(kGeneralBlocks), dim3(128), lds, s, a);
+  else hipLaunchKernelGGL((tick_general_kernel<64, LDS, SINGLE, TWO>), dim3(kGeneralBlocks), dim3(64), lds, s, a);
+}
+int general_block(const TickArgs& a) {
+  const int nt = general_threads(a.n_tick);
+  if (nt == 256 && a.s.tile % 256 == 0) return 256;
+  if (nt >= 128 && a.s.tile % 128 == 0) return 128;
+  return 64;
+}
+
+template <typename F>
+void dispatch(bool lds, bool single, bool two, F&& f) {
+  if (lds) {
+    if (single) { if (two) f(std::true_type(), std::true_type(), std::true_type()); else f(std::true_type(), std::true_type(), std::false_type()); }
+    else { if (two) f(std::true_type(), std::false_type(), std::true_type()); else f(std::true_type(), std::false_type(), std::false_type()); }
+  } else {
+    if (single) { if (two) f(std::false_type(), std::true_type(), std::true_type()); else f(std::false_type(), std::true_type(), std::false_type()); }
+    else { if (two) f(std::false_type(), std::false_type(), std::true_type()); else f(std::false_type(), std::false_type(), std::false_type()); }
+  }
 }
 
 }  // namespace
@@ -622,33 +892,62 @@ hipError_t dyn_launch_tick_cell(const TickCellArgs& a, hipStream_t s) {
   const int64_t cells = (int64_t)a.n_window * a.G;
   const int64_t blocks = (cells + kWavesPerBlock - 1) / kWavesPerBlock;
   DynTimed timed(DYN_K_TICK_TOP, s);
+  hipLaunchKernelGGL(tick_init_kernel, dim3(1), dim3(1), 0, s, a.counters);
   hipLaunchKernelGGL(tick_cell_kernel, dim3((unsigned)blocks), dim3(kWavesPerBlock * DYN_WAVE), 0, s, a);
+  hipLaunchKernelGGL(tick_deep_kernel, dim3(kDeepBlocks), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
-hipError_t dyn_launch_tick_space(const TickArgs& a, hipStream_t s) {
+// Windows a block of the evaluation kernel walks: as for the window-level kernel, less where the per-tick
+// records of that many windows would not fit beside the table rows.
+int32_t dyn_tick_win_per_block(const TickArgs& a, int32_t wanted) {
   const SpaceArgs& sa = a.s;
+  const size_t tab = (size_t)sa.n_slot * DYN_SLOT_STRIDE(sa.n_rho) * sizeof(double);
+  int32_t wpb = wanted;
+  while (wpb > 1 && tab + tick_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, wpb, a.single_point) > DYN_LDS_BUDGET) wpb /= 2;
+  return wpb;
+}
+
+hipError_t dyn_launch_tick_space(const TickArgs& a_in, hipStream_t s) {
+  TickArgs a = a_in;
+  SpaceArgs& sa = a.s;
+  sa.win_per_block = dyn_tick_win_per_block(a, sa.win_per_block);
   const int n_chunk = (sa.n_window + sa.win_per_block - 1) / sa.win_per_block;
   const dim3 grid((unsigned)((size_t)n_chunk * sa.G * sa.n_tile)), block(sa.tile);
   const size_t tab = (size_t)sa.n_slot * DYN_SLOT_STRIDE(sa.n_rho) * sizeof(double);
   // Preferences when LDS is short: keep the table rows in LDS first, the per-bucket grid
   // points second (without them the bracket is searched; without the rows the tables are
   // read from global memory).
-  bool single = a.single_point;
-  size_t tail = tick_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, sa.win_per_block, single);
-  if (single && tail + tab > DYN_LDS_BUDGET) {
-    single = false;
-    tail = tick_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, sa.win_per_block, false);
+  {
+    bool single = a.single_point;
+    size_t tail = tick_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, sa.win_per_block, single);
+    if (single && tail + tab > DYN_LDS_BUDGET) {
+      single = false;
+      tail = tick_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, sa.win_per_block, false);
+    }
+    const bool lds = sa.n_slot > 0 && tab + tail <= DYN_LDS_BUDGET;
+    if (!lds && tail > DYN_LDS_BUDGET) return hipErrorInvalidValue;
+    const size_t bytes = (lds ? tab : 0) + tail;
+    dispatch(lds, single, a.any_two_rows, [&](auto L, auto S, auto W) {
+      launch_space<decltype(L)::value, decltype(S)::value, decltype(W)::value>(a, grid, block, bytes, s);
+    });
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
   }
-  const bool lds = sa.n_slot > 0 && tab + tail <= DYN_LDS_BUDGET;
-  if (!lds && tail > DYN_LDS_BUDGET) return hipErrorInvalidValue;
-  const size_t bytes = (lds ? tab : 0) + tail;
-  if (lds) {
-    if (single) launch_rows<true, true>(a, grid, block, bytes, s);
-    else launch_rows<true, false>(a, grid, block, bytes, s);
-  } else {
-    if (single) launch_rows<false, true>(a, grid, block, bytes, s);
-    else launch_rows<false, false>(a, grid, block, bytes, s);
+  {
+    const int nt = general_block(a);
+    bool single = a.single_point;
+    size_t tail = general_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, nt, single);
+    if (single && tail + tab > DYN_LDS_BUDGET) {
+      single = false;
+      tail = general_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, nt, false);
+    }
+    const bool lds = sa.n_slot > 0 && tab + tail <= DYN_LDS_BUDGET;
+    if (!lds && tail > DYN_LDS_BUDGET) return hipErrorInvalidValue;
+    const size_t bytes = (lds ? tab : 0) + tail;
+    dispatch(lds, single, a.any_two_rows, [&](auto L, auto S, auto W) {
+      launch_general<decltype(L)::value, decltype(S)::value, decltype(W)::value>(a, bytes, s);
+    });
   }
   return hipGetLastError();
 }

@@ -45,10 +45,10 @@ def test_workspace_sizes(dyn):
     b = dyn.dyn_trace_ingest_workspace(10_000_000, 1440, 25)
     assert b % 256 == 0 and b >= 4 * 4 * 10_000_000
     assert dyn.dyn_trace_ingest_workspace(0, 1, 1) > 0
-    c = dyn.dyn_eval_ticks_workspace(1440, 12, 25, 576)
-    assert c % 256 == 0 and c >= 36000 * 12 * (64 * 4 + 53)
-    assert dyn.dyn_eval_ticks_workspace(1440, 17, 25, 576) == 0      # beyond DYN_TICK_LIMIT
-    assert dyn.dyn_eval_ticks_workspace(1440, 0, 25, 576) == 0
+    c = dyn.dyn_eval_ticks_workspace(10_000_000, 1440, 12, 25, 576)
+    assert c % 256 == 0 and c >= 4 * 10_000_000 + 36000 * 12 * 53
+    assert dyn.dyn_eval_ticks_workspace(10_000_000, 1440, 65, 25, 576) == 0      # beyond DYN_TICK_LIMIT
+    assert dyn.dyn_eval_ticks_workspace(10_000_000, 1440, 0, 25, 576) == 0
     h = dyn.dyn_hierarchy_workspace(1440, 12, 25, 48)
     assert h % 256 == 0 and h >= 36000 * 13 * 53            # both aggregations: 53 bytes per window and per tick cell
     assert dyn.dyn_hierarchy_workspace(1440, 12, 25, 0) == 0 and dyn.dyn_hierarchy_workspace(1440, 0, 25, 48) == 0
