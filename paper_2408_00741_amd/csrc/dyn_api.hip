@@ -325,8 +325,7 @@ TickWs dyn_tick_ws_layout(int64_t n_req, int64_t coarse_cells, int32_t n_tick, i
   w.part = off; off += align256(c * (size_t)w.n_wslot * sizeof(SelPart));
   w.counters = off; off += 256;
   w.deep_list = off; off += align256(c * sizeof(uint32_t));
-  // one item per (cell, tile); a tile is at least 64 configurations wide
-  w.slow_list = off; off += align256(c * (size_t)((std::max(K, 1) + DYN_WAVE - 1) / DYN_WAVE) * sizeof(uint64_t));
+  w.slow_list = off; off += align256(c * sizeof(uint32_t));
   w.total = off;
   return w;
 }
@@ -691,7 +690,7 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   ca.pct_num = o->pct_num; ca.pct_den = o->pct_den;
   ca.rec = (TickRec*)(base + w.fine.rec); ca.plan = (TickPlan*)(base + w.plan); ca.top = (int32_t*)(base + w.top);
   ca.cstat = (uint8_t*)(base + w.fine.cstat); ca.header = (WsHeader*)(base + w.fine.header);
-  ca.counters = (uint32_t*)(base + w.counters); ca.deep_list = (uint32_t*)(base + w.deep_list);
+  ca.counters = (uint32_t*)(base + w.counters); ca.deep_list = (uint32_t*)(base + w.deep_list); ca.slow_list = (uint32_t*)(base + w.slow_list);
   if (!hip_ok(dyn_launch_tick_cell(ca, s), "tick cell launch")) return DYN_E_DEVICE;
 
   TickArgs ta;
@@ -710,7 +709,7 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   a.part = (SelPart*)(base + w.part); a.n_wslot = w.n_wslot;
   ta.n_tick = n_tick; ta.tick_s = t->window_s; ta.window_s = (double)n_tick * t->window_s;
   ta.rec = (const TickRec*)(base + w.fine.rec); ta.plan = (const TickPlan*)(base + w.plan); ta.top = (const int32_t*)(base + w.top);
-  ta.counters = (uint32_t*)(base + w.counters); ta.slow_list = (uint64_t*)(base + w.slow_list);
+  ta.counters = (const uint32_t*)(base + w.counters); ta.slow_list = (const uint32_t*)(base + w.slow_list);
   ta.tstart = p->d_tstart; ta.thr = p->d_thr; ta.single_point = p->single_point; ta.any_two_rows = p->any_two_rows;
   if (!hip_ok(dyn_launch_tick_space(ta, s), "tick space launch")) return DYN_E_DEVICE;
 

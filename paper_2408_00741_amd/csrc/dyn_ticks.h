@@ -28,6 +28,7 @@ struct TickPlan {
 #define DYN_TP_SMALL 2u   // the four non-empty ticks of largest TBT hold at least j requests, whichever they are
 #define DYN_TP_DEEP 4u    // j > DYN_TICK_WAVE: lists and xj come from the deep-cell kernel
 #define DYN_TP_SKIP 8u    // j > DYN_TICK_DEPTH: not evaluated
+#define DYN_TP_GENERAL 16u  // left to the general kernel: j beyond the walk's register list, or a TBT percentile that needs all ticks
 
 struct TickCellArgs {
   const int32_t* in; const int32_t* out;
@@ -41,8 +42,9 @@ struct TickCellArgs {
   int32_t* top;              // [n_req]: per tick its min(j, cnt) largest input lengths, descending, at rec.off
   uint8_t* cstat;            // [fine cells] status bytes
   WsHeader* header;
-  uint32_t* counters;        // [0] cells on deep_list, [1] items on slow_list; zeroed before the cell kernel
+  uint32_t* counters;        // [0] cells on deep_list, [1] cells on slow_list; zeroed before the cell kernel
   uint32_t* deep_list;       // [cells]
+  uint32_t* slow_list;       // [cells] cells left to the general kernel
 };
 
 struct TickArgs {
@@ -55,8 +57,8 @@ struct TickArgs {
   const int32_t* top;      // [n_req]
   const int32_t* tstart; const double* thr; bool single_point;   // threshold form of the bucket index
   bool any_two_rows;
-  uint32_t* counters;      // [1]: number of (cell, tile) items on slow_list
-  uint64_t* slow_list;     // [cells * n_tile] items cell * n_tile + tile left to the general kernel
+  const uint32_t* counters;   // [1]: number of cells on slow_list
+  const uint32_t* slow_list;  // [cells] cells left to the general kernel
 };
 
 // Workspace: the per-cell part of the evaluation workspace for the fine cells, then the plans, the

@@ -13,17 +13,15 @@
 //                      j-th largest input length x_j; what the later kernels do with the cell;
 //   tick_deep_kernel   the same lists and x_j for the cells with j > 64 (a block per cell:
 //                      bitonic sort of a tick in LDS);
-//   tick_space_kernel  per (cell, configuration) a walk over the ticks: energy in time order,
-//                      the TBT percentile (largest tick TBT when every non-empty tick holds j
-//                      requests, else from the four largest tick TBTs), and the TTFT percentile:
-//                      j <= 16 through a sorted register list of the scaled candidates; j > 16
-//                      from the bracket [x_j * least, x_j * largest prefill time of the ticks],
-//                      which holds the percentile and is a single value whenever the prefill
-//                      time does not depend on the load;
-//   tick_general_kernel everything the walk cannot settle, (cell, tile) by (cell, tile): the
-//                      ticks' TBTs and prefill times kept in LDS, the TBT percentile by taking
-//                      ticks in descending TBT order, the TTFT percentile by bisecting the
-//                      bracket on the ticks' sorted lists.
+//   tick_space_kernel  the cells with j <= 16: per (cell, configuration) a walk over the ticks, energy in time
+//                      order, the TBT percentile (largest tick TBT when every non-empty tick holds j
+//                      requests, else from the four largest tick TBTs), the TTFT percentile through a
+//                      sorted register list of the scaled candidates;
+//   tick_general_kernel every other cell, (cell, tile) by (cell, tile): the ticks' prefill times (TBTs)
+//                      kept in an LDS strip, the TBT percentile by taking ticks in descending TBT
+//                      order, the TTFT percentile from the bracket [x_j * least, x_j * largest prefill
+//                      time of the ticks]: a single value, or settled by ranking the ticks that hold
+//                      lengths equal to x_j, or bisected on the ticks' sorted lists.
 #include <type_traits>
 
 #include "dyn_ticks.h"
@@ -103,6 +101,9 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
       if (lane == (int)__builtin_ctzll(who)) cpos = 0xFFFFFFFFu;
     }
     if (all_in || s4 >= j64) flags |= DYN_TP_SMALL;
+    // the walk kernel keeps a register list of 16 candidates beside the largest tick TBT, of 8 beside the four largest
+    const bool walk = ((flags & DYN_TP_DENSE) && j64 <= kFastDepth) || ((flags & DYN_TP_SMALL) && j64 <= kFastDepth / 2);
+    if (!skip && !walk) flags |= DYN_TP_GENERAL;
   }
 
   int32_t* buf = s_buf[wave];
@@ -228,6 +229,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
     p.pad = 0;
     a.plan[c] = p;
     if (deep) a.deep_list[atomicAdd(&a.counters[0], 1u)] = (uint32_t)c;
+    if (flags & DYN_TP_GENERAL) a.slow_list[atomicAdd(&a.counters[1], 1u)] = (uint32_t)c;
   }
   if (c == 0 && lane == 0) {                     // single writer of the header
     a.header->status = 0u;
@@ -394,31 +396,28 @@ struct TbtTop {
 };
 
 struct WalkOut {
-  double e, ttft, tbt, pf_min, pf_max;
+  double e, ttft, tbt;
   bool ov;
 };
 
-// One walk over the ticks of a cell, in time order, two look-ups in flight.  JF > 0: the cell's j <= JF
-// largest scaled candidates through a sorted list that starts with JF - j copies of +inf, so that its last
-// entry is the j-th largest of what was inserted.  JF == 0: no candidates are read; the least and the
-// largest prefill time over the non-empty ticks are returned instead.  SPARSE: the TBT percentile from the
-// four largest tick TBTs, else the largest tick TBT.
+// One walk over the ticks of a cell, in time order, two look-ups in flight.  The cell's j <= JF largest scaled
+// candidates go through a sorted list that starts with JF - j copies of +inf, so that its last entry is the j-th
+// largest of what was inserted (j == 0: nothing is inserted).  SPARSE: the TBT percentile from the four largest
+// tick TBTs, else the largest tick TBT.
 template <int JF, bool SPARSE, bool SINGLE, bool TWO>
 __device__ __forceinline__ WalkOut walk_ticks(const Lookup& L, int T, int j, const double* s_load, const int32_t* s_cnt,
                                               const int32_t* s_top, double nd, double tick_s) {
-  constexpr int JL = JF > 0 ? JF : 1;
-  double s[JL];
+  double s[JF];
 #pragma unroll
-  for (int i = 0; i < JL; ++i) s[i] = i < JL - j ? __builtin_inf() : -__builtin_inf();
-  double e = 0.0, tbmax = -__builtin_inf(), pf_min = __builtin_inf(), pf_max = -__builtin_inf();
+  for (int i = 0; i < JF; ++i) s[i] = i < JF - j ? __builtin_inf() : -__builtin_inf();
+  double e = 0.0, tbmax = -__builtin_inf();
   TbtTop tt;
   if (SPARSE) tt.clear();
   bool ov = false;
   auto one = [&](int q, int c0, double pf0, double tb0) {
-    if (c0 > 0) {                                // block-uniform
+    if (c0 > 0 && j > 0) {                       // block-uniform
       if (SPARSE) tt.offer(tb0, c0); else tbmax = max_num(tbmax, tb0);
-      if (JF > 0) offer_tick<JL>(s, s_top, T, q, c0 < j ? c0 : j, pf0);
-      else { pf_min = min_num(pf_min, pf0); pf_max = max_num(pf_max, pf0); }
+      offer_tick<JF>(s, s_top, T, q, c0 < j ? c0 : j, pf0);
     }
   };
   int q = 0;
@@ -439,7 +438,7 @@ __device__ __forceinline__ WalkOut walk_ticks(const Lookup& L, int T, int j, con
     one(q, s_cnt[q], pf0, tb0);
   }
   WalkOut r;
-  r.e = e; r.ov = ov; r.ttft = s[JL - 1]; r.pf_min = pf_min; r.pf_max = pf_max;
+  r.e = e; r.ov = ov; r.ttft = s[JF - 1];
   r.tbt = SPARSE ? tt.jth(j) : tbmax;
   return r;
 }
@@ -558,11 +557,9 @@ __device__ __forceinline__ void emit_cell(const SpaceArgs& sa, const CfgState& s
   }
 }
 
-// A block walks a run of windows of one (class, tile).  It settles every cell whose TBT percentile
-// the walk can find (DYN_TP_DENSE or DYN_TP_SMALL) and whose TTFT percentile is either within the
-// register list (j <= 16) or pinned by the bracket (the same value at both ends in every lane); the
-// other (cell, tile) items go on a list for tick_general_kernel.  The next cell's candidate lists
-// are kept in flight (NPRE registers per thread) while the current one is evaluated.
+// A block walks a run of windows of one (class, tile): the empty cells, the cells that are not evaluated and
+// the cells the cell kernel left to this kernel (the others are the general kernel's).  The next cell's
+// candidate lists are kept in flight (NPRE registers per thread) while the current one is evaluated.
 // LDS: [table rows n_slot*3*n_rho] [padded load grid n_rho+2] [reciprocal spacings n_rho+1]
 //      [SINGLE: grid point per bucket, n_bucket+1]
 //      [per window of the block, per tick: load] [the same: request count] [the same: list offset]
@@ -590,6 +587,11 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
   int32_t* s_top = (int32_t*)(s_off + sa.win_per_block * T);    // [2][kFastDepth][T]
   uint16_t* s_js = (uint16_t*)(s_top + 2 * T * kFastDepth);     // [n_bucket + 1]
 
+  // a block whose cells all belong to the general kernel has nothing to stage
+  bool any = false;
+  for (int w = w0; w < w1; ++w) any = any || !(a.plan[(size_t)w * sa.G + g].flags & DYN_TP_GENERAL);
+  if (!any) return;                                             // block-uniform
+
   if (LDS) stage_rows(sa, g, tile, s_tab);
   stage_grid<SINGLE>(a, s_rgp, s_thr, s_js);
   for (int i = threadIdx.x; i < (w1 - w0) * T; i += blockDim.x) {   // the ticks of this block's cells
@@ -604,11 +606,8 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
   CfgState st;
   load_config<LDS>(a, g, tile * sa.tile + (int)threadIdx.x, s_tab, s_rgp, s_rinv, s_thr, s_js, &st);
 
-  // which cells this kernel walks with a register list: their lists are staged [position][tick]
-  // (with the four-tick TBT list the register list is at most eight deep: both together at full depth spill)
-  auto listed = [&](const TickPlan& p) {
-    return p.j > 0 && (((p.flags & DYN_TP_DENSE) && p.j <= kFastDepth) || ((p.flags & DYN_TP_SMALL) && p.j <= kFastDepth / 2));
-  };
+  // the cells this kernel walks with candidates: their lists are staged [position][tick]
+  auto listed = [&](const TickPlan& p) { return p.j > 0 && !(p.flags & (DYN_TP_GENERAL | DYN_TP_SKIP)); };
   int32_t pre[NPRE];
   auto prefetch = [&](int w) {
     if (w >= w1) return;
@@ -633,15 +632,12 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
     const int32_t* cnt_w = s_cnt + (w - w0) * T;
     const double* load_w = s_load + (w - w0) * T;
     const TickPlan pl = s_plan[w - w0];
-    const int j = pl.j;
-    const bool empty = j == 0, skip = (pl.flags & DYN_TP_SKIP) != 0;
-    const bool dense = (pl.flags & DYN_TP_DENSE) != 0;
-    const bool walkable = (pl.flags & DYN_TP_DENSE) || ((pl.flags & DYN_TP_SMALL) && (j <= kFastDepth / 2 || j > kFastDepth));
-    if (!empty && !skip && !walkable) {          // block-uniform: the TBT percentile needs all ticks
-      if (threadIdx.x == 0) a.slow_list[atomicAdd(&a.counters[1], 1u)] = (uint64_t)cell * sa.n_tile + tile;
+    if (pl.flags & DYN_TP_GENERAL) {             // block-uniform
       prefetch(w + 1);
       continue;
     }
+    const int j = pl.j;
+    const bool skip = (pl.flags & DYN_TP_SKIP) != 0, empty = j == 0;
     // two buffers: the lists of the cell before this one may still be read by slower waves
     int32_t* top_w = s_top + buf * (T * kFastDepth);
     if (listed(pl)) {
@@ -657,19 +653,10 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
     prefetch(w + 1);
 
     WalkOut o;
-    bool settled = true;
     if (empty || skip) {
-      o = walk_ticks<0, false, SINGLE, TWO>(st.L, T, 0, load_w, cnt_w, top_w, st.nd, a.tick_s);
-      o.ttft = o.tbt = empty ? 0.0 : __builtin_inf();   // a skipped cell is reported through the status word
-    } else if (j > kFastDepth) {
-      if (dense) o = walk_ticks<0, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
-      else o = walk_ticks<0, true, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
-      // the percentile lies in [x_j * least prefill time, x_j * largest prefill time] of the non-empty ticks
-      const double xj = (double)pl.xj;
-      const double lo = xj * o.pf_min, hi = xj * o.pf_max;
-      o.ttft = lo;
-      settled = __syncthreads_or(lo != hi ? 1 : 0) == 0;
-    } else if (dense) {
+      o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, 0, load_w, cnt_w, top_w, st.nd, a.tick_s);
+      o.ttft = o.tbt = empty ? 0.0 : __builtin_inf();   // a cell that is not evaluated is reported through the status word
+    } else if (pl.flags & DYN_TP_DENSE) {
       if (j <= 4) o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
       else if (j <= 8) o = walk_ticks<8, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
       else o = walk_ticks<kFastDepth, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
@@ -677,32 +664,59 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
       if (j <= 4) o = walk_ticks<4, true, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
       else o = walk_ticks<kFastDepth / 2, true, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
     }
-    if (!settled) {                              // block-uniform
-      if (threadIdx.x == 0) a.slow_list[atomicAdd(&a.counters[1], 1u)] = (uint64_t)cell * sa.n_tile + tile;
-      continue;
-    }
     emit_cell(sa, st, cell, empty, o.ov, o.e, o.ttft, o.tbt);
   }
 }
 
-// The (cell, tile) items the kernel above listed, dealt round-robin to a fixed grid so that runs of
-// heavy cells spread over the chip.  A block of NT threads takes the tile's configurations NT at a time.
-// Per configuration: the ticks' TBTs into an LDS strip and the TBT percentile by taking ticks in
-// descending TBT order until j requests are covered; the bracket of the TTFT percentile; where its ends
-// differ, the ticks' prefill times into the strip and a bisection of the bracket: a probe value v is
-// ranked in every tick's list (binary search on the scaled entries), and either at least j scaled
-// entries are >= v, then the least of them is a new lower end, or fewer, then the largest one below v
-// is a new upper end.  Both ends are values of the lists from then on, so the search ends with the
-// percentile itself.
+// Weighted order statistic over the ticks: the largest value v among those of the ticks with weight > 0 such that the
+// ticks with a value >= v weigh at least `need` together (ticks are taken in descending order of value, equal
+// values together).  strip[q * NT + tid] is this thread's value of tick q.
+__device__ __forceinline__ double weighted_from_top(const double* strip, const int32_t* weight, int T, int NT, int need, int tid) {
+  double prev = __builtin_inf(), val = 0.0;
+  while (need > 0) {
+    double best = -__builtin_inf();
+    int c = 0;
+    for (int q = 0; q < T; ++q) {
+      const int wq = weight[q];
+      if (wq == 0) continue;
+      const double v = strip[q * NT + tid];
+      const bool lt = v < prev;
+      const bool gt = lt && v > best;
+      const bool eq = lt && v == best;
+      c = gt ? wq : (eq ? c + wq : c);
+      best = gt ? v : best;
+    }
+    if (c == 0) break;                       // cannot happen while the weights add up to at least `need`
+    need -= c;
+    prev = best;
+    val = best;
+  }
+  return val;
+}
+
+// The cells the cell kernel left to this kernel, (cell, tile) by (cell, tile), the items dealt round-robin to a
+// fixed grid so that runs of heavy cells spread over the chip.  A block of NT threads takes the tile's
+// configurations NT at a time.  One strip in LDS holds a value per (tick, configuration).  Cells whose
+// non-empty ticks all hold j requests: one pass over the ticks (energy, largest TBT = the TBT percentile,
+// prefill times into the strip).  Other cells: a first pass with the TBTs in the strip, the TBT percentile
+// by taking ticks in descending TBT order until j requests are covered, then the look-ups again for the
+// prefill times.  The TTFT percentile lies in the bracket [x_j * least, x_j * largest prefill time].  If
+// its ends differ but the prefill times are so close that (x_j + 1) * least > x_j * largest, the scaled
+// lengths above x_j lie above the bracket and those below it below: the percentile is x_j times the
+// prefill time that ranks (j - number of lengths above x_j) among the ticks weighted by their number of
+// lengths equal to x_j.  Otherwise the bracket is bisected: a probe value v is ranked in every tick's list
+// (binary search on the scaled entries), and either at least j scaled entries are >= v, then the least
+// of them is a new lower end, or fewer, then the largest one below v is a new upper end.  Both ends are
+// values of the lists from then on, so the search ends with the percentile itself.
 // LDS: [table rows] [load grid] [reciprocal spacings] [SINGLE: grid point per bucket] [strip NT x n_tick]
-//      [per tick: load] [per tick: count] [per tick: entries listed] [per tick: start of its list]
-//      [the cell's lists when they fit] [bucket index]
-template <int NT, bool LDS, bool SINGLE, bool TWO>
-__global__ __launch_bounds__(NT) void tick_general_kernel(TickArgs a) {
+//      [per tick: load] [per tick: count] [per tick: entries listed] [per tick: entries equal to x_j]
+//      [per tick: start of its list, then two words] [the cell's lists when they fit] [bucket index]
+template <bool LDS, bool SINGLE, bool TWO>
+__global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) {
   extern __shared__ double smem[];
   const SpaceArgs& sa = a.s;
   const int n_rho = sa.n_rho, T = a.n_tick;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, NT = blockDim.x;
   double* s_tab = smem;
   double* s_rgp = smem + (LDS ? (size_t)sa.n_slot * DYN_SLOT_STRIDE(n_rho) : 0);
   double* s_rinv = s_rgp + (n_rho + 2);
@@ -711,18 +725,18 @@ __global__ __launch_bounds__(NT) void tick_general_kernel(TickArgs a) {
   double* s_load = s_strip + (size_t)T * NT;                    // [T]
   int32_t* s_cnt = (int32_t*)(s_load + T);                      // [T]
   int32_t* s_len = s_cnt + T;                                   // [T] min(j, count)
-  uint32_t* s_lbase = (uint32_t*)(s_len + T);                   // [T] start of the tick's list; [T]: lists staged in LDS?
-  int32_t* s_lists = (int32_t*)(s_lbase + T + 1);               // [kListCap]
+  int32_t* s_neq = s_len + T;                                   // [T] listed lengths equal to x_j
+  uint32_t* s_lbase = (uint32_t*)(s_neq + T);                   // [T] start of the tick's list; [T]: staged in LDS? [T+1]: lengths above x_j
+  int32_t* s_lists = (int32_t*)(s_lbase + T + 2);               // [kListCap]
   uint16_t* s_js = (uint16_t*)(s_lists + kListCap);             // [n_bucket + 1]
 
-  const uint64_t n_item = a.counters[1];                         // complete: written by the previous kernel
+  const uint64_t n_item = (uint64_t)a.counters[1] * (uint64_t)sa.n_tile;   // complete: written by the cell kernel
   if (blockIdx.x >= n_item) return;                              // block-uniform
   stage_grid<SINGLE>(a, s_rgp, s_thr, s_js);
   int cur_g = -1, cur_tile = -1;
   for (uint64_t item = blockIdx.x; item < n_item; item += gridDim.x) {
-    const uint64_t packed = a.slow_list[item];
-    const size_t cell = (size_t)(packed / (uint64_t)sa.n_tile);
-    const int tile = (int)(packed % (uint64_t)sa.n_tile);
+    const size_t cell = a.slow_list[item / (uint64_t)sa.n_tile];
+    const int tile = (int)(item % (uint64_t)sa.n_tile);
     const int g = (int)(cell % sa.G);
     __syncthreads();                           // the previous item's LDS data has been consumed
     if (LDS && (g != cur_g || tile != cur_tile)) stage_rows(sa, g, tile, s_tab);
@@ -730,8 +744,9 @@ __global__ __launch_bounds__(NT) void tick_general_kernel(TickArgs a) {
     cur_tile = tile;
     const TickPlan pl = a.plan[cell];
     const int j = pl.j;
+    const bool dense = (pl.flags & DYN_TP_DENSE) != 0;
+    const TickRec* rec = a.rec + cell * T;
     if (tid == 0) {                            // where each tick's list is read from
-      const TickRec* rec = a.rec + cell * T;
       uint32_t total = 0;
       for (int q = 0; q < T; ++q) total += (uint32_t)min(rec[q].cnt, j);
       const bool fits = total <= (uint32_t)kListCap;
@@ -745,93 +760,99 @@ __global__ __launch_bounds__(NT) void tick_general_kernel(TickArgs a) {
         at += (uint32_t)min(r.cnt, j);
       }
       s_lbase[T] = fits ? 1u : 0u;
+      s_lbase[T + 1] = 0u;
     }
     __syncthreads();
     const bool staged = s_lbase[T] != 0u;
     if (staged) {
-      const TickRec* rec = a.rec + cell * T;
       for (int q = 0; q < T; ++q) {
         const int32_t* src = a.top + rec[q].off;
         int32_t* dst = s_lists + s_lbase[q];
         for (int i = tid; i < s_len[q]; i += NT) dst[i] = src[i];
       }
+      __syncthreads();
+    }
+    const int32_t* lists = staged ? s_lists : a.top;
+    if (tid < T) {                             // per tick: listed lengths above x_j and equal to it (the list is descending)
+      const int len = s_len[tid];
+      const int32_t* lq = lists + s_lbase[tid];
+      int l = 0, h = len;                      // first entry <= x_j
+      while (l < h) {
+        const int mid = (l + h) >> 1;
+        if (lq[mid] > pl.xj) l = mid + 1; else h = mid;
+      }
+      const int n_gt = l;
+      h = len;                                 // first entry < x_j
+      while (l < h) {
+        const int mid = (l + h) >> 1;
+        if (lq[mid] >= pl.xj) l = mid + 1; else h = mid;
+      }
+      s_neq[tid] = l - n_gt;
+      if (n_gt) atomicAdd(&s_lbase[T + 1], (uint32_t)n_gt);
     }
     __syncthreads();
-    const int32_t* lists = staged ? s_lists : a.top;
     const double xj = (double)pl.xj;
+    const int need_eq = j - (int)s_lbase[T + 1];   // >= 1: fewer than j lengths lie above the j-th largest
 
     for (int sub = 0; sub < sa.tile; sub += NT) {
+      const bool in_tile = sub + (tid & ~(DYN_WAVE - 1)) < sa.tile;   // wave-uniform: a wave past the tile's end stores nothing
       CfgState st;
-      load_config<LDS>(a, g, tile * sa.tile + sub + tid, s_tab, s_rgp, s_rinv, s_thr, s_js, &st);
-      // the ticks once: energy in time order, TBT of every tick kept, range of the prefill times
-      double e = 0.0, pf_min = __builtin_inf(), pf_max = -__builtin_inf();
+      load_config<LDS>(a, g, tile * sa.tile + (in_tile ? sub + tid : 0), s_tab, s_rgp, s_rinv, s_thr, s_js, &st);
+      double e = 0.0, pf_min = __builtin_inf(), pf_max = -__builtin_inf(), tb_max = -__builtin_inf();
       bool ov = false;
-      for (int q = 0; q < T; ++q) {
+      for (int q = 0; q < T; ++q) {            // energy in time order; the strip takes the prefill times, or first the TBTs
         double pf, tb, pw;
         ov = table_lookup<SINGLE, TWO>(st.L, s_load[q], &pf, &tb, &pw) | ov;
         e += (st.nd * pw) * a.tick_s;
-        s_strip[q * NT + tid] = tb;
-        if (s_cnt[q] > 0) { pf_min = min_num(pf_min, pf); pf_max = max_num(pf_max, pf); }
+        s_strip[q * NT + tid] = dense ? pf : tb;
+        if (s_cnt[q] > 0) {
+          pf_min = min_num(pf_min, pf);
+          pf_max = max_num(pf_max, pf);
+          tb_max = max_num(tb_max, tb);
+        }
       }
-      // TBT percentile: ticks in descending TBT order (equal values together) until j requests are covered
-      double p_tbt = 0.0;
-      {
-        int need = j;
-        double prev = __builtin_inf();
-        while (need > 0) {
-          double best = -__builtin_inf();
-          int c = 0;
-          for (int q = 0; q < T; ++q) {
-            const int cq = s_cnt[q];
-            if (cq == 0) continue;
-            const double v = s_strip[q * NT + tid];
-            const bool lt = v < prev;
-            const bool gt = lt && v > best;
-            const bool eq = lt && v == best;
-            c = gt ? cq : (eq ? c + cq : c);
-            best = gt ? v : best;
-          }
-          if (c == 0) break;                   // cannot happen: the cell holds at least j requests
-          need -= c;
-          prev = best;
-          p_tbt = best;
+      double p_tbt = tb_max;
+      if (!dense) {                            // block-uniform
+        p_tbt = weighted_from_top(s_strip, s_cnt, T, NT, j, tid);
+        for (int q = 0; q < T; ++q) {
+          double pf, tb, pw;
+          table_lookup<SINGLE, TWO>(st.L, s_load[q], &pf, &tb, &pw);
+          s_strip[q * NT + tid] = pf;
         }
       }
       // TTFT percentile
       double lo = xj * pf_min, hi = xj * pf_max;
       bool open = lo != hi;
-      if (__syncthreads_or(open ? 1 : 0)) {
-        for (int q = 0; q < T; ++q) {          // the same look-ups again: this time the prefill times are kept
-          double pf, tb, pw;
-          table_lookup<SINGLE, TWO>(st.L, s_load[q], &pf, &tb, &pw);
-          s_strip[q * NT + tid] = pf;
-        }
-        while (open) {
-          double v = lo + (hi - lo) * 0.5;
-          if (!(v > lo)) v = hi;
-          int n_ge = 0;
-          double a_min = __builtin_inf(), b_max = -__builtin_inf();
-          for (int q = 0; q < T; ++q) {
-            const int len = s_len[q];
-            if (len == 0) continue;
-            const double pf = s_strip[q * NT + tid];
-            const int32_t* lq = lists + s_lbase[q];
-            int l = 0, h = len;                // entries [0, l) are >= v scaled, entries [h, len) are below
-            while (l < h) {
-              const int mid = (l + h) >> 1;
-              const bool ge = (double)lq[mid] * pf >= v;
-              l = ge ? mid + 1 : l;
-              h = ge ? h : mid;
-            }
-            n_ge += l;
-            if (l > 0) a_min = min_num(a_min, (double)lq[l - 1] * pf);
-            if (l < len) b_max = max_num(b_max, (double)lq[l] * pf);
-          }
-          if (n_ge >= j) lo = a_min; else hi = b_max;
-          open = lo < hi;                      // also ends a search that lost its bracket (never with consistent lists)
-        }
+      if (open && xj * pf_max < (xj + 0.5) * pf_min) {
+        // only lengths equal to x_j scale into the bracket: rank the ticks' prefill times by those
+        lo = hi = xj * weighted_from_top(s_strip, s_neq, T, NT, need_eq, tid);
+        open = false;
       }
-      emit_cell(sa, st, cell, false, ov, e, lo, p_tbt);
+      while (open) {
+        double v = lo + (hi - lo) * 0.5;
+        if (!(v > lo)) v = hi;
+        int n_ge = 0;
+        double a_min = __builtin_inf(), b_max = -__builtin_inf();
+        for (int q = 0; q < T; ++q) {
+          const int len = s_len[q];
+          if (len == 0) continue;
+          const double pf = s_strip[q * NT + tid];
+          const int32_t* lq = lists + s_lbase[q];
+          int l = 0, h = len;                  // entries [0, l) are >= v scaled, entries [h, len) are below
+          while (l < h) {
+            const int mid = (l + h) >> 1;
+            const bool ge = (double)lq[mid] * pf >= v;
+            l = ge ? mid + 1 : l;
+            h = ge ? h : mid;
+          }
+          n_ge += l;
+          if (l > 0) a_min = min_num(a_min, (double)lq[l - 1] * pf);
+          if (l < len) b_max = max_num(b_max, (double)lq[l] * pf);
+        }
+        if (n_ge >= j) lo = a_min; else hi = b_max;
+        open = lo < hi;                        // also ends a search that lost its bracket (never with consistent lists)
+      }
+      if (in_tile) emit_cell(sa, st, cell, false, ov, e, lo, p_tbt);
       __syncthreads();                         // the strip is rewritten by the next group of configurations
     }
   }
@@ -844,13 +865,17 @@ size_t tick_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t n_tick, int32_t wi
 }
 size_t general_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t n_tick, int nt, bool single) {
   return (size_t)(2 * n_rho + 3) * sizeof(double) + (single ? ((size_t)n_bucket + 1) * sizeof(double) : 0) +
-         (size_t)n_tick * nt * sizeof(double) + (size_t)n_tick * (sizeof(double) + 3 * sizeof(int32_t)) + sizeof(uint32_t) +
-         (size_t)kListCap * sizeof(int32_t) + ((size_t)n_bucket + 1) * sizeof(uint16_t) + 8;
+         (size_t)n_tick * nt * sizeof(double) + (size_t)n_tick * (sizeof(double) + 4 * sizeof(int32_t)) +
+         2 * sizeof(uint32_t) + (size_t)kListCap * sizeof(int32_t) + ((size_t)n_bucket + 1) * sizeof(uint16_t) + 8;
 }
-// configurations a block of the general kernel takes at a time: the strip holds one double per (tick, configuration)
-int general_threads(int32_t n_tick) { return n_tick <= 16 ? 256 : (n_tick <= 32 ? 128 : 64); }
-static_assert(64 * DYN_TICK_MAX * sizeof(double) <= kStripBytes && 128 * 32 * sizeof(double) <= kStripBytes &&
-                  256 * 16 * sizeof(double) <= kStripBytes,
+// Threads of a block of the general kernel: the tile's width, less where the strip (one double per tick and
+// thread) would pass 32 KB.
+int general_threads(const TickArgs& a) {
+  const int cap = a.n_tick <= 16 ? 256 : (a.n_tick <= 32 ? 128 : 64);
+  return a.s.tile < cap ? a.s.tile : cap;
+}
+static_assert(256 * 16 * sizeof(double) <= kStripBytes && 128 * 32 * sizeof(double) <= kStripBytes &&
+                  64 * DYN_TICK_MAX * sizeof(double) <= kStripBytes,
               "the strip of the general kernel");
 
 template <bool LDS, bool SINGLE, bool TWO>
@@ -862,17 +887,7 @@ void launch_space(const TickArgs& a, dim3 grid, dim3 block, size_t lds, hipStrea
 template <bool LDS, bool SINGLE, bool TWO>
 void launch_general(const TickArgs& a, size_t lds, hipStream_t s) {
   DynTimed timed(DYN_K_TICK_MERGE, s);
-  const int nt = general_threads(a.n_tick);
-  // a tile narrower than the block (64, 128 or 192 configurations) is walked by as many threads as it is wide
-  if (nt == 256 && a.s.tile % 256 == 0) hipLaunchKernelGGL((tick_general_kernel<256, LDS, SINGLE, TWO>), dim3(kGeneralBlocks), dim3(256), lds, s, a);
-  else if (nt >= 128 && a.s.tile % 128 == 0) hipLaunchKernelGGL((tick_general_kernel<128, LDS, SINGLE, TWO>), dim3(kGeneralBlocks), dim3(128), lds, s, a);
-  else hipLaunchKernelGGL((tick_general_kernel<64, LDS, SINGLE, TWO>), dim3(kGeneralBlocks), dim3(64), lds, s, a);
-}
-int general_block(const TickArgs& a) {
-  const int nt = general_threads(a.n_tick);
-  if (nt == 256 && a.s.tile % 256 == 0) return 256;
-  if (nt >= 128 && a.s.tile % 128 == 0) return 128;
-  return 64;
+  hipLaunchKernelGGL((tick_general_kernel<LDS, SINGLE, TWO>), dim3(kGeneralBlocks), dim3(general_threads(a)), lds, s, a);
 }
 
 template <typename F>
@@ -935,7 +950,7 @@ hipError_t dyn_launch_tick_space(const TickArgs& a_in, hipStream_t s) {
     if (e != hipSuccess) return e;
   }
   {
-    const int nt = general_block(a);
+    const int nt = general_threads(a);
     bool single = a.single_point;
     size_t tail = general_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, nt, single);
     if (single && tail + tab > DYN_LDS_BUDGET) {
