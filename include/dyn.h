@@ -18,14 +18,20 @@
  *     library never frees them.  Only dyn_profile_load allocates device memory (released by
  *     dyn_profile_free).
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the default
- *     stream) and the call returns after enqueueing.  The status covers argument checks
- *     and launch errors.  Conditions that depend on device data (an offset array that is
+ *     stream) and the call returns after enqueueing; no entry point waits for the device
+ *     except dyn_profile_load and dyn_workspace_status, and any call whose candidate list,
+ *     objective or small host tables (layouts, transition table, controller lists) differ
+ *     from the copies the profile handle keeps: those are uploaded after waiting for the
+ *     stream.  The status covers argument checks and launch errors.  Conditions that depend on device data (an offset array that is
  *     not monotone, a timestamp outside the windows) cannot be seen by the host: the
  *     kernels bound-check them, skip the offending item and raise a bit in the status
  *     word at the start of the workspace, which dyn_workspace_status reads back.
  *   - Cells are numbered cell = w * G + g with w the window and g the class,
  *     g = (model * n_in_bin + in_bin) * n_out_bin + out_bin.
- *   - All floating point is IEEE binary64 without contraction.
+ *   - All floating point is IEEE binary64 without contraction.  Window and tick lengths,
+ *     max_load_tps and the spacings of the load grid must lie in [1e-100, 1e100]
+ *     (DYN_E_RANGE / DYN_E_NOTFINITE otherwise): inside that range every division of the
+ *     method is reproduced exactly by the kernels' reciprocal-based form.
  */
 #ifndef DYN_H_
 #define DYN_H_
@@ -70,7 +76,7 @@ typedef struct {
   const double* prefill_ms_per_tok; /* [G][n_tp][n_f][n_rho] finite, >= 0                  */
   const double* tbt_ms;             /* [G][n_tp][n_f][n_rho] finite, >= 0                  */
   const double* power_w;            /* [G][n_tp][n_f][n_rho] watts of one whole instance   */
-  const double* max_load_tps;       /* [G][n_tp][n_f] finite, > 0                          */
+  const double* max_load_tps;       /* [G][n_tp][n_f] within [1e-100, 1e100]               */
 } dyn_profile_desc;
 
 /* Opaque; owns the device copies of the tables and of the candidate list and objective it
@@ -108,6 +114,9 @@ size_t dyn_trace_ingest_workspace(int64_t n_req, int32_t n_window, int32_t n_cla
  *   in_sorted, out_sorted       : DEVICE [n_req] outputs; must not alias the inputs.
  *   cell_off                    : DEVICE [n_window*G + 1] output, cell_off[last] = n_req.
  *   workspace                   : DEVICE, 256-byte aligned, >= dyn_trace_ingest_workspace.
+ * A trace already in window order is moved window by window, any other by a general stable
+ * sort; the route is picked on the device (the call does not wait for it), both give the same
+ * bytes.  The edge lists travel in kernel arguments, so the HOST arrays are free on return.
  * A request whose timestamp falls outside [0, n_window*window_s) or whose model index is
  * outside [0, n_model) raises DYN_WS_BAD_REQUEST in the workspace status and is filed
  * under the nearest valid window / model 0, so that offsets stay consistent.
@@ -122,7 +131,7 @@ int dyn_trace_ingest(const double* t_s, const int32_t* in_tok, const int32_t* ou
 typedef struct {
   int64_t n_req;
   int32_t n_window;
-  double window_s;        /* > 0, seconds                                               */
+  double window_s;        /* seconds, within [1e-100, 1e100]                            */
   const int32_t* in_tok;  /* [n_req] sorted by cell                                     */
   const int32_t* out_tok; /* [n_req]                                                    */
   const int64_t* cell_off; /* [n_window*G + 1] non-decreasing, [0]==0, last == n_req    */
@@ -322,6 +331,8 @@ int dyn_eval_select_mixed(dyn_profile* profile, const dyn_trace_view* trace, con
  * finite and >= 0.  Limits: up to 64 layouts any K the profile handle takes; beyond that
  * n_layout <= 255, K <= 2048 and the per-class state (K totals, the transition table) must
  * fit in LDS: (K + n_layout^2) * 8 bytes + small <= 64 KB, else DYN_E_SHAPE.
+ * `layout` and `transition_j` are kept in the profile handle like the candidate list: a call
+ * with the same tables as the one before uploads nothing and does not wait for the stream.
  * Workspace DEVICE, 256-byte aligned, dyn_select_path_workspace bytes.                    */
 typedef struct {
   int32_t n_layout;
@@ -415,7 +426,9 @@ int dyn_account(dyn_profile* profile, const int32_t* sel, const double* window_e
  * the same requests sorted by tick (n_window * n_tick windows of tick_s seconds), both as
  * dyn_trace_ingest returns them.  lay_n / lay_tp_index HOST [n_layout].  Outputs DEVICE.
  * objective->gpu_budget and idle_cost_weight are not used.  Profiles of more than 64 TP
- * degrees or 4096 classes are refused (DYN_E_SHAPE).                                       */
+ * degrees or 4096 classes are refused (DYN_E_SHAPE), as are more than 65536 layouts (255 with
+ * a transition table).  The layout list and the table are kept in the profile handle: a call
+ * with the same ones as the call before uploads nothing and does not wait for the stream.  */
 typedef struct {
   int32_t epoch_windows;
   int32_t tp_ref_index, f_ref_index;

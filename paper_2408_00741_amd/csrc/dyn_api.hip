@@ -29,11 +29,11 @@ bool hip_ok(hipError_t e, const char* what) {
   return false;
 }
 
-__global__ void init_word_header_kernel(WsHeader* h) {   // header regions are 256 bytes
+__global__ void init_word_header_kernel(WsHeader* h, uint32_t order_word) {   // header regions are 256 bytes
   h->status = 0u;
   h->kind = DYN_WS_KIND_WORD;
   h->cells = 0;
-  ((uint32_t*)h)[DYN_WS_HEADER_ORDER_WORD] = 0u;         // ingestion: "not in window order" flag
+  ((uint32_t*)h)[DYN_WS_HEADER_ORDER_WORD] = order_word;   // ingestion: "not in window order" flag
 }
 
 // Lengths of windows and ticks, capacities and grid spacings are kept inside this range so that the
@@ -56,7 +56,8 @@ hipError_t dev_alloc(T** p, size_t count) {
 
 void free_profile_device(dyn_profile* p) {
   void* ptrs[] = {p->d_tab, p->d_ml, p->d_pw0, p->d_gridpack, p->d_jstart, p->d_tstart, p->d_thr, p->d_cfg,
-                  p->d_tile_rows, p->d_slo_ttft, p->d_slo_tbt, p->d_budget};
+                  p->d_tile_rows, p->d_slo_ttft, p->d_slo_tbt, p->d_budget, p->d_path_layout, p->d_path_order,
+                  p->d_path_seg, p->d_path_trans, p->d_hier_trans, p->d_lay_n, p->d_lay_tp, p->d_tp, p->d_ident};
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
 }
@@ -173,6 +174,18 @@ int prepare_configs(dyn_profile* p, const dyn_config* cfg, int32_t K, hipStream_
   p->any_two_rows = false;
   for (int k = 0; k < K; ++k) p->any_two_rows = p->any_two_rows || dc[k].u != 0.0;
   p->cfg_host.assign(cfg, cfg + K);
+  return DYN_OK;
+}
+
+// Uploads `n` values to a device array of the handle unless the handle already holds the same values there.  A
+// changed table is uploaded after waiting for the stream: work enqueued on it may still read the old one.
+template <typename T>
+int cache_upload(std::vector<T>& host, T* dev, const T* src, size_t n, hipStream_t s, const char* what) {
+  if (host.size() == n && (n == 0 || memcmp(host.data(), src, n * sizeof(T)) == 0)) return DYN_OK;
+  if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) return DYN_E_DEVICE;
+  host.clear();
+  if (n && !hip_ok(hipMemcpy(dev, src, n * sizeof(T), hipMemcpyHostToDevice), what)) return DYN_E_DEVICE;
+  host.assign(src, src + n);
   return DYN_OK;
 }
 
@@ -455,6 +468,8 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   p->d_tab = p->d_ml = p->d_pw0 = p->d_gridpack = nullptr;
   p->d_jstart = nullptr; p->d_tstart = nullptr; p->d_thr = nullptr; p->d_cfg = nullptr; p->d_tile_rows = nullptr;
   p->d_slo_ttft = p->d_slo_tbt = nullptr; p->d_budget = nullptr;
+  p->d_path_layout = p->d_path_order = p->d_path_seg = p->d_lay_n = p->d_lay_tp = p->d_tp = p->d_ident = nullptr;
+  p->d_path_trans = p->d_hier_trans = nullptr;
   p->obj_valid = false; p->tile = p->n_tile = p->n_slot = 0; p->any_two_rows = false;
   hipStream_t s = (hipStream_t)hip_stream;
 
@@ -514,7 +529,15 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
             hip_ok(dev_alloc(&p->d_cfg, DYN_MAX_CONFIGS), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_tile_rows, 2 * DYN_MAX_CONFIGS + 1024), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_slo_ttft, p->G), "hipMalloc") && hip_ok(dev_alloc(&p->d_slo_tbt, p->G), "hipMalloc") &&
-            hip_ok(dev_alloc(&p->d_budget, p->G), "hipMalloc");
+            hip_ok(dev_alloc(&p->d_budget, p->G), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_path_layout, DYN_MAX_CONFIGS), "hipMalloc") && hip_ok(dev_alloc(&p->d_path_order, DYN_MAX_CONFIGS), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_path_seg, DYN_MAX_LAYOUTS + 1), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_path_trans, DYN_MAX_LAYOUTS * DYN_MAX_LAYOUTS), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_hier_trans, DYN_MAX_LAYOUTS * DYN_MAX_LAYOUTS), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_lay_n, DYN_MAX_CONFIGS), "hipMalloc") && hip_ok(dev_alloc(&p->d_lay_tp, DYN_MAX_CONFIGS), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_tp, p->n_tp), "hipMalloc") && hip_ok(dev_alloc(&p->d_ident, DYN_MAX_CONFIGS + 1), "hipMalloc");
+  std::vector<int32_t> ident(DYN_MAX_CONFIGS + 1);
+  std::iota(ident.begin(), ident.end(), 0);
   ok = ok && hip_ok(hipMemcpyAsync(p->d_tab, packed.data(), 3 * n_tab * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_ml, d->max_load_tps, n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_pw0, pw0.data(), n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
@@ -522,6 +545,8 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
        hip_ok(hipMemcpyAsync(p->d_jstart, js.data(), js.size() * 4, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_tstart, tstart.data(), tstart.size() * 4, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_thr, thr.data(), thr.size() * 8, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_tp, p->tp.data(), p->tp.size() * 4, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_ident, ident.data(), ident.size() * 4, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize");
   if (!ok) {
     free_profile_device(p);
@@ -591,17 +616,12 @@ int dyn_trace_ingest(const double* t_s, const int32_t* in_tok, const int32_t* ou
   int bits = 0;
   while (((int64_t)1 << bits) < cells) ++bits;
   a.key_bits = bits;
-  // the edge lists are a few integers: a blocking copy keeps the host arrays free on return
-  if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) return DYN_E_DEVICE;
-  {   // both lists in one copy: in_edge and out_edge are neighbours in the workspace
-    const size_t n_in = (size_t)e->n_model * (e->n_in_bin - 1), n_out = (size_t)e->n_model * (e->n_out_bin - 1);
-    std::vector<int32_t> stage((w.out_edge - w.in_edge) / 4 + n_out, 0);
-    if (n_in) memcpy(stage.data(), e->in_edge, n_in * 4);
-    if (n_out) memcpy(stage.data() + (w.out_edge - w.in_edge) / 4, e->out_edge, n_out * 4);
-    if (!hip_ok(hipMemcpy(base + w.in_edge, stage.data(), stage.size() * 4, hipMemcpyHostToDevice), "copy edges")) return DYN_E_DEVICE;
-  }
-  hipLaunchKernelGGL(init_word_header_kernel, dim3(1), dim3(1), 0, s, (WsHeader*)a.status);
-  if (!hip_ok(hipGetLastError(), "launch")) return DYN_E_DEVICE;
+  // the workspace header (status 0, order word = "general sort forced") and the edge lists, which travel in a kernel's
+  // arguments: the host arrays are free on return and nothing waits for the stream
+  if (!hip_ok(dyn_launch_edges(e->in_edge, (size_t)e->n_model * (e->n_in_bin - 1), e->out_edge, (size_t)e->n_model * (e->n_out_bin - 1),
+                               (int32_t*)(base + w.in_edge), (int32_t*)(base + w.out_edge), (WsHeader*)a.status, a.force_sort ? 1u : 0u, s),
+              "edge launch"))
+    return DYN_E_DEVICE;
   if (!hip_ok(dyn_launch_ingest(a, s), "ingest launch")) return DYN_E_DEVICE;
   return DYN_OK;
 }
@@ -885,7 +905,7 @@ int dyn_select_path(dyn_profile* p, const dyn_space* space, const dyn_config* cf
   if (o->idle_cost_weight < 0.0) { dyn_set_error("idle_cost_weight must be >= 0"); return DYN_E_RANGE; }
   if ((int64_t)n_window * p->G >= ((int64_t)1 << 30)) { dyn_set_error("n_window * classes must stay below 2^30"); return DYN_E_SHAPE; }
   if (K < 1 || K > DYN_MAX_CONFIGS) { dyn_set_error("K=%d outside [1, %d]", K, DYN_MAX_CONFIGS); return DYN_E_SHAPE; }
-  if (tr->n_layout < 1) { dyn_set_error("n_layout < 1"); return DYN_E_SHAPE; }
+  if (tr->n_layout < 1 || tr->n_layout > DYN_MAX_LAYOUTS) { dyn_set_error("n_layout=%d outside [1, %d]", tr->n_layout, DYN_MAX_LAYOUTS); return DYN_E_SHAPE; }
   if (!dyn_path_fits(K, tr->n_layout)) {
     dyn_set_error("K=%d, n_layout=%d: beyond 64 layouts the per-class state (K <= %d candidates, n_layout^2 overheads) must fit in LDS", K, tr->n_layout, DYN_PATH_MAX_CONFIGS);
     return DYN_E_SHAPE;
@@ -914,19 +934,18 @@ int dyn_select_path(dyn_profile* p, const dyn_space* space, const dyn_config* cf
     std::vector<int32_t> fill(seg.begin(), seg.end() - 1);
     for (int k = 0; k < K; ++k) order[fill[tr->layout[k]]++] = k;
   }
-  // the host tables are small; they are copied before the call returns
-  if (!hip_ok(hipMemcpyAsync(base + w.layout, tr->layout, (size_t)K * sizeof(int32_t), hipMemcpyHostToDevice, s), "copy layout") ||
-      !hip_ok(hipMemcpyAsync(base + w.order, order.data(), (size_t)K * sizeof(int32_t), hipMemcpyHostToDevice, s), "copy order") ||
-      !hip_ok(hipMemcpyAsync(base + w.seg, seg.data(), seg.size() * sizeof(int32_t), hipMemcpyHostToDevice, s), "copy segments") ||
-      !hip_ok(hipMemcpyAsync(base + w.transition, tr->transition_j, (size_t)tr->n_layout * tr->n_layout * sizeof(double),
-                             hipMemcpyHostToDevice, s), "copy transitions") ||
-      !hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize"))
-    return DYN_E_DEVICE;
+  // the host tables are cached in the profile handle like the candidate list: nothing is uploaded (and nothing waits)
+  // while they stay the same
+  if ((rc = cache_upload(p->path_layout_host, p->d_path_layout, tr->layout, (size_t)K, s, "copy layout")) != DYN_OK ||
+      (rc = cache_upload(p->path_order_host, p->d_path_order, order.data(), (size_t)K, s, "copy order")) != DYN_OK ||
+      (rc = cache_upload(p->path_seg_host, p->d_path_seg, seg.data(), seg.size(), s, "copy segments")) != DYN_OK ||
+      (rc = cache_upload(p->path_trans_host, p->d_path_trans, tr->transition_j, (size_t)tr->n_layout * tr->n_layout, s, "copy transitions")) != DYN_OK)
+    return rc;
   PathArgs a;
   a.energy = space->energy_j; a.flags = space->flags; a.cfg = p->d_cfg; a.K = K; a.pw0 = p->d_pw0;
   a.G = p->G; a.n_tp_f = p->n_tp * p->n_f; a.n_window = n_window; a.window_s = window_s; a.idle_w = o->idle_cost_weight;
-  a.n_layout = tr->n_layout; a.layout = (const int32_t*)(base + w.layout); a.transition = (const double*)(base + w.transition);
-  a.order = (const int32_t*)(base + w.order); a.seg_start = (const int32_t*)(base + w.seg);
+  a.n_layout = tr->n_layout; a.layout = p->d_path_layout; a.transition = p->d_path_trans;
+  a.order = p->d_path_order; a.seg_start = p->d_path_seg;
   a.pred = (int32_t*)(base + w.pred); a.kend = (int32_t*)(base + w.kend);
   a.min_cost = (double*)(base + w.min_cost); a.min_k = (int32_t*)(base + w.min_k); a.exits = (int32_t*)(base + w.exits);
   a.sel = out->sel; a.sel_energy = out->sel_energy_j; a.path_cost = out->path_cost;
@@ -958,7 +977,7 @@ int dyn_account(dyn_profile* p, const int32_t* sel, const double* window_energy_
   hipStream_t s = (hipStream_t)hip_stream;
   if ((rc = prepare_configs(p, cfg, K, s)) != DYN_OK) return rc;
   char* base = (char*)workspace;
-  hipLaunchKernelGGL(init_word_header_kernel, dim3(1), dim3(1), 0, s, (WsHeader*)base);
+  hipLaunchKernelGGL(init_word_header_kernel, dim3(1), dim3(1), 0, s, (WsHeader*)base, 0u);
   if (!hip_ok(hipGetLastError(), "launch")) return DYN_E_DEVICE;
   AccountArgs a;
   a.sel = sel; a.window_energy = window_energy_j; a.carbon = r->carbon_g_per_kwh;
@@ -1022,6 +1041,7 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
   if (!tc->cell_off || !tf->cell_off || (tc->n_req > 0 && (!tc->in_tok || !tc->out_tok || !tf->in_tok || !tf->out_tok))) { dyn_set_error("a trace array is NULL"); return DYN_E_NULL; }
   if (!in_scale(tf->window_s)) { dyn_set_error("tick length must lie in [1e-100, 1e100]"); return DYN_E_RANGE; }
   if (c->epoch_windows < 1 || c->gpus_per_node < 1 || c->n_layout < 1) { dyn_set_error("epoch_windows, gpus_per_node or n_layout < 1"); return DYN_E_SHAPE; }
+  if (c->n_layout > DYN_MAX_CONFIGS || (c->transition_j && c->n_layout > DYN_MAX_LAYOUTS)) { dyn_set_error("n_layout=%d: at most %d layouts, %d with a transition table", c->n_layout, DYN_MAX_CONFIGS, DYN_MAX_LAYOUTS); return DYN_E_SHAPE; }
   if (p->n_tp > 64 || p->G > 4096) { dyn_set_error("dyn_hierarchy takes profiles of up to 64 TP degrees and 4096 classes"); return DYN_E_SHAPE; }
   if (c->tp_ref_index < 0 || c->tp_ref_index >= p->n_tp || c->f_ref_index < 0 || c->f_ref_index >= p->n_f) { dyn_set_error("reference configuration outside the profile"); return DYN_E_RANGE; }
   for (int l = 0; l < c->n_layout; ++l)
@@ -1049,21 +1069,13 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
   char* base = (char*)workspace;
   char* fb = base + w.fine_base;
   char* pb = base + w.path;
-  if (c->transition_j) {        // one candidate per layout: the sorted order is the identity
-    std::vector<int32_t> ident(c->n_layout + 1);
-    for (int l = 0; l <= c->n_layout; ++l) ident[l] = l;
-    if (!hip_ok(hipMemcpyAsync(pb + pw.layout, ident.data(), (size_t)c->n_layout * 4, hipMemcpyHostToDevice, s), "copy") ||
-        !hip_ok(hipMemcpyAsync(pb + pw.order, ident.data(), (size_t)c->n_layout * 4, hipMemcpyHostToDevice, s), "copy") ||
-        !hip_ok(hipMemcpyAsync(pb + pw.seg, ident.data(), ((size_t)c->n_layout + 1) * 4, hipMemcpyHostToDevice, s), "copy") ||
-        !hip_ok(hipMemcpyAsync(pb + pw.transition, c->transition_j, (size_t)c->n_layout * c->n_layout * 8, hipMemcpyHostToDevice, s), "copy") ||
-        !hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize"))   // `ident` lives until here
-      return DYN_E_DEVICE;
-  }
-  if (!hip_ok(hipMemcpyAsync(base + w.tp, p->tp.data(), (size_t)p->n_tp * 4, hipMemcpyHostToDevice, s), "copy") ||
-      !hip_ok(hipMemcpyAsync(base + w.lay_n, c->lay_n, (size_t)c->n_layout * 4, hipMemcpyHostToDevice, s), "copy") ||
-      !hip_ok(hipMemcpyAsync(base + w.lay_tp, c->lay_tp_index, (size_t)c->n_layout * 4, hipMemcpyHostToDevice, s), "copy") ||
-      !hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize"))
-    return DYN_E_DEVICE;
+  // the controllers' small tables are cached in the profile handle (uploaded again only when they change)
+  if (c->transition_j &&
+      (rc = cache_upload(p->hier_trans_host, p->d_hier_trans, c->transition_j, (size_t)c->n_layout * c->n_layout, s, "copy transitions")) != DYN_OK)
+    return rc;
+  if ((rc = cache_upload(p->lay_n_host, p->d_lay_n, c->lay_n, (size_t)c->n_layout, s, "copy layouts")) != DYN_OK ||
+      (rc = cache_upload(p->lay_tp_host, p->d_lay_tp, c->lay_tp_index, (size_t)c->n_layout, s, "copy layouts")) != DYN_OK)
+    return rc;
   const double window_s = (double)n_tick * tf->window_s;
   // tick level first: the window-level aggregation then (re)writes the workspace's header
   if (!hip_ok(dyn_launch_cell_aggregate(tf->in_tok, tf->out_tok, tf->cell_off, tf->n_req, fine_cells, tf->window_s, o->pct_num, o->pct_den,
@@ -1075,14 +1087,14 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
     return DYN_E_DEVICE;
   HierArgs a;
   a.tab = p->d_tab; a.ml = p->d_ml; a.gridpack = p->d_gridpack; a.jstart = p->d_jstart; a.tstart = p->d_tstart; a.thr = p->d_thr; a.n_bucket = p->n_bucket; a.bucket_scale = p->bucket_scale;
-  a.G = p->G; a.n_tp = p->n_tp; a.n_f = p->n_f; a.n_rho = p->n_rho; a.tp = (const int32_t*)(base + w.tp);
+  a.G = p->G; a.n_tp = p->n_tp; a.n_f = p->n_f; a.n_rho = p->n_rho; a.tp = p->d_tp;
   a.slo_ttft = p->d_slo_ttft; a.slo_tbt = p->d_slo_tbt;
   a.rec_c = (const CellRec*)(base + w.coarse.rec); a.rec_f = (const CellRec*)(fb + w.fine.rec);
   a.cstat_c = (const uint8_t*)(base + w.coarse.cstat); a.cstat_f = (const uint8_t*)(fb + w.fine.cstat); a.status = &((WsHeader*)(base + w.coarse.header))->status;
   a.n_window = tc->n_window; a.n_tick = n_tick; a.tick_s = tf->window_s; a.window_s = window_s;
   a.epoch_windows = c->epoch_windows; a.n_epoch = (tc->n_window + c->epoch_windows - 1) / c->epoch_windows;
   a.tp_ref = c->tp_ref_index; a.f_ref = c->f_ref_index; a.gpus_per_node = c->gpus_per_node;
-  a.n_layout = c->n_layout; a.lay_n = (const int32_t*)(base + w.lay_n); a.lay_tp = (const int32_t*)(base + w.lay_tp);
+  a.n_layout = c->n_layout; a.lay_n = p->d_lay_n; a.lay_tp = p->d_lay_tp;
   a.nodes = out->nodes; a.layout_sel = out->layout_sel; a.f_sel = out->f_sel; a.energy = out->energy_j; a.violations = out->violations;
   a.win_energy = out->window_energy_j; a.win_inf = out->window_infeasible;
   a.lay_energy = c->transition_j ? (double*)(base + w.lay_energy) : nullptr;
@@ -1099,8 +1111,9 @@ int dyn_hierarchy(dyn_profile* p, const dyn_trace_view* tc, const dyn_trace_view
     PathArgs pa;
     pa.energy = a.lay_energy; pa.flags = a.lay_flags; pa.cfg = nullptr; pa.K = c->n_layout; pa.pw0 = p->d_pw0;
     pa.G = p->G; pa.n_tp_f = p->n_tp * p->n_f; pa.n_window = tc->n_window; pa.window_s = window_s; pa.idle_w = 0.0;
-    pa.n_layout = c->n_layout; pa.layout = (const int32_t*)(pb + pw.layout); pa.transition = (const double*)(pb + pw.transition);
-    pa.order = (const int32_t*)(pb + pw.order); pa.seg_start = (const int32_t*)(pb + pw.seg);
+    // one candidate per layout: the layout map, the sorted order and the segment starts are all the identity
+    pa.n_layout = c->n_layout; pa.layout = p->d_ident; pa.transition = p->d_hier_trans;
+    pa.order = p->d_ident; pa.seg_start = p->d_ident;
     pa.pred = (int32_t*)(pb + pw.pred); pa.kend = (int32_t*)(pb + pw.kend);
     pa.min_cost = (double*)(pb + pw.min_cost); pa.min_k = (int32_t*)(pb + pw.min_k); pa.exits = (int32_t*)(pb + pw.exits);
     pa.sel = out->layout_sel; pa.sel_energy = (double*)(base + w.sel_energy); pa.path_cost = out->path_cost;

@@ -78,7 +78,21 @@ struct dyn_profile {
   double* d_slo_ttft;  // [G]
   double* d_slo_tbt;   // [G]
   int32_t* d_budget;   // [G]
+  // plan: the small host tables of dyn_select_path and dyn_hierarchy, cached like the candidate list (a table that
+  // equals the handle's copy is not uploaded again)
+  std::vector<int32_t> path_layout_host, path_order_host, path_seg_host, lay_n_host, lay_tp_host;
+  std::vector<double> path_trans_host, hier_trans_host;
+  int32_t* d_path_layout;  // [DYN_MAX_CONFIGS]
+  int32_t* d_path_order;   // [DYN_MAX_CONFIGS]
+  int32_t* d_path_seg;     // [DYN_MAX_LAYOUTS + 1]
+  double* d_path_trans;    // [DYN_MAX_LAYOUTS^2]
+  double* d_hier_trans;    // [DYN_MAX_LAYOUTS^2]
+  int32_t* d_lay_n;        // [DYN_MAX_CONFIGS]
+  int32_t* d_lay_tp;       // [DYN_MAX_CONFIGS]
+  int32_t* d_tp;           // [n_tp]
+  int32_t* d_ident;        // [DYN_MAX_CONFIGS + 1] 0, 1, 2, ...
 };
+#define DYN_MAX_LAYOUTS 255   // layouts a transition table can hold
 
 // Per-(cell, wave of configurations) partial result of the fused selection.
 struct SelPart {
@@ -149,10 +163,13 @@ struct IngestArgs {
   uint32_t* status; uint32_t* key_a; uint32_t* key_b; int32_t* in_tmp; int32_t* out_tmp;
   uint32_t* block_hist; int64_t n_block; int32_t key_bits;
   uint32_t* unsorted;      // word in the workspace header: 0 while every request's window is >= the one before
-  int32_t force_sort;      // != 0: take the general sort whatever the order
+  int32_t force_sort;      // != 0: take the general sort whatever the order (the word then starts at 1)
   int64_t* win_off;        // workspace [n_window + 1]
 };
 hipError_t dyn_launch_ingest(const IngestArgs& a, hipStream_t s);
+#define DYN_EDGE_PACK 960   // class edges that travel in one kernel's arguments
+hipError_t dyn_launch_edges(const int32_t* in_edge, size_t n_in, const int32_t* out_edge, size_t n_out, int32_t* d_in,
+                            int32_t* d_out, WsHeader* header, uint32_t order_word, hipStream_t s);
 int64_t dyn_ingest_blocks(int64_t n_req);
 #define DYN_INGEST_MAX_BINS 1024
 

@@ -13,6 +13,10 @@
 // counters -> stable scatter.  Inside a block every wave owns a contiguous run of rows of
 // 64 requests and walks them in order; the position of a request among the requests of
 // its row with the same digit comes from wave ballots, so arrival order is preserved.
+#include <string.h>
+
+#include <algorithm>
+
 #include "dyn_internal.h"
 #include "dyn_device.h"
 
@@ -106,10 +110,32 @@ __global__ __launch_bounds__(256) void key_kernel(IngestArgs a, double r_window,
     atomicOr(a.unsorted, 1u);
 }
 
+// The route is chosen on the device: every kernel of the two routes is launched and the kernels of the route that
+// is not taken return at once.  `order` is the flag word the key kernel leaves: 0 = every request's window is at
+// or after the window of the request before it (the trace is moved window by window), else the general sort runs.
+__device__ __forceinline__ bool sort_route(const uint32_t* order) { return *order != 0u; }
+
+// Class edges from the kernel's arguments into the workspace (a few hundred values at most per launch): the host
+// arrays are free when the call returns and nothing waits for the stream.  The first launch also writes the
+// workspace header: status 0, the order word (1 when the general sort is forced).
+struct EdgePack { int32_t v[DYN_EDGE_PACK]; };
+__global__ void edge_store_kernel(EdgePack p, int n_a, int32_t* __restrict__ dst_a, int n_b, int32_t* __restrict__ dst_b,
+                                  WsHeader* header, uint32_t order_word) {
+  for (int i = threadIdx.x; i < n_a; i += blockDim.x) dst_a[i] = p.v[i];
+  for (int i = threadIdx.x; i < n_b; i += blockDim.x) dst_b[i] = p.v[n_a + i];
+  if (header && threadIdx.x == 0) {
+    header->status = 0u;
+    header->kind = DYN_WS_KIND_WORD;
+    header->cells = 0;
+    ((uint32_t*)header)[DYN_WS_HEADER_ORDER_WORD] = order_word;
+  }
+}
+
 // digit counts of one block's tile -> block_hist[digit * n_block + block]
 __global__ __launch_bounds__(kWaves* DYN_WAVE) void hist_kernel(const uint32_t* __restrict__ keys, int64_t n,
                                                                 int shift, int bits, uint32_t* __restrict__ block_hist,
-                                                                int64_t n_block) {
+                                                                int64_t n_block, const uint32_t* __restrict__ order) {
+  if (!sort_route(order)) return;
   __shared__ uint32_t cnt[DYN_INGEST_MAX_BINS];
   const int nbins = 1 << bits;
   const uint32_t mask = (uint32_t)nbins - 1u;
@@ -146,7 +172,8 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_
 }
 
 __global__ __launch_bounds__(256) void scan_reduce_kernel(const uint32_t* __restrict__ x, int64_t count,
-                                                          uint32_t* __restrict__ partial) {
+                                                          uint32_t* __restrict__ partial, const uint32_t* __restrict__ order) {
+  if (!sort_route(order)) return;
   __shared__ uint32_t s_wave[4];
   const int64_t base = (int64_t)blockIdx.x * kScanChunk;
   uint32_t v = 0;
@@ -159,7 +186,8 @@ __global__ __launch_bounds__(256) void scan_reduce_kernel(const uint32_t* __rest
   if (threadIdx.x == 0) partial[blockIdx.x] = tot;
 }
 
-__global__ __launch_bounds__(256) void scan_partials_kernel(uint32_t* __restrict__ partial, int64_t n_partial) {
+__global__ __launch_bounds__(256) void scan_partials_kernel(uint32_t* __restrict__ partial, int64_t n_partial, const uint32_t* __restrict__ order) {
+  if (!sort_route(order)) return;
   __shared__ uint32_t s_wave[4];
   uint32_t carry = 0;
   for (int64_t base = 0; base < n_partial; base += 256) {
@@ -173,7 +201,8 @@ __global__ __launch_bounds__(256) void scan_partials_kernel(uint32_t* __restrict
 }
 
 __global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ x, int64_t count,
-                                                         const uint32_t* __restrict__ partial) {
+                                                         const uint32_t* __restrict__ partial, const uint32_t* __restrict__ order) {
+  if (!sort_route(order)) return;
   __shared__ uint32_t s_wave[4];
   // thread t owns 16 consecutive counters of the block's chunk
   constexpr int per = kScanChunk / 256;
@@ -197,7 +226,8 @@ __global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ 
 __global__ __launch_bounds__(kWaves* DYN_WAVE) void scatter_kernel(
     const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ in_in, const int32_t* __restrict__ out_in,
     uint32_t* __restrict__ keys_out, int32_t* __restrict__ in_out, int32_t* __restrict__ out_out, int64_t n,
-    int shift, int bits, const uint32_t* __restrict__ scanned, int64_t n_block) {
+    int shift, int bits, const uint32_t* __restrict__ scanned, int64_t n_block, const uint32_t* __restrict__ order) {
+  if (!sort_route(order)) return;
   __shared__ uint32_t wcnt[kWaves][DYN_INGEST_MAX_BINS];
   const int nbins = 1 << bits;
   const uint32_t mask = (uint32_t)nbins - 1u;
@@ -262,7 +292,8 @@ __global__ __launch_bounds__(kWaves* DYN_WAVE) void scatter_kernel(
 
 // cell_off[c] = number of requests with key < c, read off the sorted keys
 __global__ __launch_bounds__(256) void offsets_kernel(const uint32_t* __restrict__ keys, int64_t n, int64_t cells,
-                                                      int64_t* __restrict__ cell_off) {
+                                                      int64_t* __restrict__ cell_off, const uint32_t* __restrict__ order) {
+  if (!sort_route(order)) return;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i > n) return;
   const int64_t prev = i == 0 ? -1 : (int64_t)keys[i - 1];
@@ -290,7 +321,8 @@ __global__ __launch_bounds__(256) void window_offsets_kernel(const uint32_t* __r
 __global__ __launch_bounds__(kWaves* DYN_WAVE) void window_sort_kernel(
     const uint32_t* __restrict__ keys, const int32_t* __restrict__ in_in, const int32_t* __restrict__ out_in,
     int32_t* __restrict__ in_out, int32_t* __restrict__ out_out, const int64_t* __restrict__ win_off, int32_t G,
-    int32_t n_window, int64_t n, int64_t* __restrict__ cell_off) {
+    int32_t n_window, int64_t n, int64_t* __restrict__ cell_off, const uint32_t* __restrict__ order) {
+  if (sort_route(order)) return;
   __shared__ uint32_t wcnt[kWaves][DYN_INGEST_MAX_BINS];
   __shared__ uint32_t run[DYN_INGEST_MAX_BINS];          // next output position of every class, relative to the window's start
   const int w = blockIdx.x;
@@ -385,31 +417,47 @@ __global__ __launch_bounds__(kWaves* DYN_WAVE) void window_sort_kernel(
 
 int64_t dyn_ingest_blocks(int64_t n_req) { return n_req > 0 ? (n_req + kTile - 1) / kTile : 1; }
 
+hipError_t dyn_launch_edges(const int32_t* in_edge, size_t n_in, const int32_t* out_edge, size_t n_out, int32_t* d_in,
+                            int32_t* d_out, WsHeader* header, uint32_t order_word, hipStream_t s) {
+  EdgePack p;
+  if (n_in + n_out <= DYN_EDGE_PACK) {          // the usual case: header and both lists in one launch
+    if (n_in) memcpy(p.v, in_edge, n_in * sizeof(int32_t));
+    if (n_out) memcpy(p.v + n_in, out_edge, n_out * sizeof(int32_t));
+    hipLaunchKernelGGL(edge_store_kernel, dim3(1), dim3(256), 0, s, p, (int)n_in, d_in, (int)n_out, d_out, header, order_word);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(edge_store_kernel, dim3(1), dim3(64), 0, s, p, 0, d_in, 0, d_out, header, order_word);
+  const struct { const int32_t* src; size_t n; int32_t* dst; } parts[2] = {{in_edge, n_in, d_in}, {out_edge, n_out, d_out}};
+  for (const auto& part : parts)
+    for (size_t at = 0; at < part.n; at += DYN_EDGE_PACK) {
+      const int n = (int)std::min<size_t>(DYN_EDGE_PACK, part.n - at);
+      memcpy(p.v, part.src + at, (size_t)n * sizeof(int32_t));
+      hipLaunchKernelGGL(edge_store_kernel, dim3(1), dim3(256), 0, s, p, n, part.dst + at, 0, part.dst, (WsHeader*)nullptr, 0u);
+    }
+  return hipGetLastError();
+}
+
 hipError_t dyn_launch_ingest(const IngestArgs& a, hipStream_t s) {
   const int64_t n = a.n_req;
   const int32_t G = a.n_model * a.n_in_bin * a.n_out_bin;
   const int64_t cells = (int64_t)a.n_window * G;
   hipError_t e;
-  // Keys, and whether the trace is in window order already (the flag word was cleared with the header).  The
-  // answer picks the route, so it is read back here: this entry point synchronises with the stream anyway.
-  uint32_t unsorted = a.force_sort ? 1u : 0u;
+  // Keys, and whether the trace is in window order already: the key kernel ORs into the flag word, which the header
+  // kernel before it set to 0, or to 1 when the general sort is forced (more classes than the window route counts).
   if (n > 0) {
     const size_t edge_bytes = (size_t)a.n_model * ((a.n_in_bin - 1) + (a.n_out_bin - 1)) * sizeof(int32_t);
     const int lds_edges = edge_bytes <= 32 * 1024 ? 1 : 0;
     hipLaunchKernelGGL(key_kernel, dim3((unsigned)((n + kKeyRows * 256 - 1) / (kKeyRows * 256))), dim3(256), lds_edges ? edge_bytes : 0, s, a,
                        1.0 / a.window_s, lds_edges);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (!a.force_sort) {
-      if ((e = hipMemcpyAsync(&unsorted, a.unsorted, sizeof(uint32_t), hipMemcpyDeviceToHost, s)) != hipSuccess) return e;
-      if ((e = hipStreamSynchronize(s)) != hipSuccess) return e;
-    }
   } else {
     hipLaunchKernelGGL(window_offsets_kernel, dim3(1), dim3(256), 0, s, a.key_a, n, (uint32_t)G, a.n_window, a.win_off);
   }
-  if (!unsorted) {            // in window order: one block per window moves its requests to their cells
+  if (!a.force_sort) {        // in window order: one block per window moves its requests to their cells
     hipLaunchKernelGGL(window_sort_kernel, dim3((unsigned)a.n_window), dim3(kWaves * DYN_WAVE), 0, s, a.key_a, a.in_tok,
-                       a.out_tok, a.in_sorted, a.out_sorted, a.win_off, G, a.n_window, n, a.cell_off);
-    return hipGetLastError();
+                       a.out_tok, a.in_sorted, a.out_sorted, a.win_off, G, a.n_window, n, a.cell_off, a.unsorted);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (n == 0) return hipSuccess;   // nothing to sort: the flag word stays 0
   }
   const int passes = a.key_bits <= 0 ? 1 : (a.key_bits + 9) / 10;
   const int bits = a.key_bits <= 0 ? 1 : (a.key_bits + passes - 1) / passes;
@@ -427,12 +475,12 @@ hipError_t dyn_launch_ingest(const IngestArgs& a, hipStream_t s) {
     const int64_t n_part = (count + kScanChunk - 1) / kScanChunk;
     uint32_t* partial = a.block_hist + (size_t)DYN_INGEST_MAX_BINS * a.n_block;
     hipLaunchKernelGGL(hist_kernel, dim3((unsigned)a.n_block), dim3(kWaves * DYN_WAVE), 0, s, k_src, n, shift,
-                       bits, a.block_hist, a.n_block);
-    hipLaunchKernelGGL(scan_reduce_kernel, dim3((unsigned)n_part), dim3(256), 0, s, a.block_hist, count, partial);
-    hipLaunchKernelGGL(scan_partials_kernel, dim3(1), dim3(256), 0, s, partial, n_part);
-    hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)n_part), dim3(256), 0, s, a.block_hist, count, partial);
+                       bits, a.block_hist, a.n_block, a.unsorted);
+    hipLaunchKernelGGL(scan_reduce_kernel, dim3((unsigned)n_part), dim3(256), 0, s, a.block_hist, count, partial, a.unsorted);
+    hipLaunchKernelGGL(scan_partials_kernel, dim3(1), dim3(256), 0, s, partial, n_part, a.unsorted);
+    hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)n_part), dim3(256), 0, s, a.block_hist, count, partial, a.unsorted);
     hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)a.n_block), dim3(kWaves * DYN_WAVE), 0, s, k_src, i_src,
-                       o_src, k_dst, i_dst, o_dst, n, shift, bits, a.block_hist, a.n_block);
+                       o_src, k_dst, i_dst, o_dst, n, shift, bits, a.block_hist, a.n_block, a.unsorted);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     sorted_keys = k_dst;
     i_src = i_dst;
@@ -442,6 +490,6 @@ hipError_t dyn_launch_ingest(const IngestArgs& a, hipStream_t s) {
     k_dst = old_src;
   }
   hipLaunchKernelGGL(offsets_kernel, dim3((unsigned)((n + 1 + 255) / 256)), dim3(256), 0, s, sorted_keys, n, cells,
-                     a.cell_off);
+                     a.cell_off, a.unsorted);
   return hipGetLastError();
 }
