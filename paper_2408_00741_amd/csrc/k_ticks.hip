@@ -198,7 +198,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
     if (lane == q) load_l = div_by((double)tok, a.tick_s, a.r_tick);
     const int n_top = keep < n_q ? keep : n_q;
     if (lane < n_top) a.top[beg_q + lane] = best;           // the tick's list sits where its requests start
-    if (n_top > 0) {
+    if (n_top > 0 && (flags & DYN_TP_GENERAL)) {   // x_j is only used by the general kernel
       const int32_t mine_v = lane < n_top ? best : -1;
       if (g_empty) {
         gbest = mine_v;
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
     // every fine cell writes its own status byte: nothing to clear beforehand
     a.cstat[f] = (uint8_t)(bad_l | (neg ? DYN_WS_BAD_REQUEST : 0u) | ((skip && lane == 0) ? DYN_WS_TICK_RANK : 0u));
   }
-  const int32_t xj = keep > 0 ? __builtin_amdgcn_readlane(gbest, keep - 1) : 0;
+  const int32_t xj = (keep > 0 && (flags & DYN_TP_GENERAL)) ? __builtin_amdgcn_readlane(gbest, keep - 1) : 0;
   if (lane == 0) {
     TickPlan p;
     p.j = skip ? 0x7FFFFFFF : (int32_t)j64;
@@ -360,6 +360,13 @@ __device__ __forceinline__ void offer_tick(double (&s)[JF], const int32_t* s_top
   }
 }
 
+// Power of the configuration at load 0: what table_lookup returns for it (bracket 0, weight 0 on the second load point).
+template <bool TWO>
+__device__ __forceinline__ double idle_power(const Lookup& L) {
+  const double a = L.lo[2 * L.n_rho];
+  return TWO ? L.omu * a + L.u * L.hi[2 * L.n_rho] : a;
+}
+
 // The four largest tick TBTs with their request counts (descending; ties keep the earlier tick first).
 struct TbtTop {
   double tb[4];
@@ -420,22 +427,45 @@ __device__ __forceinline__ WalkOut walk_ticks(const Lookup& L, int T, int j, con
       offer_tick<JF>(s, s_top, T, q, c0 < j ? c0 : j, pf0);
     }
   };
+  // a tick without requests has load 0: the tables at their first load point, no look-up
+  const double e_idle = (nd * idle_power<TWO>(L)) * tick_s;
   int q = 0;
   for (; q + 2 <= T; q += 2) {
-    double pf0, tb0, pw0, pf1, tb1, pw1;
-    const bool o0 = table_lookup<SINGLE, TWO>(L, s_load[q], &pf0, &tb0, &pw0);
-    const bool o1 = table_lookup<SINGLE, TWO>(L, s_load[q + 1], &pf1, &tb1, &pw1);
-    ov = ov | o0 | o1;
-    e += (nd * pw0) * tick_s;                    // ticks in time order
-    e += (nd * pw1) * tick_s;
-    one(q, s_cnt[q], pf0, tb0);
-    one(q + 1, s_cnt[q + 1], pf1, tb1);
+    const int c0 = s_cnt[q], c1 = s_cnt[q + 1];                 // block-uniform
+    if (c0 > 0 && c1 > 0) {
+      double pf0, tb0, pw0, pf1, tb1, pw1;
+      const bool o0 = table_lookup<SINGLE, TWO>(L, s_load[q], &pf0, &tb0, &pw0);
+      const bool o1 = table_lookup<SINGLE, TWO>(L, s_load[q + 1], &pf1, &tb1, &pw1);
+      ov = ov | o0 | o1;
+      e += (nd * pw0) * tick_s;                  // ticks in time order
+      e += (nd * pw1) * tick_s;
+      one(q, c0, pf0, tb0);
+      one(q + 1, c1, pf1, tb1);
+    } else {
+#pragma unroll
+      for (int d = 0; d < 2; ++d) {
+        const int cd = d ? c1 : c0;
+        if (cd > 0) {
+          double pf0, tb0, pw0;
+          ov = ov | table_lookup<SINGLE, TWO>(L, s_load[q + d], &pf0, &tb0, &pw0);
+          e += (nd * pw0) * tick_s;
+          one(q + d, cd, pf0, tb0);
+        } else {
+          e += e_idle;
+        }
+      }
+    }
   }
   if (q < T) {
-    double pf0, tb0, pw0;
-    ov = ov | table_lookup<SINGLE, TWO>(L, s_load[q], &pf0, &tb0, &pw0);
-    e += (nd * pw0) * tick_s;
-    one(q, s_cnt[q], pf0, tb0);
+    const int c0 = s_cnt[q];
+    if (c0 > 0) {
+      double pf0, tb0, pw0;
+      ov = ov | table_lookup<SINGLE, TWO>(L, s_load[q], &pf0, &tb0, &pw0);
+      e += (nd * pw0) * tick_s;
+      one(q, c0, pf0, tb0);
+    } else {
+      e += e_idle;
+    }
   }
   WalkOut r;
   r.e = e; r.ov = ov; r.ttft = s[JF - 1];
@@ -800,21 +830,25 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
       load_config<LDS>(a, g, tile * sa.tile + (in_tile ? sub + tid : 0), s_tab, s_rgp, s_rinv, s_thr, s_js, &st);
       double e = 0.0, pf_min = __builtin_inf(), pf_max = -__builtin_inf(), tb_max = -__builtin_inf();
       bool ov = false;
+      const double e_idle = (st.nd * idle_power<TWO>(st.L)) * a.tick_s;
       for (int q = 0; q < T; ++q) {            // energy in time order; the strip takes the prefill times, or first the TBTs
+        if (s_cnt[q] == 0) {                   // block-uniform: load 0, and nothing of this tick enters a percentile
+          e += e_idle;
+          continue;
+        }
         double pf, tb, pw;
         ov = table_lookup<SINGLE, TWO>(st.L, s_load[q], &pf, &tb, &pw) | ov;
         e += (st.nd * pw) * a.tick_s;
         s_strip[q * NT + tid] = dense ? pf : tb;
-        if (s_cnt[q] > 0) {
-          pf_min = min_num(pf_min, pf);
-          pf_max = max_num(pf_max, pf);
-          tb_max = max_num(tb_max, tb);
-        }
+        pf_min = min_num(pf_min, pf);
+        pf_max = max_num(pf_max, pf);
+        tb_max = max_num(tb_max, tb);
       }
       double p_tbt = tb_max;
       if (!dense) {                            // block-uniform
         p_tbt = weighted_from_top(s_strip, s_cnt, T, NT, j, tid);
         for (int q = 0; q < T; ++q) {
+          if (s_cnt[q] == 0) continue;
           double pf, tb, pw;
           table_lookup<SINGLE, TWO>(st.L, s_load[q], &pf, &tb, &pw);
           s_strip[q * NT + tid] = pf;
