@@ -17,5 +17,25 @@ def build(force: bool = False) -> str:
     return LIB
 
 
+SAN_LIB = os.path.join(HERE, "libdynoracle_san.so")
+
+
+def build_sanitized(force: bool = False) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (host code only).  A process that loads it
+    needs the sanitizer runtime preloaded: see asan_runtime()."""
+    if not force and os.path.exists(SAN_LIB) and os.path.getmtime(SAN_LIB) >= os.path.getmtime(SRC):
+        return SAN_LIB
+    cmd = ["g++", "-O1", "-g", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-fno-omit-frame-pointer",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-Wall", "-Wextra", "-shared", "-fPIC", SRC,
+           "-o", SAN_LIB]
+    subprocess.run(cmd, check=True)
+    return SAN_LIB
+
+
+def asan_runtime() -> str:
+    """Path of the compiler's AddressSanitizer runtime (to be preloaded ahead of everything else)."""
+    return subprocess.run(["g++", "-print-file-name=libasan.so"], check=True, capture_output=True, text=True).stdout.strip()
+
+
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv))

@@ -6,6 +6,7 @@ may import this.  Argument marshalling only; all arithmetic is in the C++ file.
 from __future__ import annotations
 
 import ctypes as C
+import os
 from typing import Dict, Optional
 
 import numpy as np
@@ -20,7 +21,8 @@ _P = C.c_void_p
 def _load():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        # DYNORACLE_LIB: another build of the same source (the sanitizer build of the test-suite)
+        _lib = C.CDLL(os.environ.get("DYNORACLE_LIB") or build())
         _lib.dynoracle_ingest.restype = C.c_int
         _lib.dynoracle_eval.restype = C.c_int
         _lib.dynoracle_window_totals.restype = C.c_int
