@@ -230,6 +230,18 @@ int dyn_eval_select(dyn_profile* profile, const dyn_trace_view* trace, const dyn
                     const dyn_selection* sel, void* workspace, size_t workspace_bytes,
                     void* hip_stream);
 
+/* Measurement aid, optional: times dyn_eval_select on the caller's own buffers for several shapes of
+ * the evaluation kernel's blocks (how many windows one block walks: more amortise the staging of
+ * the table rows, fewer keep the streams the chip writes at a time closer together) and keeps the
+ * fastest in the profile handle, for this candidate list and this number of windows, until the
+ * list changes.  Without it a rule picks the shape.  The shape does not change any result: every
+ * run writes the same values, and `space` / `sel` hold them on return.  Arguments as for
+ * dyn_eval_select; `chosen` (HOST, may be NULL) receives the windows per block.  Waits for the
+ * stream between the runs (a few dozen evaluations in all).                               */
+int dyn_eval_tune(dyn_profile* profile, const dyn_trace_view* trace, const dyn_config* cfg, int32_t K,
+                  const dyn_objective* objective, const dyn_space* space, const dyn_selection* sel,
+                  void* workspace, size_t workspace_bytes, void* hip_stream, int32_t* chosen);
+
 /* dyn_eval_select for callers that cannot allocate device memory: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same computation and outputs as
  * dyn_eval_select, but the workspace is a fixed array of DYN_STATIC_WORKSPACE_BYTES that the

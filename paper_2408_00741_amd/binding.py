@@ -15,7 +15,7 @@ import torch
 
 __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_trace_ingest",
            "dyn_trace_ingest_workspace", "dyn_eval_space", "dyn_eval_space_workspace", "dyn_cell_stats",
-           "dyn_workspace_status", "dyn_select_config", "dyn_eval_select", "dyn_eval_select_static",
+           "dyn_workspace_status", "dyn_select_config", "dyn_eval_select", "dyn_eval_select_static", "dyn_eval_tune",
            "DYN_STATIC_WORKSPACE_BYTES", "dyn_last_error", "lib_path",
            "dyn_timing_enable", "dyn_timing_reset", "dyn_timing_read", "DYN_K_CELL", "DYN_K_SPACE", "DYN_K_SELECT",
            "DYN_K_TOTALS",
@@ -141,6 +141,9 @@ _lib.dyn_select_config.argtypes = [_vp, C.POINTER(_Space), C.POINTER(_Config), _
 _lib.dyn_eval_select.restype = C.c_int
 _lib.dyn_eval_select.argtypes = [_vp, C.POINTER(_TraceView), C.POINTER(_Config), _i32, C.POINTER(_Objective),
                                  C.POINTER(_Space), C.POINTER(_Selection), _vp, _sz, _vp]
+_lib.dyn_eval_tune.restype = C.c_int
+_lib.dyn_eval_tune.argtypes = [_vp, C.POINTER(_TraceView), C.POINTER(_Config), _i32, C.POINTER(_Objective),
+                               C.POINTER(_Space), C.POINTER(_Selection), _vp, _sz, _vp, C.POINTER(_i32)]
 _lib.dyn_eval_select_static.restype = C.c_int
 _lib.dyn_eval_select_static.argtypes = [_vp, C.POINTER(_TraceView), C.POINTER(_Config), _i32, C.POINTER(_Objective),
                                         C.POINTER(_Space), C.POINTER(_Selection), _vp, _vp]
@@ -401,6 +404,22 @@ def dyn_eval_select(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tenso
     _check(_lib.dyn_eval_select(profile.handle, C.byref(tv), plan.cfg, K, C.byref(plan.obj), C.byref(sp), C.byref(se),
                                 _dp(workspace), workspace.numel(), _stream(stream)), "dyn_eval_select")
     return out, sel, workspace
+
+
+def dyn_eval_tune(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tensor, cell_off: torch.Tensor, n_window: int,
+                  window_s: float, plan: Plan, out: Optional[Dict[str, torch.Tensor]] = None,
+                  sel: Optional[Dict[str, torch.Tensor]] = None, workspace: Optional[torch.Tensor] = None, stream=None) -> int:
+    """Times the evaluation for several block shapes and keeps the fastest in the profile handle.  Returns the chosen
+    number of windows per block."""
+    tv, sp, out, workspace, cells, K = _eval_args(profile, in_tok, out_tok, cell_off, n_window, window_s, plan, out,
+                                                  workspace)
+    if sel is None:
+        sel = _selection_tensors(cells, n_window, cell_off.device)
+    se = _selection_struct(sel)
+    chosen = _i32(0)
+    _check(_lib.dyn_eval_tune(profile.handle, C.byref(tv), plan.cfg, K, C.byref(plan.obj), C.byref(sp), C.byref(se),
+                              _dp(workspace), workspace.numel(), _stream(stream), C.byref(chosen)), "dyn_eval_tune")
+    return int(chosen.value)
 
 
 def dyn_eval_select_static(profile: Profile, in_tok: torch.Tensor, out_tok: torch.Tensor, cell_off: torch.Tensor,

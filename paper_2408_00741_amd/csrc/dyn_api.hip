@@ -171,6 +171,7 @@ int prepare_configs(dyn_profile* p, const dyn_config* cfg, int32_t K, hipStream_
               "copy tile rows"))
     return DYN_E_DEVICE;
   p->tile = tile; p->n_tile = n_tile; p->n_slot = n_slot;
+  p->wpb = 0; p->wpb_windows = 0; p->wpb_tuned = false;
   p->any_two_rows = false;
   for (int k = 0; k < K; ++k) p->any_two_rows = p->any_two_rows || dc[k].u != 0.0;
   p->cfg_host.assign(cfg, cfg + K);
@@ -353,6 +354,23 @@ __global__ __launch_bounds__(256) void or_cell_status_kernel(const uint8_t* __re
   if (v) atomicOr(status, v);
 }
 
+// Windows one block of the evaluation kernel walks.  Long runs amortise the staging of the table rows in LDS, but
+// the blocks a chip holds at a time then write that many more separate streams; measured on the one-day and the two
+// one-week workloads the kernel is fastest when about 16K (block, window) rows are in flight at a time (8, 6 and 8
+// windows; 14 to 32 cost 8 to 22 % more), and no run should leave the chip with fewer than ~8192 blocks in all.
+// dyn_eval_tune replaces the rule's value by a measured one.
+int32_t space_windows_per_block(dyn_profile* p, const SpaceArgs& a_in, int32_t n_window) {
+  if (p->wpb > 0 && p->wpb_windows == n_window) return p->wpb;
+  const int64_t cell_tiles = (int64_t)n_window * p->G * p->n_tile;
+  int64_t wpb = std::max<int64_t>(1, std::min<int64_t>(DYN_MAX_WIN_PER_BLOCK, (cell_tiles + 8191) / 8192));
+  SpaceArgs a = a_in;
+  a.win_per_block = 8;
+  const int per_cu = dyn_space_blocks_per_cu(a);
+  if (per_cu > 0 && p->n_cu > 0) wpb = std::min<int64_t>(wpb, std::max<int64_t>(4, 16384 / ((int64_t)per_cu * p->n_cu)));
+  p->wpb = (int32_t)wpb; p->wpb_windows = n_window; p->wpb_tuned = false;
+  return p->wpb;
+}
+
 int check_selection(const dyn_selection* out) {
   if (!out->sel || !out->sel_energy_j || !out->sel_cost || !out->window_energy_j || !out->window_infeasible) {
     dyn_set_error("a selection output array is NULL");
@@ -401,10 +419,7 @@ int eval_impl(dyn_profile* p, const dyn_trace_view* t, const dyn_config* cfg, in
   a.tile_rows = p->d_tile_rows;
   a.slo_ttft = p->d_slo_ttft; a.slo_tbt = p->d_slo_tbt; a.budget = p->d_budget;
   a.rec = (const CellRec*)(base + w.rec); a.n_window = t->n_window; a.window_s = t->window_s;
-  // several rounds of resident blocks on 256 CUs, with runs of windows long enough to
-  // amortise the LDS staging (measured optimum on the one-day workload: 13 to 20 windows)
-  const int64_t cell_tiles = cells * p->n_tile;
-  a.win_per_block = (int32_t)std::max<int64_t>(1, std::min<int64_t>(DYN_MAX_WIN_PER_BLOCK, (cell_tiles + 8191) / 8192));
+  a.win_per_block = space_windows_per_block(p, a, t->n_window);
   a.energy = out->energy_j; a.p99_ttft = out->p99_ttft_ms; a.p99_tbt = out->p99_tbt_ms; a.flags = out->flags;
   a.pw0 = p->d_pw0; a.idle_w = o->idle_cost_weight;
   a.part = sel ? (SelPart*)(base + w.part) : nullptr; a.n_wslot = w.n_wslot;
@@ -471,6 +486,7 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   p->d_path_layout = p->d_path_order = p->d_path_seg = p->d_lay_n = p->d_lay_tp = p->d_tp = p->d_ident = nullptr;
   p->d_path_trans = p->d_hier_trans = nullptr;
   p->obj_valid = false; p->tile = p->n_tile = p->n_slot = 0; p->any_two_rows = false;
+  p->wpb = p->wpb_windows = 0; p->wpb_tuned = false; p->n_cu = 0;
   hipStream_t s = (hipStream_t)hip_stream;
 
   // Bucket index over the load axis: bucket b covers [b, b+1) / bucket_scale and js[b] is the
@@ -522,6 +538,7 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   void* fixed_ws = nullptr;
   (void)scratch_address(&fixed_ws);   // set-up of dyn_eval_select_static on this device; that call reports a failure itself
   bool ok = hip_ok(hipGetDevice(&p->device), "hipGetDevice") &&
+            hip_ok(hipDeviceGetAttribute(&p->n_cu, hipDeviceAttributeMultiprocessorCount, p->device), "hipDeviceGetAttribute") &&
             hip_ok(dev_alloc(&p->d_tab, 3 * n_tab), "hipMalloc") && hip_ok(dev_alloc(&p->d_ml, n_row), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_pw0, n_row), "hipMalloc") && hip_ok(dev_alloc(&p->d_gridpack, gridpack.size()), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_jstart, js.size()), "hipMalloc") &&
@@ -642,6 +659,58 @@ int dyn_eval_select(dyn_profile* p, const dyn_trace_view* t, const dyn_config* c
                     size_t workspace_bytes, void* hip_stream) {
   if (!sel) { dyn_set_error("selection is NULL"); return DYN_E_NULL; }
   return eval_impl(p, t, cfg, K, o, out, sel, workspace, workspace_bytes, hip_stream);
+}
+
+int dyn_eval_tune(dyn_profile* p, const dyn_trace_view* t, const dyn_config* cfg, int32_t K, const dyn_objective* o,
+                  const dyn_space* out, const dyn_selection* sel, void* workspace, size_t workspace_bytes,
+                  void* hip_stream, int32_t* chosen) {
+  if (!sel) { dyn_set_error("selection is NULL"); return DYN_E_NULL; }
+  // one plain call first: it checks every argument and leaves the handle's plan in place
+  int rc = eval_impl(p, t, cfg, K, o, out, sel, workspace, workspace_bytes, hip_stream);
+  if (rc != DYN_OK) return rc;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int32_t start = p->wpb;                                  // the rule's value (or an earlier measurement)
+  const int64_t cell_tiles = (int64_t)t->n_window * p->G * p->n_tile;
+  const int32_t most = (int32_t)std::max<int64_t>(1, std::min<int64_t>(DYN_MAX_WIN_PER_BLOCK, (cell_tiles + 8191) / 8192));
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (!hip_ok(hipEventCreate(&e0), "hipEventCreate") || !hip_ok(hipEventCreate(&e1), "hipEventCreate")) {
+    if (e0) (void)hipEventDestroy(e0);
+    return DYN_E_DEVICE;
+  }
+  const int32_t cand[] = {1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 14, 16, 20, 24, 32};
+  int reps = 3;                                                  // raised after the first measurement: about 2 ms per shape
+  int32_t best = start;
+  float best_ms = -1.f;
+  bool first = true;
+  for (int32_t c : cand) {
+    if (c > most) break;
+    p->wpb = c; p->wpb_windows = t->n_window;
+    for (int pass = 0; pass < 2 && rc == DYN_OK; ++pass) {       // a warm-up call, then `reps` timed ones
+      if (pass == 1 && !hip_ok(hipEventRecord(e0, s), "hipEventRecord")) rc = DYN_E_DEVICE;
+      for (int r = 0; r < (pass ? reps : 1) && rc == DYN_OK; ++r)
+        rc = eval_impl(p, t, cfg, K, o, out, sel, workspace, workspace_bytes, hip_stream);
+    }
+    float ms = 0.f;
+    if (rc == DYN_OK && (!hip_ok(hipEventRecord(e1, s), "hipEventRecord") || !hip_ok(hipEventSynchronize(e1), "hipEventSynchronize") ||
+                         !hip_ok(hipEventElapsedTime(&ms, e0, e1), "hipEventElapsedTime")))
+      rc = DYN_E_DEVICE;
+    if (rc != DYN_OK) break;
+    ms /= (float)reps;
+    if (best_ms < 0.f || ms < best_ms) { best_ms = ms; best = c; }
+    if (first) {
+      first = false;
+      reps = (int)std::max(3.0f, std::min(16.0f, 2.0f / std::max(ms, 1e-3f)));
+    }
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  p->wpb = rc == DYN_OK ? best : start;
+  p->wpb_windows = t->n_window;
+  p->wpb_tuned = rc == DYN_OK;
+  if (rc != DYN_OK) return rc;
+  if (chosen) *chosen = best;
+  // the outputs are those of the last candidate's run; every run writes the same values
+  return DYN_OK;
 }
 
 int dyn_eval_select_static(dyn_profile* p, const dyn_trace_view* t, const dyn_config* cfg, int32_t K,

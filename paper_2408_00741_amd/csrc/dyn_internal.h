@@ -71,6 +71,11 @@ struct dyn_profile {
   int32_t* d_tile_rows;               // [2*DYN_MAX_CONFIGS + 1024]
   int32_t tile, n_tile, n_slot;       // n_slot == 0: table rows are read from global memory
   bool any_two_rows;                  // some candidate's frequency lies between two profiled ones
+  // windows one block of the evaluation kernel walks: the rule's value for this list, or what dyn_eval_tune measured
+  // (both for the number of windows they were made for)
+  int32_t wpb, wpb_windows;
+  bool wpb_tuned;
+  int32_t n_cu;                       // compute units of the device
   // plan: objective
   std::vector<double> slo_ttft_host, slo_tbt_host;
   std::vector<int32_t> budget_host;
@@ -140,6 +145,7 @@ struct SpaceArgs {
   const double* pw0; double idle_w; SelPart* part; int32_t n_wslot;
 };
 hipError_t dyn_launch_space(const SpaceArgs& a, hipStream_t s);
+int dyn_space_blocks_per_cu(const SpaceArgs& a);   // resident blocks of the evaluation kernel per compute unit (0: unknown)
 size_t dyn_space_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t win_per_block);   // LDS bytes besides the table rows
 
 struct FinishArgs {   // reduces the partial records of every cell, then the window totals

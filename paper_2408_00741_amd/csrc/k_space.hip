@@ -188,6 +188,23 @@ size_t dyn_space_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t win_per_block
          ((size_t)n_bucket + 1) * sizeof(uint16_t);
 }
 
+// Blocks of the evaluation kernel that one compute unit holds at a time for this shape (0 if the query fails).
+int dyn_space_blocks_per_cu(const SpaceArgs& a) {
+  const size_t lds_tab = (size_t)a.n_slot * 3 * a.n_rho * sizeof(double);
+  const size_t lds = (a.n_slot > 0 ? lds_tab : 0) + dyn_space_lds_tail(a.n_rho, a.n_bucket, a.win_per_block);
+  int n = 0;
+  hipError_t e;
+  if (a.n_slot > 0) {
+    if (a.one_step) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, space_kernel<true, true, true>, a.tile, lds);
+    else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, space_kernel<true, true, false>, a.tile, lds);
+  } else {
+    if (a.one_step) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, space_kernel<false, true, true>, a.tile, lds);
+    else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, space_kernel<false, true, false>, a.tile, lds);
+  }
+  if (e != hipSuccess) { (void)hipGetLastError(); return 0; }
+  return n;
+}
+
 hipError_t dyn_launch_space(const SpaceArgs& a, hipStream_t s) {
   const int n_chunk = (a.n_window + a.win_per_block - 1) / a.win_per_block;
   const size_t blocks = (size_t)n_chunk * a.G * a.n_tile;

@@ -558,6 +558,41 @@ def test_calls_in_flight_on_two_streams_give_the_same_bits(dyn):
     prof.free()
 
 
+def test_tuned_block_shape_changes_no_result(dyn):
+    """dyn_eval_tune picks how many windows a block of the evaluation kernel walks; every output stays bit-equal, the
+    choice sticks to the candidate list and is dropped when the list changes."""
+    w = make(SPECS[2].scaled(600_000, 90))
+    st = oracle.ingest(w["trace"], w["edges"], w["n_window"], w["window_s"])
+    ins, outs, off, _ = gpu_ingest(dyn, w)
+    prof = dyn.dyn_profile_load(w["profile"])
+    plan = dyn.Plan(w["configs"], w["slos"], w["pct"], None, w["idle_cost_weight"])
+    args = (prof, ins, outs, off, w["n_window"], w["window_s"], plan)
+    space0, sel0, ws = dyn.dyn_eval_select(*args)
+    torch.cuda.synchronize()
+    ref = {k: v.clone() for k, v in {**space0, **sel0}.items()}
+    chosen = dyn.dyn_eval_tune(*args, out=space0, sel=sel0, workspace=ws)
+    assert 1 <= chosen <= 32
+    torch.cuda.synchronize()
+    for k, v in {**space0, **sel0}.items():
+        assert torch.equal(v, ref[k]), k
+    space1, sel1, _ = dyn.dyn_eval_select(*args)
+    space2, _ = dyn.dyn_eval_space(*args)
+    torch.cuda.synchronize()
+    for k, v in {**space1, **sel1}.items():
+        assert torch.equal(v, ref[k]), k
+    for k, v in space2.items():
+        assert torch.equal(v, ref[k]), k
+    o = ora_eval(w, st)
+    np.testing.assert_array_equal(sel1["sel"].cpu().numpy(), o["sel"])
+    np.testing.assert_array_equal(space1["energy_j"].cpu().numpy(), o["energy_j"])
+    # another candidate list: the rule's shape again, same results as the oracle's
+    w2 = dict(w); w2["configs"] = {k: v[5:].copy() for k, v in w["configs"].items()}
+    g = gpu_eval(dyn, w2, ins, outs, off, prof=prof)
+    rep = assert_parity(w2, g, ora_eval(w2, st))
+    assert rep["bit_exact"] and rep["sel_mismatch"] == 0
+    prof.free()
+
+
 # ------------------------------------------------------------- full size, every cell
 def _excused(w, o_row, k_gpu, k_ora, g):
     """The stated tolerance for a differing selection: both candidates feasible for the oracle and their oracle costs
