@@ -171,6 +171,8 @@ def main():
                          "steps alternating between this many streams and output sets (reported as `pipelined`, never as "
                          "`value`); 0 or 1 = skip")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--checksums", action="store_true",
+                    help="add order-sensitive 64-bit checksums of every generated input array to the line (`inputs`)")
     ap.add_argument("--no-tune", action="store_true",
                     help="skip dyn_eval_tune in the set-up (the library's rule then picks the evaluation kernel's block shape)")
     ap.add_argument("--no-kernel-events", action="store_true",
@@ -407,6 +409,31 @@ def main():
                      "same_results_on_every_stream": bool(same)}
         del sets, streams
 
+    # ---- what a plain fill of the same four output arrays reaches on this GPU (torch's fill kernel, 20 repetitions
+    # after 3 warm-ups, HIP events): the practical ceiling for a kernel that only writes them
+    fill_gbps = None
+    if headline or args.unfused:
+        def fill_all():
+            for v_ in space.values():
+                v_.fill_(0)
+        keep_space = {k_: v_.clone() for k_, v_ in space.items()} if cells * K <= (1 << 26) else None
+        for _ in range(3):
+            fill_all()
+        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        f0.record()
+        for _ in range(20):
+            fill_all()
+        f1.record()
+        torch.cuda.synchronize()
+        fill_gbps = 25.0 * cells * K * 20 / (f0.elapsed_time(f1) * 1e-3) / 1e9
+        if keep_space is not None:
+            for k_, v_ in keep_space.items():
+                space[k_].copy_(v_)
+            del keep_space
+        else:
+            step()                      # the outputs are read below
+            torch.cuda.synchronize()
+
     # ---- roofline of the dominant kernel (space evaluation): 25 B written per (cell, configuration)
     space_bytes = 25.0 * cells * K
     space_ms = ktime["tick_space"] + ktime["tick_merge"] if args.ticks else ktime["space"]
@@ -454,7 +481,9 @@ def main():
                     "traffic": None if (args.unfused or args.path) else recorded_traffic(args.config),
                     "traffic_source": "profiles/space_kernel_traffic.json: FETCH_SIZE and WRITE_SIZE of two rocprofv3 --pmc runs of "
                                       "this command, scaled by a plain copy; null once the kernel's sources have changed since",
-                    "algorithmic_bytes_per_launch": space_bytes, "avg_launch_ms": space_ms}
+                    "algorithmic_bytes_per_launch": space_bytes, "avg_launch_ms": space_ms,
+                    "plain_fill_of_the_same_arrays_gbps": fill_gbps,
+                    "frac_of_plain_fill": (space_gbps / fill_gbps) if (space_gbps and fill_gbps) else None}
 
     if args.hierarchy:
         sel_h = hout["layout_sel"].cpu().numpy()
@@ -489,6 +518,13 @@ def main():
         if args.spill:
             out["result"]["nodes_without_the_fragmentation_rule"] = nodes_plain
             out["config"]["peak_nodes"] = args.peak_nodes
+    if args.checksums:
+        from workloads import checksum
+        out["inputs"] = {"seed": spec.seed,
+                         **{f"trace.{k_}": f"{checksum(v_):016x}" for k_, v_ in tr.items()},
+                         **{f"profile.{k_}": f"{checksum(v_):016x}" for k_, v_ in w["profile"].items()},
+                         **{f"configs.{k_}": f"{checksum(v_):016x}" for k_, v_ in w["configs"].items()},
+                         **{f"slos.{k_}": f"{checksum(v_):016x}" for k_, v_ in w["slos"].items()}}
     if not args.no_cpu_baseline:
         nwin = args.cpu_windows or max(1, min(NW, int(NW * (5.0e9 if args.mixed else 1.5e9 if args.path else 1.0e10) / (R * K))))
         mixed = (args.mixed, n_max, np.full(G, args.mixed_gpus, np.int32), K) if args.mixed else None

@@ -254,3 +254,39 @@ def test_full_size_day_trace_sampled_windows(dyn):
     print("cells where the mix beats every single type: %d of %d; feasible only as a mix: %d" %
           (int((g["energy_j"] < single).sum()), fin.sum(), int((fin & ~np.isfinite(single)).sum())))
     prof.free()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_tiny_pools_against_the_unfactored_product(dyn, seed):
+    """The GPU against a search that factors nothing (Eq. 1 with several types per pool): every (instances,
+    frequency, shares) of every type in one product, NumPy arithmetic, no code shared with the oracle.  The
+    sums are formed in another order there, hence the relative tolerance of a few ulps on the energy; the
+    assignment must be one of the product's optimal ones."""
+    from tests import npcheck
+    rng = np.random.default_rng(900 + seed)
+    n_tp, n_f, n_rho, G = 2 + seed % 2, 1 + seed % 3, 3, 2
+    fg = np.sort(rng.uniform(500, 2000, n_f))
+    rg = np.concatenate([[0.0], np.sort(rng.uniform(0.1, 0.95, n_rho - 1))])
+    shape = (G, n_tp, n_f, n_rho)
+    prof = {"tp": np.asarray([2, 4, 8][:n_tp], np.int32), "f_mhz": fg, "rho": rg,
+            "prefill_ms_per_tok": rng.uniform(0.05, 0.3, shape), "tbt_ms": np.sort(rng.uniform(10, 150, shape), axis=-1),
+            "power_w": np.sort(rng.uniform(100, 3000, shape), axis=-1), "max_load_tps": rng.uniform(200, 900, shape[:3])}
+    R, NW, W = 60, 2, 10.0
+    tr = {"t_s": rng.uniform(0, NW * W, R), "in_tok": rng.integers(1, 400, R).astype(np.int32),
+          "out_tok": rng.integers(1, 200, R).astype(np.int32), "model": np.zeros(R, np.int32)}
+    tr["t_s"][tr["t_s"] > 15.0] = 1.0
+    edges = {"in_edge": np.asarray([[150]], np.int32), "out_edge": np.zeros((1, 0), np.int32)}
+    slo = {"slo_ttft_ms": rng.uniform(40, 120, G), "slo_tbt_ms": rng.uniform(60, 140, G)}
+    bud = np.asarray([0, 10], np.int32)
+    n_max = [2, 2, 1][:n_tp]
+    S = 3
+    w = {"trace": tr, "edges": edges, "n_window": NW, "window_s": W, "profile": prof, "slos": slo, "pct": (99, 100),
+         "n_class": G}
+    g, _ = gpu_mixed(dyn, w, S, n_max, bud)
+    assert g["status"] == 0
+    b = npcheck.np_mixed(prof, npcheck.np_ingest(tr, edges, NW, W), NW, W, S, n_max, slo, (99, 100), bud)
+    fin = np.isfinite(b["energy_j"])
+    assert (np.isfinite(g["energy_j"]) == fin).all() and fin.any()
+    np.testing.assert_allclose(g["energy_j"][fin], b["energy_j"][fin], rtol=1e-12)
+    for c in np.nonzero(fin)[0]:
+        assert tuple(zip(g["n_inst"][c].tolist(), g["share"][c].tolist())) in b["assignments"][c]

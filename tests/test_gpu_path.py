@@ -274,3 +274,55 @@ def test_argument_errors(dyn):
     torch.cuda.synchronize()
     assert (out["sel"].cpu().numpy() == 0).all() and (out["path_cost"].cpu().numpy() == 2.0).all()
     prof.free()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_tiny_spaces_against_every_sequence(dyn, seed):
+    """The GPU against the definition written out (reconfiguration overheads between consecutive windows, Section
+    IV-C): every sequence of feasible candidates over each run of windows is priced with itertools, sums in window
+    order; the GPU's total must equal the smallest one and its sequence must be one of those that reach it."""
+    import itertools
+    rng = np.random.default_rng(1300 + seed)
+    w = make(SPECS[0])
+    G = w["n_class"]
+    NW, K, NL = int(rng.integers(2, 6)), int(rng.integers(2, 5)), int(rng.integers(1, 4))
+    energy = rng.uniform(1, 10, (NW * G, K))
+    flags = np.where(rng.uniform(0, 1, (NW * G, K)) < 0.7, 1, 4).astype(np.uint8)
+    if seed % 2:
+        flags[(NW // 2) * G + 1] = 4                         # class 1 has a window without any feasible candidate
+    feas = (flags & 1).astype(bool)
+    lay = rng.integers(0, NL, K).astype(np.int32)
+    tr = rng.uniform(0, 4, (NL, NL)); tr[np.diag_indices(NL)] = 0.0
+    cfg = {"n_inst": rng.integers(1, 5, K).astype(np.int32),
+           "tp_index": rng.integers(0, w["profile"]["tp"].size, K).astype(np.int32),
+           "f_mhz": rng.choice(w["profile"]["f_mhz"], K)}
+    prof = dyn.dyn_profile_load(w["profile"])
+    r = run_path(dyn, prof, dyn.Plan(cfg, w["slos"], w["pct"], None, 0.0), energy, flags, NW, 60.0, lay, tr)
+    prof.free()
+    sel, pc = r["sel"], r["path_cost"]
+    for g in range(G):
+        ok = [feas[x * G + g].any() for x in range(NW)]
+        total, x = 0.0, 0
+        while x < NW:
+            if not ok[x]:
+                assert sel[x * G + g] == -1
+                x += 1
+                continue
+            e = x
+            while e < NW and ok[e]:
+                e += 1
+            best, best_seq = np.inf, []
+            for seq in itertools.product(range(K), repeat=e - x):
+                if not all(feas[(x + i) * G + g, k] for i, k in enumerate(seq)):
+                    continue
+                v = energy[x * G + g, seq[0]]
+                for i in range(1, len(seq)):
+                    v = (v + tr[lay[seq[i - 1]], lay[seq[i]]]) + energy[(x + i) * G + g, seq[i]]
+                if v < best:
+                    best, best_seq = v, [seq]
+                elif v == best:
+                    best_seq.append(seq)
+            total += best
+            assert tuple(int(sel[(x + i) * G + g]) for i in range(e - x)) in best_seq
+            x = e
+        assert pc[g] == total
