@@ -525,6 +525,10 @@ def main():
                          **{f"profile.{k_}": f"{checksum(v_):016x}" for k_, v_ in w["profile"].items()},
                          **{f"configs.{k_}": f"{checksum(v_):016x}" for k_, v_ in w["configs"].items()},
                          **{f"slos.{k_}": f"{checksum(v_):016x}" for k_, v_ in w["slos"].items()}}
+        golden = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tests", "golden", "input_checksums.txt")
+        rec = {tuple(l.split()[:2]): l.split()[2] for l in open(golden) if l.strip() and not l.startswith("#")}
+        out["inputs"]["equal_to_the_recorded_checksums"] = all(
+            rec.get((str(args.config), k_)) == v_ for k_, v_ in out["inputs"].items() if k_ != "seed")
     if not args.no_cpu_baseline:
         nwin = args.cpu_windows or max(1, min(NW, int(NW * (5.0e9 if args.mixed else 1.5e9 if args.path else 1.0e10) / (R * K))))
         mixed = (args.mixed, n_max, np.full(G, args.mixed_gpus, np.int32), K) if args.mixed else None
