@@ -239,6 +239,93 @@ __device__ __forceinline__ CellOut cell_by_block(const int32_t* __restrict__ in,
   return r;
 }
 
+// Register-resident cell of 2048 < m <= 128*P requests by one wave: two 16-bit input lengths to a register (request
+// i*64 + lane in half i%2 of register i/2; 0xFFFF beyond m).  Same sums and the same search as above.  Returns false,
+// and nothing else, when a token count of 2^16 or more (a negative one included) rules the packing out: the caller
+// leaves the cell to the whole block.
+constexpr int kPackedRowsMax = 128;  // the packed path handles m <= 64 * kPackedRowsMax
+template <int P>
+__device__ __forceinline__ bool cell_in_registers_packed(const int32_t* __restrict__ in, const int32_t* __restrict__ out,
+                                                         int m, int rank, int lane, CellOut* res) {
+  uint32_t v[P];
+  uint32_t s_in = 0, s_out = 0, orv = 0, lmax = 0, lmax2 = 0;   // lmax / lmax2: largest input of the even / odd rows
+  constexpr int CH = 4;                  // registers per round: 8 + 8 loads in flight
+  static_assert(P % CH == 0, "whole rounds");
+#pragma unroll
+  for (int p0 = 0; p0 < P; p0 += CH) {
+    uint32_t a[2 * CH], b[2 * CH];
+#pragma unroll
+    for (int u = 0; u < 2 * CH; ++u) {
+      const int idx = (2 * p0 + u) * DYN_WAVE + lane;
+      a[u] = idx < m ? (uint32_t)in[idx] : 0u;
+      b[u] = idx < m ? (uint32_t)out[idx] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < 2 * CH; ++u) {
+      s_in += a[u];
+      s_out += b[u];
+      orv |= a[u] | b[u];
+      if (u % 2 == 0) lmax = max(lmax, a[u]);
+      else lmax2 = max(lmax2, a[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+      const int idx = (2 * (p0 + u)) * DYN_WAVE + lane;
+      const uint32_t x0 = idx < m ? a[2 * u] & 0xFFFFu : 0xFFFFu;
+      const uint32_t x1 = idx + DYN_WAVE < m ? a[2 * u + 1] & 0xFFFFu : 0xFFFFu;
+      v[p0 + u] = x0 | (x1 << 16);
+    }
+    // keep the rounds apart (the next round's loads after this round's arithmetic): with all loads hoisted to the
+    // top, or the arithmetic sunk to the end, 4P loaded values would be live at once
+    asm volatile("" : "+v"(s_in), "+v"(s_out), "+v"(orv), "+v"(lmax), "+v"(lmax2), "+v"(v[p0]), "+v"(v[p0 + 1]),
+                 "+v"(v[p0 + 2]), "+v"(v[p0 + 3])::"memory");
+  }
+  orv = wave_or_u32(orv);
+  if (orv >= (1u << 16)) return false;   // uniform over the wave
+  // all values below 2^16: a lane's sum stays below 2^23, the wave's below 2^29
+  res->orv = orv;
+  res->tin = (int64_t)wave_sum_u32(s_in);
+  res->tout = (int64_t)wave_sum_u32(s_out);
+  const uint32_t top = wave_max_u32(max(lmax, lmax2));
+  if (rank == m) {
+    res->p99 = top;
+    return true;
+  }
+  uint32_t lo = 0;
+  const int j = m - rank + 1;
+  if (j <= 2 * DYN_WAVE) {
+    const int nb = 32 - __builtin_clz(top | 1u);
+    for (int b = nb - 1; b >= 0; --b) {   // largest c with #{the 128 half-lane maxima >= c} >= j (all elements of the cell)
+      const uint32_t cand = lo | (1u << b);
+      if (__popcll(__ballot(lmax >= cand)) + __popcll(__ballot(lmax2 >= cand)) >= j) lo = cand;
+    }
+  }
+  uint32_t d = 0;
+  const int nb = 32 - __builtin_clz((top - lo) | 1u);
+  for (int b = nb - 1; b >= 0; --b) {
+    const uint32_t cand = lo + (d | (1u << b));
+    // low half by a 16-bit compare; high half: hi < cand exactly when the whole register < cand << 16 (no unpacking,
+    // which the compiler would otherwise hoist out of this loop into 2P registers)
+    const uint16_t cand_lo = (uint16_t)cand;
+    const uint32_t cand_hi = cand << 16;
+    int below = 0;
+#pragma unroll
+    for (int i = 0; i < P; ++i)
+      below += __popcll(__ballot((uint16_t)v[i] < cand_lo)) + __popcll(__ballot(v[i] < cand_hi));
+    if (below < rank) d |= 1u << b;
+  }
+  res->p99 = lo + d;
+  return true;
+}
+
+__device__ __forceinline__ bool cell_by_wave_packed(const int32_t* __restrict__ in, const int32_t* __restrict__ out,
+                                                    int mi, int rk, int lane, CellOut* res) {
+  if (mi <= 128 * 24) return cell_in_registers_packed<24>(in, out, mi, rk, lane, res);
+  if (mi <= 128 * 32) return cell_in_registers_packed<32>(in, out, mi, rk, lane, res);
+  if (mi <= 128 * 48) return cell_in_registers_packed<48>(in, out, mi, rk, lane, res);
+  return cell_in_registers_packed<64>(in, out, mi, rk, lane, res);
+}
+
 __device__ __forceinline__ void write_cell(int64_t c, const CellOut& r, int64_t m, uint32_t bad, double window_s,
                                            double r_window,
                                            int64_t cells, int64_t* __restrict__ tin, int64_t* __restrict__ tout,
@@ -270,6 +357,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
     int32_t* __restrict__ in_p99, CellRec* __restrict__ rec, uint8_t* __restrict__ cstat,
     WsHeader* __restrict__ header) {
   __shared__ uint32_t s_hist[kHistBins];
+  __shared__ uint32_t s_redo[kWavesPerBlock];
   __shared__ int64_t s_xch[16];
   const int lane = threadIdx.x & (DYN_WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
@@ -278,34 +366,49 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
   const int nc = (int)(cells - c0 < kWavesPerBlock ? cells - c0 : kWavesPerBlock);
   const int64_t myoff = lane <= nc ? cell_off[c0 + lane] : 0;
   const int64_t nxoff = __shfl_down(myoff, 1, DYN_WAVE);
-  // cells of this block left to the whole block (uniform over the block)
-  const uint32_t big_mask = (uint32_t)__ballot(lane < nc && myoff >= 0 && nxoff >= myoff && nxoff <= n_req &&
-                                               nxoff - myoff > DYN_WAVE * kRegRowsMax);
+  const bool sound = lane < nc && myoff >= 0 && nxoff >= myoff && nxoff <= n_req;
+  // cells of this block left to the whole block, and cells beyond the plain register tiers that a wave takes with
+  // packed registers (both uniform over the block)
+  uint32_t big_mask = (uint32_t)__ballot(sound && nxoff - myoff > DYN_WAVE * kPackedRowsMax);
+  const uint32_t packed_mask = (uint32_t)__ballot(sound && nxoff - myoff > DYN_WAVE * kRegRowsMax &&
+                                                  nxoff - myoff <= DYN_WAVE * kPackedRowsMax);
   if (wave < nc && !((big_mask >> wave) & 1u)) {
     const int64_t c = c0 + wave;
     int64_t beg = readlane_i64(myoff, wave), end = readlane_i64(nxoff, wave);
-    uint32_t bad = 0;
-    if (beg < 0 || end < beg || end > n_req) {  // never read outside the trace
-      bad = DYN_WS_BAD_OFFSETS;
-      beg = end = 0;
-    }
+    // the status lives in a scalar register while the cell is reduced (a vector register would be spilled)
+    uint32_t bad = __builtin_amdgcn_readfirstlane((beg < 0 || end < beg || end > n_req) ? DYN_WS_BAD_OFFSETS : 0u);
+    asm volatile("" : "+s"(bad));
+    if (bad) beg = end = 0;   // never read outside the trace
     const int mi = (int)(end - beg);
     CellOut r;
     r.tin = r.tout = 0;
     r.p99 = 0;
     r.orv = 0;
+    bool done = true;
     if (mi > 0) {
       const int rk = (int)(((int64_t)pct_num * mi + pct_den - 1) / pct_den);
-      r = cell_by_wave(in, out, beg, mi, rk, lane);
+      if ((packed_mask >> wave) & 1u) {
+        done = cell_by_wave_packed(in + beg, out + beg, mi, rk, lane, &r);
+        if (lane == 0) s_redo[wave] = done ? 0u : 1u;
+      } else {
+        r = cell_by_wave(in, out, beg, mi, rk, lane);
+      }
+      asm volatile("" : "+s"(bad));
       if (r.orv >> 31) bad |= DYN_WS_BAD_REQUEST;  // a negative token count
     }
-    if (lane == 0) write_cell(c, r, mi, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
+    if (done && lane == 0) write_cell(c, r, mi, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
   }
-  if (big_mask == 0) return;   // uniform over the block
+  if ((big_mask | packed_mask) == 0) return;   // uniform over the block
+  if (packed_mask) {
+    __syncthreads();
+    for (int q = 0; q < kWavesPerBlock; ++q)
+      if (((packed_mask >> q) & 1u) && s_redo[q]) big_mask |= 1u << q;
+  }
+  if (big_mask == 0) return;
   for (int q = 0; q < kWavesPerBlock; ++q) {
     if (!((big_mask >> q) & 1u)) continue;
-    const int64_t beg = readlane_i64(myoff, q);
-    const int64_t m = readlane_i64(nxoff, q) - beg;
+    const int64_t beg = cell_off[c0 + q];          // read again (the masks vouch for them): nothing is kept in
+    const int64_t m = cell_off[c0 + q + 1] - beg;  // registers across the waves' own cells
     const int64_t rank = ((int64_t)pct_num * m + pct_den - 1) / pct_den;
     const CellOut r = cell_by_block<8>(in, out, beg, m, rank, s_hist, s_xch);
     const uint32_t bad = (r.orv >> 31) ? DYN_WS_BAD_REQUEST : 0u;
