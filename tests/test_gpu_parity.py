@@ -291,19 +291,28 @@ def test_worked_example_on_gpu(dyn, golden_dir):
 
 
 @pytest.mark.parametrize("m", [1, 2, 63, 64, 65, 99, 100, 101, 128, 129, 200, 511, 513, 1024, 1025, 2047, 2048,
-                               2049, 4095, 4096, 4097, 70_001])
+                               2049, 3072, 3073, 4095, 4096, 4097, 6144, 6145, 6401, 8191, 8192, 8193, 12_801, 70_001])
 def test_rank_select_cell_sizes(dyn, m):
-    """Every register tier, the tier boundaries and the streamed path; distinct and duplicate values."""
+    """Every register tier (plain and packed), the tier boundaries and the streamed path; distinct and duplicate
+    values; 16-bit values incl. 0 and 65535 (the packed tiers' padding value) and a single 65536 among them (the
+    cell then leaves the packed tier for the streamed path)."""
     prof, cfg = _worked()
     rng = np.random.default_rng(m)
-    for kind in ("perm", "dups", "wide"):
+    for kind in ("perm", "dups", "wide", "u16", "over"):
         if kind == "perm":
             x = rng.permutation(np.arange(1, m + 1))
         elif kind == "dups":
             x = rng.integers(1, 40, m)
+        elif kind == "u16":
+            x = rng.integers(0, 65536, m)
+            x[rng.integers(0, m, 3)] = 65535
+            x[rng.integers(0, m)] = 0
+        elif kind == "over":
+            x = rng.integers(60000, 65536, m)
+            x[rng.integers(0, m)] = 65536
         else:
             x = rng.integers(0, 2 ** 30, m)            # exercises the 16-bit split sums and 30-bit selection
-        y = rng.integers(1, 8193, m)
+        y = rng.integers(1, 8193, m) if kind != "over" else rng.integers(65000, 65536, m)
         for pct in ((99, 100), (1, 2), (1, 1), (1, 100)):
             w, st, g = _single(dyn, prof, cfg, x, y, 1e12, 1e12, 1e6, pct=pct)
             rank = -(-pct[0] * m // pct[1])
@@ -343,6 +352,39 @@ def test_mixed_small_and_large_cells(dyn):
         assert g["status"] == 0
         rep = assert_parity(w, g, ora_eval(w, st))
         assert rep["bit_exact"] and rep["sel_mismatch"] == 0
+
+
+@pytest.mark.parametrize("pct", [(99, 100), (1, 2)])
+def test_blocks_mixing_packed_streamed_and_handed_over_cells(dyn, pct):
+    """Blocks of four consecutive cells in which a wave's own cell (plain or packed registers), cells beyond 8192
+    requests (streamed by the block) and packed-size cells that hold a token count of 2^16 or more, or a negative one
+    (handed over to the block after the waves' own work), sit side by side in every combination."""
+    prof, cfg = _worked()
+    rng = np.random.default_rng(77 + pct[0])
+    kinds = rng.integers(0, 5, 96)
+    sizes = np.select([kinds == 0, kinds == 1, kinds == 2, kinds == 3], [rng.integers(0, 2049, 96), rng.integers(2049, 8193, 96),
+                      rng.integers(8193, 12000, 96), rng.integers(2049, 8193, 96)], rng.integers(2049, 8193, 96))
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(off[-1])
+    x = rng.integers(1, 8193, n); y = rng.integers(1, 8193, n)
+    neg = []
+    for c in np.nonzero(kinds == 3)[0]:                       # a large input or output count somewhere in the cell
+        i = int(rng.integers(off[c], off[c + 1]))
+        if c % 2:
+            x[i] = 65536 + int(rng.integers(0, 1000))
+        else:
+            y[i] = 1 << 20
+    for c in np.nonzero(kinds == 4)[0][:3]:                   # a negative count: status bit, sums still signed
+        y[int(rng.integers(off[c], off[c + 1]))] = -5
+        neg.append(c)
+    w, st, g = _single(dyn, prof, cfg, x, y, 100, 50, 1000.0, n_window=sizes.size, off=off, lam=0.1, pct=pct)
+    assert g["status"] == (dyn.DYN_WS_BAD_REQUEST if neg else 0)
+    for c in range(sizes.size):
+        seg = x[off[c]:off[c + 1]]
+        assert g["tin"][c] == int(seg.astype(np.int64).sum())
+        assert g["tout"][c] == int(y[off[c]:off[c + 1]].astype(np.int64).sum())
+        if seg.size:
+            assert g["in_p99"][c] == np.sort(seg)[-(-pct[0] * seg.size // pct[1]) - 1], (c, kinds[c], seg.size)
 
 
 @pytest.mark.parametrize("pct", [(99, 100), (1, 2), (1, 1), (1, 100), (9, 10)])
