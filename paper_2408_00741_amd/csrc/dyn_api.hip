@@ -55,7 +55,7 @@ hipError_t dev_alloc(T** p, size_t count) {
 }
 
 void free_profile_device(dyn_profile* p) {
-  void* ptrs[] = {p->d_tab, p->d_ml, p->d_pw0, p->d_gridpack, p->d_jstart, p->d_tstart, p->d_thr, p->d_cfg,
+  void* ptrs[] = {p->d_tab, p->d_ml, p->d_pw0, p->d_pfspan, p->d_gridpack, p->d_jstart, p->d_tstart, p->d_thr, p->d_cfg,
                   p->d_tile_rows, p->d_slo_ttft, p->d_slo_tbt, p->d_budget, p->d_path_layout, p->d_path_order,
                   p->d_path_seg, p->d_path_trans, p->d_hier_trans, p->d_lay_n, p->d_lay_tp, p->d_tp, p->d_ident};
   for (void* q : ptrs)
@@ -480,7 +480,7 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   p->G = d->n_class; p->n_tp = d->n_tp; p->n_f = d->n_f; p->n_rho = d->n_rho;
   p->tp.assign(d->tp, d->tp + d->n_tp);
   p->fg.assign(d->f_mhz, d->f_mhz + d->n_f);
-  p->d_tab = p->d_ml = p->d_pw0 = p->d_gridpack = nullptr;
+  p->d_tab = p->d_ml = p->d_pw0 = p->d_pfspan = p->d_gridpack = nullptr;
   p->d_jstart = nullptr; p->d_tstart = nullptr; p->d_thr = nullptr; p->d_cfg = nullptr; p->d_tile_rows = nullptr;
   p->d_slo_ttft = p->d_slo_tbt = nullptr; p->d_budget = nullptr;
   p->d_path_layout = p->d_path_order = p->d_path_seg = p->d_lay_n = p->d_lay_tp = p->d_tp = p->d_ident = nullptr;
@@ -534,13 +534,20 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   }
   std::vector<double> pw0(n_row);
   for (size_t r = 0; r < n_row; ++r) pw0[r] = d->power_w[r * d->n_rho];
+  std::vector<double> pfspan(2 * n_row);
+  for (size_t r = 0; r < n_row; ++r) {
+    const double* row = d->prefill_ms_per_tok + r * d->n_rho;
+    pfspan[2 * r] = *std::min_element(row, row + d->n_rho);
+    pfspan[2 * r + 1] = *std::max_element(row, row + d->n_rho);
+  }
 
   void* fixed_ws = nullptr;
   (void)scratch_address(&fixed_ws);   // set-up of dyn_eval_select_static on this device; that call reports a failure itself
   bool ok = hip_ok(hipGetDevice(&p->device), "hipGetDevice") &&
             hip_ok(hipDeviceGetAttribute(&p->n_cu, hipDeviceAttributeMultiprocessorCount, p->device), "hipDeviceGetAttribute") &&
             hip_ok(dev_alloc(&p->d_tab, 3 * n_tab), "hipMalloc") && hip_ok(dev_alloc(&p->d_ml, n_row), "hipMalloc") &&
-            hip_ok(dev_alloc(&p->d_pw0, n_row), "hipMalloc") && hip_ok(dev_alloc(&p->d_gridpack, gridpack.size()), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_pw0, n_row), "hipMalloc") && hip_ok(dev_alloc(&p->d_pfspan, 2 * n_row), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_gridpack, gridpack.size()), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_jstart, js.size()), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_tstart, tstart.size()), "hipMalloc") && hip_ok(dev_alloc(&p->d_thr, thr.size()), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_cfg, DYN_MAX_CONFIGS), "hipMalloc") &&
@@ -558,6 +565,7 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   ok = ok && hip_ok(hipMemcpyAsync(p->d_tab, packed.data(), 3 * n_tab * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_ml, d->max_load_tps, n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_pw0, pw0.data(), n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_pfspan, pfspan.data(), 2 * n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_gridpack, gridpack.data(), gridpack.size() * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_jstart, js.data(), js.size() * 4, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_tstart, tstart.data(), tstart.size() * 4, hipMemcpyHostToDevice, s), "copy") &&
@@ -800,6 +808,7 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   ta.rec = (const TickRec*)(base + w.fine.rec); ta.plan = (const TickPlan*)(base + w.plan); ta.top = (const int32_t*)(base + w.top);
   ta.counters = (const uint32_t*)(base + w.counters); ta.slow_list = (const uint32_t*)(base + w.slow_list);
   ta.tstart = p->d_tstart; ta.thr = p->d_thr; ta.single_point = p->single_point; ta.any_two_rows = p->any_two_rows;
+  ta.pfspan = p->d_pfspan; ta.n_cu = p->n_cu;
   if (!hip_ok(dyn_launch_tick_space(ta, s), "tick space launch")) return DYN_E_DEVICE;
 
   FinishArgs f;

@@ -57,6 +57,8 @@ struct TickArgs {
   const int32_t* top;      // [n_req]
   const int32_t* tstart; const double* thr; bool single_point;   // threshold form of the bucket index
   bool any_two_rows;
+  int32_t n_cu;               // compute units of the device (0: unknown)
+  const double* pfspan;       // [G][n_tp_f][2] smallest and largest prefill time of every table row
   const uint32_t* counters;   // [1]: number of cells on slow_list
   const uint32_t* slow_list;  // [cells] cells left to the general kernel
 };

@@ -33,8 +33,8 @@ constexpr int kWavesPerBlock = 4;
 constexpr int kFastDepth = DYN_TICK_FAST;
 constexpr int kDeepCap = DYN_TICK_DEPTH;     // largest j, and the largest tick the deep-cell kernel sorts in one go
 constexpr int kDeepBlocks = 512;
-constexpr int kGeneralBlocks = 1024;
-constexpr int kListCap = 4096;               // list entries of one cell the general kernel stages in LDS
+constexpr int kGeneralBlocks = 1024;          // grid of the general kernel when the device cannot be asked what fits
+constexpr int kListCap = 2048;               // list entries of one cell the general kernel stages in LDS
 constexpr int kStripBytes = 32 * 1024;       // per-tick values of a block's configurations in the general kernel
 static_assert(kDeepCap == 8192, "the deep-cell kernel's LDS buffer");
 // LDS stride of a staged table row in doubles: odd, so that lanes reading the same load bracket of
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
     if (lane == q) load_l = div_by((double)tok, a.tick_s, a.r_tick);
     const int n_top = keep < n_q ? keep : n_q;
     if (lane < n_top) a.top[beg_q + lane] = best;           // the tick's list sits where its requests start
-    if (n_top > 0 && (flags & DYN_TP_GENERAL)) {   // x_j is only used by the general kernel
+    if (n_top > 0) {                             // towards x_j: the walk prunes its lists with it, the general kernel brackets with it
       const int32_t mine_v = lane < n_top ? best : -1;
       if (g_empty) {
         gbest = mine_v;
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
     // every fine cell writes its own status byte: nothing to clear beforehand
     a.cstat[f] = (uint8_t)(bad_l | (neg ? DYN_WS_BAD_REQUEST : 0u) | ((skip && lane == 0) ? DYN_WS_TICK_RANK : 0u));
   }
-  const int32_t xj = (keep > 0 && (flags & DYN_TP_GENERAL)) ? __builtin_amdgcn_readlane(gbest, keep - 1) : 0;
+  const int32_t xj = keep > 0 ? __builtin_amdgcn_readlane(gbest, keep - 1) : 0;
   if (lane == 0) {
     TickPlan p;
     p.j = skip ? 0x7FFFFFFF : (int32_t)j64;
@@ -346,10 +346,13 @@ __global__ __launch_bounds__(256) void tick_deep_kernel(TickCellArgs a) {
 // A tick's candidates (descending input lengths x its prefill time) against the sorted list
 // s[0] >= ... >= s[JF-1]: once one of them cannot enter the list in any lane, the rest of
 // that tick cannot either.
+// Lengths below `xmin` (block-uniform) cannot reach the cell's percentile under any configuration of the block.
 template <int JF>
-__device__ __forceinline__ void offer_tick(double (&s)[JF], const int32_t* s_top, int T, int q, int nc, double pf) {
+__device__ __forceinline__ void offer_tick(double (&s)[JF], const int32_t* s_top, int T, int q, int nc, int xmin, double pf) {
   for (int x = 0; x < nc; ++x) {
-    double v = (double)s_top[x * T + q] * pf;
+    const int len = __builtin_amdgcn_readfirstlane(s_top[x * T + q]);
+    if (len < xmin) break;
+    double v = (double)len * pf;
     if (__ballot(v > s[JF - 1]) == 0) break;
 #pragma unroll
     for (int i = 0; i < JF; ++i) {
@@ -413,7 +416,7 @@ struct WalkOut {
 // tick TBTs, else the largest tick TBT.
 template <int JF, bool SPARSE, bool SINGLE, bool TWO>
 __device__ __forceinline__ WalkOut walk_ticks(const Lookup& L, int T, int j, const double* s_load, const int32_t* s_cnt,
-                                              const int32_t* s_top, double nd, double tick_s) {
+                                              const int32_t* s_top, int xmin, double nd, double tick_s) {
   double s[JF];
 #pragma unroll
   for (int i = 0; i < JF; ++i) s[i] = i < JF - j ? __builtin_inf() : -__builtin_inf();
@@ -424,7 +427,7 @@ __device__ __forceinline__ WalkOut walk_ticks(const Lookup& L, int T, int j, con
   auto one = [&](int q, int c0, double pf0, double tb0) {
     if (c0 > 0 && j > 0) {                       // block-uniform
       if (SPARSE) tt.offer(tb0, c0); else tbmax = max_num(tbmax, tb0);
-      offer_tick<JF>(s, s_top, T, q, c0 < j ? c0 : j, pf0);
+      offer_tick<JF>(s, s_top, T, q, c0 < j ? c0 : j, xmin, pf0);
     }
   };
   // a tick without requests has load 0: the tables at their first load point, no look-up
@@ -610,7 +613,8 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
   double* s_rgp = smem + (LDS ? (size_t)sa.n_slot * DYN_SLOT_STRIDE(n_rho) : 0);
   double* s_rinv = s_rgp + (n_rho + 2);
   double* s_thr = s_rinv + (n_rho + 1);                         // [n_bucket + 1] when SINGLE
-  double* s_load = s_thr + (SINGLE ? sa.n_bucket + 1 : 0);      // [win_per_block][T]
+  uint32_t* s_ratio = (uint32_t*)(s_thr + (SINGLE ? sa.n_bucket + 1 : 0));   // [4] per wave (two doubles' room)
+  double* s_load = (double*)s_ratio + 2;                        // [win_per_block][T]
   TickPlan* s_plan = (TickPlan*)(s_load + sa.win_per_block * T);   // [win_per_block]
   int32_t* s_cnt = (int32_t*)(s_plan + sa.win_per_block);       // [win_per_block][T] requests per tick
   uint32_t* s_off = (uint32_t*)(s_cnt + sa.win_per_block * T);  // [win_per_block][T] start of the tick's list
@@ -632,9 +636,27 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
     s_off[i] = r.off;
   }
   for (int i = threadIdx.x; i < w1 - w0; i += blockDim.x) s_plan[i] = a.plan[(size_t)(w0 + i) * sa.G + g];
+  {
+    // How far apart a configuration's per-tick prefill times can lie: theta = least / largest entry of its table
+    // row(s), as a float rounded down; the block uses the smallest theta of its configurations.
+    const int k_mine = min(tile * sa.tile + (int)threadIdx.x, sa.K - 1);
+    const DevCfg c = sa.cfg[k_mine];
+    const double* span = a.pfspan + 2 * ((size_t)g * sa.n_tp_f);
+    double mn = span[2 * c.row_lo], mx = span[2 * c.row_lo + 1];
+    if (c.u != 0.0) {
+      mn = min_num(mn, span[2 * c.row_hi]);
+      mx = max_num(mx, span[2 * c.row_hi + 1]);
+    }
+    const float th = (mx > 0.0 && mn > 0.0) ? (float)(mn / mx) * 0.999999f : 0.0f;   // below mn / mx by 2^-21 at least
+    const uint32_t bits = wave_min_u32(__float_as_uint(th));                          // floats >= 0 order like their bits
+    if ((threadIdx.x & (DYN_WAVE - 1)) == 0) s_ratio[threadIdx.x / DYN_WAVE] = bits;
+  }
   __syncthreads();
   CfgState st;
   load_config<LDS>(a, g, tile * sa.tile + (int)threadIdx.x, s_tab, s_rgp, s_rinv, s_thr, s_js, &st);
+  uint32_t ratio_bits = s_ratio[0];
+  for (int i = 1; i < (int)blockDim.x / DYN_WAVE; ++i) ratio_bits = min(ratio_bits, s_ratio[i]);
+  const double theta = (double)__uint_as_float(ratio_bits);
 
   // the cells this kernel walks with candidates: their lists are staged [position][tick]
   auto listed = [&](const TickPlan& p) { return p.j > 0 && !(p.flags & (DYN_TP_GENERAL | DYN_TP_SKIP)); };
@@ -682,17 +704,22 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
     }
     prefetch(w + 1);
 
+    // Pruning: a request of length a < x_j * theta has, under every configuration of the block, TTFT = a * pf <
+    // x_j * (least pf of that configuration) <= the TTFT of each of the j requests of length >= x_j: it lies below the
+    // percentile, which is the j-th largest of what is left all the same.  With flat prefill tables what is left are
+    // the cell's j largest lengths, whichever ticks hold them.
+    const int xmin = (int)((double)pl.xj * theta);
     WalkOut o;
     if (empty || skip) {
-      o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, 0, load_w, cnt_w, top_w, st.nd, a.tick_s);
+      o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, 0, load_w, cnt_w, top_w, 0, st.nd, a.tick_s);
       o.ttft = o.tbt = empty ? 0.0 : __builtin_inf();   // a cell that is not evaluated is reported through the status word
     } else if (pl.flags & DYN_TP_DENSE) {
-      if (j <= 4) o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
-      else if (j <= 8) o = walk_ticks<8, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
-      else o = walk_ticks<kFastDepth, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
+      if (j <= 4) o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, xmin, st.nd, a.tick_s);
+      else if (j <= 8) o = walk_ticks<8, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, xmin, st.nd, a.tick_s);
+      else o = walk_ticks<kFastDepth, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, xmin, st.nd, a.tick_s);
     } else {
-      if (j <= 4) o = walk_ticks<4, true, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
-      else o = walk_ticks<kFastDepth / 2, true, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, st.nd, a.tick_s);
+      if (j <= 4) o = walk_ticks<4, true, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, xmin, st.nd, a.tick_s);
+      else o = walk_ticks<kFastDepth / 2, true, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, xmin, st.nd, a.tick_s);
     }
     emit_cell(sa, st, cell, empty, o.ov, o.e, o.ttft, o.tbt);
   }
@@ -756,8 +783,9 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
   int32_t* s_cnt = (int32_t*)(s_load + T);                      // [T]
   int32_t* s_len = s_cnt + T;                                   // [T] min(j, count)
   int32_t* s_neq = s_len + T;                                   // [T] listed lengths equal to x_j
-  uint32_t* s_lbase = (uint32_t*)(s_neq + T);                   // [T] start of the tick's list; [T]: staged in LDS? [T+1]: lengths above x_j
-  int32_t* s_lists = (int32_t*)(s_lbase + T + 2);               // [kListCap]
+  uint32_t* s_lbase = (uint32_t*)(s_neq + T);                   // [T] start of the tick's list; [T]: entries staged in LDS + 1, or 0; [T+1]: lengths above x_j
+  uint32_t* s_goff = s_lbase + T + 2;                           // [T] start of the tick's list in global memory
+  int32_t* s_lists = (int32_t*)(s_goff + T);                    // [kListCap]
   uint16_t* s_js = (uint16_t*)(s_lists + kListCap);             // [n_bucket + 1]
 
   const uint64_t n_item = (uint64_t)a.counters[1] * (uint64_t)sa.n_tile;   // complete: written by the cell kernel
@@ -776,29 +804,43 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
     const int j = pl.j;
     const bool dense = (pl.flags & DYN_TP_DENSE) != 0;
     const TickRec* rec = a.rec + cell * T;
-    if (tid == 0) {                            // where each tick's list is read from
-      uint32_t total = 0;
-      for (int q = 0; q < T; ++q) total += (uint32_t)min(rec[q].cnt, j);
-      const bool fits = total <= (uint32_t)kListCap;
-      uint32_t at = 0;
-      for (int q = 0; q < T; ++q) {
-        const TickRec r = rec[q];
-        s_load[q] = r.load;
-        s_cnt[q] = r.cnt;
-        s_len[q] = min(r.cnt, j);
-        s_lbase[q] = fits ? at : r.off;
-        at += (uint32_t)min(r.cnt, j);
+    if (tid < DYN_WAVE) {                      // the first wave, a tick per lane: where each tick's list is read from
+      TickRec r;
+      r.load = 0.0; r.off = 0u; r.cnt = 0;
+      if (tid < T) r = rec[tid];
+      const int len = tid < T ? min(r.cnt, j) : 0;
+      int incl = len;                          // inclusive prefix over the ticks
+#pragma unroll
+      for (int d = 1; d < DYN_WAVE; d <<= 1) {
+        const int up = __shfl_up(incl, d, DYN_WAVE);
+        if (tid >= d) incl += up;
       }
-      s_lbase[T] = fits ? 1u : 0u;
-      s_lbase[T + 1] = 0u;
+      const uint32_t total = (uint32_t)__builtin_amdgcn_readlane(incl, DYN_WAVE - 1);
+      const bool fits = total <= (uint32_t)kListCap;
+      if (tid < T) {
+        s_load[tid] = r.load;
+        s_cnt[tid] = r.cnt;
+        s_len[tid] = len;
+        s_goff[tid] = r.off;
+        s_lbase[tid] = fits ? (uint32_t)(incl - len) : r.off;
+      }
+      if (tid == 0) {
+        s_lbase[T] = fits ? total + 1u : 0u;   // 0: the lists stay in global memory
+        s_lbase[T + 1] = 0u;
+      }
     }
     __syncthreads();
     const bool staged = s_lbase[T] != 0u;
-    if (staged) {
-      for (int q = 0; q < T; ++q) {
-        const int32_t* src = a.top + rec[q].off;
-        int32_t* dst = s_lists + s_lbase[q];
-        for (int i = tid; i < s_len[q]; i += NT) dst[i] = src[i];
+    if (staged) {                              // one flat copy: the loads of all ticks are in flight together
+      const int total = (int)s_lbase[T] - 1;
+#pragma unroll 4
+      for (int i = tid; i < total; i += NT) {
+        int l = 0, h = T - 1;                  // the tick whose list holds entry i: the last q with s_lbase[q] <= i
+        while (l < h) {
+          const int mid = (l + h + 1) >> 1;
+          if ((int)s_lbase[mid] <= i) l = mid; else h = mid - 1;
+        }
+        s_lists[i] = a.top[(size_t)s_goff[l] + (uint32_t)(i - (int)s_lbase[l])];
       }
       __syncthreads();
     }
@@ -894,12 +936,12 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
 
 size_t tick_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t n_tick, int32_t win_per_block, bool single) {
   return (size_t)(2 * n_rho + 3) * sizeof(double) + (single ? ((size_t)n_bucket + 1) * sizeof(double) : 0) +
-         (size_t)win_per_block * (n_tick * (sizeof(double) + 2 * sizeof(int32_t)) + sizeof(TickPlan)) +
+         2 * sizeof(double) + (size_t)win_per_block * (n_tick * (sizeof(double) + 2 * sizeof(int32_t)) + sizeof(TickPlan)) +
          (size_t)2 * n_tick * kFastDepth * sizeof(int32_t) + ((size_t)n_bucket + 1) * sizeof(uint16_t) + 8;
 }
 size_t general_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t n_tick, int nt, bool single) {
   return (size_t)(2 * n_rho + 3) * sizeof(double) + (single ? ((size_t)n_bucket + 1) * sizeof(double) : 0) +
-         (size_t)n_tick * nt * sizeof(double) + (size_t)n_tick * (sizeof(double) + 4 * sizeof(int32_t)) +
+         (size_t)n_tick * nt * sizeof(double) + (size_t)n_tick * (sizeof(double) + 5 * sizeof(int32_t)) +
          2 * sizeof(uint32_t) + (size_t)kListCap * sizeof(int32_t) + ((size_t)n_bucket + 1) * sizeof(uint16_t) + 8;
 }
 // Threads of a block of the general kernel: the tile's width, less where the strip (one double per tick and
@@ -921,7 +963,13 @@ void launch_space(const TickArgs& a, dim3 grid, dim3 block, size_t lds, hipStrea
 template <bool LDS, bool SINGLE, bool TWO>
 void launch_general(const TickArgs& a, size_t lds, hipStream_t s) {
   DynTimed timed(DYN_K_TICK_MERGE, s);
-  hipLaunchKernelGGL((tick_general_kernel<LDS, SINGLE, TWO>), dim3(kGeneralBlocks), dim3(general_threads(a)), lds, s, a);
+  // The items are dealt round-robin to the grid: as many blocks as the device holds at once, so that none starts late.
+  const int nt = general_threads(a);
+  int per_cu = 0, blocks = kGeneralBlocks;
+  if (a.n_cu > 0 && hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tick_general_kernel<LDS, SINGLE, TWO>, nt, lds) == hipSuccess &&
+      per_cu > 0)
+    blocks = per_cu * a.n_cu;
+  hipLaunchKernelGGL((tick_general_kernel<LDS, SINGLE, TWO>), dim3(blocks), dim3(nt), lds, s, a);
 }
 
 template <typename F>
