@@ -203,6 +203,36 @@ def test_deep_percentiles_with_load_dependent_prefill(dyn, n_req, NW, T, crowd):
     assert j.max() > 16
 
 
+@pytest.mark.parametrize("kind", ["flat", "zero", "narrow", "wide"])
+@pytest.mark.parametrize("pct", [(99, 100), (9, 10)])
+def test_walk_lists_pruned_by_the_prefill_spread(dyn, kind, pct):
+    """The walk drops list entries below x_j times (least / largest prefill time of the block's table rows).  Flat
+    rows (everything below x_j goes), rows with a zero (nothing may go), rows that differ in the 7th digit (the bound
+    falls between neighbouring lengths) and rows a factor 3 apart, on lengths crowded around the percentile: many equal
+    to x_j, many one below or above it."""
+    w = _random_case(40, 5000, 4, 6, 5.0)
+    rng = np.random.default_rng(41)
+    pf = w["profile"]["prefill_ms_per_tok"]
+    base = rng.uniform(0.05, 0.3, pf.shape[:3] + (1,))
+    if kind == "flat":
+        pf[...] = base
+    elif kind == "zero":
+        pf[...] = base
+        pf[..., 0] = 0.0
+    elif kind == "narrow":
+        pf[...] = base * (1.0 + rng.uniform(-3e-7, 3e-7, pf.shape))
+    else:
+        pf[...] = base * rng.uniform(1.0, 3.0, pf.shape)
+    n = w["trace"]["in_tok"].size
+    w["trace"]["in_tok"] = (1000 + rng.integers(-2, 3, n) * (rng.uniform(0, 1, n) < 0.9)
+                            + rng.integers(-400, 400, n) * (rng.uniform(0, 1, n) < 0.1)).astype(np.int32)
+    w["edges"] = {"in_edge": np.asarray([[1000]], np.int32), "out_edge": np.zeros((1, 0), np.int32)}
+    g, fine = gpu_ticks(dyn, w, 6, pct=pct)
+    o = ora_ticks(w, fine, 6, pct=pct)
+    assert g["status"] == 0
+    assert_same(w, g, o)
+
+
 @pytest.mark.parametrize("pct", [(9, 10), (1, 2), (1, 100)])
 def test_sparse_ticks_take_the_general_route(dyn, pct):
     """Many ticks with one or two requests each and a percentile deeper than any four ticks hold: the TBT percentile
