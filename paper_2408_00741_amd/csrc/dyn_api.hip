@@ -55,7 +55,7 @@ hipError_t dev_alloc(T** p, size_t count) {
 }
 
 void free_profile_device(dyn_profile* p) {
-  void* ptrs[] = {p->d_tab, p->d_ml, p->d_pw0, p->d_pfspan, p->d_gridpack, p->d_jstart, p->d_tstart, p->d_thr, p->d_cfg,
+  void* ptrs[] = {p->d_tab, p->d_ml, p->d_pw0, p->d_pfspan, p->d_theta, p->d_gridpack, p->d_jstart, p->d_tstart, p->d_thr, p->d_cfg,
                   p->d_tile_rows, p->d_slo_ttft, p->d_slo_tbt, p->d_budget, p->d_path_layout, p->d_path_order,
                   p->d_path_seg, p->d_path_trans, p->d_hier_trans, p->d_lay_n, p->d_lay_tp, p->d_tp, p->d_ident};
   for (void* q : ptrs)
@@ -340,6 +340,7 @@ TickWs dyn_tick_ws_layout(int64_t n_req, int64_t coarse_cells, int32_t n_tick, i
   w.counters = off; off += 256;
   w.deep_list = off; off += align256(c * sizeof(uint32_t));
   w.slow_list = off; off += align256(c * sizeof(uint32_t));
+  w.list_cells = off; off += align256(c * sizeof(uint32_t));
   w.total = off;
   return w;
 }
@@ -481,6 +482,7 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
   p->tp.assign(d->tp, d->tp + d->n_tp);
   p->fg.assign(d->f_mhz, d->f_mhz + d->n_f);
   p->d_tab = p->d_ml = p->d_pw0 = p->d_pfspan = p->d_gridpack = nullptr;
+  p->d_theta = nullptr;
   p->d_jstart = nullptr; p->d_tstart = nullptr; p->d_thr = nullptr; p->d_cfg = nullptr; p->d_tile_rows = nullptr;
   p->d_slo_ttft = p->d_slo_tbt = nullptr; p->d_budget = nullptr;
   p->d_path_layout = p->d_path_order = p->d_path_seg = p->d_lay_n = p->d_lay_tp = p->d_tp = p->d_ident = nullptr;
@@ -540,6 +542,17 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
     pfspan[2 * r] = *std::min_element(row, row + d->n_rho);
     pfspan[2 * r + 1] = *std::max_element(row, row + d->n_rho);
   }
+  // per class the least ratio over its rows, as a float below the quotient by 2^-21 at least (0: no bound)
+  std::vector<float> theta(p->G, 0.0f);
+  {
+    const size_t per_class = n_row / (size_t)p->G;
+    for (int g = 0; g < p->G; ++g) {
+      double th = 1.0;
+      for (size_t r = (size_t)g * per_class; r < (size_t)(g + 1) * per_class; ++r)
+        th = (pfspan[2 * r] > 0.0 && pfspan[2 * r + 1] > 0.0) ? std::min(th, pfspan[2 * r] / pfspan[2 * r + 1]) : 0.0;
+      theta[g] = (float)th * 0.999999f;
+    }
+  }
 
   void* fixed_ws = nullptr;
   (void)scratch_address(&fixed_ws);   // set-up of dyn_eval_select_static on this device; that call reports a failure itself
@@ -547,6 +560,7 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
             hip_ok(hipDeviceGetAttribute(&p->n_cu, hipDeviceAttributeMultiprocessorCount, p->device), "hipDeviceGetAttribute") &&
             hip_ok(dev_alloc(&p->d_tab, 3 * n_tab), "hipMalloc") && hip_ok(dev_alloc(&p->d_ml, n_row), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_pw0, n_row), "hipMalloc") && hip_ok(dev_alloc(&p->d_pfspan, 2 * n_row), "hipMalloc") &&
+            hip_ok(dev_alloc(&p->d_theta, (size_t)p->G), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_gridpack, gridpack.size()), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_jstart, js.size()), "hipMalloc") &&
             hip_ok(dev_alloc(&p->d_tstart, tstart.size()), "hipMalloc") && hip_ok(dev_alloc(&p->d_thr, thr.size()), "hipMalloc") &&
@@ -566,6 +580,7 @@ int dyn_profile_load(const dyn_profile_desc* d, void* hip_stream, dyn_profile** 
        hip_ok(hipMemcpyAsync(p->d_ml, d->max_load_tps, n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_pw0, pw0.data(), n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_pfspan, pfspan.data(), 2 * n_row * 8, hipMemcpyHostToDevice, s), "copy") &&
+       hip_ok(hipMemcpyAsync(p->d_theta, theta.data(), (size_t)p->G * 4, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_gridpack, gridpack.data(), gridpack.size() * 8, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_jstart, js.data(), js.size() * 4, hipMemcpyHostToDevice, s), "copy") &&
        hip_ok(hipMemcpyAsync(p->d_tstart, tstart.data(), tstart.size() * 4, hipMemcpyHostToDevice, s), "copy") &&
@@ -788,6 +803,7 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   ca.rec = (TickRec*)(base + w.fine.rec); ca.plan = (TickPlan*)(base + w.plan); ca.top = (int32_t*)(base + w.top);
   ca.cstat = (uint8_t*)(base + w.fine.cstat); ca.header = (WsHeader*)(base + w.fine.header);
   ca.counters = (uint32_t*)(base + w.counters); ca.deep_list = (uint32_t*)(base + w.deep_list); ca.slow_list = (uint32_t*)(base + w.slow_list);
+  ca.list_cells = (uint32_t*)(base + w.list_cells); ca.theta = p->d_theta;
   if (!hip_ok(dyn_launch_tick_cell(ca, s), "tick cell launch")) return DYN_E_DEVICE;
 
   TickArgs ta;

@@ -50,6 +50,7 @@ struct dyn_profile {
   double* d_ml;   // [G][n_tp][n_f]
   double* d_pw0;  // [G][n_tp][n_f]  power at load 0 (first column of d_pw)
   double* d_pfspan;  // [G][n_tp][n_f][2]  smallest and largest prefill time of the row over the load axis
+  float* d_theta;    // [G]  least ratio smallest / largest prefill time over the class's rows, rounded down
   // load grid for the kernels: [-inf, rho[0..n_rho-1], +inf] followed by
   // [0, 1/(rho[1]-rho[0]), ..., 1/(rho[n_rho-1]-rho[n_rho-2]), 0]
   double* d_gridpack;   // [2*n_rho + 3]

@@ -12,7 +12,7 @@ static_assert(DYN_TICK_MAX == DYN_TICK_LIMIT && DYN_TICK_MAX == DYN_WAVE && DYN_
 
 struct TickRec {   // one tick of a (window, class) cell (16 bytes)
   double load;     // (input + output tokens of the tick) / tick_s
-  uint32_t off;    // first request of the tick in the sorted trace = start of the tick's list in `top`
+  uint32_t off;    // first request of the tick in the sorted trace = start of the tick's list in `top` (DYN_TP_TIGHT cells: see there)
   int32_t cnt;     // requests in the tick
 };
 
@@ -22,13 +22,14 @@ struct TickPlan {
   int32_t j;       // 0 = empty cell
   int32_t xj;      // j-th largest input length of the whole cell
   uint32_t flags;  // DYN_TP_*
-  uint32_t pad;
+  uint32_t place;  // DYN_TP_TIGHT: rank of the percentile among the ticks that hold requests of length xj (bit 31: from below)
 };
 #define DYN_TP_DENSE 1u   // every non-empty tick holds at least j requests: the TBT percentile is the largest tick TBT
 #define DYN_TP_SMALL 2u   // the four non-empty ticks of largest TBT hold at least j requests, whichever they are
 #define DYN_TP_DEEP 4u    // j > DYN_TICK_WAVE: lists and xj come from the deep-cell kernel
 #define DYN_TP_SKIP 8u    // j > DYN_TICK_DEPTH: not evaluated
 #define DYN_TP_GENERAL 16u  // left to the general kernel: j beyond the walk's register list, or a TBT percentile that needs all ticks
+#define DYN_TP_TIGHT 32u   // settled by the ticks' requests of length xj (TickRec.off then holds their number, not a list offset)
 
 struct TickCellArgs {
   const int32_t* in; const int32_t* out;
@@ -42,9 +43,11 @@ struct TickCellArgs {
   int32_t* top;              // [n_req]: per tick its min(j, cnt) largest input lengths, descending, at rec.off
   uint8_t* cstat;            // [fine cells] status bytes
   WsHeader* header;
-  uint32_t* counters;        // [0] cells on deep_list, [1] cells on slow_list; zeroed before the cell kernel
+  uint32_t* counters;        // [0] cells on deep_list, [1] cells on slow_list, [2] cells on list_cells; zeroed before the cell kernels
   uint32_t* deep_list;       // [cells]
   uint32_t* slow_list;       // [cells] cells left to the general kernel
+  uint32_t* list_cells;      // [cells] cells that need per-tick lists
+  const float* theta;        // [G] per class: least (smallest / largest prefill time of a table row), rounded down
 };
 
 struct TickArgs {
@@ -67,7 +70,7 @@ struct TickArgs {
 // per-tick lists, the partial selection records of the coarse cells and the two work lists.
 struct TickWs {
   EvalWs fine;      // header, rec (as TickRec) and cstat are used; fine.part is where `plan` starts
-  size_t plan, top, part, counters, deep_list, slow_list, total;
+  size_t plan, top, part, counters, deep_list, slow_list, list_cells, total;
   int32_t n_wslot;
 };
 TickWs dyn_tick_ws_layout(int64_t n_req, int64_t coarse_cells, int32_t n_tick, int32_t K);

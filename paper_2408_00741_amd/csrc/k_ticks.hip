@@ -22,6 +22,7 @@
 //                      order, the TTFT percentile from the bracket [x_j * least, x_j * largest prefill
 //                      time of the ticks]: a single value, or settled by ranking the ticks that hold
 //                      lengths equal to x_j, or bisected on the ticks' sorted lists.
+#include <algorithm>
 #include <type_traits>
 
 #include "dyn_ticks.h"
@@ -44,6 +45,436 @@ static_assert(kDeepCap == 8192, "the deep-cell kernel's LDS buffer");
 __global__ void tick_init_kernel(uint32_t* counters) {
   counters[0] = 0u;
   counters[1] = 0u;
+  counters[2] = 0u;
+}
+
+// How the TBT percentile of a cell can be found (lane q holds tick q's request count, 0 beyond the ticks): from the
+// largest tick TBT when every non-empty tick holds j requests (DENSE); from the four largest tick TBTs when any four
+// non-empty ticks hold j between them: the four smallest counts do, or there are no more than four (SMALL).
+__device__ __forceinline__ uint32_t tbt_route(int32_t cnt_l, int64_t j64, int lane) {
+  uint32_t flags = 0;
+  uint32_t cpos = cnt_l > 0 ? (uint32_t)cnt_l : 0xFFFFFFFFu;
+  if ((int64_t)wave_min_u32(cpos) >= j64) flags |= DYN_TP_DENSE;
+  int64_t s4 = 0;
+  bool all_in = false;
+  for (int r = 0; r < 4; ++r) {
+    const uint32_t mn = wave_min_u32(cpos);
+    if (mn == 0xFFFFFFFFu) { all_in = true; break; }
+    s4 += mn;
+    const uint64_t who = __ballot(cpos == mn);
+    if (lane == (int)__builtin_ctzll(who)) cpos = 0xFFFFFFFFu;
+  }
+  if (all_in || s4 >= j64) flags |= DYN_TP_SMALL;
+  return flags;
+}
+
+// ---- cells settled by their ties at x_j ----------------------------------------------------------
+// With theta_g = the least ratio (smallest / largest prefill time of a table row) over the rows of class g, every
+// configuration of the class has per-tick prefill times within a factor theta_g of each other.  If theta_g * (x_j + 1) > x_j
+// (flat prefill tables: always), a request longer than x_j has a larger TTFT than any request of length x_j, whatever
+// their ticks, and a shorter one a smaller TTFT: the cell's j-th largest TTFT belongs to a request of length x_j, and
+// it is x_j times the prefill time that ranks (j - number of longer requests) from the top among the ticks, each tick
+// counted as often as it holds requests of length x_j.  All the evaluation needs of such a cell is x_j, that rank and
+// the per-tick counts.  A wave takes a cell whose ticks fit its registers (rows of 64 requests, the same number of
+// rows for every tick, two 16-bit lengths to a register), finds x_j by the bit-wise search of the window-level
+// aggregation and counts.  The rank must be at most 4 from the top or from the bottom (the evaluation keeps four ticks).
+// Cells it cannot take (the bound does not hold, ticks too uneven for the registers, token counts of 2^16 or more, a
+// rank beyond four from both ends, a TBT percentile that needs all ticks) are listed for the kernel that builds
+// per-tick lists.
+struct TightCell {
+  uint32_t tok_l;     // lane q: token sum of tick q
+  uint32_t eq_l;      // lane q: requests of length x_j in tick q
+  uint32_t xj, place; // place: the rank among the ticks, from the top, or from the bottom with DYN_TIGHT_FROM_BELOW set
+  uint32_t need;      // the rank from the top
+  bool walk;          // the rank is within four of one end
+};
+#define DYN_TIGHT_FROM_BELOW 0x80000000u
+
+template <int P>   // P registers = 2P rows
+__device__ __forceinline__ bool tight_cell(const int32_t* __restrict__ in, const int32_t* __restrict__ out, int64_t beg_l,
+                                           int32_t cnt_l, int T, int rpt, int m, int rank, float theta, int lane,
+                                           TightCell* res) {
+  uint32_t v[P];
+  uint32_t orv = 0, lmax = 0, lmax2 = 0, tok_acc = 0, tok_l = 0;
+  constexpr int CH = P < 4 ? P : 4;      // registers per round: up to 8 + 8 loads in flight
+  int q = 0, r = 0;                      // tick and row of the slot being filled (wave-uniform)
+#pragma unroll
+  for (int p0 = 0; p0 < P; p0 += CH) {
+    uint32_t a[2 * CH], b[2 * CH];
+    int qs[2 * CH], rs[2 * CH];
+#pragma unroll
+    for (int u = 0; u < 2 * CH; ++u) {
+      qs[u] = q; rs[u] = r;
+      const int64_t beg_q = q < T ? readlane_i64(beg_l, q) : 0;
+      const int left = (q < T ? __builtin_amdgcn_readlane(cnt_l, q) : 0) - r * DYN_WAVE;
+      const bool ok = lane < left;
+      a[u] = ok ? (uint32_t)in[beg_q + r * DYN_WAVE + lane] : 0u;
+      b[u] = ok ? (uint32_t)out[beg_q + r * DYN_WAVE + lane] : 0u;
+      if (++r == rpt) { r = 0; ++q; }
+    }
+#pragma unroll
+    for (int u = 0; u < 2 * CH; ++u) {
+      tok_acc += a[u] + b[u];
+      orv |= a[u] | b[u];
+      if (u % 2 == 0) lmax = max(lmax, a[u]); else lmax2 = max(lmax2, a[u]);
+      if (rs[u] == rpt - 1) {            // the tick's last row: its token sum goes to lane q (below 2^30 when the cell qualifies)
+        const uint32_t tok = wave_sum_u32(tok_acc);
+        if (lane == qs[u]) tok_l = tok;
+        tok_acc = 0;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+      const int left0 = (qs[2 * u] < T ? __builtin_amdgcn_readlane(cnt_l, qs[2 * u]) : 0) - rs[2 * u] * DYN_WAVE;
+      const int left1 = (qs[2 * u + 1] < T ? __builtin_amdgcn_readlane(cnt_l, qs[2 * u + 1]) : 0) - rs[2 * u + 1] * DYN_WAVE;
+      const uint32_t x0 = lane < left0 ? a[2 * u] & 0xFFFFu : 0xFFFFu;
+      const uint32_t x1 = lane < left1 ? a[2 * u + 1] & 0xFFFFu : 0xFFFFu;
+      v[p0 + u] = x0 | (x1 << 16);
+    }
+    // keep the rounds apart: with all loads hoisted to the top 4P loaded values would be live at once
+    if (CH == 4)
+      asm volatile("" : "+v"(tok_acc), "+v"(tok_l), "+v"(orv), "+v"(lmax), "+v"(lmax2), "+v"(v[p0]), "+v"(v[p0 + 1]),
+                   "+v"(v[p0 + 2]), "+v"(v[p0 + 3])::"memory");
+  }
+  orv = wave_or_u32(orv);
+  if (orv >= (1u << 16)) return false;   // wave-uniform
+  const uint32_t top = wave_max_u32(max(lmax, lmax2));
+  uint32_t xj = top;
+  const int j = m - rank + 1;
+  if (rank != m) {
+    uint32_t lo = 0;
+    if (j <= 2 * DYN_WAVE) {
+      const int nb = 32 - __builtin_clz(top | 1u);
+      for (int b = nb - 1; b >= 0; --b) {   // largest c with #{the 128 half-lane maxima >= c} >= j (all elements of the cell)
+        const uint32_t cand = lo | (1u << b);
+        if (__popcll(__ballot(lmax >= cand)) + __popcll(__ballot(lmax2 >= cand)) >= j) lo = cand;
+      }
+    }
+    uint32_t d = 0;
+    const int nb = 32 - __builtin_clz((top - lo) | 1u);
+    for (int b = nb - 1; b >= 0; --b) {
+      const uint32_t cand = lo + (d | (1u << b));
+      const uint16_t cand_lo = (uint16_t)cand;   // low half by a 16-bit compare; high half: hi < cand exactly when the
+      const uint32_t cand_hi = cand << 16;       // whole register < cand << 16
+      int below = 0;
+#pragma unroll
+      for (int i = 0; i < P; ++i)
+        below += __popcll(__ballot((uint16_t)v[i] < cand_lo)) + __popcll(__ballot(v[i] < cand_hi));
+      if (below < rank) d |= 1u << b;
+    }
+    xj = lo + d;
+  }
+  // the bound: theta * (x_j + 1) > x_j, with theta below the true ratio by 2^-21 at least (so that no rounding of the
+  // scaled lengths can turn the order around)
+  if (!((double)theta * ((double)xj + 1.0) > (double)xj)) return false;
+  // longer requests, and per tick the requests of length x_j
+  int n_gt = 0, n_eq = 0, eq_acc = 0;
+  uint32_t eq_l = 0;
+  q = 0; r = 0;
+#pragma unroll
+  for (int i = 0; i < P; ++i) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int left = (q < T ? __builtin_amdgcn_readlane(cnt_l, q) : 0) - r * DYN_WAVE;
+      const uint32_t x = h ? v[i] >> 16 : v[i] & 0xFFFFu;
+      const bool valid = lane < left;
+      n_gt += __popcll(__ballot(valid && x > xj));
+      eq_acc += __popcll(__ballot(valid && x == xj));
+      if (++r == rpt) {
+        if (lane == q) eq_l = (uint32_t)eq_acc;
+        n_eq += eq_acc;
+        eq_acc = 0;
+        r = 0; ++q;
+      }
+    }
+  }
+  const int need = j - n_gt;             // 1 .. n_eq
+  uint32_t place = (uint32_t)need;       // beyond four from both ends: for the general kernel, from the top
+  res->walk = true;
+  if (need > 4) {
+    if (n_eq - need + 1 <= 4) place = (uint32_t)(n_eq - need + 1) | DYN_TIGHT_FROM_BELOW;
+    else res->walk = false;
+  }
+  res->need = (uint32_t)need;
+  res->tok_l = tok_l;
+  res->eq_l = eq_l;
+  res->xj = xj;
+  res->place = place;
+  return true;
+}
+
+__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_waves_per_eu(5, 8))) void tick_tight_kernel(TickCellArgs a) {
+  const int lane = threadIdx.x & (DYN_WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
+  const int T = a.n_tick, G = a.G;
+  const int64_t cells = (int64_t)a.n_window * G;
+  const int64_t c = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (c >= cells) return;
+  if (c == 0 && lane == 0) {                     // single writer of the header
+    a.header->status = 0u;
+    a.header->kind = DYN_WS_KIND_CELLS;
+    a.header->cells = cells * T;
+  }
+  const int64_t w = c / G;
+  const int g = (int)(c % G);
+  const int64_t f0 = (w * T) * G + g;           // fine cell of tick 0; tick q is q*G further
+  int64_t beg_l = 0;
+  int32_t cnt_l = 0;
+  uint32_t bad_l = 0;
+  if (lane < T) {
+    const int64_t f = f0 + (int64_t)lane * G;
+    const int64_t b = a.fine_off[f], e = a.fine_off[f + 1];
+    if (b < 0 || e < b || e > a.n_req) bad_l = DYN_WS_BAD_OFFSETS;   // such a tick is treated as empty
+    else { beg_l = b; cnt_l = (int32_t)(e - b); }
+  }
+  const int64_t m_cell = (int64_t)wave_sum_u64((uint64_t)(uint32_t)cnt_l);
+  const int64_t rank = (a.pct_num * m_cell + a.pct_den - 1) / a.pct_den;
+  const int64_t j64 = m_cell > 0 ? m_cell - rank + 1 : 0;
+  TightCell tc;
+  tc.tok_l = 0; tc.eq_l = 0; tc.xj = 0; tc.place = 0; tc.need = 0; tc.walk = true;
+  uint32_t flags = 0;
+  bool done = m_cell == 0;                       // an empty cell: loads 0, nothing else
+  if (!done) {
+    flags = tbt_route(cnt_l, j64, lane);
+    const int rpt = ((int)wave_max_u32((uint32_t)cnt_l) + DYN_WAVE - 1) / DYN_WAVE;   // rows per tick
+    const int rows = T * rpt;
+    if (rows <= 128) {
+      const float theta = a.theta[g];
+      const int m = (int)m_cell, rk = (int)rank;
+      if (rows <= 4) done = tight_cell<2>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, &tc);
+      else if (rows <= 8) done = tight_cell<4>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, &tc);
+      else if (rows <= 16) done = tight_cell<8>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, &tc);
+      else if (rows <= 32) done = tight_cell<16>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, &tc);
+      else if (rows <= 64) done = tight_cell<32>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, &tc);
+      else done = tight_cell<64>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, &tc);
+      if (done) {
+        flags |= DYN_TP_TIGHT;
+        // the walk keeps four ticks and finds the TBT percentile from the largest tick TBT or the four largest
+        if (!tc.walk || !(flags & (DYN_TP_DENSE | DYN_TP_SMALL))) {
+          flags |= DYN_TP_GENERAL;
+          tc.place = tc.need;
+        }
+      }
+    }
+  }
+  if (!done) {                                   // the kernel that builds per-tick lists writes everything about this cell
+    if (lane == 0) a.list_cells[atomicAdd(&a.counters[2], 1u)] = (uint32_t)c;
+    return;
+  }
+  if (lane < T) {
+    TickRec r;
+    r.load = div_by((double)tc.tok_l, a.tick_s, a.r_tick);
+    r.off = tc.eq_l;                             // no list: the tick's requests of length x_j
+    r.cnt = cnt_l;
+    a.rec[c * T + lane] = r;
+    a.cstat[f0 + (int64_t)lane * G] = (uint8_t)bad_l;   // every fine cell writes its own status byte
+  }
+  if (lane == 0) {
+    TickPlan p;
+    p.j = (int32_t)j64;
+    p.xj = (int32_t)tc.xj;
+    p.flags = flags;
+    p.place = tc.place;
+    a.plan[c] = p;
+    if (flags & DYN_TP_GENERAL) a.slow_list[atomicAdd(&a.counters[1], 1u)] = (uint32_t)c;
+  }
+}
+
+// The same for the listed cells whose ticks do not fit one wave's registers: a block per cell, wave w takes the ticks
+// w, w + 4, ...; x_j by the bit-wise search with the waves' counts added up through LDS (one barrier per bit).  A cell
+// it settles is taken off the list (its entry becomes DYN_LIST_DONE).
+#define DYN_LIST_DONE 0xFFFFFFFFu
+constexpr int kTightBlocks = 1024;
+
+template <int P>   // P registers = 2P rows per wave
+__device__ __forceinline__ bool tight_cell_block(const int32_t* __restrict__ in, const int32_t* __restrict__ out,
+                                                 int64_t beg_l, int32_t cnt_l, int T, int rpt, int m, int rank, float theta,
+                                                 int lane, int wave, uint32_t* s_x /* [2][kWavesPerBlock] */, TightCell* res) {
+  uint32_t v[P];
+  uint32_t orv = 0, vmax = 0, tok_acc = 0, tok_l = 0;
+  constexpr int CH = 4;
+  int q = wave, r = 0;                   // tick and row of the slot being filled (wave-uniform)
+#pragma unroll
+  for (int p0 = 0; p0 < P; p0 += CH) {
+    uint32_t a[2 * CH], b[2 * CH];
+    int qs[2 * CH], rs[2 * CH];
+#pragma unroll
+    for (int u = 0; u < 2 * CH; ++u) {
+      qs[u] = q; rs[u] = r;
+      const int64_t beg_q = q < T ? readlane_i64(beg_l, q) : 0;
+      const int left = (q < T ? __builtin_amdgcn_readlane(cnt_l, q) : 0) - r * DYN_WAVE;
+      const bool ok = lane < left;
+      a[u] = ok ? (uint32_t)in[beg_q + r * DYN_WAVE + lane] : 0u;
+      b[u] = ok ? (uint32_t)out[beg_q + r * DYN_WAVE + lane] : 0u;
+      if (++r == rpt) { r = 0; q += kWavesPerBlock; }
+    }
+#pragma unroll
+    for (int u = 0; u < 2 * CH; ++u) {
+      tok_acc += a[u] + b[u];
+      orv |= a[u] | b[u];
+      vmax = max(vmax, a[u]);
+      if (rs[u] == rpt - 1) {
+        const uint32_t tok = wave_sum_u32(tok_acc);
+        if (lane == qs[u]) tok_l = tok;
+        tok_acc = 0;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < CH; ++u) {
+      const int left0 = (qs[2 * u] < T ? __builtin_amdgcn_readlane(cnt_l, qs[2 * u]) : 0) - rs[2 * u] * DYN_WAVE;
+      const int left1 = (qs[2 * u + 1] < T ? __builtin_amdgcn_readlane(cnt_l, qs[2 * u + 1]) : 0) - rs[2 * u + 1] * DYN_WAVE;
+      const uint32_t x0 = lane < left0 ? a[2 * u] & 0xFFFFu : 0xFFFFu;
+      const uint32_t x1 = lane < left1 ? a[2 * u + 1] & 0xFFFFu : 0xFFFFu;
+      v[p0 + u] = x0 | (x1 << 16);
+    }
+    asm volatile("" : "+v"(tok_acc), "+v"(tok_l), "+v"(orv), "+v"(vmax), "+v"(v[p0]), "+v"(v[p0 + 1]), "+v"(v[p0 + 2]),
+                 "+v"(v[p0 + 3])::"memory");
+  }
+  // sums over the block: every wave writes its word, a barrier, every wave reads all four (two buffers in turn)
+  int turn = 0;
+  auto block_or = [&](uint32_t x) {
+    if (lane == 0) s_x[turn * kWavesPerBlock + wave] = x;
+    __syncthreads();
+    uint32_t all = 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) all |= s_x[turn * kWavesPerBlock + w];
+    turn ^= 1;
+    return all;
+  };
+  auto block_max = [&](uint32_t x) {
+    if (lane == 0) s_x[turn * kWavesPerBlock + wave] = x;
+    __syncthreads();
+    uint32_t all = 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) all = max(all, s_x[turn * kWavesPerBlock + w]);
+    turn ^= 1;
+    return all;
+  };
+  auto block_sum = [&](uint32_t x) {
+    if (lane == 0) s_x[turn * kWavesPerBlock + wave] = x;
+    __syncthreads();
+    uint32_t all = 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) all += s_x[turn * kWavesPerBlock + w];
+    turn ^= 1;
+    return all;
+  };
+  const uint32_t all_or = block_or(wave_or_u32(orv));
+  const uint32_t top = block_max(wave_max_u32(vmax));
+  if (all_or >= (1u << 16)) return false;   // block-uniform
+  uint32_t xj = top;
+  const int j = m - rank + 1;
+  if (rank != m) {
+    uint32_t d = 0;
+    const int nb = 32 - __builtin_clz(top | 1u);
+    for (int b = nb - 1; b >= 0; --b) {
+      const uint32_t cand = d | (1u << b);
+      const uint16_t cand_lo = (uint16_t)cand;
+      const uint32_t cand_hi = cand << 16;
+      int below = 0;
+#pragma unroll
+      for (int i = 0; i < P; ++i)
+        below += __popcll(__ballot((uint16_t)v[i] < cand_lo)) + __popcll(__ballot(v[i] < cand_hi));
+      if ((int)block_sum((uint32_t)below) < rank) d |= 1u << b;
+    }
+    xj = d;
+  }
+  if (!((double)theta * ((double)xj + 1.0) > (double)xj)) return false;
+  int n_gt = 0, n_eq = 0, eq_acc = 0;
+  uint32_t eq_l = 0;
+  q = wave; r = 0;
+#pragma unroll
+  for (int i = 0; i < P; ++i) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int left = (q < T ? __builtin_amdgcn_readlane(cnt_l, q) : 0) - r * DYN_WAVE;
+      const uint32_t x = h ? v[i] >> 16 : v[i] & 0xFFFFu;
+      const bool valid = lane < left;
+      n_gt += __popcll(__ballot(valid && x > xj));
+      eq_acc += __popcll(__ballot(valid && x == xj));
+      if (++r == rpt) {
+        if (lane == q) eq_l = (uint32_t)eq_acc;
+        n_eq += eq_acc;
+        eq_acc = 0;
+        r = 0; q += kWavesPerBlock;
+      }
+    }
+  }
+  n_gt = (int)block_sum((uint32_t)n_gt);
+  n_eq = (int)block_sum((uint32_t)n_eq);
+  const int need = j - n_gt;
+  uint32_t place = (uint32_t)need;
+  res->walk = true;
+  if (need > 4) {
+    if (n_eq - need + 1 <= 4) place = (uint32_t)(n_eq - need + 1) | DYN_TIGHT_FROM_BELOW;
+    else res->walk = false;
+  }
+  res->need = (uint32_t)need;
+  res->tok_l = tok_l;                    // lanes q with q % 4 == wave
+  res->eq_l = eq_l;
+  res->xj = xj;
+  res->place = place;
+  return true;
+}
+
+__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_tight_block_kernel(TickCellArgs a) {
+  __shared__ uint32_t s_x[2 * kWavesPerBlock];
+  const int lane = threadIdx.x & (DYN_WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
+  const int T = a.n_tick, G = a.G;
+  const uint32_t n_item = a.counters[2];         // complete: written by the kernel before this one
+  for (uint32_t item = blockIdx.x; item < n_item; item += gridDim.x) {
+    const int64_t c = a.list_cells[item];
+    const int64_t w = c / G;
+    const int g = (int)(c % G);
+    const int64_t f0 = (w * T) * G + g;
+    int64_t beg_l = 0;
+    int32_t cnt_l = 0;
+    uint32_t bad_l = 0;
+    if (lane < T) {
+      const int64_t f = f0 + (int64_t)lane * G;
+      const int64_t b = a.fine_off[f], e = a.fine_off[f + 1];
+      if (b < 0 || e < b || e > a.n_req) bad_l = DYN_WS_BAD_OFFSETS;
+      else { beg_l = b; cnt_l = (int32_t)(e - b); }
+    }
+    const int64_t m_cell = (int64_t)wave_sum_u64((uint64_t)(uint32_t)cnt_l);
+    const int64_t rank = (a.pct_num * m_cell + a.pct_den - 1) / a.pct_den;
+    const int64_t j64 = m_cell > 0 ? m_cell - rank + 1 : 0;
+    const int rpt = ((int)wave_max_u32((uint32_t)cnt_l) + DYN_WAVE - 1) / DYN_WAVE;
+    const int rows = ((T + kWavesPerBlock - 1) / kWavesPerBlock) * rpt;   // rows of the wave with most ticks
+    TightCell tc;
+    tc.tok_l = 0; tc.eq_l = 0; tc.xj = 0; tc.place = 0; tc.need = 0; tc.walk = true;
+    bool done = false;                           // block-uniform from here on
+    if (m_cell > 0 && m_cell < (1 << 24) && rows <= 128) {
+      const float theta = a.theta[g];
+      const int m = (int)m_cell, rk = (int)rank;
+      if (rows <= 32) done = tight_cell_block<16>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, wave, s_x, &tc);
+      else if (rows <= 64) done = tight_cell_block<32>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, wave, s_x, &tc);
+      else done = tight_cell_block<64>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, wave, s_x, &tc);
+    }
+    __syncthreads();                             // s_x is reused by the next item
+    if (!done) continue;
+    uint32_t flags = tbt_route(cnt_l, j64, lane) | DYN_TP_TIGHT;
+    if (!tc.walk || !(flags & (DYN_TP_DENSE | DYN_TP_SMALL))) {
+      flags |= DYN_TP_GENERAL;
+      tc.place = tc.need;
+    }
+    if (lane < T && (lane % kWavesPerBlock) == wave) {   // the wave that walked the tick
+      TickRec r;
+      r.load = div_by((double)tc.tok_l, a.tick_s, a.r_tick);
+      r.off = tc.eq_l;
+      r.cnt = cnt_l;
+      a.rec[c * T + lane] = r;
+      a.cstat[f0 + (int64_t)lane * G] = (uint8_t)bad_l;
+    }
+    if (threadIdx.x == 0) {
+      TickPlan p;
+      p.j = (int32_t)j64;
+      p.xj = (int32_t)tc.xj;
+      p.flags = flags;
+      p.place = tc.place;
+      a.plan[c] = p;
+      if (flags & DYN_TP_GENERAL) a.slow_list[atomicAdd(&a.counters[1], 1u)] = (uint32_t)c;
+      a.list_cells[item] = DYN_LIST_DONE;
+    }
+  }
 }
 
 // ---- per-tick loads and candidate lists ------------------------------------------------------
@@ -61,9 +492,10 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
   const int lane = threadIdx.x & (DYN_WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
   const int T = a.n_tick, G = a.G;
-  const int64_t cells = (int64_t)a.n_window * G;
-  const int64_t c = (int64_t)blockIdx.x * kWavesPerBlock + wave;
-  if (c >= cells) return;
+  const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (item >= (int64_t)a.counters[2]) return;   // complete: written by the kernel before this one
+  if (a.list_cells[item] == DYN_LIST_DONE) return;   // settled by the kernel before this one
+  const int64_t c = a.list_cells[item];
   const int64_t w = c / G;
   const int g = (int)(c % G);
   const int64_t f0 = (w * T) * G + g;           // fine cell of tick 0; tick q is q*G further
@@ -89,18 +521,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
   // (the four smallest counts do, or there are no more than four).
   uint32_t flags = skip ? DYN_TP_SKIP : (deep ? DYN_TP_DEEP : 0u);
   if (m_cell > 0) {
-    uint32_t cpos = cnt_l > 0 ? (uint32_t)cnt_l : 0xFFFFFFFFu;
-    if ((int64_t)wave_min_u32(cpos) >= j64) flags |= DYN_TP_DENSE;
-    int64_t s4 = 0;
-    bool all_in = false;
-    for (int r = 0; r < 4; ++r) {
-      const uint32_t mn = wave_min_u32(cpos);
-      if (mn == 0xFFFFFFFFu) { all_in = true; break; }
-      s4 += mn;
-      const uint64_t who = __ballot(cpos == mn);
-      if (lane == (int)__builtin_ctzll(who)) cpos = 0xFFFFFFFFu;
-    }
-    if (all_in || s4 >= j64) flags |= DYN_TP_SMALL;
+    flags |= tbt_route(cnt_l, j64, lane);
     // the walk kernel keeps a register list of 16 candidates beside the largest tick TBT, of 8 beside the four largest
     const bool walk = ((flags & DYN_TP_DENSE) && j64 <= kFastDepth) || ((flags & DYN_TP_SMALL) && j64 <= kFastDepth / 2);
     if (!skip && !walk) flags |= DYN_TP_GENERAL;
@@ -226,15 +647,10 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
     p.j = skip ? 0x7FFFFFFF : (int32_t)j64;
     p.xj = xj < 0 ? 0 : xj;
     p.flags = flags;
-    p.pad = 0;
+    p.place = 0;
     a.plan[c] = p;
     if (deep) a.deep_list[atomicAdd(&a.counters[0], 1u)] = (uint32_t)c;
     if (flags & DYN_TP_GENERAL) a.slow_list[atomicAdd(&a.counters[1], 1u)] = (uint32_t)c;
-  }
-  if (c == 0 && lane == 0) {                     // single writer of the header
-    a.header->status = 0u;
-    a.header->kind = DYN_WS_KIND_CELLS;
-    a.header->cells = cells * T;
   }
 }
 
@@ -414,12 +830,21 @@ struct WalkOut {
 // candidates go through a sorted list that starts with JF - j copies of +inf, so that its last entry is the j-th
 // largest of what was inserted (j == 0: nothing is inserted).  SPARSE: the TBT percentile from the four largest
 // tick TBTs, else the largest tick TBT.
-template <int JF, bool SPARSE, bool SINGLE, bool TWO>
+// TIGHT: the TTFT percentile is x_j times the prefill time of rank `place` (bit 31: from below) among the ticks, each
+// counted as often as it holds requests of length x_j (`s_top`: that number per tick; `xmin` carries x_j): the four
+// largest (smallest) prefill times are kept with their counts.
+template <int JF, bool SPARSE, bool SINGLE, bool TWO, bool TIGHT = false>
 __device__ __forceinline__ WalkOut walk_ticks(const Lookup& L, int T, int j, const double* s_load, const int32_t* s_cnt,
-                                              const int32_t* s_top, int xmin, double nd, double tick_s) {
+                                              const int32_t* s_top, int xmin, double nd, double tick_s, uint32_t place = 0) {
   double s[JF];
+  int wt[TIGHT ? JF : 1];
+  const double sign = (place & DYN_TIGHT_FROM_BELOW) ? -1.0 : 1.0;
 #pragma unroll
-  for (int i = 0; i < JF; ++i) s[i] = i < JF - j ? __builtin_inf() : -__builtin_inf();
+  for (int i = 0; i < JF; ++i) s[i] = (!TIGHT && i < JF - j) ? __builtin_inf() : -__builtin_inf();
+  if (TIGHT) {
+#pragma unroll
+    for (int i = 0; i < JF; ++i) wt[i] = 0;
+  }
   double e = 0.0, tbmax = -__builtin_inf();
   TbtTop tt;
   if (SPARSE) tt.clear();
@@ -427,7 +852,25 @@ __device__ __forceinline__ WalkOut walk_ticks(const Lookup& L, int T, int j, con
   auto one = [&](int q, int c0, double pf0, double tb0) {
     if (c0 > 0 && j > 0) {                       // block-uniform
       if (SPARSE) tt.offer(tb0, c0); else tbmax = max_num(tbmax, tb0);
-      offer_tick<JF>(s, s_top, T, q, c0 < j ? c0 : j, xmin, pf0);
+      if (TIGHT) {
+        const int eq = __builtin_amdgcn_readfirstlane(s_top[q]);
+        double key = pf0 * sign;
+        if (eq > 0 && __ballot(key > s[JF - 1]) != 0) {
+          int w_in = eq;
+#pragma unroll
+          for (int i = 0; i < JF; ++i) {
+            const bool gt = key > s[i];
+            const double tk = s[i];
+            const int tw = wt[i];
+            s[i] = gt ? key : tk;
+            wt[i] = gt ? w_in : tw;
+            key = gt ? tk : key;
+            w_in = gt ? tw : w_in;
+          }
+        }
+      } else {
+        offer_tick<JF>(s, s_top, T, q, c0 < j ? c0 : j, xmin, pf0);
+      }
     }
   };
   // a tick without requests has load 0: the tables at their first load point, no look-up
@@ -472,6 +915,20 @@ __device__ __forceinline__ WalkOut walk_ticks(const Lookup& L, int T, int j, con
   }
   WalkOut r;
   r.e = e; r.ov = ov; r.ttft = s[JF - 1];
+  if (TIGHT) {
+    const int want = (int)(place & ~DYN_TIGHT_FROM_BELOW);
+    double pick = s[JF - 1];
+    int cum = 0;
+    bool found = false;
+#pragma unroll
+    for (int i = 0; i < JF; ++i) {
+      cum += wt[i];
+      const bool hit = !found && cum >= want;
+      pick = hit ? s[i] : pick;
+      found = found || hit;
+    }
+    r.ttft = (double)xmin * (pick * sign);
+  }
   r.tbt = SPARSE ? tt.jth(j) : tbmax;
   return r;
 }
@@ -659,7 +1116,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
   const double theta = (double)__uint_as_float(ratio_bits);
 
   // the cells this kernel walks with candidates: their lists are staged [position][tick]
-  auto listed = [&](const TickPlan& p) { return p.j > 0 && !(p.flags & (DYN_TP_GENERAL | DYN_TP_SKIP)); };
+  auto listed = [&](const TickPlan& p) { return p.j > 0 && !(p.flags & (DYN_TP_GENERAL | DYN_TP_SKIP | DYN_TP_TIGHT)); };
   int32_t pre[NPRE];
   auto prefetch = [&](int w) {
     if (w >= w1) return;
@@ -713,6 +1170,10 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
     if (empty || skip) {
       o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, 0, load_w, cnt_w, top_w, 0, st.nd, a.tick_s);
       o.ttft = o.tbt = empty ? 0.0 : __builtin_inf();   // a cell that is not evaluated is reported through the status word
+    } else if (pl.flags & DYN_TP_TIGHT) {          // no lists: the ticks' counts of requests of length x_j sit where the list offsets would
+      const int32_t* eq_w = (const int32_t*)s_off + (w - w0) * T;
+      if (pl.flags & DYN_TP_DENSE) o = walk_ticks<4, false, SINGLE, TWO, true>(st.L, T, j, load_w, cnt_w, eq_w, pl.xj, st.nd, a.tick_s, pl.place);
+      else o = walk_ticks<4, true, SINGLE, TWO, true>(st.L, T, j, load_w, cnt_w, eq_w, pl.xj, st.nd, a.tick_s, pl.place);
     } else if (pl.flags & DYN_TP_DENSE) {
       if (j <= 4) o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, xmin, st.nd, a.tick_s);
       else if (j <= 8) o = walk_ticks<8, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, xmin, st.nd, a.tick_s);
@@ -803,12 +1264,13 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
     const TickPlan pl = a.plan[cell];
     const int j = pl.j;
     const bool dense = (pl.flags & DYN_TP_DENSE) != 0;
+    const bool tight = (pl.flags & DYN_TP_TIGHT) != 0;   // no lists: per tick the number of requests of length x_j, and the rank among them
     const TickRec* rec = a.rec + cell * T;
     if (tid < DYN_WAVE) {                      // the first wave, a tick per lane: where each tick's list is read from
       TickRec r;
       r.load = 0.0; r.off = 0u; r.cnt = 0;
       if (tid < T) r = rec[tid];
-      const int len = tid < T ? min(r.cnt, j) : 0;
+      const int len = (tid < T && !tight) ? min(r.cnt, j) : 0;
       int incl = len;                          // inclusive prefix over the ticks
 #pragma unroll
       for (int d = 1; d < DYN_WAVE; d <<= 1) {
@@ -823,6 +1285,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
         s_len[tid] = len;
         s_goff[tid] = r.off;
         s_lbase[tid] = fits ? (uint32_t)(incl - len) : r.off;
+        if (tight) s_neq[tid] = (int32_t)r.off;
       }
       if (tid == 0) {
         s_lbase[T] = fits ? total + 1u : 0u;   // 0: the lists stay in global memory
@@ -845,7 +1308,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
       __syncthreads();
     }
     const int32_t* lists = staged ? s_lists : a.top;
-    if (tid < T) {                             // per tick: listed lengths above x_j and equal to it (the list is descending)
+    if (tid < T && !tight) {                   // per tick: listed lengths above x_j and equal to it (the list is descending)
       const int len = s_len[tid];
       const int32_t* lq = lists + s_lbase[tid];
       int l = 0, h = len;                      // first entry <= x_j
@@ -864,7 +1327,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
     }
     __syncthreads();
     const double xj = (double)pl.xj;
-    const int need_eq = j - (int)s_lbase[T + 1];   // >= 1: fewer than j lengths lie above the j-th largest
+    const int need_eq = tight ? (int)pl.place : j - (int)s_lbase[T + 1];   // >= 1: fewer than j lengths lie above the j-th largest
 
     for (int sub = 0; sub < sa.tile; sub += NT) {
       const bool in_tile = sub + (tid & ~(DYN_WAVE - 1)) < sa.tile;   // wave-uniform: a wave past the tile's end stores nothing
@@ -899,7 +1362,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
       // TTFT percentile
       double lo = xj * pf_min, hi = xj * pf_max;
       bool open = lo != hi;
-      if (open && xj * pf_max < (xj + 0.5) * pf_min) {
+      if (tight || (open && xj * pf_max < (xj + 0.5) * pf_min)) {
         // only lengths equal to x_j scale into the bracket: rank the ticks' prefill times by those
         lo = hi = xj * weighted_from_top(s_strip, s_neq, T, NT, need_eq, tid);
         open = false;
@@ -990,6 +1453,8 @@ hipError_t dyn_launch_tick_cell(const TickCellArgs& a, hipStream_t s) {
   const int64_t blocks = (cells + kWavesPerBlock - 1) / kWavesPerBlock;
   DynTimed timed(DYN_K_TICK_TOP, s);
   hipLaunchKernelGGL(tick_init_kernel, dim3(1), dim3(1), 0, s, a.counters);
+  hipLaunchKernelGGL(tick_tight_kernel, dim3((unsigned)blocks), dim3(kWavesPerBlock * DYN_WAVE), 0, s, a);
+  hipLaunchKernelGGL(tick_tight_block_kernel, dim3(kTightBlocks), dim3(kWavesPerBlock * DYN_WAVE), 0, s, a);
   hipLaunchKernelGGL(tick_cell_kernel, dim3((unsigned)blocks), dim3(kWavesPerBlock * DYN_WAVE), 0, s, a);
   hipLaunchKernelGGL(tick_deep_kernel, dim3(kDeepBlocks), dim3(256), 0, s, a);
   return hipGetLastError();
