@@ -233,6 +233,34 @@ def test_walk_lists_pruned_by_the_prefill_spread(dyn, kind, pct):
     assert_same(w, g, o)
 
 
+@pytest.mark.parametrize("kind", ["few-values", "narrow-range", "wide-tokens", "crowded-tick", "big-cells"])
+@pytest.mark.parametrize("pct", [(99, 100), (1, 2), (1, 1)])
+def test_cells_settled_by_their_ties(dyn, kind, pct):
+    """Flat prefill tables (the percentile belongs to a request of length x_j, found from the ticks' counts of such
+    requests) with: lengths from five values (the rank among the ties lies beyond four from both ends: all ticks are
+    ranked), lengths from a range of 270 values at about six requests per value (ranks within four of the top and of
+    the bottom), one token count of 2^16 and more in some cells (those build per-tick lists), half of the trace in one
+    tick (too uneven for one wave's registers), and cells of 10^4 requests (a block per cell)."""
+    big = kind == "big-cells"
+    w = _random_case(50, 60_000 if big else 13_000, 3 if big else 4, 12, 5.0, crowd=3 if kind == "crowded-tick" else None)
+    rng = np.random.default_rng(51)
+    pf = w["profile"]["prefill_ms_per_tok"]
+    pf[...] = rng.uniform(0.05, 0.3, pf.shape[:3] + (1,))
+    n = w["trace"]["in_tok"].size
+    if kind == "few-values":
+        w["trace"]["in_tok"] = rng.choice(np.asarray([900, 950, 1000, 1050, 1100], np.int32), n)
+    else:
+        w["trace"]["in_tok"] = rng.integers(1000, 1270, n).astype(np.int32)
+    if kind == "wide-tokens":
+        w["trace"]["out_tok"][rng.integers(0, n, 4)] = 70_000
+        w["trace"]["in_tok"][rng.integers(0, n, 2)] = 65_536
+    w["edges"] = {"in_edge": np.asarray([[1100]], np.int32), "out_edge": np.zeros((1, 0), np.int32)}
+    g, fine = gpu_ticks(dyn, w, 12, pct=pct)
+    o = ora_ticks(w, fine, 12, pct=pct)
+    assert g["status"] == 0
+    assert_same(w, g, o)
+
+
 @pytest.mark.parametrize("pct", [(9, 10), (1, 2), (1, 100)])
 def test_sparse_ticks_take_the_general_route(dyn, pct):
     """Many ticks with one or two requests each and a percentile deeper than any four ticks hold: the TBT percentile
