@@ -4,10 +4,13 @@
 // order, and the cell offsets are read off the sorted keys.
 //
 // A trace that is already in window order (a request log is in time order) does not need the
-// general sort: the key kernel notices it (a flag in the workspace header stays 0; it also
-// writes where every window starts), the host reads the flag, and one block per window then
-// counts its requests by class and moves them, stably, to their cells (window_sort_kernel).
-// Any other trace takes the radix sort.
+// general sort: the key kernel notices it (a flag word in the workspace header stays 0; it also
+// writes where every window starts), and one block per window then counts its requests by class
+// and moves them, stably, to their cells (window_sort_kernel).  Any other trace takes the radix
+// sort.  The host does not read the flag: both routes are enqueued and the kernels of the route
+// not taken return at their first instruction.  The general sort is one cooperative launch (a grid
+// the device holds at once, grid-wide barriers between the phases), so the route not taken costs
+// one empty launch; where cooperative launches are not available it is the separate kernels below.
 //
 // One radix pass = per-block digit histogram -> exclusive scan of the (digit, block)
 // counters -> stable scatter.  Inside a block every wave owns a contiguous run of rows of
@@ -16,6 +19,9 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
+
+#include <hip/hip_cooperative_groups.h>
 
 #include "dyn_internal.h"
 #include "dyn_device.h"
@@ -131,23 +137,28 @@ __global__ void edge_store_kernel(EdgePack p, int n_a, int32_t* __restrict__ dst
   }
 }
 
-// digit counts of one block's tile -> block_hist[digit * n_block + block]
-__global__ __launch_bounds__(kWaves* DYN_WAVE) void hist_kernel(const uint32_t* __restrict__ keys, int64_t n,
-                                                                int shift, int bits, uint32_t* __restrict__ block_hist,
-                                                                int64_t n_block, const uint32_t* __restrict__ order) {
-  if (!sort_route(order)) return;
-  __shared__ uint32_t cnt[DYN_INGEST_MAX_BINS];
+// digit counts of one tile -> block_hist[digit * n_block + tile]; `cnt` is DYN_INGEST_MAX_BINS words of LDS
+__device__ __forceinline__ void hist_tile(int64_t tile, const uint32_t* keys, int64_t n, int shift, int bits,
+                                          uint32_t* block_hist, int64_t n_block, uint32_t* cnt) {
   const int nbins = 1 << bits;
   const uint32_t mask = (uint32_t)nbins - 1u;
   for (int b = threadIdx.x; b < nbins; b += blockDim.x) cnt[b] = 0;
   __syncthreads();
-  const int64_t base = (int64_t)blockIdx.x * kTile;
+  const int64_t base = tile * kTile;
   for (int r = 0; r < kTile / (kWaves * DYN_WAVE); ++r) {
     const int64_t idx = base + (int64_t)r * (kWaves * DYN_WAVE) + threadIdx.x;
     if (idx < n) atomicAdd(&cnt[(keys[idx] >> shift) & mask], 1u);
   }
   __syncthreads();
-  for (int b = threadIdx.x; b < nbins; b += blockDim.x) block_hist[(size_t)b * n_block + blockIdx.x] = cnt[b];
+  for (int b = threadIdx.x; b < nbins; b += blockDim.x) block_hist[(size_t)b * n_block + tile] = cnt[b];
+}
+
+__global__ __launch_bounds__(kWaves* DYN_WAVE) void hist_kernel(const uint32_t* __restrict__ keys, int64_t n,
+                                                                int shift, int bits, uint32_t* __restrict__ block_hist,
+                                                                int64_t n_block, const uint32_t* __restrict__ order) {
+  if (!sort_route(order)) return;
+  __shared__ uint32_t cnt[DYN_INGEST_MAX_BINS];
+  hist_tile(blockIdx.x, keys, n, shift, bits, block_hist, n_block, cnt);
 }
 
 // ---- exclusive scan of `count` uint32 counters in three small kernels --------------------
@@ -171,11 +182,8 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_
   return off + incl - v;
 }
 
-__global__ __launch_bounds__(256) void scan_reduce_kernel(const uint32_t* __restrict__ x, int64_t count,
-                                                          uint32_t* __restrict__ partial, const uint32_t* __restrict__ order) {
-  if (!sort_route(order)) return;
-  __shared__ uint32_t s_wave[4];
-  const int64_t base = (int64_t)blockIdx.x * kScanChunk;
+__device__ __forceinline__ void scan_reduce_chunk(int64_t chunk, const uint32_t* x, int64_t count, uint32_t* partial, uint32_t* s_wave) {
+  const int64_t base = chunk * kScanChunk;
   uint32_t v = 0;
   for (int q = 0; q < kScanChunk / 256; ++q) {
     const int64_t i = base + q * 256 + threadIdx.x;
@@ -183,12 +191,10 @@ __global__ __launch_bounds__(256) void scan_reduce_kernel(const uint32_t* __rest
   }
   uint32_t tot;
   block_exclusive_scan_256(v, &tot, s_wave);
-  if (threadIdx.x == 0) partial[blockIdx.x] = tot;
+  if (threadIdx.x == 0) partial[chunk] = tot;
 }
 
-__global__ __launch_bounds__(256) void scan_partials_kernel(uint32_t* __restrict__ partial, int64_t n_partial, const uint32_t* __restrict__ order) {
-  if (!sort_route(order)) return;
-  __shared__ uint32_t s_wave[4];
+__device__ __forceinline__ void scan_partials_all(uint32_t* partial, int64_t n_partial, uint32_t* s_wave) {
   uint32_t carry = 0;
   for (int64_t base = 0; base < n_partial; base += 256) {
     const int64_t i = base + threadIdx.x;
@@ -200,13 +206,10 @@ __global__ __launch_bounds__(256) void scan_partials_kernel(uint32_t* __restrict
   }
 }
 
-__global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ x, int64_t count,
-                                                         const uint32_t* __restrict__ partial, const uint32_t* __restrict__ order) {
-  if (!sort_route(order)) return;
-  __shared__ uint32_t s_wave[4];
-  // thread t owns 16 consecutive counters of the block's chunk
+__device__ __forceinline__ void scan_apply_chunk(int64_t chunk, uint32_t* x, int64_t count, const uint32_t* partial, uint32_t* s_wave) {
+  // thread t owns 16 consecutive counters of the chunk
   constexpr int per = kScanChunk / 256;
-  const int64_t base = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * per;
+  const int64_t base = chunk * kScanChunk + (int64_t)threadIdx.x * per;
   uint32_t v[per], sum = 0;
 #pragma unroll
   for (int q = 0; q < per; ++q) {
@@ -214,7 +217,7 @@ __global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ 
     sum += v[q];
   }
   uint32_t tot;
-  uint32_t run = partial[blockIdx.x] + block_exclusive_scan_256(sum, &tot, s_wave);
+  uint32_t run = partial[chunk] + block_exclusive_scan_256(sum, &tot, s_wave);
 #pragma unroll
   for (int q = 0; q < per; ++q) {
     if (base + q < count) x[base + q] = run;
@@ -222,13 +225,30 @@ __global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ 
   }
 }
 
-// ---- stable scatter of one radix pass -----------------------------------------------------
-__global__ __launch_bounds__(kWaves* DYN_WAVE) void scatter_kernel(
-    const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ in_in, const int32_t* __restrict__ out_in,
-    uint32_t* __restrict__ keys_out, int32_t* __restrict__ in_out, int32_t* __restrict__ out_out, int64_t n,
-    int shift, int bits, const uint32_t* __restrict__ scanned, int64_t n_block, const uint32_t* __restrict__ order) {
+__global__ __launch_bounds__(256) void scan_reduce_kernel(const uint32_t* __restrict__ x, int64_t count,
+                                                          uint32_t* __restrict__ partial, const uint32_t* __restrict__ order) {
   if (!sort_route(order)) return;
-  __shared__ uint32_t wcnt[kWaves][DYN_INGEST_MAX_BINS];
+  __shared__ uint32_t s_wave[4];
+  scan_reduce_chunk(blockIdx.x, x, count, partial, s_wave);
+}
+
+__global__ __launch_bounds__(256) void scan_partials_kernel(uint32_t* __restrict__ partial, int64_t n_partial, const uint32_t* __restrict__ order) {
+  if (!sort_route(order)) return;
+  __shared__ uint32_t s_wave[4];
+  scan_partials_all(partial, n_partial, s_wave);
+}
+
+__global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ x, int64_t count,
+                                                         const uint32_t* __restrict__ partial, const uint32_t* __restrict__ order) {
+  if (!sort_route(order)) return;
+  __shared__ uint32_t s_wave[4];
+  scan_apply_chunk(blockIdx.x, x, count, partial, s_wave);
+}
+
+// ---- stable scatter of one radix pass -----------------------------------------------------
+__device__ __forceinline__ void scatter_tile(int64_t tile, const uint32_t* keys_in, const int32_t* in_in, const int32_t* out_in,
+                                             uint32_t* keys_out, int32_t* in_out, int32_t* out_out, int64_t n, int shift, int bits,
+                                             const uint32_t* scanned, int64_t n_block, uint32_t (*wcnt)[DYN_INGEST_MAX_BINS]) {
   const int nbins = 1 << bits;
   const uint32_t mask = (uint32_t)nbins - 1u;
   const int lane = threadIdx.x & (DYN_WAVE - 1);
@@ -237,7 +257,7 @@ __global__ __launch_bounds__(kWaves* DYN_WAVE) void scatter_kernel(
   __syncthreads();
 
   // phase 1: digit counts of each wave's run of rows
-  const int64_t wbase = (int64_t)blockIdx.x * kTile + (int64_t)wave * (kRows * DYN_WAVE);
+  const int64_t wbase = tile * kTile + (int64_t)wave * (kRows * DYN_WAVE);
   uint32_t key[kRows];
   int32_t vin[kRows], vout[kRows];                       // the payload, loaded with the keys: not one row at a time later
 #pragma unroll
@@ -251,7 +271,7 @@ __global__ __launch_bounds__(kWaves* DYN_WAVE) void scatter_kernel(
   __syncthreads();
   // phase 2: per digit, the first output position of each wave's requests
   for (int d = threadIdx.x; d < nbins; d += blockDim.x) {
-    uint32_t run = scanned[(size_t)d * n_block + blockIdx.x];
+    uint32_t run = scanned[(size_t)d * n_block + tile];
     for (int w = 0; w < kWaves; ++w) {
       const uint32_t c = wcnt[w][d];
       wcnt[w][d] = run;
@@ -290,16 +310,85 @@ __global__ __launch_bounds__(kWaves* DYN_WAVE) void scatter_kernel(
   }
 }
 
-// cell_off[c] = number of requests with key < c, read off the sorted keys
-__global__ __launch_bounds__(256) void offsets_kernel(const uint32_t* __restrict__ keys, int64_t n, int64_t cells,
-                                                      int64_t* __restrict__ cell_off, const uint32_t* __restrict__ order) {
+__global__ __launch_bounds__(kWaves* DYN_WAVE) void scatter_kernel(
+    const uint32_t* __restrict__ keys_in, const int32_t* __restrict__ in_in, const int32_t* __restrict__ out_in,
+    uint32_t* __restrict__ keys_out, int32_t* __restrict__ in_out, int32_t* __restrict__ out_out, int64_t n,
+    int shift, int bits, const uint32_t* __restrict__ scanned, int64_t n_block, const uint32_t* __restrict__ order) {
   if (!sort_route(order)) return;
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  __shared__ uint32_t wcnt[kWaves][DYN_INGEST_MAX_BINS];
+  scatter_tile(blockIdx.x, keys_in, in_in, out_in, keys_out, in_out, out_out, n, shift, bits, scanned, n_block, wcnt);
+}
+
+// cell_off[c] = number of requests with key < c, read off the sorted keys
+__device__ __forceinline__ void offsets_at(int64_t i, const uint32_t* keys, int64_t n, int64_t cells, int64_t* cell_off) {
   if (i > n) return;
   const int64_t prev = i == 0 ? -1 : (int64_t)keys[i - 1];
   int64_t cur = i == n ? cells : (int64_t)keys[i];
   if (cur > cells) cur = cells;
   for (int64_t c = prev + 1; c <= cur; ++c) cell_off[c] = i;
+}
+
+__global__ __launch_bounds__(256) void offsets_kernel(const uint32_t* __restrict__ keys, int64_t n, int64_t cells,
+                                                      int64_t* __restrict__ cell_off, const uint32_t* __restrict__ order) {
+  if (!sort_route(order)) return;
+  offsets_at((int64_t)blockIdx.x * blockDim.x + threadIdx.x, keys, n, cells, cell_off);
+}
+
+// The whole general sort in one launch: a grid that the device holds at once walks the tiles of every phase, with a
+// grid-wide barrier between the phases.  A trace in window order costs this one launch that returns at its first
+// instruction (eleven gated launches otherwise).  Launched cooperatively (the runtime checks that the grid fits).
+struct RadixArgs {
+  const uint32_t* order;
+  uint32_t* key_a; uint32_t* key_b;
+  const int32_t* in_tok; const int32_t* out_tok;
+  int32_t* in_sorted; int32_t* out_sorted; int32_t* in_tmp; int32_t* out_tmp;
+  uint32_t* block_hist; int64_t n_block;
+  int64_t n, cells; int64_t* cell_off;
+  int32_t passes, bits;
+};
+
+__global__ __launch_bounds__(kWaves* DYN_WAVE) __attribute__((amdgpu_waves_per_eu(4, 4))) void radix_route_kernel(RadixArgs a) {
+  if (!sort_route(a.order)) return;              // the same word for every block: all leave, or none
+  __shared__ uint32_t wcnt[kWaves][DYN_INGEST_MAX_BINS];
+  __shared__ uint32_t s_wave[4];
+  cooperative_groups::grid_group grid = cooperative_groups::this_grid();
+  const uint32_t* k_src = a.key_a;
+  uint32_t* k_dst = a.key_b;
+  const int32_t *i_src = a.in_tok, *o_src = a.out_tok;
+  const uint32_t* sorted_keys = a.key_a;
+  uint32_t* partial = a.block_hist + (size_t)DYN_INGEST_MAX_BINS * a.n_block;
+  for (int p = 0; p < a.passes; ++p) {
+    const bool to_final = ((a.passes - 1 - p) % 2) == 0;   // ping-pong so that the last pass lands in the caller's arrays
+    int32_t* i_dst = to_final ? a.in_sorted : a.in_tmp;
+    int32_t* o_dst = to_final ? a.out_sorted : a.out_tmp;
+    const int shift = p * a.bits;
+    const int64_t count = (int64_t)(1 << a.bits) * a.n_block;
+    const int64_t n_part = (count + kScanChunk - 1) / kScanChunk;
+    for (int64_t t = blockIdx.x; t < a.n_block; t += gridDim.x) {
+      hist_tile(t, k_src, a.n, shift, a.bits, a.block_hist, a.n_block, wcnt[0]);
+      __syncthreads();
+    }
+    grid.sync();
+    for (int64_t c = blockIdx.x; c < n_part; c += gridDim.x) scan_reduce_chunk(c, a.block_hist, count, partial, s_wave);
+    grid.sync();
+    if (blockIdx.x == 0) scan_partials_all(partial, n_part, s_wave);
+    grid.sync();
+    for (int64_t c = blockIdx.x; c < n_part; c += gridDim.x) scan_apply_chunk(c, a.block_hist, count, partial, s_wave);
+    grid.sync();
+    for (int64_t t = blockIdx.x; t < a.n_block; t += gridDim.x) {
+      scatter_tile(t, k_src, i_src, o_src, k_dst, i_dst, o_dst, a.n, shift, a.bits, a.block_hist, a.n_block, wcnt);
+      __syncthreads();
+    }
+    grid.sync();
+    sorted_keys = k_dst;
+    i_src = i_dst;
+    o_src = o_dst;
+    uint32_t* old_src = const_cast<uint32_t*>(k_src);
+    k_src = k_dst;
+    k_dst = old_src;
+  }
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i <= a.n; i += (int64_t)gridDim.x * blockDim.x)
+    offsets_at(i, sorted_keys, a.n, a.cells, a.cell_off);
 }
 
 // ---- a trace in window order ----------------------------------------------------------------
@@ -461,6 +550,39 @@ hipError_t dyn_launch_ingest(const IngestArgs& a, hipStream_t s) {
   }
   const int passes = a.key_bits <= 0 ? 1 : (a.key_bits + 9) / 10;
   const int bits = a.key_bits <= 0 ? 1 : (a.key_bits + passes - 1) / passes;
+  {
+    // one cooperative launch when the device supports it and holds a useful grid; else the launches below
+    // what the device holds at once, asked once per device (0: not asked yet, -1: no cooperative launch)
+    static std::atomic<int> resident[64];
+    int dev = 0;
+    int fit = 0;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64) {
+      fit = resident[dev].load(std::memory_order_relaxed);
+      if (fit == 0) {
+        int coop = 0, n_cu = 0, per_cu = 0;
+        fit = -1;
+        if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) == hipSuccess && coop &&
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, radix_route_kernel, kWaves * DYN_WAVE, 0) == hipSuccess && per_cu > 0)
+          fit = per_cu * n_cu;
+        (void)hipGetLastError();
+        resident[dev].store(fit, std::memory_order_relaxed);
+      }
+    }
+    if (fit > 0) {
+      RadixArgs r;
+      r.order = a.unsorted; r.key_a = a.key_a; r.key_b = a.key_b; r.in_tok = a.in_tok; r.out_tok = a.out_tok;
+      r.in_sorted = a.in_sorted; r.out_sorted = a.out_sorted; r.in_tmp = a.in_tmp; r.out_tmp = a.out_tmp;
+      r.block_hist = a.block_hist; r.n_block = a.n_block; r.n = n; r.cells = cells; r.cell_off = a.cell_off;
+      r.passes = passes; r.bits = bits;
+      const int64_t useful = std::max<int64_t>(a.n_block, 1);
+      const unsigned blocks = (unsigned)std::min<int64_t>((int64_t)fit, useful);
+      void* args[] = {&r};
+      e = hipLaunchCooperativeKernel((const void*)radix_route_kernel, dim3(blocks), dim3(kWaves * DYN_WAVE), args, 0, s);
+      if (e == hipSuccess) return hipGetLastError();
+      (void)hipGetLastError();                   // not launched: take the separate kernels
+    }
+  }
   // ping-pong so that the last pass lands in the caller's arrays
   const uint32_t* k_src = a.key_a;
   uint32_t* k_dst = a.key_b;
