@@ -1078,9 +1078,12 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
   int32_t* s_top = (int32_t*)(s_off + sa.win_per_block * T);    // [2][kFastDepth][T]
   uint16_t* s_js = (uint16_t*)(s_top + 2 * T * kFastDepth);     // [n_bucket + 1]
 
-  // a block whose cells all belong to the general kernel has nothing to stage
+  // a block without a cell that is walked with lists has nothing to stage
   bool any = false;
-  for (int w = w0; w < w1; ++w) any = any || !(a.plan[(size_t)w * sa.G + g].flags & DYN_TP_GENERAL);
+  for (int w = w0; w < w1; ++w) {
+    const TickPlan p = a.plan[(size_t)w * sa.G + g];
+    any = any || (p.j > 0 && !(p.flags & (DYN_TP_GENERAL | DYN_TP_SKIP | DYN_TP_TIGHT)));
+  }
   if (!any) return;                                             // block-uniform
 
   if (LDS) stage_rows(sa, g, tile, s_tab);
@@ -1141,15 +1144,14 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
     const int32_t* cnt_w = s_cnt + (w - w0) * T;
     const double* load_w = s_load + (w - w0) * T;
     const TickPlan pl = s_plan[w - w0];
-    if (pl.flags & DYN_TP_GENERAL) {             // block-uniform
+    if (!listed(pl)) {                           // block-uniform: another kernel's cell
       prefetch(w + 1);
       continue;
     }
     const int j = pl.j;
-    const bool skip = (pl.flags & DYN_TP_SKIP) != 0, empty = j == 0;
     // two buffers: the lists of the cell before this one may still be read by slower waves
     int32_t* top_w = s_top + buf * (T * kFastDepth);
-    if (listed(pl)) {
+    {
       buf ^= 1;
       const int n = j * T;
 #pragma unroll
@@ -1167,20 +1169,82 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
     // the cell's j largest lengths, whichever ticks hold them.
     const int xmin = (int)((double)pl.xj * theta);
     WalkOut o;
-    if (empty || skip) {
-      o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, 0, load_w, cnt_w, top_w, 0, st.nd, a.tick_s);
-      o.ttft = o.tbt = empty ? 0.0 : __builtin_inf();   // a cell that is not evaluated is reported through the status word
-    } else if (pl.flags & DYN_TP_TIGHT) {          // no lists: the ticks' counts of requests of length x_j sit where the list offsets would
-      const int32_t* eq_w = (const int32_t*)s_off + (w - w0) * T;
-      if (pl.flags & DYN_TP_DENSE) o = walk_ticks<4, false, SINGLE, TWO, true>(st.L, T, j, load_w, cnt_w, eq_w, pl.xj, st.nd, a.tick_s, pl.place);
-      else o = walk_ticks<4, true, SINGLE, TWO, true>(st.L, T, j, load_w, cnt_w, eq_w, pl.xj, st.nd, a.tick_s, pl.place);
-    } else if (pl.flags & DYN_TP_DENSE) {
+    if (pl.flags & DYN_TP_DENSE) {
       if (j <= 4) o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, xmin, st.nd, a.tick_s);
       else if (j <= 8) o = walk_ticks<8, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, xmin, st.nd, a.tick_s);
       else o = walk_ticks<kFastDepth, false, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, xmin, st.nd, a.tick_s);
     } else {
       if (j <= 4) o = walk_ticks<4, true, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, xmin, st.nd, a.tick_s);
       else o = walk_ticks<kFastDepth / 2, true, SINGLE, TWO>(st.L, T, j, load_w, cnt_w, top_w, xmin, st.nd, a.tick_s);
+    }
+    emit_cell(sa, st, cell, false, o.ov, o.e, o.ttft, o.tbt);
+  }
+}
+
+// The same block mapping for the cells that need no lists: empty cells, cells that are not evaluated, and the cells
+// settled by their ticks' requests of length x_j (DYN_TP_TIGHT).  Nothing is staged per cell and the block has no
+// barrier after its set-up.
+// LDS: [table rows] [padded load grid] [reciprocal spacings] [SINGLE: grid point per bucket]
+//      [per window of the block, per tick: load] [per window: plan] [per window and tick: request count, requests of length x_j]
+//      [bucket index (16-bit)]
+template <bool LDS, bool SINGLE, bool TWO>
+__global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4, 5))) void tick_tight_walk_kernel(TickArgs a) {
+  extern __shared__ double smem[];
+  const SpaceArgs& sa = a.s;
+  const int tile = blockIdx.x % sa.n_tile;
+  const int g = (blockIdx.x / sa.n_tile) % sa.G;
+  const int chunk = blockIdx.x / (sa.n_tile * sa.G);
+  const int n_rho = sa.n_rho, T = a.n_tick;
+  const int w0 = chunk * sa.win_per_block;
+  const int w1 = min(w0 + sa.win_per_block, sa.n_window);
+
+  double* s_tab = smem;
+  double* s_rgp = smem + (LDS ? (size_t)sa.n_slot * DYN_SLOT_STRIDE(n_rho) : 0);
+  double* s_rinv = s_rgp + (n_rho + 2);
+  double* s_thr = s_rinv + (n_rho + 1);                         // [n_bucket + 1] when SINGLE
+  double* s_load = s_thr + (SINGLE ? sa.n_bucket + 1 : 0);      // [win_per_block][T]
+  TickPlan* s_plan = (TickPlan*)(s_load + sa.win_per_block * T);   // [win_per_block]
+  int32_t* s_cnt = (int32_t*)(s_plan + sa.win_per_block);       // [win_per_block][T] requests per tick
+  int32_t* s_eq = s_cnt + sa.win_per_block * T;                 // [win_per_block][T] requests of length x_j per tick
+  uint16_t* s_js = (uint16_t*)(s_eq + sa.win_per_block * T);    // [n_bucket + 1]
+
+  auto mine = [](const TickPlan& p) {
+    return p.j == 0 || (p.flags & DYN_TP_SKIP) || ((p.flags & DYN_TP_TIGHT) && !(p.flags & DYN_TP_GENERAL));
+  };
+  bool any = false;
+  for (int w = w0; w < w1; ++w) any = any || mine(a.plan[(size_t)w * sa.G + g]);
+  if (!any) return;                                             // block-uniform
+
+  if (LDS) stage_rows(sa, g, tile, s_tab);
+  stage_grid<SINGLE>(a, s_rgp, s_thr, s_js);
+  for (int i = threadIdx.x; i < (w1 - w0) * T; i += blockDim.x) {   // the ticks of this block's cells
+    const int dw = i / T, q = i - dw * T;
+    const TickRec r = a.rec[((size_t)(w0 + dw) * sa.G + g) * T + q];
+    s_load[i] = r.load;
+    s_cnt[i] = r.cnt;
+    s_eq[i] = (int32_t)r.off;
+  }
+  for (int i = threadIdx.x; i < w1 - w0; i += blockDim.x) s_plan[i] = a.plan[(size_t)(w0 + i) * sa.G + g];
+  __syncthreads();
+  CfgState st;
+  load_config<LDS>(a, g, tile * sa.tile + (int)threadIdx.x, s_tab, s_rgp, s_rinv, s_thr, s_js, &st);
+  for (int w = w0; w < w1; ++w) {
+    const TickPlan pl = s_plan[w - w0];
+    if (!mine(pl)) continue;                     // block-uniform
+    const size_t cell = (size_t)w * sa.G + g;
+    const int32_t* cnt_w = s_cnt + (w - w0) * T;
+    const double* load_w = s_load + (w - w0) * T;
+    const int32_t* eq_w = s_eq + (w - w0) * T;
+    const int j = pl.j;
+    const bool skip = (pl.flags & DYN_TP_SKIP) != 0, empty = j == 0;
+    WalkOut o;
+    if (empty || skip) {
+      o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, 0, load_w, cnt_w, eq_w, 0, st.nd, a.tick_s);
+      o.ttft = o.tbt = empty ? 0.0 : __builtin_inf();   // a cell that is not evaluated is reported through the status word
+    } else if (pl.flags & DYN_TP_DENSE) {
+      o = walk_ticks<4, false, SINGLE, TWO, true>(st.L, T, j, load_w, cnt_w, eq_w, pl.xj, st.nd, a.tick_s, pl.place);
+    } else {
+      o = walk_ticks<4, true, SINGLE, TWO, true>(st.L, T, j, load_w, cnt_w, eq_w, pl.xj, st.nd, a.tick_s, pl.place);
     }
     emit_cell(sa, st, cell, empty, o.ov, o.e, o.ttft, o.tbt);
   }
@@ -1402,6 +1466,11 @@ size_t tick_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t n_tick, int32_t wi
          2 * sizeof(double) + (size_t)win_per_block * (n_tick * (sizeof(double) + 2 * sizeof(int32_t)) + sizeof(TickPlan)) +
          (size_t)2 * n_tick * kFastDepth * sizeof(int32_t) + ((size_t)n_bucket + 1) * sizeof(uint16_t) + 8;
 }
+size_t tight_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t n_tick, int32_t win_per_block, bool single) {
+  return (size_t)(2 * n_rho + 3) * sizeof(double) + (single ? ((size_t)n_bucket + 1) * sizeof(double) : 0) +
+         (size_t)win_per_block * (n_tick * (sizeof(double) + 2 * sizeof(int32_t)) + sizeof(TickPlan)) +
+         ((size_t)n_bucket + 1) * sizeof(uint16_t) + 8;
+}
 size_t general_lds_tail(int32_t n_rho, int32_t n_bucket, int32_t n_tick, int nt, bool single) {
   return (size_t)(2 * n_rho + 3) * sizeof(double) + (single ? ((size_t)n_bucket + 1) * sizeof(double) : 0) +
          (size_t)n_tick * nt * sizeof(double) + (size_t)n_tick * (sizeof(double) + 5 * sizeof(int32_t)) +
@@ -1418,8 +1487,11 @@ static_assert(256 * 16 * sizeof(double) <= kStripBytes && 128 * 32 * sizeof(doub
               "the strip of the general kernel");
 
 template <bool LDS, bool SINGLE, bool TWO>
+void launch_tight_walk(const TickArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
+  hipLaunchKernelGGL((tick_tight_walk_kernel<LDS, SINGLE, TWO>), grid, block, lds, s, a);
+}
+template <bool LDS, bool SINGLE, bool TWO>
 void launch_space(const TickArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s) {
-  DynTimed timed(DYN_K_TICK_SPACE, s);
   if (a.n_tick <= 16) hipLaunchKernelGGL((tick_space_kernel<16, LDS, SINGLE, TWO>), grid, block, lds, s, a);
   else hipLaunchKernelGGL((tick_space_kernel<DYN_TICK_MAX, LDS, SINGLE, TWO>), grid, block, lds, s, a);
 }
@@ -1481,6 +1553,24 @@ hipError_t dyn_launch_tick_space(const TickArgs& a_in, hipStream_t s) {
   // points second (without them the bracket is searched; without the rows the tables are
   // read from global memory).
   {
+    DynTimed timed(DYN_K_TICK_SPACE, s);         // both walks
+    {
+    bool single = a.single_point;
+    size_t tail = tight_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, sa.win_per_block, single);
+    if (single && tail + tab > DYN_LDS_BUDGET) {
+      single = false;
+      tail = tight_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, sa.win_per_block, false);
+    }
+    const bool lds = sa.n_slot > 0 && tab + tail <= DYN_LDS_BUDGET;
+    if (!lds && tail > DYN_LDS_BUDGET) return hipErrorInvalidValue;
+    const size_t bytes = (lds ? tab : 0) + tail;
+    dispatch(lds, single, a.any_two_rows, [&](auto L, auto S, auto W) {
+      launch_tight_walk<decltype(L)::value, decltype(S)::value, decltype(W)::value>(a, grid, block, bytes, s);
+    });
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  {
     bool single = a.single_point;
     size_t tail = tick_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, sa.win_per_block, single);
     if (single && tail + tab > DYN_LDS_BUDGET) {
@@ -1495,6 +1585,7 @@ hipError_t dyn_launch_tick_space(const TickArgs& a_in, hipStream_t s) {
     });
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+  }
   }
   {
     const int nt = general_threads(a);
