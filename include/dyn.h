@@ -174,6 +174,8 @@ typedef struct {
 #define DYN_WS_BAD_OFFSETS 1u /* cell_off not monotone / outside [0, n_req]: cell treated as empty */
 #define DYN_WS_BAD_REQUEST 2u /* ingest: timestamp or model index out of range          */
 #define DYN_WS_TICK_RANK 4u   /* tick evaluation: a cell's percentile lies deeper than DYN_TICK_DEPTH */
+#define DYN_WS_SORT_ABANDONED 8u /* ingest: the general sort stopped waiting for its own blocks after seconds
+                                  * (the device was held by other work); the sorted outputs are not valid  */
 
 /* Bytes of workspace dyn_eval_space needs (a multiple of 256). */
 size_t dyn_eval_space_workspace(int32_t n_window, int32_t n_class, int32_t n_config);

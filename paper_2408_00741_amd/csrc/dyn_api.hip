@@ -34,6 +34,7 @@ __global__ void init_word_header_kernel(WsHeader* h, uint32_t order_word) {   //
   h->kind = DYN_WS_KIND_WORD;
   h->cells = 0;
   ((uint32_t*)h)[DYN_WS_HEADER_ORDER_WORD] = order_word;   // ingestion: "not in window order" flag
+  ((uint32_t*)h)[DYN_WS_HEADER_BARRIER_WORD] = 0u;
 }
 
 // Lengths of windows and ticks, capacities and grid spacings are kept inside this range so that the

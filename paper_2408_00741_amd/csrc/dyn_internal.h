@@ -116,6 +116,7 @@ struct WsHeader {
   int64_t cells;     // kind 2: number of per-cell status bytes
 };
 #define DYN_WS_HEADER_ORDER_WORD 8   // 32-bit word of a 256-byte header region used by the ingestion kernels
+#define DYN_WS_HEADER_BARRIER_WORD 9 // arrival counter of the general sort's grid-wide barriers (zeroed with the header)
 #define DYN_WS_KIND_WORD 1u
 #define DYN_WS_KIND_CELLS 2u
 

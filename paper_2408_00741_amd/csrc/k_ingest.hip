@@ -8,9 +8,9 @@
 // writes where every window starts), and one block per window then counts its requests by class
 // and moves them, stably, to their cells (window_sort_kernel).  Any other trace takes the radix
 // sort.  The host does not read the flag: both routes are enqueued and the kernels of the route
-// not taken return at their first instruction.  The general sort is one cooperative launch (a grid
-// the device holds at once, grid-wide barriers between the phases), so the route not taken costs
-// one empty launch; where cooperative launches are not available it is the separate kernels below.
+// not taken return at their first instruction.  The general sort is one launch of a grid the device
+// holds at once, with grid-wide barriers between the phases, so the route not taken costs one empty
+// launch; where the device does not tell what it holds it is the separate kernels below.
 //
 // One radix pass = per-block digit histogram -> exclusive scan of the (digit, block)
 // counters -> stable scatter.  Inside a block every wave owns a contiguous run of rows of
@@ -20,8 +20,6 @@
 
 #include <algorithm>
 #include <atomic>
-
-#include <hip/hip_cooperative_groups.h>
 
 #include "dyn_internal.h"
 #include "dyn_device.h"
@@ -101,13 +99,19 @@ __global__ __launch_bounds__(256) void key_kernel(IngestArgs a, double r_window,
       wp = window_of(tp[r], a.window_s, r_window, a.n_window, &ignore);
     }
     if (i == 0) wp = -1.0;
+    // The boundaries only matter to the window route: a wave that sees a request out of order, or finds the flag
+    // raised already, writes none (on a shuffled trace every request would otherwise fill hundreds of them).
+    const bool back = in && wp > wq;
+    const bool fill = __ballot(back) == 0 && __hip_atomic_load(a.unsorted, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u;
     if (in) {
       a.key_a[i] = (uint32_t)((int64_t)wq * G + g);
       bad |= bad_r;
-      dis = dis || wp > wq;
-      for (int64_t w = (int64_t)wp + 1; w <= (int64_t)wq; ++w) a.win_off[w] = i;
-      if (i == a.n_req - 1)
-        for (int64_t w = (int64_t)wq + 1; w <= a.n_window; ++w) a.win_off[w] = a.n_req;
+      dis = dis || back;
+      if (fill) {
+        for (int64_t w = (int64_t)wp + 1; w <= (int64_t)wq; ++w) a.win_off[w] = i;
+        if (i == a.n_req - 1)
+          for (int64_t w = (int64_t)wq + 1; w <= a.n_window; ++w) a.win_off[w] = a.n_req;
+      }
     }
   }
   if (bad) atomicOr(a.status, bad);
@@ -134,6 +138,7 @@ __global__ void edge_store_kernel(EdgePack p, int n_a, int32_t* __restrict__ dst
     header->kind = DYN_WS_KIND_WORD;
     header->cells = 0;
     ((uint32_t*)header)[DYN_WS_HEADER_ORDER_WORD] = order_word;
+    ((uint32_t*)header)[DYN_WS_HEADER_BARRIER_WORD] = 0u;
   }
 }
 
@@ -336,9 +341,14 @@ __global__ __launch_bounds__(256) void offsets_kernel(const uint32_t* __restrict
 
 // The whole general sort in one launch: a grid that the device holds at once walks the tiles of every phase, with a
 // grid-wide barrier between the phases.  A trace in window order costs this one launch that returns at its first
-// instruction (eleven gated launches otherwise).  Launched cooperatively (the runtime checks that the grid fits).
+// instruction (eleven gated launches otherwise).  The barrier: an arrival counter in the workspace header, zeroed with
+// the header; barrier number k is passed when the counter reaches k * blocks.  The grid is a fraction of what the
+// device holds at once (occupancy query), so every block is running when the first one waits; if other work keeps
+// part of the device for seconds the wait is given up (every block leaves, DYN_WS_SORT_ABANDONED is raised).
+// A barrier costs a write-back of the block's cache level per block, which is why the grid is kept small.
 struct RadixArgs {
   const uint32_t* order;
+  uint32_t* barrier; uint32_t* status;
   uint32_t* key_a; uint32_t* key_b;
   const int32_t* in_tok; const int32_t* out_tok;
   int32_t* in_sorted; int32_t* out_sorted; int32_t* in_tmp; int32_t* out_tmp;
@@ -347,11 +357,44 @@ struct RadixArgs {
   int32_t passes, bits;
 };
 
+constexpr int kRadixGridShare = 4;               // the grid is this fraction of what the device holds at once
+constexpr uint32_t kBarrierSpins = 1u << 22;     // x about a microsecond per look: seconds
+
+// false: given up (block-uniform).  All writes of the block before the call are visible to every block after it.
+// The waiting thread looks at the counter with relaxed loads (acquiring loads would invalidate caches all over the
+// device for as long as anyone waits) and acquires once at the end.
+__device__ __forceinline__ bool grid_barrier(uint32_t* counter, uint32_t target, uint32_t* s_flag) {
+  __syncthreads();                                // the block's stores have been issued and acknowledged
+  if (threadIdx.x == 0) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t spins = 0;
+    bool ok = true;
+    while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      if (++spins > kBarrierSpins) { ok = false; break; }
+      __builtin_amdgcn_s_sleep(20);
+    }
+    *s_flag = ok ? 1u : 0u;
+  }
+  __syncthreads();
+  const bool ok = *s_flag != 0u;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // later reads see the other blocks' writes
+  return ok;
+}
+
 __global__ __launch_bounds__(kWaves* DYN_WAVE) __attribute__((amdgpu_waves_per_eu(4, 4))) void radix_route_kernel(RadixArgs a) {
   if (!sort_route(a.order)) return;              // the same word for every block: all leave, or none
   __shared__ uint32_t wcnt[kWaves][DYN_INGEST_MAX_BINS];
   __shared__ uint32_t s_wave[4];
-  cooperative_groups::grid_group grid = cooperative_groups::this_grid();
+  __shared__ uint32_t s_flag;
+  uint32_t passed = 0;                           // barriers behind this block
+  auto sync = [&]() {
+    ++passed;
+    return grid_barrier(a.barrier, passed * gridDim.x, &s_flag);
+  };
+  auto give_up = [&]() {
+    if (threadIdx.x == 0) atomicOr(a.status, DYN_WS_SORT_ABANDONED);
+  };
   const uint32_t* k_src = a.key_a;
   uint32_t* k_dst = a.key_b;
   const int32_t *i_src = a.in_tok, *o_src = a.out_tok;
@@ -368,18 +411,18 @@ __global__ __launch_bounds__(kWaves* DYN_WAVE) __attribute__((amdgpu_waves_per_e
       hist_tile(t, k_src, a.n, shift, a.bits, a.block_hist, a.n_block, wcnt[0]);
       __syncthreads();
     }
-    grid.sync();
+    if (!sync()) { give_up(); return; }
     for (int64_t c = blockIdx.x; c < n_part; c += gridDim.x) scan_reduce_chunk(c, a.block_hist, count, partial, s_wave);
-    grid.sync();
+    if (!sync()) { give_up(); return; }
     if (blockIdx.x == 0) scan_partials_all(partial, n_part, s_wave);
-    grid.sync();
+    if (!sync()) { give_up(); return; }
     for (int64_t c = blockIdx.x; c < n_part; c += gridDim.x) scan_apply_chunk(c, a.block_hist, count, partial, s_wave);
-    grid.sync();
+    if (!sync()) { give_up(); return; }
     for (int64_t t = blockIdx.x; t < a.n_block; t += gridDim.x) {
       scatter_tile(t, k_src, i_src, o_src, k_dst, i_dst, o_dst, a.n, shift, a.bits, a.block_hist, a.n_block, wcnt);
       __syncthreads();
     }
-    grid.sync();
+    if (!sync()) { give_up(); return; }
     sorted_keys = k_dst;
     i_src = i_dst;
     o_src = o_dst;
@@ -551,36 +594,34 @@ hipError_t dyn_launch_ingest(const IngestArgs& a, hipStream_t s) {
   const int passes = a.key_bits <= 0 ? 1 : (a.key_bits + 9) / 10;
   const int bits = a.key_bits <= 0 ? 1 : (a.key_bits + passes - 1) / passes;
   {
-    // one cooperative launch when the device supports it and holds a useful grid; else the launches below
-    // what the device holds at once, asked once per device (0: not asked yet, -1: no cooperative launch)
+    // one launch of a resident grid when the device tells what it holds; else the launches below
+    // what the device holds at once, asked once per device (0: not asked yet, -1: unknown: the separate kernels below)
     static std::atomic<int> resident[64];
     int dev = 0;
     int fit = 0;
     if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64) {
       fit = resident[dev].load(std::memory_order_relaxed);
       if (fit == 0) {
-        int coop = 0, n_cu = 0, per_cu = 0;
+        int n_cu = 0, per_cu = 0;
         fit = -1;
-        if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) == hipSuccess && coop &&
-            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
             hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, radix_route_kernel, kWaves * DYN_WAVE, 0) == hipSuccess && per_cu > 0)
-          fit = per_cu * n_cu;
+          fit = std::max(1, per_cu * n_cu / kRadixGridShare);
         (void)hipGetLastError();
         resident[dev].store(fit, std::memory_order_relaxed);
       }
     }
     if (fit > 0) {
       RadixArgs r;
-      r.order = a.unsorted; r.key_a = a.key_a; r.key_b = a.key_b; r.in_tok = a.in_tok; r.out_tok = a.out_tok;
+      r.order = a.unsorted; r.barrier = a.unsorted + (DYN_WS_HEADER_BARRIER_WORD - DYN_WS_HEADER_ORDER_WORD); r.status = a.status;
+      r.key_a = a.key_a; r.key_b = a.key_b; r.in_tok = a.in_tok; r.out_tok = a.out_tok;
       r.in_sorted = a.in_sorted; r.out_sorted = a.out_sorted; r.in_tmp = a.in_tmp; r.out_tmp = a.out_tmp;
       r.block_hist = a.block_hist; r.n_block = a.n_block; r.n = n; r.cells = cells; r.cell_off = a.cell_off;
       r.passes = passes; r.bits = bits;
       const int64_t useful = std::max<int64_t>(a.n_block, 1);
       const unsigned blocks = (unsigned)std::min<int64_t>((int64_t)fit, useful);
-      void* args[] = {&r};
-      e = hipLaunchCooperativeKernel((const void*)radix_route_kernel, dim3(blocks), dim3(kWaves * DYN_WAVE), args, 0, s);
-      if (e == hipSuccess) return hipGetLastError();
-      (void)hipGetLastError();                   // not launched: take the separate kernels
+      hipLaunchKernelGGL(radix_route_kernel, dim3(blocks), dim3(kWaves * DYN_WAVE), 0, s, r);
+      return hipGetLastError();
     }
   }
   // ping-pong so that the last pass lands in the caller's arrays
