@@ -119,7 +119,10 @@ size_t dyn_trace_ingest_workspace(int64_t n_req, int32_t n_window, int32_t n_cla
  * bytes.  The edge lists travel in kernel arguments, so the HOST arrays are free on return.
  * A request whose timestamp falls outside [0, n_window*window_s) or whose model index is
  * outside [0, n_model) raises DYN_WS_BAD_REQUEST in the workspace status and is filed
- * under the nearest valid window / model 0, so that offsets stay consistent.
+ * under the nearest valid window / model 0, so that offsets stay consistent.  The general
+ * sort runs as one kernel whose blocks wait for each other between its phases; the wait is
+ * bounded: should other work hold the device for seconds, every block leaves, the outputs
+ * are not valid and DYN_WS_SORT_ABANDONED is raised.
  * Limits: n_window * G < 2^30.                                                         */
 int dyn_trace_ingest(const double* t_s, const int32_t* in_tok, const int32_t* out_tok,
                      const int32_t* model, int64_t n_req, const dyn_class_edges* edges,

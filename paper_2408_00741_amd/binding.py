@@ -26,7 +26,7 @@ __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_t
            "dyn_select_path", "dyn_account_workspace", "dyn_account", "dyn_hierarchy_workspace", "dyn_hierarchy", "DYN_K_HIER", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
 
 DYN_F_FEASIBLE, DYN_F_OVERLOAD, DYN_F_TTFT, DYN_F_TBT, DYN_F_BUDGET, DYN_F_EMPTY = 1, 2, 4, 8, 16, 32
-DYN_WS_BAD_OFFSETS, DYN_WS_BAD_REQUEST, DYN_WS_TICK_RANK = 1, 2, 4
+DYN_WS_BAD_OFFSETS, DYN_WS_BAD_REQUEST, DYN_WS_TICK_RANK, DYN_WS_SORT_ABANDONED = 1, 2, 4, 8
 DYN_TICK_LIMIT, DYN_TICK_DEPTH = 64, 8192
 DYN_STATIC_WORKSPACE_BYTES = 16 << 20
 
