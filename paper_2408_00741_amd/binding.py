@@ -20,7 +20,7 @@ __all__ = ["DynError", "Profile", "dyn_profile_load", "dyn_profile_free", "dyn_t
            "dyn_timing_enable", "dyn_timing_reset", "dyn_timing_read", "DYN_K_CELL", "DYN_K_SPACE", "DYN_K_SELECT",
            "DYN_K_TOTALS",
            "DYN_F_FEASIBLE", "DYN_F_OVERLOAD", "DYN_F_TTFT", "DYN_F_TBT", "DYN_F_BUDGET", "DYN_F_EMPTY",
-           "DYN_WS_BAD_OFFSETS", "DYN_WS_BAD_REQUEST", "DYN_WS_TICK_RANK", "dyn_eval_select_ticks",
+           "DYN_WS_BAD_OFFSETS", "DYN_WS_BAD_REQUEST", "DYN_WS_TICK_RANK", "DYN_WS_SORT_ABANDONED", "dyn_eval_select_ticks",
            "dyn_eval_ticks_workspace", "DYN_K_TICK_TOP", "DYN_K_TICK_SPACE", "DYN_K_TICK_MERGE", "DYN_K_MIXED_TYPES", "DYN_K_MIXED_COMBINE",
            "MixedPlan", "dyn_mixed_workspace", "dyn_eval_select_mixed", "DYN_K_PATH", "dyn_select_path_workspace",
            "dyn_select_path", "dyn_account_workspace", "dyn_account", "dyn_hierarchy_workspace", "dyn_hierarchy", "DYN_K_HIER", "DYN_TICK_LIMIT", "DYN_TICK_DEPTH"]
