@@ -43,7 +43,7 @@ struct TickCellArgs {
   int32_t* top;              // [n_req]: per tick its min(j, cnt) largest input lengths, descending, at rec.off
   uint8_t* cstat;            // [fine cells] status bytes
   WsHeader* header;
-  uint32_t* counters;        // [0] cells on deep_list, [1] cells on slow_list, [2] cells on list_cells; zeroed before the cell kernels
+  uint32_t* counters;        // [0] cells on deep_list, [1] cells on slow_list, [2] cells on list_cells, [3] cells walked with lists; zeroed before the cell kernels
   uint32_t* deep_list;       // [cells]
   uint32_t* slow_list;       // [cells] cells left to the general kernel
   uint32_t* list_cells;      // [cells] cells that need per-tick lists
@@ -62,7 +62,7 @@ struct TickArgs {
   bool any_two_rows;
   int32_t n_cu;               // compute units of the device (0: unknown)
   const double* pfspan;       // [G][n_tp_f][2] smallest and largest prefill time of every table row
-  const uint32_t* counters;   // [1]: number of cells on slow_list
+  const uint32_t* counters;   // [1]: number of cells on slow_list, [3]: number of cells walked with lists
   const uint32_t* slow_list;  // [cells] cells left to the general kernel
 };
 

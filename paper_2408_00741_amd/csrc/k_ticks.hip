@@ -46,6 +46,7 @@ __global__ void tick_init_kernel(uint32_t* counters) {
   counters[0] = 0u;
   counters[1] = 0u;
   counters[2] = 0u;
+  counters[3] = 0u;
 }
 
 // How the TBT percentile of a cell can be found (lane q holds tick q's request count, 0 beyond the ticks): from the
@@ -651,6 +652,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
     a.plan[c] = p;
     if (deep) a.deep_list[atomicAdd(&a.counters[0], 1u)] = (uint32_t)c;
     if (flags & DYN_TP_GENERAL) a.slow_list[atomicAdd(&a.counters[1], 1u)] = (uint32_t)c;
+    else if (!skip && j64 > 0) atomicAdd(&a.counters[3], 1u);   // a cell the walk takes with its lists
   }
 }
 
@@ -1078,7 +1080,8 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
   int32_t* s_top = (int32_t*)(s_off + sa.win_per_block * T);    // [2][kFastDepth][T]
   uint16_t* s_js = (uint16_t*)(s_top + 2 * T * kFastDepth);     // [n_bucket + 1]
 
-  // a block without a cell that is walked with lists has nothing to stage
+  // a block without a cell that is walked with lists has nothing to stage; most traces have no such cell at all
+  if (a.counters[3] == 0u) return;
   bool any = false;
   for (int w = w0; w < w1; ++w) {
     const TickPlan p = a.plan[(size_t)w * sa.G + g];
