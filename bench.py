@@ -194,8 +194,8 @@ def main():
         print(json.dumps({"copy_reference_bytes": n, "copies": 5}))
         return
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (windows would shard "
-              "independently across GPUs; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py measures one GPU: there is no multi-GPU path (windows would shard independently "
+              "across GPUs, with the profile and the candidate list replicated). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
