@@ -103,12 +103,14 @@ __device__ __forceinline__ bool tight_cell(const int32_t* __restrict__ in, const
   for (int p0 = 0; p0 < P; p0 += CH) {
     uint32_t a[2 * CH], b[2 * CH];
     int qs[2 * CH], rs[2 * CH];
+    bool oks[2 * CH];
 #pragma unroll
     for (int u = 0; u < 2 * CH; ++u) {
       qs[u] = q; rs[u] = r;
       const int64_t beg_q = q < T ? readlane_i64(beg_l, q) : 0;
       const int left = (q < T ? __builtin_amdgcn_readlane(cnt_l, q) : 0) - r * DYN_WAVE;
       const bool ok = lane < left;
+      oks[u] = ok;
       a[u] = ok ? (uint32_t)in[beg_q + r * DYN_WAVE + lane] : 0u;
       b[u] = ok ? (uint32_t)out[beg_q + r * DYN_WAVE + lane] : 0u;
       if (++r == rpt) { r = 0; ++q; }
@@ -126,10 +128,8 @@ __device__ __forceinline__ bool tight_cell(const int32_t* __restrict__ in, const
     }
 #pragma unroll
     for (int u = 0; u < CH; ++u) {
-      const int left0 = (qs[2 * u] < T ? __builtin_amdgcn_readlane(cnt_l, qs[2 * u]) : 0) - rs[2 * u] * DYN_WAVE;
-      const int left1 = (qs[2 * u + 1] < T ? __builtin_amdgcn_readlane(cnt_l, qs[2 * u + 1]) : 0) - rs[2 * u + 1] * DYN_WAVE;
-      const uint32_t x0 = lane < left0 ? a[2 * u] & 0xFFFFu : 0xFFFFu;
-      const uint32_t x1 = lane < left1 ? a[2 * u + 1] & 0xFFFFu : 0xFFFFu;
+      const uint32_t x0 = oks[2 * u] ? a[2 * u] & 0xFFFFu : 0xFFFFu;
+      const uint32_t x1 = oks[2 * u + 1] ? a[2 * u + 1] & 0xFFFFu : 0xFFFFu;
       v[p0 + u] = x0 | (x1 << 16);
     }
     // keep the rounds apart: with all loads hoisted to the top 4P loaded values would be live at once
@@ -168,19 +168,20 @@ __device__ __forceinline__ bool tight_cell(const int32_t* __restrict__ in, const
   // the bound: theta * (x_j + 1) > x_j, with theta below the true ratio by 2^-21 at least (so that no rounding of the
   // scaled lengths can turn the order around)
   if (!((double)theta * ((double)xj + 1.0) > (double)xj)) return false;
-  // longer requests, and per tick the requests of length x_j
-  int n_gt = 0, n_eq = 0, eq_acc = 0;
+  // longer requests, and per tick the requests of length x_j.  The padding (0xFFFF in every slot beyond a tick's
+  // requests) counts as longer: it is taken off afterwards.
+  if (xj == 0xFFFFu) return false;
+  int n_gt = -(2 * P * DYN_WAVE - m), n_eq = 0, eq_acc = 0;
   uint32_t eq_l = 0;
   q = 0; r = 0;
+  const uint32_t xj_hi = xj << 16;
 #pragma unroll
   for (int i = 0; i < P; ++i) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int left = (q < T ? __builtin_amdgcn_readlane(cnt_l, q) : 0) - r * DYN_WAVE;
-      const uint32_t x = h ? v[i] >> 16 : v[i] & 0xFFFFu;
-      const bool valid = lane < left;
-      n_gt += __popcll(__ballot(valid && x > xj));
-      eq_acc += __popcll(__ballot(valid && x == xj));
+      // low half by 16-bit compares; high half on the whole register (hi > x_j exactly when v >= (x_j + 1) << 16)
+      n_gt += h ? __popcll(__ballot(v[i] >= xj_hi + 0x10000u)) : __popcll(__ballot((uint16_t)v[i] > (uint16_t)xj));
+      eq_acc += h ? __popcll(__ballot((v[i] >> 16) == xj)) : __popcll(__ballot((uint16_t)v[i] == (uint16_t)xj));
       if (++r == rpt) {
         if (lane == q) eq_l = (uint32_t)eq_acc;
         n_eq += eq_acc;
@@ -299,12 +300,14 @@ __device__ __forceinline__ bool tight_cell_block(const int32_t* __restrict__ in,
   for (int p0 = 0; p0 < P; p0 += CH) {
     uint32_t a[2 * CH], b[2 * CH];
     int qs[2 * CH], rs[2 * CH];
+    bool oks[2 * CH];
 #pragma unroll
     for (int u = 0; u < 2 * CH; ++u) {
       qs[u] = q; rs[u] = r;
       const int64_t beg_q = q < T ? readlane_i64(beg_l, q) : 0;
       const int left = (q < T ? __builtin_amdgcn_readlane(cnt_l, q) : 0) - r * DYN_WAVE;
       const bool ok = lane < left;
+      oks[u] = ok;
       a[u] = ok ? (uint32_t)in[beg_q + r * DYN_WAVE + lane] : 0u;
       b[u] = ok ? (uint32_t)out[beg_q + r * DYN_WAVE + lane] : 0u;
       if (++r == rpt) { r = 0; q += kWavesPerBlock; }
@@ -322,10 +325,8 @@ __device__ __forceinline__ bool tight_cell_block(const int32_t* __restrict__ in,
     }
 #pragma unroll
     for (int u = 0; u < CH; ++u) {
-      const int left0 = (qs[2 * u] < T ? __builtin_amdgcn_readlane(cnt_l, qs[2 * u]) : 0) - rs[2 * u] * DYN_WAVE;
-      const int left1 = (qs[2 * u + 1] < T ? __builtin_amdgcn_readlane(cnt_l, qs[2 * u + 1]) : 0) - rs[2 * u + 1] * DYN_WAVE;
-      const uint32_t x0 = lane < left0 ? a[2 * u] & 0xFFFFu : 0xFFFFu;
-      const uint32_t x1 = lane < left1 ? a[2 * u + 1] & 0xFFFFu : 0xFFFFu;
+      const uint32_t x0 = oks[2 * u] ? a[2 * u] & 0xFFFFu : 0xFFFFu;
+      const uint32_t x1 = oks[2 * u + 1] ? a[2 * u + 1] & 0xFFFFu : 0xFFFFu;
       v[p0 + u] = x0 | (x1 << 16);
     }
     asm volatile("" : "+v"(tok_acc), "+v"(tok_l), "+v"(orv), "+v"(vmax), "+v"(v[p0]), "+v"(v[p0 + 1]), "+v"(v[p0 + 2]),
@@ -378,18 +379,17 @@ __device__ __forceinline__ bool tight_cell_block(const int32_t* __restrict__ in,
     xj = d;
   }
   if (!((double)theta * ((double)xj + 1.0) > (double)xj)) return false;
-  int n_gt = 0, n_eq = 0, eq_acc = 0;
+  if (xj == 0xFFFFu) return false;         // the padding value: block-uniform
+  int n_gt = 0, n_eq = 0, eq_acc = 0;      // the padding (0xFFFF) counts as longer: taken off after the block's sum
   uint32_t eq_l = 0;
   q = wave; r = 0;
+  const uint32_t xj_hi = xj << 16;
 #pragma unroll
   for (int i = 0; i < P; ++i) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int left = (q < T ? __builtin_amdgcn_readlane(cnt_l, q) : 0) - r * DYN_WAVE;
-      const uint32_t x = h ? v[i] >> 16 : v[i] & 0xFFFFu;
-      const bool valid = lane < left;
-      n_gt += __popcll(__ballot(valid && x > xj));
-      eq_acc += __popcll(__ballot(valid && x == xj));
+      n_gt += h ? __popcll(__ballot(v[i] >= xj_hi + 0x10000u)) : __popcll(__ballot((uint16_t)v[i] > (uint16_t)xj));
+      eq_acc += h ? __popcll(__ballot((v[i] >> 16) == xj)) : __popcll(__ballot((uint16_t)v[i] == (uint16_t)xj));
       if (++r == rpt) {
         if (lane == q) eq_l = (uint32_t)eq_acc;
         n_eq += eq_acc;
@@ -398,7 +398,7 @@ __device__ __forceinline__ bool tight_cell_block(const int32_t* __restrict__ in,
       }
     }
   }
-  n_gt = (int)block_sum((uint32_t)n_gt);
+  n_gt = (int)block_sum((uint32_t)n_gt) - (2 * P * DYN_WAVE * kWavesPerBlock - m);
   n_eq = (int)block_sum((uint32_t)n_eq);
   const int need = j - n_gt;
   uint32_t place = (uint32_t)need;

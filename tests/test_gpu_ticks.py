@@ -233,7 +233,7 @@ def test_walk_lists_pruned_by_the_prefill_spread(dyn, kind, pct):
     assert_same(w, g, o)
 
 
-@pytest.mark.parametrize("kind", ["few-values", "narrow-range", "wide-tokens", "crowded-tick", "big-cells"])
+@pytest.mark.parametrize("kind", ["few-values", "narrow-range", "wide-tokens", "crowded-tick", "big-cells", "top-of-16-bits"])
 @pytest.mark.parametrize("pct", [(99, 100), (1, 2), (1, 1)])
 def test_cells_settled_by_their_ties(dyn, kind, pct):
     """Flat prefill tables (the percentile belongs to a request of length x_j, found from the ticks' counts of such
@@ -251,10 +251,14 @@ def test_cells_settled_by_their_ties(dyn, kind, pct):
         w["trace"]["in_tok"] = rng.choice(np.asarray([900, 950, 1000, 1050, 1100], np.int32), n)
     else:
         w["trace"]["in_tok"] = rng.integers(1000, 1270, n).astype(np.int32)
+    if kind == "top-of-16-bits":         # x_j = 65535 is the packed registers' padding value: such a cell builds lists
+        w["trace"]["in_tok"] = rng.integers(65_530, 65_536, n).astype(np.int32)
+        w["edges"] = {"in_edge": np.asarray([[65_533]], np.int32), "out_edge": np.zeros((1, 0), np.int32)}
     if kind == "wide-tokens":
         w["trace"]["out_tok"][rng.integers(0, n, 4)] = 70_000
         w["trace"]["in_tok"][rng.integers(0, n, 2)] = 65_536
-    w["edges"] = {"in_edge": np.asarray([[1100]], np.int32), "out_edge": np.zeros((1, 0), np.int32)}
+    if kind != "top-of-16-bits":
+        w["edges"] = {"in_edge": np.asarray([[1100]], np.int32), "out_edge": np.zeros((1, 0), np.int32)}
     g, fine = gpu_ticks(dyn, w, 12, pct=pct)
     o = ora_ticks(w, fine, 12, pct=pct)
     assert g["status"] == 0
