@@ -287,6 +287,7 @@ __device__ __forceinline__ bool cell_in_registers_packed(const int32_t* __restri
   res->tin = (int64_t)wave_sum_u32(s_in);
   res->tout = (int64_t)wave_sum_u32(s_out);
   const uint32_t top = wave_max_u32(max(lmax, lmax2));
+  if (top == 0xFFFFu) return false;      // the padding value; and the search's candidates (up to top + 1) must fit 16 bits
   if (rank == m) {
     res->p99 = top;
     return true;

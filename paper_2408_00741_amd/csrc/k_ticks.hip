@@ -140,6 +140,7 @@ __device__ __forceinline__ bool tight_cell(const int32_t* __restrict__ in, const
   orv = wave_or_u32(orv);
   if (orv >= (1u << 16)) return false;   // wave-uniform
   const uint32_t top = wave_max_u32(max(lmax, lmax2));
+  if (top == 0xFFFFu) return false;      // the padding value itself; the search's candidates (up to top + 1) must fit 16 bits
   uint32_t xj = top;
   const int j = m - rank + 1;
   if (rank != m) {
@@ -170,7 +171,6 @@ __device__ __forceinline__ bool tight_cell(const int32_t* __restrict__ in, const
   if (!((double)theta * ((double)xj + 1.0) > (double)xj)) return false;
   // longer requests, and per tick the requests of length x_j.  The padding (0xFFFF in every slot beyond a tick's
   // requests) counts as longer: it is taken off afterwards.
-  if (xj == 0xFFFFu) return false;
   int n_gt = -(2 * P * DYN_WAVE - m), n_eq = 0, eq_acc = 0;
   uint32_t eq_l = 0;
   q = 0; r = 0;
@@ -360,7 +360,7 @@ __device__ __forceinline__ bool tight_cell_block(const int32_t* __restrict__ in,
   };
   const uint32_t all_or = block_or(wave_or_u32(orv));
   const uint32_t top = block_max(wave_max_u32(vmax));
-  if (all_or >= (1u << 16)) return false;   // block-uniform
+  if (all_or >= (1u << 16) || top == 0xFFFFu) return false;   // block-uniform; 0xFFFF is the padding value
   uint32_t xj = top;
   const int j = m - rank + 1;
   if (rank != m) {
@@ -379,7 +379,6 @@ __device__ __forceinline__ bool tight_cell_block(const int32_t* __restrict__ in,
     xj = d;
   }
   if (!((double)theta * ((double)xj + 1.0) > (double)xj)) return false;
-  if (xj == 0xFFFFu) return false;         // the padding value: block-uniform
   int n_gt = 0, n_eq = 0, eq_acc = 0;      // the padding (0xFFFF) counts as longer: taken off after the block's sum
   uint32_t eq_l = 0;
   q = wave; r = 0;

@@ -298,7 +298,7 @@ def test_rank_select_cell_sizes(dyn, m):
     cell then leaves the packed tier for the streamed path)."""
     prof, cfg = _worked()
     rng = np.random.default_rng(m)
-    for kind in ("perm", "dups", "wide", "u16", "over"):
+    for kind in ("perm", "dups", "wide", "u16", "top16", "over"):
         if kind == "perm":
             x = rng.permutation(np.arange(1, m + 1))
         elif kind == "dups":
@@ -307,6 +307,8 @@ def test_rank_select_cell_sizes(dyn, m):
             x = rng.integers(0, 65536, m)
             x[rng.integers(0, m, 3)] = 65535
             x[rng.integers(0, m)] = 0
+        elif kind == "top16":                          # the percentile itself is 65535 or just below it
+            x = rng.integers(65_530, 65_536, m)
         elif kind == "over":
             x = rng.integers(60000, 65536, m)
             x[rng.integers(0, m)] = 65536
