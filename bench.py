@@ -476,7 +476,7 @@ def main():
         # table look-up and the energy term + 1 multiply for the tick's largest candidate
         flops = 18.0 * cells * K * T
         tf = flops / (space_ms * 1e-3) / 1e12 if space_ms > 0 else None
-        roofline = {"bound": "alu", "kernel": "tick_space_kernel(+tick_merge_kernel)", "achieved": tf,
+        roofline = {"bound": "alu", "kernel": "tick_tight_walk_kernel + tick_space_kernel + tick_general_kernel", "achieved": tf,
                     "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": tf / FP64_VECTOR_PEAK_TFLOPS if tf else None, "traffic": None,
                     "algorithmic_flops_per_launch": flops, "avg_launch_ms": space_ms,

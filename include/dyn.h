@@ -482,8 +482,8 @@ int dyn_hierarchy(dyn_profile* profile, const dyn_trace_view* coarse, const dyn_
 #define DYN_K_SPACE 1   /* evaluation of the (cell, configuration) space                */
 #define DYN_K_SELECT 2  /* per-cell least-cost feasible configuration (or its fused finish) */
 #define DYN_K_TOTALS 3  /* per-window totals                                            */
-#define DYN_K_TICK_TOP 4   /* tick evaluation: per-tick loads and candidate lists (cell and deep-cell kernels) */
-#define DYN_K_TICK_SPACE 5 /* tick evaluation of the (cell, configuration) space: the walk over the ticks */
+#define DYN_K_TICK_TOP 4   /* tick evaluation: per-tick loads, ranks among the ties or candidate lists (all the per-cell kernels) */
+#define DYN_K_TICK_SPACE 5 /* tick evaluation of the (cell, configuration) space: the two walks over the ticks */
 #define DYN_K_TICK_MERGE 6 /* the same for the (cell, tile) items the walk cannot settle    */
 #define DYN_K_MIXED_TYPES 7   /* mixed pools: per-type least energies                      */
 #define DYN_K_MIXED_COMBINE 8 /* mixed pools: assignment of instances and shares          */
