@@ -128,15 +128,30 @@ __device__ __forceinline__ CellOut cell_by_wave(const int32_t* __restrict__ in, 
   return cell_in_registers<32>(in, out, beg, mi, rk, lane);
 }
 
-// Large cell, whole block: the 256 threads stream the cell from global memory once for the
-// sums and once per 10-bit digit of the selection (radix select through one LDS histogram).
-// Every thread returns the same result.  `hist` (kHistBins counters) and `xch` (16 words)
-// are LDS scratch; the caller guarantees nobody else uses them.
-template <int U>   // U independent loads per array in flight
-__device__ __forceinline__ CellOut cell_by_block(const int32_t* __restrict__ in, const int32_t* __restrict__ out, int64_t beg,
+// The threads of a group wait for each other: the whole block at a barrier; a single wave runs in lockstep and its LDS
+// operations complete in program order, so only the compiler has to be kept from moving them across this point.
+template <int WAVES>
+__device__ __forceinline__ void group_sync() {
+  if (WAVES == 1) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  } else {
+    __syncthreads();
+  }
+}
+
+// Large cell, by a group of WAVES waves (the whole block, or one wave on its own): the group streams the cell from
+// global memory once for the sums and once per 10-bit digit of the selection (radix select through one LDS histogram).
+// Every thread returns the same result.  `hist` (kHistBins counters) and `xch` (16 words) are LDS scratch of the
+// group; the caller guarantees nobody else uses them.
+template <int U, int WAVES>   // U independent loads per array in flight
+__device__ __forceinline__ CellOut cell_by_group(const int32_t* __restrict__ in, const int32_t* __restrict__ out, int64_t beg,
                                  int64_t m, int64_t rank, uint32_t* hist, int64_t* xch) {
-  const int tid = threadIdx.x, lane = tid & (DYN_WAVE - 1), wave = tid / DYN_WAVE;
-  constexpr int nthr = kWavesPerBlock * DYN_WAVE;
+  static_assert(WAVES == 1 || WAVES == kWavesPerBlock, "one wave or the block");
+  const int lane = threadIdx.x & (DYN_WAVE - 1);
+  const int tid = WAVES == 1 ? lane : (int)threadIdx.x, wave = tid / DYN_WAVE;
+  constexpr int nthr = WAVES * DYN_WAVE;
   int64_t sin = 0, sout = 0;
   uint32_t orv = 0;
   for (int64_t i0 = 0; i0 < m; i0 += U * nthr) {
@@ -157,13 +172,13 @@ __device__ __forceinline__ CellOut cell_by_block(const int32_t* __restrict__ in,
   sin = wave_sum_i64(sin);
   sout = wave_sum_i64(sout);
   orv = wave_or_u32(orv);
-  __syncthreads();
+  group_sync<WAVES>();
   if (lane == 0) { xch[wave * 3 + 0] = sin; xch[wave * 3 + 1] = sout; xch[wave * 3 + 2] = (int64_t)orv; }
-  __syncthreads();
+  group_sync<WAVES>();
   CellOut r;
   r.tin = r.tout = 0;
   r.orv = 0;
-  for (int w = 0; w < kWavesPerBlock; ++w) {
+  for (int w = 0; w < WAVES; ++w) {
     r.tin += xch[w * 3 + 0];
     r.tout += xch[w * 3 + 1];
     r.orv |= (uint32_t)xch[w * 3 + 2];
@@ -176,9 +191,9 @@ __device__ __forceinline__ CellOut cell_by_block(const int32_t* __restrict__ in,
     const int w = hi_bit < kHistBits ? hi_bit : kHistBits;
     const int shift = hi_bit - w;
     const uint32_t dmask = (1u << w) - 1u;
-    __syncthreads();
+    group_sync<WAVES>();
     for (int b = tid; b < kHistBins; b += nthr) hist[b] = 0;
-    __syncthreads();
+    group_sync<WAVES>();
     for (int64_t i0 = 0; i0 < m; i0 += U * nthr) {
       uint32_t a[U];
 #pragma unroll
@@ -193,7 +208,7 @@ __device__ __forceinline__ CellOut cell_by_block(const int32_t* __restrict__ in,
         if (match) atomicAdd(&hist[(a[u] >> shift) & dmask], 1u);
       }
     }
-    __syncthreads();
+    group_sync<WAVES>();
     if (wave == 0) {
       // lane l owns bins [16 l, 16 l + 16); find the bin where the running count reaches `need`
       constexpr int per = kHistBins / DYN_WAVE;
@@ -228,13 +243,13 @@ __device__ __forceinline__ CellOut cell_by_block(const int32_t* __restrict__ in,
       }
       if (lane == owner) { xch[12] = (int64_t)digit; xch[13] = below; }
     }
-    __syncthreads();
+    group_sync<WAVES>();
     const uint32_t digit = (uint32_t)xch[12];
     need -= xch[13];
     prefix = (prefix << w) | digit;
     hi_bit = shift;
   }
-  __syncthreads();
+  group_sync<WAVES>();
   r.p99 = prefix;
   return r;
 }
@@ -242,7 +257,7 @@ __device__ __forceinline__ CellOut cell_by_block(const int32_t* __restrict__ in,
 // Register-resident cell of 2048 < m <= 128*P requests by one wave: two 16-bit input lengths to a register (request
 // i*64 + lane in half i%2 of register i/2; 0xFFFF beyond m).  Same sums and the same search as above.  Returns false,
 // and nothing else, when a token count of 2^16 or more (a negative one included) rules the packing out: the caller
-// leaves the cell to the whole block.
+// streams the cell instead.
 constexpr int kPackedRowsMax = 128;  // the packed path handles m <= 64 * kPackedRowsMax
 template <int P>
 __device__ __forceinline__ bool cell_in_registers_packed(const int32_t* __restrict__ in, const int32_t* __restrict__ out,
@@ -357,9 +372,8 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
     int32_t pct_num, int32_t pct_den, int64_t* __restrict__ tin, int64_t* __restrict__ tout,
     int32_t* __restrict__ in_p99, CellRec* __restrict__ rec, uint8_t* __restrict__ cstat,
     WsHeader* __restrict__ header) {
-  __shared__ uint32_t s_hist[kHistBins];
-  __shared__ uint32_t s_redo[kWavesPerBlock];
-  __shared__ int64_t s_xch[16];
+  __shared__ uint32_t s_hist[kWavesPerBlock][kHistBins];
+  __shared__ int64_t s_xch[kWavesPerBlock][16];
   const int lane = threadIdx.x & (DYN_WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
   const int64_t c0 = (int64_t)blockIdx.x * kWavesPerBlock;
@@ -370,7 +384,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
   const bool sound = lane < nc && myoff >= 0 && nxoff >= myoff && nxoff <= n_req;
   // cells of this block left to the whole block, and cells beyond the plain register tiers that a wave takes with
   // packed registers (both uniform over the block)
-  uint32_t big_mask = (uint32_t)__ballot(sound && nxoff - myoff > DYN_WAVE * kPackedRowsMax);
+  const uint32_t big_mask = (uint32_t)__ballot(sound && nxoff - myoff > DYN_WAVE * kPackedRowsMax);
   const uint32_t packed_mask = (uint32_t)__ballot(sound && nxoff - myoff > DYN_WAVE * kRegRowsMax &&
                                                   nxoff - myoff <= DYN_WAVE * kPackedRowsMax);
   if (wave < nc && !((big_mask >> wave) & 1u)) {
@@ -385,33 +399,27 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
     r.tin = r.tout = 0;
     r.p99 = 0;
     r.orv = 0;
-    bool done = true;
     if (mi > 0) {
       const int rk = (int)(((int64_t)pct_num * mi + pct_den - 1) / pct_den);
       if ((packed_mask >> wave) & 1u) {
-        done = cell_by_wave_packed(in + beg, out + beg, mi, rk, lane, &r);
-        if (lane == 0) s_redo[wave] = done ? 0u : 1u;
+        // values the packing cannot hold: the wave streams its cell on its own (its own histogram; no other wave waits)
+        if (!cell_by_wave_packed(in + beg, out + beg, mi, rk, lane, &r))
+          r = cell_by_group<8, 1>(in, out, beg, mi, rk, s_hist[wave], s_xch[wave]);
       } else {
         r = cell_by_wave(in, out, beg, mi, rk, lane);
       }
       asm volatile("" : "+s"(bad));
       if (r.orv >> 31) bad |= DYN_WS_BAD_REQUEST;  // a negative token count
     }
-    if (done && lane == 0) write_cell(c, r, mi, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
+    if (lane == 0) write_cell(c, r, mi, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
   }
-  if ((big_mask | packed_mask) == 0) return;   // uniform over the block
-  if (packed_mask) {
-    __syncthreads();
-    for (int q = 0; q < kWavesPerBlock; ++q)
-      if (((packed_mask >> q) & 1u) && s_redo[q]) big_mask |= 1u << q;
-  }
-  if (big_mask == 0) return;
+  if (big_mask == 0) return;   // uniform over the block
   for (int q = 0; q < kWavesPerBlock; ++q) {
     if (!((big_mask >> q) & 1u)) continue;
-    const int64_t beg = cell_off[c0 + q];          // read again (the masks vouch for them): nothing is kept in
+    const int64_t beg = cell_off[c0 + q];          // read again (the mask vouches for them): nothing is kept in
     const int64_t m = cell_off[c0 + q + 1] - beg;  // registers across the waves' own cells
     const int64_t rank = ((int64_t)pct_num * m + pct_den - 1) / pct_den;
-    const CellOut r = cell_by_block<8>(in, out, beg, m, rank, s_hist, s_xch);
+    const CellOut r = cell_by_group<8, kWavesPerBlock>(in, out, beg, m, rank, s_hist[0], s_xch[0]);
     const uint32_t bad = (r.orv >> 31) ? DYN_WS_BAD_REQUEST : 0u;
     if (threadIdx.x == 0) write_cell(c0 + q, r, m, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
   }
@@ -560,7 +568,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
       const int64_t beg = s_off[w][q];
       const int64_t m = s_off[w][q + 1] - beg;
       const int64_t rank = ((int64_t)pct_num * m + pct_den - 1) / pct_den;
-      const CellOut r = cell_by_block<2>(in, out, beg, m, rank, s_hist, s_xch);
+      const CellOut r = cell_by_group<2, kWavesPerBlock>(in, out, beg, m, rank, s_hist, s_xch);
       const uint32_t bad = (r.orv >> 31) ? DYN_WS_BAD_REQUEST : 0u;
       const int64_t c = ((int64_t)blockIdx.x * kWavesPerBlock + w) * kTinyCells + q;
       if (threadIdx.x == 0) write_cell(c, r, m, bad, window_s, r_window, cells, tin, tout, in_p99, rec, cstat, header);
