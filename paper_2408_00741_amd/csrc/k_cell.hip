@@ -366,7 +366,7 @@ __device__ __forceinline__ void write_cell(int64_t c, const CellOut& r, int64_t 
 
 // Four consecutive cells per block, one wave each; cells beyond the register tiers are then
 // taken one after the other by the whole block.
-__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_waves_per_eu(5, 8))) void cell_aggregate_kernel(
+__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_waves_per_eu(6, 8))) void cell_aggregate_kernel(
     const int32_t* __restrict__ in, const int32_t* __restrict__ out,
     const int64_t* __restrict__ cell_off, int64_t n_req, int64_t cells, double window_s, double r_window,
     int32_t pct_num, int32_t pct_den, int64_t* __restrict__ tin, int64_t* __restrict__ tout,
