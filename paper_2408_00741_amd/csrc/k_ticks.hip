@@ -205,7 +205,7 @@ __device__ __forceinline__ bool tight_cell(const int32_t* __restrict__ in, const
   return true;
 }
 
-__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_waves_per_eu(5, 8))) void tick_tight_kernel(TickCellArgs a) {
+__global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_waves_per_eu(6, 8))) void tick_tight_kernel(TickCellArgs a) {
   const int lane = threadIdx.x & (DYN_WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
   const int T = a.n_tick, G = a.G;
