@@ -805,6 +805,7 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   ca.cstat = (uint8_t*)(base + w.fine.cstat); ca.header = (WsHeader*)(base + w.fine.header);
   ca.counters = (uint32_t*)(base + w.counters); ca.deep_list = (uint32_t*)(base + w.deep_list); ca.slow_list = (uint32_t*)(base + w.slow_list);
   ca.list_cells = (uint32_t*)(base + w.list_cells); ca.theta = p->d_theta;
+  ca.few_cells = cells <= 4 * (int64_t)p->n_cu ? 1 : 0;   // every cell's block is resident at once (four blocks of four waves per compute unit)
   if (!hip_ok(dyn_launch_tick_cell(ca, s), "tick cell launch")) return DYN_E_DEVICE;
 
   TickArgs ta;

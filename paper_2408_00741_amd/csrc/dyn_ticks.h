@@ -48,6 +48,7 @@ struct TickCellArgs {
   uint32_t* slow_list;       // [cells] cells left to the general kernel
   uint32_t* list_cells;      // [cells] cells that need per-tick lists
   const float* theta;        // [G] per class: least (smallest / largest prefill time of a table row), rounded down
+  int32_t few_cells;         // so few cells that a block per cell leaves no compute unit short of work
 };
 
 struct TickArgs {

@@ -240,7 +240,8 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) __attribute__((amdgpu_wav
     flags = tbt_route(cnt_l, j64, lane);
     const int rpt = ((int)wave_max_u32((uint32_t)cnt_l) + DYN_WAVE - 1) / DYN_WAVE;   // rows per tick
     const int rows = T * rpt;
-    if (rows <= 128) {
+    // with few cells on the whole device a cell of many rows is quicker with a block's four waves: it goes on the list
+    if (rows <= 128 && !(a.few_cells && rows > 8)) {
       const float theta = a.theta[g];
       const int m = (int)m_cell, rk = (int)rank;
       if (rows <= 4) done = tight_cell<2>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, &tc);
