@@ -1293,17 +1293,18 @@ __device__ __forceinline__ double weighted_from_top(const double* strip, const i
 // (binary search on the scaled entries), and either at least j scaled entries are >= v, then the least
 // of them is a new lower end, or fewer, then the largest one below v is a new upper end.  Both ends are
 // values of the lists from then on, so the search ends with the percentile itself.
-// LDS: [table rows] [load grid] [reciprocal spacings] [SINGLE: grid point per bucket] [strip NT x n_tick]
+// LDS: [load grid] [reciprocal spacings] [SINGLE: grid point per bucket] [strip NT x n_tick]
 //      [per tick: load] [per tick: count] [per tick: entries listed] [per tick: entries equal to x_j]
 //      [per tick: start of its list, then two words] [the cell's lists when they fit] [bucket index]
-template <bool LDS, bool SINGLE, bool TWO>
+template <bool SINGLE, bool TWO>
 __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) {
   extern __shared__ double smem[];
   const SpaceArgs& sa = a.s;
   const int n_rho = sa.n_rho, T = a.n_tick;
   const int tid = threadIdx.x, NT = blockDim.x;
-  double* s_tab = smem;
-  double* s_rgp = smem + (LDS ? (size_t)sa.n_slot * DYN_SLOT_STRIDE(n_rho) : 0);
+  // The table rows stay in global memory (they are read through the caches): consecutive items of a block belong to
+  // different classes, and staging a class's rows per item cost more than the look-ups of the item.
+  double* s_rgp = smem;
   double* s_rinv = s_rgp + (n_rho + 2);
   double* s_thr = s_rinv + (n_rho + 1);
   double* s_strip = s_thr + (SINGLE ? sa.n_bucket + 1 : 0);     // [T][NT]
@@ -1319,15 +1320,11 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
   const uint64_t n_item = (uint64_t)a.counters[1] * (uint64_t)sa.n_tile;   // complete: written by the cell kernel
   if (blockIdx.x >= n_item) return;                              // block-uniform
   stage_grid<SINGLE>(a, s_rgp, s_thr, s_js);
-  int cur_g = -1, cur_tile = -1;
   for (uint64_t item = blockIdx.x; item < n_item; item += gridDim.x) {
     const size_t cell = a.slow_list[item / (uint64_t)sa.n_tile];
     const int tile = (int)(item % (uint64_t)sa.n_tile);
     const int g = (int)(cell % sa.G);
     __syncthreads();                           // the previous item's LDS data has been consumed
-    if (LDS && (g != cur_g || tile != cur_tile)) stage_rows(sa, g, tile, s_tab);
-    cur_g = g;
-    cur_tile = tile;
     const TickPlan pl = a.plan[cell];
     const int j = pl.j;
     const bool dense = (pl.flags & DYN_TP_DENSE) != 0;
@@ -1399,7 +1396,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
     for (int sub = 0; sub < sa.tile; sub += NT) {
       const bool in_tile = sub + (tid & ~(DYN_WAVE - 1)) < sa.tile;   // wave-uniform: a wave past the tile's end stores nothing
       CfgState st;
-      load_config<LDS>(a, g, tile * sa.tile + (in_tile ? sub + tid : 0), s_tab, s_rgp, s_rinv, s_thr, s_js, &st);
+      load_config<false>(a, g, tile * sa.tile + (in_tile ? sub + tid : 0), nullptr, s_rgp, s_rinv, s_thr, s_js, &st);
       double e = 0.0, pf_min = __builtin_inf(), pf_max = -__builtin_inf(), tb_max = -__builtin_inf();
       bool ov = false;
       const double e_idle = (st.nd * idle_power<TWO>(st.L)) * a.tick_s;
@@ -1498,16 +1495,16 @@ void launch_space(const TickArgs& a, dim3 grid, dim3 block, size_t lds, hipStrea
   if (a.n_tick <= 16) hipLaunchKernelGGL((tick_space_kernel<16, LDS, SINGLE, TWO>), grid, block, lds, s, a);
   else hipLaunchKernelGGL((tick_space_kernel<DYN_TICK_MAX, LDS, SINGLE, TWO>), grid, block, lds, s, a);
 }
-template <bool LDS, bool SINGLE, bool TWO>
+template <bool SINGLE, bool TWO>
 void launch_general(const TickArgs& a, size_t lds, hipStream_t s) {
   DynTimed timed(DYN_K_TICK_MERGE, s);
   // The items are dealt round-robin to the grid: as many blocks as the device holds at once, so that none starts late.
   const int nt = general_threads(a);
   int per_cu = 0, blocks = kGeneralBlocks;
-  if (a.n_cu > 0 && hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tick_general_kernel<LDS, SINGLE, TWO>, nt, lds) == hipSuccess &&
+  if (a.n_cu > 0 && hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tick_general_kernel<SINGLE, TWO>, nt, lds) == hipSuccess &&
       per_cu > 0)
     blocks = per_cu * a.n_cu;
-  hipLaunchKernelGGL((tick_general_kernel<LDS, SINGLE, TWO>), dim3(blocks), dim3(nt), lds, s, a);
+  hipLaunchKernelGGL((tick_general_kernel<SINGLE, TWO>), dim3(blocks), dim3(nt), lds, s, a);
 }
 
 template <typename F>
@@ -1594,15 +1591,13 @@ hipError_t dyn_launch_tick_space(const TickArgs& a_in, hipStream_t s) {
     const int nt = general_threads(a);
     bool single = a.single_point;
     size_t tail = general_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, nt, single);
-    if (single && tail + tab > DYN_LDS_BUDGET) {
+    if (single && tail > DYN_LDS_BUDGET) {
       single = false;
       tail = general_lds_tail(sa.n_rho, sa.n_bucket, a.n_tick, nt, false);
     }
-    const bool lds = sa.n_slot > 0 && tab + tail <= DYN_LDS_BUDGET;
-    if (!lds && tail > DYN_LDS_BUDGET) return hipErrorInvalidValue;
-    const size_t bytes = (lds ? tab : 0) + tail;
-    dispatch(lds, single, a.any_two_rows, [&](auto L, auto S, auto W) {
-      launch_general<decltype(L)::value, decltype(S)::value, decltype(W)::value>(a, bytes, s);
+    if (tail > DYN_LDS_BUDGET) return hipErrorInvalidValue;
+    dispatch(false, single, a.any_two_rows, [&](auto, auto S, auto W) {
+      launch_general<decltype(S)::value, decltype(W)::value>(a, tail, s);
     });
   }
   return hipGetLastError();
