@@ -539,7 +539,8 @@ def main():
         out["inputs"]["equal_to_the_recorded_checksums"] = all(
             rec.get((str(args.config), k_)) == v_ for k_, v_ in out["inputs"].items() if k_ != "seed")
     if not args.no_cpu_baseline:
-        nwin = args.cpu_windows or max(1, min(NW, int(NW * (5.0e9 if args.mixed else 1.5e9 if args.path else 1.0e10) / (R * K))))
+        print("bench: GPU part done, timing the CPU oracle on a sample", file=sys.stderr, flush=True)
+        nwin = args.cpu_windows or max(1, min(NW, int(NW * (5.0e9 if args.mixed else 1.5e9 if (args.path or args.ticks) else 1.0e10) / (R * K))))
         mixed = (args.mixed, n_max, np.full(G, args.mixed_gpus, np.int32), K) if args.mixed else None
         if args.hierarchy:
             nwin = args.cpu_windows or NW
