@@ -103,16 +103,22 @@ __device__ __forceinline__ bool tight_cell(const int32_t* __restrict__ in, const
   for (int p0 = 0; p0 < P; p0 += CH) {
     uint32_t a[2 * CH], b[2 * CH];
     int qs[2 * CH], rs[2 * CH];
-    bool oks[2 * CH];
 #pragma unroll
     for (int u = 0; u < 2 * CH; ++u) {
       qs[u] = q; rs[u] = r;
-      const int64_t beg_q = q < T ? readlane_i64(beg_l, q) : 0;
-      const int left = (q < T ? __builtin_amdgcn_readlane(cnt_l, q) : 0) - r * DYN_WAVE;
+      // lane reads without a branch around them: beyond the last tick the lane index is clamped and the count zeroed
+      const int qc = q < DYN_WAVE - 1 ? q : DYN_WAVE - 1;
+      const int64_t beg_q = readlane_i64(beg_l, qc);
+      const int cnt_q = __builtin_amdgcn_readlane(cnt_l, qc);
+      const int left = (q < T ? cnt_q : 0) - r * DYN_WAVE;
       const bool ok = lane < left;
-      oks[u] = ok;
-      a[u] = ok ? (uint32_t)in[beg_q + r * DYN_WAVE + lane] : 0u;
-      b[u] = ok ? (uint32_t)out[beg_q + r * DYN_WAVE + lane] : 0u;
+      // the padding of a slot without a request goes into its half of the register now; the length is ORed in below
+      // (a lane without a request loads 0), so no mask has to live across the loads
+      if (u % 2 == 0) v[p0 + u / 2] = ok ? 0u : 0xFFFFu;
+      else v[p0 + u / 2] |= ok ? 0u : 0xFFFF0000u;
+      const int64_t row_q = beg_q + (int64_t)(r * DYN_WAVE);   // one scalar offset for both arrays
+      a[u] = ok ? (uint32_t)in[row_q + lane] : 0u;
+      b[u] = ok ? (uint32_t)out[row_q + lane] : 0u;
       if (++r == rpt) { r = 0; ++q; }
     }
 #pragma unroll
@@ -128,9 +134,7 @@ __device__ __forceinline__ bool tight_cell(const int32_t* __restrict__ in, const
     }
 #pragma unroll
     for (int u = 0; u < CH; ++u) {
-      const uint32_t x0 = oks[2 * u] ? a[2 * u] & 0xFFFFu : 0xFFFFu;
-      const uint32_t x1 = oks[2 * u + 1] ? a[2 * u + 1] & 0xFFFFu : 0xFFFFu;
-      v[p0 + u] = x0 | (x1 << 16);
+      v[p0 + u] |= (a[2 * u] & 0xFFFFu) | (a[2 * u + 1] << 16);   // lengths of 2^16 and more: the cell is given up below
     }
     // keep the rounds apart: with all loads hoisted to the top 4P loaded values would be live at once
     if (CH == 4)
@@ -301,16 +305,22 @@ __device__ __forceinline__ bool tight_cell_block(const int32_t* __restrict__ in,
   for (int p0 = 0; p0 < P; p0 += CH) {
     uint32_t a[2 * CH], b[2 * CH];
     int qs[2 * CH], rs[2 * CH];
-    bool oks[2 * CH];
 #pragma unroll
     for (int u = 0; u < 2 * CH; ++u) {
       qs[u] = q; rs[u] = r;
-      const int64_t beg_q = q < T ? readlane_i64(beg_l, q) : 0;
-      const int left = (q < T ? __builtin_amdgcn_readlane(cnt_l, q) : 0) - r * DYN_WAVE;
+      // lane reads without a branch around them: beyond the last tick the lane index is clamped and the count zeroed
+      const int qc = q < DYN_WAVE - 1 ? q : DYN_WAVE - 1;
+      const int64_t beg_q = readlane_i64(beg_l, qc);
+      const int cnt_q = __builtin_amdgcn_readlane(cnt_l, qc);
+      const int left = (q < T ? cnt_q : 0) - r * DYN_WAVE;
       const bool ok = lane < left;
-      oks[u] = ok;
-      a[u] = ok ? (uint32_t)in[beg_q + r * DYN_WAVE + lane] : 0u;
-      b[u] = ok ? (uint32_t)out[beg_q + r * DYN_WAVE + lane] : 0u;
+      // the padding of a slot without a request goes into its half of the register now; the length is ORed in below
+      // (a lane without a request loads 0), so no mask has to live across the loads
+      if (u % 2 == 0) v[p0 + u / 2] = ok ? 0u : 0xFFFFu;
+      else v[p0 + u / 2] |= ok ? 0u : 0xFFFF0000u;
+      const int64_t row_q = beg_q + (int64_t)(r * DYN_WAVE);   // one scalar offset for both arrays
+      a[u] = ok ? (uint32_t)in[row_q + lane] : 0u;
+      b[u] = ok ? (uint32_t)out[row_q + lane] : 0u;
       if (++r == rpt) { r = 0; q += kWavesPerBlock; }
     }
 #pragma unroll
@@ -326,9 +336,7 @@ __device__ __forceinline__ bool tight_cell_block(const int32_t* __restrict__ in,
     }
 #pragma unroll
     for (int u = 0; u < CH; ++u) {
-      const uint32_t x0 = oks[2 * u] ? a[2 * u] & 0xFFFFu : 0xFFFFu;
-      const uint32_t x1 = oks[2 * u + 1] ? a[2 * u + 1] & 0xFFFFu : 0xFFFFu;
-      v[p0 + u] = x0 | (x1 << 16);
+      v[p0 + u] |= (a[2 * u] & 0xFFFFu) | (a[2 * u + 1] << 16);   // lengths of 2^16 and more: the cell is given up below
     }
     asm volatile("" : "+v"(tok_acc), "+v"(tok_l), "+v"(orv), "+v"(vmax), "+v"(v[p0]), "+v"(v[p0 + 1]), "+v"(v[p0 + 2]),
                  "+v"(v[p0 + 3])::"memory");
