@@ -91,6 +91,35 @@ struct TightCell {
 };
 #define DYN_TIGHT_FROM_BELOW 0x80000000u
 
+// The up to four smallest positive per-tick counts of a wave (e_l: lane q holds tick q's count, 0 elsewhere), ascending,
+// 0xFFFFFFFF where there are fewer; returns the number of positive counts.  Wave-uniform results.
+__device__ __forceinline__ int smallest_four(uint32_t e_l, int lane, uint32_t (&m4)[4]) {
+  const int npos = __popcll(__ballot(e_l > 0u));
+  uint32_t cur = e_l > 0u ? e_l : 0xFFFFFFFFu;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    m4[i] = wave_min_u32(cur);
+    const uint64_t at = __ballot(cur == m4[i] && cur != 0xFFFFFFFFu);
+    if (at != 0 && lane == __builtin_ctzll(at)) cur = 0xFFFFFFFFu;   // one lane leaves per round
+  }
+  return npos;
+}
+
+// Where the walk finds the rank `need` (1 .. n_eq) among the ticks weighted by their counts of lengths equal to x_j,
+// with its list of four ticks: from the top if the four ticks of largest prefill time are sure to weigh `need`
+// together (need <= 4, or at most four ticks have such lengths, or the four smallest positive counts add up to it),
+// else from the bottom by the same test on n_eq - need + 1, else not at all (returns false; `place` = need).
+__device__ __forceinline__ bool tight_place(int need, int n_eq, int npos, uint32_t s4, uint32_t* place) {
+  const int below = n_eq - need + 1;
+  *place = (uint32_t)need;
+  if (need <= 4 || npos <= 4 || (uint32_t)need <= s4) return true;
+  if (below <= 4 || (uint32_t)below <= s4) {
+    *place = (uint32_t)below | DYN_TIGHT_FROM_BELOW;
+    return true;
+  }
+  return false;
+}
+
 template <int P>   // P registers = 2P rows
 __device__ __forceinline__ bool tight_cell(const int32_t* __restrict__ in, const int32_t* __restrict__ out, int64_t beg_l,
                                            int32_t cnt_l, int T, int rpt, int m, int rank, float theta, int lane,
@@ -195,11 +224,15 @@ __device__ __forceinline__ bool tight_cell(const int32_t* __restrict__ in, const
     }
   }
   const int need = j - n_gt;             // 1 .. n_eq
-  uint32_t place = (uint32_t)need;       // beyond four from both ends: for the general kernel, from the top
+  uint32_t place = (uint32_t)need;       // out of the list's reach from both ends: for the general kernel, from the top
   res->walk = true;
-  if (need > 4) {
-    if (n_eq - need + 1 <= 4) place = (uint32_t)(n_eq - need + 1) | DYN_TIGHT_FROM_BELOW;
-    else res->walk = false;
+  if (need > 4 && n_eq - need + 1 > 4) {
+    uint32_t m4[4];
+    const int npos = smallest_four(eq_l, lane, m4);
+    const uint32_t s4 = npos >= 4 ? m4[0] + m4[1] + m4[2] + m4[3] : 0u;   // counts stay below 2^24
+    res->walk = tight_place(need, n_eq, npos, s4, &place);
+  } else if (need > 4) {
+    place = (uint32_t)(n_eq - need + 1) | DYN_TIGHT_FROM_BELOW;
   }
   res->need = (uint32_t)need;
   res->tok_l = tok_l;
@@ -296,7 +329,8 @@ constexpr int kTightBlocks = 1024;
 template <int P>   // P registers = 2P rows per wave
 __device__ __forceinline__ bool tight_cell_block(const int32_t* __restrict__ in, const int32_t* __restrict__ out,
                                                  int64_t beg_l, int32_t cnt_l, int T, int rpt, int m, int rank, float theta,
-                                                 int lane, int wave, uint32_t* s_x /* [2][kWavesPerBlock] */, TightCell* res) {
+                                                 int lane, int wave, uint32_t* s_x /* [2][kWavesPerBlock] */,
+                                                 uint32_t* s_m /* [4 * kWavesPerBlock] */, TightCell* res) {
   uint32_t v[P];
   uint32_t orv = 0, vmax = 0, tok_acc = 0, tok_l = 0;
   constexpr int CH = 4;
@@ -411,9 +445,28 @@ __device__ __forceinline__ bool tight_cell_block(const int32_t* __restrict__ in,
   const int need = j - n_gt;
   uint32_t place = (uint32_t)need;
   res->walk = true;
-  if (need > 4) {
-    if (n_eq - need + 1 <= 4) place = (uint32_t)(n_eq - need + 1) | DYN_TIGHT_FROM_BELOW;
-    else res->walk = false;
+  if (need > 4 && n_eq - need + 1 > 4) {   // block-uniform
+    // every wave's four smallest positive counts meet in LDS; the four smallest of the sixteen are the block's
+    uint32_t m4[4];
+    const int npos_w = smallest_four(eq_l, lane, m4);
+    const int npos = (int)block_sum((uint32_t)npos_w);
+    if (lane < 4) s_m[wave * 4 + lane] = lane == 0 ? m4[0] : lane == 1 ? m4[1] : lane == 2 ? m4[2] : m4[3];
+    __syncthreads();
+    uint32_t best[4] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+    for (int i = 0; i < 4 * kWavesPerBlock; ++i) {
+      uint32_t x = s_m[i];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {        // insertion into the ascending four
+        const uint32_t lo = min(best[k], x);
+        x = max(best[k], x);
+        best[k] = lo;
+      }
+    }
+    __syncthreads();                       // s_m is free again
+    const uint32_t s4 = npos >= 4 ? best[0] + best[1] + best[2] + best[3] : 0u;
+    res->walk = tight_place(need, n_eq, npos, s4, &place);
+  } else if (need > 4) {
+    place = (uint32_t)(n_eq - need + 1) | DYN_TIGHT_FROM_BELOW;
   }
   res->need = (uint32_t)need;
   res->tok_l = tok_l;                    // lanes q with q % 4 == wave
@@ -425,6 +478,7 @@ __device__ __forceinline__ bool tight_cell_block(const int32_t* __restrict__ in,
 
 __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_tight_block_kernel(TickCellArgs a) {
   __shared__ uint32_t s_x[2 * kWavesPerBlock];
+  __shared__ uint32_t s_m[4 * kWavesPerBlock];
   const int lane = threadIdx.x & (DYN_WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DYN_WAVE);
   const int T = a.n_tick, G = a.G;
@@ -454,9 +508,9 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_tight_block_ker
     if (m_cell > 0 && m_cell < (1 << 24) && rows <= 128) {
       const float theta = a.theta[g];
       const int m = (int)m_cell, rk = (int)rank;
-      if (rows <= 32) done = tight_cell_block<16>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, wave, s_x, &tc);
-      else if (rows <= 64) done = tight_cell_block<32>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, wave, s_x, &tc);
-      else done = tight_cell_block<64>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, wave, s_x, &tc);
+      if (rows <= 32) done = tight_cell_block<16>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, wave, s_x, s_m, &tc);
+      else if (rows <= 64) done = tight_cell_block<32>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, wave, s_x, s_m, &tc);
+      else done = tight_cell_block<64>(a.in, a.out, beg_l, cnt_l, T, rpt, m, rk, theta, lane, wave, s_x, s_m, &tc);
     }
     __syncthreads();                             // s_x is reused by the next item
     if (!done) continue;
