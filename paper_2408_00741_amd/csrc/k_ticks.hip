@@ -78,16 +78,16 @@ __device__ __forceinline__ uint32_t tbt_route(int32_t cnt_l, int64_t j64, int la
 // counted as often as it holds requests of length x_j.  All the evaluation needs of such a cell is x_j, that rank and
 // the per-tick counts.  A wave takes a cell whose ticks fit its registers (rows of 64 requests, the same number of
 // rows for every tick, two 16-bit lengths to a register), finds x_j by the bit-wise search of the window-level
-// aggregation and counts.  The rank must be at most 4 from the top or from the bottom (the evaluation keeps four ticks).
-// Cells it cannot take (the bound does not hold, ticks too uneven for the registers, token counts of 2^16 or more, a
-// rank beyond four from both ends, a TBT percentile that needs all ticks) are listed for the kernel that builds
-// per-tick lists.
+// aggregation and counts.  The evaluation keeps four ticks: the rank must be within their reach from the top or from
+// the bottom (tight_place), else the cell is ranked over all ticks by the general kernel, like a cell whose TBT
+// percentile needs all ticks.  Cells it cannot take (the bound does not hold, ticks too uneven for the registers,
+// token counts of 2^16 or more) are listed for the kernel that builds per-tick lists.
 struct TightCell {
   uint32_t tok_l;     // lane q: token sum of tick q
   uint32_t eq_l;      // lane q: requests of length x_j in tick q
   uint32_t xj, place; // place: the rank among the ticks, from the top, or from the bottom with DYN_TIGHT_FROM_BELOW set
   uint32_t need;      // the rank from the top
-  bool walk;          // the rank is within four of one end
+  bool walk;          // the rank is within reach of the walk's four ticks from one end
 };
 #define DYN_TIGHT_FROM_BELOW 0x80000000u
 

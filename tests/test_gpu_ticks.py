@@ -237,9 +237,10 @@ def test_walk_lists_pruned_by_the_prefill_spread(dyn, kind, pct):
 @pytest.mark.parametrize("pct", [(99, 100), (1, 2), (1, 1)])
 def test_cells_settled_by_their_ties(dyn, kind, pct):
     """Flat prefill tables (the percentile belongs to a request of length x_j, found from the ticks' counts of such
-    requests) with: lengths from five values (the rank among the ties lies beyond four from both ends: all ticks are
-    ranked), lengths from a range of 270 values at about six requests per value (ranks within four of the top and of
-    the bottom), one token count of 2^16 and more in some cells (those build per-tick lists), half of the trace in one
+    requests) with: lengths from five values (hundreds of ties: at the median the rank among them is out of reach of
+    the walk's four ticks from both ends and all ticks are ranked; at the 99th percentile the four smallest per-tick
+    counts cover it), lengths from a range of 270 values at about six requests per value (ranks within four of the top
+    and of the bottom), one token count of 2^16 and more in some cells (those build per-tick lists), half of the trace in one
     tick (too uneven for one wave's registers), and cells of 10^4 requests (a block per cell)."""
     big = kind == "big-cells"
     w = _random_case(50, 60_000 if big else 13_000, 3 if big else 4, 12, 5.0, crowd=3 if kind == "crowded-tick" else None)
