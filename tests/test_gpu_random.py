@@ -107,3 +107,43 @@ def test_random_draws_tick_level(dyn, block):
             assert_same(w, g, o)
         except AssertionError as e:
             raise AssertionError(f"{tag}\n{e}") from None
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_draws_with_many_ties(dyn, block):
+    """Tick-level draws with flat (or nearly flat) prefill tables and input lengths from a handful of values: every
+    percentile falls among many equal lengths, whose rank the evaluation finds from the ticks' counts of them, with its
+    list of four ticks from either end or by ranking all ticks."""
+    for seed in range(block * PER_BLOCK, (block + 1) * PER_BLOCK):
+        rng = np.random.default_rng(29000 + seed)
+        NW = int(rng.integers(1, 7))
+        T = int(rng.choice([2, 3, 5, 7, 8, 12, 16, 31, 64]))
+        n_req = int(np.exp(rng.uniform(np.log(200), np.log(40000))))
+        in_hi = int(rng.choice([3, 7, 20, 50, 600, 8000]))
+        crowd = int(rng.integers(0, NW * T)) if rng.random() < 0.3 else None
+        w = _random_case(seed, n_req, NW, T, 5.0, in_hi=in_hi, crowd=crowd)
+        pf = w["profile"]["prefill_ms_per_tok"]
+        pf[...] = rng.uniform(0.05, 0.3, pf.shape[:3] + (1,))
+        if rng.random() < 0.2:
+            pf *= 1 + rng.uniform(0, 10.0 ** -rng.integers(3, 9), pf.shape)
+        n = w["trace"]["in_tok"].size
+        kind = str(rng.choice(["few", "narrow", "top"]))
+        if kind == "few":
+            w["trace"]["in_tok"] = rng.choice(rng.integers(0, in_hi, 5), n).astype(np.int32)
+        elif kind == "narrow":
+            base = int(rng.integers(0, max(1, in_hi - 40)))
+            w["trace"]["in_tok"] = rng.integers(base, base + 40, n).astype(np.int32)
+        else:
+            w["trace"]["in_tok"] = rng.integers(max(0, in_hi - 6), in_hi, n).astype(np.int32)
+        pct = PCTS[int(rng.integers(0, len(PCTS)))]
+        tag = f"seed {seed}: NW {NW} T {T} n {n_req} in_hi {in_hi} crowd {crowd} lengths {kind} pct {pct}"
+        g, fine = gpu_ticks(dyn, w, T, pct=pct)
+        o = ora_ticks(w, fine, T, pct=pct)
+        j_max = (o["m"] - np.ceil(pct[0] * o["m"] / pct[1]) + 1).max()
+        if g["status"] == dyn.DYN_WS_TICK_RANK and j_max > dyn.DYN_TICK_DEPTH:
+            continue
+        assert g["status"] == 0, tag
+        try:
+            assert_same(w, g, o)
+        except AssertionError as e:
+            raise AssertionError(f"{tag}\n{e}") from None
