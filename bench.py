@@ -352,7 +352,7 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
     status = dyn.dyn_workspace_status(ws)
-    assert status == 0 or (args.ticks and status == dyn.DYN_WS_TICK_RANK), status
+    assert status == 0, status
 
     # ---- the same step timed one by one with a pair of HIP events each, on the stream the kernels are launched on
     # (torch's current stream is the one the binding hands to the library): the median of at least 20 repetitions

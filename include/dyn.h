@@ -176,7 +176,7 @@ typedef struct {
 /* Status bits kept in the first 4 bytes of a workspace. */
 #define DYN_WS_BAD_OFFSETS 1u /* cell_off not monotone / outside [0, n_req]: cell treated as empty */
 #define DYN_WS_BAD_REQUEST 2u /* ingest: timestamp or model index out of range          */
-#define DYN_WS_TICK_RANK 4u   /* tick evaluation: a cell's percentile lies deeper than DYN_TICK_DEPTH */
+#define DYN_WS_TICK_RANK 4u   /* not raised any more (tick evaluation once left cells deeper than DYN_TICK_DEPTH out) */
 #define DYN_WS_SORT_ABANDONED 8u /* ingest: the general sort stopped waiting for its own blocks after seconds
                                   * (the device was held by other work); the sorted outputs are not valid  */
 
@@ -283,9 +283,9 @@ int dyn_eval_select_static(dyn_profile* profile, const dyn_trace_view* trace, co
  * `space` and `sel` are indexed by the coarse cell w * G + g: [n_window*G][K], [n_window*G]
  * and [n_window].  1 <= n_tick <= DYN_TICK_LIMIT, else DYN_E_SHAPE.
  * The percentile of a cell with m requests is its j-th largest value, j = m - rank + 1; any
- * j up to DYN_TICK_DEPTH is evaluated (m < 819200 at P99).  A cell beyond that is not: its
- * percentiles are +inf, its TTFT and TBT flags are set, sel = -1, and DYN_WS_TICK_RANK is
- * raised in the workspace status (its energies are still written).
+ * j is evaluated.  A cell whose prefill tables depend on the load and whose j exceeds
+ * DYN_TICK_DEPTH (m >= 819200 at P99) takes a slow route: no sorted per-tick lists, every
+ * probe of the search scans the cell's requests.
  * Workspace: dyn_eval_ticks_workspace bytes (it depends on the number of requests: the
  * per-tick candidate lists take 4 bytes per request), DEVICE, 256-byte aligned.          */
 #define DYN_TICK_LIMIT 64

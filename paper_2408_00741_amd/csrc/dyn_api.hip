@@ -825,6 +825,7 @@ int dyn_eval_select_ticks(dyn_profile* p, const dyn_trace_view* t, int32_t n_tic
   a.part = (SelPart*)(base + w.part); a.n_wslot = w.n_wslot;
   ta.n_tick = n_tick; ta.tick_s = t->window_s; ta.window_s = (double)n_tick * t->window_s;
   ta.rec = (const TickRec*)(base + w.fine.rec); ta.plan = (const TickPlan*)(base + w.plan); ta.top = (const int32_t*)(base + w.top);
+  ta.in = t->in_tok;
   ta.counters = (const uint32_t*)(base + w.counters); ta.slow_list = (const uint32_t*)(base + w.slow_list);
   ta.tstart = p->d_tstart; ta.thr = p->d_thr; ta.single_point = p->single_point; ta.any_two_rows = p->any_two_rows;
   ta.pfspan = p->d_pfspan; ta.n_cu = p->n_cu;

@@ -27,7 +27,7 @@ struct TickPlan {
 #define DYN_TP_DENSE 1u   // every non-empty tick holds at least j requests: the TBT percentile is the largest tick TBT
 #define DYN_TP_SMALL 2u   // the four non-empty ticks of largest TBT hold at least j requests, whichever they are
 #define DYN_TP_DEEP 4u    // j > DYN_TICK_WAVE: lists and xj come from the deep-cell kernel
-#define DYN_TP_SKIP 8u    // j > DYN_TICK_DEPTH: not evaluated
+#define DYN_TP_RAW 8u     // j > DYN_TICK_DEPTH: no lists; the general kernel scans the ticks' requests themselves (xj holds the cell's largest input length)
 #define DYN_TP_GENERAL 16u  // left to the general kernel: j beyond the walk's register list, or a TBT percentile that needs all ticks
 #define DYN_TP_TIGHT 32u   // settled by the ticks' requests of length xj (TickRec.off then holds their number, not a list offset)
 
@@ -59,6 +59,7 @@ struct TickArgs {
   const TickRec* rec;      // [cells][n_tick]
   const TickPlan* plan;    // [cells]
   const int32_t* top;      // [n_req]
+  const int32_t* in;       // [n_req] input lengths of the trace sorted by tick (DYN_TP_RAW cells)
   const int32_t* tstart; const double* thr; bool single_point;   // threshold form of the bucket index
   bool any_two_rows;
   int32_t n_cu;               // compute units of the device (0: unknown)

@@ -575,19 +575,19 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
   const int64_t m_cell = (int64_t)wave_sum_u64((uint64_t)(uint32_t)cnt_l);
   const int64_t rank = (a.pct_num * m_cell + a.pct_den - 1) / a.pct_den;
   const int64_t j64 = m_cell > 0 ? m_cell - rank + 1 : 0;
-  const bool skip = j64 > DYN_TICK_DEPTH;
-  const bool deep = !skip && j64 > DYN_TICK_WAVE;
-  const int keep = (skip || deep) ? 0 : (int)j64;               // wave-uniform, 0 .. 64
+  const bool raw = j64 > DYN_TICK_DEPTH;         // deeper than any list: the general kernel scans the requests themselves
+  const bool deep = !raw && j64 > DYN_TICK_WAVE;
+  const int keep = (raw || deep) ? 0 : (int)j64;                // wave-uniform, 0 .. 64
 
   // How the TBT percentile can be found: from the largest tick TBT when every non-empty tick holds
   // j requests; from the four largest tick TBTs when any four non-empty ticks hold j between them
   // (the four smallest counts do, or there are no more than four).
-  uint32_t flags = skip ? DYN_TP_SKIP : (deep ? DYN_TP_DEEP : 0u);
+  uint32_t flags = raw ? DYN_TP_RAW : (deep ? DYN_TP_DEEP : 0u);
   if (m_cell > 0) {
     flags |= tbt_route(cnt_l, j64, lane);
     // the walk kernel keeps a register list of 16 candidates beside the largest tick TBT, of 8 beside the four largest
     const bool walk = ((flags & DYN_TP_DENSE) && j64 <= kFastDepth) || ((flags & DYN_TP_SMALL) && j64 <= kFastDepth / 2);
-    if (!skip && !walk) flags |= DYN_TP_GENERAL;
+    if (raw || !walk) flags |= DYN_TP_GENERAL;
   }
 
   int32_t* buf = s_buf[wave];
@@ -639,6 +639,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
   uint32_t neg_mask_lo = 0, neg_mask_hi = 0;    // ticks holding a negative token count
   int32_t gbest = -1;                           // the j largest input lengths of the cell so far
   bool g_empty = true;
+  int32_t vmax = 0;                             // largest input length of the cell (used for DYN_TP_RAW cells)
   // (x, y) always hold the row after the one being processed: the next row of the same tick,
   // else the first row of the next tick
   int32_t x, y;
@@ -668,6 +669,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
       else fetch(beg_n, n_n);
       acc += have ? (uint64_t)((int64_t)cx + (int64_t)cy) : 0;
       orv |= have ? (uint32_t)(cx | cy) : 0u;
+      vmax = max(vmax, cx);                       // -1 in lanes without a request
       if (keep == 0) continue;
       const int32_t thr = __builtin_amdgcn_readlane(best, keep - 1);
       best = merge(best, cx, have && cx > thr);    // a value <= thr has `keep` kept values ahead of it
@@ -702,19 +704,19 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
     a.rec[c * T + lane] = r;
     const uint32_t neg = lane < 32 ? (neg_mask_lo >> lane) & 1u : (neg_mask_hi >> (lane - 32)) & 1u;
     // every fine cell writes its own status byte: nothing to clear beforehand
-    a.cstat[f] = (uint8_t)(bad_l | (neg ? DYN_WS_BAD_REQUEST : 0u) | ((skip && lane == 0) ? DYN_WS_TICK_RANK : 0u));
+    a.cstat[f] = (uint8_t)(bad_l | (neg ? DYN_WS_BAD_REQUEST : 0u));
   }
-  const int32_t xj = keep > 0 ? __builtin_amdgcn_readlane(gbest, keep - 1) : 0;
+  const int32_t xj = keep > 0 ? __builtin_amdgcn_readlane(gbest, keep - 1) : (raw ? wave_max_i32(vmax) : 0);
   if (lane == 0) {
     TickPlan p;
-    p.j = skip ? 0x7FFFFFFF : (int32_t)j64;
+    p.j = (int32_t)j64;                          // below 2^31 like the number of requests
     p.xj = xj < 0 ? 0 : xj;
     p.flags = flags;
     p.place = 0;
     a.plan[c] = p;
     if (deep) a.deep_list[atomicAdd(&a.counters[0], 1u)] = (uint32_t)c;
     if (flags & DYN_TP_GENERAL) a.slow_list[atomicAdd(&a.counters[1], 1u)] = (uint32_t)c;
-    else if (!skip && j64 > 0) atomicAdd(&a.counters[3], 1u);   // a cell the walk takes with its lists
+    else if (j64 > 0) atomicAdd(&a.counters[3], 1u);   // a cell the walk takes with its lists
   }
 }
 
@@ -1147,7 +1149,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
   bool any = false;
   for (int w = w0; w < w1; ++w) {
     const TickPlan p = a.plan[(size_t)w * sa.G + g];
-    any = any || (p.j > 0 && !(p.flags & (DYN_TP_GENERAL | DYN_TP_SKIP | DYN_TP_TIGHT)));
+    any = any || (p.j > 0 && !(p.flags & (DYN_TP_GENERAL | DYN_TP_TIGHT)));
   }
   if (!any) return;                                             // block-uniform
 
@@ -1184,7 +1186,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
   const double theta = (double)__uint_as_float(ratio_bits);
 
   // the cells this kernel walks with candidates: their lists are staged [position][tick]
-  auto listed = [&](const TickPlan& p) { return p.j > 0 && !(p.flags & (DYN_TP_GENERAL | DYN_TP_SKIP | DYN_TP_TIGHT)); };
+  auto listed = [&](const TickPlan& p) { return p.j > 0 && !(p.flags & (DYN_TP_GENERAL | DYN_TP_TIGHT)); };
   int32_t pre[NPRE];
   auto prefetch = [&](int w) {
     if (w >= w1) return;
@@ -1274,7 +1276,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
   uint16_t* s_js = (uint16_t*)(s_eq + sa.win_per_block * T);    // [n_bucket + 1]
 
   auto mine = [](const TickPlan& p) {
-    return p.j == 0 || (p.flags & DYN_TP_SKIP) || ((p.flags & DYN_TP_TIGHT) && !(p.flags & DYN_TP_GENERAL));
+    return p.j == 0 || ((p.flags & DYN_TP_TIGHT) && !(p.flags & DYN_TP_GENERAL));
   };
   bool any = false;
   for (int w = w0; w < w1; ++w) any = any || mine(a.plan[(size_t)w * sa.G + g]);
@@ -1301,11 +1303,11 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
     const double* load_w = s_load + (w - w0) * T;
     const int32_t* eq_w = s_eq + (w - w0) * T;
     const int j = pl.j;
-    const bool skip = (pl.flags & DYN_TP_SKIP) != 0, empty = j == 0;
+    const bool empty = j == 0;
     WalkOut o;
-    if (empty || skip) {
+    if (empty) {
       o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, 0, load_w, cnt_w, eq_w, 0, st.nd, a.tick_s);
-      o.ttft = o.tbt = empty ? 0.0 : __builtin_inf();   // a cell that is not evaluated is reported through the status word
+      o.ttft = o.tbt = 0.0;
     } else if (pl.flags & DYN_TP_DENSE) {
       o = walk_ticks<4, false, SINGLE, TWO, true>(st.L, T, j, load_w, cnt_w, eq_w, pl.xj, st.nd, a.tick_s, pl.place);
     } else {
@@ -1391,12 +1393,13 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
     const int j = pl.j;
     const bool dense = (pl.flags & DYN_TP_DENSE) != 0;
     const bool tight = (pl.flags & DYN_TP_TIGHT) != 0;   // no lists: per tick the number of requests of length x_j, and the rank among them
+    const bool raw = (pl.flags & DYN_TP_RAW) != 0;       // no lists either: the ticks' requests themselves, unsorted; x_j holds the largest length
     const TickRec* rec = a.rec + cell * T;
     if (tid < DYN_WAVE) {                      // the first wave, a tick per lane: where each tick's list is read from
       TickRec r;
       r.load = 0.0; r.off = 0u; r.cnt = 0;
       if (tid < T) r = rec[tid];
-      const int len = (tid < T && !tight) ? min(r.cnt, j) : 0;
+      const int len = (tid < T && !tight) ? (raw ? r.cnt : min(r.cnt, j)) : 0;
       int incl = len;                          // inclusive prefix over the ticks
 #pragma unroll
       for (int d = 1; d < DYN_WAVE; d <<= 1) {
@@ -1404,7 +1407,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
         if (tid >= d) incl += up;
       }
       const uint32_t total = (uint32_t)__builtin_amdgcn_readlane(incl, DYN_WAVE - 1);
-      const bool fits = total <= (uint32_t)kListCap;
+      const bool fits = !raw && total <= (uint32_t)kListCap;
       if (tid < T) {
         s_load[tid] = r.load;
         s_cnt[tid] = r.cnt;
@@ -1433,8 +1436,9 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
       }
       __syncthreads();
     }
-    const int32_t* lists = staged ? s_lists : a.top;
-    if (tid < T && !tight) {                   // per tick: listed lengths above x_j and equal to it (the list is descending)
+    const int32_t* lists = staged ? s_lists : (raw ? a.in : a.top);
+    if (tid < T && raw) s_neq[tid] = 0;
+    if (tid < T && !tight && !raw) {                   // per tick: listed lengths above x_j and equal to it (the list is descending)
       const int len = s_len[tid];
       const int32_t* lq = lists + s_lbase[tid];
       int l = 0, h = len;                      // first entry <= x_j
@@ -1453,7 +1457,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
     }
     __syncthreads();
     const double xj = (double)pl.xj;
-    const int need_eq = tight ? (int)pl.place : j - (int)s_lbase[T + 1];   // >= 1: fewer than j lengths lie above the j-th largest
+    const int need_eq = tight ? (int)pl.place : (raw ? 0 : j - (int)s_lbase[T + 1]);   // >= 1: fewer than j lengths lie above the j-th largest
 
     for (int sub = 0; sub < sa.tile; sub += NT) {
       const bool in_tile = sub + (tid & ~(DYN_WAVE - 1)) < sa.tile;   // wave-uniform: a wave past the tile's end stores nothing
@@ -1486,9 +1490,10 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
         }
       }
       // TTFT percentile
-      double lo = xj * pf_min, hi = xj * pf_max;
+      // (a cell without lists: every scaled length lies in [0, largest length x largest prefill time])
+      double lo = raw ? 0.0 : xj * pf_min, hi = xj * pf_max;
       bool open = lo != hi;
-      if (tight || (open && xj * pf_max < (xj + 0.5) * pf_min)) {
+      if (tight || (!raw && open && xj * pf_max < (xj + 0.5) * pf_min)) {
         // only lengths equal to x_j scale into the bracket: rank the ticks' prefill times by those
         lo = hi = xj * weighted_from_top(s_strip, s_neq, T, NT, need_eq, tid);
         open = false;
@@ -1503,6 +1508,16 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
           if (len == 0) continue;
           const double pf = s_strip[q * NT + tid];
           const int32_t* lq = lists + s_lbase[q];
+          if (raw) {                           // block-uniform: the tick's requests in trace order, every one is scaled
+            for (int i = 0; i < len; ++i) {
+              const double sv = (double)lq[i] * pf;
+              const bool ge = sv >= v;
+              n_ge += ge ? 1 : 0;
+              a_min = ge ? min_num(a_min, sv) : a_min;
+              b_max = ge ? b_max : max_num(b_max, sv);
+            }
+            continue;
+          }
           int l = 0, h = len;                  // entries [0, l) are >= v scaled, entries [h, len) are below
           while (l < h) {
             const int mid = (l + h) >> 1;

@@ -281,18 +281,23 @@ def test_sparse_ticks_take_the_general_route(dyn, pct):
     assert (four_smallest < j).any()
 
 
-def test_deepest_supported_rank(dyn):
-    """One cell whose median is exactly DYN_TICK_DEPTH deep (m = 16383) is evaluated; one more request is not."""
-    for extra, expect in ((0, 0), (1, 4)):
+def test_ranks_around_the_depth_of_the_lists(dyn):
+    """One cell whose median is exactly DYN_TICK_DEPTH deep (m = 16383: the deepest that gets per-tick lists), one
+    request more (searched over the requests themselves), and cells three times as deep with half of the trace in
+    one tick, at the median and at the first percentile (j = 99 % of the cell)."""
+    for extra in (0, 1):
         w = _one_class(_random_case(5, 2 * dyn.DYN_TICK_DEPTH - 1 + extra, 1, 8, 5.0, in_hi=5000))
         g, fine = gpu_ticks(dyn, w, 8, pct=(1, 2))
-        assert g["status"] == expect
-        o = ora_ticks(w, fine, 8, pct=(1, 2))
-        if expect == 0:
-            assert_same(w, g, o)
-        else:
-            np.testing.assert_array_equal(g["energy_j"], o["energy_j"])
-            assert np.all(np.isinf(g["p99_ttft_ms"])) and np.all(g["sel"] == -1) and np.all(g["flags"] & 12 == 12)
+        assert g["status"] == 0
+        assert_same(w, g, ora_ticks(w, fine, 8, pct=(1, 2)))
+    for pct, crowd in (((1, 2), 3), ((1, 100), None), ((99, 100), 5)):
+        w = _random_case(6, 50_000, 1, 8, 5.0, in_hi=3000, crowd=crowd)
+        g, fine = gpu_ticks(dyn, w, 8, pct=pct)
+        o = ora_ticks(w, fine, 8, pct=pct)
+        assert g["status"] == 0
+        assert_same(w, g, o)
+        j = o["m"] - np.ceil(pct[0] * o["m"] / pct[1]) + 1
+        assert pct == (99, 100) or j.max() > dyn.DYN_TICK_DEPTH
 
 
 def test_empty_trace_and_empty_ticks(dyn):
