@@ -12,7 +12,9 @@
 //                      descending order (j <= 64: kept sorted in a wave's lanes) and the cell's
 //                      j-th largest input length x_j; what the later kernels do with the cell;
 //   tick_deep_kernel   the same lists and x_j for the cells with j > 64 (a block per cell:
-//                      bitonic sort of a tick in LDS);
+//                      bitonic sort of a tick in LDS); beyond j = 8192 the lists are whole ticks, and a
+//                      tick of more than 8192 requests is then left as it is in the trace (marked:
+//                      the general kernel scans it instead of searching a sorted list);
 //   tick_space_kernel  the cells with j <= 16: per (cell, configuration) a walk over the ticks, energy in time
 //                      order, the TBT percentile (largest tick TBT when every non-empty tick holds j
 //                      requests, else from the four largest tick TBTs), the TTFT percentile through a
@@ -575,7 +577,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
   const int64_t m_cell = (int64_t)wave_sum_u64((uint64_t)(uint32_t)cnt_l);
   const int64_t rank = (a.pct_num * m_cell + a.pct_den - 1) / a.pct_den;
   const int64_t j64 = m_cell > 0 ? m_cell - rank + 1 : 0;
-  const bool raw = j64 > DYN_TICK_DEPTH;         // deeper than any list: the general kernel scans the requests themselves
+  const bool raw = j64 > DYN_TICK_DEPTH;         // deeper than a cut-down list: whole ticks are sorted, or scanned unsorted
   const bool deep = !raw && j64 > DYN_TICK_WAVE;
   const int keep = (raw || deep) ? 0 : (int)j64;                // wave-uniform, 0 .. 64
 
@@ -639,7 +641,6 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
   uint32_t neg_mask_lo = 0, neg_mask_hi = 0;    // ticks holding a negative token count
   int32_t gbest = -1;                           // the j largest input lengths of the cell so far
   bool g_empty = true;
-  int32_t vmax = 0;                             // largest input length of the cell (used for DYN_TP_RAW cells)
   // (x, y) always hold the row after the one being processed: the next row of the same tick,
   // else the first row of the next tick
   int32_t x, y;
@@ -669,7 +670,6 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
       else fetch(beg_n, n_n);
       acc += have ? (uint64_t)((int64_t)cx + (int64_t)cy) : 0;
       orv |= have ? (uint32_t)(cx | cy) : 0u;
-      vmax = max(vmax, cx);                       // -1 in lanes without a request
       if (keep == 0) continue;
       const int32_t thr = __builtin_amdgcn_readlane(best, keep - 1);
       best = merge(best, cx, have && cx > thr);    // a value <= thr has `keep` kept values ahead of it
@@ -706,7 +706,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
     // every fine cell writes its own status byte: nothing to clear beforehand
     a.cstat[f] = (uint8_t)(bad_l | (neg ? DYN_WS_BAD_REQUEST : 0u));
   }
-  const int32_t xj = keep > 0 ? __builtin_amdgcn_readlane(gbest, keep - 1) : (raw ? wave_max_i32(vmax) : 0);
+  const int32_t xj = keep > 0 ? __builtin_amdgcn_readlane(gbest, keep - 1) : 0;
   if (lane == 0) {
     TickPlan p;
     p.j = (int32_t)j64;                          // below 2^31 like the number of requests
@@ -714,7 +714,7 @@ __global__ __launch_bounds__(kWavesPerBlock* DYN_WAVE) void tick_cell_kernel(Tic
     p.flags = flags;
     p.place = 0;
     a.plan[c] = p;
-    if (deep) a.deep_list[atomicAdd(&a.counters[0], 1u)] = (uint32_t)c;
+    if (deep || raw) a.deep_list[atomicAdd(&a.counters[0], 1u)] = (uint32_t)c;   // x_j and the sorted ticks come from there
     if (flags & DYN_TP_GENERAL) a.slow_list[atomicAdd(&a.counters[1], 1u)] = (uint32_t)c;
     else if (j64 > 0) atomicAdd(&a.counters[3], 1u);   // a cell the walk takes with its lists
   }
@@ -764,7 +764,7 @@ __global__ __launch_bounds__(256) void tick_deep_kernel(TickCellArgs a) {
   };
   for (uint32_t it = blockIdx.x; it < n_deep; it += gridDim.x) {
     const int64_t c = a.deep_list[it];
-    const int32_t j = a.plan[c].j;               // 64 < j <= 8192
+    const int32_t j = a.plan[c].j;               // beyond 64; beyond 8192 for DYN_TP_RAW cells
     const TickRec* rec = a.rec + c * T;
     int32_t mx = 0;
     for (int q = 0; q < T; ++q) {
@@ -785,6 +785,9 @@ __global__ __launch_bounds__(256) void tick_deep_kernel(TickCellArgs a) {
         n_sort = r.cnt;
         n_out = r.cnt < j ? r.cnt : j;
         for (int i = tid; i < r.cnt; i += 256) s_val[i] = src[i];
+      } else if (j > kDeepCap) {                 // block-uniform: neither the tick nor its j largest fit: left unsorted
+        if (tid == 0) a.rec[c * T + q].off = r.off | DYN_TICK_UNSORTED;
+        continue;
       } else {                                   // more than 8192 requests, of which the j <= 8192 largest are wanted
         const int32_t thr = jth_largest(rec, q, q + 1, bits, j);
         if (tid == 0) s_fill = 0u;
@@ -1393,12 +1396,14 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
     const int j = pl.j;
     const bool dense = (pl.flags & DYN_TP_DENSE) != 0;
     const bool tight = (pl.flags & DYN_TP_TIGHT) != 0;   // no lists: per tick the number of requests of length x_j, and the rank among them
-    const bool raw = (pl.flags & DYN_TP_RAW) != 0;       // no lists either: the ticks' requests themselves, unsorted; x_j holds the largest length
+    const bool raw = (pl.flags & DYN_TP_RAW) != 0;       // the lists are whole ticks; a tick marked DYN_TICK_UNSORTED is read from the trace as it is
     const TickRec* rec = a.rec + cell * T;
     if (tid < DYN_WAVE) {                      // the first wave, a tick per lane: where each tick's list is read from
       TickRec r;
       r.load = 0.0; r.off = 0u; r.cnt = 0;
       if (tid < T) r = rec[tid];
+      const bool unsorted = raw && (r.off & DYN_TICK_UNSORTED) != 0u;
+      const uint32_t off = raw ? (r.off & ~DYN_TICK_UNSORTED) : r.off;
       const int len = (tid < T && !tight) ? (raw ? r.cnt : min(r.cnt, j)) : 0;
       int incl = len;                          // inclusive prefix over the ticks
 #pragma unroll
@@ -1411,9 +1416,9 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
       if (tid < T) {
         s_load[tid] = r.load;
         s_cnt[tid] = r.cnt;
-        s_len[tid] = len;
-        s_goff[tid] = r.off;
-        s_lbase[tid] = fits ? (uint32_t)(incl - len) : r.off;
+        s_len[tid] = unsorted ? -len : len;      // negative: the tick's requests in trace order, every probe scans them
+        s_goff[tid] = off;
+        s_lbase[tid] = fits ? (uint32_t)(incl - len) : off;
         if (tight) s_neq[tid] = (int32_t)r.off;
       }
       if (tid == 0) {
@@ -1436,9 +1441,9 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
       }
       __syncthreads();
     }
-    const int32_t* lists = staged ? s_lists : (raw ? a.in : a.top);
-    if (tid < T && raw) s_neq[tid] = 0;
-    if (tid < T && !tight && !raw) {                   // per tick: listed lengths above x_j and equal to it (the list is descending)
+    const int32_t* lists = staged ? s_lists : a.top;
+    if (tid < T && !tight && s_len[tid] < 0) s_neq[tid] = 0;
+    if (tid < T && !tight && s_len[tid] >= 0) {        // per tick: listed lengths above x_j and equal to it (the list is descending)
       const int len = s_len[tid];
       const int32_t* lq = lists + s_lbase[tid];
       int l = 0, h = len;                      // first entry <= x_j
@@ -1455,9 +1460,26 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
       s_neq[tid] = l - n_gt;
       if (n_gt) atomicAdd(&s_lbase[T + 1], (uint32_t)n_gt);
     }
+    if (raw) {                                 // block-uniform: the same two counts of the unsorted ticks, by the whole block
+      __syncthreads();
+      for (int q = 0; q < T; ++q) {
+        const int len = -s_len[q];
+        if (len <= 0) continue;
+        const int32_t* lq = a.in + s_lbase[q];
+        uint32_t n_gt = 0;
+        int32_t n_eq = 0;
+        for (int i = tid; i < len; i += NT) {
+          const int32_t x = lq[i];
+          n_gt += x > pl.xj ? 1u : 0u;
+          n_eq += x == pl.xj ? 1 : 0;
+        }
+        if (n_gt) atomicAdd(&s_lbase[T + 1], n_gt);
+        if (n_eq) atomicAdd(&s_neq[q], n_eq);
+      }
+    }
     __syncthreads();
     const double xj = (double)pl.xj;
-    const int need_eq = tight ? (int)pl.place : (raw ? 0 : j - (int)s_lbase[T + 1]);   // >= 1: fewer than j lengths lie above the j-th largest
+    const int need_eq = tight ? (int)pl.place : j - (int)s_lbase[T + 1];   // >= 1: fewer than j lengths lie above the j-th largest
 
     for (int sub = 0; sub < sa.tile; sub += NT) {
       const bool in_tile = sub + (tid & ~(DYN_WAVE - 1)) < sa.tile;   // wave-uniform: a wave past the tile's end stores nothing
@@ -1490,10 +1512,9 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
         }
       }
       // TTFT percentile
-      // (a cell without lists: every scaled length lies in [0, largest length x largest prefill time])
-      double lo = raw ? 0.0 : xj * pf_min, hi = xj * pf_max;
+      double lo = xj * pf_min, hi = xj * pf_max;
       bool open = lo != hi;
-      if (tight || (!raw && open && xj * pf_max < (xj + 0.5) * pf_min)) {
+      if (tight || (open && xj * pf_max < (xj + 0.5) * pf_min)) {
         // only lengths equal to x_j scale into the bracket: rank the ticks' prefill times by those
         lo = hi = xj * weighted_from_top(s_strip, s_neq, T, NT, need_eq, tid);
         open = false;
@@ -1504,11 +1525,12 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
         int n_ge = 0;
         double a_min = __builtin_inf(), b_max = -__builtin_inf();
         for (int q = 0; q < T; ++q) {
-          const int len = s_len[q];
+          int len = s_len[q];
           if (len == 0) continue;
           const double pf = s_strip[q * NT + tid];
-          const int32_t* lq = lists + s_lbase[q];
-          if (raw) {                           // block-uniform: the tick's requests in trace order, every one is scaled
+          const int32_t* lq = (len < 0 ? a.in : lists) + s_lbase[q];
+          if (len < 0) {                       // block-uniform: the tick's requests in trace order, every one is scaled
+            len = -len;
             for (int i = 0; i < len; ++i) {
               const double sv = (double)lq[i] * pf;
               const bool ge = sv >= v;
