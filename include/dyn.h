@@ -283,9 +283,8 @@ int dyn_eval_select_static(dyn_profile* profile, const dyn_trace_view* trace, co
  * `space` and `sel` are indexed by the coarse cell w * G + g: [n_window*G][K], [n_window*G]
  * and [n_window].  1 <= n_tick <= DYN_TICK_LIMIT, else DYN_E_SHAPE.
  * The percentile of a cell with m requests is its j-th largest value, j = m - rank + 1; any
- * j is evaluated.  In a cell whose prefill tables depend on the load and whose j exceeds
- * DYN_TICK_DEPTH (m >= 819200 at P99), a tick of more than DYN_TICK_DEPTH requests is slow:
- * it is not sorted, and every probe of the search scans its requests.
+ * j is evaluated (DYN_TICK_DEPTH is the depth up to which a tick's list is cut down to its
+ * j largest input lengths; beyond it whole ticks are sorted, long ones in pieces).
  * Workspace: dyn_eval_ticks_workspace bytes (it depends on the number of requests: the
  * per-tick candidate lists take 4 bytes per request), DEVICE, 256-byte aligned.          */
 #define DYN_TICK_LIMIT 64

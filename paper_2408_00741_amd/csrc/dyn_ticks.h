@@ -27,8 +27,8 @@ struct TickPlan {
 #define DYN_TP_DENSE 1u   // every non-empty tick holds at least j requests: the TBT percentile is the largest tick TBT
 #define DYN_TP_SMALL 2u   // the four non-empty ticks of largest TBT hold at least j requests, whichever they are
 #define DYN_TP_DEEP 4u    // j > DYN_TICK_WAVE: lists and xj come from the deep-cell kernel
-#define DYN_TP_RAW 8u     // j > DYN_TICK_DEPTH: the lists are whole ticks, sorted; a tick too long to sort in LDS stays as it is in the trace
-#define DYN_TICK_UNSORTED 0x80000000u   // in TickRec.off of such a tick: scan `in` from the offset in the other bits (offsets stay below 2^31)
+#define DYN_TP_RAW 8u     // j > DYN_TICK_DEPTH: the lists are whole ticks, sorted
+#define DYN_TICK_PIECES 0x80000000u   // in TickRec.off of a tick of such a cell that is too long to sort in LDS: its list is sorted in pieces of DYN_TICK_DEPTH (offsets stay below 2^31)
 #define DYN_TP_GENERAL 16u  // left to the general kernel: j beyond the walk's register list, or a TBT percentile that needs all ticks
 #define DYN_TP_TIGHT 32u   // settled by the ticks' requests of length xj (TickRec.off then holds their number, not a list offset)
 

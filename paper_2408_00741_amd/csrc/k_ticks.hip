@@ -13,8 +13,8 @@
 //                      j-th largest input length x_j; what the later kernels do with the cell;
 //   tick_deep_kernel   the same lists and x_j for the cells with j > 64 (a block per cell:
 //                      bitonic sort of a tick in LDS); beyond j = 8192 the lists are whole ticks, and a
-//                      tick of more than 8192 requests is then left as it is in the trace (marked:
-//                      the general kernel scans it instead of searching a sorted list);
+//                      tick of more than 8192 requests is then sorted in pieces of 8192 (marked: the
+//                      general kernel searches every piece);
 //   tick_space_kernel  the cells with j <= 16: per (cell, configuration) a walk over the ticks, energy in time
 //                      order, the TBT percentile (largest tick TBT when every non-empty tick holds j
 //                      requests, else from the four largest tick TBTs), the TTFT percentile through a
@@ -776,34 +776,8 @@ __global__ __launch_bounds__(256) void tick_deep_kernel(TickCellArgs a) {
     const int bits = 32 - __builtin_clz((uint32_t)mx | 1u);   // mx >= 0: at most 31
     const int32_t xj = jth_largest(rec, 0, T, bits, j);
     if (tid == 0) a.plan[c].xj = xj;
-    for (int q = 0; q < T; ++q) {
-      const TickRec r = rec[q];
-      if (r.cnt == 0) continue;                  // block-uniform
-      const int32_t* src = a.in + r.off;
-      int n_sort, n_out;
-      if (r.cnt <= kDeepCap) {
-        n_sort = r.cnt;
-        n_out = r.cnt < j ? r.cnt : j;
-        for (int i = tid; i < r.cnt; i += 256) s_val[i] = src[i];
-      } else if (j > kDeepCap) {                 // block-uniform: neither the tick nor its j largest fit: left unsorted
-        if (tid == 0) a.rec[c * T + q].off = r.off | DYN_TICK_UNSORTED;
-        continue;
-      } else {                                   // more than 8192 requests, of which the j <= 8192 largest are wanted
-        const int32_t thr = jth_largest(rec, q, q + 1, bits, j);
-        if (tid == 0) s_fill = 0u;
-        __syncthreads();
-        for (int i = tid; i < r.cnt; i += 256) {
-          const int32_t v = src[i];
-          if (v > thr) {                         // fewer than j of them
-            const uint32_t at = atomicAdd(&s_fill, 1u);
-            if (at < (uint32_t)kDeepCap) s_val[at] = v;
-          }
-        }
-        __syncthreads();
-        const int got = (int)min(s_fill, (uint32_t)j);
-        for (int i = got + tid; i < j; i += 256) s_val[i] = thr;
-        n_sort = n_out = j;
-      }
+    // sorts s_val[0 .. n_sort) descending (bitonic, padded to a power of two) and writes its first n_out entries to dst
+    auto sort_and_store = [&](int n_sort, int n_out, int32_t* dst) {
       int n2 = 2;
       while (n2 < n_sort) n2 <<= 1;              // at most 8192
       for (int i = n_sort + tid; i < n2; i += 256) s_val[i] = (int32_t)0x80000000;
@@ -820,9 +794,40 @@ __global__ __launch_bounds__(256) void tick_deep_kernel(TickCellArgs a) {
           }
           __syncthreads();
         }
-      int32_t* dst = a.top + r.off;
       for (int i = tid; i < n_out; i += 256) dst[i] = s_val[i];
-      __syncthreads();                           // s_val is reused by the next tick
+      __syncthreads();                           // s_val is reused
+    };
+    for (int q = 0; q < T; ++q) {
+      const TickRec r = rec[q];
+      if (r.cnt == 0) continue;                  // block-uniform
+      const int32_t* src = a.in + r.off;
+      int32_t* dst = a.top + r.off;
+      if (r.cnt <= kDeepCap) {
+        for (int i = tid; i < r.cnt; i += 256) s_val[i] = src[i];
+        sort_and_store(r.cnt, r.cnt < j ? r.cnt : j, dst);
+      } else if (j > kDeepCap) {                 // block-uniform: neither the tick nor its j largest fit: sorted piece by piece
+        for (int base = 0; base < r.cnt; base += kDeepCap) {
+          const int n = r.cnt - base < kDeepCap ? r.cnt - base : kDeepCap;
+          for (int i = tid; i < n; i += 256) s_val[i] = src[base + i];
+          sort_and_store(n, n, dst + base);
+        }
+        if (tid == 0) a.rec[c * T + q].off = r.off | DYN_TICK_PIECES;
+      } else {                                   // more than 8192 requests, of which the j <= 8192 largest are wanted
+        const int32_t thr = jth_largest(rec, q, q + 1, bits, j);
+        if (tid == 0) s_fill = 0u;
+        __syncthreads();
+        for (int i = tid; i < r.cnt; i += 256) {
+          const int32_t v = src[i];
+          if (v > thr) {                         // fewer than j of them
+            const uint32_t at = atomicAdd(&s_fill, 1u);
+            if (at < (uint32_t)kDeepCap) s_val[at] = v;
+          }
+        }
+        __syncthreads();
+        const int got = (int)min(s_fill, (uint32_t)j);
+        for (int i = got + tid; i < j; i += 256) s_val[i] = thr;
+        sort_and_store(j, j, dst);
+      }
     }
   }
 }
@@ -1396,14 +1401,14 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
     const int j = pl.j;
     const bool dense = (pl.flags & DYN_TP_DENSE) != 0;
     const bool tight = (pl.flags & DYN_TP_TIGHT) != 0;   // no lists: per tick the number of requests of length x_j, and the rank among them
-    const bool raw = (pl.flags & DYN_TP_RAW) != 0;       // the lists are whole ticks; a tick marked DYN_TICK_UNSORTED is read from the trace as it is
+    const bool raw = (pl.flags & DYN_TP_RAW) != 0;       // the lists are whole ticks; a tick marked DYN_TICK_PIECES is sorted in pieces of DYN_TICK_DEPTH
     const TickRec* rec = a.rec + cell * T;
     if (tid < DYN_WAVE) {                      // the first wave, a tick per lane: where each tick's list is read from
       TickRec r;
       r.load = 0.0; r.off = 0u; r.cnt = 0;
       if (tid < T) r = rec[tid];
-      const bool unsorted = raw && (r.off & DYN_TICK_UNSORTED) != 0u;
-      const uint32_t off = raw ? (r.off & ~DYN_TICK_UNSORTED) : r.off;
+      const bool pieces = raw && (r.off & DYN_TICK_PIECES) != 0u;
+      const uint32_t off = raw ? (r.off & ~DYN_TICK_PIECES) : r.off;
       const int len = (tid < T && !tight) ? (raw ? r.cnt : min(r.cnt, j)) : 0;
       int incl = len;                          // inclusive prefix over the ticks
 #pragma unroll
@@ -1416,7 +1421,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
       if (tid < T) {
         s_load[tid] = r.load;
         s_cnt[tid] = r.cnt;
-        s_len[tid] = unsorted ? -len : len;      // negative: the tick's requests in trace order, every probe scans them
+        s_len[tid] = pieces ? -len : len;        // negative: a long tick whose list is sorted piece by piece
         s_goff[tid] = off;
         s_lbase[tid] = fits ? (uint32_t)(incl - len) : off;
         if (tight) s_neq[tid] = (int32_t)r.off;
@@ -1460,7 +1465,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
       s_neq[tid] = l - n_gt;
       if (n_gt) atomicAdd(&s_lbase[T + 1], (uint32_t)n_gt);
     }
-    if (raw) {                                 // block-uniform: the same two counts of the unsorted ticks, by the whole block
+    if (raw) {                                 // block-uniform: the same two counts of the ticks sorted in pieces, by the whole block (from the trace)
       __syncthreads();
       for (int q = 0; q < T; ++q) {
         const int len = -s_len[q];
@@ -1528,15 +1533,22 @@ __global__ __launch_bounds__(DYN_MAX_TILE) void tick_general_kernel(TickArgs a) 
           int len = s_len[q];
           if (len == 0) continue;
           const double pf = s_strip[q * NT + tid];
-          const int32_t* lq = (len < 0 ? a.in : lists) + s_lbase[q];
-          if (len < 0) {                       // block-uniform: the tick's requests in trace order, every one is scaled
+          const int32_t* lq = lists + s_lbase[q];
+          if (len < 0) {                       // block-uniform: a long tick, sorted piece by piece
             len = -len;
-            for (int i = 0; i < len; ++i) {
-              const double sv = (double)lq[i] * pf;
-              const bool ge = sv >= v;
-              n_ge += ge ? 1 : 0;
-              a_min = ge ? min_num(a_min, sv) : a_min;
-              b_max = ge ? b_max : max_num(b_max, sv);
+            for (int base = 0; base < len; base += DYN_TICK_DEPTH) {
+              const int n = len - base < DYN_TICK_DEPTH ? len - base : DYN_TICK_DEPTH;
+              const int32_t* lp = lq + base;
+              int l = 0, h = n;                // entries [0, l) of the piece are >= v scaled, entries [h, n) are below
+              while (l < h) {
+                const int mid = (l + h) >> 1;
+                const bool ge = (double)lp[mid] * pf >= v;
+                l = ge ? mid + 1 : l;
+                h = ge ? h : mid;
+              }
+              n_ge += l;
+              if (l > 0) a_min = min_num(a_min, (double)lp[l - 1] * pf);
+              if (l < n) b_max = max_num(b_max, (double)lp[l] * pf);
             }
             continue;
           }
