@@ -283,17 +283,18 @@ def test_sparse_ticks_take_the_general_route(dyn, pct):
 
 def test_ranks_around_the_depth_of_the_lists(dyn):
     """One cell whose median is exactly DYN_TICK_DEPTH deep (m = 16383: the deepest that gets per-tick lists), one
-    request more (searched over the requests themselves), and cells three times as deep with half of the trace in
-    one tick, at the median and at the first percentile (j = 99 % of the cell)."""
+    request more (whole ticks sorted), and cells three times as deep with half of the trace in one tick (sorted in
+    pieces), at the median and at the first percentile (j = 99 % of the cell)."""
     for extra in (0, 1):
         w = _one_class(_random_case(5, 2 * dyn.DYN_TICK_DEPTH - 1 + extra, 1, 8, 5.0, in_hi=5000))
         g, fine = gpu_ticks(dyn, w, 8, pct=(1, 2))
         assert g["status"] == 0
         assert_same(w, g, ora_ticks(w, fine, 8, pct=(1, 2)))
-    for pct, crowd in (((1, 2), 3), ((1, 100), None), ((99, 100), 5)):
-        w = _random_case(6, 50_000, 1, 8, 5.0, in_hi=3000, crowd=crowd)
-        g, fine = gpu_ticks(dyn, w, 8, pct=pct)
-        o = ora_ticks(w, fine, 8, pct=pct)
+    for pct, crowd, n_req, T in (((1, 2), 3, 50_000, 8), ((1, 100), None, 50_000, 8), ((99, 100), 5, 50_000, 8),
+                                ((1, 2), 1, 90_000, 4)):          # the last: a tick of 2 x 22 000 requests, sorted in three pieces
+        w = _random_case(6, n_req, 1, T, 5.0, in_hi=3000, crowd=crowd)
+        g, fine = gpu_ticks(dyn, w, T, pct=pct)
+        o = ora_ticks(w, fine, T, pct=pct)
         assert g["status"] == 0
         assert_same(w, g, o)
         j = o["m"] - np.ceil(pct[0] * o["m"] / pct[1]) + 1
