@@ -900,14 +900,15 @@ struct WalkOut {
   bool ov;
 };
 
-// One walk over the ticks of a cell, in time order, two look-ups in flight.  The cell's j <= JF largest scaled
+// One walk over the ticks of a cell, in time order, two look-ups in flight (PAIR; one at a time leaves registers for
+// a fifth wave per SIMD in the kernel without lists, which gains more than the second look-up in flight).  The cell's j <= JF largest scaled
 // candidates go through a sorted list that starts with JF - j copies of +inf, so that its last entry is the j-th
 // largest of what was inserted (j == 0: nothing is inserted).  SPARSE: the TBT percentile from the four largest
 // tick TBTs, else the largest tick TBT.
 // TIGHT: the TTFT percentile is x_j times the prefill time of rank `place` (bit 31: from below) among the ticks, each
 // counted as often as it holds requests of length x_j (`s_top`: that number per tick; `xmin` carries x_j): the four
 // largest (smallest) prefill times are kept with their counts.
-template <int JF, bool SPARSE, bool SINGLE, bool TWO, bool TIGHT = false>
+template <int JF, bool SPARSE, bool SINGLE, bool TWO, bool TIGHT = false, bool PAIR = true>
 __device__ __forceinline__ WalkOut walk_ticks(const Lookup& L, int T, int j, const double* s_load, const int32_t* s_cnt,
                                               const int32_t* s_top, int xmin, double nd, double tick_s, uint32_t place = 0) {
   double s[JF];
@@ -952,7 +953,7 @@ __device__ __forceinline__ WalkOut walk_ticks(const Lookup& L, int T, int j, con
   int q = 0;
   for (; q + 2 <= T; q += 2) {
     const int c0 = s_cnt[q], c1 = s_cnt[q + 1];                 // block-uniform
-    if (c0 > 0 && c1 > 0) {
+    if (PAIR && c0 > 0 && c1 > 0) {
       double pf0, tb0, pw0, pf1, tb1, pw1;
       const bool o0 = table_lookup<SINGLE, TWO>(L, s_load[q], &pf0, &tb0, &pw0);
       const bool o1 = table_lookup<SINGLE, TWO>(L, s_load[q + 1], &pf1, &tb1, &pw1);
@@ -1263,7 +1264,7 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
 //      [per window of the block, per tick: load] [per window: plan] [per window and tick: request count, requests of length x_j]
 //      [bucket index (16-bit)]
 template <bool LDS, bool SINGLE, bool TWO>
-__global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4, 5))) void tick_tight_walk_kernel(TickArgs a) {
+__global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(5, 5))) void tick_tight_walk_kernel(TickArgs a) {
   extern __shared__ double smem[];
   const SpaceArgs& sa = a.s;
   const int tile = blockIdx.x % sa.n_tile;
@@ -1314,12 +1315,12 @@ __global__ __launch_bounds__(DYN_MAX_TILE) __attribute__((amdgpu_waves_per_eu(4,
     const bool empty = j == 0;
     WalkOut o;
     if (empty) {
-      o = walk_ticks<4, false, SINGLE, TWO>(st.L, T, 0, load_w, cnt_w, eq_w, 0, st.nd, a.tick_s);
+      o = walk_ticks<4, false, SINGLE, TWO, false, false>(st.L, T, 0, load_w, cnt_w, eq_w, 0, st.nd, a.tick_s);
       o.ttft = o.tbt = 0.0;
     } else if (pl.flags & DYN_TP_DENSE) {
-      o = walk_ticks<4, false, SINGLE, TWO, true>(st.L, T, j, load_w, cnt_w, eq_w, pl.xj, st.nd, a.tick_s, pl.place);
+      o = walk_ticks<4, false, SINGLE, TWO, true, false>(st.L, T, j, load_w, cnt_w, eq_w, pl.xj, st.nd, a.tick_s, pl.place);
     } else {
-      o = walk_ticks<4, true, SINGLE, TWO, true>(st.L, T, j, load_w, cnt_w, eq_w, pl.xj, st.nd, a.tick_s, pl.place);
+      o = walk_ticks<4, true, SINGLE, TWO, true, false>(st.L, T, j, load_w, cnt_w, eq_w, pl.xj, st.nd, a.tick_s, pl.place);
     }
     emit_cell(sa, st, cell, empty, o.ov, o.e, o.ttft, o.tbt);
   }
